@@ -1,0 +1,99 @@
+"""Seeded synthetic inputs with the attention shapes of the paper's DiT workloads.
+
+This module holds no arithmetic of the method: it only draws numbers.  Both the
+tests' oracle side and the GPU side are fed from here so they see identical
+bits (values are rounded to the storage dtype on the host, once, before either
+side touches them).
+
+The paper trains DiT-XL/2 on ImageNet 256x256 / 512x512 latents with patch
+size 2 (Sec. 6, App. F), i.e. self-attention over 16x16 = 256 or 32x32 = 1024
+tokens, hidden 1152 split in 16 heads of 72 (the original DiT split).  Those
+datasets and weights are not used; iid Gaussian tensors of the same shapes
+stand in for the activations.
+
+Recipe for every config: one numpy PCG64 stream seeded with `seed`; float32
+standard normals drawn in the order q, k, v, tq, tk, tv, gO, gTO, each as a
+whole [B,H,N,d] array; then the per-config scaling (tangent std, key scale);
+then round-to-nearest-even to the storage dtype.
+"""
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+NAMES = ("q", "k", "v", "tq", "tk", "tv", "gO", "gTO")
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    N: int
+    d: int
+    dtype: str            # "f32" or "bf16"
+    tangent_std: float = 1.0
+    key_scale: float = 1.0
+    note: str = ""
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    @property
+    def heads(self):
+        return self.B * self.H
+
+    def fwd_flops(self):
+        """Six N x N x d products (S, two for Sdot, and three PV-type)."""
+        return 12.0 * self.B * self.H * self.N * self.N * self.d
+
+    def bwd_flops(self):
+        """Fifteen N x N x d products (six score-type incl. the recompute, nine output)."""
+        return 30.0 * self.B * self.H * self.N * self.N * self.d
+
+    def elem_bytes(self):
+        return 4 if self.dtype == "f32" else 2
+
+    def fwd_bytes(self):
+        """Reads q,k,v,tq,tk,tv; writes o,to and two fp32 row vectors."""
+        n = self.B * self.H * self.N
+        return 8 * n * self.d * self.elem_bytes() + 8 * n
+
+    def bwd_bytes(self):
+        """Reads ten [B,H,N,d] tensors and two row vectors; writes six tensors."""
+        n = self.B * self.H * self.N
+        return 16 * n * self.d * self.elem_bytes() + 8 * n
+
+
+CONFIGS = {
+    "C1": Workload("C1", 1, 2, 64, 32, "f32", note="tiny plumbing case"),
+    "C2": Workload("C2", 32, 12, 256, 64, "bf16", note="DiT-B/2, 256px latents"),
+    "C3": Workload("C3", 32, 16, 256, 72, "bf16", note="DiT-XL/2, 256px latents"),
+    "C4": Workload("C4", 16, 16, 1024, 72, "bf16", tangent_std=0.1, note="DiT-XL/2, 512px latents"),
+    "C5": Workload("C5", 2, 24, 4096, 128, "bf16", key_scale=2.0, note="long-sequence stress"),
+}
+
+
+def custom(B, H, N, d, dtype="bf16", tangent_std=1.0, key_scale=1.0, name=None):
+    return Workload(name or f"B{B}H{H}N{N}d{d}{dtype}", B, H, N, d, dtype, tangent_std, key_scale)
+
+
+def make_inputs(w: Workload, seed: int):
+    """dict name -> CPU torch tensor [B,H,N,d] in the workload's storage dtype."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    shape = (w.B, w.H, w.N, w.d)
+    out = {}
+    for name in NAMES:
+        x = rng.standard_normal(shape, dtype=np.float32)
+        if name in ("tq", "tk", "tv") and w.tangent_std != 1.0:
+            x *= np.float32(w.tangent_std)
+        if name == "k" and w.key_scale != 1.0:
+            x *= np.float32(w.key_scale)
+        out[name] = torch.from_numpy(x).to(w.torch_dtype).contiguous()
+    return out
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
+    return t.detach().cpu().to(torch.float64).numpy()
