@@ -1,0 +1,131 @@
+/*
+ * tvmattn -- fused multi-head softmax attention with a JVP tangent, and its
+ * backward through both outputs, for AMD MI355X (gfx950).
+ *
+ * Operation (Terminal Velocity Matching, App. C "Flash Attention JVP with
+ * Backward Pass"; eq. (sdpa), the "Background" paragraph and the equations
+ * under "Step 1").  Per batch b and head h, with Q,K,V and tangents
+ * tQ,tK,tV all [N,D] and alpha = scale:
+ *
+ *     z  = alpha Q K^T                       zt = alpha (tQ K^T + Q tK^T)
+ *     P  = softmax_rows(z)                   lse_i   = log sum_j exp(z_ij)
+ *     stats_i = sum_j P_ij zt_ij             (the paper's mu_i / l_i)
+ *     O  = P V                               tO = (P o (zt - stats 1^T)) V + P tV
+ *
+ * tO is the directional derivative of O along (tQ,tK,tV).  No N x N matrix is
+ * ever stored ("Caching softmax statistics": only lse and stats are kept).
+ *
+ * The backward returns the gradient of  <gO,O> + <gTO,tO>  with respect to all
+ * six inputs (Steps 1-6 of App. C give the gTO part; the gO part is ordinary
+ * attention backward; the library returns their sum).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device.  The
+ *     caller owns every buffer; the library never allocates, frees or
+ *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t cast
+ *     to void*; NULL is the default stream).
+ *   - Big tensors have logical shape [B,H,N,D], element type `dtype`, innermost
+ *     stride 1 and the element strides given in the descriptor, which apply to
+ *     every [B,H,N,D] tensor of the call (inputs, outputs, gradients alike).
+ *     All strides 0 means contiguous [B,H,N,D].  Base pointers must be 16-byte
+ *     aligned and stride_n, stride_h, stride_b multiples of 16 bytes.
+ *   - Row vectors (lse, stats) are contiguous [B,H,N] float32.
+ *   - Arithmetic: products of dtype elements accumulate in float32; softmax and
+ *     all row statistics are float32; outputs are rounded once to dtype.
+ *   - Return value: TVMATTN_OK (0) or a negative tvmattn_status.  Arguments are
+ *     validated before the first launch: on INVALID_ARG, UNSUPPORTED or
+ *     WORKSPACE_TOO_SMALL nothing has been enqueued.  No C++ exception crosses
+ *     this boundary.
+ *   - Outputs must not alias inputs.  Calls on the same stream are ordered;
+ *     calls on different streams may overlap if their buffers are disjoint.
+ */
+#ifndef TVMATTN_H
+#define TVMATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TVMATTN_F32 = 0,  /* float32 storage; float32 arithmetic */
+  TVMATTN_BF16 = 1  /* bfloat16 storage; bf16 x bf16 -> float32 matrix-core products */
+} tvmattn_dtype;
+
+typedef enum {
+  TVMATTN_OK = 0,
+  TVMATTN_INVALID_ARG = -1,         /* null pointer, bad shape, misaligned pointer or stride */
+  TVMATTN_UNSUPPORTED = -2,         /* dtype unknown, D > 256, sizes beyond 2^31 rows */
+  TVMATTN_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < tvmattn_jvp_bwd_workspace_bytes() */
+  TVMATTN_LAUNCH_FAILED = -4        /* hipGetLastError() after a launch was not hipSuccess */
+} tvmattn_status;
+
+typedef struct {
+  int32_t B;        /* batch                       >= 1 */
+  int32_t H;        /* heads                       >= 1 */
+  int32_t N;        /* tokens (queries = keys)     >= 1 */
+  int32_t D;        /* head dimension              1..256 */
+  int32_t dtype;    /* tvmattn_dtype */
+  float scale;      /* alpha; 0 selects 1/sqrt(D) (the true D, never a padded one) */
+  int64_t stride_b; /* element strides of every [B,H,N,D] tensor; all zero = contiguous */
+  int64_t stride_h;
+  int64_t stride_n;
+} tvmattn_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int tvmattn_version(void);
+
+/* Static, never-NULL description of a status code. */
+const char* tvmattn_strerror(int status);
+
+/*
+ * Diagnostic switch, process-wide, not thread-safe: 0 (default) picks the kernel family per
+ * shape (matrix-core kernels for bf16 with D a multiple of 8 and D <= 128, plain-ALU kernels
+ * otherwise); 1 forces the plain-ALU kernels for every call.  Returns TVMATTN_OK or
+ * TVMATTN_INVALID_ARG.  Both families compute the operation stated above.
+ */
+int tvmattn_set_path(int path);
+
+/*
+ * Forward with tangent (one online-softmax pass over the keys).
+ *   in : q,k,v,tq,tk,tv   [B,H,N,D] dtype
+ *   out: o, to            [B,H,N,D] dtype
+ *        lse, stats       [B,H,N]   float32 (natural log of the row sum of exp(z); mu/l)
+ */
+int tvmattn_jvp_fwd(const tvmattn_desc* desc,
+                    const void* q, const void* k, const void* v,
+                    const void* tq, const void* tk, const void* tv,
+                    void* o, void* to, float* lse, float* stats,
+                    void* hip_stream);
+
+/* Bytes of device scratch tvmattn_jvp_bwd needs for this descriptor (0 on a bad descriptor). */
+size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc);
+
+/*
+ * Backward through both outputs.
+ *   in : q,k,v,tq,tk,tv   as given to the forward
+ *        o,to,lse,stats   as written by the forward
+ *        gO, gTO          [B,H,N,D] dtype, upstream gradients of o and to
+ *   out: dq,dk,dv,dtq,dtk,dtv  [B,H,N,D] dtype, each element written exactly once
+ *   workspace: device memory, 16-byte aligned, at least
+ *        tvmattn_jvp_bwd_workspace_bytes(desc) bytes; contents need not be initialised
+ *        and are undefined afterwards.
+ * Three launches on the stream: row scalars (Step 1: delta = gO.O, Sigma_1 = gTO.O,
+ * Sigma_2 = gTO.tO per row), a key-side pass (dk,dtk,dv,dtv; Steps 2,4,6) and a
+ * query-side pass (dq,dtq; Steps 3,5).  No atomics: results are bitwise reproducible.
+ */
+int tvmattn_jvp_bwd(const tvmattn_desc* desc,
+                    const void* q, const void* k, const void* v,
+                    const void* tq, const void* tk, const void* tv,
+                    const void* o, const void* to, const float* lse, const float* stats,
+                    const void* gO, const void* gTO,
+                    void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
+                    void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TVMATTN_H */

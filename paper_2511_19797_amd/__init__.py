@@ -1,0 +1,8 @@
+"""MI355X-native fused attention with a JVP tangent and its backward (see include/tvmattn.h).
+
+The Python layer is a ctypes binding with the C entry points' names; importing the
+package does not load the shared library, calling any entry point does (and raises if
+it has not been built).
+"""
+from .binding import (TvmattnError, tvmattn_desc, tvmattn_jvp_bwd, tvmattn_jvp_bwd_workspace_bytes,  # noqa: F401
+                      tvmattn_jvp_fwd, tvmattn_set_path, tvmattn_strerror, tvmattn_version)

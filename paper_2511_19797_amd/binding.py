@@ -1,0 +1,143 @@
+"""ctypes binding of libtvmattn.so: argument marshalling only.
+
+Same names as the C entry points (include/tvmattn.h).  torch supplies device
+memory and the current stream; every step of the computation runs in the
+library's HIP kernels.  There is no fallback: if the shared library is missing
+or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtvmattn.so")
+
+TVMATTN_F32, TVMATTN_BF16 = 0, 1
+
+
+class tvmattn_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+
+
+class TvmattnError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"tvmattn status {status}: {msg}")
+        self.status = status
+
+
+_lib = None
+_P = ctypes.c_void_p
+
+
+def lib():
+    """Loads the library on first use; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: run `python -m paper_2511_19797_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.tvmattn_version.restype = ctypes.c_int
+        L.tvmattn_strerror.restype = ctypes.c_char_p
+        L.tvmattn_strerror.argtypes = [ctypes.c_int]
+        L.tvmattn_set_path.restype = ctypes.c_int
+        L.tvmattn_set_path.argtypes = [ctypes.c_int]
+        L.tvmattn_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 11
+        L.tvmattn_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_jvp_bwd_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
+        L.tvmattn_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_jvp_bwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 19 + [ctypes.c_size_t, _P]
+        _lib = L
+    return _lib
+
+
+def tvmattn_version():
+    return lib().tvmattn_version()
+
+
+def tvmattn_strerror(status):
+    return lib().tvmattn_strerror(int(status)).decode()
+
+
+def tvmattn_set_path(path):
+    _check(lib().tvmattn_set_path(int(path)))
+
+
+def _check(status):
+    if status != 0:
+        raise TvmattnError(status, tvmattn_strerror(status))
+
+
+def make_desc(x: torch.Tensor, scale=0.0) -> tvmattn_desc:
+    """Descriptor for a [B,H,N,D] tensor (any strides with unit innermost stride)."""
+    if x.dim() != 4:
+        raise ValueError("expected a [B,H,N,D] tensor")
+    if x.dtype == torch.float32:
+        dt = TVMATTN_F32
+    elif x.dtype == torch.bfloat16:
+        dt = TVMATTN_BF16
+    else:
+        raise ValueError(f"unsupported dtype {x.dtype}")
+    if x.stride(3) != 1:
+        raise ValueError("innermost stride must be 1")
+    B, H, N, D = x.shape
+    return tvmattn_desc(B, H, N, D, dt, float(scale), x.stride(0), x.stride(1), x.stride(2))
+
+
+def _same_layout(ref, *ts):
+    for t in ts:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype or t.device != ref.device:
+            raise ValueError("all [B,H,N,D] tensors of one call must share shape, strides, dtype and device")
+        if not t.is_cuda:
+            raise ValueError("device tensors required")
+
+
+def _stream():
+    return _P(torch.cuda.current_stream().cuda_stream)
+
+
+def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None):
+    """Returns (o, to, lse, stats).  `out`, if given, is that same tuple of preallocated tensors."""
+    _same_layout(q, k, v, tq, tk, tv)
+    desc = make_desc(q, scale)
+    B, H, N, _ = q.shape
+    if out is None:
+        o, to = torch.empty_like(q), torch.empty_like(q)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+        stats = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    else:
+        o, to, lse, stats = out
+        _same_layout(q, o, to)
+    _check(lib().tvmattn_jvp_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(),
+                                 tk.data_ptr(), tv.data_ptr(), o.data_ptr(), to.data_ptr(), lse.data_ptr(),
+                                 stats.data_ptr(), _stream()))
+    return o, to, lse, stats
+
+
+def tvmattn_jvp_bwd_workspace_bytes(x, scale=0.0):
+    desc = make_desc(x, scale)
+    return int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
+
+
+def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, out=None, workspace=None):
+    """Returns (dq, dk, dv, dtq, dtk, dtv)."""
+    _same_layout(q, k, v, tq, tk, tv, o, to, gO, gTO)
+    desc = make_desc(q, scale)
+    if out is None:
+        out = tuple(torch.empty_like(q) for _ in range(6))
+    else:
+        _same_layout(q, *out)
+    need = int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    dq, dk, dv, dtq, dtk, dtv = out
+    _check(lib().tvmattn_jvp_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(),
+                                 tk.data_ptr(), tv.data_ptr(), o.data_ptr(), to.data_ptr(), lse.data_ptr(),
+                                 stats.data_ptr(), gO.data_ptr(), gTO.data_ptr(), dq.data_ptr(), dk.data_ptr(),
+                                 dv.data_ptr(), dtq.data_ptr(), dtk.data_ptr(), dtv.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return out

@@ -1,0 +1,57 @@
+// Shared device-side types for the tvmattn kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tvm {
+
+typedef __bf16 bf16;
+
+// Logical [B,H,N,D] problem with the element strides shared by every big tensor.
+struct Shape {
+  int B, H, N, D;
+  float alpha;          // softmax scale actually used (already resolved from desc.scale)
+  long long sb, sh, sn; // element strides
+};
+
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16* p) { return (float)*p; }
+__device__ __forceinline__ void stf(float* p, float x) { *p = x; }
+__device__ __forceinline__ void stf(bf16* p, float x) { *p = (bf16)x; }  // round-to-nearest-even
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// Host-side launchers (defined in the kernel translation units; all return hipGetLastError()).
+struct FwdArgs {
+  const void *q, *k, *v, *tq, *tk, *tv;
+  void *o, *to;
+  float *lse, *stats;
+};
+struct BwdArgs {
+  const void *q, *k, *v, *tq, *tk, *tv, *o, *to;
+  const float *lse, *stats;
+  const void *gO, *gTO;
+  void *dq, *dk, *dv, *dtq, *dtk, *dtv;
+  float *dsig;  // workspace: delta + Sigma_2 per row
+  float *sig1;  // workspace: Sigma_1 per row
+};
+
+hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_pre(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
+
+// bf16 matrix-core paths; `supported` says whether the shape is one they take.
+bool mfma_supported(const Shape& s, int dtype);
+hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
+
+}  // namespace tvm

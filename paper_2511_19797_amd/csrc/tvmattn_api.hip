@@ -1,0 +1,134 @@
+// C-ABI entry points: argument validation and dispatch.  No allocation, no synchronisation.
+#include "../../include/tvmattn.h"
+
+#include <math.h>
+
+#include "tvm_common.h"
+
+namespace {
+
+int g_path = 0;  // 0 = choose per shape, 1 = plain-ALU kernels only (diagnostic)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates the descriptor and resolves strides and scale.
+int resolve(const tvmattn_desc* d, tvm::Shape* s) {
+  if (!d) return TVMATTN_INVALID_ARG;
+  if (d->B < 1 || d->H < 1 || d->N < 1 || d->D < 1) return TVMATTN_INVALID_ARG;
+  if (d->dtype != TVMATTN_F32 && d->dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
+  if (d->D > 256) return TVMATTN_UNSUPPORTED;
+  if (!(d->scale >= 0.f) || isinf(d->scale)) return TVMATTN_INVALID_ARG;
+  const long long esz = d->dtype == TVMATTN_F32 ? 4 : 2;
+  long long sb = d->stride_b, sh = d->stride_h, sn = d->stride_n;
+  if (sb == 0 && sh == 0 && sn == 0) {
+    sn = d->D;
+    sh = (long long)d->N * d->D;
+    sb = sh * d->H;
+  }
+  if (sn < d->D || sh < 1 || sb < 1) return TVMATTN_INVALID_ARG;
+  if ((sn * esz) % 16 || (sh * esz) % 16 || (sb * esz) % 16) return TVMATTN_INVALID_ARG;
+  const long long rows = (long long)d->B * d->H * d->N;
+  if (rows >= (1ll << 31)) return TVMATTN_UNSUPPORTED;
+  s->B = d->B;
+  s->H = d->H;
+  s->N = d->N;
+  s->D = d->D;
+  s->alpha = d->scale == 0.f ? 1.0f / sqrtf((float)d->D) : d->scale;
+  s->sb = sb;
+  s->sh = sh;
+  s->sn = sn;
+  return TVMATTN_OK;
+}
+
+template <size_t NI, size_t NO>
+int check_ptrs(const void* const (&in)[NI], void* const (&out)[NO]) {
+  for (size_t i = 0; i < NI; ++i)
+    if (!in[i] || !aligned16(in[i])) return TVMATTN_INVALID_ARG;
+  for (size_t o = 0; o < NO; ++o) {
+    if (!out[o] || !aligned16(out[o])) return TVMATTN_INVALID_ARG;
+    for (size_t i = 0; i < NI; ++i)
+      if (out[o] == in[i]) return TVMATTN_INVALID_ARG;
+    for (size_t p = 0; p < o; ++p)
+      if (out[o] == out[p]) return TVMATTN_INVALID_ARG;
+  }
+  return TVMATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tvmattn_version(void) { return 100; }
+
+const char* tvmattn_strerror(int status) {
+  switch (status) {
+    case TVMATTN_OK: return "ok";
+    case TVMATTN_INVALID_ARG: return "invalid argument (null/misaligned pointer, bad shape, stride or scale, or aliasing)";
+    case TVMATTN_UNSUPPORTED: return "unsupported (dtype, head dimension > 256, or too many rows)";
+    case TVMATTN_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case TVMATTN_LAUNCH_FAILED: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int tvmattn_set_path(int path) {
+  if (path != 0 && path != 1) return TVMATTN_INVALID_ARG;
+  g_path = path;
+  return TVMATTN_OK;
+}
+
+int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
+                    const void* tk, const void* tv, void* o, void* to, float* lse, float* stats, void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  const void* const in[] = {q, k, v, tq, tk, tv};
+  void* const out[] = {o, to, lse, stats};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  tvm::FwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats};
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (g_path == 0 && tvm::mfma_supported(s, desc->dtype))
+    e = tvm::launch_fwd_mfma(s, a, st);
+  else
+    e = tvm::launch_fwd_generic(s, desc->dtype, a, st);
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
+size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc) {
+  tvm::Shape s;
+  if (resolve(desc, &s)) return 0;
+  // two float32 row vectors (delta + Sigma_2, Sigma_1), each padded to a 256-byte multiple
+  const size_t rows = (size_t)s.B * s.H * s.N;
+  const size_t one = (rows * sizeof(float) + 255) & ~(size_t)255;
+  return 2 * one;
+}
+
+int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
+                    const void* tk, const void* tv, const void* o, const void* to, const float* lse,
+                    const float* stats, const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq,
+                    void* dtk, void* dtv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  const void* const in[] = {q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO};
+  void* const out[] = {dq, dk, dv, dtq, dtk, dtv, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  const size_t need = tvmattn_jvp_bwd_workspace_bytes(desc);
+  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::BwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
+                 static_cast<float*>(workspace),
+                 reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2)};
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = tvm::launch_bwd_pre(s, desc->dtype, a, st);
+  if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
+  if (g_path == 0 && tvm::mfma_supported(s, desc->dtype))
+    e = tvm::launch_bwd_mfma(s, a, st);
+  else
+    e = tvm::launch_bwd_generic(s, desc->dtype, a, st);
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_19797_amd as tvm
+from paper_2511_19797_amd import binding, build as tvm_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        tvm_build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if not f.endswith(".h"):
+            continue
+        src = open(os.path.join(inc, f)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(tvmattn_\w+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_symbols_exported(L):
+    names = declared_functions()
+    assert {"tvmattn_jvp_fwd", "tvmattn_jvp_bwd", "tvmattn_jvp_bwd_workspace_bytes", "tvmattn_strerror",
+            "tvmattn_version", "tvmattn_set_path"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/ but not exported"
+
+
+def test_version_and_strerror(L):
+    assert tvm.tvmattn_version() >= 100
+    for code in (0, -1, -2, -3, -4, -99):
+        assert isinstance(tvm.tvmattn_strerror(code), str) and tvm.tvmattn_strerror(code)
+
+
+def desc(B=1, H=1, N=8, D=8, dtype=1, scale=0.0, sb=0, sh=0, sn=0):
+    return binding.tvmattn_desc(B, H, N, D, dtype, scale, sb, sh, sn)
+
+
+def fwd_status(L, d, ptrs=None):
+    p = ptrs or [0x1000 * (i + 1) for i in range(10)]
+    return L.tvmattn_jvp_fwd(ctypes.byref(d), *p, None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), -1), (dict(N=0), -1), (dict(D=0), -1), (dict(H=-3), -1),
+    (dict(D=257), -2), (dict(dtype=7), -2), (dict(scale=-1.0), -1), (dict(scale=float("nan")), -1),
+    (dict(scale=float("inf")), -1),
+    (dict(sn=4, sh=64, sb=64), -1),            # stride_n < D
+    (dict(D=8, sn=12, sh=96, sb=96), -1),       # 24-byte row pitch is not a 16-byte multiple
+    (dict(B=1 << 15, H=1 << 15, N=4), -2),      # 2^32 rows
+])
+def test_bad_descriptors_rejected_without_gpu(L, kw, status):
+    assert fwd_status(L, desc(**kw)) == status
+    assert L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc(**kw))) == 0
+
+
+def test_null_misaligned_and_aliased_pointers(L):
+    d = desc()
+    good = [0x1000 * (i + 1) for i in range(10)]
+    assert L.tvmattn_jvp_fwd(None, *good, None) == -1
+    for i in range(10):
+        p = list(good)
+        p[i] = None
+        assert fwd_status(L, d, p) == -1
+        p[i] = good[i] + 4
+        assert fwd_status(L, d, p) == -1
+    p = list(good)
+    p[6] = p[0]            # o aliases q
+    assert fwd_status(L, d, p) == -1
+    p = list(good)
+    p[7] = p[6]            # to aliases o
+    assert fwd_status(L, d, p) == -1
+
+
+def test_bwd_workspace_contract(L):
+    d = desc(B=2, H=3, N=100, D=72)
+    need = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
+    assert need >= 2 * 2 * 3 * 100 * 4 and need % 256 == 0
+    ptrs = [0x1000 * (i + 1) for i in range(19)]
+    assert L.tvmattn_jvp_bwd(ctypes.byref(d), *ptrs, need - 1, None) == -3
+    bad = list(ptrs)
+    bad[18] = None
+    assert L.tvmattn_jvp_bwd(ctypes.byref(d), *bad, need, None) == -1
+    assert L.tvmattn_set_path(5) == -1 and L.tvmattn_set_path(0) == 0

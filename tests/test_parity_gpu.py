@@ -1,0 +1,131 @@
+"""GPU-vs-oracle parity through the C-ABI (ctypes binding).  Every case prints its name
+before touching the GPU so a failing run names its case."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_19797_amd as tvm
+from paper_2511_19797_amd import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_case(w, seed, heads=None, scale=0.0, force_generic=False):
+    announce(f"{w} seed={seed} scale={scale} generic={force_generic}")
+    inp = wl.make_inputs(w, seed)
+    tvm.tvmattn_set_path(1 if force_generic else 0)
+    try:
+        fwd, grads = pu.run_gpu(inp, scale)
+    finally:
+        tvm.tvmattn_set_path(0)
+    heads = pu.all_heads(w) if heads is None else heads
+    worst = pu.check_heads(w, inp, fwd, grads, heads, scale=(scale or None))
+    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    return inp, fwd, grads
+
+
+# ---------------------------------------------------------------- float32 (plain-ALU kernels)
+def test_c1_f32_tiny():
+    run_case(wl.CONFIGS["C1"], seed=1)
+
+
+@pytest.mark.parametrize("B,H,N,d", [(2, 3, 77, 40), (1, 2, 1, 8), (1, 1, 130, 256), (1, 2, 64, 4), (2, 1, 200, 72)])
+def test_f32_ragged_shapes(B, H, N, d):
+    run_case(wl.custom(B, H, N, d, "f32"), seed=2)
+
+
+def test_f32_explicit_scale():
+    run_case(wl.custom(1, 2, 50, 16, "f32"), seed=3, scale=0.3)
+
+
+# ---------------------------------------------------------------- bf16 on the plain-ALU kernels
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 96, 64), (2, 2, 70, 136), (1, 1, 33, 72)])
+def test_bf16_generic_kernels(B, H, N, d):
+    run_case(wl.custom(B, H, N, d, "bf16"), seed=4, force_generic=True)
+
+
+# ---------------------------------------------------------------- bf16 matrix-core kernels, small
+@pytest.mark.parametrize("B,H,N,d", [
+    (2, 2, 256, 64),    # C2 shape, few heads
+    (2, 2, 256, 72),    # C3 shape, few heads: padded head dim
+    (1, 3, 200, 72),    # ragged tail in both the last key tile and the last query tile
+    (1, 2, 65, 72),     # one full tile plus one row
+    (1, 2, 1, 64),      # single token
+    (1, 2, 31, 8),      # smallest head dim, less than one tile
+    (2, 1, 300, 128),   # C5 head dim, ragged
+    (1, 2, 129, 40), (1, 1, 257, 96), (1, 1, 130, 32), (1, 1, 100, 16), (1, 1, 192, 80), (1, 1, 64, 104),
+    (1, 1, 160, 120),
+])
+def test_bf16_mfma_small(B, H, N, d):
+    run_case(wl.custom(B, H, N, d, "bf16"), seed=5)
+
+
+def test_bf16_mfma_scaled_inputs():
+    # C4's small tangents and C5's sharpened keys at a size the oracle does in full
+    run_case(wl.custom(1, 2, 384, 72, "bf16", tangent_std=0.1), seed=6)
+    run_case(wl.custom(1, 2, 512, 128, "bf16", key_scale=2.0), seed=7)
+    run_case(wl.custom(1, 2, 128, 64, "bf16"), seed=8, scale=0.2)
+
+
+def test_strided_layout_bnhd():
+    """Tensors stored [B,N,H,D] and viewed as [B,H,N,D] (what a fused QKV projection hands over)."""
+    for dtype, d in (("bf16", 72), ("f32", 24)):
+        w = wl.custom(2, 3, 150, d, dtype)
+        announce(f"strided {w}")
+        inp = wl.make_inputs(w, 9)
+        dev = {n: t.cuda().permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for n, t in inp.items()}
+        assert dev["q"].stride(1) == d and dev["q"].stride(2) == 3 * d
+        o, to, lse, stats = tvm.tvmattn_jvp_fwd(*(dev[n] for n in wl.NAMES[:6]))
+        grads = tvm.tvmattn_jvp_bwd(*(dev[n] for n in wl.NAMES[:6]), o, to, lse, stats, dev["gO"], dev["gTO"])
+        torch.cuda.synchronize()
+        assert o.stride() == dev["q"].stride()
+        pu.check_heads(w, inp, (o, to, lse, stats), grads, pu.all_heads(w))
+
+
+def test_bitwise_reproducible():
+    w = wl.custom(2, 2, 333, 72, "bf16")
+    announce(f"determinism {w}")
+    inp = wl.make_inputs(w, 10)
+    f1, g1 = pu.run_gpu(inp)
+    f2, g2 = pu.run_gpu(inp)
+    for a, b in zip(list(f1) + list(g1), list(f2) + list(g2)):
+        assert torch.equal(a, b)
+
+
+def test_zero_tangents_and_zero_grads_on_gpu():
+    w = wl.custom(1, 2, 100, 72, "bf16")
+    announce(f"zero tangents {w}")
+    inp = wl.make_inputs(w, 11)
+    for n in ("tq", "tk", "tv"):
+        inp[n].zero_()
+    fwd, grads = pu.run_gpu(inp)
+    assert float(fwd[1].float().abs().max()) == 0.0 and float(fwd[3].abs().max()) == 0.0
+    pu.check_heads(w, inp, fwd, grads, pu.all_heads(w))
+
+
+# ---------------------------------------------------------------- the five configs at full size
+@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2)])
+def test_full_size_configs_sampled_heads(name, nheads):
+    """Full B,H,N,d in the launch configuration bench.py times; the oracle checks whole heads
+    (every element of all ten outputs) for a seeded sample of (b,h), always including the first
+    and the last head; all outputs must be finite everywhere."""
+    w = wl.CONFIGS[name]
+    announce(f"full-size {w}")
+    inp = wl.make_inputs(w, 100 + int(name[1]))
+    fwd, grads = pu.run_gpu(inp)
+    for t in list(fwd) + list(grads):
+        assert bool(torch.isfinite(t.float()).all())
+    rng = np.random.default_rng(12)
+    heads = {(0, 0), (w.B - 1, w.H - 1)}
+    while len(heads) < nheads:
+        heads.add((int(rng.integers(w.B)), int(rng.integers(w.H))))
+    worst = pu.check_heads(w, inp, fwd, grads, sorted(heads))
+    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
