@@ -1,0 +1,339 @@
+// Backward through both outputs on the bf16 matrix cores (gfx950): a key-side kernel
+// (dK, dtK, dV, dtV; Steps 2, 4, 6 of App. C plus the ordinary-attention terms of gO) and a
+// query-side kernel (dQ, dtQ; Steps 3, 5), both recomputing the tile quantities from lse and
+// stats ("Caching softmax statistics").  With G = gO, Gt = gTO and the row scalars of Step 1
+// collapsed to dot products (dsig = G.O + Gt.tO, sig1 = Gt.O):
+//
+//   S = Q K^T             St = tQ K^T + Q tK^T        P = exp(alpha S - lse)
+//   N = alpha St - stats  DF = G V^T + Gt tV^T        E = Gt V^T
+//   gZt = P o (E - sig1)  gZ = P o (DF - dsig) + gZt o N        Pd = P o N
+//
+//   dV = P^T G + Pd^T Gt       dtV = P^T Gt
+//   dK = alpha (gZ^T Q + gZt^T tQ)      dtK = alpha gZt^T Q
+//   dQ = alpha (gZ K + gZt tK)          dtQ = alpha gZt K
+//
+// Both kernels share one skeleton.  A wave owns 32 rows of the "fixed" side (keys for the
+// key-side kernel, queries for the query-side one) and keeps that side's four tensors as
+// B-operand fragments in registers; the other side is streamed through LDS in tiles of 64
+// rows, row-major for the score products and transposed (slot order) for the output products.
+// Score tiles are D[streamed][fixed]: a lane owns one fixed row, its 16 registers run over
+// streamed rows, and the tile feeds the output products straight from registers.
+// No atomics anywhere: every output element is produced by exactly one lane.
+#include "mfma_tiles.h"
+
+namespace tvm {
+namespace {
+
+constexpr int kFix = 128;  // fixed-side rows per workgroup (4 waves x 32)
+constexpr int kTS = 64;    // streamed rows per LDS tile
+constexpr int kNT = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int DK, int DV>
+struct ColLds {
+  static constexpr int KP = DK + 8, IP = kTS + 8;
+  bf16 q[kTS * KP], tq[kTS * KP], g[kTS * KP], tg[kTS * KP];
+  bf16 qT[DV * IP], tqT[DV * IP], gT[DV * IP], tgT[DV * IP];
+  float lse2[kTS], mub[kTS], dsig[kTS], sig1[kTS];
+};
+
+template <int DK, int DV>
+struct RowLds {
+  static constexpr int KP = DK + 8, JP = kTS + 8;
+  bf16 k[kTS * KP], tk[kTS * KP], v[kTS * KP], tv[kTS * KP];
+  bf16 kT[DV * JP], tkT[DV * JP];
+};
+
+template <int NDB>
+__device__ __forceinline__ void zero_acc(f32x16 (&a)[NDB]) {
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[db][r] = 0.f;
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+
+// Stores a transposed accumulator (rows = d, column = this lane's fixed row) as bf16, scaled.
+template <int NDB>
+__device__ __forceinline__ void store_acc(bf16* __restrict__ dst, const f32x16 (&a)[NDB], float scale, int D, int hh) {
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = db * 32 + 8 * g + 4 * hh;
+      if (d0 < D) {
+        bf16x4 o;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
+        *reinterpret_cast<bf16x4*>(dst + d0) = o;
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Key side.
+// ------------------------------------------------------------------------------------------
+template <int DK, int DV>
+__global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
+    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
+    const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
+    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
+    bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
+  using L = ColLds<DK, DV>;
+  __shared__ __attribute__((aligned(16))) L sm;
+  constexpr int NKS = DK / 16, NDB = DV / 32;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int nfb = (s.N + kFix - 1) / kFix;
+  const int bh = blockIdx.x / nfb, fb = blockIdx.x - bh * nfb;
+  const int b = bh / s.H, h = bh - b * s.H;
+  const long long base = b * s.sb + h * s.sh;
+  const int j = fb * kFix + wave * 32 + ic;  // this lane's key
+  const bool jok = j < s.N;
+
+  bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    const int c0 = kk * 16 + hh * 8;
+    const bool ok = jok && c0 < s.D;
+    const long long a = base + (long long)j * s.sn + c0;
+    kf[kk] = gld_frag(k + a, ok);
+    tkf[kk] = gld_frag(tk + a, ok);
+    vf[kk] = gld_frag(v + a, ok);
+    tvf[kk] = gld_frag(tv + a, ok);
+  }
+  f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
+  zero_acc(aK);
+  zero_acc(aTK);
+  zero_acc(aV);
+  zero_acc(aTV);
+  const float c1 = s.alpha * kLog2e;
+
+  for (int i0 = 0; i0 < s.N; i0 += kTS) {
+    __syncthreads();
+    load_rows<kTS, DK, L::KP, kNT>(sm.q, q + base, s.sn, i0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.tq, tq + base, s.sn, i0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.g, gO + base, s.sn, i0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.tg, gTO + base, s.sn, i0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::IP, kNT>(sm.qT, q + base, s.sn, i0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::IP, kNT>(sm.tqT, tq + base, s.sn, i0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::IP, kNT>(sm.gT, gO + base, s.sn, i0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::IP, kNT>(sm.tgT, gTO + base, s.sn, i0, s.N, s.D, tid);
+    if (tid < kTS) {
+      // rows beyond N: lse = +inf gives them probability exactly 0 (and their Q/G rows are zero)
+      const bool ok = i0 + tid < s.N;
+      const long long r = (long long)bh * s.N + i0 + tid;
+      sm.lse2[tid] = ok ? lse[r] * kLog2e : INFINITY;
+      sm.mub[tid] = ok ? stats[r] : 0.f;
+      sm.dsig[tid] = ok ? dsig[r] : 0.f;
+      sm.sig1[tid] = ok ? sig1[r] : 0.f;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int ib = 0; ib < kTS / 32; ++ib) {
+      if (i0 + ib * 32 >= s.N) break;  // uniform
+      f32x16 sS = zero16(), sT = zero16(), sDF = zero16(), sE = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        const int off = (ib * 32 + ic) * L::KP + kk * 16 + hh * 8;
+        const bf16x8 qf = lds_frag(sm.q + off), tqf = lds_frag(sm.tq + off);
+        const bf16x8 gf = lds_frag(sm.g + off), tgf = lds_frag(sm.tg + off);
+        sS = mfma(qf, kf[kk], sS);
+        sT = mfma(tqf, kf[kk], sT);
+        sT = mfma(qf, tkf[kk], sT);
+        sDF = mfma(gf, vf[kk], sDF);
+        sDF = mfma(tgf, tvf[kk], sDF);
+        sE = mfma(tgf, vf[kk], sE);
+      }
+      bf16x8 pf[2], pdf[2], gzf[2], gztf[2];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int ro = ib * 32 + 8 * g4 + 4 * hh;
+        const float4 l4 = *reinterpret_cast<const float4*>(sm.lse2 + ro);
+        const float4 m4 = *reinterpret_cast<const float4*>(sm.mub + ro);
+        const float4 d4 = *reinterpret_cast<const float4*>(sm.dsig + ro);
+        const float4 s4 = *reinterpret_cast<const float4*>(sm.sig1 + ro);
+        const float la[4] = {l4.x, l4.y, l4.z, l4.w}, ma[4] = {m4.x, m4.y, m4.z, m4.w};
+        const float da[4] = {d4.x, d4.y, d4.z, d4.w}, sa[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = 4 * g4 + t;
+          const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -la[t]));
+          const float n = fmaf(sT[r], s.alpha, -ma[t]);
+          const float gzt = p * (sE[r] - sa[t]);
+          const float gz = fmaf(gzt, n, p * (sDF[r] - da[t]));
+          pf[r >> 3][r & 7] = (bf16)p;
+          pdf[r >> 3][r & 7] = (bf16)(p * n);
+          gzf[r >> 3][r & 7] = (bf16)gz;
+          gztf[r >> 3][r & 7] = (bf16)gzt;
+        }
+      }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+          const int off = (db * 32 + ic) * L::IP + (2 * ib + cc) * 16 + hh * 8;
+          const bf16x8 qT = lds_frag(sm.qT + off), tqT = lds_frag(sm.tqT + off);
+          const bf16x8 gT = lds_frag(sm.gT + off), tgT = lds_frag(sm.tgT + off);
+          aV[db] = mfma(gT, pf[cc], aV[db]);
+          aV[db] = mfma(tgT, pdf[cc], aV[db]);
+          aTV[db] = mfma(tgT, pf[cc], aTV[db]);
+          aK[db] = mfma(qT, gzf[cc], aK[db]);
+          aK[db] = mfma(tqT, gztf[cc], aK[db]);
+          aTK[db] = mfma(qT, gztf[cc], aTK[db]);
+        }
+    }
+  }
+  if (!jok) return;
+  const long long ro = base + (long long)j * s.sn;
+  store_acc<NDB>(dk + ro, aK, s.alpha, s.D, hh);
+  store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
+  store_acc<NDB>(dv + ro, aV, 1.f, s.D, hh);
+  store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
+}
+
+// ------------------------------------------------------------------------------------------
+// Query side.
+// ------------------------------------------------------------------------------------------
+template <int DK, int DV>
+__global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
+    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
+    const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
+    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
+    bf16* __restrict__ dq, bf16* __restrict__ dtq) {
+  using L = RowLds<DK, DV>;
+  __shared__ __attribute__((aligned(16))) L sm;
+  constexpr int NKS = DK / 16, NDB = DV / 32;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int nfb = (s.N + kFix - 1) / kFix;
+  const int bh = blockIdx.x / nfb, fb = blockIdx.x - bh * nfb;
+  const int b = bh / s.H, h = bh - b * s.H;
+  const long long base = b * s.sb + h * s.sh;
+  const int i = fb * kFix + wave * 32 + ic;  // this lane's query
+  const bool iok = i < s.N;
+
+  bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    const int c0 = kk * 16 + hh * 8;
+    const bool ok = iok && c0 < s.D;
+    const long long a = base + (long long)i * s.sn + c0;
+    qf[kk] = gld_frag(q + a, ok);
+    tqf[kk] = gld_frag(tq + a, ok);
+    gf[kk] = gld_frag(gO + a, ok);
+    tgf[kk] = gld_frag(gTO + a, ok);
+  }
+  // rows beyond N: zeros keep everything finite; nothing of theirs is stored
+  const long long r = (long long)bh * s.N + (iok ? i : 0);
+  const float lse2 = iok ? lse[r] * kLog2e : 0.f;
+  const float mub = iok ? stats[r] : 0.f;
+  const float ds = iok ? dsig[r] : 0.f;
+  const float s1 = iok ? sig1[r] : 0.f;
+  f32x16 aQ[NDB], aTQ[NDB];
+  zero_acc(aQ);
+  zero_acc(aTQ);
+  const float c1 = s.alpha * kLog2e;
+
+  for (int j0 = 0; j0 < s.N; j0 += kTS) {
+    __syncthreads();
+    load_rows<kTS, DK, L::KP, kNT>(sm.k, k + base, s.sn, j0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.tk, tk + base, s.sn, j0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.v, v + base, s.sn, j0, s.N, s.D, tid);
+    load_rows<kTS, DK, L::KP, kNT>(sm.tv, tv + base, s.sn, j0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::JP, kNT>(sm.kT, k + base, s.sn, j0, s.N, s.D, tid);
+    load_transposed<kTS, DV, L::JP, kNT>(sm.tkT, tk + base, s.sn, j0, s.N, s.D, tid);
+    __syncthreads();
+
+#pragma unroll
+    for (int jb = 0; jb < kTS / 32; ++jb) {
+      if (j0 + jb * 32 >= s.N) break;  // uniform
+      f32x16 sS = zero16(), sT = zero16(), sDF = zero16(), sE = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        const int off = (jb * 32 + ic) * L::KP + kk * 16 + hh * 8;
+        const bf16x8 kf = lds_frag(sm.k + off), tkf = lds_frag(sm.tk + off);
+        const bf16x8 vf = lds_frag(sm.v + off), tvf = lds_frag(sm.tv + off);
+        sS = mfma(kf, qf[kk], sS);
+        sT = mfma(kf, tqf[kk], sT);
+        sT = mfma(tkf, qf[kk], sT);
+        sDF = mfma(vf, gf[kk], sDF);
+        sDF = mfma(tvf, tgf[kk], sDF);
+        sE = mfma(vf, tgf[kk], sE);
+      }
+      if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr)
+          if (j0 + jb * 32 + drow(rr, hh) >= s.N) sS[rr] = -INFINITY;
+      }
+      bf16x8 gzf[2], gztf[2];
+#pragma unroll
+      for (int rr = 0; rr < 16; ++rr) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sS[rr], c1, -lse2));
+        const float n = fmaf(sT[rr], s.alpha, -mub);
+        const float gzt = p * (sE[rr] - s1);
+        const float gz = fmaf(gzt, n, p * (sDF[rr] - ds));
+        gzf[rr >> 3][rr & 7] = (bf16)gz;
+        gztf[rr >> 3][rr & 7] = (bf16)gzt;
+      }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+          const int off = (db * 32 + ic) * L::JP + (2 * jb + cc) * 16 + hh * 8;
+          const bf16x8 kT = lds_frag(sm.kT + off), tkT = lds_frag(sm.tkT + off);
+          aQ[db] = mfma(kT, gzf[cc], aQ[db]);
+          aQ[db] = mfma(tkT, gztf[cc], aQ[db]);
+          aTQ[db] = mfma(kT, gztf[cc], aTQ[db]);
+        }
+    }
+  }
+  if (!iok) return;
+  const long long ro = base + (long long)i * s.sn;
+  store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
+  store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+}
+
+template <int DK, int DV>
+hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const int nfb = (s.N + kFix - 1) / kFix;
+  const dim3 grid(nfb * s.B * s.H), block(kNT);
+  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
+                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse, a.stats,
+                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk, (bf16*)a.dtk, (bf16*)a.dv,
+                     (bf16*)a.dtv);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
+                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse, a.stats,
+                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 == 0 && s.D <= 128; }
+
+hipError_t launch_bwd_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const int dk = (s.D + 15) / 16 * 16;
+  switch (dk) {
+    case 16: return launch<16, 32>(s, a, st);
+    case 32: return launch<32, 32>(s, a, st);
+    case 48: return launch<48, 64>(s, a, st);
+    case 64: return launch<64, 64>(s, a, st);
+    case 80: return launch<80, 96>(s, a, st);
+    case 96: return launch<96, 96>(s, a, st);
+    case 112: return launch<112, 128>(s, a, st);
+    case 128: return launch<128, 128>(s, a, st);
+    default: return hipErrorNotSupported;
+  }
+}
+
+}  // namespace tvm
