@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one step = tvmattn_jvp_fwd + tvmattn_jvp_bwd over one batch of
+synthetic DiT-shaped inputs resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--also C3] [--no-cpu]
+
+value = algorithmic TFLOP/s of the whole step, 42*B*H*N^2*d flops per step (forward 12, backward
+30; true head dim, no padding, no recompute counted).  roofline = the kernel with the longest
+average launch, timed with HIP events recorded on the launch stream around every launch of the
+timed region.  cpu_baseline = the float64 oracle timed on this machine's host cores on a bounded
+sample of heads of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "fwd+JVP and bwd attention TFLOP/s & %MFMA peak at DiT-XL/2 N=256/1024"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# Algorithmic flops per launch, in units of B*H*N^2*d.  The six score-type products of the
+# backward are counted once, with the key-side kernel; the query-side kernel's recompute of
+# them is overhead, not algorithmic work.  12 + 24 + 6 = 42.
+KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.0}
+
+# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
+# copy kernel of known size (see profiles/).  None until measured for that workload and kernel.
+MEASURED_TRAFFIC = {}
+
+
+class Hip:
+    """The handful of HIP runtime calls needed for event timing on torch's stream."""
+
+    def __init__(self):
+        self.rt = ctypes.CDLL("libamdhip64.so")
+        self.rt.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.rt.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def check(self, rc, what):
+        if rc != 0:
+            raise RuntimeError(f"{what} failed with hipError {rc}")
+
+    def event(self):
+        e = ctypes.c_void_p()
+        self.check(self.rt.hipEventCreate(ctypes.byref(e)), "hipEventCreate")
+        return e.value
+
+    def record(self, e, stream):
+        self.check(self.rt.hipEventRecord(e, stream), "hipEventRecord")
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        self.check(self.rt.hipEventSynchronize(b), "hipEventSynchronize")
+        self.check(self.rt.hipEventElapsedTime(ctypes.byref(ms), a, b), "hipEventElapsedTime")
+        return float(ms.value)
+
+    def destroy(self, e):
+        self.rt.hipEventDestroy(e)
+
+
+def run_workload(w, steps, warmup, hip, seed=2024):
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    inp = wl.make_inputs(w, seed)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    del inp
+    six = [dev[n] for n in wl.NAMES[:6]]
+    B, H, N, d = w.B, w.H, w.N, w.d
+    fwd_out = (torch.empty_like(six[0]), torch.empty_like(six[0]),
+               torch.empty((B, H, N), dtype=torch.float32, device="cuda"),
+               torch.empty((B, H, N), dtype=torch.float32, device="cuda"))
+    bwd_out = tuple(torch.empty_like(six[0]) for _ in range(6))
+    ws = torch.empty(tvm.tvmattn_jvp_bwd_workspace_bytes(six[0]), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(ev=None):
+        if ev is not None:
+            hip.record(ev[0], stream)
+        tvm.tvmattn_jvp_fwd(*six, out=fwd_out)
+        if ev is not None:
+            hip.record(ev[1], stream)
+            tvm.tvmattn_set_bwd_events(ev[2:6])
+        tvm.tvmattn_jvp_bwd(*six, *fwd_out, dev["gO"], dev["gTO"], out=bwd_out, workspace=ws)
+
+    for _ in range(warmup):
+        step()
+    events = [[hip.event() for _ in range(6)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tvm.tvmattn_set_bwd_events(None)
+
+    names = ("fwd", "bwd_pre", "bwd_col", "bwd_row")
+    pairs = ((0, 1), (2, 3), (3, 4), (4, 5))
+    kern_ms = {n: sum(hip.elapsed_ms(ev[a], ev[b]) for ev in events) / steps for n, (a, b) in zip(names, pairs)}
+    for ev in events:
+        for e in ev:
+            hip.destroy(e)
+    for t in list(fwd_out) + list(bwd_out):
+        assert bool(torch.isfinite(t.float()).all()), "non-finite output in the timed region"
+
+    unit = float(B) * H * N * N * d
+    ms_step = (t1 - t0) * 1e3 / steps
+    res = {
+        "workload": f"{w.name} {w.note}: B={B} H={H} N={N} d={d} {w.dtype}",
+        "ms_per_step": ms_step,
+        "tflops": 42.0 * unit / (ms_step * 1e-3) / 1e12,
+        "kernels": {},
+    }
+    for n in names:
+        ms = kern_ms[n]
+        fl = KERNEL_FLOP_UNITS[n] * unit
+        res["kernels"][n] = {"ms": ms, "tflops": fl / (ms * 1e-3) / 1e12 if ms > 0 else None}
+    res["fwd_tflops"] = res["kernels"]["fwd"]["tflops"]
+    bwd_ms = kern_ms["bwd_pre"] + kern_ms["bwd_col"] + kern_ms["bwd_row"]
+    res["bwd_tflops"] = 30.0 * unit / (bwd_ms * 1e-3) / 1e12
+    res["fwd_hbm_gbs"] = w.fwd_bytes() / (kern_ms["fwd"] * 1e-3) / 1e9
+    res["bwd_hbm_gbs"] = w.bwd_bytes() / (bwd_ms * 1e-3) / 1e9
+    return res, kern_ms, unit
+
+
+def cpu_baseline(w, budget_s=20.0, seed=2024):
+    """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
+    from oracle import tvmattn_oracle as orc
+    from paper_2511_19797_amd import workloads as wl
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    small = wl.custom(1, min(w.heads, 256), w.N, w.d, w.dtype, w.tangent_std, w.key_scale)
+    inp = wl.make_inputs(small, seed)
+    arrs = [wl.to_f64(inp[n]) for n in wl.NAMES]
+    done, t0 = 0, time.perf_counter()
+    while done < small.H:
+        a = [x[0, done] for x in arrs]
+        orc.attn_jvp_fwd_head(*a[:6])
+        orc.attn_jvp_bwd_head(*a)
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    flops = 42.0 * done * w.N * w.N * w.d
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {w.heads} heads of {w.name} (N={w.N}, d={w.d}), float64 numpy, "
+                      f"forward+backward, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--also", default="C3", help="comma-separated extra workloads reported under 'also'")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
+              "Heads shard over GPUs with no exchange; no multi-GPU figure is produced.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2511_19797_amd import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    hip = Hip()
+    w = wl.CONFIGS[args.workload]
+    res, kern_ms, unit = run_workload(w, args.steps, args.warmup, hip)
+
+    dom = max(("fwd", "bwd_col", "bwd_row"), key=lambda n: kern_ms[n])
+    achieved = KERNEL_FLOP_UNITS[dom] * unit / (kern_ms[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_ms": kern_ms[dom],
+                "traffic": MEASURED_TRAFFIC.get((w.name, dom))}
+
+    also = {}
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        r, _, _ = run_workload(wl.CONFIGS[name], args.steps, args.warmup, hip)
+        also[name] = r
+
+    out = {
+        "metric": METRIC, "value": res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": res["workload"], "flops_per_step": 42.0 * unit,
+                   "flop_formula": "42*B*H*N^2*d (fwd 12, bwd 30)"},
+        "pct_mfma_peak": 100.0 * res["tflops"] / PEAK_BF16_TFLOPS,
+        "fwd_tflops": res["fwd_tflops"], "bwd_tflops": res["bwd_tflops"],
+        "fwd_hbm_gbs": res["fwd_hbm_gbs"], "bwd_hbm_gbs": res["bwd_hbm_gbs"],
+        "kernels": res["kernels"], "roofline": roofline, "also": also,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

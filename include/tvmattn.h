@@ -89,6 +89,15 @@ const char* tvmattn_strerror(int status);
 int tvmattn_set_path(int path);
 
 /*
+ * Diagnostic timing hook, process-wide, not thread-safe.  `events` is NULL (off, the default)
+ * or points to four hipEvent_t handles created by the caller with timing enabled; while set,
+ * every tvmattn_jvp_bwd call records, on its stream, events[0] before its first launch,
+ * events[1] after the row-scalar kernel, events[2] after the key-side kernel and events[3]
+ * after the query-side kernel.  The four handles are copied; the array need not outlive the call.
+ */
+int tvmattn_set_bwd_events(void* const* events);
+
+/*
  * Forward with tangent (one online-softmax pass over the keys).
  *   in : q,k,v,tq,tk,tv   [B,H,N,D] dtype
  *   out: o, to            [B,H,N,D] dtype

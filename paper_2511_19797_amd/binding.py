@@ -45,6 +45,8 @@ def lib():
         L.tvmattn_strerror.argtypes = [ctypes.c_int]
         L.tvmattn_set_path.restype = ctypes.c_int
         L.tvmattn_set_path.argtypes = [ctypes.c_int]
+        L.tvmattn_set_bwd_events.restype = ctypes.c_int
+        L.tvmattn_set_bwd_events.argtypes = [ctypes.POINTER(_P)]
         L.tvmattn_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 11
         L.tvmattn_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -65,6 +67,15 @@ def tvmattn_strerror(status):
 
 def tvmattn_set_path(path):
     _check(lib().tvmattn_set_path(int(path)))
+
+
+def tvmattn_set_bwd_events(events):
+    """`events`: None, or four raw hipEvent_t handles (ints) created with timing enabled."""
+    if events is None:
+        _check(lib().tvmattn_set_bwd_events(None))
+    else:
+        arr = (_P * 4)(*[_P(int(e)) for e in events])
+        _check(lib().tvmattn_set_bwd_events(arr))
 
 
 def _check(status):

@@ -302,18 +302,22 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 }
 
 template <int DK, int DV>
-hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  const dim3 grid(nfb * s.B * s.H), block(kNT);
-  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
-                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse, a.stats,
-                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk, (bf16*)a.dtk, (bf16*)a.dv,
-                     (bf16*)a.dtv);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
-                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse, a.stats,
-                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
+                     a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
+                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
+  return hipGetLastError();
+}
+
+template <int DK, int DV>
+hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const int nfb = (s.N + kFix - 1) / kFix;
+  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
+                     a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq,
+                     (bf16*)a.dtq);
   return hipGetLastError();
 }
 
@@ -321,19 +325,20 @@ hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
 
 bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 == 0 && s.D <= 128; }
 
-hipError_t launch_bwd_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  const int dk = (s.D + 15) / 16 * 16;
-  switch (dk) {
-    case 16: return launch<16, 32>(s, a, st);
-    case 32: return launch<32, 32>(s, a, st);
-    case 48: return launch<48, 64>(s, a, st);
-    case 64: return launch<64, 64>(s, a, st);
-    case 80: return launch<80, 96>(s, a, st);
-    case 96: return launch<96, 96>(s, a, st);
-    case 112: return launch<112, 128>(s, a, st);
-    case 128: return launch<128, 128>(s, a, st);
-    default: return hipErrorNotSupported;
+#define TVM_DISPATCH_D(FN)                        \
+  switch ((s.D + 15) / 16 * 16) {                 \
+    case 16: return FN<16, 32>(s, a, st);         \
+    case 32: return FN<32, 32>(s, a, st);         \
+    case 48: return FN<48, 64>(s, a, st);         \
+    case 64: return FN<64, 64>(s, a, st);         \
+    case 80: return FN<80, 96>(s, a, st);         \
+    case 96: return FN<96, 96>(s, a, st);         \
+    case 112: return FN<112, 128>(s, a, st);      \
+    case 128: return FN<128, 128>(s, a, st);      \
+    default: return hipErrorNotSupported;         \
   }
-}
+
+hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) { TVM_DISPATCH_D(launch_col) }
+hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) { TVM_DISPATCH_D(launch_row) }
 
 }  // namespace tvm

@@ -336,13 +336,17 @@ hipError_t bwd_pre_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
 }
 
 template <typename T>
-hipError_t bwd_generic_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t bwd_col_generic_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
   dim3 grid(((s.N + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
   hipLaunchKernelGGL(bwd_col_generic_kernel<T>, grid, dim3(256), 0, st, s, (const T*)a.q, (const T*)a.k,
                      (const T*)a.v, (const T*)a.tq, (const T*)a.tk, (const T*)a.tv, a.lse, a.stats, (const T*)a.gO,
                      (const T*)a.gTO, a.dsig, a.sig1, (T*)a.dk, (T*)a.dtk, (T*)a.dv, (T*)a.dtv);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t bwd_row_generic_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  dim3 grid(((s.N + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
   hipLaunchKernelGGL(bwd_row_generic_kernel<T>, grid, dim3(256), 0, st, s, (const T*)a.q, (const T*)a.k,
                      (const T*)a.v, (const T*)a.tq, (const T*)a.tk, (const T*)a.tv, a.lse, a.stats, (const T*)a.gO,
                      (const T*)a.gTO, a.dsig, a.sig1, (T*)a.dq, (T*)a.dtq);
@@ -357,8 +361,11 @@ hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipSt
 hipError_t launch_bwd_pre(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st) {
   return dtype == 0 ? bwd_pre_t<float>(s, a, st) : bwd_pre_t<bf16>(s, a, st);
 }
-hipError_t launch_bwd_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st) {
-  return dtype == 0 ? bwd_generic_t<float>(s, a, st) : bwd_generic_t<bf16>(s, a, st);
+hipError_t launch_bwd_col_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st) {
+  return dtype == 0 ? bwd_col_generic_t<float>(s, a, st) : bwd_col_generic_t<bf16>(s, a, st);
+}
+hipError_t launch_bwd_row_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st) {
+  return dtype == 0 ? bwd_row_generic_t<float>(s, a, st) : bwd_row_generic_t<bf16>(s, a, st);
 }
 
 }  // namespace tvm

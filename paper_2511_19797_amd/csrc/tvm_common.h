@@ -47,11 +47,13 @@ struct BwdArgs {
 
 hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_pre(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
-hipError_t launch_bwd_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_col_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_generic(const Shape& s, int dtype, const BwdArgs& a, hipStream_t st);
 
 // bf16 matrix-core paths; `supported` says whether the shape is one they take.
 bool mfma_supported(const Shape& s, int dtype);
 hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
-hipError_t launch_bwd_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 
 }  // namespace tvm

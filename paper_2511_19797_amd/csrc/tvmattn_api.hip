@@ -8,6 +8,12 @@
 namespace {
 
 int g_path = 0;  // 0 = choose per shape, 1 = plain-ALU kernels only (diagnostic)
+hipEvent_t g_ev[4];
+bool g_ev_on = false;
+
+inline void mark(int i, hipStream_t st) {
+  if (g_ev_on) (void)hipEventRecord(g_ev[i], st);
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -77,6 +83,19 @@ int tvmattn_set_path(int path) {
   return TVMATTN_OK;
 }
 
+int tvmattn_set_bwd_events(void* const* events) {
+  g_ev_on = events != nullptr;
+  if (events)
+    for (int i = 0; i < 4; ++i) {
+      if (!events[i]) {
+        g_ev_on = false;
+        return TVMATTN_INVALID_ARG;
+      }
+      g_ev[i] = static_cast<hipEvent_t>(events[i]);
+    }
+  return TVMATTN_OK;
+}
+
 int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
                     const void* tk, const void* tv, void* o, void* to, float* lse, float* stats, void* hip_stream) {
   tvm::Shape s;
@@ -122,12 +141,16 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
                  static_cast<float*>(workspace),
                  reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2)};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  mark(0, st);
   hipError_t e = tvm::launch_bwd_pre(s, desc->dtype, a, st);
   if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
-  if (g_path == 0 && tvm::mfma_supported(s, desc->dtype))
-    e = tvm::launch_bwd_mfma(s, a, st);
-  else
-    e = tvm::launch_bwd_generic(s, desc->dtype, a, st);
+  mark(1, st);
+  const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
+  e = mf ? tvm::launch_bwd_col_mfma(s, a, st) : tvm::launch_bwd_col_generic(s, desc->dtype, a, st);
+  if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
+  mark(2, st);
+  e = mf ? tvm::launch_bwd_row_mfma(s, a, st) : tvm::launch_bwd_row_generic(s, desc->dtype, a, st);
+  mark(3, st);
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
 
