@@ -15,9 +15,11 @@
 // Both kernels share one skeleton.  A wave owns 32 rows of the "fixed" side (keys for the
 // key-side kernel, queries for the query-side one) and keeps that side's four tensors as
 // B-operand fragments in registers; the other side is streamed through LDS in tiles of 64
-// rows, row-major for the score products and transposed (slot order) for the output products.
-// Score tiles are D[streamed][fixed]: a lane owns one fixed row, its 16 registers run over
-// streamed rows, and the tile feeds the output products straight from registers.
+// rows (row-major, swizzled), read directly for the score products and through the
+// transposing LDS read for the output products.  The next tile's global loads are issued into
+// registers before the current tile is computed.  Score tiles are D[streamed][fixed]: a lane
+// owns one fixed row, its 16 registers run over streamed rows, and the tile feeds the output
+// products straight from registers.
 // No atomics anywhere: every output element is produced by exactly one lane.
 #include "mfma_tiles.h"
 
@@ -29,51 +31,10 @@ constexpr int kTS = 64;    // streamed rows per LDS tile
 constexpr int kNT = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int DK, int DV>
-struct ColLds {
-  static constexpr int KP = DK + 8, IP = kTS + 8;
-  bf16 q[kTS * KP], tq[kTS * KP], g[kTS * KP], tg[kTS * KP];
-  bf16 qT[DV * IP], tqT[DV * IP], gT[DV * IP], tgT[DV * IP];
-  float lse2[kTS], mub[kTS], dsig[kTS], sig1[kTS];
-};
-
-template <int DK, int DV>
-struct RowLds {
-  static constexpr int KP = DK + 8, JP = kTS + 8;
-  bf16 k[kTS * KP], tk[kTS * KP], v[kTS * KP], tv[kTS * KP];
-  bf16 kT[DV * JP], tkT[DV * JP];
-};
-
 template <int NDB>
 __device__ __forceinline__ void zero_acc(f32x16 (&a)[NDB]) {
 #pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) a[db][r] = 0.f;
-}
-
-__device__ __forceinline__ f32x16 zero16() {
-  f32x16 z;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) z[r] = 0.f;
-  return z;
-}
-
-// Stores a transposed accumulator (rows = d, column = this lane's fixed row) as bf16, scaled.
-template <int NDB>
-__device__ __forceinline__ void store_acc(bf16* __restrict__ dst, const f32x16 (&a)[NDB], float scale, int D, int hh) {
-#pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = db * 32 + 8 * g + 4 * hh;
-      if (d0 < D) {
-        bf16x4 o;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
-        *reinterpret_cast<bf16x4*>(dst + d0) = o;
-      }
-    }
+  for (int db = 0; db < NDB; ++db) a[db] = zero16();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -86,16 +47,39 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
     bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
-  using L = ColLds<DK, DV>;
-  __shared__ __attribute__((aligned(16))) L sm;
+  using TX = Tile<kTS, DV / 8, kNT>;  // read both ways: columns up to DV
+  __shared__ __attribute__((aligned(16))) char lds_q[TX::BYTES], lds_tq[TX::BYTES], lds_g[TX::BYTES],
+      lds_tg[TX::BYTES];
+  __shared__ __attribute__((aligned(16))) float row_lse2[kTS], row_mub[kTS], row_dsig[kTS], row_sig1[kTS];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
-  const int bh = blockIdx.x / nfb, fb = blockIdx.x - bh * nfb;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
   const long long base = b * s.sb + h * s.sh;
+  const long long rbase = (long long)bh * s.N;
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
   const bool jok = j < s.N;
+
+  uint4 stQ[TX::NIT], stTQ[TX::NIT], stG[TX::NIT], stTG[TX::NIT];
+  float st_lse2 = 0.f, st_mub = 0.f, st_dsig = 0.f, st_sig1 = 0.f;
+  auto prefetch = [&](int i0) {
+    TX::gload(stQ, q + base, s.sn, i0, s.N, s.D, tid);
+    TX::gload(stTQ, tq + base, s.sn, i0, s.N, s.D, tid);
+    TX::gload(stG, gO + base, s.sn, i0, s.N, s.D, tid);
+    TX::gload(stTG, gTO + base, s.sn, i0, s.N, s.D, tid);
+    if (tid < kTS) {
+      // rows beyond N: lse = +inf gives them probability exactly 0 (and their Q/G rows are zero)
+      const bool ok = i0 + tid < s.N;
+      const long long r = rbase + i0 + tid;
+      st_lse2 = ok ? lse[r] * kLog2e : INFINITY;
+      st_mub = ok ? stats[r] : 0.f;
+      st_dsig = ok ? dsig[r] : 0.f;
+      st_sig1 = ok ? sig1[r] : 0.f;
+    }
+  };
+  prefetch(0);
 
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
 #pragma unroll
@@ -116,50 +100,48 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   const float c1 = s.alpha * kLog2e;
 
   for (int i0 = 0; i0 < s.N; i0 += kTS) {
-    __syncthreads();
-    load_rows<kTS, DK, L::KP, kNT>(sm.q, q + base, s.sn, i0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.tq, tq + base, s.sn, i0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.g, gO + base, s.sn, i0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.tg, gTO + base, s.sn, i0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::IP, kNT>(sm.qT, q + base, s.sn, i0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::IP, kNT>(sm.tqT, tq + base, s.sn, i0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::IP, kNT>(sm.gT, gO + base, s.sn, i0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::IP, kNT>(sm.tgT, gTO + base, s.sn, i0, s.N, s.D, tid);
+    __syncthreads();  // everyone is done reading the previous tile
+    TX::sstore(lds_q, stQ, tid);
+    TX::sstore(lds_tq, stTQ, tid);
+    TX::sstore(lds_g, stG, tid);
+    TX::sstore(lds_tg, stTG, tid);
     if (tid < kTS) {
-      // rows beyond N: lse = +inf gives them probability exactly 0 (and their Q/G rows are zero)
-      const bool ok = i0 + tid < s.N;
-      const long long r = (long long)bh * s.N + i0 + tid;
-      sm.lse2[tid] = ok ? lse[r] * kLog2e : INFINITY;
-      sm.mub[tid] = ok ? stats[r] : 0.f;
-      sm.dsig[tid] = ok ? dsig[r] : 0.f;
-      sm.sig1[tid] = ok ? sig1[r] : 0.f;
+      row_lse2[tid] = st_lse2;
+      row_mub[tid] = st_mub;
+      row_dsig[tid] = st_dsig;
+      row_sig1[tid] = st_sig1;
     }
     __syncthreads();
+    if (i0 + kTS < s.N) prefetch(i0 + kTS);  // uniform: in flight while this tile is computed
 
-#pragma unroll
+#pragma unroll 1
     for (int ib = 0; ib < kTS / 32; ++ib) {
       if (i0 + ib * 32 >= s.N) break;  // uniform
-      f32x16 sS = zero16(), sT = zero16(), sDF = zero16(), sE = zero16();
+      const int srow = ib * 32 + ic;
+      f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const int off = (ib * 32 + ic) * L::KP + kk * 16 + hh * 8;
-        const bf16x8 qf = lds_frag(sm.q + off), tqf = lds_frag(sm.tq + off);
-        const bf16x8 gf = lds_frag(sm.g + off), tgf = lds_frag(sm.tg + off);
+        const bf16x8 qf = TX::frag_row(lds_q, srow, kk, hh), tqf = TX::frag_row(lds_tq, srow, kk, hh);
         sS = mfma(qf, kf[kk], sS);
         sT = mfma(tqf, kf[kk], sT);
         sT = mfma(qf, tkf[kk], sT);
+      }
+      f32x16 sDF = zero16(), sE = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        const bf16x8 gf = TX::frag_row(lds_g, srow, kk, hh), tgf = TX::frag_row(lds_tg, srow, kk, hh);
+        sE = mfma(tgf, vf[kk], sE);
         sDF = mfma(gf, vf[kk], sDF);
         sDF = mfma(tgf, tvf[kk], sDF);
-        sE = mfma(tgf, vf[kk], sE);
       }
       bf16x8 pf[2], pdf[2], gzf[2], gztf[2];
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int ro = ib * 32 + 8 * g4 + 4 * hh;
-        const float4 l4 = *reinterpret_cast<const float4*>(sm.lse2 + ro);
-        const float4 m4 = *reinterpret_cast<const float4*>(sm.mub + ro);
-        const float4 d4 = *reinterpret_cast<const float4*>(sm.dsig + ro);
-        const float4 s4 = *reinterpret_cast<const float4*>(sm.sig1 + ro);
+        const float4 l4 = *reinterpret_cast<const float4*>(row_lse2 + ro);
+        const float4 m4 = *reinterpret_cast<const float4*>(row_mub + ro);
+        const float4 d4 = *reinterpret_cast<const float4*>(row_dsig + ro);
+        const float4 s4 = *reinterpret_cast<const float4*>(row_sig1 + ro);
         const float la[4] = {l4.x, l4.y, l4.z, l4.w}, ma[4] = {m4.x, m4.y, m4.z, m4.w};
         const float da[4] = {d4.x, d4.y, d4.z, d4.w}, sa[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
@@ -176,15 +158,16 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
         }
       }
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+      for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const int off = (db * 32 + ic) * L::IP + (2 * ib + cc) * 16 + hh * 8;
-          const bf16x8 qT = lds_frag(sm.qT + off), tqT = lds_frag(sm.tqT + off);
-          const bf16x8 gT = lds_frag(sm.gT + off), tgT = lds_frag(sm.tgT + off);
+        for (int db = 0; db < NDB; ++db) {
+          const bf16x8 gT = TX::frag_tr(lds_g, 2 * ib + cc, db, ic, hh);
+          const bf16x8 tgT = TX::frag_tr(lds_tg, 2 * ib + cc, db, ic, hh);
           aV[db] = mfma(gT, pf[cc], aV[db]);
           aV[db] = mfma(tgT, pdf[cc], aV[db]);
           aTV[db] = mfma(tgT, pf[cc], aTV[db]);
+          const bf16x8 qT = TX::frag_tr(lds_q, 2 * ib + cc, db, ic, hh);
+          const bf16x8 tqT = TX::frag_tr(lds_tq, 2 * ib + cc, db, ic, hh);
           aK[db] = mfma(qT, gzf[cc], aK[db]);
           aK[db] = mfma(tqT, gztf[cc], aK[db]);
           aTK[db] = mfma(qT, gztf[cc], aTK[db]);
@@ -209,16 +192,28 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
     bf16* __restrict__ dq, bf16* __restrict__ dtq) {
-  using L = RowLds<DK, DV>;
-  __shared__ __attribute__((aligned(16))) L sm;
+  using TK = Tile<kTS, DV / 8, kNT>;  // K, tK: read both ways
+  using TV = Tile<kTS, DK / 8, kNT>;  // V, tV: score products only
+  __shared__ __attribute__((aligned(16))) char lds_k[TK::BYTES], lds_tk[TK::BYTES], lds_v[TV::BYTES],
+      lds_tv[TV::BYTES];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
-  const int bh = blockIdx.x / nfb, fb = blockIdx.x - bh * nfb;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
   const long long base = b * s.sb + h * s.sh;
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
   const bool iok = i < s.N;
+
+  uint4 stK[TK::NIT], stTK[TK::NIT], stV[TV::NIT], stTV[TV::NIT];
+  auto prefetch = [&](int j0) {
+    TK::gload(stK, k + base, s.sn, j0, s.N, s.D, tid);
+    TK::gload(stTK, tk + base, s.sn, j0, s.N, s.D, tid);
+    TV::gload(stV, v + base, s.sn, j0, s.N, s.D, tid);
+    TV::gload(stTV, tv + base, s.sn, j0, s.N, s.D, tid);
+  };
+  prefetch(0);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
 #pragma unroll
@@ -244,29 +239,32 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 
   for (int j0 = 0; j0 < s.N; j0 += kTS) {
     __syncthreads();
-    load_rows<kTS, DK, L::KP, kNT>(sm.k, k + base, s.sn, j0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.tk, tk + base, s.sn, j0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.v, v + base, s.sn, j0, s.N, s.D, tid);
-    load_rows<kTS, DK, L::KP, kNT>(sm.tv, tv + base, s.sn, j0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::JP, kNT>(sm.kT, k + base, s.sn, j0, s.N, s.D, tid);
-    load_transposed<kTS, DV, L::JP, kNT>(sm.tkT, tk + base, s.sn, j0, s.N, s.D, tid);
+    TK::sstore(lds_k, stK, tid);
+    TK::sstore(lds_tk, stTK, tid);
+    TV::sstore(lds_v, stV, tid);
+    TV::sstore(lds_tv, stTV, tid);
     __syncthreads();
+    if (j0 + kTS < s.N) prefetch(j0 + kTS);  // uniform
 
-#pragma unroll
+#pragma unroll 1
     for (int jb = 0; jb < kTS / 32; ++jb) {
       if (j0 + jb * 32 >= s.N) break;  // uniform
-      f32x16 sS = zero16(), sT = zero16(), sDF = zero16(), sE = zero16();
+      const int srow = jb * 32 + ic;
+      f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const int off = (jb * 32 + ic) * L::KP + kk * 16 + hh * 8;
-        const bf16x8 kf = lds_frag(sm.k + off), tkf = lds_frag(sm.tk + off);
-        const bf16x8 vf = lds_frag(sm.v + off), tvf = lds_frag(sm.tv + off);
+        const bf16x8 kf = TK::frag_row(lds_k, srow, kk, hh), tkf = TK::frag_row(lds_tk, srow, kk, hh);
         sS = mfma(kf, qf[kk], sS);
         sT = mfma(kf, tqf[kk], sT);
         sT = mfma(tkf, qf[kk], sT);
+      }
+      f32x16 sDF = zero16(), sE = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        const bf16x8 vf = TV::frag_row(lds_v, srow, kk, hh), tvf = TV::frag_row(lds_tv, srow, kk, hh);
+        sE = mfma(vf, tgf[kk], sE);
         sDF = mfma(vf, gf[kk], sDF);
         sDF = mfma(tvf, tgf[kk], sDF);
-        sE = mfma(vf, tgf[kk], sE);
       }
       if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
 #pragma unroll
@@ -284,11 +282,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
         gztf[rr >> 3][rr & 7] = (bf16)gzt;
       }
 #pragma unroll
-      for (int db = 0; db < NDB; ++db)
+      for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const int off = (db * 32 + ic) * L::JP + (2 * jb + cc) * 16 + hh * 8;
-          const bf16x8 kT = lds_frag(sm.kT + off), tkT = lds_frag(sm.tkT + off);
+        for (int db = 0; db < NDB; ++db) {
+          const bf16x8 kT = TK::frag_tr(lds_k, 2 * jb + cc, db, ic, hh);
+          const bf16x8 tkT = TK::frag_tr(lds_tk, 2 * jb + cc, db, ic, hh);
           aQ[db] = mfma(kT, gzf[cc], aQ[db]);
           aQ[db] = mfma(tkT, gztf[cc], aQ[db]);
           aTQ[db] = mfma(kT, gztf[cc], aTQ[db]);

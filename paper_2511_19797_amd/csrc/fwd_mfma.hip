@@ -1,16 +1,20 @@
 // Forward with tangent on the bf16 matrix cores (gfx950).
 //
-// One workgroup = 4 waves = 128 query rows of one (batch, head); wave w owns rows 32w..32w+31
-// and keeps Q, tQ as B-operand fragments in registers for the whole kernel.  Keys are streamed
-// in tiles of 64 through LDS: K, tK row-major (A operands of the score products), V, tV
-// transposed in slot order (A operands of the output products).
+// One workgroup = NW waves, 32 query rows per wave, all of one (batch, head); a wave keeps Q, tQ
+// as B-operand fragments in registers for the whole kernel.  Keys are streamed in tiles of 64
+// through LDS (row-major, swizzled): K, tK are read as score-product A operands, V, tV through
+// the transposing LDS read as output-product A operands.  The next tile's global loads are
+// issued into registers before the current tile is computed, so HBM/L2 latency hides behind
+// the matrix-core work.
 //
-// Everything is computed transposed, S^T = K Q^T, so that a lane owns ONE query row
-// (column ic of every D tile): row max / row sums are in-lane reductions plus one exchange
-// between the two half-waves, the online-softmax rescale is a per-lane scalar, and the
-// probabilities feed the next product from registers.
+// Everything is computed transposed, S^T = K Q^T, so that a lane owns ONE query row (column ic
+// of every D tile): row max / row sums are in-lane reductions plus one exchange between the two
+// half-waves, the online-softmax rescale is a per-lane scalar, and the probabilities feed the
+// next product from registers.
 //
-// Per key tile (the equations under "Step 1" of App. C, evaluated with a running maximum):
+// Per 32-key block (the equations under "Step 1" of App. C, evaluated against a reference
+// maximum m that is only raised when some row's maximum outgrows it by more than 2^8, so the
+// accumulator rescale is rare; the final division by l makes the choice of m immaterial):
 //   S^T  = K Q^T            St^T = K tQ^T + tK Q^T
 //   p    = exp(alpha S - m)               (un-normalised)
 //   l   += sum p ;  c += sum p * alpha St
@@ -21,37 +25,37 @@
 namespace tvm {
 namespace {
 
-constexpr int kBM = 128;  // query rows per workgroup
-constexpr int kBN = 64;   // keys per LDS tile
-constexpr int kNT = 256;
+constexpr int kBN = 64;            // keys per LDS tile
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRescaleLog2 = 8.f;  // raise the reference maximum only beyond this growth (log2 units)
 
-template <int DK, int DV>
-struct FwdLds {
-  static constexpr int KP = DK + 8;   // row pitch (elements): 16-byte odd multiple -> conflict-free b128 reads
-  static constexpr int JP = kBN + 8;
-  bf16 k[kBN * KP];
-  bf16 tk[kBN * KP];
-  bf16 vt[DV * JP];
-  bf16 tvt[DV * JP];
-};
-
-template <int DK, int DV>
-__global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* __restrict__ q,
-                                                         const bf16* __restrict__ k, const bf16* __restrict__ v,
-                                                         const bf16* __restrict__ tq, const bf16* __restrict__ tk,
-                                                         const bf16* __restrict__ tv, bf16* __restrict__ o,
-                                                         bf16* __restrict__ to, float* __restrict__ lse,
-                                                         float* __restrict__ stats) {
-  using L = FwdLds<DK, DV>;
-  __shared__ __attribute__((aligned(16))) L sm;
+template <int DK, int DV, int NW>
+__global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* __restrict__ q,
+                                                          const bf16* __restrict__ k, const bf16* __restrict__ v,
+                                                          const bf16* __restrict__ tq, const bf16* __restrict__ tk,
+                                                          const bf16* __restrict__ tv, bf16* __restrict__ o,
+                                                          bf16* __restrict__ to, float* __restrict__ lse,
+                                                          float* __restrict__ stats) {
+  constexpr int NT = 64 * NW, BM = 32 * NW;
+  using TK = Tile<kBN, DK / 8, NT>;
+  using TV = Tile<kBN, DV / 8, NT>;
+  __shared__ __attribute__((aligned(16))) char lds_k[TK::BYTES], lds_tk[TK::BYTES], lds_v[TV::BYTES],
+      lds_tv[TV::BYTES];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
-  const int nmb = (s.N + kBM - 1) / kBM;
-  const int bh = blockIdx.x / nmb, mb = blockIdx.x - bh * nmb;
+  const int nmb = (s.N + BM - 1) / BM;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nmb, mb = wg - bh * nmb;
   const int b = bh / s.H, h = bh - b * s.H;
   const long long base = b * s.sb + h * s.sh;
-  const int i = mb * kBM + wave * 32 + ic;  // this lane's query row
+  const int i = mb * BM + wave * 32 + ic;  // this lane's query row
   const bool iok = i < s.N;
+
+  uint4 stK[TK::NIT], stTK[TK::NIT], stV[TV::NIT], stTV[TV::NIT];
+  TK::gload(stK, k + base, s.sn, 0, s.N, s.D, tid);
+  TK::gload(stTK, tk + base, s.sn, 0, s.N, s.D, tid);
+  TV::gload(stV, v + base, s.sn, 0, s.N, s.D, tid);
+  TV::gload(stTV, tv + base, s.sn, 0, s.N, s.D, tid);
 
   bf16x8 qf[NKS], tqf[NKS];
 #pragma unroll
@@ -64,36 +68,35 @@ __global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* _
 
   f32x16 accO[NDB], accT[NDB];
 #pragma unroll
-  for (int db = 0; db < NDB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      accO[db][r] = 0.f;
-      accT[db][r] = 0.f;
-    }
+  for (int db = 0; db < NDB; ++db) {
+    accO[db] = zero16();
+    accT[db] = zero16();
+  }
   float m = -INFINITY, l = 0.f, cs = 0.f;
-  const float c1 = s.alpha * 1.4426950408889634f;  // scores are exponentiated in base 2
+  const float c1 = s.alpha * kLog2e;  // scores are exponentiated in base 2
 
   for (int j0 = 0; j0 < s.N; j0 += kBN) {
+    __syncthreads();  // everyone is done reading the previous tile
+    TK::sstore(lds_k, stK, tid);
+    TK::sstore(lds_tk, stTK, tid);
+    TV::sstore(lds_v, stV, tid);
+    TV::sstore(lds_tv, stTV, tid);
     __syncthreads();
-    load_rows<kBN, DK, L::KP, kNT>(sm.k, k + base, s.sn, j0, s.N, s.D, tid);
-    load_rows<kBN, DK, L::KP, kNT>(sm.tk, tk + base, s.sn, j0, s.N, s.D, tid);
-    load_transposed<kBN, DV, L::JP, kNT>(sm.vt, v + base, s.sn, j0, s.N, s.D, tid);
-    load_transposed<kBN, DV, L::JP, kNT>(sm.tvt, tv + base, s.sn, j0, s.N, s.D, tid);
-    __syncthreads();
+    if (j0 + kBN < s.N) {  // uniform: prefetch the next tile while this one is computed
+      TK::gload(stK, k + base, s.sn, j0 + kBN, s.N, s.D, tid);
+      TK::gload(stTK, tk + base, s.sn, j0 + kBN, s.N, s.D, tid);
+      TV::gload(stV, v + base, s.sn, j0 + kBN, s.N, s.D, tid);
+      TV::gload(stTV, tv + base, s.sn, j0 + kBN, s.N, s.D, tid);
+    }
 
-#pragma unroll
+#pragma unroll 1
     for (int jb = 0; jb < kBN / 32; ++jb) {
       if (j0 + jb * 32 >= s.N) break;  // uniform: the rest of the tile is beyond the last key
-      f32x16 sS, sT;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        sS[r] = 0.f;
-        sT[r] = 0.f;
-      }
+      f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 kf = lds_frag(sm.k + (jb * 32 + ic) * L::KP + kk * 16 + hh * 8);
-        const bf16x8 tkf = lds_frag(sm.tk + (jb * 32 + ic) * L::KP + kk * 16 + hh * 8);
+        const bf16x8 kf = TK::frag_row(lds_k, jb * 32 + ic, kk, hh);
+        const bf16x8 tkf = TK::frag_row(lds_tk, jb * 32 + ic, kk, hh);
         sS = mfma(kf, qf[kk], sS);
         sT = mfma(kf, tqf[kk], sT);
         sT = mfma(tkf, qf[kk], sT);
@@ -106,11 +109,22 @@ __global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* _
       float mx = sS[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sS[r]);
-      mx = fmaxf(mx, xhalf(mx));
-      const float mn = fmaxf(m, mx);  // finite: key 0 is never masked
-      const float f = __builtin_amdgcn_exp2f((m - mn) * c1);
-      m = mn;
-      const float mc = mn * c1;
+      mx = fmaxf(mx, xhalf(mx));  // finite: key 0 is never masked and lives in the first block
+      if (__builtin_amdgcn_ballot_w64((mx - m) * c1 > kRescaleLog2) != 0) {  // uniform
+        const float mn = fmaxf(m, mx);
+        const float f = __builtin_amdgcn_exp2f((m - mn) * c1);  // m = -inf on the first block: 0
+        m = mn;
+        l *= f;
+        cs *= f;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            accO[db][r] *= f;
+            accT[db][r] *= f;
+          }
+      }
+      const float mc = m * c1;
       float ps = 0.f, pzs = 0.f;
       bf16x8 pf[2], pzf[2];
 #pragma unroll
@@ -122,23 +136,14 @@ __global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* _
         pf[r >> 3][r & 7] = (bf16)p;
         pzf[r >> 3][r & 7] = (bf16)pz;
       }
-      ps += xhalf(ps);
-      pzs += xhalf(pzs);
-      l = fmaf(l, f, ps);
-      cs = fmaf(cs, f, pzs);
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          accO[db][r] *= f;
-          accT[db][r] *= f;
-        }
+      l += ps;   // per-half partial sums; the halves are combined once, in the epilogue
+      cs += pzs;
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 vf = lds_frag(sm.vt + (db * 32 + ic) * L::JP + (2 * jb + cc) * 16 + hh * 8);
-          const bf16x8 tvf = lds_frag(sm.tvt + (db * 32 + ic) * L::JP + (2 * jb + cc) * 16 + hh * 8);
+          const bf16x8 vf = TV::frag_tr(lds_v, 2 * jb + cc, db, ic, hh);
+          const bf16x8 tvf = TV::frag_tr(lds_tv, 2 * jb + cc, db, ic, hh);
           accO[db] = mfma(vf, pf[cc], accO[db]);
           accT[db] = mfma(vf, pzf[cc], accT[db]);
           accT[db] = mfma(tvf, pf[cc], accT[db]);
@@ -146,6 +151,8 @@ __global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* _
     }
   }
 
+  l += xhalf(l);
+  cs += xhalf(cs);
   if (!iok) return;
   const float inv = 1.f / l;
   const float mubar = cs * inv;
@@ -175,18 +182,18 @@ __global__ __launch_bounds__(kNT, 2) void fwd_mfma_kernel(Shape s, const bf16* _
 
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  const int nmb = (s.N + kBM - 1) / kBM;
-  hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV>), dim3(nmb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
-                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
-                     (bf16*)a.o, (bf16*)a.to, a.lse, a.stats);
+  constexpr int NW = 8;
+  const int nmb = (s.N + 32 * NW - 1) / (32 * NW);
+  hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW>), dim3(nmb * s.B * s.H), dim3(64 * NW), 0, st, s,
+                     (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
+                     (const bf16*)a.tv, (bf16*)a.o, (bf16*)a.to, a.lse, a.stats);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  const int dk = (s.D + 15) / 16 * 16;
-  switch (dk) {
+  switch ((s.D + 15) / 16 * 16) {
     case 16: return launch<16, 32>(s, a, st);
     case 32: return launch<32, 32>(s, a, st);
     case 48: return launch<48, 64>(s, a, st);

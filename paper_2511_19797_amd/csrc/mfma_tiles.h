@@ -1,15 +1,24 @@
 // bf16 matrix-core building blocks shared by the forward and backward kernels (gfx950).
 //
-// One instruction is used throughout: v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] B[16x32].
+// One MFMA is used throughout: v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] B[16x32].
 // Operand layout per lane (lane = 32*hh + ic):
 //   A: row ic of A, eight consecutive k starting at 8*hh          (8 bf16 = 16 bytes)
 //   B: column ic of B, the same eight k
 //   D: column ic of D, rows 8*(r/4) + 4*hh + (r%4) for register r = 0..15
 // Since A and B index k the same way, any fixed permutation of k applied to both operands
-// leaves the product unchanged.  That is used to feed a D-layout tile straight back in as an
-// operand: registers 8c..8c+7 of a D tile are, for this lane, the eight "rows"
-// 16c + {0,1,2,3, 8,9,10,11} + 4*hh, so the other operand is stored in LDS with its
-// contraction index permuted to match ("slot order", see slot_pos below).
+// leaves the product unchanged.  That is used to feed a D-layout tile straight back in as the
+// B operand of the next product: registers 8c..8c+7 of a D tile are, for this lane, the eight
+// rows 16c + {0,1,2,3, 8,9,10,11} + 4*hh ("slot order"), so the A operand of that product is
+// fetched from LDS with its contraction index in the same order.
+//
+// LDS tiles are row-major [rows][D] in 16-byte chunks with a swizzle: element (s, col) lives in
+// physical chunk  s*PCH + ((col/8) ^ ((s>>2)&3)),  PCH = 4 (mod 8) chunks per row.  Two access
+// patterns hit every bank exactly once per pass with this layout:
+//   (R) ds_read_b128, lanes = 16 consecutive rows, same logical chunk      (score products)
+//   (T) ds_read_b64_tr_b16, a 32-lane half = 4 consecutive rows x 64 bytes  (output products)
+// The transposing read hands lane i of a 16-lane group the i-th column of the 4 x 16 block whose
+// row e is supplied by lanes 4e..4e+3 (four elements each); two of them build one A fragment of
+// X^T in slot order, with no transposed copy in LDS and no data movement through the VALU.
 #pragma once
 #include "tvm_common.h"
 
@@ -26,64 +35,71 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 // Row (M index) held in register r of a D tile by a lane of half hh.
 __device__ __forceinline__ int drow(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
 
-// Position, within a transposed LDS row, of contraction index x (0 <= x < multiple of 16):
-// x = 16c + 8g + 4h + t  ->  16c + 8h + 4g + t.  Runs of four consecutive x stay contiguous, and
-// the eight values a lane of half h needs for 16-chunk c are the 16 bytes at 16c + 8h.
-__device__ __forceinline__ int slot_pos(int x) {
-  return (x & ~15) | ((x & 4) << 1) | ((x & 8) >> 1) | (x & 3);
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
 }
 
-// Copies rows [r0, r0+ROWS) of a [N,D] bf16 matrix (row pitch sn) into dst[ROWS][PITCH], columns
-// [0,DK), zero-filling rows >= N and columns >= D.  D must be a multiple of 8.
-template <int ROWS, int DK, int PITCH, int NT>
-__device__ __forceinline__ void load_rows(bf16* dst, const bf16* __restrict__ src, long long sn, int r0, int N, int D,
-                                          int tid) {
-  constexpr int CH = DK / 8;
-  for (int idx = tid; idx < ROWS * CH; idx += NT) {
-    const int r = idx / CH, c = idx - r * CH;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (r0 + r < N && c * 8 < D) val = *reinterpret_cast<const uint4*>(src + (long long)(r0 + r) * sn + c * 8);
-    *reinterpret_cast<uint4*>(dst + r * PITCH + c * 8) = val;
-  }
+// Chunks (16 B) per LDS row for a tile whose widest access covers `cols` columns.
+constexpr int pitch_chunks(int cols) {
+  int p = (cols / 8 + 3) / 4 * 4;
+  return (p % 8 == 0) ? p + 4 : p;
 }
 
-// Same source rows, stored transposed and in slot order: dst[d][slot_pos(r)] for d in [0,DV).
-// Each thread takes four consecutive rows times eight columns and writes eight 8-byte runs.
-template <int ROWS, int DV, int PITCH, int NT>
-__device__ __forceinline__ void load_transposed(bf16* dst, const bf16* __restrict__ src, long long sn, int r0, int N,
-                                                int D, int tid) {
-  constexpr int OCT = DV / 8;
-  for (int idx = tid; idx < (ROWS / 4) * OCT; idx += NT) {
-    const int qd = idx / OCT, oc = idx - qd * OCT;
-    uint32_t w[4][4];
+// Byte offset of logical chunk c of row s.
+template <int PCH>
+__device__ __forceinline__ int chunk_off(int s, int c) {
+  return (s * PCH + (c ^ ((s >> 2) & 3))) * 16;
+}
+
+// A streamed tile: ROWS rows, logical chunks [0, NCH) staged (zero beyond D and beyond N).
+template <int ROWS_, int NCH_, int NT_>
+struct Tile {
+  static constexpr int ROWS = ROWS_, NCH = NCH_, NT = NT_;
+  static constexpr int PCH = pitch_chunks(NCH_ * 8);
+  static constexpr int BYTES = ROWS_ * PCH * 16;
+  static constexpr int NIT = (ROWS_ * NCH_ + NT_ - 1) / NT_;  // staging registers (uint4) per thread
+
+  // global -> registers for rows [r0, r0+ROWS) of a [N,D] matrix with row pitch sn
+  __device__ __forceinline__ static void gload(uint4 (&st)[NIT], const bf16* __restrict__ src, long long sn, int r0,
+                                               int N, int D, int tid) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int row = r0 + 4 * qd + t;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (row < N && oc * 8 < D) val = *reinterpret_cast<const uint4*>(src + (long long)row * sn + oc * 8);
-      w[t][0] = val.x;
-      w[t][1] = val.y;
-      w[t][2] = val.z;
-      w[t][3] = val.w;
-    }
-    const int pos = slot_pos(4 * qd);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int wi = e >> 1;
-      uint2 out;
-      if (e & 1) {
-        out.x = (w[0][wi] >> 16) | (w[1][wi] & 0xffff0000u);
-        out.y = (w[2][wi] >> 16) | (w[3][wi] & 0xffff0000u);
-      } else {
-        out.x = (w[0][wi] & 0xffffu) | (w[1][wi] << 16);
-        out.y = (w[2][wi] & 0xffffu) | (w[3][wi] << 16);
-      }
-      *reinterpret_cast<uint2*>(dst + (oc * 8 + e) * PITCH + pos) = out;
+    for (int t = 0; t < NIT; ++t) {
+      const int idx = tid + t * NT;
+      const int s = idx / NCH, c = idx - s * NCH;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (idx < ROWS * NCH && r0 + s < N && c * 8 < D)
+        v = *reinterpret_cast<const uint4*>(src + (long long)(r0 + s) * sn + c * 8);
+      st[t] = v;
     }
   }
-}
-
-__device__ __forceinline__ bf16x8 lds_frag(const bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+  // registers -> LDS (swizzled)
+  __device__ __forceinline__ static void sstore(char* lds, const uint4 (&st)[NIT], int tid) {
+#pragma unroll
+    for (int t = 0; t < NIT; ++t) {
+      const int idx = tid + t * NT;
+      const int s = idx / NCH, c = idx - s * NCH;
+      if (idx < ROWS * NCH) *reinterpret_cast<uint4*>(lds + chunk_off<PCH>(s, c)) = st[t];
+    }
+  }
+  // (R): eight consecutive columns 16*kk + 8*hh.. of row s
+  __device__ __forceinline__ static bf16x8 frag_row(const char* lds, int s, int kk, int hh) {
+    return *reinterpret_cast<const bf16x8*>(lds + chunk_off<PCH>(s, 2 * kk + hh));
+  }
+  // (T): A fragment of X^T: row (32*db + ic) of X^T, contraction index = rows 16*cc.. of X in slot order
+  __device__ __forceinline__ static bf16x8 frag_tr(const char* lds, int cc, int db, int ic, int hh) {
+    const int i = ic & 15, bq = ic >> 4;
+    const int s0 = 16 * cc + 4 * hh + (i >> 2);
+    const int c = 4 * db + 2 * bq + ((i & 3) >> 1);
+    const int sub = (i & 1) * 8;
+    typedef bf16x4 __attribute__((address_space(3))) * lp;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(lds + chunk_off<PCH>(s0, c) + sub));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(lds + chunk_off<PCH>(s0 + 8, c) + sub));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+};
 
 // Eight bf16 from global memory (16-byte aligned) or zeros.
 __device__ __forceinline__ bf16x8 gld_frag(const bf16* p, bool ok) {
@@ -93,5 +109,31 @@ __device__ __forceinline__ bf16x8 gld_frag(const bf16* p, bool ok) {
 }
 
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }
+
+// Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  This maps the
+// hardware id to a logical id such that consecutive logical ids (the blocks of one head, which
+// stream the same tensors) run on the same XCD.
+__device__ __forceinline__ int xcd_remap(int wg, int nwg) {
+  const int per = nwg >> 3;
+  if ((nwg & 7) != 0) return wg;
+  return (wg & 7) * per + (wg >> 3);
+}
+
+// Stores a transposed accumulator (rows = d, column = this lane's row of the output) as bf16, scaled.
+template <int NDB>
+__device__ __forceinline__ void store_acc(bf16* __restrict__ dst, const f32x16 (&a)[NDB], float scale, int D, int hh) {
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = db * 32 + 8 * g + 4 * hh;
+      if (d0 < D) {
+        bf16x4 o;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
+        *reinterpret_cast<bf16x4*>(dst + d0) = o;
+      }
+    }
+}
 
 }  // namespace tvm
