@@ -27,7 +27,6 @@ namespace tvm {
 namespace {
 
 constexpr int kFix = 128;  // fixed-side rows per workgroup (4 waves x 32)
-constexpr int kTS = 64;    // streamed rows per LDS tile
 constexpr int kNT = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -40,17 +39,17 @@ __device__ __forceinline__ void zero_acc(f32x16 (&a)[NDB]) {
 // ------------------------------------------------------------------------------------------
 // Key side.
 // ------------------------------------------------------------------------------------------
-template <int DK, int DV>
+template <int DK, int DV, int kTS>
 __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
     bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
-  using TX = Tile<kTS, DV / 8, kNT>;  // read both ways: columns up to DV
-  __shared__ __attribute__((aligned(16))) char lds_q[TX::BYTES], lds_tq[TX::BYTES], lds_g[TX::BYTES],
-      lds_tg[TX::BYTES];
-  __shared__ __attribute__((aligned(16))) float row_lse2[kTS], row_mub[kTS], row_dsig[kTS], row_sig1[kTS];
+  using TX = Tile<kTS, DV / 8, kNT / 64>;  // read both ways: columns up to DV
+  constexpr int ROWV = 4 * kTS * 4;                   // four float32 row vectors per stage
+  constexpr int BUF = 4 * TX::BYTES + ROWV;           // one stage: Q, tQ, G, tG, row vectors
+  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
@@ -62,24 +61,22 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
   const bool jok = j < s.N;
 
-  uint4 stQ[TX::NIT], stTQ[TX::NIT], stG[TX::NIT], stTG[TX::NIT];
-  float st_lse2 = 0.f, st_mub = 0.f, st_dsig = 0.f, st_sig1 = 0.f;
-  auto prefetch = [&](int i0) {
-    TX::gload(stQ, q + base, s.sn, i0, s.N, s.D, tid);
-    TX::gload(stTQ, tq + base, s.sn, i0, s.N, s.D, tid);
-    TX::gload(stG, gO + base, s.sn, i0, s.N, s.D, tid);
-    TX::gload(stTG, gTO + base, s.sn, i0, s.N, s.D, tid);
-    if (tid < kTS) {
-      // rows beyond N: lse = +inf gives them probability exactly 0 (and their Q/G rows are zero)
-      const bool ok = i0 + tid < s.N;
-      const long long r = rbase + i0 + tid;
-      st_lse2 = ok ? lse[r] * kLog2e : INFINITY;
-      st_mub = ok ? stats[r] : 0.f;
-      st_dsig = ok ? dsig[r] : 0.f;
-      st_sig1 = ok ? sig1[r] : 0.f;
-    }
+  const typename TX::Lane lx = TX::lane_setup(s.sn, s.D, wave, lane);
+  // wave w also fetches row vector w (lse, stats, dsig, sig1) of the tile, one float per lane
+  const float* const rowsrc = (wave == 0 ? lse : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
+  auto issue = [&](int i0, char* buf) {
+    TX::issue(lx, q + base, s.sn, i0, s.N, buf, wave);
+    TX::issue(lx, tq + base, s.sn, i0, s.N, buf + TX::BYTES, wave);
+    TX::issue(lx, gO + base, s.sn, i0, s.N, buf + 2 * TX::BYTES, wave);
+    TX::issue(lx, gTO + base, s.sn, i0, s.N, buf + 3 * TX::BYTES, wave);
+    if (lane < kTS && i0 + lane < s.N)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rowsrc + i0 + lane),
+                                       (__attribute__((address_space(3))) void*)(buf + 4 * TX::BYTES + wave * kTS * 4),
+                                       4, 0, 0);
   };
-  prefetch(0);
+  lds_zero<kNT>(lds, 2 * BUF, tid);
+  __syncthreads();
+  issue(0, lds);
 
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
 #pragma unroll
@@ -99,20 +96,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   zero_acc(aTV);
   const float c1 = s.alpha * kLog2e;
 
-  for (int i0 = 0; i0 < s.N; i0 += kTS) {
-    __syncthreads();  // everyone is done reading the previous tile
-    TX::sstore(lds_q, stQ, tid);
-    TX::sstore(lds_tq, stTQ, tid);
-    TX::sstore(lds_g, stG, tid);
-    TX::sstore(lds_tg, stTG, tid);
-    if (tid < kTS) {
-      row_lse2[tid] = st_lse2;
-      row_mub[tid] = st_mub;
-      row_dsig[tid] = st_dsig;
-      row_sig1[tid] = st_sig1;
-    }
-    __syncthreads();
-    if (i0 + kTS < s.N) prefetch(i0 + kTS);  // uniform: in flight while this tile is computed
+  __syncthreads();  // tile 0 has landed (the barrier waits for this wave's outstanding loads)
+  for (int i0 = 0, it = 0; i0 < s.N; i0 += kTS, ++it) {
+    const char* lds_q = lds + (it & 1) * BUF;
+    const char* lds_tq = lds_q + TX::BYTES;
+    const char* lds_g = lds_q + 2 * TX::BYTES;
+    const char* lds_tg = lds_q + 3 * TX::BYTES;
+    const float* row_lse = reinterpret_cast<const float*>(lds_q + 4 * TX::BYTES);
+    const float* row_mub = row_lse + kTS;
+    const float* row_dsig = row_lse + 2 * kTS;
+    const float* row_sig1 = row_lse + 3 * kTS;
+    if (i0 + kTS < s.N) issue(i0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll 1
     for (int ib = 0; ib < kTS / 32; ++ib) {
@@ -134,11 +128,16 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
         sDF = mfma(gf, vf[kk], sDF);
         sDF = mfma(tgf, tvf[kk], sDF);
       }
+      if (i0 + ib * 32 + 32 > s.N) {  // uniform: ragged last block, queries >= N get probability 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (i0 + ib * 32 + drow(r, hh) >= s.N) sS[r] = -INFINITY;
+      }
       bf16x8 pf[2], pdf[2], gzf[2], gztf[2];
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int ro = ib * 32 + 8 * g4 + 4 * hh;
-        const float4 l4 = *reinterpret_cast<const float4*>(row_lse2 + ro);
+        const float4 l4 = *reinterpret_cast<const float4*>(row_lse + ro);
         const float4 m4 = *reinterpret_cast<const float4*>(row_mub + ro);
         const float4 d4 = *reinterpret_cast<const float4*>(row_dsig + ro);
         const float4 s4 = *reinterpret_cast<const float4*>(row_sig1 + ro);
@@ -147,7 +146,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = 4 * g4 + t;
-          const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -la[t]));
+          const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -la[t] * kLog2e));
           const float n = fmaf(sT[r], s.alpha, -ma[t]);
           const float gzt = p * (sE[r] - sa[t]);
           const float gz = fmaf(gzt, n, p * (sDF[r] - da[t]));
@@ -173,6 +172,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
           aTK[db] = mfma(qT, gztf[cc], aTK[db]);
         }
     }
+    __syncthreads();  // next tile landed; everyone is done with this one
   }
   if (!jok) return;
   const long long ro = base + (long long)j * s.sn;
@@ -185,17 +185,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
 // ------------------------------------------------------------------------------------------
 // Query side.
 // ------------------------------------------------------------------------------------------
-template <int DK, int DV>
+template <int DK, int DV, int kTS>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
     bf16* __restrict__ dq, bf16* __restrict__ dtq) {
-  using TK = Tile<kTS, DV / 8, kNT>;  // K, tK: read both ways
-  using TV = Tile<kTS, DK / 8, kNT>;  // V, tV: score products only
-  __shared__ __attribute__((aligned(16))) char lds_k[TK::BYTES], lds_tk[TK::BYTES], lds_v[TV::BYTES],
-      lds_tv[TV::BYTES];
+  using TK = Tile<kTS, DV / 8, kNT / 64>;  // K, tK: read both ways
+  using TV = Tile<kTS, DK / 8, kNT / 64>;  // V, tV: score products only
+  constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
+  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
@@ -206,14 +206,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
   const bool iok = i < s.N;
 
-  uint4 stK[TK::NIT], stTK[TK::NIT], stV[TV::NIT], stTV[TV::NIT];
-  auto prefetch = [&](int j0) {
-    TK::gload(stK, k + base, s.sn, j0, s.N, s.D, tid);
-    TK::gload(stTK, tk + base, s.sn, j0, s.N, s.D, tid);
-    TV::gload(stV, v + base, s.sn, j0, s.N, s.D, tid);
-    TV::gload(stTV, tv + base, s.sn, j0, s.N, s.D, tid);
+  const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
+  const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
+  auto issue = [&](int j0, char* buf) {
+    TK::issue(lk, k + base, s.sn, j0, s.N, buf, wave);
+    TK::issue(lk, tk + base, s.sn, j0, s.N, buf + TK::BYTES, wave);
+    TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
+    TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
-  prefetch(0);
+  lds_zero<kNT>(lds, 2 * BUF, tid);
+  __syncthreads();
+  issue(0, lds);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
 #pragma unroll
@@ -237,14 +240,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   zero_acc(aTQ);
   const float c1 = s.alpha * kLog2e;
 
-  for (int j0 = 0; j0 < s.N; j0 += kTS) {
-    __syncthreads();
-    TK::sstore(lds_k, stK, tid);
-    TK::sstore(lds_tk, stTK, tid);
-    TV::sstore(lds_v, stV, tid);
-    TV::sstore(lds_tv, stTV, tid);
-    __syncthreads();
-    if (j0 + kTS < s.N) prefetch(j0 + kTS);  // uniform
+  __syncthreads();  // tile 0 has landed
+  for (int j0 = 0, it = 0; j0 < s.N; j0 += kTS, ++it) {
+    const char* lds_k = lds + (it & 1) * BUF;
+    const char* lds_tk = lds_k + TK::BYTES;
+    const char* lds_v = lds_k + 2 * TK::BYTES;
+    const char* lds_tv = lds_v + TV::BYTES;
+    if (j0 + kTS < s.N) issue(j0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll 1
     for (int jb = 0; jb < kTS / 32; ++jb) {
@@ -292,6 +294,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
           aTQ[db] = mfma(kT, gztf[cc], aTQ[db]);
         }
     }
+    __syncthreads();  // next tile landed; everyone is done with this one
   }
   if (!iok) return;
   const long long ro = base + (long long)i * s.sn;
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 template <int DK, int DV>
 hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
                      (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
@@ -312,7 +315,7 @@ hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
 template <int DK, int DV>
 hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq,
                      (bf16*)a.dtq);

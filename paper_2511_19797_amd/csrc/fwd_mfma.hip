@@ -25,22 +25,21 @@
 namespace tvm {
 namespace {
 
-constexpr int kBN = 64;            // keys per LDS tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRescaleLog2 = 8.f;  // raise the reference maximum only beyond this growth (log2 units)
 
-template <int DK, int DV, int NW>
-__global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* __restrict__ q,
+template <int DK, int DV, int NW, int kBN>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shape s, const bf16* __restrict__ q,
                                                           const bf16* __restrict__ k, const bf16* __restrict__ v,
                                                           const bf16* __restrict__ tq, const bf16* __restrict__ tk,
                                                           const bf16* __restrict__ tv, bf16* __restrict__ o,
                                                           bf16* __restrict__ to, float* __restrict__ lse,
                                                           float* __restrict__ stats) {
   constexpr int NT = 64 * NW, BM = 32 * NW;
-  using TK = Tile<kBN, DK / 8, NT>;
-  using TV = Tile<kBN, DV / 8, NT>;
-  __shared__ __attribute__((aligned(16))) char lds_k[TK::BYTES], lds_tk[TK::BYTES], lds_v[TV::BYTES],
-      lds_tv[TV::BYTES];
+  using TK = Tile<kBN, DK / 8, NW>;
+  using TV = Tile<kBN, DV / 8, NW>;
+  constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
+  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nmb = (s.N + BM - 1) / BM;
@@ -51,11 +50,17 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* 
   const int i = mb * BM + wave * 32 + ic;  // this lane's query row
   const bool iok = i < s.N;
 
-  uint4 stK[TK::NIT], stTK[TK::NIT], stV[TV::NIT], stTV[TV::NIT];
-  TK::gload(stK, k + base, s.sn, 0, s.N, s.D, tid);
-  TK::gload(stTK, tk + base, s.sn, 0, s.N, s.D, tid);
-  TV::gload(stV, v + base, s.sn, 0, s.N, s.D, tid);
-  TV::gload(stTV, tv + base, s.sn, 0, s.N, s.D, tid);
+  const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
+  const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
+  auto issue = [&](int j0, char* buf) {
+    TK::issue(lk, k + base, s.sn, j0, s.N, buf, wave);
+    TK::issue(lk, tk + base, s.sn, j0, s.N, buf + TK::BYTES, wave);
+    TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
+    TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
+  };
+  lds_zero<NT>(lds, 2 * BUF, tid);
+  __syncthreads();
+  issue(0, lds);
 
   bf16x8 qf[NKS], tqf[NKS];
 #pragma unroll
@@ -75,19 +80,13 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* 
   float m = -INFINITY, l = 0.f, cs = 0.f;
   const float c1 = s.alpha * kLog2e;  // scores are exponentiated in base 2
 
-  for (int j0 = 0; j0 < s.N; j0 += kBN) {
-    __syncthreads();  // everyone is done reading the previous tile
-    TK::sstore(lds_k, stK, tid);
-    TK::sstore(lds_tk, stTK, tid);
-    TV::sstore(lds_v, stV, tid);
-    TV::sstore(lds_tv, stTV, tid);
-    __syncthreads();
-    if (j0 + kBN < s.N) {  // uniform: prefetch the next tile while this one is computed
-      TK::gload(stK, k + base, s.sn, j0 + kBN, s.N, s.D, tid);
-      TK::gload(stTK, tk + base, s.sn, j0 + kBN, s.N, s.D, tid);
-      TV::gload(stV, v + base, s.sn, j0 + kBN, s.N, s.D, tid);
-      TV::gload(stTV, tv + base, s.sn, j0 + kBN, s.N, s.D, tid);
-    }
+  __syncthreads();  // tile 0 has landed (the barrier waits for this wave's outstanding loads)
+  for (int j0 = 0, it = 0; j0 < s.N; j0 += kBN, ++it) {
+    const char* lds_k = lds + (it & 1) * BUF;
+    const char* lds_tk = lds_k + TK::BYTES;
+    const char* lds_v = lds_k + 2 * TK::BYTES;
+    const char* lds_tv = lds_v + TV::BYTES;
+    if (j0 + kBN < s.N) issue(j0 + kBN, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll 1
     for (int jb = 0; jb < kBN / 32; ++jb) {
@@ -149,6 +148,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* 
           accT[db] = mfma(tvf, pf[cc], accT[db]);
         }
     }
+    __syncthreads();  // next tile landed; everyone is done with this one
   }
 
   l += xhalf(l);
@@ -182,9 +182,9 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(Shape s, const bf16* 
 
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  constexpr int NW = 8;
+  constexpr int NW = 8, BN = (DV > 96) ? 32 : 64;  // waves per workgroup, keys per LDS tile
   const int nmb = (s.N + 32 * NW - 1) / (32 * NW);
-  hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW>), dim3(nmb * s.B * s.H), dim3(64 * NW), 0, st, s,
+  hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN>), dim3(nmb * s.B * s.H), dim3(64 * NW), 0, st, s,
                      (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
                      (const bf16*)a.tv, (bf16*)a.o, (bf16*)a.to, a.lse, a.stats);
   return hipGetLastError();

@@ -54,34 +54,54 @@ __device__ __forceinline__ int chunk_off(int s, int c) {
   return (s * PCH + (c ^ ((s >> 2) & 3))) * 16;
 }
 
-// A streamed tile: ROWS rows, logical chunks [0, NCH) staged (zero beyond D and beyond N).
-template <int ROWS_, int NCH_, int NT_>
+// A streamed tile: ROWS rows, logical chunks [0, NCH) (columns [0, 8*NCH)), filled by NW waves
+// with asynchronous global->LDS loads (global_load_lds_dwordx4: each wave instruction fills 64
+// consecutive physical chunks, every lane fetching the global chunk that the swizzle puts at
+// its position).  No staging registers; the loads complete in the background and are waited
+// for (vmcnt) at the workgroup barrier that ends the computation on the other buffer.
+// Chunks beyond D and rows beyond N are never written: the buffers are zeroed once at kernel
+// start, pad columns therefore stay zero, and rows past N hold zeros or an older tile's
+// (finite) rows, which the kernels give weight exactly 0.
+template <int ROWS_, int NCH_, int NW_>
 struct Tile {
-  static constexpr int ROWS = ROWS_, NCH = NCH_, NT = NT_;
+  static constexpr int ROWS = ROWS_, NCH = NCH_, NW = NW_;
   static constexpr int PCH = pitch_chunks(NCH_ * 8);
   static constexpr int BYTES = ROWS_ * PCH * 16;
-  static constexpr int NIT = (ROWS_ * NCH_ + NT_ - 1) / NT_;  // staging registers (uint4) per thread
+  static constexpr int NINST = ROWS_ * PCH / 64;       // wave-wide load instructions per tile
+  static constexpr int IPW = (NINST + NW_ - 1) / NW_;  // of which each wave issues this many
+  static_assert((ROWS_ * PCH) % 64 == 0, "tile must be a whole number of wave loads");
 
-  // global -> registers for rows [r0, r0+ROWS) of a [N,D] matrix with row pitch sn
-  __device__ __forceinline__ static void gload(uint4 (&st)[NIT], const bf16* __restrict__ src, long long sn, int r0,
-                                               int N, int D, int tid) {
+  // Per-lane constants: where in the head (relative to the tile's first row) each of this lane's
+  // chunks comes from, and which tile row it is (1<<30 if the column is beyond D: never loaded).
+  struct Lane {
+    long long goff[IPW];
+    int srow[IPW];
+  };
+  __device__ __forceinline__ static Lane lane_setup(long long sn, int D, int wave, int lane) {
+    Lane L;
 #pragma unroll
-    for (int t = 0; t < NIT; ++t) {
-      const int idx = tid + t * NT;
-      const int s = idx / NCH, c = idx - s * NCH;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (idx < ROWS * NCH && r0 + s < N && c * 8 < D)
-        v = *reinterpret_cast<const uint4*>(src + (long long)(r0 + s) * sn + c * 8);
-      st[t] = v;
+    for (int t = 0; t < IPW; ++t) {
+      const int P = (wave + t * NW) * 64 + lane;
+      const int s = P / PCH;
+      const int c = (P - s * PCH) ^ ((s >> 2) & 3);
+      L.goff[t] = (long long)s * sn + c * 8;
+      L.srow[t] = (c * 8 < D) ? s : (1 << 30);
     }
+    return L;
   }
-  // registers -> LDS (swizzled)
-  __device__ __forceinline__ static void sstore(char* lds, const uint4 (&st)[NIT], int tid) {
+  // Starts the loads of rows [r0, r0+ROWS) of the [N,D] matrix at `src` (row pitch sn) into `lds`.
+  __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ src, long long sn, int r0,
+                                               int N, char* lds, int wave) {
+    typedef const __attribute__((address_space(1))) void* gp;
+    typedef __attribute__((address_space(3))) void* lp;
 #pragma unroll
-    for (int t = 0; t < NIT; ++t) {
-      const int idx = tid + t * NT;
-      const int s = idx / NCH, c = idx - s * NCH;
-      if (idx < ROWS * NCH) *reinterpret_cast<uint4*>(lds + chunk_off<PCH>(s, c)) = st[t];
+    for (int t = 0; t < IPW; ++t) {
+      const int inst = wave + t * NW;
+      if (NINST % NW == 0 || inst < NINST) {
+        if (L.srow[t] < N - r0)
+          __builtin_amdgcn_global_load_lds((gp)(src + (long long)r0 * sn + L.goff[t]), (lp)(lds + inst * 1024), 16, 0,
+                                           0);
+      }
     }
   }
   // (R): eight consecutive columns 16*kk + 8*hh.. of row s
@@ -100,6 +120,12 @@ struct Tile {
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 };
+
+// Zero-fills `bytes` (a multiple of 16) of LDS with all NT threads of the workgroup.
+template <int NT>
+__device__ __forceinline__ void lds_zero(char* lds, int bytes, int tid) {
+  for (int o = tid * 16; o < bytes; o += NT * 16) *reinterpret_cast<uint4*>(lds + o) = make_uint4(0, 0, 0, 0);
+}
 
 // Eight bf16 from global memory (16-byte aligned) or zeros.
 __device__ __forceinline__ bf16x8 gld_frag(const bf16* p, bool ok) {
