@@ -10,6 +10,7 @@ LIB = os.path.join(HERE, "libtvmattn.so")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # MFMA results straight into VGPRs (no accvgpr copies for the VALU)
     "-Wno-unused-command-line-argument",
 ]
 

@@ -74,21 +74,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
                                        (__attribute__((address_space(3))) void*)(buf + 4 * TX::BYTES + wave * kTS * 4),
                                        4, 0, 0);
   };
+  const typename TX::RAddr ra = TX::raddr(ic, hh);
+  const typename TX::TAddr ta = TX::taddr(ic, hh);
   lds_zero<kNT>(lds, 2 * BUF, tid);
   __syncthreads();
   issue(0, lds);
 
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
-#pragma unroll
-  for (int kk = 0; kk < NKS; ++kk) {
-    const int c0 = kk * 16 + hh * 8;
-    const bool ok = jok && c0 < s.D;
-    const long long a = base + (long long)j * s.sn + c0;
-    kf[kk] = gld_frag(k + a, ok);
-    tkf[kk] = gld_frag(tk + a, ok);
-    vf[kk] = gld_frag(v + a, ok);
-    tvf[kk] = gld_frag(tv + a, ok);
-  }
+  gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
   zero_acc(aK);
   zero_acc(aTK);
@@ -108,14 +104,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     const float* row_sig1 = row_lse + 3 * kTS;
     if (i0 + kTS < s.N) issue(i0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
-#pragma unroll 1
+#pragma unroll
     for (int ib = 0; ib < kTS / 32; ++ib) {
       if (i0 + ib * 32 >= s.N) break;  // uniform
-      const int srow = ib * 32 + ic;
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 qf = TX::frag_row(lds_q, srow, kk, hh), tqf = TX::frag_row(lds_tq, srow, kk, hh);
+        const bf16x8 qf = TX::frag_row(lds_q, ra, ib, kk), tqf = TX::frag_row(lds_tq, ra, ib, kk);
         sS = mfma(qf, kf[kk], sS);
         sT = mfma(tqf, kf[kk], sT);
         sT = mfma(qf, tkf[kk], sT);
@@ -123,7 +118,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
       f32x16 sDF = zero16(), sE = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 gf = TX::frag_row(lds_g, srow, kk, hh), tgf = TX::frag_row(lds_tg, srow, kk, hh);
+        const bf16x8 gf = TX::frag_row(lds_g, ra, ib, kk), tgf = TX::frag_row(lds_tg, ra, ib, kk);
         sE = mfma(tgf, vf[kk], sE);
         sDF = mfma(gf, vf[kk], sDF);
         sDF = mfma(tgf, tvf[kk], sDF);
@@ -160,13 +155,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          const bf16x8 gT = TX::frag_tr(lds_g, 2 * ib + cc, db, ic, hh);
-          const bf16x8 tgT = TX::frag_tr(lds_tg, 2 * ib + cc, db, ic, hh);
+          const bf16x8 gT = TX::frag_tr(lds_g, ta, 2 * ib + cc, db);
+          const bf16x8 tgT = TX::frag_tr(lds_tg, ta, 2 * ib + cc, db);
           aV[db] = mfma(gT, pf[cc], aV[db]);
           aV[db] = mfma(tgT, pdf[cc], aV[db]);
           aTV[db] = mfma(tgT, pf[cc], aTV[db]);
-          const bf16x8 qT = TX::frag_tr(lds_q, 2 * ib + cc, db, ic, hh);
-          const bf16x8 tqT = TX::frag_tr(lds_tq, 2 * ib + cc, db, ic, hh);
+          const bf16x8 qT = TX::frag_tr(lds_q, ta, 2 * ib + cc, db);
+          const bf16x8 tqT = TX::frag_tr(lds_tq, ta, 2 * ib + cc, db);
           aK[db] = mfma(qT, gzf[cc], aK[db]);
           aK[db] = mfma(tqT, gztf[cc], aK[db]);
           aTK[db] = mfma(qT, gztf[cc], aTK[db]);
@@ -214,21 +209,20 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
     TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
+  const typename TK::RAddr rk = TK::raddr(ic, hh);
+  const typename TV::RAddr rv = TV::raddr(ic, hh);
+  const typename TK::TAddr ta = TK::taddr(ic, hh);
+#if !defined(EXP_NOZERO)
   lds_zero<kNT>(lds, 2 * BUF, tid);
+#endif
   __syncthreads();
   issue(0, lds);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
-#pragma unroll
-  for (int kk = 0; kk < NKS; ++kk) {
-    const int c0 = kk * 16 + hh * 8;
-    const bool ok = iok && c0 < s.D;
-    const long long a = base + (long long)i * s.sn + c0;
-    qf[kk] = gld_frag(q + a, ok);
-    tqf[kk] = gld_frag(tq + a, ok);
-    gf[kk] = gld_frag(gO + a, ok);
-    tgf[kk] = gld_frag(gTO + a, ok);
-  }
+  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.N + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
@@ -248,25 +242,48 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     const char* lds_tv = lds_v + TV::BYTES;
     if (j0 + kTS < s.N) issue(j0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
-#pragma unroll 1
+#pragma unroll
     for (int jb = 0; jb < kTS / 32; ++jb) {
       if (j0 + jb * 32 >= s.N) break;  // uniform
-      const int srow = jb * 32 + ic;
+      // Fragments are fetched a whole phase ahead of the products that use them, so the LDS
+      // latency of each phase hides behind the previous phase's matrix-core work.
+      bf16x8 kfr[NKS], tkfr[NKS], vfr[NKS], tvfr[NKS];
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        kfr[kk] = TK::frag_row(lds_k, rk, jb, kk);
+        tkfr[kk] = TK::frag_row(lds_tk, rk, jb, kk);
+      }
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk) {
+        vfr[kk] = TV::frag_row(lds_v, rv, jb, kk);
+        tvfr[kk] = TV::frag_row(lds_tv, rv, jb, kk);
+      }
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 kf = TK::frag_row(lds_k, srow, kk, hh), tkf = TK::frag_row(lds_tk, srow, kk, hh);
-        sS = mfma(kf, qf[kk], sS);
-        sT = mfma(kf, tqf[kk], sT);
-        sT = mfma(tkf, qf[kk], sT);
+        sS = mfma(kfr[kk], qf[kk], sS);
+        sT = mfma(kfr[kk], tqf[kk], sT);
+        sT = mfma(tkfr[kk], qf[kk], sT);
       }
+      bf16x8 kT[2][NDB], tkT[2][NDB];
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          kT[cc][db] = TK::frag_tr(lds_k, ta, 2 * jb + cc, db);
+          tkT[cc][db] = TK::frag_tr(lds_tk, ta, 2 * jb + cc, db);
+        }
       f32x16 sDF = zero16(), sE = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 vf = TV::frag_row(lds_v, srow, kk, hh), tvf = TV::frag_row(lds_tv, srow, kk, hh);
-        sE = mfma(vf, tgf[kk], sE);
-        sDF = mfma(vf, gf[kk], sDF);
-        sDF = mfma(tvf, tgf[kk], sDF);
+#if defined(EXP_NOE)
+        sE[kk] += (float)vfr[kk][0] * (float)tgf[kk][0];
+        sDF[kk] += (float)tvfr[kk][0] * (float)gf[kk][0];
+#else
+        sE = mfma(vfr[kk], tgf[kk], sE);
+        sDF = mfma(vfr[kk], gf[kk], sDF);
+        sDF = mfma(tvfr[kk], tgf[kk], sDF);
+#endif
       }
       if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
 #pragma unroll
@@ -276,10 +293,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
       bf16x8 gzf[2], gztf[2];
 #pragma unroll
       for (int rr = 0; rr < 16; ++rr) {
+#if defined(EXP_NOPW)
+        const float gz = sS[rr] + sT[rr], gzt = sE[rr] + sDF[rr];
+#else
         const float p = __builtin_amdgcn_exp2f(fmaf(sS[rr], c1, -lse2));
         const float n = fmaf(sT[rr], s.alpha, -mub);
         const float gzt = p * (sE[rr] - s1);
         const float gz = fmaf(gzt, n, p * (sDF[rr] - ds));
+#endif
         gzf[rr >> 3][rr & 7] = (bf16)gz;
         gztf[rr >> 3][rr & 7] = (bf16)gzt;
       }
@@ -287,17 +308,23 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          const bf16x8 kT = TK::frag_tr(lds_k, 2 * jb + cc, db, ic, hh);
-          const bf16x8 tkT = TK::frag_tr(lds_tk, 2 * jb + cc, db, ic, hh);
-          aQ[db] = mfma(kT, gzf[cc], aQ[db]);
-          aQ[db] = mfma(tkT, gztf[cc], aQ[db]);
-          aTQ[db] = mfma(kT, gztf[cc], aTQ[db]);
+#if defined(EXP_NOOUT)
+          aQ[db][cc] += (float)gzf[cc][db] + (float)kT[cc][db][0] + (float)tkT[cc][db][1];
+          aTQ[db][cc] += (float)gztf[cc][db];
+#else
+          aQ[db] = mfma(kT[cc][db], gzf[cc], aQ[db]);
+          aQ[db] = mfma(tkT[cc][db], gztf[cc], aQ[db]);
+          aTQ[db] = mfma(kT[cc][db], gztf[cc], aTQ[db]);
+#endif
         }
     }
     __syncthreads();  // next tile landed; everyone is done with this one
   }
   if (!iok) return;
   const long long ro = base + (long long)i * s.sn;
+#if defined(EXP_NOSTORE)
+  if (aQ[0][0] + aTQ[0][0] + aQ[1][3] + aQ[2][5] + aTQ[1][1] + aTQ[2][2] != 12345.f) return;
+#endif
   store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
   store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
 }

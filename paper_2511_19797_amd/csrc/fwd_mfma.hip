@@ -21,6 +21,10 @@
 //   accO += p V ;   accT += (p * alpha St) V + p tV
 // Epilogue: O = accO / l,  stats = c / l,  tO = accT / l - stats * O,  lse = m + log l.
 #include "mfma_tiles.h"
+#ifndef FWD_NW
+#define FWD_NW 4   // waves per workgroup (two workgroups share a CU)
+#define FWD_BN 32  // keys per LDS tile
+#endif
 
 namespace tvm {
 namespace {
@@ -58,18 +62,15 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
     TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
     TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
+  const typename TK::RAddr rk = TK::raddr(ic, hh);
+  const typename TV::TAddr tv_a = TV::taddr(ic, hh);
   lds_zero<NT>(lds, 2 * BUF, tid);
   __syncthreads();
   issue(0, lds);
 
   bf16x8 qf[NKS], tqf[NKS];
-#pragma unroll
-  for (int kk = 0; kk < NKS; ++kk) {
-    const int c0 = kk * 16 + hh * 8;
-    const bool ok = iok && c0 < s.D;
-    qf[kk] = gld_frag(q + base + (long long)i * s.sn + c0, ok);
-    tqf[kk] = gld_frag(tq + base + (long long)i * s.sn + c0, ok);
-  }
+  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
 
   f32x16 accO[NDB], accT[NDB];
 #pragma unroll
@@ -81,21 +82,25 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   const float c1 = s.alpha * kLog2e;  // scores are exponentiated in base 2
 
   __syncthreads();  // tile 0 has landed (the barrier waits for this wave's outstanding loads)
+#if defined(EXP_FNOLOOP)
+  for (int j0 = 0, it = 0; j0 < kBN; j0 += kBN, ++it) {
+#else
   for (int j0 = 0, it = 0; j0 < s.N; j0 += kBN, ++it) {
+#endif
     const char* lds_k = lds + (it & 1) * BUF;
     const char* lds_tk = lds_k + TK::BYTES;
     const char* lds_v = lds_k + 2 * TK::BYTES;
     const char* lds_tv = lds_v + TV::BYTES;
     if (j0 + kBN < s.N) issue(j0 + kBN, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
-#pragma unroll 1
+#pragma unroll
     for (int jb = 0; jb < kBN / 32; ++jb) {
       if (j0 + jb * 32 >= s.N) break;  // uniform: the rest of the tile is beyond the last key
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 kf = TK::frag_row(lds_k, jb * 32 + ic, kk, hh);
-        const bf16x8 tkf = TK::frag_row(lds_tk, jb * 32 + ic, kk, hh);
+        const bf16x8 kf = TK::frag_row(lds_k, rk, jb, kk);
+        const bf16x8 tkf = TK::frag_row(lds_tk, rk, jb, kk);
         sS = mfma(kf, qf[kk], sS);
         sT = mfma(kf, tqf[kk], sT);
         sT = mfma(tkf, qf[kk], sT);
@@ -141,8 +146,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 vf = TV::frag_tr(lds_v, 2 * jb + cc, db, ic, hh);
-          const bf16x8 tvf = TV::frag_tr(lds_tv, 2 * jb + cc, db, ic, hh);
+          const bf16x8 vf = TV::frag_tr(lds_v, tv_a, 2 * jb + cc, db);
+          const bf16x8 tvf = TV::frag_tr(lds_tv, tv_a, 2 * jb + cc, db);
           accO[db] = mfma(vf, pf[cc], accO[db]);
           accT[db] = mfma(vf, pzf[cc], accT[db]);
           accT[db] = mfma(tvf, pf[cc], accT[db]);
@@ -154,6 +159,9 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   l += xhalf(l);
   cs += xhalf(cs);
   if (!iok) return;
+#if defined(EXP_FNOSTORE)
+  if (accO[0][0] + accT[0][0] + accO[1][3] + accO[2][5] + accT[1][1] + accT[2][2] + l + cs != 12345.f) return;
+#endif
   const float inv = 1.f / l;
   const float mubar = cs * inv;
 #pragma unroll
@@ -182,7 +190,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
 
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  constexpr int NW = 8, BN = (DV > 96) ? 32 : 64;  // waves per workgroup, keys per LDS tile
+  constexpr int NW = FWD_NW, BN = (DV > 96) ? 32 : FWD_BN;  // waves per workgroup, keys per LDS tile
   const int nmb = (s.N + 32 * NW - 1) / (32 * NW);
   hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN>), dim3(nmb * s.B * s.H), dim3(64 * NW), 0, st, s,
                      (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,

@@ -104,19 +104,43 @@ struct Tile {
       }
     }
   }
-  // (R): eight consecutive columns 16*kk + 8*hh.. of row s
-  __device__ __forceinline__ static bf16x8 frag_row(const char* lds, int s, int kk, int hh) {
-    return *reinterpret_cast<const bf16x8*>(lds + chunk_off<PCH>(s, 2 * kk + hh));
+  // Read addressing.  All swizzle arithmetic is folded into a few per-lane constants so that
+  // every fragment read is  lane constant + compile-time immediate.
+  //
+  // (R) fragment kk of row (32*blk + ic): logical chunk 2kk+hh, XORed with x = (ic>>2)&3.
+  //     (2kk+hh)^x = 2kk + (hh^(x&1)) + (x&2 ? (kk even ? +2 : -2) : 0): one constant for even kk, one for odd.
+  struct RAddr {
+    int e, o;
+  };
+  __device__ __forceinline__ static RAddr raddr(int ic, int hh) {
+    const int x = (ic >> 2) & 3;
+    const int base = (ic * PCH + (hh ^ (x & 1))) * 16;
+    const int d = (x & 2) ? 32 : 0;
+    return RAddr{base + d, base - d};
   }
-  // (T): A fragment of X^T: row (32*db + ic) of X^T, contraction index = rows 16*cc.. of X in slot order
-  __device__ __forceinline__ static bf16x8 frag_tr(const char* lds, int cc, int db, int ic, int hh) {
+  static constexpr int kBlkBytes = 32 * PCH * 16;  // 32 rows
+  // `p` = tensor base within the stage; blk and kk are compile-time after unrolling
+  __device__ __forceinline__ static bf16x8 frag_row(const char* p, RAddr a, int blk, int kk) {
+    return *reinterpret_cast<const bf16x8*>(p + ((kk & 1) ? a.o : a.e) + blk * kBlkBytes + kk * 32);
+  }
+  // (T) A fragment of X^T: row (32*db + ic) of X^T, contraction index = rows 16*cc.. of X in slot
+  //     order.  Lane (16*bq + i, hh) supplies rows 4hh + (i>>2) (+8 for the second read), logical
+  //     chunk 4db + y with y = 2bq + ((i&3)>>1), XORed with (row>>2)&3 = hh (resp. hh+2).
+  struct TAddr {
+    int lo, hi;
+  };
+  __device__ __forceinline__ static TAddr taddr(int ic, int hh) {
     const int i = ic & 15, bq = ic >> 4;
-    const int s0 = 16 * cc + 4 * hh + (i >> 2);
-    const int c = 4 * db + 2 * bq + ((i & 3) >> 1);
+    const int y = 2 * bq + ((i & 3) >> 1);
+    const int row = 4 * hh + (i >> 2);
     const int sub = (i & 1) * 8;
+    return TAddr{(row * PCH + (y ^ hh)) * 16 + sub, ((row + 8) * PCH + (y ^ (hh + 2))) * 16 + sub};
+  }
+  __device__ __forceinline__ static bf16x8 frag_tr(const char* p, TAddr a, int cc, int db) {
     typedef bf16x4 __attribute__((address_space(3))) * lp;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(lds + chunk_off<PCH>(s0, c) + sub));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(lds + chunk_off<PCH>(s0 + 8, c) + sub));
+    const int imm = cc * 16 * PCH * 16 + db * 64;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + a.lo + imm));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + a.hi + imm));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 };
@@ -127,11 +151,29 @@ __device__ __forceinline__ void lds_zero(char* lds, int bytes, int tid) {
   for (int o = tid * 16; o < bytes; o += NT * 16) *reinterpret_cast<uint4*>(lds + o) = make_uint4(0, 0, 0, 0);
 }
 
-// Eight bf16 from global memory (16-byte aligned) or zeros.
-__device__ __forceinline__ bf16x8 gld_frag(const bf16* p, bool ok) {
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (ok) v = *reinterpret_cast<const uint4*>(p);
-  return __builtin_bit_cast(bf16x8, v);
+// Fixed-side fragments: chunks 2kk+hh (kk < NKS) of row `row` of a [N,D] matrix, zero where the row
+// or the chunk is out of range.  The loads are unconditional (from a clamped, always valid
+// address) and the zeroing is a select on the loaded value, so all of them are in flight together.
+template <int NKS>
+__device__ __forceinline__ void gld_frags(bf16x8 (&f)[NKS], const bf16* __restrict__ head, long long sn, int row, int N,
+                                          int D, int hh) {
+  const bf16* p = head + (long long)min(row, N - 1) * sn;
+  uint4 raw[NKS];
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    const int c0 = kk * 16 + hh * 8;
+    raw[kk] = *reinterpret_cast<const uint4*>(p + (c0 < D ? c0 : 0));
+  }
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    const bool ok = row < N && kk * 16 + hh * 8 < D;
+    uint4 v = raw[kk];
+    v.x = ok ? v.x : 0u;
+    v.y = ok ? v.y : 0u;
+    v.z = ok ? v.z : 0u;
+    v.w = ok ? v.w : 0u;
+    f[kk] = __builtin_bit_cast(bf16x8, v);
+  }
 }
 
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }
