@@ -107,7 +107,7 @@ def run_workload(w, steps, warmup, hip, seed=2024):
     tvm.tvmattn_set_bwd_events(None)
 
     names = ("fwd", "bwd_pre", "bwd_col", "bwd_row")
-    pairs = ((0, 1), (2, 3), (3, 4), (4, 5))
+    pairs = ((0, 1), (2, 3), (4, 5), (3, 4))  # bwd events: start, after pre, after row, after col
     kern_ms = {n: sum(hip.elapsed_ms(ev[a], ev[b]) for ev in events) / steps for n, (a, b) in zip(names, pairs)}
     for ev in events:
         for e in ev:

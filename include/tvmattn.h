@@ -92,8 +92,9 @@ int tvmattn_set_path(int path);
  * Diagnostic timing hook, process-wide, not thread-safe.  `events` is NULL (off, the default)
  * or points to four hipEvent_t handles created by the caller with timing enabled; while set,
  * every tvmattn_jvp_bwd call records, on its stream, events[0] before its first launch,
- * events[1] after the row-scalar kernel, events[2] after the key-side kernel and events[3]
- * after the query-side kernel.  The four handles are copied; the array need not outlive the call.
+ * events[1] after the row-scalar kernel (a separate launch only on the plain-ALU path),
+ * events[2] after the query-side kernel and events[3] after the key-side kernel.  The four
+ * handles are copied; the array need not outlive the call.
  */
 int tvmattn_set_bwd_events(void* const* events);
 
@@ -121,9 +122,10 @@ size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc);
  *   workspace: device memory, 16-byte aligned, at least
  *        tvmattn_jvp_bwd_workspace_bytes(desc) bytes; contents need not be initialised
  *        and are undefined afterwards.
- * Three launches on the stream: row scalars (Step 1: delta = gO.O, Sigma_1 = gTO.O,
- * Sigma_2 = gTO.tO per row), a key-side pass (dk,dtk,dv,dtv; Steps 2,4,6) and a
- * query-side pass (dq,dtq; Steps 3,5).  No atomics: results are bitwise reproducible.
+ * Launches on the stream: a query-side pass (dq,dtq; Steps 3,5) that also forms the row
+ * scalars of Step 1 (delta = gO.O, Sigma_1 = gTO.O, Sigma_2 = gTO.tO per row; a separate
+ * launch on the plain-ALU path), then a key-side pass (dk,dtk,dv,dtv; Steps 2,4,6).
+ * No atomics: results are bitwise reproducible.
  */
 int tvmattn_jvp_bwd(const tvmattn_desc* desc,
                     const void* q, const void* k, const void* v,

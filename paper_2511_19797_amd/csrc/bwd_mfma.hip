@@ -1,359 +1,18 @@
-// Backward through both outputs on the bf16 matrix cores (gfx950): a key-side kernel
-// (dK, dtK, dV, dtV; Steps 2, 4, 6 of App. C plus the ordinary-attention terms of gO) and a
-// query-side kernel (dQ, dtQ; Steps 3, 5), both recomputing the tile quantities from lse and
-// stats ("Caching softmax statistics").  With G = gO, Gt = gTO and the row scalars of Step 1
-// collapsed to dot products (dsig = G.O + Gt.tO, sig1 = Gt.O):
-//
-//   S = Q K^T             St = tQ K^T + Q tK^T        P = exp(alpha S - lse)
-//   N = alpha St - stats  DF = G V^T + Gt tV^T        E = Gt V^T
-//   gZt = P o (E - sig1)  gZ = P o (DF - dsig) + gZt o N        Pd = P o N
-//
-//   dV = P^T G + Pd^T Gt       dtV = P^T Gt
-//   dK = alpha (gZ^T Q + gZt^T tQ)      dtK = alpha gZt^T Q
-//   dQ = alpha (gZ K + gZt tK)          dtQ = alpha gZt K
-//
-// Both kernels share one skeleton.  A wave owns 32 rows of the "fixed" side (keys for the
-// key-side kernel, queries for the query-side one) and keeps that side's four tensors as
-// B-operand fragments in registers; the other side is streamed through LDS in tiles of 64
-// rows (row-major, swizzled), read directly for the score products and through the
-// transposing LDS read for the output products.  The next tile's global loads are issued into
-// registers before the current tile is computed.  Score tiles are D[streamed][fixed]: a lane
-// owns one fixed row, its 16 registers run over streamed rows, and the tile feeds the output
-// products straight from registers.
-// No atomics anywhere: every output element is produced by exactly one lane.
-#include "mfma_tiles.h"
+// Backward launchers, head dims up to 96 (see bwd_mfma_kernels.h for the kernels).
+#include "bwd_mfma_kernels.h"
 
 namespace tvm {
-namespace {
 
-constexpr int kFix = 128;  // fixed-side rows per workgroup (4 waves x 32)
-constexpr int kNT = 256;
-constexpr float kLog2e = 1.4426950408889634f;
+// d > 96 is instantiated in bwd_mfma_wide.hip (built with different code-generation flags)
+hipError_t launch_bwd_col_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
 
-template <int NDB>
-__device__ __forceinline__ void zero_acc(f32x16 (&a)[NDB]) {
-#pragma unroll
-  for (int db = 0; db < NDB; ++db) a[db] = zero16();
+bool mfma_supported(const Shape& s, int dtype) {
+  // bf16, 16-byte chunks, and row pitches whose tile offsets fit the 32-bit lane offsets of the LDS loads
+  return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22);
 }
 
-// ------------------------------------------------------------------------------------------
-// Key side.
-// ------------------------------------------------------------------------------------------
-template <int DK, int DV, int kTS>
-__global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
-    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
-    const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
-    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
-    bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
-  using TX = Tile<kTS, DV / 8, kNT / 64>;  // read both ways: columns up to DV
-  constexpr int ROWV = 4 * kTS * 4;                   // four float32 row vectors per stage
-  constexpr int BUF = 4 * TX::BYTES + ROWV;           // one stage: Q, tQ, G, tG, row vectors
-  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
-  constexpr int NKS = DK / 16, NDB = DV / 32;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
-  const int nfb = (s.N + kFix - 1) / kFix;
-  const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = wg / nfb, fb = wg - bh * nfb;
-  const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
-  const long long rbase = (long long)bh * s.N;
-  const int j = fb * kFix + wave * 32 + ic;  // this lane's key
-  const bool jok = j < s.N;
-
-  const typename TX::Lane lx = TX::lane_setup(s.sn, s.D, wave, lane);
-  // wave w also fetches row vector w (lse, stats, dsig, sig1) of the tile, one float per lane
-  const float* const rowsrc = (wave == 0 ? lse : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
-  auto issue = [&](int i0, char* buf) {
-    TX::issue(lx, q + base, s.sn, i0, s.N, buf, wave);
-    TX::issue(lx, tq + base, s.sn, i0, s.N, buf + TX::BYTES, wave);
-    TX::issue(lx, gO + base, s.sn, i0, s.N, buf + 2 * TX::BYTES, wave);
-    TX::issue(lx, gTO + base, s.sn, i0, s.N, buf + 3 * TX::BYTES, wave);
-    if (lane < kTS && i0 + lane < s.N)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rowsrc + i0 + lane),
-                                       (__attribute__((address_space(3))) void*)(buf + 4 * TX::BYTES + wave * kTS * 4),
-                                       4, 0, 0);
-  };
-  const typename TX::RAddr ra = TX::raddr(ic, hh);
-  const typename TX::TAddr ta = TX::taddr(ic, hh);
-  lds_zero<kNT>(lds, 2 * BUF, tid);
-  __syncthreads();
-  issue(0, lds);
-
-  bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
-  gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
-  f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
-  zero_acc(aK);
-  zero_acc(aTK);
-  zero_acc(aV);
-  zero_acc(aTV);
-  const float c1 = s.alpha * kLog2e;
-
-  __syncthreads();  // tile 0 has landed (the barrier waits for this wave's outstanding loads)
-  for (int i0 = 0, it = 0; i0 < s.N; i0 += kTS, ++it) {
-    const char* lds_q = lds + (it & 1) * BUF;
-    const char* lds_tq = lds_q + TX::BYTES;
-    const char* lds_g = lds_q + 2 * TX::BYTES;
-    const char* lds_tg = lds_q + 3 * TX::BYTES;
-    const float* row_lse = reinterpret_cast<const float*>(lds_q + 4 * TX::BYTES);
-    const float* row_mub = row_lse + kTS;
-    const float* row_dsig = row_lse + 2 * kTS;
-    const float* row_sig1 = row_lse + 3 * kTS;
-    if (i0 + kTS < s.N) issue(i0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
-
-#pragma unroll
-    for (int ib = 0; ib < kTS / 32; ++ib) {
-      if (i0 + ib * 32 >= s.N) break;  // uniform
-      f32x16 sS = zero16(), sT = zero16();
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 qf = TX::frag_row(lds_q, ra, ib, kk), tqf = TX::frag_row(lds_tq, ra, ib, kk);
-        sS = mfma(qf, kf[kk], sS);
-        sT = mfma(tqf, kf[kk], sT);
-        sT = mfma(qf, tkf[kk], sT);
-      }
-      f32x16 sDF = zero16(), sE = zero16();
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 gf = TX::frag_row(lds_g, ra, ib, kk), tgf = TX::frag_row(lds_tg, ra, ib, kk);
-        sE = mfma(tgf, vf[kk], sE);
-        sDF = mfma(gf, vf[kk], sDF);
-        sDF = mfma(tgf, tvf[kk], sDF);
-      }
-      if (i0 + ib * 32 + 32 > s.N) {  // uniform: ragged last block, queries >= N get probability 0
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (i0 + ib * 32 + drow(r, hh) >= s.N) sS[r] = -INFINITY;
-      }
-      bf16x8 pf[2], pdf[2], gzf[2], gztf[2];
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int ro = ib * 32 + 8 * g4 + 4 * hh;
-        const float4 l4 = *reinterpret_cast<const float4*>(row_lse + ro);
-        const float4 m4 = *reinterpret_cast<const float4*>(row_mub + ro);
-        const float4 d4 = *reinterpret_cast<const float4*>(row_dsig + ro);
-        const float4 s4 = *reinterpret_cast<const float4*>(row_sig1 + ro);
-        const float la[4] = {l4.x, l4.y, l4.z, l4.w}, ma[4] = {m4.x, m4.y, m4.z, m4.w};
-        const float da[4] = {d4.x, d4.y, d4.z, d4.w}, sa[4] = {s4.x, s4.y, s4.z, s4.w};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int r = 4 * g4 + t;
-          const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -la[t] * kLog2e));
-          const float n = fmaf(sT[r], s.alpha, -ma[t]);
-          const float gzt = p * (sE[r] - sa[t]);
-          const float gz = fmaf(gzt, n, p * (sDF[r] - da[t]));
-          pf[r >> 3][r & 7] = (bf16)p;
-          pdf[r >> 3][r & 7] = (bf16)(p * n);
-          gzf[r >> 3][r & 7] = (bf16)gz;
-          gztf[r >> 3][r & 7] = (bf16)gzt;
-        }
-      }
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const bf16x8 gT = TX::frag_tr(lds_g, ta, 2 * ib + cc, db);
-          const bf16x8 tgT = TX::frag_tr(lds_tg, ta, 2 * ib + cc, db);
-          aV[db] = mfma(gT, pf[cc], aV[db]);
-          aV[db] = mfma(tgT, pdf[cc], aV[db]);
-          aTV[db] = mfma(tgT, pf[cc], aTV[db]);
-          const bf16x8 qT = TX::frag_tr(lds_q, ta, 2 * ib + cc, db);
-          const bf16x8 tqT = TX::frag_tr(lds_tq, ta, 2 * ib + cc, db);
-          aK[db] = mfma(qT, gzf[cc], aK[db]);
-          aK[db] = mfma(tqT, gztf[cc], aK[db]);
-          aTK[db] = mfma(qT, gztf[cc], aTK[db]);
-        }
-    }
-    __syncthreads();  // next tile landed; everyone is done with this one
-  }
-  if (!jok) return;
-  const long long ro = base + (long long)j * s.sn;
-  store_acc<NDB>(dk + ro, aK, s.alpha, s.D, hh);
-  store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
-  store_acc<NDB>(dv + ro, aV, 1.f, s.D, hh);
-  store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
-}
-
-// ------------------------------------------------------------------------------------------
-// Query side.
-// ------------------------------------------------------------------------------------------
-template <int DK, int DV, int kTS>
-__global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
-    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
-    const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
-    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
-    bf16* __restrict__ dq, bf16* __restrict__ dtq) {
-  using TK = Tile<kTS, DV / 8, kNT / 64>;  // K, tK: read both ways
-  using TV = Tile<kTS, DK / 8, kNT / 64>;  // V, tV: score products only
-  constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
-  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
-  constexpr int NKS = DK / 16, NDB = DV / 32;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
-  const int nfb = (s.N + kFix - 1) / kFix;
-  const int wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = wg / nfb, fb = wg - bh * nfb;
-  const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
-  const int i = fb * kFix + wave * 32 + ic;  // this lane's query
-  const bool iok = i < s.N;
-
-  const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
-  const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
-  auto issue = [&](int j0, char* buf) {
-    TK::issue(lk, k + base, s.sn, j0, s.N, buf, wave);
-    TK::issue(lk, tk + base, s.sn, j0, s.N, buf + TK::BYTES, wave);
-    TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
-  };
-  const typename TK::RAddr rk = TK::raddr(ic, hh);
-  const typename TV::RAddr rv = TV::raddr(ic, hh);
-  const typename TK::TAddr ta = TK::taddr(ic, hh);
-#if !defined(EXP_NOZERO)
-  lds_zero<kNT>(lds, 2 * BUF, tid);
-#endif
-  __syncthreads();
-  issue(0, lds);
-
-  bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
-  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
-  // rows beyond N: zeros keep everything finite; nothing of theirs is stored
-  const long long r = (long long)bh * s.N + (iok ? i : 0);
-  const float lse2 = iok ? lse[r] * kLog2e : 0.f;
-  const float mub = iok ? stats[r] : 0.f;
-  const float ds = iok ? dsig[r] : 0.f;
-  const float s1 = iok ? sig1[r] : 0.f;
-  f32x16 aQ[NDB], aTQ[NDB];
-  zero_acc(aQ);
-  zero_acc(aTQ);
-  const float c1 = s.alpha * kLog2e;
-
-  __syncthreads();  // tile 0 has landed
-  for (int j0 = 0, it = 0; j0 < s.N; j0 += kTS, ++it) {
-    const char* lds_k = lds + (it & 1) * BUF;
-    const char* lds_tk = lds_k + TK::BYTES;
-    const char* lds_v = lds_k + 2 * TK::BYTES;
-    const char* lds_tv = lds_v + TV::BYTES;
-    if (j0 + kTS < s.N) issue(j0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
-
-#pragma unroll
-    for (int jb = 0; jb < kTS / 32; ++jb) {
-      if (j0 + jb * 32 >= s.N) break;  // uniform
-      // Fragments are fetched a whole phase ahead of the products that use them, so the LDS
-      // latency of each phase hides behind the previous phase's matrix-core work.
-      bf16x8 kfr[NKS], tkfr[NKS], vfr[NKS], tvfr[NKS];
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        kfr[kk] = TK::frag_row(lds_k, rk, jb, kk);
-        tkfr[kk] = TK::frag_row(lds_tk, rk, jb, kk);
-      }
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        vfr[kk] = TV::frag_row(lds_v, rv, jb, kk);
-        tvfr[kk] = TV::frag_row(lds_tv, rv, jb, kk);
-      }
-      f32x16 sS = zero16(), sT = zero16();
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        sS = mfma(kfr[kk], qf[kk], sS);
-        sT = mfma(kfr[kk], tqf[kk], sT);
-        sT = mfma(tkfr[kk], qf[kk], sT);
-      }
-      bf16x8 kT[2][NDB], tkT[2][NDB];
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          kT[cc][db] = TK::frag_tr(lds_k, ta, 2 * jb + cc, db);
-          tkT[cc][db] = TK::frag_tr(lds_tk, ta, 2 * jb + cc, db);
-        }
-      f32x16 sDF = zero16(), sE = zero16();
-#pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-#if defined(EXP_NOE)
-        sE[kk] += (float)vfr[kk][0] * (float)tgf[kk][0];
-        sDF[kk] += (float)tvfr[kk][0] * (float)gf[kk][0];
-#else
-        sE = mfma(vfr[kk], tgf[kk], sE);
-        sDF = mfma(vfr[kk], gf[kk], sDF);
-        sDF = mfma(tvfr[kk], tgf[kk], sDF);
-#endif
-      }
-      if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
-#pragma unroll
-        for (int rr = 0; rr < 16; ++rr)
-          if (j0 + jb * 32 + drow(rr, hh) >= s.N) sS[rr] = -INFINITY;
-      }
-      bf16x8 gzf[2], gztf[2];
-#pragma unroll
-      for (int rr = 0; rr < 16; ++rr) {
-#if defined(EXP_NOPW)
-        const float gz = sS[rr] + sT[rr], gzt = sE[rr] + sDF[rr];
-#else
-        const float p = __builtin_amdgcn_exp2f(fmaf(sS[rr], c1, -lse2));
-        const float n = fmaf(sT[rr], s.alpha, -mub);
-        const float gzt = p * (sE[rr] - s1);
-        const float gz = fmaf(gzt, n, p * (sDF[rr] - ds));
-#endif
-        gzf[rr >> 3][rr & 7] = (bf16)gz;
-        gztf[rr >> 3][rr & 7] = (bf16)gzt;
-      }
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-#if defined(EXP_NOOUT)
-          aQ[db][cc] += (float)gzf[cc][db] + (float)kT[cc][db][0] + (float)tkT[cc][db][1];
-          aTQ[db][cc] += (float)gztf[cc][db];
-#else
-          aQ[db] = mfma(kT[cc][db], gzf[cc], aQ[db]);
-          aQ[db] = mfma(tkT[cc][db], gztf[cc], aQ[db]);
-          aTQ[db] = mfma(kT[cc][db], gztf[cc], aTQ[db]);
-#endif
-        }
-    }
-    __syncthreads();  // next tile landed; everyone is done with this one
-  }
-  if (!iok) return;
-  const long long ro = base + (long long)i * s.sn;
-#if defined(EXP_NOSTORE)
-  if (aQ[0][0] + aTQ[0][0] + aQ[1][3] + aQ[2][5] + aTQ[1][1] + aTQ[2][2] != 12345.f) return;
-#endif
-  store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
-  store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
-}
-
-template <int DK, int DV>
-hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
-                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
-                     a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
-                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
-  return hipGetLastError();
-}
-
-template <int DK, int DV>
-hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
-                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
-                     a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq,
-                     (bf16*)a.dtq);
-  return hipGetLastError();
-}
-
-}  // namespace
-
-bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 == 0 && s.D <= 128; }
-
-#define TVM_DISPATCH_D(FN)                        \
+#define TVM_DISPATCH_D(FN, WIDE)                  \
   switch ((s.D + 15) / 16 * 16) {                 \
     case 16: return FN<16, 32>(s, a, st);         \
     case 32: return FN<32, 32>(s, a, st);         \
@@ -361,12 +20,14 @@ bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 ==
     case 64: return FN<64, 64>(s, a, st);         \
     case 80: return FN<80, 96>(s, a, st);         \
     case 96: return FN<96, 96>(s, a, st);         \
-    case 112: return FN<112, 128>(s, a, st);      \
-    case 128: return FN<128, 128>(s, a, st);      \
-    default: return hipErrorNotSupported;         \
+    default: return WIDE(s, a, st);               \
   }
 
-hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) { TVM_DISPATCH_D(launch_col) }
-hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) { TVM_DISPATCH_D(launch_row) }
+hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  TVM_DISPATCH_D(launch_col, launch_bwd_col_mfma_wide)
+}
+hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  TVM_DISPATCH_D(launch_row, launch_bwd_row_mfma_wide)
+}
 
 }  // namespace tvm

@@ -57,10 +57,10 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
   const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
   auto issue = [&](int j0, char* buf) {
-    TK::issue(lk, k + base, s.sn, j0, s.N, buf, wave);
-    TK::issue(lk, tk + base, s.sn, j0, s.N, buf + TK::BYTES, wave);
-    TV::issue(lv, v + base, s.sn, j0, s.N, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + base, s.sn, j0, s.N, buf + 2 * TK::BYTES + TV::BYTES, wave);
+    TK::issue(lk, k + base + (long long)j0 * s.sn, s.N - j0, buf, wave);
+    TK::issue(lk, tk + base + (long long)j0 * s.sn, s.N - j0, buf + TK::BYTES, wave);
+    TV::issue(lv, v + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES, wave);
+    TV::issue(lv, tv + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::TAddr tv_a = TV::taddr(ic, hh);
@@ -81,7 +81,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   float m = -INFINITY, l = 0.f, cs = 0.f;
   const float c1 = s.alpha * kLog2e;  // scores are exponentiated in base 2
 
-  __syncthreads();  // tile 0 has landed (the barrier waits for this wave's outstanding loads)
+  dma_wait();
+  __syncthreads();  // tile 0 has landed
 #if defined(EXP_FNOLOOP)
   for (int j0 = 0, it = 0; j0 < kBN; j0 += kBN, ++it) {
 #else
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
           accT[db] = mfma(tvf, pf[cc], accT[db]);
         }
     }
+    dma_wait();
     __syncthreads();  // next tile landed; everyone is done with this one
   }
 

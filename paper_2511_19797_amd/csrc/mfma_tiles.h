@@ -54,14 +54,39 @@ __device__ __forceinline__ int chunk_off(int s, int c) {
   return (s * PCH + (c ^ ((s >> 2) & 3))) * 16;
 }
 
+// Asynchronous global -> LDS copy: every active lane fetches `BYTES` (16 or 4) from
+// `base + off` (wave-uniform 64-bit base, per-lane unsigned 32-bit byte offset) and the wave
+// writes them to LDS at lds_wave_base + lane * BYTES.  Written as inline assembly so that the
+// compiler does not serialise later LDS reads of OTHER buffers behind these loads; the kernels
+// wait for them explicitly (dma_wait) before the barrier that publishes a tile.
+template <int BYTES>
+__device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, const char* lds_wave_base) {
+  static_assert(BYTES == 16 || BYTES == 4, "dword or dwordx4");
+  const unsigned m = __builtin_amdgcn_readfirstlane(
+      (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_wave_base);
+  const unsigned long long b = (unsigned long long)(uintptr_t)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+  const unsigned long long bu = ((unsigned long long)hi << 32) | lo;  // provably uniform: lives in an SGPR pair
+  if (BYTES == 16)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
+}
+// Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // A streamed tile: ROWS rows, logical chunks [0, NCH) (columns [0, 8*NCH)), filled by NW waves
 // with asynchronous global->LDS loads (global_load_lds_dwordx4: each wave instruction fills 64
 // consecutive physical chunks, every lane fetching the global chunk that the swizzle puts at
-// its position).  No staging registers; the loads complete in the background and are waited
-// for (vmcnt) at the workgroup barrier that ends the computation on the other buffer.
-// Chunks beyond D and rows beyond N are never written: the buffers are zeroed once at kernel
-// start, pad columns therefore stay zero, and rows past N hold zeros or an older tile's
-// (finite) rows, which the kernels give weight exactly 0.
+// its position).  No staging registers and, for a full tile, no per-tile vector arithmetic: the
+// lane offsets are constants and the tile's base address is scalar.  The loads complete in the
+// background and are waited for (dma_wait) just before the workgroup barrier that ends the
+// computation on the other buffer.
+// Columns beyond D: the lane fetches chunk 0 of its row instead, so pad columns hold finite
+// data; whatever multiplies them is zero (fixed-side fragments are zero beyond D) or lands in
+// output rows beyond D that are never stored.  Rows beyond N are not written: the buffers are
+// zeroed once at kernel start, so such rows hold zeros or an older tile's (finite) rows, which
+// the kernels give weight exactly 0.
 template <int ROWS_, int NCH_, int NW_>
 struct Tile {
   static constexpr int ROWS = ROWS_, NCH = NCH_, NW = NW_;
@@ -71,10 +96,10 @@ struct Tile {
   static constexpr int IPW = (NINST + NW_ - 1) / NW_;  // of which each wave issues this many
   static_assert((ROWS_ * PCH) % 64 == 0, "tile must be a whole number of wave loads");
 
-  // Per-lane constants: where in the head (relative to the tile's first row) each of this lane's
-  // chunks comes from, and which tile row it is (1<<30 if the column is beyond D: never loaded).
+  // Per-lane constants: byte offset from the tile's first row of each chunk this lane fetches
+  // (chunk 0 of the row for columns beyond D and for pad positions), and the tile row it belongs to.
   struct Lane {
-    long long goff[IPW];
+    unsigned off[IPW];
     int srow[IPW];
   };
   __device__ __forceinline__ static Lane lane_setup(long long sn, int D, int wave, int lane) {
@@ -84,23 +109,28 @@ struct Tile {
       const int P = (wave + t * NW) * 64 + lane;
       const int s = P / PCH;
       const int c = (P - s * PCH) ^ ((s >> 2) & 3);
-      L.goff[t] = (long long)s * sn + c * 8;
-      L.srow[t] = (c * 8 < D) ? s : (1 << 30);
+      L.off[t] = (unsigned)(((long long)s * sn + (c * 8 < D ? c * 8 : 0)) * 2);
+      L.srow[t] = s;
     }
     return L;
   }
-  // Starts the loads of rows [r0, r0+ROWS) of the [N,D] matrix at `src` (row pitch sn) into `lds`.
-  __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ src, long long sn, int r0,
-                                               int N, char* lds, int wave) {
-    typedef const __attribute__((address_space(1))) void* gp;
-    typedef __attribute__((address_space(3))) void* lp;
+  // Starts the loads of ROWS rows starting at `tile` (first row of the tile in global memory, row
+  // pitch as given to lane_setup) into `lds`; only rows < rows_left exist.
+  __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ tile, int rows_left, char* lds,
+                                               int wave) {
+    if (rows_left >= ROWS) {  // uniform: whole tile, no predication
 #pragma unroll
-    for (int t = 0; t < IPW; ++t) {
-      const int inst = wave + t * NW;
-      if (NINST % NW == 0 || inst < NINST) {
-        if (L.srow[t] < N - r0)
-          __builtin_amdgcn_global_load_lds((gp)(src + (long long)r0 * sn + L.goff[t]), (lp)(lds + inst * 1024), 16, 0,
-                                           0);
+      for (int t = 0; t < IPW; ++t) {
+        const int inst = wave + t * NW;
+        if (NINST % NW == 0 || inst < NINST) dma_to_lds<16>(tile, L.off[t], lds + inst * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < IPW; ++t) {
+        const int inst = wave + t * NW;
+        if (NINST % NW == 0 || inst < NINST) {
+          if (L.srow[t] < rows_left) dma_to_lds<16>(tile, L.off[t], lds + inst * 1024);
+        }
       }
     }
   }

@@ -141,15 +141,16 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
                  static_cast<float*>(workspace),
                  reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2)};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
+  hipError_t e = hipSuccess;
   mark(0, st);
-  hipError_t e = tvm::launch_bwd_pre(s, desc->dtype, a, st);
+  if (!mf) e = tvm::launch_bwd_pre(s, desc->dtype, a, st);  // the matrix-core query-side kernel does Step 1 itself
   if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
   mark(1, st);
-  const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
-  e = mf ? tvm::launch_bwd_col_mfma(s, a, st) : tvm::launch_bwd_col_generic(s, desc->dtype, a, st);
+  e = mf ? tvm::launch_bwd_row_mfma(s, a, st) : tvm::launch_bwd_row_generic(s, desc->dtype, a, st);
   if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
   mark(2, st);
-  e = mf ? tvm::launch_bwd_row_mfma(s, a, st) : tvm::launch_bwd_row_generic(s, desc->dtype, a, st);
+  e = mf ? tvm::launch_bwd_col_mfma(s, a, st) : tvm::launch_bwd_col_generic(s, desc->dtype, a, st);
   mark(3, st);
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
