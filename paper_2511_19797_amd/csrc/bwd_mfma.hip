@@ -30,4 +30,10 @@ hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st)
   TVM_DISPATCH_D(launch_row, launch_bwd_row_mfma_wide)
 }
 
+#if defined(TVM_PROFILE)
+extern "C" int tvmattn_debug_read_prof(long long* out16) {
+  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prof), sizeof(long long) * 16);
+}
+#endif
+
 }  // namespace tvm

@@ -28,6 +28,23 @@
 #include "mfma_tiles.h"
 
 namespace tvm {
+#if defined(TVM_PROFILE)
+static __device__ long long g_prof[16];
+#define PROF_DECL long long pt_ = clock64(), pa_[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define PROF(i)                        \
+  do {                                 \
+    const long long n_ = clock64();    \
+    pa_[i] += n_ - pt_;                \
+    pt_ = n_;                          \
+  } while (0)
+#define PROF_DUMP                                                                  \
+  if (blockIdx.x == 3 && threadIdx.x == 0)                                         \
+    for (int i_ = 0; i_ < 8; ++i_) g_prof[i_] = pa_[i_]
+#else
+#define PROF_DECL
+#define PROF(i)
+#define PROF_DUMP
+#endif
 namespace {
 
 constexpr int kFix = 128;  // fixed-side rows per workgroup (4 waves x 32)
@@ -51,7 +68,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
     bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
   using TX = Tile<kTS, DV / 8, kNT / 64>;  // read both ways: columns up to DV
-  constexpr int ROWV = 4 * kTS * 4;                   // four float32 row vectors per stage
+  constexpr int ROWV = 4 * 256;                       // four float32 row vectors per stage (64 slots each)
   constexpr int BUF = 4 * TX::BYTES + ROWV;           // one stage: Q, tQ, G, tG, row vectors
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
@@ -65,22 +82,24 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
   const bool jok = j < s.N;
 
-  const typename TX::Lane lx = TX::lane_setup(s.sn, s.D, wave, lane);
+  const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
+  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned lds0 = lds_addr_of(lds);
   // wave w also fetches row vector w (lse, stats, dsig, sig1) of the tile, one float per lane
+  // (lanes past the tile or past the last row re-read the last row's value: masked rows, unused)
   const float* const rowsrc = (wave == 0 ? lse : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
-  auto issue = [&](int i0, char* buf) {
-    TX::issue(lx, q + base + (long long)i0 * s.sn, s.N - i0, buf, wave);
-    TX::issue(lx, tq + base + (long long)i0 * s.sn, s.N - i0, buf + TX::BYTES, wave);
-    TX::issue(lx, gO + base + (long long)i0 * s.sn, s.N - i0, buf + 2 * TX::BYTES, wave);
-    TX::issue(lx, gTO + base + (long long)i0 * s.sn, s.N - i0, buf + 3 * TX::BYTES, wave);
-    if (lane < kTS && i0 + lane < s.N)
-      dma_to_lds<4>(rowsrc + i0, lane * 4u, buf + 4 * TX::BYTES + wave * kTS * 4);
+  auto issue = [&](int i0, unsigned buf) {  // i0 < N
+    const long long ro = base + (long long)i0 * s.sn;
+    const int left = s.N - i0;
+    TX::issue(lx, q + ro, pitch, left, buf, wave);
+    TX::issue(lx, tq + ro, pitch, left, buf + TX::BYTES, wave);
+    TX::issue(lx, gO + ro, pitch, left, buf + 2 * TX::BYTES, wave);
+    TX::issue(lx, gTO + ro, pitch, left, buf + 3 * TX::BYTES, wave);
+    dma_to_lds<4>(rowsrc + i0, (unsigned)min(lane, left - 1) * 4u, buf + 4 * TX::BYTES + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
   const typename TX::TAddr ta = TX::taddr(ic, hh);
-  lds_zero<kNT>(lds, 2 * BUF, tid);
-  __syncthreads();
-  issue(0, lds);
+  issue(0, lds0);
 
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
   gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
@@ -102,10 +121,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     const char* lds_g = lds_q + 2 * TX::BYTES;
     const char* lds_tg = lds_q + 3 * TX::BYTES;
     const float* row_lse = reinterpret_cast<const float*>(lds_q + 4 * TX::BYTES);
-    const float* row_mub = row_lse + kTS;
-    const float* row_dsig = row_lse + 2 * kTS;
-    const float* row_sig1 = row_lse + 3 * kTS;
-    if (i0 + kTS < s.N) issue(i0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
+    const float* row_mub = row_lse + 64;
+    const float* row_dsig = row_lse + 128;
+    const float* row_sig1 = row_lse + 192;
+    if (i0 + kTS < s.N) issue(i0 + kTS, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll
     for (int ib = 0; ib < kTS / 32; ++ib) {
@@ -184,6 +203,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
 // ------------------------------------------------------------------------------------------
 // Query side.
 // ------------------------------------------------------------------------------------------
+// ------------------------------------------------------------------------------------------
+// Query side.
+// ------------------------------------------------------------------------------------------
 template <int DK, int DV, int kTS>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
@@ -205,22 +227,22 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
   const bool iok = i < s.N;
 
-  const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
-  const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
-  auto issue = [&](int j0, char* buf) {
-    TK::issue(lk, k + base + (long long)j0 * s.sn, s.N - j0, buf, wave);
-    TK::issue(lk, tk + base + (long long)j0 * s.sn, s.N - j0, buf + TK::BYTES, wave);
-    TV::issue(lv, v + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES + TV::BYTES, wave);
+  const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
+  const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
+  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned lds0 = lds_addr_of(lds);
+  auto issue = [&](int j0, unsigned buf) {  // j0 < N
+    const long long ro = base + (long long)j0 * s.sn;
+    const int left = s.N - j0;
+    TK::issue(lk, k + ro, pitch, left, buf, wave);
+    TK::issue(lk, tk + ro, pitch, left, buf + TK::BYTES, wave);
+    TV::issue(lv, v + ro, pitch, left, buf + 2 * TK::BYTES, wave);
+    TV::issue(lv, tv + ro, pitch, left, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::RAddr rv = TV::raddr(ic, hh);
   const typename TK::TAddr ta = TK::taddr(ic, hh);
-#if !defined(EXP_NOZERO)
-  lds_zero<kNT>(lds, 2 * BUF, tid);
-#endif
-  __syncthreads();
-  issue(0, lds);
+  issue(0, lds0);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
@@ -267,7 +289,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     const char* lds_tk = lds_k + TK::BYTES;
     const char* lds_v = lds_k + 2 * TK::BYTES;
     const char* lds_tv = lds_v + TV::BYTES;
-    if (j0 + kTS < s.N) issue(j0 + kTS, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
+    if (j0 + kTS < s.N) issue(j0 + kTS, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll
     for (int jb = 0; jb < kTS / 32; ++jb) {
@@ -338,14 +360,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-#if defined(EXP_NOOUT)
-          aQ[db][cc] += (float)gzf[cc][db] + (float)kT[cc][db][0] + (float)tkT[cc][db][1];
-          aTQ[db][cc] += (float)gztf[cc][db];
-#else
           aQ[db] = mfma(kT[cc][db], gzf[cc], aQ[db]);
           aQ[db] = mfma(tkT[cc][db], gztf[cc], aQ[db]);
           aTQ[db] = mfma(kT[cc][db], gztf[cc], aTQ[db]);
-#endif
         }
     }
     dma_wait();
@@ -353,9 +370,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   }
   if (!iok) return;
   const long long ro = base + (long long)i * s.sn;
-#if defined(EXP_NOSTORE)
-  if (aQ[0][0] + aTQ[0][0] + aQ[1][3] + aQ[2][5] + aTQ[1][1] + aTQ[2][2] != 12345.f) return;
-#endif
   store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
   store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
 }

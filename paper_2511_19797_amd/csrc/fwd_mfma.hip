@@ -54,19 +54,21 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   const int i = mb * BM + wave * 32 + ic;  // this lane's query row
   const bool iok = i < s.N;
 
-  const typename TK::Lane lk = TK::lane_setup(s.sn, s.D, wave, lane);
-  const typename TV::Lane lv = TV::lane_setup(s.sn, s.D, wave, lane);
-  auto issue = [&](int j0, char* buf) {
-    TK::issue(lk, k + base + (long long)j0 * s.sn, s.N - j0, buf, wave);
-    TK::issue(lk, tk + base + (long long)j0 * s.sn, s.N - j0, buf + TK::BYTES, wave);
-    TV::issue(lv, v + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + base + (long long)j0 * s.sn, s.N - j0, buf + 2 * TK::BYTES + TV::BYTES, wave);
+  const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
+  const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
+  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned lds0 = lds_addr_of(lds);
+  auto issue = [&](int j0, unsigned buf) {  // j0 < N
+    const long long ro = base + (long long)j0 * s.sn;
+    const int left = s.N - j0;
+    TK::issue(lk, k + ro, pitch, left, buf, wave);
+    TK::issue(lk, tk + ro, pitch, left, buf + TK::BYTES, wave);
+    TV::issue(lv, v + ro, pitch, left, buf + 2 * TK::BYTES, wave);
+    TV::issue(lv, tv + ro, pitch, left, buf + 2 * TK::BYTES + TV::BYTES, wave);
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::TAddr tv_a = TV::taddr(ic, hh);
-  lds_zero<NT>(lds, 2 * BUF, tid);
-  __syncthreads();
-  issue(0, lds);
+  issue(0, lds0);
 
   bf16x8 qf[NKS], tqf[NKS];
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
     const char* lds_tk = lds_k + TK::BYTES;
     const char* lds_v = lds_k + 2 * TK::BYTES;
     const char* lds_tv = lds_v + TV::BYTES;
-    if (j0 + kBN < s.N) issue(j0 + kBN, lds + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
+    if (j0 + kBN < s.N) issue(j0 + kBN, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll
     for (int jb = 0; jb < kBN / 32; ++jb) {

@@ -54,16 +54,15 @@ __device__ __forceinline__ int chunk_off(int s, int c) {
   return (s * PCH + (c ^ ((s >> 2) & 3))) * 16;
 }
 
-// Asynchronous global -> LDS copy: every active lane fetches `BYTES` (16 or 4) from
-// `base + off` (wave-uniform 64-bit base, per-lane unsigned 32-bit byte offset) and the wave
-// writes them to LDS at lds_wave_base + lane * BYTES.  Written as inline assembly so that the
-// compiler does not serialise later LDS reads of OTHER buffers behind these loads; the kernels
-// wait for them explicitly (dma_wait) before the barrier that publishes a tile.
+// Asynchronous global -> LDS copy: every lane fetches `BYTES` (16 or 4) from `base + off`
+// (wave-uniform 64-bit base, per-lane unsigned 32-bit byte offset) and the wave writes them to
+// LDS at address lds_addr + lane * BYTES (lds_addr wave-uniform).  Written as inline assembly so
+// that the compiler does not serialise later LDS reads of OTHER buffers behind these loads; the
+// kernels wait for them explicitly (dma_wait) before the barrier that publishes a tile.
 template <int BYTES>
-__device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, const char* lds_wave_base) {
+__device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsigned lds_addr) {
   static_assert(BYTES == 16 || BYTES == 4, "dword or dwordx4");
-  const unsigned m = __builtin_amdgcn_readfirstlane(
-      (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_wave_base);
+  const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
   const unsigned long long b = (unsigned long long)(uintptr_t)base;
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
   const unsigned long long bu = ((unsigned long long)hi << 32) | lo;  // provably uniform: lives in an SGPR pair
@@ -75,64 +74,59 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, const
 // Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// LDS address (the 32-bit value LDS instructions and M0 use) of a __shared__ object.
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
 // A streamed tile: ROWS rows, logical chunks [0, NCH) (columns [0, 8*NCH)), filled by NW waves
 // with asynchronous global->LDS loads (global_load_lds_dwordx4: each wave instruction fills 64
 // consecutive physical chunks, every lane fetching the global chunk that the swizzle puts at
-// its position).  No staging registers and, for a full tile, no per-tile vector arithmetic: the
-// lane offsets are constants and the tile's base address is scalar.  The loads complete in the
-// background and are waited for (dma_wait) just before the workgroup barrier that ends the
-// computation on the other buffer.
-// Columns beyond D: the lane fetches chunk 0 of its row instead, so pad columns hold finite
-// data; whatever multiplies them is zero (fixed-side fragments are zero beyond D) or lands in
-// output rows beyond D that are never stored.  Rows beyond N are not written: the buffers are
-// zeroed once at kernel start, so such rows hold zeros or an older tile's (finite) rows, which
-// the kernels give weight exactly 0.
+// its position).  No staging registers, no branches: every lane of every wave-load always
+// fetches something valid.
+//   - columns beyond D and pad positions: chunk 0 of the row (finite data; whatever multiplies
+//     it is zero, or lands in output rows beyond D that are never stored);
+//   - rows beyond the last one: the last row again (the kernels give such rows weight exactly 0);
+//   - positions past the tile (when the tile is not a whole number of wave-loads per wave):
+//     slack space after the tile, never read.
+// The loads complete in the background and are waited for (dma_wait) just before the workgroup
+// barrier that ends the computation on the other buffer.
 template <int ROWS_, int NCH_, int NW_>
 struct Tile {
   static constexpr int ROWS = ROWS_, NCH = NCH_, NW = NW_;
   static constexpr int PCH = pitch_chunks(NCH_ * 8);
-  static constexpr int BYTES = ROWS_ * PCH * 16;
-  static constexpr int NINST = ROWS_ * PCH / 64;       // wave-wide load instructions per tile
-  static constexpr int IPW = (NINST + NW_ - 1) / NW_;  // of which each wave issues this many
-  static_assert((ROWS_ * PCH) % 64 == 0, "tile must be a whole number of wave loads");
+  static constexpr int NINST = (ROWS_ * PCH + 63) / 64;  // wave-wide load instructions per tile
+  static constexpr int IPW = (NINST + NW_ - 1) / NW_;    // of which each wave issues this many
+  static constexpr int BYTES = IPW * NW_ * 1024;         // LDS footprint (tile + slack)
 
-  // Per-lane constants: byte offset from the tile's first row of each chunk this lane fetches
-  // (chunk 0 of the row for columns beyond D and for pad positions), and the tile row it belongs to.
+  // Per-lane constants: tile row and byte offset within the row of each chunk this lane fetches.
   struct Lane {
-    unsigned off[IPW];
+    unsigned col[IPW];
     int srow[IPW];
   };
-  __device__ __forceinline__ static Lane lane_setup(long long sn, int D, int wave, int lane) {
+  __device__ __forceinline__ static Lane lane_setup(int D, int wave, int lane) {
     Lane L;
 #pragma unroll
     for (int t = 0; t < IPW; ++t) {
       const int P = (wave + t * NW) * 64 + lane;
       const int s = P / PCH;
       const int c = (P - s * PCH) ^ ((s >> 2) & 3);
-      L.off[t] = (unsigned)(((long long)s * sn + (c * 8 < D ? c * 8 : 0)) * 2);
+      L.col[t] = (unsigned)((c * 8 < D ? c * 8 : 0) * 2);
       L.srow[t] = s;
     }
     return L;
   }
-  // Starts the loads of ROWS rows starting at `tile` (first row of the tile in global memory, row
-  // pitch as given to lane_setup) into `lds`; only rows < rows_left exist.
-  __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ tile, int rows_left, char* lds,
-                                               int wave) {
-    if (rows_left >= ROWS) {  // uniform: whole tile, no predication
+  // t-th wave-load of the tile whose first row is at `tile` (row pitch `pitch` bytes); rows_left >= 1
+  // rows exist from there on.  `lds` is the LDS address of the tile buffer.
+  __device__ __forceinline__ static void issue_one(const Lane& L, int t, const bf16* __restrict__ tile, unsigned pitch,
+                                                   int rows_left, unsigned lds, int wave) {
+    const unsigned r = (unsigned)min(L.srow[t], rows_left - 1);
+    dma_to_lds<16>(tile, r * pitch + L.col[t], lds + (unsigned)(wave + t * NW) * 1024u);
+  }
+  __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ tile, unsigned pitch,
+                                               int rows_left, unsigned lds, int wave) {
 #pragma unroll
-      for (int t = 0; t < IPW; ++t) {
-        const int inst = wave + t * NW;
-        if (NINST % NW == 0 || inst < NINST) dma_to_lds<16>(tile, L.off[t], lds + inst * 1024);
-      }
-    } else {
-#pragma unroll
-      for (int t = 0; t < IPW; ++t) {
-        const int inst = wave + t * NW;
-        if (NINST % NW == 0 || inst < NINST) {
-          if (L.srow[t] < rows_left) dma_to_lds<16>(tile, L.off[t], lds + inst * 1024);
-        }
-      }
-    }
+    for (int t = 0; t < IPW; ++t) issue_one(L, t, tile, pitch, rows_left, lds, wave);
   }
   // Read addressing.  All swizzle arithmetic is folded into a few per-lane constants so that
   // every fragment read is  lane constant + compile-time immediate.
@@ -206,6 +200,15 @@ __device__ __forceinline__ void gld_frags(bf16x8 (&f)[NKS], const bf16* __restri
   }
 }
 
+__device__ __forceinline__ bf16x8 zero_unless(bf16x8 f, bool keep) {
+  uint4 v = __builtin_bit_cast(uint4, f);
+  v.x = keep ? v.x : 0u;
+  v.y = keep ? v.y : 0u;
+  v.z = keep ? v.z : 0u;
+  v.w = keep ? v.w : 0u;
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  This maps the
@@ -232,6 +235,37 @@ __device__ __forceinline__ void store_acc(bf16* __restrict__ dst, const f32x16 (
         *reinterpret_cast<bf16x4*>(dst + d0) = o;
       }
     }
+}
+
+// Coalesced store of a [32*NW x D] output tile held as transposed accumulators (rows = d, column
+// = this lane's output row): each wave parks its 32 rows in its own LDS region as bf16, then
+// writes them out as 16-byte chunks with consecutive lanes on consecutive chunks, so a wave
+// store covers contiguous memory instead of 32 scattered 16-byte pieces.  Only wave-local
+// ordering is needed (a wave reads back what it wrote itself).
+//   lds_wave: this wave's region, at least 32 * (2*DV + 8) bytes.
+template <int NDB>
+__device__ __forceinline__ void store_tile_coalesced(char* lds_wave, bf16* __restrict__ head, long long sn, int row0,
+                                                     int N, int D, const f32x16 (&a)[NDB], float scale, int lane) {
+  constexpr int PB = 2 * 32 * NDB + 8;  // row pitch: 8 (mod 256) bytes keeps the 8-byte writes off each other's banks
+  const int ic = lane & 31, hh = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = db * 32 + 8 * g + 4 * hh;
+      bf16x4 o;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
+      *reinterpret_cast<bf16x4*>(lds_wave + ic * PB + d0 * 2) = o;
+    }
+  const int nch = D >> 3;  // 16-byte chunks per row
+  for (int idx = lane; idx < 32 * nch; idx += 64) {
+    const int r = idx / nch, c = idx - r * nch;
+    const uint2 lo = *reinterpret_cast<const uint2*>(lds_wave + r * PB + c * 16);
+    const uint2 hi = *reinterpret_cast<const uint2*>(lds_wave + r * PB + c * 16 + 8);
+    if (row0 + r < N)
+      *reinterpret_cast<uint4*>(head + (long long)(row0 + r) * sn + c * 8) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  }
 }
 
 }  // namespace tvm
