@@ -30,9 +30,18 @@ PEAK_HBM_GBS = 8000.0
 # them is overhead, not algorithmic work.  12 + 24 + 6 = 42.
 KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.0}
 
-# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# copy kernel of known size (see profiles/).  None until measured for that workload and kernel.
-MEASURED_TRAFFIC = {}
+# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch),
+# each scaled by what the same counter reads for a 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0);
+# figures and commands in profiles/tvmattn_kernels_C4_counters.md.  None where not measured.
+_KIB = 1024.0
+MEASURED_TRAFFIC = {
+    ("C4", "fwd"): 110659.6 * _KIB * 2.0 + 75777.2 * _KIB,
+    ("C4", "bwd_row"): 185473.9 * _KIB * 2.0 + 75776.0 * _KIB,
+    ("C4", "bwd_col"): 149662.9 * _KIB * 2.0 + 147456.0 * _KIB,
+    ("C3", "fwd"): 55371.4 * _KIB * 2.0 + 37897.3 * _KIB,
+    ("C3", "bwd_row"): 92780.0 * _KIB * 2.0 + 37888.0 * _KIB,
+    ("C3", "bwd_col"): 74909.5 * _KIB * 2.0 + 73728.0 * _KIB,
+}
 
 
 class Hip:
