@@ -85,11 +85,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
 
   dma_wait();
   __syncthreads();  // tile 0 has landed
-#if defined(EXP_FNOLOOP)
-  for (int j0 = 0, it = 0; j0 < kBN; j0 += kBN, ++it) {
-#else
   for (int j0 = 0, it = 0; j0 < s.N; j0 += kBN, ++it) {
-#endif
     const char* lds_k = lds + (it & 1) * BUF;
     const char* lds_tk = lds_k + TK::BYTES;
     const char* lds_v = lds_k + 2 * TK::BYTES;
@@ -163,9 +159,6 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   l += xhalf(l);
   cs += xhalf(cs);
   if (!iok) return;
-#if defined(EXP_FNOSTORE)
-  if (accO[0][0] + accT[0][0] + accO[1][3] + accO[2][5] + accT[1][1] + accT[2][2] + l + cs != 12345.f) return;
-#endif
   const float inv = 1.f / l;
   const float mubar = cs * inv;
 #pragma unroll
