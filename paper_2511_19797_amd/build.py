@@ -18,6 +18,8 @@ COMMON = [
 PER_FILE = {
     "bwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    # hand-ordered instruction stream: source order must survive to the ISA
+    "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],
 }
 
 

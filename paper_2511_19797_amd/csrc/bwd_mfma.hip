@@ -27,7 +27,8 @@ hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st)
   TVM_DISPATCH_D(launch_col, launch_bwd_col_mfma_wide)
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  TVM_DISPATCH_D(launch_row, launch_bwd_row_mfma_wide)
+  if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);  // hand-scheduled variant (bwd_row_pipe.hip)
+  return launch_bwd_row_mfma_wide(s, a, st);
 }
 
 #if defined(TVM_PROFILE)

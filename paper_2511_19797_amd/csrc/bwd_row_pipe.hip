@@ -1,0 +1,403 @@
+// Query-side backward kernel (dQ, dtQ; Steps 3 and 5 of App. C plus the ordinary-attention terms
+// of gO, and the row scalars of Step 1) for head dims up to 96, with the instruction stream of a
+// 64-key tile laid out by hand.  Same mathematics and data layout as the generic-order kernel
+// in bwd_mfma_kernels.h; what differs is when things are issued.
+//
+// A wave runs alone on its SIMD (the register budget allows no second wave), so nothing hides
+// its VALU work, LDS reads or load issue unless they sit between its own matrix-core products.
+// A tile is two 32-key blocks; the products of one block are interleaved with the pointwise work
+// of the other, and every memory instruction is issued between products, at least a phase
+// before its data is needed:
+//
+//   phase        products (matrix cores)              in their shadow
+//   S(0)         S, St of block 0                     E-fragments of block 0 <- LDS; loads of tile t+1, 2nd half
+//   E(0)         E, DF of block 0                     P, N of block 0;  S-fragments of block 1 <- LDS
+//   S(1)         S, St of block 1                     gZ, gZt of block 0;  E-fragments of block 1 <- LDS
+//   E(1)         E, DF of block 1                     P, N of block 1;  transposed K, tK of block 0 <- LDS
+//   O(0)         dQ, dtQ += (gZ, gZt of block 0) .    gZ, gZt of block 1;  transposed K, tK of block 1 <- LDS
+//   -- all reads of this tile's buffer are done: wait for tile t+1, workgroup barrier --
+//   O(1)         dQ, dtQ += (gZ, gZt of block 1) .    S-fragments of tile t+1 <- LDS; loads of tile t+2, 1st half
+//
+// The translation unit is built with the machine scheduler off: source order is issue order.
+#include "mfma_tiles.h"
+
+#include <type_traits>
+
+namespace tvm {
+namespace {
+
+constexpr int kFix = 128;  // queries per workgroup (4 waves x 32)
+constexpr int kNT = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr, int imm) {
+  typedef const bf16x8 __attribute__((address_space(3))) * lp;
+  return *(lp)(uintptr_t)(addr + (unsigned)imm);
+}
+__device__ __forceinline__ bf16x8 lds_read_tr(unsigned lo, unsigned hi, int imm) {
+  typedef bf16x4 __attribute__((address_space(3))) * lp;
+  const bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(uintptr_t)(lo + (unsigned)imm));
+  const bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(uintptr_t)(hi + (unsigned)imm));
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// The pointwise work is inline assembly too, so that it stays in the slot it is written in (the
+// optimizer moves plain arithmetic freely between the matrix-core instructions otherwise).
+//   P = exp2(S c1 - lse2),  N = St alpha - mub
+__device__ __forceinline__ void pw1_asm(float& p, float& n, float sv, float st, float c1, float lse2, float alpha,
+                                        float mub) {
+  float t;
+  asm volatile(
+      "v_fma_f32 %2, %3, %5, -%6\n\t"
+      "v_fma_f32 %1, %4, %7, -%8\n\t"
+      "v_exp_f32 %0, %2"
+      : "=v"(p), "=v"(n), "=&v"(t)
+      : "v"(sv), "v"(st), "s"(c1), "v"(lse2), "s"(alpha), "v"(mub));
+}
+//   gZt = P (E - sig1),  gZ = P (DF - dsig) + gZt N, for two neighbouring elements, rounded to bf16 and packed
+__device__ __forceinline__ void pw2_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1, float p0,
+                                        float p1, float n0, float n1, float s1, float ds) {
+  float t0, t1, w0, w1;
+  asm volatile(
+      "v_sub_f32 %2, %6, %14\n\t"
+      "v_sub_f32 %3, %7, %14\n\t"
+      "v_sub_f32 %4, %8, %15\n\t"
+      "v_sub_f32 %5, %9, %15\n\t"
+      "v_mul_f32 %2, %10, %2\n\t"
+      "v_mul_f32 %3, %11, %3\n\t"
+      "v_mul_f32 %4, %10, %4\n\t"
+      "v_mul_f32 %5, %11, %5\n\t"
+      "v_fmac_f32 %4, %2, %12\n\t"
+      "v_fmac_f32 %5, %3, %13\n\t"
+      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
+      "v_cvt_pk_bf16_f32 %1, %2, %3"
+      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
+      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1), "v"(s1), "v"(ds));
+}
+// From here on the compiler may read the tiles: every use below this point depends on it.  Placed
+// after enough further products that the ones writing the tiles have finished.
+__device__ __forceinline__ void landed(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void landed_acc(f32x16& a) { asm volatile("" : "+a"(a)); }
+__device__ __forceinline__ bf16x8 frag_of(const unsigned (&w)[8], int cc) {
+  const uint4 v = make_uint4(w[4 * cc], w[4 * cc + 1], w[4 * cc + 2], w[4 * cc + 3]);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
+    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
+    const bf16* __restrict__ o, const bf16* __restrict__ to, const float* __restrict__ lse,
+    const float* __restrict__ stats, const bf16* __restrict__ gO, const bf16* __restrict__ gTO,
+    float* __restrict__ dsig, float* __restrict__ sig1, bf16* __restrict__ dq, bf16* __restrict__ dtq) {
+  using TK = Tile<64, DV / 8, kNT / 64>;  // K, tK: read both ways
+  using TV = Tile<64, DK / 8, kNT / 64>;  // V, tV: score-type products only
+  constexpr int OFF_TK = TK::BYTES, OFF_V = 2 * TK::BYTES, OFF_TV = 2 * TK::BYTES + TV::BYTES;
+  constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
+  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
+  constexpr int NKS = DK / 16, NDB = DV / 32;
+  constexpr int NS = 3 * NKS;                         // products of a score-type phase
+  constexpr int NO = 6 * NDB;                         // products of an output phase
+  constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
+  constexpr int FO = 4;                               // ... of an output phase (NO >= 6)
+  constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
+  constexpr int NDMA_A = NDMA / 2;                    // of which issued in O(1), the rest in the next S(0)
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int nfb = (s.N + kFix - 1) / kFix;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nfb, fb = wg - bh * nfb;
+  const int b = bh / s.H, h = bh - b * s.H;
+  const long long base = b * s.sb + h * s.sh;
+  const int i = fb * kFix + wave * 32 + ic;  // this lane's query
+  const bool iok = i < s.N;
+
+  const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
+  const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
+  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned lds0 = lds_addr_of(lds);
+  // wave-load number x (compile-time) of the tile whose first key is j0 (< N), into the stage at `buf`
+  auto dma = [&](int x, int j0, unsigned buf) {
+    const long long ro = base + (long long)j0 * s.sn;
+    const int left = s.N - j0;
+    if (x < TK::IPW) TK::issue_one(lk, x, k + ro, pitch, left, buf, wave);
+    else if (x < 2 * TK::IPW) TK::issue_one(lk, x - TK::IPW, tk + ro, pitch, left, buf + OFF_TK, wave);
+    else if (x < 2 * TK::IPW + TV::IPW) TV::issue_one(lv, x - 2 * TK::IPW, v + ro, pitch, left, buf + OFF_V, wave);
+    else TV::issue_one(lv, x - 2 * TK::IPW - TV::IPW, tv + ro, pitch, left, buf + OFF_TV, wave);
+  };
+  const typename TK::RAddr rk = TK::raddr(ic, hh);
+  const typename TV::RAddr rv = TV::raddr(ic, hh);
+  const typename TK::TAddr ta = TK::taddr(ic, hh);
+#pragma unroll
+  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
+
+  bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
+  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
+  // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
+  // this lane's query, from the same fragment layout (each half-wave holds half of the row);
+  // they are also written out for the key-side kernel, which runs after this one.
+  float ds = 0.f, s1 = 0.f;
+  {
+    bf16x8 of[NKS], tof[NKS];
+    gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
+    gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
+#pragma unroll
+    for (int kk = 0; kk < NKS; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float oe = (float)of[kk][e], gte = (float)tgf[kk][e];
+        ds = fmaf((float)gf[kk][e], oe, ds);
+        ds = fmaf(gte, (float)tof[kk][e], ds);
+        s1 = fmaf(gte, oe, s1);
+      }
+    ds += xhalf(ds);
+    s1 += xhalf(s1);
+  }
+  // rows beyond N: zeros keep everything finite; nothing of theirs is stored
+  const long long r = (long long)bh * s.N + (iok ? i : 0);
+  const float lse2 = iok ? lse[r] * kLog2e : 0.f;
+  const float mub = iok ? stats[r] : 0.f;
+  if (iok && hh == 0) {
+    dsig[r] = ds;
+    sig1[r] = s1;
+  }
+  f32x16 aQ[NDB], aTQ[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    aQ[db] = zero16();
+    aTQ[db] = zero16();
+  }
+  // wave-uniform scalars for the assembly blocks (SGPR operands)
+  const float c1u = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha * kLog2e)));
+  const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
+  const int nt = (s.N + 63) >> 6;      // tiles
+  const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
+
+  dma_wait();
+  __syncthreads();  // tile 0 has landed
+#pragma unroll
+  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, jlast), lds0 + BUF);
+  bf16x8 ra[NKS], rb[NKS];  // S-fragments (K, tK rows) of the block whose S phase comes next
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    ra[kk] = lds_read16(lds0 + ((kk & 1) ? rk.o : rk.e), kk * 32);
+    rb[kk] = lds_read16(lds0 + ((kk & 1) ? rk.o : rk.e), OFF_TK + kk * 32);
+  }
+
+  // One tile.  RAG: keys beyond N exist in this tile (only ever the last one).
+  //   sb / sbn: LDS address of this tile's stage / of the other one;  j0: first key;
+  //   jn1 / jn2: first key of the next tile / of the one after it (clamped to the last tile).
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, int j0, int jn1, int jn2) {
+    constexpr bool RAG = decltype(rag)::value;
+    const unsigned ke = sb + rk.e, ko = sb + rk.o;                   // K rows; tK at + OFF_TK
+    const unsigned ve = sb + OFF_V + rv.e, vo = sb + OFF_V + rv.o;   // V rows; tV at + TV::BYTES
+    const unsigned tl = sb + ta.lo, th = sb + ta.hi;                 // K transposed; tK at + OFF_TK
+    const unsigned nke = sbn + rk.e, nko = sbn + rk.o;               // next tile's K rows
+    bf16x8 rc[NKS], rd[NKS];
+    f32x16 sS, sT, sE, sDF;
+    float pp[16], nn[16];
+    unsigned gz0[8], gzt0[8], gz1[8], gzt1[8];
+    bf16x8 kT[2][NDB], tkT[2][NDB], kT1[2][NDB], tkT1[2][NDB];
+
+    auto s_product = [&](int m) {  // m-th product of an S phase (operands ra, rb)
+      const int kk = m / 3, w = m - 3 * kk;
+      if (w == 0) {
+        if (kk == 0) mfma_fix0<RAG>(sS, ra[0], qf[0]);
+        else mfma_fix<RAG>(sS, ra[kk], qf[kk]);
+      } else if (w == 1) {
+        if (kk == 0) mfma_fix0<RAG>(sT, ra[0], tqf[0]);
+        else mfma_fix<RAG>(sT, ra[kk], tqf[kk]);
+      } else {
+        mfma_fix<RAG>(sT, rb[kk], qf[kk]);
+      }
+    };
+    auto e_product = [&](int m) {  // m-th product of an E phase (operands rc, rd)
+      const int kk = m / 3, w = m - 3 * kk;
+      if (w == 0) {
+        if (kk == 0) mfma_fix0<RAG>(sE, rc[0], tgf[0]);
+        else mfma_fix<RAG>(sE, rc[kk], tgf[kk]);
+      } else if (w == 1) {
+        if (kk == 0) mfma_fix0<RAG>(sDF, rc[0], gf[0]);
+        else mfma_fix<RAG>(sDF, rc[kk], gf[kk]);
+      } else {
+        mfma_fix<RAG>(sDF, rd[kk], tgf[kk]);
+      }
+    };
+    auto o_product = [&](int m, const bf16x8 (&xT)[2][NDB], const bf16x8 (&txT)[2][NDB], const unsigned (&gz)[8],
+                         const unsigned (&gzt)[8]) {
+      const int cc = m / (3 * NDB), db = (m / 3) % NDB, w = m % 3;
+      if (w == 0) mfma_acc<RAG>(aQ[db], xT[cc][db], frag_of(gz, cc));
+      else if (w == 1) mfma_acc<RAG>(aQ[db], txT[cc][db], frag_of(gzt, cc));
+      else mfma_acc<RAG>(aTQ[db], xT[cc][db], frag_of(gzt, cc));
+    };
+    // P and N of element e of a block
+    auto pw1 = [&](int blk, int e) {
+      float sv = sS[e];
+      if (RAG && j0 + blk * 32 + drow(e, hh) >= s.N) sv = -INFINITY;  // keys beyond N: probability 0
+      pw1_asm(pp[e], nn[e], sv, sT[e], c1u, lse2, alphau, mub);
+    };
+    // gZ, gZt of elements 2e, 2e+1 of a block
+    auto pw2 = [&](unsigned (&gz)[8], unsigned (&gzt)[8], int e) {
+      pw2_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1], nn[2 * e],
+              nn[2 * e + 1], s1, ds);
+    };
+    // share [m*CNT/N, (m+1)*CNT/N) of CNT side instructions goes after the m-th of N products
+#define TVM_SHARE(x, m, CNT, N) for (int x = (m) * (CNT) / (N); x < ((m) + 1) * (CNT) / (N); ++x)
+
+    // ---- S(0)
+#pragma unroll
+    for (int m = 0; m < NS; ++m) {
+      s_product(m);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NKS, NS) {
+        const int kk = x % NKS;
+        if (x < NKS) rc[kk] = lds_read16((kk & 1) ? vo : ve, kk * 32);
+        else rd[kk] = lds_read16((kk & 1) ? vo : ve, TV::BYTES + kk * 32);
+      }
+#pragma unroll
+      TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, jn1, sbn);
+    }
+    // ---- E(0), with P, N of block 0
+#pragma unroll
+    for (int m = 0; m < NS; ++m) {
+      e_product(m);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NKS, NS) {  // S-fragments of block 1
+        const int kk = x % NKS;
+        if (x < NKS) ra[kk] = lds_read16((kk & 1) ? ko : ke, TK::kBlkBytes + kk * 32);
+        else rb[kk] = lds_read16((kk & 1) ? ko : ke, OFF_TK + TK::kBlkBytes + kk * 32);
+      }
+      if (m == FS) {
+        if (NS < 6) mfma_settle();
+        landed(sS, sT);
+      }
+      if (m >= FS) {
+#pragma unroll
+        TVM_SHARE(e, m - FS, 16, NS - FS) pw1(0, e);
+      }
+    }
+    // ---- S(1), with gZ, gZt of block 0
+#pragma unroll
+    for (int m = 0; m < NS; ++m) {
+      s_product(m);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NKS, NS) {  // E-fragments of block 1
+        const int kk = x % NKS;
+        if (x < NKS) rc[kk] = lds_read16((kk & 1) ? vo : ve, TV::kBlkBytes + kk * 32);
+        else rd[kk] = lds_read16((kk & 1) ? vo : ve, TV::BYTES + TV::kBlkBytes + kk * 32);
+      }
+      if (m == FS) {
+        if (NS < 6) mfma_settle();
+        landed(sE, sDF);
+      }
+      if (m >= FS) {
+#pragma unroll
+        TVM_SHARE(e, m - FS, 8, NS - FS) pw2(gz0, gzt0, e);
+      }
+    }
+    // ---- E(1), with P, N of block 1
+#pragma unroll
+    for (int m = 0; m < NS; ++m) {
+      e_product(m);
+#pragma unroll
+      TVM_SHARE(x, m, 4 * NDB, NS) {  // transposed K, tK of block 0
+        const int cc = (x >> 1) / NDB, db = (x >> 1) % NDB;
+        if ((x & 1) == 0) kT[cc][db] = lds_read_tr(tl, th, cc * 16 * TK::PCH * 16 + db * 64);
+        else tkT[cc][db] = lds_read_tr(tl, th, OFF_TK + cc * 16 * TK::PCH * 16 + db * 64);
+      }
+      if (m == FS) {
+        if (NS < 6) mfma_settle();
+        landed(sS, sT);
+      }
+      if (m >= FS) {
+#pragma unroll
+        TVM_SHARE(e, m - FS, 16, NS - FS) pw1(1, e);
+      }
+    }
+    // ---- O(0), with gZ, gZt of block 1
+#pragma unroll
+    for (int m = 0; m < NO; ++m) {
+      o_product(m, kT, tkT, gz0, gzt0);
+#pragma unroll
+      TVM_SHARE(x, m, 4 * NDB, NO) {  // transposed K, tK of block 1
+        const int cc = (x >> 1) / NDB, db = (x >> 1) % NDB;
+        if ((x & 1) == 0) kT1[cc][db] = lds_read_tr(tl, th, (2 + cc) * 16 * TK::PCH * 16 + db * 64);
+        else tkT1[cc][db] = lds_read_tr(tl, th, OFF_TK + (2 + cc) * 16 * TK::PCH * 16 + db * 64);
+      }
+      if (m == FO) landed(sE, sDF);
+      if (m >= FO) {
+#pragma unroll
+        TVM_SHARE(e, m - FO, 8, NO - FO) pw2(gz1, gzt1, e);
+      }
+    }
+    // every read of this stage has been issued; the next tile must have landed before anyone goes on
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    dma_wait();
+    __syncthreads();
+    // ---- O(1)
+#pragma unroll
+    for (int m = 0; m < NO; ++m) {
+      o_product(m, kT1, tkT1, gz1, gzt1);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NKS, NO) {  // S-fragments of the next tile's block 0
+        const int kk = x % NKS;
+        if (x < NKS) ra[kk] = lds_read16((kk & 1) ? nko : nke, kk * 32);
+        else rb[kk] = lds_read16((kk & 1) ? nko : nke, OFF_TK + kk * 32);
+      }
+#pragma unroll
+      TVM_SHARE(x, m, NDMA_A, NO) dma(x, jn2, sb);
+    }
+#undef TVM_SHARE
+  };
+
+  // the row scalars are first used inside the tile: make the compiler wait for their loads here,
+  // not in the loop (where its wait would also cover the tile loads in flight)
+  asm volatile("" ::"v"(lse2), "v"(mub), "v"(ds), "v"(s1));
+  const int nfull = s.N >> 6;  // tiles without keys beyond N
+  for (int t = 0; t < nfull; ++t)
+    tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, jlast),
+         min((t + 2) * 64, jlast));
+  if (nt > nfull)
+    tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, jlast, jlast);
+  dma_wait();      // the last tiles' loads (re-fetches of the last tile, unused) must not outlive the workgroup
+  mfma_settle();   // the last output products have landed before the accumulators are read
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    landed_acc(aQ[db]);
+    landed_acc(aTQ[db]);
+  }
+  if (!iok) return;
+  const long long ro = base + (long long)i * s.sn;
+  store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
+  store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+}
+
+template <int DK, int DV>
+hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const int nfb = (s.N + kFix - 1) / kFix;
+  hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
+                     (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,
+                     a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Head dims up to 96.
+hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  switch ((s.D + 15) / 16 * 16) {
+    case 16: return launch<16, 32>(s, a, st);
+    case 32: return launch<32, 32>(s, a, st);
+    case 48: return launch<48, 64>(s, a, st);
+    case 64: return launch<64, 64>(s, a, st);
+    case 80: return launch<80, 96>(s, a, st);
+    case 96: return launch<96, 96>(s, a, st);
+    default: return hipErrorNotSupported;
+  }
+}
+
+}  // namespace tvm

@@ -32,6 +32,39 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// The same product with the register file of every operand spelled out, for kernels whose
+// instruction order is laid out by hand (their translation unit is built with the machine
+// scheduler off, so source order is issue order).  The compiler treats these as ordinary
+// instructions: it knows neither that the result lands some 40-50 cycles after issue nor that a
+// VALU read before then would see stale data.  The caller keeps at least four further
+// matrix-core products (or mfma_settle) between a product and the first non-matrix read of its
+// result; feeding the result to the next product as C needs no distance.
+//   mfma_acc : accumulator in AGPRs, both operands in VGPRs        (output products)
+//   mfma_fix : result in VGPRs, B = a fixed-side fragment in AGPRs  (score-type products)
+//   mfma_fix0: the same with C = 0 (starts a tile)
+// PAD puts two idle issue slots in front of the product: a matrix-core instruction must not read a
+// register that a VALU instruction (a register copy the compiler placed there, say) wrote in
+// one of the two slots before it.
+#define TVM_MFMA_PAD "s_nop 1\n\t"
+template <bool PAD = false>
+__device__ __forceinline__ void mfma_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+  if (PAD) asm volatile(TVM_MFMA_PAD "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+template <bool PAD = false>
+__device__ __forceinline__ void mfma_fix(f32x16& sc, bf16x8 a, bf16x8 fixed_b) {
+  if (PAD) asm volatile(TVM_MFMA_PAD "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(sc) : "v"(a), "a"(fixed_b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(sc) : "v"(a), "a"(fixed_b));
+}
+template <bool PAD = false>
+__device__ __forceinline__ void mfma_fix0(f32x16& sc, bf16x8 a, bf16x8 fixed_b) {
+  if (PAD) asm volatile(TVM_MFMA_PAD "v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sc) : "v"(a), "a"(fixed_b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sc) : "v"(a), "a"(fixed_b));
+}
+#undef TVM_MFMA_PAD
+// Idles long enough for every product issued so far to have written its result.
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 // Row (M index) held in register r of a D tile by a lane of half hh.
 __device__ __forceinline__ int drow(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
 

@@ -55,5 +55,6 @@ bool mfma_supported(const Shape& s, int dtype);
 hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96
 
 }  // namespace tvm

@@ -1,0 +1,94 @@
+"""Static check of the hand-scheduled kernels' instruction streams (no GPU needed).
+
+The hand-scheduled translation units issue their matrix-core products from inline assembly, which
+the compiler's hazard recognizer does not look into.  One hazard is therefore ours to keep out: a
+matrix-core instruction must not read a register that a VALU instruction wrote in one of the
+two issue slots before it (the hardware does not interlock that case; s_nop N fills N+1 slots).
+The compiler is free to put register copies right in front of an inline-assembly statement, so
+this is checked on the generated assembly of every instantiation rather than argued from the
+source.
+"""
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+from paper_2511_19797_amd import build
+
+CSRC = os.path.join(os.path.dirname(build.__file__), "csrc")
+HAND_SCHEDULED = ["bwd_row_pipe.hip"]
+
+REG = re.compile(r"\b([va])(?:(\d+)|\[(\d+):(\d+)\])")
+
+
+def regs(operand):
+    out = set()
+    for m in REG.finditer(operand):
+        f = m.group(1)
+        if m.group(2) is not None:
+            out.add((f, int(m.group(2))))
+        else:
+            out.update((f, i) for i in range(int(m.group(3)), int(m.group(4)) + 1))
+    return out
+
+
+def instructions(asm_text):
+    """(mnemonic, [operands]) of every instruction, in file order (labels, directives, comments dropped)."""
+    for line in asm_text.splitlines():
+        t = line.split(";")[0].strip()
+        if not t or t.startswith(".") or t.endswith(":") or t.startswith("//"):
+            continue
+        parts = t.split(None, 1)
+        ops = [o.strip() for o in parts[1].split(",")] if len(parts) > 1 else []
+        yield parts[0], ops
+
+
+def violations(asm_text):
+    ins = list(instructions(asm_text))
+    bad = []
+    for i, (op, ops) in enumerate(ins):
+        if not op.startswith("v_mfma"):
+            continue
+        srcs = set().union(*[regs(o) for o in ops[1:]])
+        slots = 0
+        j = i - 1
+        while j >= 0 and slots < 2:
+            pop, pops = ins[j]
+            if pop == "s_nop":
+                slots += int(pops[0], 0) + 1
+            else:
+                is_valu = pop.startswith("v_") and not pop.startswith("v_mfma")
+                if is_valu and pops and regs(pops[0]) & srcs:
+                    bad.append((i, " ".join([pop] + pops), " ".join([op] + ops)))
+                slots += 1
+            j -= 1
+    return bad
+
+
+def test_parser_flags_a_planted_hazard():
+    planted = """
+    v_accvgpr_write_b32 a4, v9
+    s_mov_b32 s0, 1
+    v_mfma_f32_32x32x16_bf16 v[0:15], v[20:23], a[4:7], v[0:15]
+    """
+    assert len(violations(planted)) == 1
+    padded = planted.replace("s_mov_b32 s0, 1", "s_nop 1")
+    assert violations(padded) == []
+    far = planted.replace("s_mov_b32 s0, 1", "s_mov_b32 s0, 1\n v_add_u32 v100, v101, v102")
+    assert violations(far) == []
+
+
+@pytest.mark.parametrize("name", HAND_SCHEDULED)
+def test_no_valu_write_feeds_next_matrix_instruction(name):
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, name + ".s")
+        cmd = ["hipcc", *build.COMMON, *build.PER_FILE.get(name, []), "--cuda-device-only", "-S",
+               os.path.join(CSRC, name), "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        text = open(out).read()
+    assert text.count("v_mfma") > 100, "expected the matrix-core kernels in the assembly"
+    bad = violations(text)
+    assert not bad, f"{len(bad)} VALU->MFMA hazards, first: {bad[:3]}"
