@@ -20,6 +20,7 @@ PER_FILE = {
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],
+    "bwd_col_pipe.hip": ["-mllvm", "-enable-misched=false"],
 }
 
 

@@ -1,0 +1,360 @@
+// Key-side backward kernel (dK, dtK, dV, dtV; Steps 2, 4, 6 of App. C plus the ordinary-attention
+// terms of gO) for head dims up to 96, with the instruction stream laid out by hand.  Same
+// mathematics and data layout as the generic-order kernel in bwd_mfma_kernels.h.
+//
+// A wave owns 32 keys (their K, tK, V, tV fragments stay in registers, four accumulators in
+// AGPRs) and runs alone on its SIMD, so its VALU work, LDS reads and load issue are hidden only
+// if they sit between its own matrix-core products.  Queries are streamed in tiles of 64 = two
+// blocks of 32.  The output products of a block split by the contraction half cc (16 queries
+// each), which is what lets the pointwise work trail the products by half a block:
+//
+//   phase     products (matrix cores)            in their shadow
+//   S         S, St                              G, tG rows and lse, stats of the block <- LDS
+//   E         E, DF                              P, N, Pd of half 0;  G^T, tG^T of half 0 <- LDS;  dsig, sig1 <- LDS
+//   OV(0)     dV, dtV += (P, Pd of half 0) .     P, N, Pd of half 1;  G^T, tG^T of half 1 <- LDS
+//   OV(1)     dV, dtV += (P, Pd of half 1) .     gZ, gZt of half 0;   Q^T, tQ^T of half 0 <- LDS
+//   OK(0)     dK, dtK += (gZ, gZt of half 0) .   gZ, gZt of half 1;   Q^T, tQ^T of half 1 <- LDS
+//   -- after the tile's second block: all reads of this buffer are done; wait for the next tile, barrier --
+//   OK(1)     dK, dtK += (gZ, gZt of half 1) .   Q, tQ rows of the next block <- LDS;  tile loads
+//
+// The translation unit is built with the machine scheduler off: source order is issue order.
+#include "pipe_ops.h"
+
+#include <type_traits>
+
+namespace tvm {
+namespace {
+
+constexpr int kFix = 128;  // keys per workgroup (4 waves x 32)
+constexpr int kNT = 256;
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+__device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
+  typedef const f32x4 __attribute__((address_space(3))) * lp;
+  return *(lp)(uintptr_t)(addr + (unsigned)imm);
+}
+__device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
+
+template <int DK, int DV>
+__global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
+    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
+    const float* __restrict__ lse2w, const float* __restrict__ stats, const bf16* __restrict__ gO,
+    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
+    bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
+  using TX = Tile<64, DV / 8, kNT / 64>;  // Q, tQ, G, tG: read both ways
+  constexpr int OFF_TQ = TX::BYTES, OFF_G = 2 * TX::BYTES, OFF_TG = 3 * TX::BYTES, OFF_ROW = 4 * TX::BYTES;
+  constexpr int BUF = 4 * TX::BYTES + 4 * 256;  // one stage: four tiles and four float32 row vectors (64 each)
+  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
+  constexpr int NKS = DK / 16, NDB = DV / 32;
+  constexpr int NS = 3 * NKS;                      // products of a score-type phase
+  constexpr int NH = 3 * NDB;                      // products of half an output phase
+  constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
+  constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
+  constexpr int NDMA_A = NDMA / 2;                 // of which issued in the last OK(1), the rest in the next S
+  // register files: the accumulators fill 4*NDB*16 AGPRs; K, tK fragments always fit beside them,
+  // V and tV fragments where there is room, else they stay in VGPRs
+  constexpr bool V_IN_A = 64 * NDB + 12 * NKS <= 256, TV_IN_A = 64 * NDB + 16 * NKS <= 256;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int nfb = (s.N + kFix - 1) / kFix;
+  const int wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = wg / nfb, fb = wg - bh * nfb;
+  const int b = bh / s.H, h = bh - b * s.H;
+  const long long base = b * s.sb + h * s.sh;
+  const long long rbase = (long long)bh * s.N;
+  const int j = fb * kFix + wave * 32 + ic;  // this lane's key
+  const bool jok = j < s.N;
+
+  const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
+  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned lds0 = lds_addr_of(lds);
+  // wave w also fetches row vector w (lse in log2 units, stats, dsig, sig1) of the tile, one float per
+  // lane (lanes past the last row re-read the last row's value: masked rows, unused)
+  const float* const rowsrc = (wave == 0 ? lse2w : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
+  // wave-load number x (compile-time) of the tile whose first query is i0 (< N), into the stage at `buf`
+  auto dma = [&](int x, int i0, unsigned buf) {
+    const long long ro = base + (long long)i0 * s.sn;
+    const int left = s.N - i0;
+    if (x < TX::IPW) TX::issue_one(lx, x, q + ro, pitch, left, buf, wave);
+    else if (x < 2 * TX::IPW) TX::issue_one(lx, x - TX::IPW, tq + ro, pitch, left, buf + OFF_TQ, wave);
+    else if (x < 3 * TX::IPW) TX::issue_one(lx, x - 2 * TX::IPW, gO + ro, pitch, left, buf + OFF_G, wave);
+    else if (x < 4 * TX::IPW) TX::issue_one(lx, x - 3 * TX::IPW, gTO + ro, pitch, left, buf + OFF_TG, wave);
+    else dma_to_lds<4>(rowsrc + i0, (unsigned)min(lane, left - 1) * 4u, buf + OFF_ROW + wave * 256);
+  };
+  const typename TX::RAddr ra = TX::raddr(ic, hh);
+  const typename TX::TAddr ta = TX::taddr(ic, hh);
+#pragma unroll
+  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
+
+  bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
+  gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
+  f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    aK[db] = zero16();
+    aTK[db] = zero16();
+    aV[db] = zero16();
+    aTV[db] = zero16();
+  }
+  // wave-uniform scalars for the assembly blocks (SGPR operands)
+  const float c1u = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha * 1.4426950408889634f)));
+  const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
+  const int nt = (s.N + 63) >> 6;   // tiles
+  const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
+
+  dma_wait();
+  __syncthreads();  // tile 0 has landed
+#pragma unroll
+  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, ilast), lds0 + BUF);
+  bf16x8 rq[NKS], rtq[NKS];  // Q, tQ rows of the block whose S phase comes next
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    rq[kk] = lds_read16(lds0 + ((kk & 1) ? ra.o : ra.e), kk * 32);
+    rtq[kk] = lds_read16(lds0 + ((kk & 1) ? ra.o : ra.e), OFF_TQ + kk * 32);
+  }
+
+  // One tile.  RAG: queries beyond N exist in this tile (only ever the last one).
+  //   sb / sbn: LDS address of this tile's stage / of the other one;  i0: first query;
+  //   in1 / in2: first query of the next tile / of the one after it (clamped to the last tile).
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, int i0, int in1, int in2) {
+    constexpr bool RAG = decltype(rag)::value;
+    const unsigned re = sb + ra.e, ro = sb + ra.o;        // rows of Q; tQ, G, tG at + OFF_*
+    const unsigned tl = sb + ta.lo, th = sb + ta.hi;      // transposed
+    const unsigned rv = sb + OFF_ROW + 16 * hh;           // row vectors: this half's four rows of each group of eight
+    const unsigned nre = sbn + ra.e, nro = sbn + ra.o;    // the next tile's rows of Q
+#define TVM_SHARE(x, m, CNT, N) for (int x = (m) * (CNT) / (N); x < ((m) + 1) * (CNT) / (N); ++x)
+
+    auto block = [&](auto ibc) {
+      constexpr int ib = decltype(ibc)::value;
+      bf16x8 rg[NKS], rtg[NKS];
+      f32x16 sS, sT, sE, sDF;
+      f32x4 la[4], ma[4], da[4], sa[4];  // row scalars of the block's queries, by group of eight
+      float pp[16], nn[16];
+      unsigned pk[8], pdk[8], gz[8], gzt[8];
+      bf16x8 xT[NDB], txT[NDB], yT[NDB], tyT[NDB];  // transposed fragments of the half in use / of the next half
+
+      // P, N, Pd of elements 2e, 2e+1
+      auto pw1 = [&](int e) {
+        const int g4 = e >> 1, t = (2 * e) & 3;
+        float s0 = sS[2 * e], s1 = sS[2 * e + 1];
+        if (RAG) {  // queries beyond N: probability 0
+          if (i0 + ib * 32 + drow(2 * e, hh) >= s.N) s0 = -INFINITY;
+          if (i0 + ib * 32 + drow(2 * e + 1, hh) >= s.N) s1 = -INFINITY;
+        }
+        pw1_pair_asm(pp[2 * e], pp[2 * e + 1], nn[2 * e], nn[2 * e + 1], pk[e], pdk[e], s0, s1, sT[2 * e],
+                     sT[2 * e + 1], c1u, f4(la[g4], t), f4(la[g4], t + 1), alphau, f4(ma[g4], t), f4(ma[g4], t + 1));
+      };
+      // gZ, gZt of elements 2e, 2e+1: sig1 and dsig differ per element here, so one element at a time
+      auto pw2 = [&](int e) {
+        const int g4 = e >> 1, t = (2 * e) & 3;
+        pw2_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1],
+                     nn[2 * e], nn[2 * e + 1], f4(sa[g4], t), f4(sa[g4], t + 1), f4(da[g4], t), f4(da[g4], t + 1));
+      };
+      auto tr_imm = [&](int cc, int db) { return (2 * ib + cc) * 16 * TX::PCH * 16 + db * 64; };
+
+      // ---- S
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int kk = m / 3, w = m - 3 * kk;
+        if (w == 0) {
+          if (kk == 0) mfma_fix0<RAG>(sS, rq[0], kf[0]);
+          else mfma_fix<RAG>(sS, rq[kk], kf[kk]);
+        } else if (w == 1) {
+          if (kk == 0) mfma_fix0<RAG>(sT, rtq[0], kf[0]);
+          else mfma_fix<RAG>(sT, rtq[kk], kf[kk]);
+        } else {
+          mfma_fix<RAG>(sT, rq[kk], tkf[kk]);
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NKS, NS) {
+          const int k2 = x % NKS;
+          if (x < NKS) rg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_G + ib * TX::kBlkBytes + k2 * 32);
+          else rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + ib * TX::kBlkBytes + k2 * 32);
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 4, NS) {  // lse, stats of half 0
+          if (x < 2) la[x] = lds_read_f4(rv, ib * 128 + x * 32);
+          else ma[x - 2] = lds_read_f4(rv, 256 + ib * 128 + (x - 2) * 32);
+        }
+        if (ib == 0) {
+#pragma unroll
+          TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, in1, sbn);
+        }
+      }
+      // ---- E, with P, N, Pd of half 0
+#pragma unroll
+      for (int m = 0; m < NS; ++m) {
+        const int kk = m / 3, w = m - 3 * kk;
+        if (w == 0) {
+          if (kk == 0) { if (V_IN_A) mfma_fix0<RAG>(sE, rtg[0], vf[0]); else mfma_vv0<RAG>(sE, rtg[0], vf[0]); }
+          else { if (V_IN_A) mfma_fix<RAG>(sE, rtg[kk], vf[kk]); else mfma_vv<RAG>(sE, rtg[kk], vf[kk]); }
+        } else if (w == 1) {
+          if (kk == 0) { if (V_IN_A) mfma_fix0<RAG>(sDF, rg[0], vf[0]); else mfma_vv0<RAG>(sDF, rg[0], vf[0]); }
+          else { if (V_IN_A) mfma_fix<RAG>(sDF, rg[kk], vf[kk]); else mfma_vv<RAG>(sDF, rg[kk], vf[kk]); }
+        } else {
+          if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]); else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NDB, NS) {  // G^T, tG^T of half 0
+          const int db = x >> 1;
+          if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, OFF_G + tr_imm(0, db));
+          else txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 4, NS) {  // lse, stats of half 1
+          if (x < 2) la[2 + x] = lds_read_f4(rv, ib * 128 + (2 + x) * 32);
+          else ma[x] = lds_read_f4(rv, 256 + ib * 128 + x * 32);
+        }
+        if (m == FS) {
+          if (NS < 6) mfma_settle();
+          landed(sS, sT);
+        }
+        if (m >= FS) {
+#pragma unroll
+          TVM_SHARE(e, m - FS, 4, NS - FS) pw1(e);
+        }
+      }
+      // ---- OV(0), with P, N, Pd of half 1
+#pragma unroll
+      for (int m = 0; m < NH; ++m) {
+        const int db = m / 3, w = m - 3 * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], xT[db], frag_of(pk, 0)); else mfma_acc<RAG>(aV[db], xT[db], frag_of(pk, 0)); }
+        else if (w == 1) mfma_acc<RAG>(aV[db], txT[db], frag_of(pdk, 0));
+        else mfma_acc<RAG>(aTV[db], txT[db], frag_of(pk, 0));
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NDB, NH) {  // G^T, tG^T of half 1
+          const int d2 = x >> 1;
+          if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
+          else tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 4, NH) {  // sig1, dsig of half 0
+          if (x < 2) sa[x] = lds_read_f4(rv, 768 + ib * 128 + x * 32);
+          else da[x - 2] = lds_read_f4(rv, 512 + ib * 128 + (x - 2) * 32);
+        }
+#pragma unroll
+        TVM_SHARE(e, m, 4, NH) pw1(4 + e);
+      }
+      // ---- OV(1), with gZ, gZt of half 0
+#pragma unroll
+      for (int m = 0; m < NH; ++m) {
+        const int db = m / 3, w = m - 3 * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], yT[db], frag_of(pk, 1)); else mfma_acc<RAG>(aV[db], yT[db], frag_of(pk, 1)); }
+        else if (w == 1) mfma_acc<RAG>(aV[db], tyT[db], frag_of(pdk, 1));
+        else mfma_acc<RAG>(aTV[db], tyT[db], frag_of(pk, 1));
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 0
+          const int d2 = x >> 1;
+          if ((x & 1) == 0) xT[d2] = lds_read_tr(tl, th, tr_imm(0, d2));
+          else txT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(0, d2));
+        }
+#pragma unroll
+        TVM_SHARE(x, m, 4, NH) {  // sig1, dsig of half 1
+          if (x < 2) sa[2 + x] = lds_read_f4(rv, 768 + ib * 128 + (2 + x) * 32);
+          else da[x] = lds_read_f4(rv, 512 + ib * 128 + x * 32);
+        }
+        if (m == 0) landed(sE, sDF);  // at least four products after the last one of E
+#pragma unroll
+        TVM_SHARE(e, m, 4, NH) pw2(e);
+      }
+      // ---- OK(0), with gZ, gZt of half 1
+#pragma unroll
+      for (int m = 0; m < NH; ++m) {
+        const int db = m / 3, w = m - 3 * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aK[db], xT[db], frag_of(gz, 0)); else mfma_acc<RAG>(aK[db], xT[db], frag_of(gz, 0)); }
+        else if (w == 1) mfma_acc<RAG>(aK[db], txT[db], frag_of(gzt, 0));
+        else mfma_acc<RAG>(aTK[db], xT[db], frag_of(gzt, 0));
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 1
+          const int d2 = x >> 1;
+          if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, tr_imm(1, d2));
+          else tyT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(1, d2));
+        }
+#pragma unroll
+        TVM_SHARE(e, m, 4, NH) pw2(4 + e);
+      }
+      if (ib == 1) {
+        // every read of this stage has been issued; the next tile must have landed before anyone goes on
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        dma_wait();
+        __syncthreads();
+      }
+      // ---- OK(1)
+#pragma unroll
+      for (int m = 0; m < NH; ++m) {
+        const int db = m / 3, w = m - 3 * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aK[db], yT[db], frag_of(gz, 1)); else mfma_acc<RAG>(aK[db], yT[db], frag_of(gz, 1)); }
+        else if (w == 1) mfma_acc<RAG>(aK[db], tyT[db], frag_of(gzt, 1));
+        else mfma_acc<RAG>(aTK[db], yT[db], frag_of(gzt, 1));
+#pragma unroll
+        TVM_SHARE(x, m, 2 * NKS, NH) {  // Q, tQ rows of the next block
+          const int k2 = x % NKS;
+          const unsigned a0 = ib == 0 ? ((k2 & 1) ? ro : re) : ((k2 & 1) ? nro : nre);
+          const int blk = ib == 0 ? TX::kBlkBytes : 0;
+          if (x < NKS) rq[k2] = lds_read16(a0, blk + k2 * 32);
+          else rtq[k2] = lds_read16(a0, OFF_TQ + blk + k2 * 32);
+        }
+        if (ib == 1) {
+#pragma unroll
+          TVM_SHARE(x, m, NDMA_A, NH) dma(x, in2, sb);
+        }
+      }
+    };
+    block(std::integral_constant<int, 0>{});
+    block(std::integral_constant<int, 1>{});
+#undef TVM_SHARE
+  };
+
+  const int nfull = s.N >> 6;  // tiles without queries beyond N
+  for (int t = 0; t < nfull; ++t)
+    tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, ilast),
+         min((t + 2) * 64, ilast));
+  if (nt > nfull)
+    tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, ilast, ilast);
+  dma_wait();      // the last tiles' loads (re-fetches of the last tile, unused) must not outlive the workgroup
+  mfma_settle();   // the last output products have landed before the accumulators are read
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) {
+    landed_acc(aK[db]);
+    landed_acc(aTK[db]);
+    landed_acc(aV[db]);
+    landed_acc(aTV[db]);
+  }
+  if (!jok) return;
+  const long long ro = base + (long long)j * s.sn;
+  store_acc<NDB>(dk + ro, aK, s.alpha, s.D, hh);
+  store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
+  store_acc<NDB>(dv + ro, aV, 1.f, s.D, hh);
+  store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
+}
+
+template <int DK, int DV>
+hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  const int nfb = (s.N + kFix - 1) / kFix;
+  hipLaunchKernelGGL((bwd_col_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
+                     a.lse2, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
+                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Head dims up to 96.  Needs the row vectors the hand-scheduled query-side kernel leaves in the
+// workspace (dsig, sig1 and lse in log2 units).
+hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  switch ((s.D + 15) / 16 * 16) {
+    case 16: return launch<16, 32>(s, a, st);
+    case 32: return launch<32, 32>(s, a, st);
+    case 48: return launch<48, 64>(s, a, st);
+    case 64: return launch<64, 64>(s, a, st);
+    case 80: return launch<80, 96>(s, a, st);
+    case 96: return launch<96, 96>(s, a, st);
+    default: return hipErrorNotSupported;
+  }
+}
+
+}  // namespace tvm

@@ -24,7 +24,8 @@ bool mfma_supported(const Shape& s, int dtype) {
   }
 
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  TVM_DISPATCH_D(launch_col, launch_bwd_col_mfma_wide)
+  if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);  // hand-scheduled variant (bwd_col_pipe.hip)
+  return launch_bwd_col_mfma_wide(s, a, st);
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);  // hand-scheduled variant (bwd_row_pipe.hip)

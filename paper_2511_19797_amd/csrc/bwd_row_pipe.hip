@@ -19,7 +19,7 @@
 //   O(1)         dQ, dtQ += (gZ, gZt of block 1) .    S-fragments of tile t+1 <- LDS; loads of tile t+2, 1st half
 //
 // The translation unit is built with the machine scheduler off: source order is issue order.
-#include "mfma_tiles.h"
+#include "pipe_ops.h"
 
 #include <type_traits>
 
@@ -30,59 +30,37 @@ constexpr int kFix = 128;  // queries per workgroup (4 waves x 32)
 constexpr int kNT = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-
-__device__ __forceinline__ bf16x8 lds_read16(unsigned addr, int imm) {
-  typedef const bf16x8 __attribute__((address_space(3))) * lp;
-  return *(lp)(uintptr_t)(addr + (unsigned)imm);
-}
-__device__ __forceinline__ bf16x8 lds_read_tr(unsigned lo, unsigned hi, int imm) {
-  typedef bf16x4 __attribute__((address_space(3))) * lp;
-  const bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(uintptr_t)(lo + (unsigned)imm));
-  const bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(uintptr_t)(hi + (unsigned)imm));
-  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-// The pointwise work is inline assembly too, so that it stays in the slot it is written in (the
-// optimizer moves plain arithmetic freely between the matrix-core instructions otherwise).
-//   P = exp2(S c1 - lse2),  N = St alpha - mub
-__device__ __forceinline__ void pw1_asm(float& p, float& n, float sv, float st, float c1, float lse2, float alpha,
-                                        float mub) {
-  float t;
-  asm volatile(
-      "v_fma_f32 %2, %3, %5, -%6\n\t"
-      "v_fma_f32 %1, %4, %7, -%8\n\t"
-      "v_exp_f32 %0, %2"
-      : "=v"(p), "=v"(n), "=&v"(t)
-      : "v"(sv), "v"(st), "s"(c1), "v"(lse2), "s"(alpha), "v"(mub));
-}
-//   gZt = P (E - sig1),  gZ = P (DF - dsig) + gZt N, for two neighbouring elements, rounded to bf16 and packed
-__device__ __forceinline__ void pw2_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1, float p0,
-                                        float p1, float n0, float n1, float s1, float ds) {
-  float t0, t1, w0, w1;
-  asm volatile(
-      "v_sub_f32 %2, %6, %14\n\t"
-      "v_sub_f32 %3, %7, %14\n\t"
-      "v_sub_f32 %4, %8, %15\n\t"
-      "v_sub_f32 %5, %9, %15\n\t"
-      "v_mul_f32 %2, %10, %2\n\t"
-      "v_mul_f32 %3, %11, %3\n\t"
-      "v_mul_f32 %4, %10, %4\n\t"
-      "v_mul_f32 %5, %11, %5\n\t"
-      "v_fmac_f32 %4, %2, %12\n\t"
-      "v_fmac_f32 %5, %3, %13\n\t"
-      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
-      "v_cvt_pk_bf16_f32 %1, %2, %3"
-      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
-      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1), "v"(s1), "v"(ds));
-}
-// From here on the compiler may read the tiles: every use below this point depends on it.  Placed
-// after enough further products that the ones writing the tiles have finished.
-__device__ __forceinline__ void landed(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
-__device__ __forceinline__ void landed_acc(f32x16& a) { asm volatile("" : "+a"(a)); }
-__device__ __forceinline__ bf16x8 frag_of(const unsigned (&w)[8], int cc) {
-  const uint4 v = make_uint4(w[4 * cc], w[4 * cc + 1], w[4 * cc + 2], w[4 * cc + 3]);
-  return __builtin_bit_cast(bf16x8, v);
-}
+// Optional cycle stamps per phase (build with -DTVM_PROFILE; read back with tvmattn_debug_read_prof_pipe).
+#if defined(TVM_PROFILE)
+__device__ long long g_prof_pipe[16];
+#define PROF_ENTRY const long long pe_ = clock64(); long long pp_[16]
+#define PROF_P(i) pp_[i] = clock64() - pe_
+#define PROF_DECL long long pt_ = clock64(), pa_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; const long long pl_ = pt_
+#define PROF(i)                        \
+  do {                                 \
+    const long long n_ = clock64();    \
+    pa_[i] += n_ - pt_;                \
+    pt_ = n_;                          \
+  } while (0)
+#define PROF_DUMP                                  \
+  const long long px_ = clock64();                 \
+  if (blockIdx.x == 3 && threadIdx.x == 0)         \
+    for (int i_ = 0; i_ < 8; ++i_) g_prof_pipe[i_] = pa_[i_]
+#define PROF_EXIT                                                      \
+  if (blockIdx.x == 3 && threadIdx.x == 0) {                           \
+    g_prof_pipe[8] = pl_ - pe_;                                        \
+    g_prof_pipe[9] = px_ - pl_;                                        \
+    g_prof_pipe[10] = clock64() - px_;                                 \
+    for (int i_ = 11; i_ < 16; ++i_) g_prof_pipe[i_] = pp_[i_];        \
+  }
+#else
+#define PROF_ENTRY
+#define PROF_P(i)
+#define PROF_DECL
+#define PROF(i)
+#define PROF_DUMP
+#define PROF_EXIT
+#endif
 
 template <int DK, int DV>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
@@ -90,7 +68,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const bf16* __restrict__ o, const bf16* __restrict__ to, const float* __restrict__ lse,
     const float* __restrict__ stats, const bf16* __restrict__ gO, const bf16* __restrict__ gTO,
-    float* __restrict__ dsig, float* __restrict__ sig1, bf16* __restrict__ dq, bf16* __restrict__ dtq) {
+    float* __restrict__ dsig, float* __restrict__ sig1, float* __restrict__ lse2w, bf16* __restrict__ dq,
+    bf16* __restrict__ dtq) {
   using TK = Tile<64, DV / 8, kNT / 64>;  // K, tK: read both ways
   using TV = Tile<64, DK / 8, kNT / 64>;  // V, tV: score-type products only
   constexpr int OFF_TK = TK::BYTES, OFF_V = 2 * TK::BYTES, OFF_TV = 2 * TK::BYTES + TV::BYTES;
@@ -103,6 +82,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   constexpr int FO = 4;                               // ... of an output phase (NO >= 6)
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
   constexpr int NDMA_A = NDMA / 2;                    // of which issued in O(1), the rest in the next S(0)
+  PROF_ENTRY;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
@@ -130,6 +110,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const typename TK::TAddr ta = TK::taddr(ic, hh);
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
+  PROF_P(11);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
@@ -153,9 +134,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         ds = fmaf(gte, (float)tof[kk][e], ds);
         s1 = fmaf(gte, oe, s1);
       }
+    PROF_P(12);
     ds += xhalf(ds);
     s1 += xhalf(s1);
   }
+  PROF_P(13);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.N + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
@@ -163,6 +146,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   if (iok && hh == 0) {
     dsig[r] = ds;
     sig1[r] = s1;
+    lse2w[r] = lse2;
   }
   f32x16 aQ[NDB], aTQ[NDB];
 #pragma unroll
@@ -176,8 +160,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const int nt = (s.N + 63) >> 6;      // tiles
   const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
 
+  PROF_P(14);
   dma_wait();
   __syncthreads();  // tile 0 has landed
+  PROF_P(15);
 #pragma unroll
   for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, jlast), lds0 + BUF);
   bf16x8 ra[NKS], rb[NKS];  // S-fragments (K, tK rows) of the block whose S phase comes next
@@ -187,6 +173,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     rb[kk] = lds_read16(lds0 + ((kk & 1) ? rk.o : rk.e), OFF_TK + kk * 32);
   }
 
+  PROF_DECL;
   // One tile.  RAG: keys beyond N exist in this tile (only ever the last one).
   //   sb / sbn: LDS address of this tile's stage / of the other one;  j0: first key;
   //   jn1 / jn2: first key of the next tile / of the one after it (clamped to the last tile).
@@ -247,6 +234,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     // share [m*CNT/N, (m+1)*CNT/N) of CNT side instructions goes after the m-th of N products
 #define TVM_SHARE(x, m, CNT, N) for (int x = (m) * (CNT) / (N); x < ((m) + 1) * (CNT) / (N); ++x)
 
+    PROF(7);
     // ---- S(0)
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
@@ -260,6 +248,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
       TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, jn1, sbn);
     }
+    PROF(0);
     // ---- E(0), with P, N of block 0
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
@@ -279,6 +268,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         TVM_SHARE(e, m - FS, 16, NS - FS) pw1(0, e);
       }
     }
+    PROF(1);
     // ---- S(1), with gZ, gZt of block 0
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
@@ -298,6 +288,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         TVM_SHARE(e, m - FS, 8, NS - FS) pw2(gz0, gzt0, e);
       }
     }
+    PROF(2);
     // ---- E(1), with P, N of block 1
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
@@ -317,6 +308,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         TVM_SHARE(e, m - FS, 16, NS - FS) pw1(1, e);
       }
     }
+    PROF(3);
     // ---- O(0), with gZ, gZt of block 1
 #pragma unroll
     for (int m = 0; m < NO; ++m) {
@@ -333,10 +325,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         TVM_SHARE(e, m - FO, 8, NO - FO) pw2(gz1, gzt1, e);
       }
     }
+    PROF(4);
     // every read of this stage has been issued; the next tile must have landed before anyone goes on
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     dma_wait();
     __syncthreads();
+    PROF(5);
     // ---- O(1)
 #pragma unroll
     for (int m = 0; m < NO; ++m) {
@@ -351,6 +345,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       TVM_SHARE(x, m, NDMA_A, NO) dma(x, jn2, sb);
     }
 #undef TVM_SHARE
+    PROF(6);
   };
 
   // the row scalars are first used inside the tile: make the compiler wait for their loads here,
@@ -362,6 +357,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
          min((t + 2) * 64, jlast));
   if (nt > nfull)
     tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, jlast, jlast);
+  PROF_DUMP;
   dma_wait();      // the last tiles' loads (re-fetches of the last tile, unused) must not outlive the workgroup
   mfma_settle();   // the last output products have landed before the accumulators are read
 #pragma unroll
@@ -369,10 +365,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     landed_acc(aQ[db]);
     landed_acc(aTQ[db]);
   }
-  if (!iok) return;
-  const long long ro = base + (long long)i * s.sn;
-  store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
-  store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+  if (iok) {
+    const long long ro = base + (long long)i * s.sn;
+    store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
+    store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+  }
+  PROF_EXIT;
 }
 
 template <int DK, int DV>
@@ -381,7 +379,7 @@ hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,
-                     a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+                     a.dsig, a.sig1, a.lse2, (bf16*)a.dq, (bf16*)a.dtq);
   return hipGetLastError();
 }
 
@@ -400,4 +398,9 @@ hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st)
   }
 }
 
+#if defined(TVM_PROFILE)
+extern "C" int tvmattn_debug_read_prof_pipe(long long* out16) {
+  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
+}
+#endif
 }  // namespace tvm

@@ -43,6 +43,7 @@ struct BwdArgs {
   void *dq, *dk, *dv, *dtq, *dtk, *dtv;
   float *dsig;  // workspace: delta + Sigma_2 per row
   float *sig1;  // workspace: Sigma_1 per row
+  float *lse2;  // workspace: lse in log2 units per row (written and read by the hand-scheduled kernels only)
 };
 
 hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipStream_t st);
@@ -56,5 +57,6 @@ hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96
+hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96, after the former
 
 }  // namespace tvm

@@ -118,10 +118,10 @@ int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, cons
 size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc) {
   tvm::Shape s;
   if (resolve(desc, &s)) return 0;
-  // two float32 row vectors (delta + Sigma_2, Sigma_1), each padded to a 256-byte multiple
+  // three float32 row vectors (delta + Sigma_2, Sigma_1, lse in log2 units), each padded to a 256-byte multiple
   const size_t rows = (size_t)s.B * s.H * s.N;
   const size_t one = (rows * sizeof(float) + 255) & ~(size_t)255;
-  return 2 * one;
+  return 3 * one;
 }
 
 int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
@@ -139,7 +139,8 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::BwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
                  static_cast<float*>(workspace),
-                 reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2)};
+                 reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 3),
+                 reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * (need / 3))};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
   hipError_t e = hipSuccess;
