@@ -55,6 +55,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   // register files: the accumulators fill 4*NDB*16 AGPRs; K, tK fragments always fit beside them,
   // V and tV fragments where there is room, else they stay in VGPRs
   constexpr bool V_IN_A = 64 * NDB + 12 * NKS <= 256, TV_IN_A = 64 * NDB + 16 * NKS <= 256;
+  PROF_ENTRY;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
@@ -63,7 +64,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const long long base = b * s.sb + h * s.sh;
   const long long rbase = (long long)bh * s.N;
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
-  const bool jok = j < s.N;
 
   const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
@@ -83,14 +83,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
   const typename TX::TAddr ta = TX::taddr(ic, hh);
+  // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
+  // barrier anyway), then the fixed-side fragments (scattered loads), then the first part of tile 1
+  // (the second stage is free from the start).
+  const int nt = (s.N + 63) >> 6;   // tiles
+  const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
-
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
   gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
+#pragma unroll
+  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, ilast), lds0 + BUF);
+  PROF_P(11);
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
@@ -102,13 +109,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   // wave-uniform scalars for the assembly blocks (SGPR operands)
   const float c1u = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha * 1.4426950408889634f)));
   const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
-  const int nt = (s.N + 63) >> 6;   // tiles
-  const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
 
+  PROF_P(14);
   dma_wait();
+  PROF_P(12);
   __syncthreads();  // tile 0 has landed
-#pragma unroll
-  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, ilast), lds0 + BUF);
+  PROF_P(15);
   bf16x8 rq[NKS], rtq[NKS];  // Q, tQ rows of the block whose S phase comes next
 #pragma unroll
   for (int kk = 0; kk < NKS; ++kk) {
@@ -116,6 +122,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     rtq[kk] = lds_read16(lds0 + ((kk & 1) ? ra.o : ra.e), OFF_TQ + kk * 32);
   }
 
+  PROF_P(13);
+  PROF_DECL;
   // One tile.  RAG: queries beyond N exist in this tile (only ever the last one).
   //   sb / sbn: LDS address of this tile's stage / of the other one;  i0: first query;
   //   in1 / in2: first query of the next tile / of the one after it (clamped to the last tile).
@@ -155,6 +163,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       };
       auto tr_imm = [&](int cc, int db) { return (2 * ib + cc) * 16 * TX::PCH * 16 + db * 64; };
 
+      PROF(7);
       // ---- S
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
@@ -184,6 +193,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, in1, sbn);
         }
       }
+      PROF(0);
       // ---- E, with P, N, Pd of half 0
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
@@ -217,6 +227,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           TVM_SHARE(e, m - FS, 4, NS - FS) pw1(e);
         }
       }
+      PROF(1);
       // ---- OV(0), with P, N, Pd of half 1
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
@@ -238,6 +249,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 #pragma unroll
         TVM_SHARE(e, m, 4, NH) pw1(4 + e);
       }
+      PROF(2);
       // ---- OV(1), with gZ, gZt of half 0
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
@@ -260,6 +272,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 #pragma unroll
         TVM_SHARE(e, m, 4, NH) pw2(e);
       }
+      PROF(3);
       // ---- OK(0), with gZ, gZt of half 1
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
@@ -276,12 +289,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 #pragma unroll
         TVM_SHARE(e, m, 4, NH) pw2(4 + e);
       }
+      PROF(4);
       if (ib == 1) {
         // every read of this stage has been issued; the next tile must have landed before anyone goes on
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         dma_wait();
         __syncthreads();
       }
+      PROF(5);
       // ---- OK(1)
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
@@ -302,19 +317,24 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           TVM_SHARE(x, m, NDMA_A, NH) dma(x, in2, sb);
         }
       }
+      PROF(6);
     };
     block(std::integral_constant<int, 0>{});
     block(std::integral_constant<int, 1>{});
 #undef TVM_SHARE
   };
 
-  const int nfull = s.N >> 6;  // tiles without queries beyond N
+  // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
+  // registers for best); tiles that do not exist are "fetched" as the last tile again.
+  const int nfull = s.N >> 6;           // tiles without queries beyond N
   for (int t = 0; t < nfull; ++t)
     tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, ilast),
          min((t + 2) * 64, ilast));
   if (nt > nfull)
     tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, ilast, ilast);
-  dma_wait();      // the last tiles' loads (re-fetches of the last tile, unused) must not outlive the workgroup
+  dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
+  __syncthreads();
+  PROF_DUMP;
   mfma_settle();   // the last output products have landed before the accumulators are read
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
@@ -323,12 +343,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     landed_acc(aV[db]);
     landed_acc(aTV[db]);
   }
-  if (!jok) return;
-  const long long ro = base + (long long)j * s.sn;
-  store_acc<NDB>(dk + ro, aK, s.alpha, s.D, hh);
-  store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
-  store_acc<NDB>(dv + ro, aV, 1.f, s.D, hh);
-  store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
+  {
+    // nobody reads the tile buffers any more and no tile load is in flight: each wave stages its
+    // four output tiles through a region of its own
+    const unsigned lw = lds0 + wave * (32 * (64 * NDB + 16));
+    const int row0 = fb * kFix + wave * 32;
+    store_tile_coalesced<NDB>(lw, dk + base, s.sn, row0, s.N, s.D, aK, s.alpha, lane);
+    store_tile_coalesced<NDB>(lw, dtk + base, s.sn, row0, s.N, s.D, aTK, s.alpha, lane);
+    store_tile_coalesced<NDB>(lw, dv + base, s.sn, row0, s.N, s.D, aV, 1.f, lane);
+    store_tile_coalesced<NDB>(lw, dtv + base, s.sn, row0, s.N, s.D, aTV, 1.f, lane);
+  }
+  PROF_EXIT;
 }
 
 template <int DK, int DV>
@@ -357,4 +382,9 @@ hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st)
   }
 }
 
+#if defined(TVM_PROFILE)
+extern "C" int tvmattn_debug_read_prof_col_pipe(long long* out16) {
+  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
+}
+#endif
 }  // namespace tvm

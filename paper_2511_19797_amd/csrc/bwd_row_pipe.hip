@@ -30,37 +30,6 @@ constexpr int kFix = 128;  // queries per workgroup (4 waves x 32)
 constexpr int kNT = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Optional cycle stamps per phase (build with -DTVM_PROFILE; read back with tvmattn_debug_read_prof_pipe).
-#if defined(TVM_PROFILE)
-__device__ long long g_prof_pipe[16];
-#define PROF_ENTRY const long long pe_ = clock64(); long long pp_[16]
-#define PROF_P(i) pp_[i] = clock64() - pe_
-#define PROF_DECL long long pt_ = clock64(), pa_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; const long long pl_ = pt_
-#define PROF(i)                        \
-  do {                                 \
-    const long long n_ = clock64();    \
-    pa_[i] += n_ - pt_;                \
-    pt_ = n_;                          \
-  } while (0)
-#define PROF_DUMP                                  \
-  const long long px_ = clock64();                 \
-  if (blockIdx.x == 3 && threadIdx.x == 0)         \
-    for (int i_ = 0; i_ < 8; ++i_) g_prof_pipe[i_] = pa_[i_]
-#define PROF_EXIT                                                      \
-  if (blockIdx.x == 3 && threadIdx.x == 0) {                           \
-    g_prof_pipe[8] = pl_ - pe_;                                        \
-    g_prof_pipe[9] = px_ - pl_;                                        \
-    g_prof_pipe[10] = clock64() - px_;                                 \
-    for (int i_ = 11; i_ < 16; ++i_) g_prof_pipe[i_] = pp_[i_];        \
-  }
-#else
-#define PROF_ENTRY
-#define PROF_P(i)
-#define PROF_DECL
-#define PROF(i)
-#define PROF_DUMP
-#define PROF_EXIT
-#endif
 
 template <int DK, int DV>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
@@ -108,41 +77,48 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::RAddr rv = TV::raddr(ic, hh);
   const typename TK::TAddr ta = TK::taddr(ic, hh);
+  // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
+  // barrier anyway), then this lane's row scalars and fixed-side fragments (scattered loads), then
+  // the first part of tile 1 (the second stage is free from the start).
+  const int nt = (s.N + 63) >> 6;      // tiles
+  const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
-  PROF_P(11);
-
-  bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
-  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
-  // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
-  // this lane's query, from the same fragment layout (each half-wave holds half of the row);
-  // they are also written out for the key-side kernel, which runs after this one.
-  float ds = 0.f, s1 = 0.f;
-  {
-    bf16x8 of[NKS], tof[NKS];
-    gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
-    gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
-#pragma unroll
-    for (int kk = 0; kk < NKS; ++kk)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float oe = (float)of[kk][e], gte = (float)tgf[kk][e];
-        ds = fmaf((float)gf[kk][e], oe, ds);
-        ds = fmaf(gte, (float)tof[kk][e], ds);
-        s1 = fmaf(gte, oe, s1);
-      }
-    PROF_P(12);
-    ds += xhalf(ds);
-    s1 += xhalf(s1);
-  }
-  PROF_P(13);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.N + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
   const float mub = iok ? stats[r] : 0.f;
+  bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS], of[NKS], tof[NKS];
+  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+#pragma unroll
+  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, jlast), lds0 + BUF);
+  PROF_P(11);
+  // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
+  // this lane's query, from the same fragment layout (each half-wave holds half of the row), two
+  // bf16 products per instruction, accumulated in float32; they are also written out for the
+  // key-side kernel, which runs after this one.
+  float ds = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk)
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const bf16x2 g2 = {gf[kk][e], gf[kk][e + 1]};
+      const bf16x2 tg2 = {tgf[kk][e], tgf[kk][e + 1]};
+      const bf16x2 o2 = {of[kk][e], of[kk][e + 1]};
+      const bf16x2 to2 = {tof[kk][e], tof[kk][e + 1]};
+      ds = __builtin_amdgcn_fdot2_f32_bf16(g2, o2, ds, false);
+      ds = __builtin_amdgcn_fdot2_f32_bf16(tg2, to2, ds, false);
+      s1 = __builtin_amdgcn_fdot2_f32_bf16(tg2, o2, s1, false);
+    }
+  PROF_P(12);
+  ds += xhalf(ds);
+  s1 += xhalf(s1);
+  PROF_P(13);
   if (iok && hh == 0) {
     dsig[r] = ds;
     sig1[r] = s1;
@@ -157,15 +133,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   // wave-uniform scalars for the assembly blocks (SGPR operands)
   const float c1u = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha * kLog2e)));
   const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
-  const int nt = (s.N + 63) >> 6;      // tiles
-  const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
 
   PROF_P(14);
   dma_wait();
   __syncthreads();  // tile 0 has landed
   PROF_P(15);
-#pragma unroll
-  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, jlast), lds0 + BUF);
   bf16x8 ra[NKS], rb[NKS];  // S-fragments (K, tK rows) of the block whose S phase comes next
 #pragma unroll
   for (int kk = 0; kk < NKS; ++kk) {
@@ -351,24 +323,30 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   // the row scalars are first used inside the tile: make the compiler wait for their loads here,
   // not in the loop (where its wait would also cover the tile loads in flight)
   asm volatile("" ::"v"(lse2), "v"(mub), "v"(ds), "v"(s1));
-  const int nfull = s.N >> 6;  // tiles without keys beyond N
+  // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
+  // registers for best); tiles that do not exist are "fetched" as the last tile again.
+  const int nfull = s.N >> 6;           // tiles without keys beyond N
   for (int t = 0; t < nfull; ++t)
     tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, jlast),
          min((t + 2) * 64, jlast));
   if (nt > nfull)
     tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, jlast, jlast);
+  dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
+  __syncthreads();
   PROF_DUMP;
-  dma_wait();      // the last tiles' loads (re-fetches of the last tile, unused) must not outlive the workgroup
   mfma_settle();   // the last output products have landed before the accumulators are read
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
     landed_acc(aQ[db]);
     landed_acc(aTQ[db]);
   }
-  if (iok) {
-    const long long ro = base + (long long)i * s.sn;
-    store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
-    store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+  {
+    // nobody reads the tile buffers any more and no tile load is in flight: each wave stages its
+    // two output tiles through a region of its own
+    const unsigned lw = lds0 + wave * (32 * (64 * NDB + 16));
+    const int row0 = fb * kFix + wave * 32;
+    store_tile_coalesced<NDB>(lw, dq + base, s.sn, row0, s.N, s.D, aQ, s.alpha, lane);
+    store_tile_coalesced<NDB>(lw, dtq + base, s.sn, row0, s.N, s.D, aTQ, s.alpha, lane);
   }
   PROF_EXIT;
 }
@@ -399,7 +377,7 @@ hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st)
 }
 
 #if defined(TVM_PROFILE)
-extern "C" int tvmattn_debug_read_prof_pipe(long long* out16) {
+extern "C" int tvmattn_debug_read_prof_row_pipe(long long* out16) {
   return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
 }
 #endif

@@ -116,6 +116,21 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
   else
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
 }
+// The same, skipped altogether when `pred` (wave-uniform) is zero.  The branch lives inside the
+// assembly block, so the surrounding code stays one basic block.
+template <int BYTES>
+__device__ __forceinline__ void dma_to_lds_if(int pred, const void* base, unsigned off, unsigned lds_addr) {
+  static_assert(BYTES == 16 || BYTES == 4, "dword or dwordx4");
+  const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+  const unsigned long long b = (unsigned long long)(uintptr_t)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+  const unsigned long long bu = ((unsigned long long)hi << 32) | lo;
+  const int p = __builtin_amdgcn_readfirstlane(pred);
+  if (BYTES == 16)
+    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n1:" ::"s"(m), "v"(off), "s"(bu), "s"(p) : "memory", "m0", "scc");
+  else
+    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2\n1:" ::"s"(m), "v"(off), "s"(bu), "s"(p) : "memory", "m0", "scc");
+}
 // Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -167,6 +182,11 @@ struct Tile {
                                                    int rows_left, unsigned lds, int wave) {
     const unsigned r = (unsigned)min(L.srow[t], rows_left - 1);
     dma_to_lds<16>(tile, r * pitch + L.col[t], lds + (unsigned)(wave + t * NW) * 1024u);
+  }
+  __device__ __forceinline__ static void issue_one_if(int pred, const Lane& L, int t, const bf16* __restrict__ tile,
+                                                      unsigned pitch, int rows_left, unsigned lds, int wave) {
+    const unsigned r = (unsigned)min(L.srow[t], rows_left - 1);
+    dma_to_lds_if<16>(pred, tile, r * pitch + L.col[t], lds + (unsigned)(wave + t * NW) * 1024u);
   }
   __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ tile, unsigned pitch,
                                                int rows_left, unsigned lds, int wave) {
@@ -282,34 +302,41 @@ __device__ __forceinline__ void store_acc(bf16* __restrict__ dst, const f32x16 (
     }
 }
 
-// Coalesced store of a [32*NW x D] output tile held as transposed accumulators (rows = d, column
-// = this lane's output row): each wave parks its 32 rows in its own LDS region as bf16, then
-// writes them out as 16-byte chunks with consecutive lanes on consecutive chunks, so a wave
-// store covers contiguous memory instead of 32 scattered 16-byte pieces.  Only wave-local
-// ordering is needed (a wave reads back what it wrote itself).
-//   lds_wave: this wave's region, at least 32 * (2*DV + 8) bytes.
+// Coalesced store of one wave's [32 x D] output tile held as transposed accumulators (rows = d,
+// column = this lane's output row): the wave parks the tile in its own LDS region as bf16, row by
+// row, then writes it out in 16-byte chunks with consecutive lanes on consecutive chunks, so a
+// wave store covers whole rows instead of 32 scattered 8-byte pieces (which cost about four
+// times as much per byte).  Only wave-local ordering is needed: a wave reads back what it wrote
+// itself, and the LDS executes one wave's instructions in order.
+//   lds_wave: LDS address of this wave's region, 32 * (64*NDB + 16) bytes, not in use by anyone else.
+//   head: the tensor's (batch, head) base;  row0: first of the wave's 32 rows;  rows >= N are skipped.
 template <int NDB>
-__device__ __forceinline__ void store_tile_coalesced(char* lds_wave, bf16* __restrict__ head, long long sn, int row0,
+__device__ __forceinline__ void store_tile_coalesced(unsigned lds_wave, bf16* __restrict__ head, long long sn, int row0,
                                                      int N, int D, const f32x16 (&a)[NDB], float scale, int lane) {
-  constexpr int PB = 2 * 32 * NDB + 8;  // row pitch: 8 (mod 256) bytes keeps the 8-byte writes off each other's banks
+  constexpr int PB = 64 * NDB + 16;  // row pitch: 16-byte aligned, and 8-byte writes of 32 lanes hit 64 distinct banks
+  constexpr int NCH = 4 * NDB;       // 16-byte chunks per (padded) row
+  typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+  typedef u32x2 __attribute__((address_space(3))) * wp;
+  typedef const u32x4 __attribute__((address_space(3))) * rp;
   const int ic = lane & 31, hh = lane >> 5;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int d0 = db * 32 + 8 * g + 4 * hh;
       bf16x4 o;
 #pragma unroll
       for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
-      *reinterpret_cast<bf16x4*>(lds_wave + ic * PB + d0 * 2) = o;
+      *(wp)(uintptr_t)(lds_wave + (unsigned)(ic * PB + (db * 32 + 8 * g + 4 * hh) * 2)) = __builtin_bit_cast(u32x2, o);
     }
-  const int nch = D >> 3;  // 16-byte chunks per row
-  for (int idx = lane; idx < 32 * nch; idx += 64) {
-    const int r = idx / nch, c = idx - r * nch;
-    const uint2 lo = *reinterpret_cast<const uint2*>(lds_wave + r * PB + c * 16);
-    const uint2 hi = *reinterpret_cast<const uint2*>(lds_wave + r * PB + c * 16 + 8);
-    if (row0 + r < N)
-      *reinterpret_cast<uint4*>(head + (long long)(row0 + r) * sn + c * 8) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#pragma unroll
+  for (int it = 0; it < (32 * NCH + 63) / 64; ++it) {
+    const int idx = it * 64 + lane;
+    const int r = idx / NCH, c = idx - r * NCH;
+    if (idx < 32 * NCH && c * 8 < D && row0 + r < N) {
+      const u32x4 v = *(rp)(uintptr_t)(lds_wave + (unsigned)(r * PB + c * 16));
+      *reinterpret_cast<u32x4*>(head + (long long)(row0 + r) * sn + c * 8) = v;
+    }
   }
 }
 
