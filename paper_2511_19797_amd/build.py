@@ -16,7 +16,6 @@ COMMON = [
 # MFMA results straight into VGPRs (the score tiles are consumed by the VALU).  Not used for the
 # d > 96 instantiations, whose register pressure sends the compiler's AGPR rewrite pass astray.
 PER_FILE = {
-    "bwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],

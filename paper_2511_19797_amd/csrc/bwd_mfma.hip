@@ -1,9 +1,9 @@
-// Backward launchers, head dims up to 96 (see bwd_mfma_kernels.h for the kernels).
-#include "bwd_mfma_kernels.h"
+// Backward dispatch on the bf16 matrix cores: hand-scheduled kernels for head dims up to 96
+// (bwd_row_pipe.hip, bwd_col_pipe.hip), generic-order kernels above (bwd_mfma_wide.hip).
+#include "tvm_common.h"
 
 namespace tvm {
 
-// d > 96 is instantiated in bwd_mfma_wide.hip (built with different code-generation flags)
 hipError_t launch_bwd_col_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
 
@@ -12,30 +12,15 @@ bool mfma_supported(const Shape& s, int dtype) {
   return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22);
 }
 
-#define TVM_DISPATCH_D(FN, WIDE)                  \
-  switch ((s.D + 15) / 16 * 16) {                 \
-    case 16: return FN<16, 32>(s, a, st);         \
-    case 32: return FN<32, 32>(s, a, st);         \
-    case 48: return FN<48, 64>(s, a, st);         \
-    case 64: return FN<64, 64>(s, a, st);         \
-    case 80: return FN<80, 96>(s, a, st);         \
-    case 96: return FN<96, 96>(s, a, st);         \
-    default: return WIDE(s, a, st);               \
-  }
-
+// The query-side kernel runs first in both families: it leaves the row scalars of Step 1 of
+// App. C in the workspace for the key-side kernel (the hand-scheduled pair also lse in log2 units).
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);  // hand-scheduled variant (bwd_col_pipe.hip)
+  if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);
   return launch_bwd_col_mfma_wide(s, a, st);
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);  // hand-scheduled variant (bwd_row_pipe.hip)
+  if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);
   return launch_bwd_row_mfma_wide(s, a, st);
 }
-
-#if defined(TVM_PROFILE)
-extern "C" int tvmattn_debug_read_prof(long long* out16) {
-  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prof), sizeof(long long) * 16);
-}
-#endif
 
 }  // namespace tvm

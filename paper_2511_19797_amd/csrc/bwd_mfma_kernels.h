@@ -1,4 +1,6 @@
-// Backward through both outputs on the bf16 matrix cores (gfx950): a key-side kernel
+// Backward through both outputs on the bf16 matrix cores (gfx950), generic instruction order
+// (the compiler schedules; used for head dims above 96, see bwd_row_pipe.hip and
+// bwd_col_pipe.hip for the hand-scheduled kernels of the smaller head dims): a key-side kernel
 // (dK, dtK, dV, dtV; Steps 2, 4, 6 of App. C plus the ordinary-attention terms of gO) and a
 // query-side kernel (dQ, dtQ; Steps 3, 5), both recomputing the tile quantities from lse and
 // stats ("Caching softmax statistics").  With G = gO, Gt = gTO and the row scalars of Step 1
@@ -28,23 +30,6 @@
 #include "mfma_tiles.h"
 
 namespace tvm {
-#if defined(TVM_PROFILE)
-static __device__ long long g_prof[16];
-#define PROF_DECL long long pt_ = clock64(), pa_[8] = {0, 0, 0, 0, 0, 0, 0, 0}
-#define PROF(i)                        \
-  do {                                 \
-    const long long n_ = clock64();    \
-    pa_[i] += n_ - pt_;                \
-    pt_ = n_;                          \
-  } while (0)
-#define PROF_DUMP                                                                  \
-  if (blockIdx.x == 3 && threadIdx.x == 0)                                         \
-    for (int i_ = 0; i_ < 8; ++i_) g_prof[i_] = pa_[i_]
-#else
-#define PROF_DECL
-#define PROF(i)
-#define PROF_DUMP
-#endif
 namespace {
 
 constexpr int kFix = 128;  // fixed-side rows per workgroup (4 waves x 32)

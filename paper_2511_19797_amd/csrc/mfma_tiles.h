@@ -116,21 +116,6 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
   else
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
 }
-// The same, skipped altogether when `pred` (wave-uniform) is zero.  The branch lives inside the
-// assembly block, so the surrounding code stays one basic block.
-template <int BYTES>
-__device__ __forceinline__ void dma_to_lds_if(int pred, const void* base, unsigned off, unsigned lds_addr) {
-  static_assert(BYTES == 16 || BYTES == 4, "dword or dwordx4");
-  const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
-  const unsigned long long b = (unsigned long long)(uintptr_t)base;
-  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
-  const unsigned long long bu = ((unsigned long long)hi << 32) | lo;
-  const int p = __builtin_amdgcn_readfirstlane(pred);
-  if (BYTES == 16)
-    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n1:" ::"s"(m), "v"(off), "s"(bu), "s"(p) : "memory", "m0", "scc");
-  else
-    asm volatile("s_cmp_eq_u32 %3, 0\n\ts_cbranch_scc1 1f\n\ts_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2\n1:" ::"s"(m), "v"(off), "s"(bu), "s"(p) : "memory", "m0", "scc");
-}
 // Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -182,11 +167,6 @@ struct Tile {
                                                    int rows_left, unsigned lds, int wave) {
     const unsigned r = (unsigned)min(L.srow[t], rows_left - 1);
     dma_to_lds<16>(tile, r * pitch + L.col[t], lds + (unsigned)(wave + t * NW) * 1024u);
-  }
-  __device__ __forceinline__ static void issue_one_if(int pred, const Lane& L, int t, const bf16* __restrict__ tile,
-                                                      unsigned pitch, int rows_left, unsigned lds, int wave) {
-    const unsigned r = (unsigned)min(L.srow[t], rows_left - 1);
-    dma_to_lds_if<16>(pred, tile, r * pitch + L.col[t], lds + (unsigned)(wave + t * NW) * 1024u);
   }
   __device__ __forceinline__ static void issue(const Lane& L, const bf16* __restrict__ tile, unsigned pitch,
                                                int rows_left, unsigned lds, int wave) {
