@@ -254,7 +254,12 @@ __device__ __forceinline__ bf16x8 zero_unless(bf16x8 f, bool keep) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }
+// The value the lane 32 away holds (one VALU swap of the two half-waves, no trip through LDS).
+__device__ __forceinline__ float xhalf(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // r[0] = {lo, lo}, r[1] = {hi, hi}
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  This maps the
 // hardware id to a logical id such that consecutive logical ids (the blocks of one head, which
