@@ -155,11 +155,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         pw1_pair_asm(pp[2 * e], pp[2 * e + 1], nn[2 * e], nn[2 * e + 1], pk[e], pdk[e], s0, s1, sT[2 * e],
                      sT[2 * e + 1], c1u, f4(la[g4], t), f4(la[g4], t + 1), alphau, f4(ma[g4], t), f4(ma[g4], t + 1));
       };
-      // gZ, gZt of elements 2e, 2e+1: sig1 and dsig differ per element here, so one element at a time
+      // gZ, gZt of elements 2e, 2e+1 (E, DF come with sig1, dsig already subtracted)
       auto pw2 = [&](int e) {
-        const int g4 = e >> 1, t = (2 * e) & 3;
-        pw2_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1],
-                     nn[2 * e], nn[2 * e + 1], f4(sa[g4], t), f4(sa[g4], t + 1), f4(da[g4], t), f4(da[g4], t + 1));
+        pw2_shifted_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e],
+                             pp[2 * e + 1], nn[2 * e], nn[2 * e + 1]);
       };
       auto tr_imm = [&](int cc, int db) { return (2 * ib + cc) * 16 * TX::PCH * 16 + db * 64; };
 
@@ -184,9 +183,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + ib * TX::kBlkBytes + k2 * 32);
         }
 #pragma unroll
-        TVM_SHARE(x, m, 4, NS) {  // lse, stats of half 0
+        TVM_SHARE(x, m, 12, NS) {  // lse, stats of half 0; -sig1 and -dsig of the block, the start values of E and DF
           if (x < 2) la[x] = lds_read_f4(rv, ib * 128 + x * 32);
-          else ma[x - 2] = lds_read_f4(rv, 256 + ib * 128 + (x - 2) * 32);
+          else if (x < 4) ma[x - 2] = lds_read_f4(rv, 256 + ib * 128 + (x - 2) * 32);
+          else if (x < 8) sa[x - 4] = lds_read_f4(rv, 768 + ib * 128 + (x - 4) * 32);
+          else da[x - 8] = lds_read_f4(rv, 512 + ib * 128 + (x - 8) * 32);
         }
         if (ib == 0) {
 #pragma unroll
@@ -194,18 +195,26 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         }
       }
       PROF(0);
-      // ---- E, with P, N, Pd of half 0
+      // ---- E, with P, N, Pd of half 0.  E and DF start from -sig1 and -dsig of their rows (queries).
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          sE[4 * g4 + t] = sa[g4][t];
+          sDF[4 * g4 + t] = da[g4][t];
+        }
 #pragma unroll
       for (int m = 0; m < NS; ++m) {
         const int kk = m / 3, w = m - 3 * kk;
         if (w == 0) {
-          if (kk == 0) { if (V_IN_A) mfma_fix0<RAG>(sE, rtg[0], vf[0]); else mfma_vv0<RAG>(sE, rtg[0], vf[0]); }
-          else { if (V_IN_A) mfma_fix<RAG>(sE, rtg[kk], vf[kk]); else mfma_vv<RAG>(sE, rtg[kk], vf[kk]); }
+          if (V_IN_A) mfma_fix<RAG>(sE, rtg[kk], vf[kk]);
+          else mfma_vv<RAG>(sE, rtg[kk], vf[kk]);
         } else if (w == 1) {
-          if (kk == 0) { if (V_IN_A) mfma_fix0<RAG>(sDF, rg[0], vf[0]); else mfma_vv0<RAG>(sDF, rg[0], vf[0]); }
-          else { if (V_IN_A) mfma_fix<RAG>(sDF, rg[kk], vf[kk]); else mfma_vv<RAG>(sDF, rg[kk], vf[kk]); }
+          if (V_IN_A) mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
+          else mfma_vv<RAG>(sDF, rg[kk], vf[kk]);
         } else {
-          if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]); else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
+          if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
+          else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
         }
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NS) {  // G^T, tG^T of half 0
@@ -242,11 +251,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
         }
 #pragma unroll
-        TVM_SHARE(x, m, 4, NH) {  // sig1, dsig of half 0
-          if (x < 2) sa[x] = lds_read_f4(rv, 768 + ib * 128 + x * 32);
-          else da[x - 2] = lds_read_f4(rv, 512 + ib * 128 + (x - 2) * 32);
-        }
-#pragma unroll
         TVM_SHARE(e, m, 4, NH) pw1(4 + e);
       }
       PROF(2);
@@ -262,11 +266,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           const int d2 = x >> 1;
           if ((x & 1) == 0) xT[d2] = lds_read_tr(tl, th, tr_imm(0, d2));
           else txT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(0, d2));
-        }
-#pragma unroll
-        TVM_SHARE(x, m, 4, NH) {  // sig1, dsig of half 1
-          if (x < 2) sa[2 + x] = lds_read_f4(rv, 768 + ib * 128 + (2 + x) * 32);
-          else da[x] = lds_read_f4(rv, 512 + ib * 128 + x * 32);
         }
         if (m == 0) landed(sE, sDF);  // at least four products after the last one of E
 #pragma unroll

@@ -120,8 +120,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   s1 += xhalf(s1);
   PROF_P(13);
   if (iok && hh == 0) {
-    dsig[r] = ds;
-    sig1[r] = s1;
+    dsig[r] = -ds;  // negated: the key-side kernel starts its DF and E tiles from these
+    sig1[r] = -s1;
     lse2w[r] = lse2;
   }
   f32x16 aQ[NDB], aTQ[NDB];

@@ -112,6 +112,23 @@ __device__ __forceinline__ void pw2_pair_asm(unsigned& gz, unsigned& gzt, float 
       : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1), "v"(sa0), "v"(sa1), "v"(da0),
         "v"(da1));
 }
+//   The key-side kernel's second step when E and DF already have sig1 and dsig subtracted (their
+//   tiles start from -sig1, -dsig instead of 0):  gZt = P E',  gZ = P DF' + gZt N.
+__device__ __forceinline__ void pw2_shifted_pair_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1,
+                                                     float p0, float p1, float n0, float n1) {
+  float t0, t1, w0, w1;
+  asm volatile(
+      "v_mul_f32 %2, %10, %6\n\t"
+      "v_mul_f32 %3, %11, %7\n\t"
+      "v_mul_f32 %4, %10, %8\n\t"
+      "v_mul_f32 %5, %11, %9\n\t"
+      "v_fmac_f32 %4, %2, %12\n\t"
+      "v_fmac_f32 %5, %3, %13\n\t"
+      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
+      "v_cvt_pk_bf16_f32 %1, %2, %3"
+      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
+      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1));
+}
 //   The key-side kernel's form of the first step, for two neighbouring elements: P and N as above
 //   (lse2, mub per element), plus Pd = P N, with P and Pd rounded to bf16 and packed.
 __device__ __forceinline__ void pw1_pair_asm(float& p0, float& p1, float& n0, float& n1, unsigned& pk, unsigned& pdk,
