@@ -46,9 +46,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   constexpr int NS = 3 * NKS;                         // products of a score-type phase
-  constexpr int NO = 6 * NDB;                         // products of an output phase
+  constexpr int NH = 3 * NDB;                         // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
-  constexpr int FO = 4;                               // ... of an output phase (NO >= 6)
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
   constexpr int NDMA_A = NDMA / 2;                    // of which issued in O(1), the rest in the next S(0)
   PROF_ENTRY;
@@ -119,6 +118,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   ds += xhalf(ds);
   s1 += xhalf(s1);
   PROF_P(13);
+  // E and DF tiles start from -sig1 and -dsig of this lane's query (the same value in all 16
+  // registers), which takes the subtractions out of the pointwise work
+  f32x16 cE, cDF;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    cE[e] = -s1;
+    cDF[e] = -ds;
+  }
+  asm volatile("" : "+v"(cE), "+v"(cDF));  // materialised here, once
   if (iok && hh == 0) {
     dsig[r] = -ds;  // negated: the key-side kernel starts its DF and E tiles from these
     sig1[r] = -s1;
@@ -159,7 +167,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     f32x16 sS, sT, sE, sDF;
     float pp[16], nn[16];
     unsigned gz0[8], gzt0[8], gz1[8], gzt1[8];
-    bf16x8 kT[2][NDB], tkT[2][NDB], kT1[2][NDB], tkT1[2][NDB];
+    bf16x8 xT[NDB], txT[NDB], yT[NDB], tyT[NDB];  // transposed K, tK of the half in use / of the next half
 
     auto s_product = [&](int m) {  // m-th product of an S phase (operands ra, rb)
       const int kk = m / 3, w = m - 3 * kk;
@@ -176,22 +184,29 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     auto e_product = [&](int m) {  // m-th product of an E phase (operands rc, rd)
       const int kk = m / 3, w = m - 3 * kk;
       if (w == 0) {
-        if (kk == 0) mfma_fix0<RAG>(sE, rc[0], tgf[0]);
+        if (kk == 0) mfma_fixc<RAG>(sE, rc[0], tgf[0], cE);
         else mfma_fix<RAG>(sE, rc[kk], tgf[kk]);
       } else if (w == 1) {
-        if (kk == 0) mfma_fix0<RAG>(sDF, rc[0], gf[0]);
+        if (kk == 0) mfma_fixc<RAG>(sDF, rc[0], gf[0], cDF);
         else mfma_fix<RAG>(sDF, rc[kk], gf[kk]);
       } else {
         mfma_fix<RAG>(sDF, rd[kk], tgf[kk]);
       }
     };
-    auto o_product = [&](int m, const bf16x8 (&xT)[2][NDB], const bf16x8 (&txT)[2][NDB], const unsigned (&gz)[8],
+    // m-th product of half cc of an output phase (transposed fragments xT, txT of that half)
+    auto o_product = [&](int m, int cc, const bf16x8 (&xT)[NDB], const bf16x8 (&txT)[NDB], const unsigned (&gz)[8],
                          const unsigned (&gzt)[8]) {
-      const int cc = m / (3 * NDB), db = (m / 3) % NDB, w = m % 3;
-      if (w == 0) mfma_acc<RAG>(aQ[db], xT[cc][db], frag_of(gz, cc));
-      else if (w == 1) mfma_acc<RAG>(aQ[db], txT[cc][db], frag_of(gzt, cc));
-      else mfma_acc<RAG>(aTQ[db], xT[cc][db], frag_of(gzt, cc));
+      const int db = m / 3, w = m - 3 * db;
+      if (w == 0) {
+        if (m == 0) mfma_acc<true>(aQ[db], xT[db], frag_of(gz, cc));  // gz, gzt may have been written just before
+        else mfma_acc<RAG>(aQ[db], xT[db], frag_of(gz, cc));
+      } else if (w == 1) {
+        mfma_acc<RAG>(aQ[db], txT[db], frag_of(gzt, cc));
+      } else {
+        mfma_acc<RAG>(aTQ[db], xT[db], frag_of(gzt, cc));
+      }
     };
+    auto tr_imm = [&](int blk, int cc, int db) { return (2 * blk + cc) * 16 * TK::PCH * 16 + db * 64; };
     // P and N of element e of a block
     auto pw1 = [&](int blk, int e) {
       float sv = sS[e];
@@ -200,8 +215,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     };
     // gZ, gZt of elements 2e, 2e+1 of a block
     auto pw2 = [&](unsigned (&gz)[8], unsigned (&gzt)[8], int e) {
-      pw2_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1], nn[2 * e],
-              nn[2 * e + 1], s1, ds);
+      pw2_shifted_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1],
+                           nn[2 * e], nn[2 * e + 1]);
     };
     // share [m*CNT/N, (m+1)*CNT/N) of CNT side instructions goes after the m-th of N products
 #define TVM_SHARE(x, m, CNT, N) for (int x = (m) * (CNT) / (N); x < ((m) + 1) * (CNT) / (N); ++x)
@@ -266,10 +281,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NS; ++m) {
       e_product(m);
 #pragma unroll
-      TVM_SHARE(x, m, 4 * NDB, NS) {  // transposed K, tK of block 0
-        const int cc = (x >> 1) / NDB, db = (x >> 1) % NDB;
-        if ((x & 1) == 0) kT[cc][db] = lds_read_tr(tl, th, cc * 16 * TK::PCH * 16 + db * 64);
-        else tkT[cc][db] = lds_read_tr(tl, th, OFF_TK + cc * 16 * TK::PCH * 16 + db * 64);
+      TVM_SHARE(x, m, 2 * NDB, NS) {  // transposed K, tK of block 0, half 0
+        const int db = x >> 1;
+        if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, tr_imm(0, 0, db));
+        else txT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(0, 0, db));
       }
       if (m == FS) {
         if (NS < 6) mfma_settle();
@@ -281,40 +296,61 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
     }
     PROF(3);
-    // ---- O(0), with gZ, gZt of block 1
+    // ---- O(0), with gZ, gZt of block 1 (spread over both halves)
 #pragma unroll
-    for (int m = 0; m < NO; ++m) {
-      o_product(m, kT, tkT, gz0, gzt0);
+    for (int m = 0; m < NH; ++m) {
+      o_product(m, 0, xT, txT, gz0, gzt0);
 #pragma unroll
-      TVM_SHARE(x, m, 4 * NDB, NO) {  // transposed K, tK of block 1
-        const int cc = (x >> 1) / NDB, db = (x >> 1) % NDB;
-        if ((x & 1) == 0) kT1[cc][db] = lds_read_tr(tl, th, (2 + cc) * 16 * TK::PCH * 16 + db * 64);
-        else tkT1[cc][db] = lds_read_tr(tl, th, OFF_TK + (2 + cc) * 16 * TK::PCH * 16 + db * 64);
+      TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 0, half 1
+        const int db = x >> 1;
+        if ((x & 1) == 0) yT[db] = lds_read_tr(tl, th, tr_imm(0, 1, db));
+        else tyT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(0, 1, db));
       }
-      if (m == FO) landed(sE, sDF);
-      if (m >= FO) {
+      if (m == NH - 1) landed(sE, sDF);  // at least NH >= 3 products behind the last one of E(1): see below
+    }
 #pragma unroll
-        TVM_SHARE(e, m - FO, 8, NO - FO) pw2(gz1, gzt1, e);
+    for (int m = 0; m < NH; ++m) {
+      o_product(m, 1, yT, tyT, gz0, gzt0);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 0
+        const int db = x >> 1;
+        if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, tr_imm(1, 0, db));
+        else txT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(1, 0, db));
+      }
+      if (m < NH - 1) {  // none behind the last product: the product after it reads them
+#pragma unroll
+        TVM_SHARE(e, m, 8, NH - 1) pw2(gz1, gzt1, e);
       }
     }
     PROF(4);
+    // ---- O(1), half 0
+#pragma unroll
+    for (int m = 0; m < NH; ++m) {
+      o_product(m, 0, xT, txT, gz1, gzt1);
+#pragma unroll
+      TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 1
+        const int db = x >> 1;
+        if ((x & 1) == 0) yT[db] = lds_read_tr(tl, th, tr_imm(1, 1, db));
+        else tyT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(1, 1, db));
+      }
+    }
     // every read of this stage has been issued; the next tile must have landed before anyone goes on
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     dma_wait();
     __syncthreads();
     PROF(5);
-    // ---- O(1)
+    // ---- O(1), half 1
 #pragma unroll
-    for (int m = 0; m < NO; ++m) {
-      o_product(m, kT1, tkT1, gz1, gzt1);
+    for (int m = 0; m < NH; ++m) {
+      o_product(m, 1, yT, tyT, gz1, gzt1);
 #pragma unroll
-      TVM_SHARE(x, m, 2 * NKS, NO) {  // S-fragments of the next tile's block 0
+      TVM_SHARE(x, m, 2 * NKS, NH) {  // S-fragments of the next tile's block 0
         const int kk = x % NKS;
         if (x < NKS) ra[kk] = lds_read16((kk & 1) ? nko : nke, kk * 32);
         else rb[kk] = lds_read16((kk & 1) ? nko : nke, OFF_TK + kk * 32);
       }
 #pragma unroll
-      TVM_SHARE(x, m, NDMA_A, NO) dma(x, jn2, sb);
+      TVM_SHARE(x, m, NDMA_A, NH) dma(x, jn2, sb);
     }
 #undef TVM_SHARE
     PROF(6);
@@ -322,7 +358,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 
   // the row scalars are first used inside the tile: make the compiler wait for their loads here,
   // not in the loop (where its wait would also cover the tile loads in flight)
-  asm volatile("" ::"v"(lse2), "v"(mub), "v"(ds), "v"(s1));
+  asm volatile("" ::"v"(lse2), "v"(mub));
   // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
   // registers for best); tiles that do not exist are "fetched" as the last tile again.
   const int nfull = s.N >> 6;           // tiles without keys beyond N

@@ -42,6 +42,7 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 //   mfma_acc : accumulator in AGPRs, both operands in VGPRs        (output products)
 //   mfma_fix : result in VGPRs, B = a fixed-side fragment in AGPRs  (score-type products)
 //   mfma_fix0: the same with C = 0 (starts a tile)
+//   mfma_fixc: as mfma_fix0 with a tile of start values instead of 0
 //   mfma_vv, mfma_vv0: as mfma_fix, mfma_fix0 with B in VGPRs too
 // PAD puts two idle issue slots in front of the product: a matrix-core instruction must not read a
 // register that a VALU instruction (a register copy the compiler placed there, say) wrote in
@@ -61,6 +62,12 @@ template <bool PAD = false>
 __device__ __forceinline__ void mfma_fix0(f32x16& sc, bf16x8 a, bf16x8 fixed_b) {
   if (PAD) asm volatile(TVM_MFMA_PAD "v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sc) : "v"(a), "a"(fixed_b));
   else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sc) : "v"(a), "a"(fixed_b));
+}
+// result in VGPRs, B = a fixed-side fragment in AGPRs, C = a separate tile in VGPRs (starts a tile from it)
+template <bool PAD = false>
+__device__ __forceinline__ void mfma_fixc(f32x16& sc, bf16x8 a, bf16x8 fixed_b, const f32x16& c) {
+  if (PAD) asm volatile(TVM_MFMA_PAD "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(sc) : "v"(a), "a"(fixed_b), "v"(c));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(sc) : "v"(a), "a"(fixed_b), "v"(c));
 }
 // result in VGPRs, both operands in VGPRs
 template <bool PAD = false>
