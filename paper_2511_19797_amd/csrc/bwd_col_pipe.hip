@@ -45,13 +45,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   using TX = Tile<64, DV / 8, kNT / 64>;  // Q, tQ, G, tG: read both ways
   constexpr int OFF_TQ = TX::BYTES, OFF_G = 2 * TX::BYTES, OFF_TG = 3 * TX::BYTES, OFF_ROW = 4 * TX::BYTES;
   constexpr int BUF = 4 * TX::BYTES + 4 * 256;  // one stage: four tiles and four float32 row vectors (64 each)
-  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
+  __shared__ __attribute__((aligned(16))) char lds[3 * BUF];  // three stages: in use, landed or landing, being filled
   constexpr int NKS = DK / 16, NDB = DV / 32;
   constexpr int NS = 3 * NKS;                      // products of a score-type phase
   constexpr int NH = 3 * NDB;                      // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
   constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
-  constexpr int NDMA_A = NDMA / 2;                 // of which issued in the last OK(1), the rest in the next S
+  constexpr int NBLK = 2 * NS + 4 * NH;            // products of a block
+  constexpr int NPRE = 2 * NBLK - NH;              // products of a tile before its barrier: the tile after next is fetched behind them
   // register files: the accumulators fill 4*NDB*16 AGPRs; K, tK fragments always fit beside them,
   // V and tV fragments where there is room, else they stay in VGPRs
   constexpr bool V_IN_A = 64 * NDB + 12 * NKS <= 256, TV_IN_A = 64 * NDB + 16 * NKS <= 256;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
 #pragma unroll
-  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, ilast), lds0 + BUF);
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, ilast), lds0 + BUF);
   PROF_P(11);
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
 #pragma unroll
@@ -125,9 +126,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   PROF_P(13);
   PROF_DECL;
   // One tile.  RAG: queries beyond N exist in this tile (only ever the last one).
-  //   sb / sbn: LDS address of this tile's stage / of the other one;  i0: first query;
-  //   in1 / in2: first query of the next tile / of the one after it (clamped to the last tile).
-  auto tile = [&](auto rag, unsigned sb, unsigned sbn, int i0, int in1, int in2) {
+  //   sb / sbn / sbf: LDS address of this tile's stage / of the next tile's (landed) / of the free one, into
+  //   which the tile after next is fetched, one wave-load every few products;  i0: first query;
+  //   in2: first query of the tile after next (clamped to the last tile).
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int i0, int in2, bool last) {
     constexpr bool RAG = decltype(rag)::value;
     const unsigned re = sb + ra.e, ro = sb + ra.o;        // rows of Q; tQ, G, tG at + OFF_*
     const unsigned tl = sb + ta.lo, th = sb + ta.hi;      // transposed
@@ -189,10 +191,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else if (x < 8) sa[x - 4] = lds_read_f4(rv, 768 + ib * 128 + (x - 4) * 32);
           else da[x - 8] = lds_read_f4(rv, 512 + ib * 128 + (x - 8) * 32);
         }
-        if (ib == 0) {
 #pragma unroll
-          TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, in1, sbn);
-        }
+        TVM_SHARE(x, ib * NBLK + m, NDMA, NPRE) dma(x, in2, sbf);
       }
       PROF(0);
       // ---- E, with P, N, Pd of half 0.  E and DF start from -sig1 and -dsig of their rows (queries).
@@ -216,6 +216,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
           else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
         }
+#pragma unroll
+        TVM_SHARE(x, ib * NBLK + NS + m, NDMA, NPRE) dma(x, in2, sbf);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NS) {  // G^T, tG^T of half 0
           const int db = x >> 1;
@@ -245,6 +247,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         else if (w == 1) mfma_acc<RAG>(aV[db], txT[db], frag_of(pdk, 0));
         else mfma_acc<RAG>(aTV[db], txT[db], frag_of(pk, 0));
 #pragma unroll
+        TVM_SHARE(x, ib * NBLK + 2 * NS + m, NDMA, NPRE) dma(x, in2, sbf);
+#pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // G^T, tG^T of half 1
           const int d2 = x >> 1;
           if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
@@ -261,6 +265,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], yT[db], frag_of(pk, 1)); else mfma_acc<RAG>(aV[db], yT[db], frag_of(pk, 1)); }
         else if (w == 1) mfma_acc<RAG>(aV[db], tyT[db], frag_of(pdk, 1));
         else mfma_acc<RAG>(aTV[db], tyT[db], frag_of(pk, 1));
+#pragma unroll
+        TVM_SHARE(x, ib * NBLK + 2 * NS + NH + m, NDMA, NPRE) dma(x, in2, sbf);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
@@ -280,6 +286,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         else if (w == 1) mfma_acc<RAG>(aK[db], txT[db], frag_of(gzt, 0));
         else mfma_acc<RAG>(aTK[db], xT[db], frag_of(gzt, 0));
 #pragma unroll
+        TVM_SHARE(x, ib * NBLK + 2 * NS + 2 * NH + m, NDMA, NPRE) dma(x, in2, sbf);
+#pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 1
           const int d2 = x >> 1;
           if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, tr_imm(1, d2));
@@ -290,9 +298,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       }
       PROF(4);
       if (ib == 1) {
-        // every read of this stage has been issued; the next tile must have landed before anyone goes on
+        // every read of this stage has been issued; the next tile (fetched during the previous one) must
+        // have landed before anyone goes on, the loads of the tile after next stay in flight
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        dma_wait();
+        dma_wait_keep<NDMA>();
         __syncthreads();
       }
       PROF(5);
@@ -303,6 +312,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         if (w == 0) { if (m == 0) mfma_acc<true>(aK[db], yT[db], frag_of(gz, 1)); else mfma_acc<RAG>(aK[db], yT[db], frag_of(gz, 1)); }
         else if (w == 1) mfma_acc<RAG>(aK[db], tyT[db], frag_of(gzt, 1));
         else mfma_acc<RAG>(aTK[db], yT[db], frag_of(gzt, 1));
+        if (ib == 0) {
+#pragma unroll
+          TVM_SHARE(x, 2 * NS + 3 * NH + m, NDMA, NPRE) dma(x, in2, sbf);
+        }
 #pragma unroll
         TVM_SHARE(x, m, 2 * NKS, NH) {  // Q, tQ rows of the next block
           const int k2 = x % NKS;
@@ -311,26 +324,29 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           if (x < NKS) rq[k2] = lds_read16(a0, blk + k2 * 32);
           else rtq[k2] = lds_read16(a0, OFF_TQ + blk + k2 * 32);
         }
-        if (ib == 1) {
-#pragma unroll
-          TVM_SHARE(x, m, NDMA_A, NH) dma(x, in2, sb);
-        }
       }
       PROF(6);
     };
     block(std::integral_constant<int, 0>{});
     block(std::integral_constant<int, 1>{});
 #undef TVM_SHARE
+    // behind the last tile the compiler may move the accumulators right away (a loop exit is where it
+    // re-assigns registers): let the last products finish first
+    if (last) mfma_settle();
   };
 
   // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
   // registers for best); tiles that do not exist are "fetched" as the last tile again.
-  const int nfull = s.N >> 6;           // tiles without queries beyond N
-  for (int t = 0; t < nfull; ++t)
-    tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, ilast),
-         min((t + 2) * 64, ilast));
-  if (nt > nfull)
-    tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, ilast, ilast);
+  const int nfull = s.N >> 6;  // tiles without queries beyond N
+  unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
+  for (int t = 0; t < nfull; ++t) {
+    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, ilast), t + 1 == nt);
+    const unsigned r0 = st0;
+    st0 = st1;
+    st1 = st2;
+    st2 = r0;
+  }
+  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, ilast, true);
   dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
   __syncthreads();
   PROF_DUMP;

@@ -43,13 +43,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   using TV = Tile<64, DK / 8, kNT / 64>;  // V, tV: score-type products only
   constexpr int OFF_TK = TK::BYTES, OFF_V = 2 * TK::BYTES, OFF_TV = 2 * TK::BYTES + TV::BYTES;
   constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
-  __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
+  __shared__ __attribute__((aligned(16))) char lds[3 * BUF];  // three stages: in use, landed or landing, being filled
   constexpr int NKS = DK / 16, NDB = DV / 32;
   constexpr int NS = 3 * NKS;                         // products of a score-type phase
   constexpr int NH = 3 * NDB;                         // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
-  constexpr int NDMA_A = NDMA / 2;                    // of which issued in O(1), the rest in the next S(0)
+  constexpr int NPRE = 4 * NS + 3 * NH;               // products of a tile before its barrier: the tile after next is fetched behind them
   PROF_ENTRY;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
   gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
 #pragma unroll
-  for (int x = 0; x < NDMA_A; ++x) dma(x, min(64, jlast), lds0 + BUF);
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, jlast), lds0 + BUF);
   PROF_P(11);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row), two
@@ -155,9 +155,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 
   PROF_DECL;
   // One tile.  RAG: keys beyond N exist in this tile (only ever the last one).
-  //   sb / sbn: LDS address of this tile's stage / of the other one;  j0: first key;
-  //   jn1 / jn2: first key of the next tile / of the one after it (clamped to the last tile).
-  auto tile = [&](auto rag, unsigned sb, unsigned sbn, int j0, int jn1, int jn2) {
+  //   sb / sbn / sbf: LDS address of this tile's stage / of the next tile's (landed) / of the free one, into
+  //   which the tile after next is fetched, one wave-load every few products;  j0: first key;
+  //   jn2: first key of the tile after next (clamped to the last tile).
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int j0, int jn2, bool last) {
     constexpr bool RAG = decltype(rag)::value;
     const unsigned ke = sb + rk.e, ko = sb + rk.o;                   // K rows; tK at + OFF_TK
     const unsigned ve = sb + OFF_V + rv.e, vo = sb + OFF_V + rv.o;   // V rows; tV at + TV::BYTES
@@ -233,13 +234,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         else rd[kk] = lds_read16((kk & 1) ? vo : ve, TV::BYTES + kk * 32);
       }
 #pragma unroll
-      TVM_SHARE(x, m, NDMA - NDMA_A, NS) dma(NDMA_A + x, jn1, sbn);
+      TVM_SHARE(x, m, NDMA, NPRE) dma(x, jn2, sbf);
     }
     PROF(0);
     // ---- E(0), with P, N of block 0
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
       e_product(m);
+#pragma unroll
+      TVM_SHARE(x, NS + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NS) {  // S-fragments of block 1
         const int kk = x % NKS;
@@ -261,6 +264,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NS; ++m) {
       s_product(m);
 #pragma unroll
+      TVM_SHARE(x, 2 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
+#pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NS) {  // E-fragments of block 1
         const int kk = x % NKS;
         if (x < NKS) rc[kk] = lds_read16((kk & 1) ? vo : ve, TV::kBlkBytes + kk * 32);
@@ -280,6 +285,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
       e_product(m);
+#pragma unroll
+      TVM_SHARE(x, 3 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NS) {  // transposed K, tK of block 0, half 0
         const int db = x >> 1;
@@ -301,6 +308,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz0, gzt0);
 #pragma unroll
+      TVM_SHARE(x, 4 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
+#pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 0, half 1
         const int db = x >> 1;
         if ((x & 1) == 0) yT[db] = lds_read_tr(tl, th, tr_imm(0, 1, db));
@@ -311,6 +320,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
     for (int m = 0; m < NH; ++m) {
       o_product(m, 1, yT, tyT, gz0, gzt0);
+#pragma unroll
+      TVM_SHARE(x, 4 * NS + NH + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 0
         const int db = x >> 1;
@@ -328,15 +339,18 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz1, gzt1);
 #pragma unroll
+      TVM_SHARE(x, 4 * NS + 2 * NH + m, NDMA, NPRE) dma(x, jn2, sbf);
+#pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 1
         const int db = x >> 1;
         if ((x & 1) == 0) yT[db] = lds_read_tr(tl, th, tr_imm(1, 1, db));
         else tyT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(1, 1, db));
       }
     }
-    // every read of this stage has been issued; the next tile must have landed before anyone goes on
+    // every read of this stage has been issued; the next tile (fetched during the previous one) must have
+    // landed before anyone goes on, the loads of the tile after next stay in flight
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    dma_wait();
+    dma_wait_keep<NDMA>();
     __syncthreads();
     PROF(5);
     // ---- O(1), half 1
@@ -349,11 +363,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         if (x < NKS) ra[kk] = lds_read16((kk & 1) ? nko : nke, kk * 32);
         else rb[kk] = lds_read16((kk & 1) ? nko : nke, OFF_TK + kk * 32);
       }
-#pragma unroll
-      TVM_SHARE(x, m, NDMA_A, NH) dma(x, jn2, sb);
     }
 #undef TVM_SHARE
     PROF(6);
+    // behind the last tile the compiler may move the accumulators right away (a loop exit is where it
+    // re-assigns registers): let the last products finish first
+    if (last) mfma_settle();
   };
 
   // the row scalars are first used inside the tile: make the compiler wait for their loads here,
@@ -361,12 +376,16 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   asm volatile("" ::"v"(lse2), "v"(mub));
   // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
   // registers for best); tiles that do not exist are "fetched" as the last tile again.
-  const int nfull = s.N >> 6;           // tiles without keys beyond N
-  for (int t = 0; t < nfull; ++t)
-    tile(std::false_type{}, lds0 + (t & 1) * BUF, lds0 + ((t + 1) & 1) * BUF, t * 64, min((t + 1) * 64, jlast),
-         min((t + 2) * 64, jlast));
-  if (nt > nfull)
-    tile(std::true_type{}, lds0 + (nfull & 1) * BUF, lds0 + ((nfull + 1) & 1) * BUF, nfull * 64, jlast, jlast);
+  const int nfull = s.N >> 6;  // tiles without keys beyond N
+  unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
+  for (int t = 0; t < nfull; ++t) {
+    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, jlast), t + 1 == nt);
+    const unsigned r0 = st0;
+    st0 = st1;
+    st1 = st2;
+    st2 = r0;
+  }
+  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, jlast, true);
   dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
   __syncthreads();
   PROF_DUMP;

@@ -126,6 +126,13 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
 // Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Waits until at most KEEP of them are outstanding (they complete in issue order).
+template <int KEEP>
+__device__ __forceinline__ void dma_wait_keep() {
+  static_assert(KEEP >= 0 && KEEP < 64, "vmcnt is six bits");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KEEP) : "memory");
+}
+
 // LDS address (the 32-bit value LDS instructions and M0 use) of a __shared__ object.
 __device__ __forceinline__ unsigned lds_addr_of(const void* p) {
   return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;

@@ -1,12 +1,16 @@
 """Static check of the hand-scheduled kernels' instruction streams (no GPU needed).
 
 The hand-scheduled translation units issue their matrix-core products from inline assembly, which
-the compiler's hazard recognizer does not look into.  One hazard is therefore ours to keep out: a
-matrix-core instruction must not read a register that a VALU instruction wrote in one of the
-two issue slots before it (the hardware does not interlock that case; s_nop N fills N+1 slots).
-The compiler is free to put register copies right in front of an inline-assembly statement, so
-this is checked on the generated assembly of every instantiation rather than argued from the
-source.
+the compiler's hazard recognizer does not look into.  Two hazards are therefore ours to keep out
+(the hardware interlocks neither):
+  1. a matrix-core instruction must not read a register that a VALU instruction wrote in one of
+     the two issue slots before it (s_nop N fills N+1 slots);
+  2. nothing but a matrix-core accumulate into the same registers may touch the result registers
+     of a matrix-core instruction until it has finished: 12 issue slots, a further matrix-core
+     instruction counting as the 8 passes it keeps the pipe for.
+The compiler is free to put register copies right in front of or right behind an inline-assembly
+statement (at a loop exit, say), so this is checked on the generated assembly of every
+instantiation rather than argued from the source.
 """
 import os
 import re
@@ -67,6 +71,35 @@ def violations(asm_text):
     return bad
 
 
+def result_violations(asm_text, need=12):
+    """Hazard 2: (index, toucher, mfma) for every instruction that touches an unfinished result."""
+    ins = list(instructions(asm_text))
+    bad = []
+    for i, (op, ops) in enumerate(ins):
+        if not op.startswith("v_mfma"):
+            continue
+        dst = regs(ops[0])
+        slots = 0
+        for j in range(i + 1, len(ins)):
+            nop, nops = ins[j]
+            if nop.startswith("v_mfma"):
+                same_acc = regs(nops[0]) == dst and regs(nops[-1]) == dst
+                srcs = set().union(*[regs(o) for o in nops[1:3]])
+                if (srcs & dst) or (not same_acc and (regs(nops[0]) | regs(nops[-1])) & dst):
+                    bad.append((i, " ".join([nop] + nops), " ".join([op] + ops)))
+                slots += 8
+            elif nop == "s_nop":
+                slots += int(nops[0], 0) + 1
+            else:
+                touched = set().union(*[regs(o) for o in nops]) if nops else set()
+                if touched & dst:
+                    bad.append((i, " ".join([nop] + nops), " ".join([op] + ops)))
+                slots += 1
+            if slots >= need:
+                break
+    return bad
+
+
 def test_parser_flags_a_planted_hazard():
     planted = """
     v_accvgpr_write_b32 a4, v9
@@ -78,6 +111,20 @@ def test_parser_flags_a_planted_hazard():
     assert violations(padded) == []
     far = planted.replace("s_mov_b32 s0, 1", "s_mov_b32 s0, 1\n v_add_u32 v100, v101, v102")
     assert violations(far) == []
+    early = """
+    v_mfma_f32_32x32x16_bf16 a[64:79], v[2:5], v[22:25], a[64:79]
+    ds_read_b128 v[2:5], v100
+    v_accvgpr_mov_b32 a48, a64
+    """
+    assert len(result_violations(early)) == 1
+    chained = """
+    v_mfma_f32_32x32x16_bf16 a[64:79], v[2:5], v[22:25], a[64:79]
+    v_mfma_f32_32x32x16_bf16 a[64:79], v[6:9], v[22:25], a[64:79]
+    v_mfma_f32_32x32x16_bf16 a[0:15], v[6:9], v[22:25], a[0:15]
+    v_mfma_f32_32x32x16_bf16 a[16:31], v[6:9], v[22:25], a[16:31]
+    v_accvgpr_mov_b32 a48, a64
+    """
+    assert result_violations(chained) == []
 
 
 @pytest.mark.parametrize("name", HAND_SCHEDULED)
@@ -92,3 +139,5 @@ def test_no_valu_write_feeds_next_matrix_instruction(name):
     assert text.count("v_mfma") > 100, "expected the matrix-core kernels in the assembly"
     bad = violations(text)
     assert not bad, f"{len(bad)} VALU->MFMA hazards, first: {bad[:3]}"
+    bad = result_violations(text)
+    assert not bad, f"{len(bad)} touches of unfinished matrix-core results, first: {bad[:3]}"
