@@ -51,8 +51,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   constexpr int NH = 3 * NDB;                      // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
   constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
-  constexpr int NBLK = 2 * NS + 4 * NH;            // products of a block
-  constexpr int NPRE = 2 * NBLK - NH;              // products of a tile before its barrier: the tile after next is fetched behind them
+  // the tile after next is fetched behind the products of the phases that carry no pointwise work:
+  // S and OK(1) of both blocks (the last of them behind the tile's barrier)
+  constexpr int NQB = NS + NH;                     // such products per block
+  constexpr int NDMA_PRE = (2 * NQB - NH) * NDMA / (2 * NQB);  // wave-loads issued before the barrier
   // register files: the accumulators fill 4*NDB*16 AGPRs; K, tK fragments always fit beside them,
   // V and tV fragments where there is room, else they stay in VGPRs
   constexpr bool V_IN_A = 64 * NDB + 12 * NKS <= 256, TV_IN_A = 64 * NDB + 16 * NKS <= 256;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else da[x - 8] = lds_read_f4(rv, 512 + ib * 128 + (x - 8) * 32);
         }
 #pragma unroll
-        TVM_SHARE(x, ib * NBLK + m, NDMA, NPRE) dma(x, in2, sbf);
+        TVM_SHARE(x, ib * NQB + m, NDMA, 2 * NQB) dma(x, in2, sbf);
       }
       PROF(0);
       // ---- E, with P, N, Pd of half 0.  E and DF start from -sig1 and -dsig of their rows (queries).
@@ -216,8 +218,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
           else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
         }
-#pragma unroll
-        TVM_SHARE(x, ib * NBLK + NS + m, NDMA, NPRE) dma(x, in2, sbf);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NS) {  // G^T, tG^T of half 0
           const int db = x >> 1;
@@ -247,8 +247,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         else if (w == 1) mfma_acc<RAG>(aV[db], txT[db], frag_of(pdk, 0));
         else mfma_acc<RAG>(aTV[db], txT[db], frag_of(pk, 0));
 #pragma unroll
-        TVM_SHARE(x, ib * NBLK + 2 * NS + m, NDMA, NPRE) dma(x, in2, sbf);
-#pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // G^T, tG^T of half 1
           const int d2 = x >> 1;
           if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
@@ -265,8 +263,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], yT[db], frag_of(pk, 1)); else mfma_acc<RAG>(aV[db], yT[db], frag_of(pk, 1)); }
         else if (w == 1) mfma_acc<RAG>(aV[db], tyT[db], frag_of(pdk, 1));
         else mfma_acc<RAG>(aTV[db], tyT[db], frag_of(pk, 1));
-#pragma unroll
-        TVM_SHARE(x, ib * NBLK + 2 * NS + NH + m, NDMA, NPRE) dma(x, in2, sbf);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
@@ -286,8 +282,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         else if (w == 1) mfma_acc<RAG>(aK[db], txT[db], frag_of(gzt, 0));
         else mfma_acc<RAG>(aTK[db], xT[db], frag_of(gzt, 0));
 #pragma unroll
-        TVM_SHARE(x, ib * NBLK + 2 * NS + 2 * NH + m, NDMA, NPRE) dma(x, in2, sbf);
-#pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 1
           const int d2 = x >> 1;
           if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, tr_imm(1, d2));
@@ -301,7 +295,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         // every read of this stage has been issued; the next tile (fetched during the previous one) must
         // have landed before anyone goes on, the loads of the tile after next stay in flight
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        dma_wait_keep<NDMA>();
+        dma_wait_keep<NDMA_PRE>();
         __syncthreads();
       }
       PROF(5);
@@ -312,10 +306,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         if (w == 0) { if (m == 0) mfma_acc<true>(aK[db], yT[db], frag_of(gz, 1)); else mfma_acc<RAG>(aK[db], yT[db], frag_of(gz, 1)); }
         else if (w == 1) mfma_acc<RAG>(aK[db], tyT[db], frag_of(gzt, 1));
         else mfma_acc<RAG>(aTK[db], yT[db], frag_of(gzt, 1));
-        if (ib == 0) {
 #pragma unroll
-          TVM_SHARE(x, 2 * NS + 3 * NH + m, NDMA, NPRE) dma(x, in2, sbf);
-        }
+        TVM_SHARE(x, ib * NQB + NS + m, NDMA, 2 * NQB) dma(x, in2, sbf);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NKS, NH) {  // Q, tQ rows of the next block
           const int k2 = x % NKS;

@@ -49,7 +49,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   constexpr int NH = 3 * NDB;                         // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
-  constexpr int NPRE = 4 * NS + 3 * NH;               // products of a tile before its barrier: the tile after next is fetched behind them
+  // the tile after next is fetched behind the products of the phases that carry no pointwise work:
+  // S(0), O(0) half 0, O(1) half 0 (before the barrier) and O(1) half 1 (behind it)
+  constexpr int NQUIET = NS + 3 * NH;
+  constexpr int NDMA_PRE = (NS + 2 * NH) * NDMA / NQUIET;  // wave-loads issued before the barrier
   PROF_ENTRY;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int nfb = (s.N + kFix - 1) / kFix;
@@ -234,15 +237,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         else rd[kk] = lds_read16((kk & 1) ? vo : ve, TV::BYTES + kk * 32);
       }
 #pragma unroll
-      TVM_SHARE(x, m, NDMA, NPRE) dma(x, jn2, sbf);
+      TVM_SHARE(x, m, NDMA, NQUIET) dma(x, jn2, sbf);
     }
     PROF(0);
     // ---- E(0), with P, N of block 0
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
       e_product(m);
-#pragma unroll
-      TVM_SHARE(x, NS + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NS) {  // S-fragments of block 1
         const int kk = x % NKS;
@@ -264,8 +265,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NS; ++m) {
       s_product(m);
 #pragma unroll
-      TVM_SHARE(x, 2 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
-#pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NS) {  // E-fragments of block 1
         const int kk = x % NKS;
         if (x < NKS) rc[kk] = lds_read16((kk & 1) ? vo : ve, TV::kBlkBytes + kk * 32);
@@ -285,8 +284,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
     for (int m = 0; m < NS; ++m) {
       e_product(m);
-#pragma unroll
-      TVM_SHARE(x, 3 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NS) {  // transposed K, tK of block 0, half 0
         const int db = x >> 1;
@@ -308,7 +305,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz0, gzt0);
 #pragma unroll
-      TVM_SHARE(x, 4 * NS + m, NDMA, NPRE) dma(x, jn2, sbf);
+      TVM_SHARE(x, NS + m, NDMA, NQUIET) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 0, half 1
         const int db = x >> 1;
@@ -320,8 +317,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
     for (int m = 0; m < NH; ++m) {
       o_product(m, 1, yT, tyT, gz0, gzt0);
-#pragma unroll
-      TVM_SHARE(x, 4 * NS + NH + m, NDMA, NPRE) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 0
         const int db = x >> 1;
@@ -339,7 +334,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz1, gzt1);
 #pragma unroll
-      TVM_SHARE(x, 4 * NS + 2 * NH + m, NDMA, NPRE) dma(x, jn2, sbf);
+      TVM_SHARE(x, NS + NH + m, NDMA, NQUIET) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 1
         const int db = x >> 1;
@@ -350,13 +345,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     // every read of this stage has been issued; the next tile (fetched during the previous one) must have
     // landed before anyone goes on, the loads of the tile after next stay in flight
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    dma_wait_keep<NDMA>();
+    dma_wait_keep<NDMA_PRE>();
     __syncthreads();
     PROF(5);
     // ---- O(1), half 1
 #pragma unroll
     for (int m = 0; m < NH; ++m) {
       o_product(m, 1, yT, tyT, gz1, gzt1);
+#pragma unroll
+      TVM_SHARE(x, NS + 2 * NH + m, NDMA, NQUIET) dma(x, jn2, sbf);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NH) {  // S-fragments of the next tile's block 0
         const int kk = x % NKS;
