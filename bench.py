@@ -35,12 +35,12 @@ KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.
 # figures and commands in profiles/tvmattn_kernels_C4_counters.md.  None where not measured.
 _KIB = 1024.0
 MEASURED_TRAFFIC = {
-    ("C4", "fwd"): 110659.6 * _KIB * 2.0 + 75777.2 * _KIB,
-    ("C4", "bwd_row"): 185473.9 * _KIB * 2.0 + 75776.0 * _KIB,
-    ("C4", "bwd_col"): 149662.9 * _KIB * 2.0 + 147456.0 * _KIB,
-    ("C3", "fwd"): 55371.4 * _KIB * 2.0 + 37897.3 * _KIB,
-    ("C3", "bwd_row"): 92780.0 * _KIB * 2.0 + 37888.0 * _KIB,
-    ("C3", "bwd_col"): 74909.5 * _KIB * 2.0 + 73728.0 * _KIB,
+    ("C4", "fwd"): 110658.8 * _KIB * 2.0 + 75778.5 * _KIB,
+    ("C4", "bwd_row"): 185468.6 * _KIB * 2.0 + 76800.0 * _KIB,
+    ("C4", "bwd_col"): 149644.4 * _KIB * 2.0 + 147456.0 * _KIB,
+    ("C3", "fwd"): 55376.0 * _KIB * 2.0 + 37903.8 * _KIB,
+    ("C3", "bwd_row"): 92795.7 * _KIB * 2.0 + 38400.0 * _KIB,
+    ("C3", "bwd_col"): 74892.0 * _KIB * 2.0 + 73728.0 * _KIB,
 }
 
 
