@@ -68,6 +68,15 @@ def test_bf16_mfma_small(B, H, N, d):
     run_case(wl.custom(B, H, N, d, "bf16"), seed=5)
 
 
+@pytest.mark.parametrize("d", [8, 24, 40, 64, 72, 96])
+def test_bf16_hand_scheduled_tile_boundaries(d):
+    """Every instantiation of the hand-scheduled backward kernels (one per padded head dim) at the
+    sequence lengths where their tile pipeline changes shape: less than a tile, exactly one, two
+    and three tiles (the three LDS stages wrap), one row more or fewer, a workgroup boundary."""
+    for N in (17, 63, 64, 65, 127, 128, 129, 191, 192, 193, 320):
+        run_case(wl.custom(1, 1, N, d, "bf16"), seed=20 + N % 7)
+
+
 def test_bf16_mfma_scaled_inputs():
     # C4's small tangents and C5's sharpened keys at a size the oracle does in full
     run_case(wl.custom(1, 2, 384, 72, "bf16", tangent_std=0.1), seed=6)
