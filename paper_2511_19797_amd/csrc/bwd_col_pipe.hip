@@ -87,8 +87,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const typename TX::RAddr ra = TX::raddr(ic, hh);
   const typename TX::TAddr ta = TX::taddr(ic, hh);
   // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
-  // barrier anyway), then the fixed-side fragments (scattered loads), then the first part of tile 1
-  // (the second stage is free from the start).
+  // barrier anyway), then the fixed-side fragments (scattered loads), then, once those have arrived, tile 1.
   const int nt = (s.N + 63) >> 6;   // tiles
   const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
@@ -98,8 +97,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
-#pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, min(64, ilast), lds0 + BUF);
   PROF_P(11);
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
 #pragma unroll
@@ -114,8 +111,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
 
   PROF_P(14);
-  dma_wait();
+  dma_wait();  // tile 0 and this wave's fixed rows
   PROF_P(12);
+  // tile 1 goes into the second stage now (any earlier and the waits for the fixed rows, which count
+  // outstanding loads, would also wait for it); it lands while tile 0 is computed
+#pragma unroll
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, ilast), lds0 + BUF);
   __syncthreads();  // tile 0 has landed
   PROF_P(15);
   bf16x8 rq[NKS], rtq[NKS];  // Q, tQ rows of the block whose S phase comes next

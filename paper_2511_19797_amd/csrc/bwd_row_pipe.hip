@@ -80,8 +80,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const typename TV::RAddr rv = TV::raddr(ic, hh);
   const typename TK::TAddr ta = TK::taddr(ic, hh);
   // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
-  // barrier anyway), then this lane's row scalars and fixed-side fragments (scattered loads), then
-  // the first part of tile 1 (the second stage is free from the start).
+  // barrier anyway), then this lane's row scalars and fixed-side fragments (scattered loads), then, once those have arrived, tile 1.
   const int nt = (s.N + 63) >> 6;      // tiles
   const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
@@ -97,8 +96,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
   gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
-#pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, min(64, jlast), lds0 + BUF);
   PROF_P(11);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row), two
@@ -146,7 +143,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const float alphau = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s.alpha)));
 
   PROF_P(14);
-  dma_wait();
+  dma_wait();  // tile 0 and this wave's fixed rows
+  // tile 1 goes into the second stage now (any earlier and the waits for the fixed rows, which count
+  // outstanding loads, would also wait for it); it lands while tile 0 is computed
+#pragma unroll
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, jlast), lds0 + BUF);
   __syncthreads();  // tile 0 has landed
   PROF_P(15);
   bf16x8 ra[NKS], rb[NKS];  // S-fragments (K, tK rows) of the block whose S phase comes next
