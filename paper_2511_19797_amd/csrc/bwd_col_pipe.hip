@@ -9,13 +9,19 @@
 // each), which is what lets the pointwise work trail the products by half a block:
 //
 //   phase     products (matrix cores)            in their shadow
-//   S         S, St                              G, tG rows and lse, stats of the block <- LDS
-//   E         E, DF                              P, N, Pd of half 0;  G^T, tG^T of half 0 <- LDS;  dsig, sig1 <- LDS
+//   S         S, St                              G, tG rows <- LDS;  lse, stats (half 0), -sig1, -dsig <- LDS;  tile loads
+//   E         E, DF (from -sig1, -dsig)          P, N, Pd of half 0;  G^T, tG^T of half 0 <- LDS;  lse, stats (half 1) <- LDS
 //   OV(0)     dV, dtV += (P, Pd of half 0) .     P, N, Pd of half 1;  G^T, tG^T of half 1 <- LDS
 //   OV(1)     dV, dtV += (P, Pd of half 1) .     gZ, gZt of half 0;   Q^T, tQ^T of half 0 <- LDS
 //   OK(0)     dK, dtK += (gZ, gZt of half 0) .   gZ, gZt of half 1;   Q^T, tQ^T of half 1 <- LDS
-//   -- after the tile's second block: all reads of this buffer are done; wait for the next tile, barrier --
+//   -- after the tile's second block: all reads of this buffer are done; the next tile must have landed, barrier --
 //   OK(1)     dK, dtK += (gZ, gZt of half 1) .   Q, tQ rows of the next block <- LDS;  tile loads
+//
+// The row scalars come from the workspace as the hand-scheduled query-side kernel leaves them:
+// lse in log2 units, and sig1, dsig negated, so that the E and DF tiles can start from them (the C
+// operand of their first product) and gZt = P E, gZ = P DF + gZt N need no subtraction.
+// Three LDS stages: tile t in use, tile t+1 landed (it was fetched during tile t-1), tile t+2 being
+// fetched, one wave-load every few products and only in the phases without pointwise work.
 //
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"

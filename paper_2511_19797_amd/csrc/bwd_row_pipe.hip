@@ -10,13 +10,20 @@
 // before its data is needed:
 //
 //   phase        products (matrix cores)              in their shadow
-//   S(0)         S, St of block 0                     E-fragments of block 0 <- LDS; loads of tile t+1, 2nd half
+//   S(0)         S, St of block 0                     E-fragments of block 0 <- LDS;  tile loads
 //   E(0)         E, DF of block 0                     P, N of block 0;  S-fragments of block 1 <- LDS
 //   S(1)         S, St of block 1                     gZ, gZt of block 0;  E-fragments of block 1 <- LDS
-//   E(1)         E, DF of block 1                     P, N of block 1;  transposed K, tK of block 0 <- LDS
-//   O(0)         dQ, dtQ += (gZ, gZt of block 0) .    gZ, gZt of block 1;  transposed K, tK of block 1 <- LDS
-//   -- all reads of this tile's buffer are done: wait for tile t+1, workgroup barrier --
-//   O(1)         dQ, dtQ += (gZ, gZt of block 1) .    S-fragments of tile t+1 <- LDS; loads of tile t+2, 1st half
+//   E(1)         E, DF of block 1                     P, N of block 1;  K^T, tK^T of block 0, half 0 <- LDS
+//   O(0) half 0  dQ, dtQ += (gZ, gZt of block 0) .    K^T, tK^T of block 0, half 1 <- LDS;  tile loads
+//   O(0) half 1                                       gZ, gZt of block 1;  K^T, tK^T of block 1, half 0 <- LDS
+//   O(1) half 0  dQ, dtQ += (gZ, gZt of block 1) .    K^T, tK^T of block 1, half 1 <- LDS;  tile loads
+//   -- all reads of this tile's buffer are done: the next tile must have landed, workgroup barrier --
+//   O(1) half 1                                       S-fragments of tile t+1 <- LDS;  tile loads
+//
+// "half" = contraction half of an output product (16 keys).  E and DF start from constant tiles
+// holding -sig1 and -dsig of the lane's query, so gZt = P E, gZ = P DF + gZt N need no subtraction.
+// Three LDS stages: tile t in use, tile t+1 landed (it was fetched during tile t-1), tile t+2 being
+// fetched, one wave-load every few products and only in the phases without pointwise work.
 //
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"
