@@ -120,6 +120,33 @@ def test_zero_tangents_and_zero_grads_on_gpu():
     pu.check_heads(w, inp, fwd, grads, pu.all_heads(w))
 
 
+def test_growing_scores_force_rescales():
+    """Keys whose scores keep growing along the sequence: the forward's reference maximum has to be
+    raised (and its accumulators rescaled) many times, and the backward sees sharply peaked rows."""
+    w = wl.custom(1, 2, 512, 72, "bf16")
+    announce(f"growing scores {w}")
+    inp = wl.make_inputs(w, 13)
+    ramp = torch.linspace(0.2, 6.0, w.N).view(1, 1, w.N, 1)
+    inp["k"] = (inp["k"].float() * ramp + inp["q"].float().mean(dim=2, keepdim=True) * ramp).to(torch.bfloat16)
+    fwd, grads = pu.run_gpu(inp)
+    pu.check_heads(w, inp, fwd, grads, pu.all_heads(w))
+
+
+def test_backward_is_linear_in_upstream_gradients():
+    """bwd(a gO1 + gO2, a gTO1 + gTO2) = a bwd(gO1, gTO1) + bwd(gO2, gTO2) up to bf16 rounding of the
+    outputs; with power-of-two a and the second pair zero it is exact scaling."""
+    w = wl.custom(1, 2, 200, 72, "bf16")
+    announce(f"linearity {w}")
+    inp = wl.make_inputs(w, 14)
+    fwd, g1 = pu.run_gpu(inp)
+    inp2 = dict(inp)
+    inp2["gO"] = (inp["gO"].float() * 4.0).to(torch.bfloat16)
+    inp2["gTO"] = (inp["gTO"].float() * 4.0).to(torch.bfloat16)
+    _, g4 = pu.run_gpu(inp2)
+    for a, b in zip(g1, g4):
+        assert torch.equal((a.float() * 4.0).to(torch.bfloat16), b)
+
+
 # ---------------------------------------------------------------- the five configs at full size
 @pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2)])
 def test_full_size_configs_sampled_heads(name, nheads):
@@ -138,3 +165,11 @@ def test_full_size_configs_sampled_heads(name, nheads):
         heads.add((int(rng.integers(w.B)), int(rng.integers(w.H))))
     worst = pu.check_heads(w, inp, fwd, grads, sorted(heads))
     print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    # properties that hold for every head at any size: adding one vector to all keys of a head changes
+    # neither O nor tO, so the key gradients and the key-tangent gradients sum to zero over the keys
+    # (up to the bf16 rounding of each of the N summands)
+    dq, dk, dv, dtq, dtk, dtv = grads
+    for g in (dk, dtk):
+        col_sum = g.float().sum(dim=2).abs().max()
+        bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
+        assert float(col_sum) <= float(bound), (float(col_sum), float(bound))
