@@ -93,8 +93,9 @@ int tvmattn_set_path(int path);
  * or points to four hipEvent_t handles created by the caller with timing enabled; while set,
  * every tvmattn_jvp_bwd call records, on its stream, events[0] before its first launch,
  * events[1] after the row-scalar kernel (a separate launch only on the plain-ALU path),
- * events[2] after the query-side kernel and events[3] after the key-side kernel.  The four
- * handles are copied; the array need not outlive the call.
+ * events[2] after the query-side kernel and events[3] after the key-side kernel.  A NULL
+ * handle among the four skips that record.  The four handles are copied; the array need not
+ * outlive the call.
  */
 int tvmattn_set_bwd_events(void* const* events);
 

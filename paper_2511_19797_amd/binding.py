@@ -70,11 +70,12 @@ def tvmattn_set_path(path):
 
 
 def tvmattn_set_bwd_events(events):
-    """`events`: None, or four raw hipEvent_t handles (ints) created with timing enabled."""
+    """`events`: None, or four raw hipEvent_t handles (ints, created with timing enabled; None or 0
+    skips that record)."""
     if events is None:
         _check(lib().tvmattn_set_bwd_events(None))
     else:
-        arr = (_P * 4)(*[_P(int(e)) for e in events])
+        arr = (_P * 4)(*[_P(int(e)) if e else _P(None) for e in events])
         _check(lib().tvmattn_set_bwd_events(arr))
 
 

@@ -12,7 +12,7 @@ hipEvent_t g_ev[4];
 bool g_ev_on = false;
 
 inline void mark(int i, hipStream_t st) {
-  if (g_ev_on) (void)hipEventRecord(g_ev[i], st);
+  if (g_ev_on && g_ev[i]) (void)hipEventRecord(g_ev[i], st);
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -86,13 +86,7 @@ int tvmattn_set_path(int path) {
 int tvmattn_set_bwd_events(void* const* events) {
   g_ev_on = events != nullptr;
   if (events)
-    for (int i = 0; i < 4; ++i) {
-      if (!events[i]) {
-        g_ev_on = false;
-        return TVMATTN_INVALID_ARG;
-      }
-      g_ev[i] = static_cast<hipEvent_t>(events[i]);
-    }
+    for (int i = 0; i < 4; ++i) g_ev[i] = static_cast<hipEvent_t>(events[i]);  // NULL: that record is skipped
   return TVMATTN_OK;
 }
 
