@@ -56,6 +56,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   constexpr int NS = 3 * NKS;                      // products of a score-type phase
   constexpr int NH = 3 * NDB;                      // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
+  // the 48 pieces of P, N, Pd of a block are dealt out over the products of E (from FS on) and OV(0) in
+  // proportion, but half 0 (the first 24) must be complete when OV(0) starts
+  constexpr int PW1_PROP = (48 * (NS - FS) + NS - FS + NH - 1) / (NS - FS + NH);
+  constexpr int PW1_E = PW1_PROP > 24 ? PW1_PROP : 24;
   constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
   // the tile after next is fetched behind the products of the phases that carry no pointwise work:
   // S and OK(1) of both blocks (the last of them behind the tile's barrier)
@@ -65,7 +69,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   // V and tV fragments where there is room, else they stay in VGPRs
   constexpr bool V_IN_A = 64 * NDB + 12 * NKS <= 256, TV_IN_A = 64 * NDB + 16 * NKS <= 256;
   PROF_ENTRY;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
   const int nfb = (s.N + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
@@ -74,30 +79,41 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const long long rbase = (long long)bh * s.N;
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
 
-  const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
   const unsigned lds0 = lds_addr_of(lds);
-  // wave w also fetches row vector w (lse in log2 units, stats, dsig, sig1) of the tile, one float per
-  // lane (lanes past the last row re-read the last row's value: masked rows, unused)
+  const int nt = (s.N + 63) >> 6;   // tiles
+  const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
+  // Per-lane byte offsets of this wave's loads within a tile, worked out once: for whole tiles, and for
+  // the last tile, where rows past the end fetch its last row again (masked rows, unused).  Wave w also
+  // fetches row vector w (lse in log2 units, stats, dsig, sig1) of the tile, one float per lane.
+  typename TX::Offs of_full, of_last;
+  unsigned rv_full, rv_last;
+  {
+    const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
+    of_full = TX::offsets(lx, pitch, 64);
+    of_last = TX::offsets(lx, pitch, s.N - ilast);
+    rv_full = (unsigned)lane * 4u;
+    rv_last = (unsigned)min(lane, s.N - ilast - 1) * 4u;
+  }
   const float* const rowsrc = (wave == 0 ? lse2w : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
-  // wave-load number x (compile-time) of the tile whose first query is i0 (< N), into the stage at `buf`
-  auto dma = [&](int x, int i0, unsigned buf) {
+  // wave-load number x (compile-time) of the tile whose first query is i0 (< N), into the stage at `buf`;
+  // `last`: that tile is the last one
+  auto dma = [&](int x, int i0, unsigned buf, bool last) {
     const long long ro = base + (long long)i0 * s.sn;
-    const int left = s.N - i0;
-    if (x < TX::IPW) TX::issue_one(lx, x, q + ro, pitch, left, buf, wave);
-    else if (x < 2 * TX::IPW) TX::issue_one(lx, x - TX::IPW, tq + ro, pitch, left, buf + OFF_TQ, wave);
-    else if (x < 3 * TX::IPW) TX::issue_one(lx, x - 2 * TX::IPW, gO + ro, pitch, left, buf + OFF_G, wave);
-    else if (x < 4 * TX::IPW) TX::issue_one(lx, x - 3 * TX::IPW, gTO + ro, pitch, left, buf + OFF_TG, wave);
-    else dma_to_lds<4>(rowsrc + i0, (unsigned)min(lane, left - 1) * 4u, buf + OFF_ROW + wave * 256);
+    const int t = x % TX::IPW;
+    const unsigned off = last ? of_last.o[t] : of_full.o[t];
+    if (x < TX::IPW) TX::issue_at(off, t, q + ro, buf, wave);
+    else if (x < 2 * TX::IPW) TX::issue_at(off, t, tq + ro, buf + OFF_TQ, wave);
+    else if (x < 3 * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
+    else if (x < 4 * TX::IPW) TX::issue_at(off, t, gTO + ro, buf + OFF_TG, wave);
+    else dma_to_lds<4>(rowsrc + i0, last ? rv_last : rv_full, buf + OFF_ROW + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
   const typename TX::TAddr ta = TX::taddr(ic, hh);
   // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
   // barrier anyway), then the fixed-side fragments (scattered loads), then, once those have arrived, tile 1.
-  const int nt = (s.N + 63) >> 6;   // tiles
-  const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
+  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
   gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
@@ -122,7 +138,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   // tile 1 goes into the second stage now (any earlier and the waits for the fixed rows, which count
   // outstanding loads, would also wait for it); it lands while tile 0 is computed
 #pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, min(64, ilast), lds0 + BUF);
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, ilast), lds0 + BUF, nt <= 2);
   __syncthreads();  // tile 0 has landed
   PROF_P(15);
   bf16x8 rq[NKS], rtq[NKS];  // Q, tQ rows of the block whose S phase comes next
@@ -137,8 +153,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   // One tile.  RAG: queries beyond N exist in this tile (only ever the last one).
   //   sb / sbn / sbf: LDS address of this tile's stage / of the next tile's (landed) / of the free one, into
   //   which the tile after next is fetched, one wave-load every few products;  i0: first query;
-  //   in2: first query of the tile after next (clamped to the last tile).
-  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int i0, int in2, bool last) {
+  //   in2: first query of the tile after next (clamped to the last tile);  in2last: that is the last tile.
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int i0, int in2, bool in2last, bool last) {
     constexpr bool RAG = decltype(rag)::value;
     const unsigned re = sb + ra.e, ro = sb + ra.o;        // rows of Q; tQ, G, tG at + OFF_*
     const unsigned tl = sb + ta.lo, th = sb + ta.hi;      // transposed
@@ -155,21 +171,37 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       unsigned pk[8], pdk[8], gz[8], gzt[8];
       bf16x8 xT[NDB], txT[NDB], yT[NDB], tyT[NDB];  // transposed fragments of the half in use / of the next half
 
-      // P, N, Pd of elements 2e, 2e+1
-      auto pw1 = [&](int e) {
-        const int g4 = e >> 1, t = (2 * e) & 3;
-        float s0 = sS[2 * e], s1 = sS[2 * e + 1];
-        if (RAG) {  // queries beyond N: probability 0
-          if (i0 + ib * 32 + drow(2 * e, hh) >= s.N) s0 = -INFINITY;
-          if (i0 + ib * 32 + drow(2 * e + 1, hh) >= s.N) s1 = -INFINITY;
+      float ta[8], tb[8], wa[8], wb[8];  // temporaries of element pair e, alive between its pieces
+      // P, N, Pd of the block as a stream of 8 x 6 pieces (pair e = u / 6: elements 2e, 2e+1)
+      auto pw1_op = [&](int u) {
+        const int e = u / 6, st = u - 6 * e, g4 = e >> 1, t = (2 * e) & 3;
+        if (st == 0) {
+          float s0 = sS[2 * e], s1 = sS[2 * e + 1];
+          if (RAG) {  // queries beyond N: probability 0
+            if (i0 + ib * 32 + drow(2 * e, hh) >= s.N) s0 = -INFINITY;
+            if (i0 + ib * 32 + drow(2 * e + 1, hh) >= s.N) s1 = -INFINITY;
+          }
+          pw_fma2(ta[e], tb[e], s0, s1, c1u, f4(la[g4], t), f4(la[g4], t + 1));
+        } else if (st == 1) {
+          pw_exp_fma(pp[2 * e], ta[e], nn[2 * e], sT[2 * e], alphau, f4(ma[g4], t));
+        } else if (st == 2) {
+          pw_exp_fma(pp[2 * e + 1], tb[e], nn[2 * e + 1], sT[2 * e + 1], alphau, f4(ma[g4], t + 1));
+        } else if (st == 3) {
+          pw_mul2(ta[e], tb[e], pp[2 * e], nn[2 * e], pp[2 * e + 1], nn[2 * e + 1]);
+        } else if (st == 4) {
+          pw_cvt(pk[e], pp[2 * e], pp[2 * e + 1]);
+        } else {
+          pw_cvt(pdk[e], ta[e], tb[e]);
         }
-        pw1_pair_asm(pp[2 * e], pp[2 * e + 1], nn[2 * e], nn[2 * e + 1], pk[e], pdk[e], s0, s1, sT[2 * e],
-                     sT[2 * e + 1], c1u, f4(la[g4], t), f4(la[g4], t + 1), alphau, f4(ma[g4], t), f4(ma[g4], t + 1));
       };
-      // gZ, gZt of elements 2e, 2e+1 (E, DF come with sig1, dsig already subtracted)
-      auto pw2 = [&](int e) {
-        pw2_shifted_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e],
-                             pp[2 * e + 1], nn[2 * e], nn[2 * e + 1]);
+      // gZ, gZt of the block as a stream of 8 x 5 pieces (E, DF come with sig1, dsig already subtracted)
+      auto pw2_op = [&](int u) {
+        const int e = u / 5, st = u - 5 * e;
+        if (st == 0) pw_mul2(ta[e], tb[e], pp[2 * e], sE[2 * e], pp[2 * e + 1], sE[2 * e + 1]);
+        else if (st == 1) pw_mul2(wa[e], wb[e], pp[2 * e], sDF[2 * e], pp[2 * e + 1], sDF[2 * e + 1]);
+        else if (st == 2) pw_fmac2(wa[e], wb[e], ta[e], nn[2 * e], tb[e], nn[2 * e + 1]);
+        else if (st == 3) pw_cvt(gzt[e], ta[e], tb[e]);
+        else pw_cvt(gz[e], wa[e], wb[e]);
       };
       auto tr_imm = [&](int cc, int db) { return (2 * ib + cc) * 16 * TX::PCH * 16 + db * 64; };
 
@@ -201,7 +233,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else da[x - 8] = lds_read_f4(rv, 512 + ib * 128 + (x - 8) * 32);
         }
 #pragma unroll
-        TVM_SHARE(x, ib * NQB + m, NDMA, 2 * NQB) dma(x, in2, sbf);
+        TVM_SHARE(x, ib * NQB + m, NDMA, 2 * NQB) dma(x, in2, sbf, in2last);
       }
       PROF(0);
       // ---- E, with P, N, Pd of half 0.  E and DF start from -sig1 and -dsig of their rows (queries).
@@ -231,10 +263,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, OFF_G + tr_imm(0, db));
           else txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
         }
+        if (m < FS) {
 #pragma unroll
-        TVM_SHARE(x, m, 4, NS) {  // lse, stats of half 1
-          if (x < 2) la[2 + x] = lds_read_f4(rv, ib * 128 + (2 + x) * 32);
-          else ma[x] = lds_read_f4(rv, 256 + ib * 128 + x * 32);
+          TVM_SHARE(x, m, 4, FS) {  // lse, stats of half 1
+            if (x < 2) la[2 + x] = lds_read_f4(rv, ib * 128 + (2 + x) * 32);
+            else ma[x] = lds_read_f4(rv, 256 + ib * 128 + x * 32);
+          }
         }
         if (m == FS) {
           if (NS < 6) mfma_settle();
@@ -242,7 +276,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         }
         if (m >= FS) {
 #pragma unroll
-          TVM_SHARE(e, m - FS, 4, NS - FS) pw1(e);
+          TVM_SHARE(u, m - FS, PW1_E, NS - FS) pw1_op(u);
         }
       }
       PROF(1);
@@ -260,7 +294,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
         }
 #pragma unroll
-        TVM_SHARE(e, m, 4, NH) pw1(4 + e);
+        TVM_SHARE(u, m, 48 - PW1_E, NH) pw1_op(PW1_E + u);
       }
       PROF(2);
       // ---- OV(1), with gZ, gZt of half 0
@@ -278,7 +312,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         }
         if (m == 0) landed(sE, sDF);  // at least four products after the last one of E
 #pragma unroll
-        TVM_SHARE(e, m, 4, NH) pw2(e);
+        TVM_SHARE(u, m, 20, NH) pw2_op(u);
       }
       PROF(3);
       // ---- OK(0), with gZ, gZt of half 1
@@ -295,7 +329,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(1, d2));
         }
 #pragma unroll
-        TVM_SHARE(e, m, 4, NH) pw2(4 + e);
+        TVM_SHARE(u, m, 20, NH) pw2_op(20 + u);
       }
       PROF(4);
       if (ib == 1) {
@@ -314,7 +348,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         else if (w == 1) mfma_acc<RAG>(aK[db], tyT[db], frag_of(gzt, 1));
         else mfma_acc<RAG>(aTK[db], yT[db], frag_of(gzt, 1));
 #pragma unroll
-        TVM_SHARE(x, ib * NQB + NS + m, NDMA, 2 * NQB) dma(x, in2, sbf);
+        TVM_SHARE(x, ib * NQB + NS + m, NDMA, 2 * NQB) dma(x, in2, sbf, in2last);
 #pragma unroll
         TVM_SHARE(x, m, 2 * NKS, NH) {  // Q, tQ rows of the next block
           const int k2 = x % NKS;
@@ -339,13 +373,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const int nfull = s.N >> 6;  // tiles without queries beyond N
   unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
   for (int t = 0; t < nfull; ++t) {
-    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, ilast), t + 1 == nt);
+    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, ilast), t + 3 >= nt, t + 1 == nt);
     const unsigned r0 = st0;
     st0 = st1;
     st1 = st2;
     st2 = r0;
   }
-  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, ilast, true);
+  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, ilast, true, true);
   dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
   __syncthreads();
   PROF_DUMP;

@@ -55,13 +55,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   constexpr int NS = 3 * NKS;                         // products of a score-type phase
   constexpr int NH = 3 * NDB;                         // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
+  constexpr int P2S = NH > 3 ? 3 : NH;                // first product of O(0) behind which gZ, gZt of block 1 are made
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
   // the tile after next is fetched behind the products of the phases that carry no pointwise work:
   // S(0), O(0) half 0, O(1) half 0 (before the barrier) and O(1) half 1 (behind it)
   constexpr int NQUIET = NS + 3 * NH;
   constexpr int NDMA_PRE = (NS + 2 * NH) * NDMA / NQUIET;  // wave-loads issued before the barrier
   PROF_ENTRY;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
   const int nfb = (s.N + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
@@ -70,28 +72,45 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
   const bool iok = i < s.N;
 
-  const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
-  const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
   const unsigned lds0 = lds_addr_of(lds);
-  // wave-load number x (compile-time) of the tile whose first key is j0 (< N), into the stage at `buf`
-  auto dma = [&](int x, int j0, unsigned buf) {
+  const int nt = (s.N + 63) >> 6;      // tiles
+  const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
+  // Per-lane byte offsets of this wave's loads within a tile, worked out once: for whole tiles, and for
+  // the last tile, where rows past the end fetch its last row again (keys of probability 0)
+  typename TK::Offs ok_full, ok_last;
+  typename TV::Offs ov_full, ov_last;
+  {
+    const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
+    const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
+    ok_full = TK::offsets(lk, pitch, 64);
+    ok_last = TK::offsets(lk, pitch, s.N - jlast);
+    ov_full = TV::offsets(lv, pitch, 64);
+    ov_last = TV::offsets(lv, pitch, s.N - jlast);
+  }
+  // wave-load number x (compile-time) of the tile whose first key is j0 (< N), into the stage at `buf`;
+  // `last`: that tile is the last one
+  auto dma = [&](int x, int j0, unsigned buf, bool last) {
     const long long ro = base + (long long)j0 * s.sn;
-    const int left = s.N - j0;
-    if (x < TK::IPW) TK::issue_one(lk, x, k + ro, pitch, left, buf, wave);
-    else if (x < 2 * TK::IPW) TK::issue_one(lk, x - TK::IPW, tk + ro, pitch, left, buf + OFF_TK, wave);
-    else if (x < 2 * TK::IPW + TV::IPW) TV::issue_one(lv, x - 2 * TK::IPW, v + ro, pitch, left, buf + OFF_V, wave);
-    else TV::issue_one(lv, x - 2 * TK::IPW - TV::IPW, tv + ro, pitch, left, buf + OFF_TV, wave);
+    if (x < 2 * TK::IPW) {
+      const int t = x % TK::IPW;
+      const unsigned off = last ? ok_last.o[t] : ok_full.o[t];
+      if (x < TK::IPW) TK::issue_at(off, t, k + ro, buf, wave);
+      else TK::issue_at(off, t, tk + ro, buf + OFF_TK, wave);
+    } else {
+      const int t = (x - 2 * TK::IPW) % TV::IPW;
+      const unsigned off = last ? ov_last.o[t] : ov_full.o[t];
+      if (x < 2 * TK::IPW + TV::IPW) TV::issue_at(off, t, v + ro, buf + OFF_V, wave);
+      else TV::issue_at(off, t, tv + ro, buf + OFF_TV, wave);
+    }
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::RAddr rv = TV::raddr(ic, hh);
   const typename TK::TAddr ta = TK::taddr(ic, hh);
   // Start-up: tile 0 first (its loads are cheap to issue and everything waits for them at the first
   // barrier anyway), then this lane's row scalars and fixed-side fragments (scattered loads), then, once those have arrived, tile 1.
-  const int nt = (s.N + 63) >> 6;      // tiles
-  const int jlast = (nt - 1) * 64;     // first key of the last tile; loads "beyond" it fetch it again, unused
 #pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0);
+  for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.N + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
@@ -154,7 +173,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   // tile 1 goes into the second stage now (any earlier and the waits for the fixed rows, which count
   // outstanding loads, would also wait for it); it lands while tile 0 is computed
 #pragma unroll
-  for (int x = 0; x < NDMA; ++x) dma(x, min(64, jlast), lds0 + BUF);
+  for (int x = 0; x < NDMA; ++x) dma(x, min(64, jlast), lds0 + BUF, nt <= 2);
   __syncthreads();  // tile 0 has landed
   PROF_P(15);
   bf16x8 ra[NKS], rb[NKS];  // S-fragments (K, tK rows) of the block whose S phase comes next
@@ -168,8 +187,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   // One tile.  RAG: keys beyond N exist in this tile (only ever the last one).
   //   sb / sbn / sbf: LDS address of this tile's stage / of the next tile's (landed) / of the free one, into
   //   which the tile after next is fetched, one wave-load every few products;  j0: first key;
-  //   jn2: first key of the tile after next (clamped to the last tile).
-  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int j0, int jn2, bool last) {
+  //   jn2: first key of the tile after next (clamped to the last tile);  jn2last: that is the last tile.
+  auto tile = [&](auto rag, unsigned sb, unsigned sbn, unsigned sbf, int j0, int jn2, bool jn2last, bool last) {
     constexpr bool RAG = decltype(rag)::value;
     const unsigned ke = sb + rk.e, ko = sb + rk.o;                   // K rows; tK at + OFF_TK
     const unsigned ve = sb + OFF_V + rv.e, vo = sb + OFF_V + rv.o;   // V rows; tV at + TV::BYTES
@@ -219,16 +238,31 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
     };
     auto tr_imm = [&](int blk, int cc, int db) { return (2 * blk + cc) * 16 * TK::PCH * 16 + db * 64; };
-    // P and N of element e of a block
-    auto pw1 = [&](int blk, int e) {
-      float sv = sS[e];
-      if (RAG && j0 + blk * 32 + drow(e, hh) >= s.N) sv = -INFINITY;  // keys beyond N: probability 0
-      pw1_asm(pp[e], nn[e], sv, sT[e], c1u, lse2, alphau, mub);
+    float ta[8], tb[8], wa[8], wb[8];  // temporaries, alive between the pieces of an element pair
+    // P and N of a block as a stream of 8 x 3 pieces (pair e = u / 3: elements 2e, 2e+1)
+    auto pw1_op = [&](int blk, int u) {
+      const int e = u / 3, st = u - 3 * e;
+      if (st == 0) {
+        float s0 = sS[2 * e], s1 = sS[2 * e + 1];
+        if (RAG) {  // keys beyond N: probability 0
+          if (j0 + blk * 32 + drow(2 * e, hh) >= s.N) s0 = -INFINITY;
+          if (j0 + blk * 32 + drow(2 * e + 1, hh) >= s.N) s1 = -INFINITY;
+        }
+        pw_fma2(ta[e], tb[e], s0, s1, c1u, lse2, lse2);
+      } else if (st == 1) {
+        pw_exp_fma(pp[2 * e], ta[e], nn[2 * e], sT[2 * e], alphau, mub);
+      } else {
+        pw_exp_fma(pp[2 * e + 1], tb[e], nn[2 * e + 1], sT[2 * e + 1], alphau, mub);
+      }
     };
-    // gZ, gZt of elements 2e, 2e+1 of a block
-    auto pw2 = [&](unsigned (&gz)[8], unsigned (&gzt)[8], int e) {
-      pw2_shifted_pair_asm(gz[e], gzt[e], sE[2 * e], sE[2 * e + 1], sDF[2 * e], sDF[2 * e + 1], pp[2 * e], pp[2 * e + 1],
-                           nn[2 * e], nn[2 * e + 1]);
+    // gZ, gZt of a block as a stream of 8 x 5 pieces (pair e = u / 5: elements 2e, 2e+1)
+    auto pw2_op = [&](unsigned (&gz)[8], unsigned (&gzt)[8], int u) {
+      const int e = u / 5, st = u - 5 * e;
+      if (st == 0) pw_mul2(ta[e], tb[e], pp[2 * e], sE[2 * e], pp[2 * e + 1], sE[2 * e + 1]);
+      else if (st == 1) pw_mul2(wa[e], wb[e], pp[2 * e], sDF[2 * e], pp[2 * e + 1], sDF[2 * e + 1]);
+      else if (st == 2) pw_fmac2(wa[e], wb[e], ta[e], nn[2 * e], tb[e], nn[2 * e + 1]);
+      else if (st == 3) pw_cvt(gzt[e], ta[e], tb[e]);
+      else pw_cvt(gz[e], wa[e], wb[e]);
     };
     // share [m*CNT/N, (m+1)*CNT/N) of CNT side instructions goes after the m-th of N products
 #define TVM_SHARE(x, m, CNT, N) for (int x = (m) * (CNT) / (N); x < ((m) + 1) * (CNT) / (N); ++x)
@@ -245,7 +279,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         else rd[kk] = lds_read16((kk & 1) ? vo : ve, TV::BYTES + kk * 32);
       }
 #pragma unroll
-      TVM_SHARE(x, m, NDMA, NQUIET) dma(x, jn2, sbf);
+      TVM_SHARE(x, m, NDMA, NQUIET) dma(x, jn2, sbf, jn2last);
     }
     PROF(0);
     // ---- E(0), with P, N of block 0
@@ -264,7 +298,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
       if (m >= FS) {
 #pragma unroll
-        TVM_SHARE(e, m - FS, 16, NS - FS) pw1(0, e);
+        TVM_SHARE(u, m - FS, 24, NS - FS) pw1_op(0, u);
       }
     }
     PROF(1);
@@ -284,7 +318,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
       if (m >= FS) {
 #pragma unroll
-        TVM_SHARE(e, m - FS, 8, NS - FS) pw2(gz0, gzt0, e);
+        TVM_SHARE(u, m - FS, 40, NS - FS) pw2_op(gz0, gzt0, u);
       }
     }
     PROF(2);
@@ -304,7 +338,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
       if (m >= FS) {
 #pragma unroll
-        TVM_SHARE(e, m - FS, 16, NS - FS) pw1(1, e);
+        TVM_SHARE(u, m - FS, 24, NS - FS) pw1_op(1, u);
       }
     }
     PROF(3);
@@ -313,14 +347,20 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz0, gzt0);
 #pragma unroll
-      TVM_SHARE(x, NS + m, NDMA, NQUIET) dma(x, jn2, sbf);
+      TVM_SHARE(x, NS + m, NDMA, NQUIET) dma(x, jn2, sbf, jn2last);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 0, half 1
         const int db = x >> 1;
         if ((x & 1) == 0) yT[db] = lds_read_tr(tl, th, tr_imm(0, 1, db));
         else tyT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(0, 1, db));
       }
-      if (m == NH - 1) landed(sE, sDF);  // at least NH >= 3 products behind the last one of E(1): see below
+      // gZ, gZt of block 1 start four products behind the last one of E(1) (where half 0 is that long) and
+      // run to the end of half 1
+      if (m == P2S) landed(sE, sDF);
+      if (m >= P2S) {
+#pragma unroll
+        TVM_SHARE(u, m - P2S, 40, 2 * NH - P2S) pw2_op(gz1, gzt1, u);
+      }
     }
 #pragma unroll
     for (int m = 0; m < NH; ++m) {
@@ -331,10 +371,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
         if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, tr_imm(1, 0, db));
         else txT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(1, 0, db));
       }
-      if (m < NH - 1) {  // none behind the last product: the product after it reads them
+      if (P2S == NH && m == 0) landed(sE, sDF);  // NH + 1 >= 4 products behind the last one of E(1)
 #pragma unroll
-        TVM_SHARE(e, m, 8, NH - 1) pw2(gz1, gzt1, e);
-      }
+      TVM_SHARE(u, NH - P2S + m, 40, 2 * NH - P2S) pw2_op(gz1, gzt1, u);
     }
     PROF(4);
     // ---- O(1), half 0
@@ -342,7 +381,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 0, xT, txT, gz1, gzt1);
 #pragma unroll
-      TVM_SHARE(x, NS + NH + m, NDMA, NQUIET) dma(x, jn2, sbf);
+      TVM_SHARE(x, NS + NH + m, NDMA, NQUIET) dma(x, jn2, sbf, jn2last);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NDB, NH) {  // ... of block 1, half 1
         const int db = x >> 1;
@@ -361,7 +400,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     for (int m = 0; m < NH; ++m) {
       o_product(m, 1, yT, tyT, gz1, gzt1);
 #pragma unroll
-      TVM_SHARE(x, NS + 2 * NH + m, NDMA, NQUIET) dma(x, jn2, sbf);
+      TVM_SHARE(x, NS + 2 * NH + m, NDMA, NQUIET) dma(x, jn2, sbf, jn2last);
 #pragma unroll
       TVM_SHARE(x, m, 2 * NKS, NH) {  // S-fragments of the next tile's block 0
         const int kk = x % NKS;
@@ -384,13 +423,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const int nfull = s.N >> 6;  // tiles without keys beyond N
   unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
   for (int t = 0; t < nfull; ++t) {
-    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, jlast), t + 1 == nt);
+    tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, jlast), t + 3 >= nt, t + 1 == nt);
     const unsigned r0 = st0;
     st0 = st1;
     st1 = st2;
     st2 = r0;
   }
-  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, jlast, true);
+  if (nt > nfull) tile(std::true_type{}, st0, st1, st2, nfull * 64, jlast, true, true);
   dma_wait();       // the re-fetches of the last tile must be over before the buffers are reused below
   __syncthreads();
   PROF_DUMP;

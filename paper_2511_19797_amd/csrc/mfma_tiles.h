@@ -187,6 +187,23 @@ struct Tile {
 #pragma unroll
     for (int t = 0; t < IPW; ++t) issue_one(L, t, tile, pitch, rows_left, lds, wave);
   }
+  // The same with the per-lane byte offsets worked out once: `rows` = rows that exist from the
+  // tile's first row on (64 or more for a whole tile; the last tile's count for the last one).
+  struct Offs {
+    unsigned o[IPW];
+  };
+  __device__ __forceinline__ static Offs offsets(const Lane& L, unsigned pitch, int rows) {
+    Offs f;
+#pragma unroll
+    for (int t = 0; t < IPW; ++t) f.o[t] = (unsigned)min(L.srow[t], rows - 1) * pitch + L.col[t];
+    return f;
+  }
+  // t-th wave-load with a ready offset; `wave` must be wave-uniform in the compiler's eyes (read
+  // through readfirstlane) so that the LDS address is scalar arithmetic
+  __device__ __forceinline__ static void issue_at(unsigned off, int t, const bf16* __restrict__ tile, unsigned lds,
+                                                  int wave) {
+    dma_to_lds<16>(tile, off, lds + (unsigned)(wave + t * NW) * 1024u);
+  }
   // Read addressing.  All swizzle arithmetic is folded into a few per-lane constants so that
   // every fragment read is  lane constant + compile-time immediate.
   //

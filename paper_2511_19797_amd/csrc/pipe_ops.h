@@ -58,96 +58,49 @@ __device__ __forceinline__ bf16x8 lds_read_tr(unsigned lo, unsigned hi, int imm)
   return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 // The pointwise work is inline assembly too, so that it stays in the slot it is written in (the
-// optimizer moves plain arithmetic freely between the matrix-core instructions otherwise).
-//   P = exp2(S c1 - lse2),  N = St alpha - mub
-__device__ __forceinline__ void pw1_asm(float& p, float& n, float sv, float st, float c1, float lse2, float alpha,
-                                        float mub) {
-  float t;
+// optimizer moves plain arithmetic freely between the matrix-core instructions otherwise).  It comes
+// in pieces of one or two instructions (about 8 cycles each: v_exp_f32 and
+// v_cvt_pk_bf16_f32 take the VALU for two issue slots), so that it can be dealt out evenly: behind one
+// matrix-core product a lone wave has room for about 24 cycles of other VALU work (measured: six
+// plain instructions, or three of the slow ones), whatever is issued beyond that delays the next
+// product.  Dependent instructions closer than three apart also cost extra cycles.
+//   a = x0 c - y0,  b = x1 c - y1      (c wave-uniform)
+__device__ __forceinline__ void pw_fma2(float& a, float& b, float x0, float x1, float c, float y0, float y1) {
   asm volatile(
-      "v_fma_f32 %2, %3, %5, -%6\n\t"
-      "v_fma_f32 %1, %4, %7, -%8\n\t"
-      "v_exp_f32 %0, %2"
-      : "=v"(p), "=v"(n), "=&v"(t)
-      : "v"(sv), "v"(st), "s"(c1), "v"(lse2), "s"(alpha), "v"(mub));
+      "v_fma_f32 %0, %2, %4, -%5\n\t"
+      "v_fma_f32 %1, %3, %4, -%6"
+      : "=&v"(a), "=&v"(b)
+      : "v"(x0), "v"(x1), "s"(c), "v"(y0), "v"(y1));
 }
-//   gZt = P (E - sig1),  gZ = P (DF - dsig) + gZt N, for two neighbouring elements, rounded to bf16 and packed
-__device__ __forceinline__ void pw2_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1, float p0,
-                                        float p1, float n0, float n1, float s1, float ds) {
-  float t0, t1, w0, w1;
+//   p = exp2(t),  n = x c - y          (c wave-uniform).  The exponential never ends a piece: the VALU
+//   instruction right behind a transcendental one must not read its result (no interlock), and what
+//   follows a piece may be a register copy of the compiler's.
+__device__ __forceinline__ void pw_exp_fma(float& p, float t, float& n, float x, float c, float y) {
   asm volatile(
-      "v_sub_f32 %2, %6, %14\n\t"
-      "v_sub_f32 %3, %7, %14\n\t"
-      "v_sub_f32 %4, %8, %15\n\t"
-      "v_sub_f32 %5, %9, %15\n\t"
-      "v_mul_f32 %2, %10, %2\n\t"
-      "v_mul_f32 %3, %11, %3\n\t"
-      "v_mul_f32 %4, %10, %4\n\t"
-      "v_mul_f32 %5, %11, %5\n\t"
-      "v_fmac_f32 %4, %2, %12\n\t"
-      "v_fmac_f32 %5, %3, %13\n\t"
-      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
-      "v_cvt_pk_bf16_f32 %1, %2, %3"
-      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
-      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1), "v"(s1), "v"(ds));
+      "v_exp_f32 %0, %2\n\t"
+      "v_fma_f32 %1, %3, %4, -%5"
+      : "=&v"(p), "=&v"(n)
+      : "v"(t), "v"(x), "s"(c), "v"(y));
 }
-//   The same with sig1 and dsig per element (the key-side kernel: its elements are different queries).
-__device__ __forceinline__ void pw2_pair_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1,
-                                             float p0, float p1, float n0, float n1, float sa0, float sa1, float da0,
-                                             float da1) {
-  float t0, t1, w0, w1;
+//   a = x0 y0,  b = x1 y1
+__device__ __forceinline__ void pw_mul2(float& a, float& b, float x0, float y0, float x1, float y1) {
   asm volatile(
-      "v_sub_f32 %2, %6, %14\n\t"
-      "v_sub_f32 %3, %7, %15\n\t"
-      "v_sub_f32 %4, %8, %16\n\t"
-      "v_sub_f32 %5, %9, %17\n\t"
-      "v_mul_f32 %2, %10, %2\n\t"
-      "v_mul_f32 %3, %11, %3\n\t"
-      "v_mul_f32 %4, %10, %4\n\t"
-      "v_mul_f32 %5, %11, %5\n\t"
-      "v_fmac_f32 %4, %2, %12\n\t"
-      "v_fmac_f32 %5, %3, %13\n\t"
-      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
-      "v_cvt_pk_bf16_f32 %1, %2, %3"
-      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
-      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1), "v"(sa0), "v"(sa1), "v"(da0),
-        "v"(da1));
+      "v_mul_f32 %0, %2, %3\n\t"
+      "v_mul_f32 %1, %4, %5"
+      : "=&v"(a), "=&v"(b)
+      : "v"(x0), "v"(y0), "v"(x1), "v"(y1));
 }
-//   The key-side kernel's second step when E and DF already have sig1 and dsig subtracted (their
-//   tiles start from -sig1, -dsig instead of 0):  gZt = P E',  gZ = P DF' + gZt N.
-__device__ __forceinline__ void pw2_shifted_pair_asm(unsigned& gz, unsigned& gzt, float e0, float e1, float f0, float f1,
-                                                     float p0, float p1, float n0, float n1) {
-  float t0, t1, w0, w1;
+//   a += x0 y0,  b += x1 y1
+__device__ __forceinline__ void pw_fmac2(float& a, float& b, float x0, float y0, float x1, float y1) {
   asm volatile(
-      "v_mul_f32 %2, %10, %6\n\t"
-      "v_mul_f32 %3, %11, %7\n\t"
-      "v_mul_f32 %4, %10, %8\n\t"
-      "v_mul_f32 %5, %11, %9\n\t"
-      "v_fmac_f32 %4, %2, %12\n\t"
-      "v_fmac_f32 %5, %3, %13\n\t"
-      "v_cvt_pk_bf16_f32 %0, %4, %5\n\t"
-      "v_cvt_pk_bf16_f32 %1, %2, %3"
-      : "=&v"(gz), "=&v"(gzt), "=&v"(t0), "=&v"(t1), "=&v"(w0), "=&v"(w1)
-      : "v"(e0), "v"(e1), "v"(f0), "v"(f1), "v"(p0), "v"(p1), "v"(n0), "v"(n1));
+      "v_fmac_f32 %0, %2, %3\n\t"
+      "v_fmac_f32 %1, %4, %5"
+      : "+v"(a), "+v"(b)
+      : "v"(x0), "v"(y0), "v"(x1), "v"(y1));
 }
-//   The key-side kernel's form of the first step, for two neighbouring elements: P and N as above
-//   (lse2, mub per element), plus Pd = P N, with P and Pd rounded to bf16 and packed.
-__device__ __forceinline__ void pw1_pair_asm(float& p0, float& p1, float& n0, float& n1, unsigned& pk, unsigned& pdk,
-                                             float s0, float s1, float st0, float st1, float c1, float l0, float l1,
-                                             float alpha, float m0, float m1) {
-  float t0, t1;
-  asm volatile(
-      "v_fma_f32 %6, %8, %12, -%13\n\t"
-      "v_fma_f32 %7, %9, %12, -%14\n\t"
-      "v_exp_f32 %0, %6\n\t"
-      "v_exp_f32 %1, %7\n\t"
-      "v_fma_f32 %2, %10, %15, -%16\n\t"
-      "v_fma_f32 %3, %11, %15, -%17\n\t"
-      "v_mul_f32 %6, %0, %2\n\t"
-      "v_mul_f32 %7, %1, %3\n\t"
-      "v_cvt_pk_bf16_f32 %4, %0, %1\n\t"
-      "v_cvt_pk_bf16_f32 %5, %6, %7"
-      : "=&v"(p0), "=&v"(p1), "=&v"(n0), "=&v"(n1), "=&v"(pk), "=&v"(pdk), "=&v"(t0), "=&v"(t1)
-      : "v"(s0), "v"(s1), "v"(st0), "v"(st1), "s"(c1), "v"(l0), "v"(l1), "s"(alpha), "v"(m0), "v"(m1));
+//   r = (bf16(lo), bf16(hi)), round to nearest even
+__device__ __forceinline__ void pw_cvt(unsigned& r, float lo, float hi) {
+  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
 }
 // From here on the compiler may read the tiles: every use below this point depends on it.  Placed
 // after enough further products that the ones writing the tiles have finished.

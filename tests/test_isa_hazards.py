@@ -1,13 +1,16 @@
 """Static check of the hand-scheduled kernels' instruction streams (no GPU needed).
 
 The hand-scheduled translation units issue their matrix-core products from inline assembly, which
-the compiler's hazard recognizer does not look into.  Two hazards are therefore ours to keep out
+the compiler's hazard recognizer does not look into.  Three hazards are therefore ours to keep out
 (the hardware interlocks neither):
   1. a matrix-core instruction must not read a register that a VALU instruction wrote in one of
      the two issue slots before it (s_nop N fills N+1 slots);
   2. nothing but a matrix-core accumulate into the same registers may touch the result registers
      of a matrix-core instruction until it has finished: 12 issue slots, a further matrix-core
      instruction counting as the 8 passes it keeps the pipe for.
+  3. the VALU instruction right behind a transcendental one (v_exp_f32, ...) must not read its result;
+     the compiler keeps this apart in its own code but does not look into inline assembly, and may put
+     a register copy right behind an assembly statement that ends in one.
 The compiler is free to put register copies right in front of or right behind an inline-assembly
 statement (at a loop exit, say), so this is checked on the generated assembly of every
 instantiation rather than argued from the source.
@@ -100,6 +103,27 @@ def result_violations(asm_text, need=12):
     return bad
 
 
+TRANS = ("v_exp_", "v_log_", "v_rcp_", "v_rsq_", "v_sqrt_", "v_sin_", "v_cos_")
+
+
+def trans_violations(asm_text):
+    """Hazard 3: (index, reader, transcendental) for every VALU read of a transcendental result in the next slot."""
+    ins = list(instructions(asm_text))
+    bad = []
+    for i, (op, ops) in enumerate(ins[:-1]):
+        if not op.startswith(TRANS):
+            continue
+        nop, nops = ins[i + 1]
+        if not nop.startswith("v_") or nop.startswith(TRANS):
+            continue
+        srcs = set().union(*[regs(o) for o in nops[1:]]) if len(nops) > 1 else set()
+        if nop.startswith(("v_fmac", "v_mac")) or nop.startswith("v_mfma"):
+            srcs |= regs(nops[0]) | (regs(nops[-1]) if nop.startswith("v_mfma") else set())
+        if regs(ops[0]) & srcs:
+            bad.append((i, " ".join([nop] + nops), " ".join([op] + ops)))
+    return bad
+
+
 def test_parser_flags_a_planted_hazard():
     planted = """
     v_accvgpr_write_b32 a4, v9
@@ -125,6 +149,13 @@ def test_parser_flags_a_planted_hazard():
     v_accvgpr_mov_b32 a48, a64
     """
     assert result_violations(chained) == []
+    trans = """
+    v_exp_f32 v3, v4
+    v_accvgpr_write_b32 a9, v3
+    """
+    assert len(trans_violations(trans)) == 1
+    assert trans_violations(trans.replace("v_accvgpr", "v_fma_f32 v7, v8, v9, v10\n v_accvgpr")) == []
+    assert trans_violations("v_exp_f32 v3, v4\n v_exp_f32 v5, v3") == []
 
 
 @pytest.mark.parametrize("name", HAND_SCHEDULED)
@@ -141,3 +172,5 @@ def test_no_valu_write_feeds_next_matrix_instruction(name):
     assert not bad, f"{len(bad)} VALU->MFMA hazards, first: {bad[:3]}"
     bad = result_violations(text)
     assert not bad, f"{len(bad)} touches of unfinished matrix-core results, first: {bad[:3]}"
+    bad = trans_violations(text)
+    assert not bad, f"{len(bad)} reads of a transcendental result in the next slot, first: {bad[:3]}"
