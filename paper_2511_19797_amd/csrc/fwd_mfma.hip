@@ -20,10 +20,15 @@
 //   l   += sum p ;  c += sum p * alpha St
 //   accO += p V ;   accT += (p * alpha St) V + p tV
 // Epilogue: O = accO / l,  stats = c / l,  tO = accT / l - stats * O,  lse = m + log l.
+//
+// Where the head dim leaves a spare column in the output tiles (D < DV, e.g. 72 in 96) the two
+// row sums cost no VALU work: column D of the V tile is set to one and that of the tV tile to
+// zero in LDS, so row D of accO is l and row D of accT is c, accumulated (and rescaled) by the
+// matrix cores along with everything else, from the same bf16-rounded weights as the outputs.
 #include "mfma_tiles.h"
 #ifndef FWD_NW
 #define FWD_NW 4   // waves per workgroup (two workgroups share a CU)
-#define FWD_BN 32  // keys per LDS tile
+#define FWD_BN 32  // keys per LDS tile (one 32-key block)
 #endif
 
 namespace tvm {
@@ -32,7 +37,7 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRescaleLog2 = 8.f;  // raise the reference maximum only beyond this growth (log2 units)
 
-template <int DK, int DV, int NW, int kBN>
+template <int DK, int DV, int NW, int kBN, bool SPARE>
 __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shape s, const bf16* __restrict__ q,
                                                           const bf16* __restrict__ k, const bf16* __restrict__ v,
                                                           const bf16* __restrict__ tq, const bf16* __restrict__ tk,
@@ -45,7 +50,9 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  static_assert(kBN == 32, "one block per tile: the spare-column rows are planted by 32 lanes");
+  const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
   const int nmb = (s.N + BM - 1) / BM;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nmb, mb = wg - bh * nmb;
@@ -54,17 +61,44 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   const int i = mb * BM + wave * 32 + ic;  // this lane's query row
   const bool iok = i < s.N;
 
-  const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
-  const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
   const unsigned lds0 = lds_addr_of(lds);
-  auto issue = [&](int j0, unsigned buf) {  // j0 < N
+  // per-lane byte offsets of this wave's loads within a tile, worked out once: for whole tiles, and for
+  // the last tile, where rows past the end fetch its last row again (keys of probability 0)
+  const int jlast = ((s.N - 1) / kBN) * kBN;
+  typename TK::Offs ok_full, ok_last;
+  typename TV::Offs ov_full, ov_last;
+  {
+    const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
+    const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
+    ok_full = TK::offsets(lk, pitch, kBN);
+    ok_last = TK::offsets(lk, pitch, s.N - jlast);
+    ov_full = TV::offsets(lv, pitch, kBN);
+    ov_last = TV::offsets(lv, pitch, s.N - jlast);
+  }
+  auto issue = [&](int j0, unsigned buf) {  // j0 < N, a multiple of kBN
     const long long ro = base + (long long)j0 * s.sn;
-    const int left = s.N - j0;
-    TK::issue(lk, k + ro, pitch, left, buf, wave);
-    TK::issue(lk, tk + ro, pitch, left, buf + TK::BYTES, wave);
-    TV::issue(lv, v + ro, pitch, left, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + ro, pitch, left, buf + 2 * TK::BYTES + TV::BYTES, wave);
+    const bool last = j0 == jlast;
+#pragma unroll
+    for (int t = 0; t < TK::IPW; ++t) {
+      const unsigned off = last ? ok_last.o[t] : ok_full.o[t];
+      TK::issue_at(off, t, k + ro, buf, wave);
+      TK::issue_at(off, t, tk + ro, buf + TK::BYTES, wave);
+    }
+#pragma unroll
+    for (int t = 0; t < TV::IPW; ++t) {
+      const unsigned off = last ? ov_last.o[t] : ov_full.o[t];
+      TV::issue_at(off, t, v + ro, buf + 2 * TK::BYTES, wave);
+      TV::issue_at(off, t, tv + ro, buf + 2 * TK::BYTES + TV::BYTES, wave);
+    }
+  };
+  // SPARE: once a stage has landed, every wave sets column D of its V rows to one (lanes 0..31, row =
+  // lane) and of its tV rows to zero (lanes 32..63) before it reads them; the loads had put a copy of
+  // the row's first chunk there.  All waves write the same values, so they need not wait for each other.
+  const int plant_off = (hh ? 2 * TK::BYTES + TV::BYTES : 2 * TK::BYTES) +
+                        (ic * TV::PCH + ((s.D >> 3) ^ ((ic >> 2) & 3))) * 16;
+  auto plant = [&](char* stage) {
+    if (SPARE) *reinterpret_cast<uint4*>(stage + plant_off) = make_uint4(hh ? 0u : 0x3F80u, 0u, 0u, 0u);
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::TAddr tv_a = TV::taddr(ic, hh);
@@ -85,100 +119,143 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
 
   dma_wait();
   __syncthreads();  // tile 0 has landed
+  plant(lds);
+  // K, tK row fragments of the tile about to be computed: read one tile ahead, right behind the
+  // barrier that says it has landed, so that their LDS latency hides behind the last output products
+  bf16x8 kpre[NKS], tkpre[NKS];
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) {
+    kpre[kk] = TK::frag_row(lds, rk, 0, kk);
+    tkpre[kk] = TK::frag_row(lds + TK::BYTES, rk, 0, kk);
+  }
   for (int j0 = 0, it = 0; j0 < s.N; j0 += kBN, ++it) {
     const char* lds_k = lds + (it & 1) * BUF;
-    const char* lds_tk = lds_k + TK::BYTES;
     const char* lds_v = lds_k + 2 * TK::BYTES;
     const char* lds_tv = lds_v + TV::BYTES;
+    char* lds_next = lds + ((it + 1) & 1) * BUF;
     if (j0 + kBN < s.N) issue(j0 + kBN, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
+    f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
-    for (int jb = 0; jb < kBN / 32; ++jb) {
-      if (j0 + jb * 32 >= s.N) break;  // uniform: the rest of the tile is beyond the last key
-      f32x16 sS = zero16(), sT = zero16();
+    for (int kk = 0; kk < NKS; ++kk) {
+      sS = mfma(kpre[kk], qf[kk], sS);
+      sT = mfma(kpre[kk], tqf[kk], sT);
+      sT = mfma(tkpre[kk], qf[kk], sT);
+    }
+    if (j0 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
 #pragma unroll
-      for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 kf = TK::frag_row(lds_k, rk, jb, kk);
-        const bf16x8 tkf = TK::frag_row(lds_tk, rk, jb, kk);
-        sS = mfma(kf, qf[kk], sS);
-        sT = mfma(kf, tqf[kk], sT);
-        sT = mfma(tkf, qf[kk], sT);
-      }
-      if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
+      for (int r = 0; r < 16; ++r)
+        if (j0 + drow(r, hh) >= s.N) sS[r] = -INFINITY;
+    }
+    float mx = sS[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (j0 + jb * 32 + drow(r, hh) >= s.N) sS[r] = -INFINITY;
-      }
-      float mx = sS[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sS[r]);
-      mx = fmaxf(mx, xhalf(mx));  // finite: key 0 is never masked and lives in the first block
-      if (__builtin_amdgcn_ballot_w64((mx - m) * c1 > kRescaleLog2) != 0) {  // uniform
-        const float mn = fmaxf(m, mx);
-        const float f = __builtin_amdgcn_exp2f((m - mn) * c1);  // m = -inf on the first block: 0
-        m = mn;
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sS[r]);
+    mx = fmaxf(mx, xhalf(mx));  // finite: key 0 is never masked and lives in the first block
+    if (__builtin_amdgcn_ballot_w64((mx - m) * c1 > kRescaleLog2) != 0) {  // uniform
+      const float mn = fmaxf(m, mx);
+      const float f = __builtin_amdgcn_exp2f((m - mn) * c1);  // m = -inf on the first block: 0
+      m = mn;
+      if (!SPARE) {
         l *= f;
         cs *= f;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            accO[db][r] *= f;
-            accT[db][r] *= f;
-          }
       }
-      const float mc = m * c1;
-      float ps = 0.f, pzs = 0.f;
-      bf16x8 pf[2], pzf[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -mc));
-        const float pz = p * (sT[r] * s.alpha);
-        ps += p;
-        pzs += pz;
-        pf[r >> 3][r & 7] = (bf16)p;
-        pzf[r >> 3][r & 7] = (bf16)pz;
-      }
-      l += ps;   // per-half partial sums; the halves are combined once, in the epilogue
-      cs += pzs;
 #pragma unroll
       for (int db = 0; db < NDB; ++db)
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-          const bf16x8 vf = TV::frag_tr(lds_v, tv_a, 2 * jb + cc, db);
-          const bf16x8 tvf = TV::frag_tr(lds_tv, tv_a, 2 * jb + cc, db);
-          accO[db] = mfma(vf, pf[cc], accO[db]);
-          accT[db] = mfma(vf, pzf[cc], accT[db]);
-          accT[db] = mfma(tvf, pf[cc], accT[db]);
+        for (int r = 0; r < 16; ++r) {
+          accO[db][r] *= f;
+          accT[db][r] *= f;
         }
+    }
+    const float mc = m * c1;
+    float ps = 0.f, pzs = 0.f;
+    bf16x8 pf[2], pzf[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -mc));
+      const float pz = p * (sT[r] * s.alpha);
+      if (!SPARE) {
+        ps += p;
+        pzs += pz;
+      }
+      pf[r >> 3][r & 7] = (bf16)p;
+      pzf[r >> 3][r & 7] = (bf16)pz;
+    }
+    if (!SPARE) {
+      l += ps;   // per-half partial sums; the halves are combined once, in the epilogue
+      cs += pzs;
+    }
+    // output products of the first 16 keys, fragments straight from LDS
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const bf16x8 vf = TV::frag_tr(lds_v, tv_a, 0, db);
+      const bf16x8 tvf = TV::frag_tr(lds_tv, tv_a, 0, db);
+      accO[db] = mfma(vf, pf[0], accO[db]);
+      accT[db] = mfma(vf, pzf[0], accT[db]);
+      accT[db] = mfma(tvf, pf[0], accT[db]);
+    }
+    // the fragments of the other 16 keys go to registers: that is the last read of this tile's buffers
+    bf16x8 vf1[NDB], tvf1[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      vf1[db] = TV::frag_tr(lds_v, tv_a, 1, db);
+      tvf1[db] = TV::frag_tr(lds_tv, tv_a, 1, db);
     }
     dma_wait();
     __syncthreads();  // next tile landed; everyone is done with this one
+    if (j0 + kBN < s.N) plant(lds_next);  // uniform; none behind the last tile: the buffers become the output staging
+#pragma unroll
+    for (int kk = 0; kk < NKS; ++kk) {  // (behind the last tile: stale data, unused)
+      kpre[kk] = TK::frag_row(lds_next, rk, 0, kk);
+      tkpre[kk] = TK::frag_row(lds_next + TK::BYTES, rk, 0, kk);
+    }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      accO[db] = mfma(vf1[db], pf[1], accO[db]);
+      accT[db] = mfma(vf1[db], pzf[1], accT[db]);
+      accT[db] = mfma(tvf1[db], pf[1], accT[db]);
+    }
   }
+  // every wave is past the last barrier, but the staging below reuses the buffers that the reads just
+  // issued (stale data of a tile that does not exist) still target: they are complete once their
+  // registers are (which nothing uses); make that explicit
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __syncthreads();
 
-  l += xhalf(l);
-  cs += xhalf(cs);
-  if (!iok) return;
+  if (SPARE) {
+    // row D of the accumulators (held by the lower half-wave) has the sums
+    float lv = 0.f, cv = 0.f;
+#pragma unroll
+    for (int cand = DK - 8; cand <= DK; cand += 8)
+      if (cand < DV && s.D == cand) {
+        lv = accO[cand / 32][4 * ((cand % 32) / 8)];
+        cv = accT[cand / 32][4 * ((cand % 32) / 8)];
+      }
+    const float lx = xhalf(lv), cx = xhalf(cv);
+    l = hh ? lx : lv;
+    cs = hh ? cx : cv;
+  } else {
+    l += xhalf(l);
+    cs += xhalf(cs);
+  }
+  // rows beyond N hold garbage (possibly not finite) from here on; nothing of theirs is stored
   const float inv = 1.f / l;
   const float mubar = cs * inv;
+  const float nmi = -mubar * inv;
 #pragma unroll
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = db * 32 + 8 * g + 4 * hh;
-      if (d0 < s.D) {
-        bf16x4 vo, vt;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const float oc = accO[db][4 * g + t] * inv;
-          vo[t] = (bf16)oc;
-          vt[t] = (bf16)fmaf(-mubar, oc, accT[db][4 * g + t] * inv);
-        }
-        *reinterpret_cast<bf16x4*>(o + base + (long long)i * s.sn + d0) = vo;
-        *reinterpret_cast<bf16x4*>(to + base + (long long)i * s.sn + d0) = vt;
-      }
-    }
-  if (hh == 0) {
+    for (int r = 0; r < 16; ++r) accT[db][r] = fmaf(nmi, accO[db][r], accT[db][r] * inv);
+  {
+    // the loop ended with a barrier and no tile load is in flight: each wave stages its two output
+    // tiles through a region of the tile buffers of its own and stores whole rows
+    const unsigned lw = lds0 + (unsigned)wave * (32 * (64 * NDB + 16));
+    static_assert(NW * 32 * (64 * NDB + 16) <= 2 * BUF, "staging fits in the tile buffers");
+    const int row0 = mb * BM + wave * 32;
+    store_tile_coalesced<NDB>(lw, o + base, s.sn, row0, s.N, s.D, accO, inv, lane);
+    store_tile_coalesced<NDB>(lw, to + base, s.sn, row0, s.N, s.D, accT, 1.f, lane);
+  }
+  if (iok && hh == 0) {
     const long long r = (long long)bh * s.N + i;
     lse[r] = (m * c1 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
     stats[r] = mubar;
@@ -187,11 +264,19 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
 
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  constexpr int NW = FWD_NW, BN = (DV > 96) ? 32 : FWD_BN;  // waves per workgroup, keys per LDS tile
+  constexpr int NW = FWD_NW, BN = FWD_BN;  // waves per workgroup, keys per LDS tile
   const int nmb = (s.N + 32 * NW - 1) / (32 * NW);
-  hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN>), dim3(nmb * s.B * s.H), dim3(64 * NW), 0, st, s,
-                     (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
-                     (const bf16*)a.tv, (bf16*)a.o, (bf16*)a.to, a.lse, a.stats);
+  const dim3 grid(nmb * s.B * s.H), block(64 * NW);
+  const bf16 *q = (const bf16*)a.q, *k = (const bf16*)a.k, *v = (const bf16*)a.v, *tq = (const bf16*)a.tq,
+             *tk = (const bf16*)a.tk, *tv = (const bf16*)a.tv;
+  if (s.D < DV)  // a spare column in the output tiles carries the row sums
+    hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN, true>), grid, block, 0, st, s, q, k, v, tq, tk, tv, (bf16*)a.o,
+                       (bf16*)a.to, a.lse, a.stats);
+  else if constexpr (DK == DV)
+    hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN, false>), grid, block, 0, st, s, q, k, v, tq, tk, tv, (bf16*)a.o,
+                       (bf16*)a.to, a.lse, a.stats);
+  else
+    return hipErrorNotSupported;  // D <= DK < DV: not reached
   return hipGetLastError();
 }
 
