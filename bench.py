@@ -2,7 +2,7 @@
 """Benchmark of the hot path: one step = tvmattn_jvp_fwd + tvmattn_jvp_bwd over one batch of
 synthetic DiT-shaped inputs resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--also C3] [--no-cpu] [--ramp-ms 100]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--also C3] [--no-cpu] [--ramp-ms 100] [--sweep]
 
 value = algorithmic TFLOP/s of the whole step, 42*B*H*N^2*d flops per step (forward 12, backward
 30; true head dim, no padding, no recompute counted), over exactly K timed steps.  roofline = the
@@ -45,6 +45,14 @@ MEASURED_TRAFFIC = {
     ("C3", "fwd"): 55365.4 * _KIB * 2.0 + 37894.2 * _KIB,
     ("C3", "bwd_row"): 92794.3 * _KIB * 2.0 + 38400.0 * _KIB,
     ("C3", "bwd_col"): 74890.9 * _KIB * 2.0 + 73728.0 * _KIB,
+}
+
+
+# Backward latency of the paper's own kernels on one H100 (App. C "Evaluation"; batch size and head
+# dim not stated there), by (H, S): context for --sweep, whose batch 1 / head dim 64 are our choice.
+PAPER_H100_BWD_MS = {
+    (1, 128): 1.31, (1, 1024): 1.38, (1, 4096): 1.96, (1, 8192): 3.98, (1, 16384): 10.06, (1, 32768): 40.24,
+    (24, 128): 1.40, (24, 1024): 1.42, (24, 4096): 15.13, (24, 8192): 58.70, (24, 16384): 238.4, (24, 32768): 958.6,
 }
 
 
@@ -212,6 +220,8 @@ def main():
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--also", default="C3", help="comma-separated extra workloads reported under 'also'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the shapes of the paper's kernel benchmark (H in 1, 24; S = 128 ... 32768) under 'sweep'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
@@ -250,6 +260,16 @@ def main():
         "fwd_hbm_gbs": res["fwd_hbm_gbs"], "bwd_hbm_gbs": res["bwd_hbm_gbs"],
         "kernels": res["kernels"], "roofline": roofline, "also": also,
     }
+    if args.sweep:
+        out["sweep"] = []
+        for sw in wl.sweep_configs():
+            # a few steps suffice for the long sequences (a step at H = 24, S = 32768 takes ~0.1 s)
+            k = max(3, min(args.steps, int(2e14 / (42.0 * sw.B * sw.H * sw.N * sw.N * sw.d))))
+            r, km, _ = run_workload(sw, k, min(args.warmup, k), hip, ramp_ms=args.ramp_ms)
+            out["sweep"].append({
+                "H": sw.H, "S": sw.N, "B": sw.B, "d": sw.d, "steps": k, "ms_per_step": r["ms_per_step"],
+                "fwd_ms": km["fwd"], "bwd_ms": km["bwd_pre"] + km["bwd_row"] + km["bwd_col"], "tflops": r["tflops"],
+                "paper_h100_bwd_ms": PAPER_H100_BWD_MS.get((sw.H, sw.N))})
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

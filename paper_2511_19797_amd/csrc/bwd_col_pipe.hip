@@ -17,6 +17,9 @@
 //   -- after the tile's second block: all reads of this buffer are done; the next tile must have landed, barrier --
 //   OK(1)     dK, dtK += (gZ, gZt of half 1) .   Q, tQ rows of the next block <- LDS;  tile loads
 //
+// The pointwise work comes in pieces of one or two instructions, dealt out evenly over the products that
+// can carry it (a lone wave has room for about 24 cycles of VALU work behind each product): P, N, Pd
+// run from the fifth product of E to the end of OV(0), with half 0 complete when OV(0) starts.
 // The row scalars come from the workspace as the hand-scheduled query-side kernel leaves them:
 // lse in log2 units, and sig1, dsig negated, so that the E and DF tiles can start from them (the C
 // operand of their first product) and gZt = P E, gZ = P DF + gZt N need no subtraction.

@@ -14,12 +14,15 @@
 //   E(0)         E, DF of block 0                     P, N of block 0;  S-fragments of block 1 <- LDS
 //   S(1)         S, St of block 1                     gZ, gZt of block 0;  E-fragments of block 1 <- LDS
 //   E(1)         E, DF of block 1                     P, N of block 1;  K^T, tK^T of block 0, half 0 <- LDS
-//   O(0) half 0  dQ, dtQ += (gZ, gZt of block 0) .    K^T, tK^T of block 0, half 1 <- LDS;  tile loads
+//   O(0) half 0  dQ, dtQ += (gZ, gZt of block 0) .    K^T, tK^T of block 0, half 1 <- LDS;  tile loads;  from the
+//                                                     fourth product on: gZ, gZt of block 1
 //   O(0) half 1                                       gZ, gZt of block 1;  K^T, tK^T of block 1, half 0 <- LDS
 //   O(1) half 0  dQ, dtQ += (gZ, gZt of block 1) .    K^T, tK^T of block 1, half 1 <- LDS;  tile loads
 //   -- all reads of this tile's buffer are done: the next tile must have landed, workgroup barrier --
 //   O(1) half 1                                       S-fragments of tile t+1 <- LDS;  tile loads
 //
+// The pointwise work comes in pieces of one or two instructions, dealt out evenly over the products of
+// its phase: a lone wave has room for about 24 cycles of VALU work behind each product.
 // "half" = contraction half of an output product (16 keys).  E and DF start from constant tiles
 // holding -sig1 and -dsig of the lane's query, so gZt = P E, gZ = P DF + gZt N need no subtraction.
 // Three LDS stages: tile t in use, tile t+1 landed (it was fetched during tile t-1), tile t+2 being

@@ -72,7 +72,22 @@ CONFIGS = {
     "C3": Workload("C3", 32, 16, 256, 72, "bf16", note="DiT-XL/2, 256px latents"),
     "C4": Workload("C4", 16, 16, 1024, 72, "bf16", tangent_std=0.1, note="DiT-XL/2, 512px latents"),
     "C5": Workload("C5", 2, 24, 4096, 128, "bf16", key_scale=2.0, note="long-sequence stress"),
+    # the head split the paper itself trains DiT-XL/2 with (hidden 1152 as 18 heads of 64, App. F:
+    # its kernel ran 1.25x slower with 16 heads of 72)
+    "X3": Workload("X3", 32, 18, 256, 64, "bf16", note="DiT-XL/2 as 18 x 64, 256px latents"),
+    "X4": Workload("X4", 16, 18, 1024, 64, "bf16", tangent_std=0.1, note="DiT-XL/2 as 18 x 64, 512px latents"),
 }
+
+# The shapes of the paper's own kernel benchmark (App. C "Evaluation": backward latency over heads H
+# and sequence length S).  The table states neither batch size nor head dim: batch 1 and head dim 64
+# are this repository's choice, so its rows give context, not a comparison.
+SWEEP_H = (1, 24)
+SWEEP_S = (128, 1024, 4096, 8192, 16384, 32768)
+
+
+def sweep_configs():
+    return [Workload(f"H{h}S{s}", 1, h, s, 64, "bf16", note="kernel-benchmark shape, batch 1, head dim 64")
+            for h in SWEEP_H for s in SWEEP_S]
 
 
 def custom(B, H, N, d, dtype="bf16", tangent_std=1.0, key_scale=1.0, name=None):

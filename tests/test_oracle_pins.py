@@ -354,3 +354,26 @@ def test_explicit_scale_and_batched_wrapper():
     g2 = orc.attn_jvp_bwd_head(*(a[0, 1] for a in arrs), scale=0.37)
     for x, y in zip(g, g2):
         assert np.array_equal(x[0, 1], y)
+
+
+def test_query_rows_are_independent():
+    """A query row's outputs depend on no other query row, and the key-side gradients are sums over
+    the query rows: the oracle applied to blocks of query rows (M != N, which its definition allows)
+    gives the whole-head result.  The long-sequence GPU tests lean on this."""
+    args = head_inputs(23, 11, 11, 4)
+    Q, K, V, Qd, Kd, Vd, G, Gd = args
+    whole_f = orc.attn_jvp_fwd_head(*args[:6])
+    whole_g = orc.attn_jvp_bwd_head(*args)
+    dK, dV, dKd, dVd = (np.zeros_like(K) for _ in range(4))
+    for r in (slice(0, 4), slice(4, 5), slice(5, 11)):
+        f = orc.attn_jvp_fwd_head(Q[r], K, V, Qd[r], Kd, Vd)
+        for x, y in zip(f, whole_f):
+            assert np.allclose(x, y[r], atol=1e-14)
+        g = orc.attn_jvp_bwd_head(Q[r], K, V, Qd[r], Kd, Vd, G[r], Gd[r])
+        assert np.allclose(g[0], whole_g[0][r], atol=1e-13) and np.allclose(g[3], whole_g[3][r], atol=1e-13)
+        dK += g[1]
+        dV += g[2]
+        dKd += g[4]
+        dVd += g[5]
+    for x, y in zip((dK, dV, dKd, dVd), (whole_g[1], whole_g[2], whole_g[4], whole_g[5])):
+        assert np.allclose(x, y, atol=1e-13)

@@ -148,14 +148,14 @@ def test_backward_is_linear_in_upstream_gradients():
 
 
 # ---------------------------------------------------------------- the five configs at full size
-@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2)])
+@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2), ("X3", 4), ("X4", 2)])
 def test_full_size_configs_sampled_heads(name, nheads):
     """Full B,H,N,d in the launch configuration bench.py times; the oracle checks whole heads
     (every element of all ten outputs) for a seeded sample of (b,h), always including the first
     and the last head; all outputs must be finite everywhere."""
     w = wl.CONFIGS[name]
     announce(f"full-size {w}")
-    inp = wl.make_inputs(w, 100 + int(name[1]))
+    inp = wl.make_inputs(w, 100 + int(name[1]) + (10 if name[0] == "X" else 0))
     fwd, grads = pu.run_gpu(inp)
     for t in list(fwd) + list(grads):
         assert bool(torch.isfinite(t.float()).all())
@@ -169,6 +169,73 @@ def test_full_size_configs_sampled_heads(name, nheads):
     # neither O nor tO, so the key gradients and the key-tangent gradients sum to zero over the keys
     # (up to the bf16 rounding of each of the N summands)
     dq, dk, dv, dtq, dtk, dtv = grads
+    for g in (dk, dtk):
+        col_sum = g.float().sum(dim=2).abs().max()
+        bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
+        assert float(col_sum) <= float(bound), (float(col_sum), float(bound))
+
+
+# ---------------------------------------------------------------- long sequences (the paper's kernel-benchmark shapes)
+def _chunked_oracle_bwd(a, rows_per_chunk=512):
+    """The oracle's backward of one head, one block of query rows at a time: softmax rows are
+    independent, so the query gradients of a block are exact and the key-side gradients are the sums
+    of the blocks' contributions.  Keeps the N x N matrices out of memory."""
+    q, k, v, tq, tk, tv, gO, gTO = a
+    N = q.shape[0]
+    dq, dtq = np.zeros_like(q), np.zeros_like(q)
+    dk, dv, dtk, dtv = (np.zeros_like(k) for _ in range(4))
+    for r0 in range(0, N, rows_per_chunk):
+        r = slice(r0, min(N, r0 + rows_per_chunk))
+        g = pu.orc.attn_jvp_bwd_head(q[r], k, v, tq[r], tk, tv, gO[r], gTO[r])
+        dq[r], dtq[r] = g[0], g[3]
+        dk += g[1]
+        dv += g[2]
+        dtk += g[4]
+        dtv += g[5]
+    return dq, dk, dv, dtq, dtk, dtv
+
+
+def test_long_sequence_whole_head():
+    """N = 8192 (128 tiles; every LDS stage reused 40 times), one head of 64: every element of all ten
+    outputs against the oracle, which works through the head in blocks of query rows."""
+    w = wl.custom(1, 1, 8192, 64, "bf16")
+    announce(f"long sequence {w}")
+    inp = wl.make_inputs(w, 31)
+    fwd, grads = pu.run_gpu(inp)
+    a = [wl.to_f64(inp[n][0, 0]) for n in wl.NAMES]
+    ref_f = [np.concatenate(x) for x in zip(*[
+        pu.orc.attn_jvp_fwd_head(a[0][r0:r0 + 1024], a[1], a[2], a[3][r0:r0 + 1024], a[4], a[5])
+        for r0 in range(0, w.N, 1024)])]
+    ref_g = _chunked_oracle_bwd(a)
+    worst = {}
+    for name, got, ref in list(zip(pu.FWD_NAMES, fwd, ref_f)) + list(zip(pu.BWD_NAMES, grads, ref_g)):
+        worst[name] = pu.rel_err(got[0, 0].float().cpu().numpy(), ref)
+    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    bad = {k: v for k, v in worst.items() if not (v <= pu.TOL["bf16"])}
+    assert not bad, bad
+
+
+def test_longest_benchmark_shape_sampled_rows():
+    """N = 32768, the longest sequence of the paper's kernel benchmark (2 heads of 64): the oracle checks
+    o, to, lse, stats, dq and dtq on a seeded sample of query rows (all of them row-local), the key-side
+    gradients through the properties that hold at any size."""
+    w = wl.custom(1, 2, 32768, 64, "bf16")
+    announce(f"longest benchmark shape {w}")
+    inp = wl.make_inputs(w, 32)
+    fwd, grads = pu.run_gpu(inp)
+    for t in list(fwd) + list(grads):
+        assert bool(torch.isfinite(t.float()).all())
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 127, 128, w.N - 1], rng.integers(0, w.N, 252)]))
+    dq, dk, dv, dtq, dtk, dtv = grads
+    for h in range(w.H):
+        a = [wl.to_f64(inp[n][0, h]) for n in wl.NAMES]
+        ro = pu.orc.attn_jvp_fwd_head(a[0][rows], a[1], a[2], a[3][rows], a[4], a[5])
+        rg = pu.orc.attn_jvp_bwd_head(a[0][rows], a[1], a[2], a[3][rows], a[4], a[5], a[6][rows], a[7][rows])
+        # the row sample's maxima stand in for the tensors' (rel_err scales by the reference's maximum)
+        for name, got, ref in list(zip(pu.FWD_NAMES, fwd, ro)) + [("dq", dq, rg[0]), ("dtq", dtq, rg[3])]:
+            e = pu.rel_err(got[0, h].float().cpu().numpy()[rows], ref)
+            assert e <= pu.TOL["bf16"], (name, h, e)
     for g in (dk, dtk):
         col_sum = g.float().sum(dim=2).abs().max()
         bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
