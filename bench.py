@@ -182,6 +182,48 @@ def run_workload(w, steps, warmup, hip, seed=2024, ramp_ms=RAMP_MS):
     return res, kern_ms, unit
 
 
+def one_sided(w, steps, seed=2024):
+    """Backward with one upstream gradient only, and the forward that saves nothing, timed outside
+    the timed region of the headline figure (wall clock over `steps` calls each, device synchronised)."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    inp = wl.make_inputs(w, seed)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    del inp
+    q, k, v, tq, tk, tv = [dev[n] for n in wl.NAMES[:6]]
+    fwd_out = tvm.tvmattn_jvp_fwd(q, k, v, tq, tk, tv)
+    o, to, lse, stats = fwd_out
+    nosave = (torch.empty_like(o), torch.empty_like(o), None, None)
+    g3 = tuple(torch.empty_like(q) for _ in range(3)) + (None, None, None)
+    g6 = tuple(torch.empty_like(q) for _ in range(6))
+    ws = torch.empty(tvm.tvmattn_jvp_bwd_workspace_bytes(q), dtype=torch.uint8, device="cuda")
+    unit = float(w.B) * w.H * w.N * w.N * w.d
+    cases = {
+        # the ordinary attention backward: 5 of the 15 products (S, G V^T, and three output products)
+        "bwd_gO_only": (10.0, lambda: tvm.tvmattn_jvp_bwd(q, k, v, None, None, None, o, None, lse, None, dev["gO"], None,
+                                                          out=g3, workspace=ws)),
+        # the tangent path alone: 13 of the 15
+        "bwd_gTO_only": (26.0, lambda: tvm.tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, None, dev["gTO"],
+                                                           out=g6, workspace=ws)),
+        "fwd_nothing_saved": (12.0, lambda: tvm.tvmattn_jvp_fwd(q, k, v, tq, tk, tv, out=nosave, save=False)),
+    }
+    out = {}
+    for name, (units, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        out[name] = {"ms": ms, "tflops": units * unit / (ms * 1e-3) / 1e12}
+    return out
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -260,6 +302,7 @@ def main():
         "fwd_hbm_gbs": res["fwd_hbm_gbs"], "bwd_hbm_gbs": res["bwd_hbm_gbs"],
         "kernels": res["kernels"], "roofline": roofline, "also": also,
     }
+    out["one_sided"] = one_sided(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

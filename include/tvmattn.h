@@ -104,6 +104,8 @@ int tvmattn_set_bwd_events(void* const* events);
  *   in : q,k,v,tq,tk,tv   [B,H,N,D] dtype
  *   out: o, to            [B,H,N,D] dtype
  *        lse, stats       [B,H,N]   float32 (natural log of the row sum of exp(z); mu/l)
+ * lse and stats may both be NULL: a forward whose backward will not be taken saves nothing
+ * (the "detached" use of the tangent; one of the two alone is TVMATTN_INVALID_ARG).
  */
 int tvmattn_jvp_fwd(const tvmattn_desc* desc,
                     const void* q, const void* k, const void* v,
@@ -127,6 +129,15 @@ size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc);
  * scalars of Step 1 (delta = gO.O, Sigma_1 = gTO.O, Sigma_2 = gTO.tO per row; a separate
  * launch on the plain-ALU path), then a key-side pass (dk,dtk,dv,dtv; Steps 2,4,6).
  * No atomics: results are bitwise reproducible.
+ *
+ * One upstream gradient only (both NULL is TVMATTN_INVALID_ARG):
+ *   gTO == NULL  the gradient of <gO, O> alone, i.e. the ordinary attention backward (the part
+ *                the paper leaves to a standard kernel, App. C).  The tangent path drops out:
+ *                tq, tk, tv, to and stats are not read, dtq, dtk, dtv are not written, and any of
+ *                these eight may be NULL.
+ *   gO == NULL   the gradient of <gTO, tO> alone (the paper's Steps 1-6 by themselves); all
+ *                six outputs are written.
+ * Both are served by kernels that leave out the products that vanish, not by zero-filled inputs.
  */
 int tvmattn_jvp_bwd(const tvmattn_desc* desc,
                     const void* q, const void* k, const void* v,

@@ -112,21 +112,26 @@ def _stream():
     return _P(torch.cuda.current_stream().cuda_stream)
 
 
-def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None):
-    """Returns (o, to, lse, stats).  `out`, if given, is that same tuple of preallocated tensors."""
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True):
+    """Returns (o, to, lse, stats).  `out`, if given, is that same tuple of preallocated tensors.
+    save=False: nothing is kept for a backward (lse and stats are None)."""
     _same_layout(q, k, v, tq, tk, tv)
     desc = make_desc(q, scale)
     B, H, N, _ = q.shape
     if out is None:
         o, to = torch.empty_like(q), torch.empty_like(q)
-        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
-        stats = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if save else None
+        stats = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if save else None
     else:
         o, to, lse, stats = out
         _same_layout(q, o, to)
     _check(lib().tvmattn_jvp_fwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(),
-                                 tk.data_ptr(), tv.data_ptr(), o.data_ptr(), to.data_ptr(), lse.data_ptr(),
-                                 stats.data_ptr(), _stream()))
+                                 tk.data_ptr(), tv.data_ptr(), o.data_ptr(), to.data_ptr(), _ptr(lse), _ptr(stats),
+                                 _stream()))
     return o, to, lse, stats
 
 
@@ -136,20 +141,22 @@ def tvmattn_jvp_bwd_workspace_bytes(x, scale=0.0):
 
 
 def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, out=None, workspace=None):
-    """Returns (dq, dk, dv, dtq, dtk, dtv)."""
-    _same_layout(q, k, v, tq, tk, tv, o, to, gO, gTO)
+    """Returns (dq, dk, dv, dtq, dtk, dtv).
+
+    gTO=None: the ordinary attention backward (gradient of <gO, O> alone); tq, tk, tv, to, stats may be
+    None and dtq, dtk, dtv come back as None.  gO=None: the gradient of <gTO, tO> alone."""
+    _same_layout(*[t for t in (q, k, v, tq, tk, tv, o, to, gO, gTO) if t is not None])
     desc = make_desc(q, scale)
     if out is None:
-        out = tuple(torch.empty_like(q) for _ in range(6))
+        out = tuple(torch.empty_like(q) if (gTO is not None or n < 3) else None for n in range(6))
     else:
-        _same_layout(q, *out)
+        _same_layout(q, *[t for t in out if t is not None])
     need = int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     dq, dk, dv, dtq, dtk, dtv = out
-    _check(lib().tvmattn_jvp_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(),
-                                 tk.data_ptr(), tv.data_ptr(), o.data_ptr(), to.data_ptr(), lse.data_ptr(),
-                                 stats.data_ptr(), gO.data_ptr(), gTO.data_ptr(), dq.data_ptr(), dk.data_ptr(),
-                                 dv.data_ptr(), dtq.data_ptr(), dtk.data_ptr(), dtv.data_ptr(),
+    _check(lib().tvmattn_jvp_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk),
+                                 _ptr(tv), o.data_ptr(), _ptr(to), lse.data_ptr(), _ptr(stats), _ptr(gO), _ptr(gTO),
+                                 dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _ptr(dtq), _ptr(dtk), _ptr(dtv),
                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
     return out

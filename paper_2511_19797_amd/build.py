@@ -4,6 +4,7 @@ import os
 import subprocess
 import sys
 import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libtvmattn.so")
@@ -17,6 +18,8 @@ COMMON = [
 # d > 96 instantiations, whose register pressure sends the compiler's AGPR rewrite pass astray.
 PER_FILE = {
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "bwd_mfma_onesided1.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "bwd_mfma_onesided2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_col_pipe.hip": ["-mllvm", "-enable-misched=false"],
@@ -35,15 +38,18 @@ def _run(cmd, verbose):
         print(err)
 
 
-def build(verbose=False, extra=()):
+def build(verbose=False, extra=(), jobs=None):
     srcs = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
+    jobs = jobs or min(8, os.cpu_count() or 1, len(srcs))
     with tempfile.TemporaryDirectory() as tmp:
-        objs = []
-        for src in srcs:
+        def compile_one(src):
             name = os.path.basename(src)
             obj = os.path.join(tmp, name + ".o")
             _run(["hipcc", *COMMON, *PER_FILE.get(name, []), *extra, "-c", src, "-o", obj], verbose)
-            objs.append(obj)
+            return obj
+
+        with ThreadPoolExecutor(max_workers=jobs) as pool:  # one hipcc process per translation unit
+            objs = list(pool.map(compile_one, srcs))
         _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
     return LIB
 

@@ -26,6 +26,11 @@
 // owns one fixed row, its 16 registers run over streamed rows, and the tile feeds the output
 // products straight from registers.
 // No atomics anywhere: every output element is produced by exactly one lane.
+//
+// MODE selects the upstream gradients that exist: 0 both; 1 gO only (gTO = 0: the ordinary
+// attention backward, where E = gZt = 0, the tangent inputs drop out and only dQ, dK, dV are
+// produced); 2 gTO only (the tangent path by itself, the paper's own split: the two products with
+// gO drop out).  The one-sided modes serve every head dim; mode 0 only those above 96.
 #pragma once
 #include "mfma_tiles.h"
 
@@ -45,8 +50,8 @@ __device__ __forceinline__ void zero_acc(f32x16 (&a)[NDB]) {
 // ------------------------------------------------------------------------------------------
 // Key side.
 // ------------------------------------------------------------------------------------------
-template <int DK, int DV, int kTS>
-__global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
+template <int DK, int DV, int kTS, int MODE>
+__global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const float* __restrict__ lse, const float* __restrict__ stats, const bf16* __restrict__ gO,
@@ -54,7 +59,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
   using TX = Tile<kTS, DV / 8, kNT / 64>;  // read both ways: columns up to DV
   constexpr int ROWV = 4 * 256;                       // four float32 row vectors per stage (64 slots each)
-  constexpr int BUF = 4 * TX::BYTES + ROWV;           // one stage: Q, tQ, G, tG, row vectors
+  // one stage: Q, tQ, G, tG, row vectors; without gTO only Q and G (half the LDS: two workgroups per CU)
+  constexpr int OFF_TQ = TX::BYTES, OFF_G = (MODE == 1 ? 1 : 2) * TX::BYTES, OFF_TG = 3 * TX::BYTES;
+  constexpr int OFF_ROW = (MODE == 1 ? 2 : 4) * TX::BYTES;
+  constexpr int BUF = OFF_ROW + ROWV;
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
@@ -77,10 +85,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
     const long long ro = base + (long long)i0 * s.sn;
     const int left = s.N - i0;
     TX::issue(lx, q + ro, pitch, left, buf, wave);
-    TX::issue(lx, tq + ro, pitch, left, buf + TX::BYTES, wave);
-    TX::issue(lx, gO + ro, pitch, left, buf + 2 * TX::BYTES, wave);
-    TX::issue(lx, gTO + ro, pitch, left, buf + 3 * TX::BYTES, wave);
-    dma_to_lds<4>(rowsrc + i0, (unsigned)min(lane, left - 1) * 4u, buf + 4 * TX::BYTES + wave * 256);
+    if (MODE != 1) TX::issue(lx, tq + ro, pitch, left, buf + OFF_TQ, wave);
+    if (MODE != 2) TX::issue(lx, gO + ro, pitch, left, buf + OFF_G, wave);
+    if (MODE != 1) TX::issue(lx, gTO + ro, pitch, left, buf + OFF_TG, wave);
+    if (MODE != 1 || (wave & 1) == 0)  // uniform: stats and sig1 are not needed without gTO
+      dma_to_lds<4>(rowsrc + i0, (unsigned)min(lane, left - 1) * 4u, buf + OFF_ROW + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
   const typename TX::TAddr ta = TX::taddr(ic, hh);
@@ -88,9 +97,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
 
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
   gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
   gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
+  if (MODE != 1) {
+    gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
+    gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
+  }
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
   zero_acc(aK);
   zero_acc(aTK);
@@ -102,10 +113,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   __syncthreads();  // tile 0 has landed
   for (int i0 = 0, it = 0; i0 < s.N; i0 += kTS, ++it) {
     const char* lds_q = lds + (it & 1) * BUF;
-    const char* lds_tq = lds_q + TX::BYTES;
-    const char* lds_g = lds_q + 2 * TX::BYTES;
-    const char* lds_tg = lds_q + 3 * TX::BYTES;
-    const float* row_lse = reinterpret_cast<const float*>(lds_q + 4 * TX::BYTES);
+    const char* lds_tq = lds_q + OFF_TQ;
+    const char* lds_g = lds_q + OFF_G;
+    const char* lds_tg = lds_q + OFF_TG;
+    const float* row_lse = reinterpret_cast<const float*>(lds_q + OFF_ROW);
     const float* row_mub = row_lse + 64;
     const float* row_dsig = row_lse + 128;
     const float* row_sig1 = row_lse + 192;
@@ -117,18 +128,26 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 qf = TX::frag_row(lds_q, ra, ib, kk), tqf = TX::frag_row(lds_tq, ra, ib, kk);
+        const bf16x8 qf = TX::frag_row(lds_q, ra, ib, kk);
         sS = mfma(qf, kf[kk], sS);
-        sT = mfma(tqf, kf[kk], sT);
-        sT = mfma(qf, tkf[kk], sT);
+        if (MODE != 1) {
+          const bf16x8 tqf = TX::frag_row(lds_tq, ra, ib, kk);
+          sT = mfma(tqf, kf[kk], sT);
+          sT = mfma(qf, tkf[kk], sT);
+        }
       }
       f32x16 sDF = zero16(), sE = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        const bf16x8 gf = TX::frag_row(lds_g, ra, ib, kk), tgf = TX::frag_row(lds_tg, ra, ib, kk);
-        sE = mfma(tgf, vf[kk], sE);
-        sDF = mfma(gf, vf[kk], sDF);
-        sDF = mfma(tgf, tvf[kk], sDF);
+        if (MODE != 2) {
+          const bf16x8 gf = TX::frag_row(lds_g, ra, ib, kk);
+          sDF = mfma(gf, vf[kk], sDF);
+        }
+        if (MODE != 1) {
+          const bf16x8 tgf = TX::frag_row(lds_tg, ra, ib, kk);
+          sE = mfma(tgf, vf[kk], sE);
+          sDF = mfma(tgf, tvf[kk], sDF);
+        }
       }
       if (i0 + ib * 32 + 32 > s.N) {  // uniform: ragged last block, queries >= N get probability 0
 #pragma unroll
@@ -140,38 +159,49 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
       for (int g4 = 0; g4 < 4; ++g4) {
         const int ro = ib * 32 + 8 * g4 + 4 * hh;
         const float4 l4 = *reinterpret_cast<const float4*>(row_lse + ro);
-        const float4 m4 = *reinterpret_cast<const float4*>(row_mub + ro);
         const float4 d4 = *reinterpret_cast<const float4*>(row_dsig + ro);
-        const float4 s4 = *reinterpret_cast<const float4*>(row_sig1 + ro);
+        float4 m4 = make_float4(0.f, 0.f, 0.f, 0.f), s4 = m4;
+        if (MODE != 1) {
+          m4 = *reinterpret_cast<const float4*>(row_mub + ro);
+          s4 = *reinterpret_cast<const float4*>(row_sig1 + ro);
+        }
         const float la[4] = {l4.x, l4.y, l4.z, l4.w}, ma[4] = {m4.x, m4.y, m4.z, m4.w};
         const float da[4] = {d4.x, d4.y, d4.z, d4.w}, sa[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = 4 * g4 + t;
           const float p = __builtin_amdgcn_exp2f(fmaf(sS[r], c1, -la[t] * kLog2e));
-          const float n = fmaf(sT[r], s.alpha, -ma[t]);
-          const float gzt = p * (sE[r] - sa[t]);
-          const float gz = fmaf(gzt, n, p * (sDF[r] - da[t]));
           pf[r >> 3][r & 7] = (bf16)p;
-          pdf[r >> 3][r & 7] = (bf16)(p * n);
-          gzf[r >> 3][r & 7] = (bf16)gz;
-          gztf[r >> 3][r & 7] = (bf16)gzt;
+          if (MODE == 1) {
+            gzf[r >> 3][r & 7] = (bf16)(p * (sDF[r] - da[t]));
+          } else {
+            const float n = fmaf(sT[r], s.alpha, -ma[t]);
+            const float gzt = p * (sE[r] - sa[t]);
+            const float gz = fmaf(gzt, n, p * (sDF[r] - da[t]));
+            pdf[r >> 3][r & 7] = (bf16)(p * n);
+            gzf[r >> 3][r & 7] = (bf16)gz;
+            gztf[r >> 3][r & 7] = (bf16)gzt;
+          }
         }
       }
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          const bf16x8 gT = TX::frag_tr(lds_g, ta, 2 * ib + cc, db);
-          const bf16x8 tgT = TX::frag_tr(lds_tg, ta, 2 * ib + cc, db);
-          aV[db] = mfma(gT, pf[cc], aV[db]);
-          aV[db] = mfma(tgT, pdf[cc], aV[db]);
-          aTV[db] = mfma(tgT, pf[cc], aTV[db]);
+          if (MODE != 2) {
+            const bf16x8 gT = TX::frag_tr(lds_g, ta, 2 * ib + cc, db);
+            aV[db] = mfma(gT, pf[cc], aV[db]);
+          }
           const bf16x8 qT = TX::frag_tr(lds_q, ta, 2 * ib + cc, db);
-          const bf16x8 tqT = TX::frag_tr(lds_tq, ta, 2 * ib + cc, db);
           aK[db] = mfma(qT, gzf[cc], aK[db]);
-          aK[db] = mfma(tqT, gztf[cc], aK[db]);
-          aTK[db] = mfma(qT, gztf[cc], aTK[db]);
+          if (MODE != 1) {
+            const bf16x8 tgT = TX::frag_tr(lds_tg, ta, 2 * ib + cc, db);
+            aV[db] = mfma(tgT, pdf[cc], aV[db]);
+            aTV[db] = mfma(tgT, pf[cc], aTV[db]);
+            const bf16x8 tqT = TX::frag_tr(lds_tq, ta, 2 * ib + cc, db);
+            aK[db] = mfma(tqT, gztf[cc], aK[db]);
+            aTK[db] = mfma(qT, gztf[cc], aTK[db]);
+          }
         }
     }
     dma_wait();
@@ -180,19 +210,18 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_mfma_kernel(
   if (!jok) return;
   const long long ro = base + (long long)j * s.sn;
   store_acc<NDB>(dk + ro, aK, s.alpha, s.D, hh);
-  store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
   store_acc<NDB>(dv + ro, aV, 1.f, s.D, hh);
-  store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
+  if (MODE != 1) {
+    store_acc<NDB>(dtk + ro, aTK, s.alpha, s.D, hh);
+    store_acc<NDB>(dtv + ro, aTV, 1.f, s.D, hh);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
 // Query side.
 // ------------------------------------------------------------------------------------------
-// ------------------------------------------------------------------------------------------
-// Query side.
-// ------------------------------------------------------------------------------------------
-template <int DK, int DV, int kTS>
-__global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
+template <int DK, int DV, int kTS, int MODE>
+__global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const bf16* __restrict__ o, const bf16* __restrict__ to, const float* __restrict__ lse,
@@ -200,7 +229,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     float* __restrict__ dsig, float* __restrict__ sig1, bf16* __restrict__ dq, bf16* __restrict__ dtq) {
   using TK = Tile<kTS, DV / 8, kNT / 64>;  // K, tK: read both ways
   using TV = Tile<kTS, DK / 8, kNT / 64>;  // V, tV: score products only
-  constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
+  // one stage: K, tK, V, tV; without gTO only K and V (half the LDS: two workgroups per CU)
+  constexpr int OFF_TK = TK::BYTES, OFF_V = (MODE == 1 ? 1 : 2) * TK::BYTES, OFF_TV = 2 * TK::BYTES + TV::BYTES;
+  constexpr int BUF = MODE == 1 ? TK::BYTES + TV::BYTES : 2 * TK::BYTES + 2 * TV::BYTES;
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
@@ -220,9 +251,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
     const long long ro = base + (long long)j0 * s.sn;
     const int left = s.N - j0;
     TK::issue(lk, k + ro, pitch, left, buf, wave);
-    TK::issue(lk, tk + ro, pitch, left, buf + TK::BYTES, wave);
-    TV::issue(lv, v + ro, pitch, left, buf + 2 * TK::BYTES, wave);
-    TV::issue(lv, tv + ro, pitch, left, buf + 2 * TK::BYTES + TV::BYTES, wave);
+    TV::issue(lv, v + ro, pitch, left, buf + OFF_V, wave);
+    if (MODE != 1) {
+      TK::issue(lk, tk + ro, pitch, left, buf + OFF_TK, wave);
+      TV::issue(lv, tv + ro, pitch, left, buf + OFF_TV, wave);
+    }
   };
   const typename TK::RAddr rk = TK::raddr(ic, hh);
   const typename TV::RAddr rv = TV::raddr(ic, hh);
@@ -231,9 +264,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
   gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
+  if (MODE != 1) gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+  if (MODE != 2) gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
+  if (MODE != 1) gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row);
   // they are also written out for the key-side kernel, which runs after this one.
@@ -241,15 +274,18 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   {
     bf16x8 of[NKS], tof[NKS];
     gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
-    gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
+    if (MODE != 1) gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
 #pragma unroll
     for (int kk = 0; kk < NKS; ++kk)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float oe = (float)of[kk][e], gte = (float)tgf[kk][e];
-        ds = fmaf((float)gf[kk][e], oe, ds);
-        ds = fmaf(gte, (float)tof[kk][e], ds);
-        s1 = fmaf(gte, oe, s1);
+        const float oe = (float)of[kk][e];
+        if (MODE != 2) ds = fmaf((float)gf[kk][e], oe, ds);
+        if (MODE != 1) {
+          const float gte = (float)tgf[kk][e];
+          ds = fmaf(gte, (float)tof[kk][e], ds);
+          s1 = fmaf(gte, oe, s1);
+        }
       }
     ds += xhalf(ds);
     s1 += xhalf(s1);
@@ -257,10 +293,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.N + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
-  const float mub = iok ? stats[r] : 0.f;
+  const float mub = (MODE != 1 && iok) ? stats[r] : 0.f;
   if (iok && hh == 0) {
     dsig[r] = ds;
-    sig1[r] = s1;
+    if (MODE != 1) sig1[r] = s1;
   }
   f32x16 aQ[NDB], aTQ[NDB];
   zero_acc(aQ);
@@ -271,9 +307,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   __syncthreads();  // tile 0 has landed
   for (int j0 = 0, it = 0; j0 < s.N; j0 += kTS, ++it) {
     const char* lds_k = lds + (it & 1) * BUF;
-    const char* lds_tk = lds_k + TK::BYTES;
-    const char* lds_v = lds_k + 2 * TK::BYTES;
-    const char* lds_tv = lds_v + TV::BYTES;
+    const char* lds_tk = lds_k + OFF_TK;
+    const char* lds_v = lds_k + OFF_V;
+    const char* lds_tv = lds_k + OFF_TV;
     if (j0 + kTS < s.N) issue(j0 + kTS, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll
@@ -285,19 +321,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
         kfr[kk] = TK::frag_row(lds_k, rk, jb, kk);
-        tkfr[kk] = TK::frag_row(lds_tk, rk, jb, kk);
+        if (MODE != 1) tkfr[kk] = TK::frag_row(lds_tk, rk, jb, kk);
       }
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
         vfr[kk] = TV::frag_row(lds_v, rv, jb, kk);
-        tvfr[kk] = TV::frag_row(lds_tv, rv, jb, kk);
+        if (MODE != 1) tvfr[kk] = TV::frag_row(lds_tv, rv, jb, kk);
       }
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
         sS = mfma(kfr[kk], qf[kk], sS);
-        sT = mfma(kfr[kk], tqf[kk], sT);
-        sT = mfma(tkfr[kk], qf[kk], sT);
+        if (MODE != 1) {
+          sT = mfma(kfr[kk], tqf[kk], sT);
+          sT = mfma(tkfr[kk], qf[kk], sT);
+        }
       }
       bf16x8 kT[2][NDB], tkT[2][NDB];
 #pragma unroll
@@ -305,7 +343,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           kT[cc][db] = TK::frag_tr(lds_k, ta, 2 * jb + cc, db);
-          tkT[cc][db] = TK::frag_tr(lds_tk, ta, 2 * jb + cc, db);
+          if (MODE != 1) tkT[cc][db] = TK::frag_tr(lds_tk, ta, 2 * jb + cc, db);
         }
       if (j0 + jb * 32 + 32 > s.N) {  // uniform: ragged last block, keys >= N get probability 0
 #pragma unroll
@@ -319,16 +357,16 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
       auto pw1 = [&](int rr) {
         if (rr < 16) {
           pp[rr] = __builtin_amdgcn_exp2f(fmaf(sS[rr], c1, -lse2));
-          nn[rr] = fmaf(sT[rr], s.alpha, -mub);
+          if (MODE != 1) nn[rr] = fmaf(sT[rr], s.alpha, -mub);
         }
       };
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
-        sE = mfma(vfr[kk], tgf[kk], sE);
+        if (MODE != 1) sE = mfma(vfr[kk], tgf[kk], sE);
         pw1(3 * kk);
-        sDF = mfma(vfr[kk], gf[kk], sDF);
+        if (MODE != 2) sDF = mfma(vfr[kk], gf[kk], sDF);
         pw1(3 * kk + 1);
-        sDF = mfma(tvfr[kk], tgf[kk], sDF);
+        if (MODE != 1) sDF = mfma(tvfr[kk], tgf[kk], sDF);
         pw1(3 * kk + 2);
       }
 #pragma unroll
@@ -336,18 +374,24 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
       bf16x8 gzf[2], gztf[2];
 #pragma unroll
       for (int rr = 0; rr < 16; ++rr) {
-        const float gzt = pp[rr] * (sE[rr] - s1);
-        const float gz = fmaf(gzt, nn[rr], pp[rr] * (sDF[rr] - ds));
-        gzf[rr >> 3][rr & 7] = (bf16)gz;
-        gztf[rr >> 3][rr & 7] = (bf16)gzt;
+        if (MODE == 1) {
+          gzf[rr >> 3][rr & 7] = (bf16)(pp[rr] * (sDF[rr] - ds));
+        } else {
+          const float gzt = pp[rr] * (sE[rr] - s1);
+          const float gz = fmaf(gzt, nn[rr], pp[rr] * (sDF[rr] - ds));
+          gzf[rr >> 3][rr & 7] = (bf16)gz;
+          gztf[rr >> 3][rr & 7] = (bf16)gzt;
+        }
       }
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
           aQ[db] = mfma(kT[cc][db], gzf[cc], aQ[db]);
-          aQ[db] = mfma(tkT[cc][db], gztf[cc], aQ[db]);
-          aTQ[db] = mfma(kT[cc][db], gztf[cc], aTQ[db]);
+          if (MODE != 1) {
+            aQ[db] = mfma(tkT[cc][db], gztf[cc], aQ[db]);
+            aTQ[db] = mfma(kT[cc][db], gztf[cc], aTQ[db]);
+          }
         }
     }
     dma_wait();
@@ -356,26 +400,26 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_mfma_kernel(
   if (!iok) return;
   const long long ro = base + (long long)i * s.sn;
   store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
-  store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
+  if (MODE != 1) store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
 }
 
-template <int DK, int DV>
+template <int DK, int DV, int MODE>
 hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
-                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
-                     a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
-                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
+  hipLaunchKernelGGL((bwd_col_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64), MODE>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s,
+                     (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
+                     (const bf16*)a.tv, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1,
+                     (bf16*)a.dk, (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
   return hipGetLastError();
 }
 
-template <int DK, int DV>
+template <int DK, int DV, int MODE>
 hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64)>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
-                     (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
-                     (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,
-                     a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+  hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64), MODE>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s,
+                     (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
+                     (const bf16*)a.tv, (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO,
+                     (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
   return hipGetLastError();
 }
 

@@ -4,13 +4,13 @@
 namespace tvm {
 
 hipError_t launch_bwd_col_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  if (s.D <= 112) return launch_col<112, 128>(s, a, st);
-  if (s.D <= 128) return launch_col<128, 128>(s, a, st);
+  if (s.D <= 112) return launch_col<112, 128, 0>(s, a, st);
+  if (s.D <= 128) return launch_col<128, 128, 0>(s, a, st);
   return hipErrorNotSupported;
 }
 hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  if (s.D <= 112) return launch_row<112, 128>(s, a, st);
-  if (s.D <= 128) return launch_row<128, 128>(s, a, st);
+  if (s.D <= 112) return launch_row<112, 128, 0>(s, a, st);
+  if (s.D <= 128) return launch_row<128, 128, 0>(s, a, st);
   return hipErrorNotSupported;
 }
 

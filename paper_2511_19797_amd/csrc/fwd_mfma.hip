@@ -257,8 +257,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   }
   if (iok && hh == 0) {
     const long long r = (long long)bh * s.N + i;
-    lse[r] = (m * c1 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
-    stats[r] = mubar;
+    if (lse) lse[r] = (m * c1 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;  // (null: forward only, nothing saved)
+    if (stats) stats[r] = mubar;
   }
 }
 

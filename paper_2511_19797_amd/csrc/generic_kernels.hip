@@ -102,9 +102,15 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Shape s, const T* __re
   }
   if (lane == 0) {
     const long long r = (long long)bh * s.N + i;
-    lse[r] = m + __logf(l);
-    stats[r] = mubar;
+    if (lse) lse[r] = m + __logf(l);
+    if (stats) stats[r] = mubar;
   }
+}
+
+// A tensor that one-sided calls leave out (null) reads as zero.
+template <typename T>
+__device__ __forceinline__ float ldz(const T* p, long long i) {
+  return p ? ldf(p + i) : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -122,8 +128,8 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Shape s, const T* __restri
   const long long ro = b * s.sb + h * s.sh + (long long)i * s.sn;
   float a = 0.f, c1 = 0.f;
   for (int c = lane; c < s.D; c += 64) {
-    const float oc = ldf(o + ro + c), toc = ldf(to + ro + c);
-    const float g = ldf(gO + ro + c), gt = ldf(gTO + ro + c);
+    const float oc = ldf(o + ro + c), toc = ldz(to, ro + c);
+    const float g = ldz(gO, ro + c), gt = ldz(gTO, ro + c);
     a = fmaf(g, oc, a);
     a = fmaf(gt, toc, a);
     c1 = fmaf(gt, oc, c1);
@@ -163,12 +169,12 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
   for (int c = lane; c < s.D; c += 64) {
     const long long a = base + (long long)i * s.sn + c;
     qs[w][c] = rowok ? ldf(q + a) : 0.f;
-    tqs[w][c] = rowok ? ldf(tq + a) : 0.f;
-    gs[w][c] = rowok ? ldf(gO + a) : 0.f;
-    tgs[w][c] = rowok ? ldf(gTO + a) : 0.f;
+    tqs[w][c] = rowok ? ldz(tq, a) : 0.f;
+    gs[w][c] = rowok ? ldz(gO, a) : 0.f;
+    tgs[w][c] = rowok ? ldz(gTO, a) : 0.f;
   }
   const long long r = (long long)bh * s.N + (rowok ? i : 0);
-  const float lse_i = lse[r], mubar_i = stats[r], dsig_i = dsig[r], sig1_i = sig1[r];
+  const float lse_i = lse[r], mubar_i = stats ? stats[r] : 0.f, dsig_i = dsig[r], sig1_i = sig1[r];
   __syncthreads();
   float aq[kDMax / 64] = {}, atq[kDMax / 64] = {};
   for (int j0 = 0; j0 < s.N; j0 += kTile) {
@@ -178,8 +184,8 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
       const long long ro = base + (long long)j * s.sn;
       float a0 = 0.f, a1 = 0.f, df = 0.f, e = 0.f;
       for (int c = 0; c < s.D; ++c) {
-        const float kc = ldf(k + ro + c), tkc = ldf(tk + ro + c);
-        const float vc = ldf(v + ro + c), tvc = ldf(tv + ro + c);
+        const float kc = ldf(k + ro + c), tkc = ldz(tk, ro + c);
+        const float vc = ldf(v + ro + c), tvc = ldz(tv, ro + c);
         a0 = fmaf(qs[w][c], kc, a0);
         a1 = fmaf(tqs[w][c], kc, a1);
         a1 = fmaf(qs[w][c], tkc, a1);
@@ -203,7 +209,7 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
       for (int t = 0; t < kDMax / 64; ++t) {
         const int c = lane + 64 * t;
         if (c < s.D) {
-          const float kc = ldf(k + ro + c), tkc = ldf(tk + ro + c);
+          const float kc = ldf(k + ro + c), tkc = ldz(tk, ro + c);
           aq[t] = fmaf(a, kc, aq[t]);
           aq[t] = fmaf(bt, tkc, aq[t]);
           atq[t] = fmaf(bt, kc, atq[t]);
@@ -218,7 +224,7 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
     const int c = lane + 64 * t;
     if (c < s.D) {
       stf(dq + base + (long long)i * s.sn + c, aq[t] * s.alpha);
-      stf(dtq + base + (long long)i * s.sn + c, atq[t] * s.alpha);
+      if (dtq) stf(dtq + base + (long long)i * s.sn + c, atq[t] * s.alpha);
     }
   }
 }
@@ -250,9 +256,9 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
   for (int c = lane; c < s.D; c += 64) {
     const long long a = base + (long long)j * s.sn + c;
     ks[w][c] = rowok ? ldf(k + a) : 0.f;
-    tks[w][c] = rowok ? ldf(tk + a) : 0.f;
+    tks[w][c] = rowok ? ldz(tk, a) : 0.f;
     vs[w][c] = rowok ? ldf(v + a) : 0.f;
-    tvs[w][c] = rowok ? ldf(tv + a) : 0.f;
+    tvs[w][c] = rowok ? ldz(tv, a) : 0.f;
   }
   __syncthreads();
   float ak[kDMax / 64] = {}, atk[kDMax / 64] = {}, av[kDMax / 64] = {}, atv[kDMax / 64] = {};
@@ -263,8 +269,8 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
       const long long ro = base + (long long)i * s.sn;
       float a0 = 0.f, a1 = 0.f, df = 0.f, e = 0.f;
       for (int c = 0; c < s.D; ++c) {
-        const float qc = ldf(q + ro + c), tqc = ldf(tq + ro + c);
-        const float gc = ldf(gO + ro + c), tgc = ldf(gTO + ro + c);
+        const float qc = ldf(q + ro + c), tqc = ldz(tq, ro + c);
+        const float gc = ldz(gO, ro + c), tgc = ldz(gTO, ro + c);
         a0 = fmaf(qc, ks[w][c], a0);
         a1 = fmaf(tqc, ks[w][c], a1);
         a1 = fmaf(qc, tks[w][c], a1);
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
       }
       const long long r = (long long)bh * s.N + i;
       p = __expf(a0 * s.alpha - lse[r]);
-      const float n = a1 * s.alpha - stats[r];
+      const float n = a1 * s.alpha - (stats ? stats[r] : 0.f);
       gzt = p * (e - sig1[r]);
       gz = fmaf(gzt, n, p * (df - dsig[r]));
       pd = p * n;
@@ -292,8 +298,8 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
       for (int t = 0; t < kDMax / 64; ++t) {
         const int c = lane + 64 * t;
         if (c < s.D) {
-          const float qc = ldf(q + ro + c), tqc = ldf(tq + ro + c);
-          const float gc = ldf(gO + ro + c), tgc = ldf(gTO + ro + c);
+          const float qc = ldf(q + ro + c), tqc = ldz(tq, ro + c);
+          const float gc = ldz(gO, ro + c), tgc = ldz(gTO, ro + c);
           av[t] = fmaf(p_, gc, av[t]);
           av[t] = fmaf(pd_, tgc, av[t]);
           atv[t] = fmaf(p_, tgc, atv[t]);
@@ -312,9 +318,9 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
     if (c < s.D) {
       const long long a = base + (long long)j * s.sn + c;
       stf(dk + a, ak[t] * s.alpha);
-      stf(dtk + a, atk[t] * s.alpha);
+      if (dtk) stf(dtk + a, atk[t] * s.alpha);
       stf(dv + a, av[t]);
-      stf(dtv + a, atv[t]);
+      if (dtv) stf(dtv + a, atv[t]);
     }
   }
 }

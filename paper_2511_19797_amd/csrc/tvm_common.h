@@ -44,6 +44,7 @@ struct BwdArgs {
   float *dsig;  // workspace: delta + Sigma_2 per row
   float *sig1;  // workspace: Sigma_1 per row
   float *lse2;  // workspace: lse in log2 units per row (written and read by the hand-scheduled kernels only)
+  int mode;     // upstream gradients that exist: 0 both, 1 gO only (gTO null), 2 gTO only (gO null)
 };
 
 hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipStream_t st);
@@ -56,6 +57,8 @@ bool mfma_supported(const Shape& s, int dtype);
 hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t st);  // a.mode 1 or 2, any head dim
+hipError_t launch_bwd_row_onesided(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96
 hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96, after the former
 

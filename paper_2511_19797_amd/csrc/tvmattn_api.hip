@@ -46,11 +46,16 @@ int resolve(const tvmattn_desc* d, tvm::Shape* s) {
   return TVMATTN_OK;
 }
 
+// Every listed pointer must be non-null and 16-byte aligned, no output may be an input or another
+// output.  Entries that the call's mode does not use are passed as `skip` (a null there is fine,
+// and the pointer takes no part in the aliasing check).
+const void* const skip = reinterpret_cast<const void*>(uintptr_t(1));
 template <size_t NI, size_t NO>
 int check_ptrs(const void* const (&in)[NI], void* const (&out)[NO]) {
   for (size_t i = 0; i < NI; ++i)
-    if (!in[i] || !aligned16(in[i])) return TVMATTN_INVALID_ARG;
+    if (in[i] != skip && (!in[i] || !aligned16(in[i]))) return TVMATTN_INVALID_ARG;
   for (size_t o = 0; o < NO; ++o) {
+    if (out[o] == skip) continue;
     if (!out[o] || !aligned16(out[o])) return TVMATTN_INVALID_ARG;
     for (size_t i = 0; i < NI; ++i)
       if (out[o] == in[i]) return TVMATTN_INVALID_ARG;
@@ -59,6 +64,8 @@ int check_ptrs(const void* const (&in)[NI], void* const (&out)[NO]) {
   }
   return TVMATTN_OK;
 }
+inline const void* unless(bool unused, const void* p) { return unused ? skip : p; }
+inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(skip) : p; }
 
 }  // namespace
 
@@ -95,8 +102,10 @@ int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   tvm::Shape s;
   int rc = resolve(desc, &s);
   if (rc) return rc;
+  if ((lse == nullptr) != (stats == nullptr)) return TVMATTN_INVALID_ARG;  // saved together or not at all
+  const bool nosave = lse == nullptr;
   const void* const in[] = {q, k, v, tq, tk, tv};
-  void* const out[] = {o, to, lse, stats};
+  void* const out[] = {o, to, unless(nosave, (void*)lse), unless(nosave, (void*)stats)};
   rc = check_ptrs(in, out);
   if (rc) return rc;
   tvm::FwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats};
@@ -125,8 +134,13 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   tvm::Shape s;
   int rc = resolve(desc, &s);
   if (rc) return rc;
-  const void* const in[] = {q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO};
-  void* const out[] = {dq, dk, dv, dtq, dtk, dtv, workspace};
+  if (!gO && !gTO) return TVMATTN_INVALID_ARG;
+  // one upstream gradient only: 1 = gO (the tangent inputs and outputs take no part), 2 = gTO
+  const int mode = !gTO ? 1 : !gO ? 2 : 0;
+  const bool m1 = mode == 1;
+  const void* const in[] = {q, k, v, unless(m1, tq), unless(m1, tk), unless(m1, tv), o, unless(m1, to), lse,
+                            unless(m1, (const void*)stats), unless(mode == 2, gO), unless(m1, gTO)};
+  void* const out[] = {dq, dk, dv, unless(m1, dtq), unless(m1, dtk), unless(m1, dtv), workspace};
   rc = check_ptrs(in, out);
   if (rc) return rc;
   const size_t need = tvmattn_jvp_bwd_workspace_bytes(desc);
@@ -134,7 +148,12 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   tvm::BwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
                  static_cast<float*>(workspace),
                  reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 3),
-                 reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * (need / 3))};
+                 reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * (need / 3)), mode};
+  if (m1) {  // not read, not written: whatever was passed
+    a.tq = a.tk = a.tv = a.to = nullptr;
+    a.stats = nullptr;
+    a.dtq = a.dtk = a.dtv = nullptr;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
   hipError_t e = hipSuccess;

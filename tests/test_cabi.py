@@ -95,3 +95,28 @@ def test_bwd_workspace_contract(L):
     bad[18] = None
     assert L.tvmattn_jvp_bwd(ctypes.byref(d), *bad, need, None) == -1
     assert L.tvmattn_set_path(5) == -1 and L.tvmattn_set_path(0) == 0
+
+
+def test_one_sided_backward_argument_rules(L):
+    """gTO NULL: the tangent tensors take no part and may be NULL too; gO NULL: everything else is
+    still required; both NULL is an error.  (Status -3, workspace too small, shows that the
+    pointer checks were passed; nothing is launched.)"""
+    d = desc(B=2, H=3, N=100, D=72)
+    need = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
+    ptrs = [0x1000 * (i + 1) for i in range(19)]
+    Q, K, V, TQ, TK, TV, O, TO, LSE, STATS, GO, GTO, DQ, DK, DV, DTQ, DTK, DTV, WS = range(19)
+
+    def call(nulls, ws=need - 1):
+        p = [None if i in nulls else x for i, x in enumerate(ptrs)]
+        return L.tvmattn_jvp_bwd(ctypes.byref(d), *p, ws, None)
+
+    assert call({GO, GTO}) == -1
+    assert call({GTO}) == -3
+    assert call({GTO, TQ, TK, TV, TO, STATS, DTQ, DTK, DTV}) == -3
+    assert call({GTO, DQ}) == -1 and call({GTO, O}) == -1 and call({GTO, LSE}) == -1
+    assert call({GO}) == -3
+    assert call({GO, TQ}) == -1 and call({GO, DTK}) == -1 and call({GO, STATS}) == -1
+    # forward: lse and stats are saved together or not at all (both NULL is accepted: GPU tests)
+    one = [0x1000 * (i + 1) for i in range(10)]
+    one[9] = None
+    assert fwd_status(L, d, one) == -1

@@ -240,3 +240,63 @@ def test_longest_benchmark_shape_sampled_rows():
         col_sum = g.float().sum(dim=2).abs().max()
         bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
         assert float(col_sum) <= float(bound), (float(col_sum), float(bound))
+
+
+# ---------------------------------------------------------------- one upstream gradient only
+@pytest.mark.parametrize("B,H,N,d,dtype", [
+    (1, 2, 100, 16, "bf16"), (2, 1, 200, 64, "bf16"), (1, 2, 320, 72, "bf16"), (1, 1, 193, 96, "bf16"),
+    (1, 1, 257, 128, "bf16"), (1, 2, 70, 136, "bf16"), (1, 2, 64, 32, "f32"),
+])
+def test_one_sided_backward(B, H, N, d, dtype):
+    """gTO = None is the ordinary attention backward (the oracle with a zero gTO; tangent tensors not
+    even passed), gO = None the tangent path alone (the oracle with a zero gO); a forward that saves
+    nothing returns the same o, to bit for bit."""
+    w = wl.custom(B, H, N, d, dtype)
+    announce(f"one-sided {w}")
+    inp = wl.make_inputs(w, 41)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(*six)
+    o2, to2, none1, none2 = tvm.tvmattn_jvp_fwd(*six, save=False)
+    assert none1 is None and none2 is None and torch.equal(o, o2) and torch.equal(to, to2)
+    g_only = tvm.tvmattn_jvp_bwd(six[0], six[1], six[2], None, None, None, o, None, lse, None, dev["gO"], None)
+    assert g_only[3] is None and g_only[4] is None and g_only[5] is None
+    t_only = tvm.tvmattn_jvp_bwd(*six, o, to, lse, stats, None, dev["gTO"])
+    torch.cuda.synchronize()
+    tol = pu.TOL[dtype]
+    for b in range(B):
+        for h in range(H):
+            a = [wl.to_f64(inp[n][b, h]) for n in wl.NAMES]
+            zero = np.zeros_like(a[6])
+            ref_g = pu.orc.attn_jvp_bwd_head(*a[:6], a[6], zero)
+            ref_t = pu.orc.attn_jvp_bwd_head(*a[:6], zero, a[7])
+            for name, got, ref in zip(pu.BWD_NAMES[:3], g_only[:3], ref_g[:3]):
+                e = pu.rel_err(got[b, h].float().cpu().numpy(), ref)
+                assert e <= tol, ("gO only", name, b, h, e)
+            for name, got, ref in zip(pu.BWD_NAMES, t_only, ref_t):
+                e = pu.rel_err(got[b, h].float().cpu().numpy(), ref)
+                assert e <= tol, ("gTO only", name, b, h, e)
+
+
+def test_one_sided_backward_full_size():
+    """C4 in the launch configuration bench.py reports for the ordinary-attention backward: sampled heads
+    against the oracle, key-gradient column sums for all."""
+    w = wl.CONFIGS["C4"]
+    announce(f"one-sided full-size {w}")
+    inp = wl.make_inputs(w, 104)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(*six)
+    dq, dk, dv, _, _, _ = tvm.tvmattn_jvp_bwd(six[0], six[1], six[2], None, None, None, o, None, lse, None,
+                                              dev["gO"], None)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert bool(torch.isfinite(t.float()).all())
+    for (b, h) in ((0, 0), (w.B - 1, w.H - 1), (7, 3)):
+        a = [wl.to_f64(inp[n][b, h]) for n in wl.NAMES]
+        ref = pu.orc.attn_jvp_bwd_head(*a[:6], a[6], np.zeros_like(a[6]))
+        for name, got, r in zip(pu.BWD_NAMES[:3], (dq, dk, dv), ref[:3]):
+            e = pu.rel_err(got[b, h].float().cpu().numpy(), r)
+            assert e <= pu.TOL["bf16"], (name, b, h, e)
+    col_sum = dk.float().sum(dim=2).abs().max()
+    assert float(col_sum) <= 4.0 * (2.0 ** -8) * float(dk.float().abs().max()) * (w.N ** 0.5)
