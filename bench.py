@@ -39,12 +39,12 @@ KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.
 # figures and commands in profiles/tvmattn_kernels_C4_counters.md.  None where not measured.
 _KIB = 1024.0
 MEASURED_TRAFFIC = {
-    ("C4", "fwd"): 110657.5 * _KIB * 2.0 + 75780.1 * _KIB,
-    ("C4", "bwd_row"): 185467.3 * _KIB * 2.0 + 76800.0 * _KIB,
-    ("C4", "bwd_col"): 149643.7 * _KIB * 2.0 + 147456.0 * _KIB,
-    ("C3", "fwd"): 55365.4 * _KIB * 2.0 + 37894.2 * _KIB,
-    ("C3", "bwd_row"): 92794.3 * _KIB * 2.0 + 38400.0 * _KIB,
-    ("C3", "bwd_col"): 74890.9 * _KIB * 2.0 + 73728.0 * _KIB,
+    ("C4", "fwd"): 110665.0 * _KIB * 2.0 + 75776.0 * _KIB,
+    ("C4", "bwd_row"): 185467.2 * _KIB * 2.0 + 76800.0 * _KIB,
+    ("C4", "bwd_col"): 149646.2 * _KIB * 2.0 + 147456.0 * _KIB,
+    ("C3", "fwd"): 55369.0 * _KIB * 2.0 + 37888.0 * _KIB,
+    ("C3", "bwd_row"): 92794.4 * _KIB * 2.0 + 38400.0 * _KIB,
+    ("C3", "bwd_col"): 74893.3 * _KIB * 2.0 + 73728.0 * _KIB,
 }
 
 

@@ -71,7 +71,7 @@ inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(sk
 
 extern "C" {
 
-int tvmattn_version(void) { return 100; }
+int tvmattn_version(void) { return 200; }  // 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
