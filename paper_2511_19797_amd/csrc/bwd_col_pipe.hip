@@ -59,10 +59,20 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   constexpr int NS = 3 * NKS;                      // products of a score-type phase
   constexpr int NH = 3 * NDB;                      // products of half an output phase
   constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
-  // the 48 pieces of P, N, Pd of a block are dealt out over the products of E (from FS on) and OV(0) in
-  // proportion, but half 0 (the first 24) must be complete when OV(0) starts
-  constexpr int PW1_PROP = (48 * (NS - FS) + NS - FS + NH - 1) / (NS - FS + NH);
-  constexpr int PW1_E = PW1_PROP > 24 ? PW1_PROP : 24;
+  // The 48 pieces of P, N, Pd of a block are dealt out by cost over the products of E (from FS on) and of
+  // OV(0), half 0 (the first 24) complete when OV(0) starts; the 40 pieces of gZ, gZt over those of OV(1)
+  // and OK(0), half 0 complete when OK(0) starts.  The transposing reads of those phases count as load.
+  struct C {
+    static constexpr int pw1(int u) { return ((u % 12) >> 1 == 1 || (u % 12) >> 1 == 2) ? 12 : 8; }
+    static constexpr int pw2(int) { return 8; }
+    static constexpr int base1(int v) {
+      return v < NS ? 8 * share_count(v, 2 * NDB, NS) + (v < FS ? 4 * share_count(v, 4, FS) : 0)
+                    : 8 * share_count(v - NS, 2 * NDB, NH);
+    }
+    static constexpr int base2(int v) { return 8 * share_count(v % NH, 2 * NDB, NH); }
+  };
+  static constexpr Deal<NS + NH> kPw1 = deal_out<NS + NH>(48, FS, NS, 24, C::pw1, C::base1);
+  static constexpr Deal<2 * NH> kPw2 = deal_out<2 * NH>(40, 0, NH, 20, C::pw2, C::base2);
   constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
   // the tile after next is fetched behind the products of the phases that carry no pointwise work:
   // S and OK(1) of both blocks (the last of them behind the tile's barrier)
@@ -175,9 +185,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       bf16x8 xT[NDB], txT[NDB], yT[NDB], tyT[NDB];  // transposed fragments of the half in use / of the next half
 
       float ta[8], tb[8], wa[8], wb[8];  // temporaries of element pair e, alive between its pieces
-      // P, N, Pd of the block as a stream of 8 x 6 pieces (pair e = u / 6: elements 2e, 2e+1)
+      // P, N, Pd of the block as a stream of 8 x 6 pieces (pair e: elements 2e, 2e+1)
       auto pw1_op = [&](int u) {
-        const int e = u / 6, st = u - 6 * e, g4 = e >> 1, t = (2 * e) & 3;
+        // two pairs take turns, so that no piece reads what the piece right before it wrote
+        const int e = 2 * (u / 12) + (u & 1), st = (u % 12) >> 1, g4 = e >> 1, t = (2 * e) & 3;
         if (st == 0) {
           float s0 = sS[2 * e], s1 = sS[2 * e + 1];
           if (RAG) {  // queries beyond N: probability 0
@@ -199,7 +210,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       };
       // gZ, gZt of the block as a stream of 8 x 5 pieces (E, DF come with sig1, dsig already subtracted)
       auto pw2_op = [&](int u) {
-        const int e = u / 5, st = u - 5 * e;
+        const int e = 2 * (u / 10) + (u & 1), st = (u % 10) >> 1;  // two pairs take turns here too
         if (st == 0) pw_mul2(ta[e], tb[e], pp[2 * e], sE[2 * e], pp[2 * e + 1], sE[2 * e + 1]);
         else if (st == 1) pw_mul2(wa[e], wb[e], pp[2 * e], sDF[2 * e], pp[2 * e + 1], sDF[2 * e + 1]);
         else if (st == 2) pw_fmac2(wa[e], wb[e], ta[e], nn[2 * e], tb[e], nn[2 * e + 1]);
@@ -229,11 +240,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + ib * TX::kBlkBytes + k2 * 32);
         }
 #pragma unroll
-        TVM_SHARE(x, m, 12, NS) {  // lse, stats of half 0; -sig1 and -dsig of the block, the start values of E and DF
-          if (x < 2) la[x] = lds_read_f4(rv, ib * 128 + x * 32);
-          else if (x < 4) ma[x - 2] = lds_read_f4(rv, 256 + ib * 128 + (x - 2) * 32);
-          else if (x < 8) sa[x - 4] = lds_read_f4(rv, 768 + ib * 128 + (x - 4) * 32);
-          else da[x - 8] = lds_read_f4(rv, 512 + ib * 128 + (x - 8) * 32);
+        TVM_SHARE(x, m, 12, NS) {  // -sig1 and -dsig of the block first (the first products of E start from them), then lse, stats of half 0
+          if (x < 4) sa[x] = lds_read_f4(rv, 768 + ib * 128 + x * 32);
+          else if (x < 8) da[x - 4] = lds_read_f4(rv, 512 + ib * 128 + (x - 4) * 32);
+          else if (x < 10) la[x - 8] = lds_read_f4(rv, ib * 128 + (x - 8) * 32);
+          else ma[x - 10] = lds_read_f4(rv, 256 + ib * 128 + (x - 10) * 32);
         }
 #pragma unroll
         TVM_SHARE(x, ib * NQB + m, NDMA, 2 * NQB) dma(x, in2, sbf, in2last);
@@ -279,7 +290,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         }
         if (m >= FS) {
 #pragma unroll
-          TVM_SHARE(u, m - FS, PW1_E, NS - FS) pw1_op(u);
+          for (int u = kPw1.first[m]; u < kPw1.first[m + 1]; ++u) pw1_op(u);
         }
       }
       PROF(1);
@@ -297,7 +308,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
         }
 #pragma unroll
-        TVM_SHARE(u, m, 48 - PW1_E, NH) pw1_op(PW1_E + u);
+        for (int u = kPw1.first[NS + m]; u < kPw1.first[NS + m + 1]; ++u) pw1_op(u);
       }
       PROF(2);
       // ---- OV(1), with gZ, gZt of half 0
@@ -315,7 +326,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         }
         if (m == 0) landed(sE, sDF);  // at least four products after the last one of E
 #pragma unroll
-        TVM_SHARE(u, m, 20, NH) pw2_op(u);
+        for (int u = kPw2.first[m]; u < kPw2.first[m + 1]; ++u) pw2_op(u);
       }
       PROF(3);
       // ---- OK(0), with gZ, gZt of half 1
@@ -332,7 +343,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(1, d2));
         }
 #pragma unroll
-        TVM_SHARE(u, m, 20, NH) pw2_op(20 + u);
+        for (int u = kPw2.first[NH + m]; u < kPw2.first[NH + m + 1]; ++u) pw2_op(u);
       }
       PROF(4);
       if (ib == 1) {

@@ -102,6 +102,50 @@ __device__ __forceinline__ void pw_fmac2(float& a, float& b, float x0, float y0,
 __device__ __forceinline__ void pw_cvt(unsigned& r, float lo, float hi) {
   asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
 }
+// Dealing side operations out over the products of a phase by cost.  Operation u (issued in order) costs
+// cost(u) cycles, slot s (the gap behind product s) already carries base(s) cycles of other side
+// instructions; slots before s0 take none.  Greedy: every slot takes operations while that brings it closer
+// to the average load of the slots that are left.  At least k_ops operations are placed before slot k_slot
+// (a deadline: the products from k_slot on read their results).  Operations [first[s], first[s+1]) go
+// behind product s.
+template <int NSLOT>
+struct Deal {
+  int first[NSLOT + 1];
+};
+__host__ __device__ constexpr int share_count(int m, int cnt, int n) { return (m + 1) * cnt / n - m * cnt / n; }
+template <int NSLOT, typename Cost, typename Base>
+__host__ __device__ constexpr void deal_range(Deal<NSLOT>& d, int u0, int u1, int sa, int sb, Cost cost, Base base) {
+  int total = 0;
+  for (int u = u0; u < u1; ++u) total += cost(u);
+  for (int s = sa; s < sb; ++s) total += base(s);
+  int u = u0;
+  for (int s = sa; s < sb; ++s) {
+    d.first[s] = u;
+    const int left = sb - s;
+    const int target = (total + left - 1) / left;
+    int load = base(s);
+    if (s == sb - 1) {
+      while (u < u1) load += cost(u++);
+    } else {
+      while (u < u1 && load + cost(u) / 2 < target) load += cost(u++);
+    }
+    total -= load;
+  }
+}
+template <int NSLOT, typename Cost, typename Base>
+__host__ __device__ constexpr Deal<NSLOT> deal_out(int nops, int s0, int k_slot, int k_ops, Cost cost, Base base) {
+  Deal<NSLOT> d{};
+  for (int s = 0; s <= NSLOT; ++s) d.first[s] = s < s0 ? 0 : nops;
+  if (s0 >= NSLOT) return d;
+  deal_range(d, 0, nops, s0, NSLOT, cost, base);
+  if (k_slot > s0 && k_slot < NSLOT && d.first[k_slot] < k_ops) {
+    deal_range(d, 0, k_ops, s0, k_slot, cost, base);
+    deal_range(d, k_ops, nops, k_slot, NSLOT, cost, base);
+  }
+  d.first[NSLOT] = nops;
+  return d;
+}
+
 // From here on the compiler may read the tiles: every use below this point depends on it.  Placed
 // after enough further products that the ones writing the tiles have finished.
 __device__ __forceinline__ void landed(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
