@@ -4,8 +4,9 @@
  *
  * Operation (Terminal Velocity Matching, App. C "Flash Attention JVP with
  * Backward Pass"; eq. (sdpa), the "Background" paragraph and the equations
- * under "Step 1").  Per batch b and head h, with Q,K,V and tangents
- * tQ,tK,tV all [N,D] and alpha = scale:
+ * under "Step 1").  Per batch b and head h, with Q, tQ [M,D] (queries), K, V,
+ * tK, tV [N,D] (keys; the paper's Background allows M != N, self-attention has
+ * M = N) and alpha = scale:
  *
  *     z  = alpha Q K^T                       zt = alpha (tQ K^T + Q tK^T)
  *     P  = softmax_rows(z)                   lse_i   = log sum_j exp(z_ij)
@@ -24,12 +25,15 @@
  *     caller owns every buffer; the library never allocates, frees or
  *     synchronises.  All work is enqueued on `hip_stream` (a hipStream_t cast
  *     to void*; NULL is the default stream).
- *   - Big tensors have logical shape [B,H,N,D], element type `dtype`, innermost
- *     stride 1 and the element strides given in the descriptor, which apply to
- *     every [B,H,N,D] tensor of the call (inputs, outputs, gradients alike).
- *     All strides 0 means contiguous [B,H,N,D].  Base pointers must be 16-byte
- *     aligned and stride_n, stride_h, stride_b multiples of 16 bytes.
- *   - Row vectors (lse, stats) are contiguous [B,H,N] float32.
+ *   - Big tensors have element type `dtype` and innermost stride 1.  Key-side
+ *     tensors (k, v, tk, tv and their gradients) have logical shape [B,H,N,D]
+ *     and the element strides stride_b, stride_h, stride_n of the descriptor;
+ *     query-side tensors (q, tq, o, to, gO, gTO, dq, dtq) have [B,H,M,D] and
+ *     qstride_b, qstride_h, qstride_n.  All three strides of a side 0 means
+ *     contiguous (for the query side with M = 0 or M = N: the key side's
+ *     strides).  Base pointers must be 16-byte aligned and all strides
+ *     multiples of 16 bytes.
+ *   - Row vectors (lse, stats) are contiguous [B,H,M] float32.
  *   - Arithmetic: products of dtype elements accumulate in float32; softmax and
  *     all row statistics are float32; outputs are rounded once to dtype.
  *   - Return value: TVMATTN_OK (0) or a negative tvmattn_status.  Arguments are
@@ -65,13 +69,18 @@ typedef enum {
 typedef struct {
   int32_t B;        /* batch                       >= 1 */
   int32_t H;        /* heads                       >= 1 */
-  int32_t N;        /* tokens (queries = keys)     >= 1 */
+  int32_t N;        /* keys (and queries, unless M is set)  >= 1 */
   int32_t D;        /* head dimension              1..256 */
   int32_t dtype;    /* tvmattn_dtype */
   float scale;      /* alpha; 0 selects 1/sqrt(D) (the true D, never a padded one) */
-  int64_t stride_b; /* element strides of every [B,H,N,D] tensor; all zero = contiguous */
+  int64_t stride_b; /* element strides of the key-side [B,H,N,D] tensors; all zero = contiguous */
   int64_t stride_h;
   int64_t stride_n;
+  int32_t M;        /* queries; 0 = N (self-attention) */
+  int32_t reserved; /* 0 */
+  int64_t qstride_b; /* element strides of the query-side [B,H,M,D] tensors; all zero = contiguous, */
+  int64_t qstride_h; /* or the key side's strides where M is 0 or N */
+  int64_t qstride_n;
 } tvmattn_desc;
 
 /* Library version, major*10000 + minor*100 + patch. */

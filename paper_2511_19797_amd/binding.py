@@ -19,7 +19,9 @@ TVMATTN_F32, TVMATTN_BF16 = 0, 1
 class tvmattn_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("M", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("qstride_b", ctypes.c_int64), ("qstride_h", ctypes.c_int64), ("qstride_n", ctypes.c_int64)]
 
 
 class TvmattnError(RuntimeError):
@@ -84,26 +86,33 @@ def _check(status):
         raise TvmattnError(status, tvmattn_strerror(status))
 
 
-def make_desc(x: torch.Tensor, scale=0.0) -> tvmattn_desc:
-    """Descriptor for a [B,H,N,D] tensor (any strides with unit innermost stride)."""
-    if x.dim() != 4:
-        raise ValueError("expected a [B,H,N,D] tensor")
+def make_desc(x: torch.Tensor, scale=0.0, q: torch.Tensor = None) -> tvmattn_desc:
+    """Descriptor for key-side tensors shaped and strided like `x` [B,H,N,D] and query-side tensors like `q`
+    [B,H,M,D] (default: like `x`); any strides with unit innermost stride."""
+    q = x if q is None else q
+    for t in (x, q):
+        if t.dim() != 4:
+            raise ValueError("expected [B,H,N,D] tensors")
+        if t.stride(3) != 1:
+            raise ValueError("innermost stride must be 1")
     if x.dtype == torch.float32:
         dt = TVMATTN_F32
     elif x.dtype == torch.bfloat16:
         dt = TVMATTN_BF16
     else:
         raise ValueError(f"unsupported dtype {x.dtype}")
-    if x.stride(3) != 1:
-        raise ValueError("innermost stride must be 1")
     B, H, N, D = x.shape
-    return tvmattn_desc(B, H, N, D, dt, float(scale), x.stride(0), x.stride(1), x.stride(2))
+    if q.dtype != x.dtype or (q.shape[0], q.shape[1], q.shape[3]) != (B, H, D):
+        raise ValueError("query-side and key-side tensors must agree in B, H, D and dtype")
+    return tvmattn_desc(B, H, N, D, dt, float(scale), x.stride(0), x.stride(1), x.stride(2),
+                        q.shape[2], 0, q.stride(0), q.stride(1), q.stride(2))
 
 
 def _same_layout(ref, *ts):
     for t in ts:
         if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype or t.device != ref.device:
-            raise ValueError("all [B,H,N,D] tensors of one call must share shape, strides, dtype and device")
+            raise ValueError("all tensors of one side (query side [B,H,M,D], key side [B,H,N,D]) of a call must "
+                             "share shape, strides, dtype and device")
         if not t.is_cuda:
             raise ValueError("device tensors required")
 
@@ -119,9 +128,10 @@ def _ptr(t):
 def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True):
     """Returns (o, to, lse, stats).  `out`, if given, is that same tuple of preallocated tensors.
     save=False: nothing is kept for a backward (lse and stats are None)."""
-    _same_layout(q, k, v, tq, tk, tv)
-    desc = make_desc(q, scale)
-    B, H, N, _ = q.shape
+    _same_layout(q, tq)
+    _same_layout(k, v, tk, tv)
+    desc = make_desc(k, scale, q)
+    B, H, N, _ = q.shape  # row vectors go with the queries
     if out is None:
         o, to = torch.empty_like(q), torch.empty_like(q)
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if save else None
@@ -135,8 +145,9 @@ def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True):
     return o, to, lse, stats
 
 
-def tvmattn_jvp_bwd_workspace_bytes(x, scale=0.0):
-    desc = make_desc(x, scale)
+def tvmattn_jvp_bwd_workspace_bytes(q, scale=0.0, k=None):
+    """`q`: a query-side tensor; `k`: a key-side one (default: self-attention, shaped like `q`)."""
+    desc = make_desc(q if k is None else k, scale, q)
     return int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
 
 
@@ -145,12 +156,14 @@ def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, 
 
     gTO=None: the ordinary attention backward (gradient of <gO, O> alone); tq, tk, tv, to, stats may be
     None and dtq, dtk, dtv come back as None.  gO=None: the gradient of <gTO, tO> alone."""
-    _same_layout(*[t for t in (q, k, v, tq, tk, tv, o, to, gO, gTO) if t is not None])
-    desc = make_desc(q, scale)
-    if out is None:
-        out = tuple(torch.empty_like(q) if (gTO is not None or n < 3) else None for n in range(6))
+    _same_layout(*[t for t in (q, tq, o, to, gO, gTO) if t is not None])
+    _same_layout(*[t for t in (k, v, tk, tv) if t is not None])
+    desc = make_desc(k, scale, q)
+    if out is None:  # dq, dk, dv, dtq, dtk, dtv
+        out = tuple(torch.empty_like(q if n in (0, 3) else k) if (gTO is not None or n < 3) else None for n in range(6))
     else:
-        _same_layout(q, *[t for t in out if t is not None])
+        _same_layout(q, *[t for n, t in enumerate(out) if t is not None and n in (0, 3)])
+        _same_layout(k, *[t for n, t in enumerate(out) if t is not None and n not in (0, 3)])
     need = int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)

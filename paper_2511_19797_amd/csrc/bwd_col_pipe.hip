@@ -88,13 +88,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
-  const long long rbase = (long long)bh * s.N;
+  const long long base = b * s.sb + h * s.sh;     // key side (fixed)
+  const long long qbase = b * s.qsb + h * s.qsh;  // query side (streamed)
+  const long long rbase = (long long)bh * s.M;
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
 
-  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned pitch = (unsigned)(s.qsn * 2);  // row pitch of the streamed (query-side) tensors in bytes
   const unsigned lds0 = lds_addr_of(lds);
-  const int nt = (s.N + 63) >> 6;   // tiles
+  const int nt = (s.M + 63) >> 6;   // tiles
   const int ilast = (nt - 1) * 64;  // first query of the last tile; loads "beyond" it fetch it again, unused
   // Per-lane byte offsets of this wave's loads within a tile, worked out once: for whole tiles, and for
   // the last tile, where rows past the end fetch its last row again (masked rows, unused).  Wave w also
@@ -104,15 +105,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   {
     const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
     of_full = TX::offsets(lx, pitch, 64);
-    of_last = TX::offsets(lx, pitch, s.N - ilast);
+    of_last = TX::offsets(lx, pitch, s.M - ilast);
     rv_full = (unsigned)lane * 4u;
-    rv_last = (unsigned)min(lane, s.N - ilast - 1) * 4u;
+    rv_last = (unsigned)min(lane, s.M - ilast - 1) * 4u;
   }
   const float* const rowsrc = (wave == 0 ? lse2w : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
   // wave-load number x (compile-time) of the tile whose first query is i0 (< N), into the stage at `buf`;
   // `last`: that tile is the last one
   auto dma = [&](int x, int i0, unsigned buf, bool last) {
-    const long long ro = base + (long long)i0 * s.sn;
+    const long long ro = qbase + (long long)i0 * s.qsn;
     const int t = x % TX::IPW;
     const unsigned off = last ? of_last.o[t] : of_full.o[t];
     if (x < TX::IPW) TX::issue_at(off, t, q + ro, buf, wave);
@@ -192,8 +193,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
         if (st == 0) {
           float s0 = sS[2 * e], s1 = sS[2 * e + 1];
           if (RAG) {  // queries beyond N: probability 0
-            if (i0 + ib * 32 + drow(2 * e, hh) >= s.N) s0 = -INFINITY;
-            if (i0 + ib * 32 + drow(2 * e + 1, hh) >= s.N) s1 = -INFINITY;
+            if (i0 + ib * 32 + drow(2 * e, hh) >= s.M) s0 = -INFINITY;
+            if (i0 + ib * 32 + drow(2 * e + 1, hh) >= s.M) s1 = -INFINITY;
           }
           pw_fma2(ta[e], tb[e], s0, s1, c1u, f4(la[g4], t), f4(la[g4], t + 1));
         } else if (st == 1) {
@@ -384,7 +385,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 
   // One copy of the whole-tile code serves every whole tile (it is the copy the compiler allocates
   // registers for best); tiles that do not exist are "fetched" as the last tile again.
-  const int nfull = s.N >> 6;  // tiles without queries beyond N
+  const int nfull = s.M >> 6;  // tiles without queries beyond M
   unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
   for (int t = 0; t < nfull; ++t) {
     tile(std::false_type{}, st0, st1, st2, t * 64, min((t + 2) * 64, ilast), t + 3 >= nt, t + 1 == nt);

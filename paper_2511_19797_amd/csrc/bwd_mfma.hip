@@ -14,7 +14,7 @@ hipError_t launch_bwd_row_onesided2(const Shape& s, const BwdArgs& a, hipStream_
 
 bool mfma_supported(const Shape& s, int dtype) {
   // bf16, 16-byte chunks, and row pitches whose tile offsets fit the 32-bit lane offsets of the LDS loads
-  return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22);
+  return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22) && s.qsn < (1ll << 22);
 }
 
 // The query-side kernel runs first in both families: it leaves the row scalars of Step 1 of

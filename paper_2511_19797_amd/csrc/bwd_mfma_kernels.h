@@ -70,20 +70,21 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
-  const long long rbase = (long long)bh * s.N;
+  const long long base = b * s.sb + h * s.sh;     // key side (fixed)
+  const long long qbase = b * s.qsb + h * s.qsh;  // query side (streamed)
+  const long long rbase = (long long)bh * s.M;
   const int j = fb * kFix + wave * 32 + ic;  // this lane's key
   const bool jok = j < s.N;
 
   const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
-  const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
+  const unsigned pitch = (unsigned)(s.qsn * 2);  // row pitch of the streamed (query-side) tensors in bytes
   const unsigned lds0 = lds_addr_of(lds);
   // wave w also fetches row vector w (lse, stats, dsig, sig1) of the tile, one float per lane
   // (lanes past the tile or past the last row re-read the last row's value: masked rows, unused)
   const float* const rowsrc = (wave == 0 ? lse : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
   auto issue = [&](int i0, unsigned buf) {  // i0 < N
-    const long long ro = base + (long long)i0 * s.sn;
-    const int left = s.N - i0;
+    const long long ro = qbase + (long long)i0 * s.qsn;
+    const int left = s.M - i0;
     TX::issue(lx, q + ro, pitch, left, buf, wave);
     if (MODE != 1) TX::issue(lx, tq + ro, pitch, left, buf + OFF_TQ, wave);
     if (MODE != 2) TX::issue(lx, gO + ro, pitch, left, buf + OFF_G, wave);
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
 
   dma_wait();
   __syncthreads();  // tile 0 has landed
-  for (int i0 = 0, it = 0; i0 < s.N; i0 += kTS, ++it) {
+  for (int i0 = 0, it = 0; i0 < s.M; i0 += kTS, ++it) {
     const char* lds_q = lds + (it & 1) * BUF;
     const char* lds_tq = lds_q + OFF_TQ;
     const char* lds_g = lds_q + OFF_G;
@@ -120,11 +121,11 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
     const float* row_mub = row_lse + 64;
     const float* row_dsig = row_lse + 128;
     const float* row_sig1 = row_lse + 192;
-    if (i0 + kTS < s.N) issue(i0 + kTS, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
+    if (i0 + kTS < s.M) issue(i0 + kTS, lds0 + ((it + 1) & 1) * BUF);  // uniform: lands during this tile
 
 #pragma unroll
     for (int ib = 0; ib < kTS / 32; ++ib) {
-      if (i0 + ib * 32 >= s.N) break;  // uniform
+      if (i0 + ib * 32 >= s.M) break;  // uniform
       f32x16 sS = zero16(), sT = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKS; ++kk) {
@@ -149,10 +150,10 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
           sDF = mfma(tgf, tvf[kk], sDF);
         }
       }
-      if (i0 + ib * 32 + 32 > s.N) {  // uniform: ragged last block, queries >= N get probability 0
+      if (i0 + ib * 32 + 32 > s.M) {  // uniform: ragged last block, queries >= M get probability 0
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (i0 + ib * 32 + drow(r, hh) >= s.N) sS[r] = -INFINITY;
+          if (i0 + ib * 32 + drow(r, hh) >= s.M) sS[r] = -INFINITY;
       }
       bf16x8 pf[2], pdf[2], gzf[2], gztf[2];
 #pragma unroll
@@ -235,13 +236,14 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
   __shared__ __attribute__((aligned(16))) char lds[2 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
-  const int nfb = (s.N + kFix - 1) / kFix;
+  const int nfb = (s.M + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
+  const long long base = b * s.sb + h * s.sh;     // key side (streamed)
+  const long long qbase = b * s.qsb + h * s.qsh;  // query side (fixed)
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
-  const bool iok = i < s.N;
+  const bool iok = i < s.M;
 
   const typename TK::Lane lk = TK::lane_setup(s.D, wave, lane);
   const typename TV::Lane lv = TV::lane_setup(s.D, wave, lane);
@@ -263,18 +265,18 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
   issue(0, lds0);
 
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS];
-  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  if (MODE != 1) gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
-  if (MODE != 2) gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
-  if (MODE != 1) gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(qf, q + qbase, s.qsn, i, s.M, s.D, hh);
+  if (MODE != 1) gld_frags<NKS>(tqf, tq + qbase, s.qsn, i, s.M, s.D, hh);
+  if (MODE != 2) gld_frags<NKS>(gf, gO + qbase, s.qsn, i, s.M, s.D, hh);
+  if (MODE != 1) gld_frags<NKS>(tgf, gTO + qbase, s.qsn, i, s.M, s.D, hh);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row);
   // they are also written out for the key-side kernel, which runs after this one.
   float ds = 0.f, s1 = 0.f;
   {
     bf16x8 of[NKS], tof[NKS];
-    gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
-    if (MODE != 1) gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
+    gld_frags<NKS>(of, o + qbase, s.qsn, i, s.M, s.D, hh);
+    if (MODE != 1) gld_frags<NKS>(tof, to + qbase, s.qsn, i, s.M, s.D, hh);
 #pragma unroll
     for (int kk = 0; kk < NKS; ++kk)
 #pragma unroll
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
     s1 += xhalf(s1);
   }
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
-  const long long r = (long long)bh * s.N + (iok ? i : 0);
+  const long long r = (long long)bh * s.M + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
   const float mub = (MODE != 1 && iok) ? stats[r] : 0.f;
   if (iok && hh == 0) {
@@ -398,7 +400,7 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
     __syncthreads();  // next tile landed; everyone is done with this one
   }
   if (!iok) return;
-  const long long ro = base + (long long)i * s.sn;
+  const long long ro = qbase + (long long)i * s.qsn;
   store_acc<NDB>(dq + ro, aQ, s.alpha, s.D, hh);
   if (MODE != 1) store_acc<NDB>(dtq + ro, aTQ, s.alpha, s.D, hh);
 }
@@ -415,7 +417,7 @@ hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
 
 template <int DK, int DV, int MODE>
 hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  const int nfb = (s.N + kFix - 1) / kFix;
+  const int nfb = (s.M + kFix - 1) / kFix;
   hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64), MODE>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s,
                      (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
                      (const bf16*)a.tv, (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO,

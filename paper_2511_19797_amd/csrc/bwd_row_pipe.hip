@@ -67,13 +67,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   PROF_ENTRY;
   const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
-  const int nfb = (s.N + kFix - 1) / kFix;
+  const int nfb = (s.M + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
+  const long long base = b * s.sb + h * s.sh;     // key side (streamed)
+  const long long qbase = b * s.qsb + h * s.qsh;  // query side (fixed)
   const int i = fb * kFix + wave * 32 + ic;  // this lane's query
-  const bool iok = i < s.N;
+  const bool iok = i < s.M;
 
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
   const unsigned lds0 = lds_addr_of(lds);
@@ -115,16 +116,16 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
-  const long long r = (long long)bh * s.N + (iok ? i : 0);
+  const long long r = (long long)bh * s.M + (iok ? i : 0);
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
   const float mub = iok ? stats[r] : 0.f;
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS], of[NKS], tof[NKS];
-  gld_frags<NKS>(gf, gO + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tgf, gTO + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(of, o + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tof, to + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(gf, gO + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tgf, gTO + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(of, o + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tof, to + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(qf, q + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tqf, tq + qbase, s.qsn, i, s.M, s.D, hh);
   PROF_P(11);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row), two
@@ -447,15 +448,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     // two output tiles through a region of its own
     const unsigned lw = lds0 + wave * (32 * (64 * NDB + 16));
     const int row0 = fb * kFix + wave * 32;
-    store_tile_coalesced<NDB>(lw, dq + base, s.sn, row0, s.N, s.D, aQ, s.alpha, lane);
-    store_tile_coalesced<NDB>(lw, dtq + base, s.sn, row0, s.N, s.D, aTQ, s.alpha, lane);
+    store_tile_coalesced<NDB>(lw, dq + qbase, s.qsn, row0, s.M, s.D, aQ, s.alpha, lane);
+    store_tile_coalesced<NDB>(lw, dtq + qbase, s.qsn, row0, s.M, s.D, aTQ, s.alpha, lane);
   }
   PROF_EXIT;
 }
 
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  const int nfb = (s.N + kFix - 1) / kFix;
+  const int nfb = (s.M + kFix - 1) / kFix;
   hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,

@@ -1,6 +1,6 @@
 // Forward with tangent on the bf16 matrix cores (gfx950).
 //
-// One workgroup = NW waves, 32 query rows per wave, all of one (batch, head); a wave keeps Q, tQ
+// One workgroup = NW waves, 32 query rows per wave, all of one (batch, head) (M queries, N keys); a wave keeps Q, tQ
 // as B-operand fragments in registers for the whole kernel.  Keys are streamed in tiles of 64
 // through LDS (row-major, swizzled): K, tK are read as score-product A operands, V, tV through
 // the transposing LDS read as output-product A operands.  The next tile's global loads are
@@ -53,13 +53,14 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   static_assert(kBN == 32, "one block per tile: the spare-column rows are planted by 32 lanes");
   const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
-  const int nmb = (s.N + BM - 1) / BM;
+  const int nmb = (s.M + BM - 1) / BM;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nmb, mb = wg - bh * nmb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;
+  const long long base = b * s.sb + h * s.sh;     // key side
+  const long long qbase = b * s.qsb + h * s.qsh;  // query side
   const int i = mb * BM + wave * 32 + ic;  // this lane's query row
-  const bool iok = i < s.N;
+  const bool iok = i < s.M;
 
   const unsigned pitch = (unsigned)(s.sn * 2);  // row pitch in bytes
   const unsigned lds0 = lds_addr_of(lds);
@@ -105,8 +106,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   issue(0, lds0);
 
   bf16x8 qf[NKS], tqf[NKS];
-  gld_frags<NKS>(qf, q + base, s.sn, i, s.N, s.D, hh);
-  gld_frags<NKS>(tqf, tq + base, s.sn, i, s.N, s.D, hh);
+  gld_frags<NKS>(qf, q + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tqf, tq + qbase, s.qsn, i, s.M, s.D, hh);
 
   f32x16 accO[NDB], accT[NDB];
 #pragma unroll
@@ -252,11 +253,11 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
     const unsigned lw = lds0 + (unsigned)wave * (32 * (64 * NDB + 16));
     static_assert(NW * 32 * (64 * NDB + 16) <= 2 * BUF, "staging fits in the tile buffers");
     const int row0 = mb * BM + wave * 32;
-    store_tile_coalesced<NDB>(lw, o + base, s.sn, row0, s.N, s.D, accO, inv, lane);
-    store_tile_coalesced<NDB>(lw, to + base, s.sn, row0, s.N, s.D, accT, 1.f, lane);
+    store_tile_coalesced<NDB>(lw, o + qbase, s.qsn, row0, s.M, s.D, accO, inv, lane);
+    store_tile_coalesced<NDB>(lw, to + qbase, s.qsn, row0, s.M, s.D, accT, 1.f, lane);
   }
   if (iok && hh == 0) {
-    const long long r = (long long)bh * s.N + i;
+    const long long r = (long long)bh * s.M + i;
     if (lse) lse[r] = (m * c1 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;  // (null: forward only, nothing saved)
     if (stats) stats[r] = mubar;
   }
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
   constexpr int NW = FWD_NW, BN = FWD_BN;  // waves per workgroup, keys per LDS tile
-  const int nmb = (s.N + 32 * NW - 1) / (32 * NW);
+  const int nmb = (s.M + 32 * NW - 1) / (32 * NW);
   const dim3 grid(nmb * s.B * s.H), block(64 * NW);
   const bf16 *q = (const bf16*)a.q, *k = (const bf16*)a.k, *v = (const bf16*)a.v, *tq = (const bf16*)a.tq,
              *tk = (const bf16*)a.tk, *tv = (const bf16*)a.tv;

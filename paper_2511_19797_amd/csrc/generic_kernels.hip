@@ -28,14 +28,14 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Shape s, const T* __re
   __shared__ float qs[kRowsPerBlock][kDMax], tqs[kRowsPerBlock][kDMax];
   __shared__ float ps[kRowsPerBlock][kTile], pzs[kRowsPerBlock][kTile];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nblk = (s.N + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int nblk = (s.M + kRowsPerBlock - 1) / kRowsPerBlock;
   const int bh = blockIdx.x / nblk, b = bh / s.H, h = bh % s.H;
   const int i = (blockIdx.x % nblk) * kRowsPerBlock + w;
-  const long long base = b * s.sb + h * s.sh;
-  const bool rowok = i < s.N;
+  const long long base = b * s.sb + h * s.sh, qbase = b * s.qsb + h * s.qsh;  // key side, query side
+  const bool rowok = i < s.M;
   for (int c = lane; c < s.D; c += 64) {
-    qs[w][c] = rowok ? ldf(q + base + i * s.sn + c) : 0.f;
-    tqs[w][c] = rowok ? ldf(tq + base + i * s.sn + c) : 0.f;
+    qs[w][c] = rowok ? ldf(q + qbase + i * s.qsn + c) : 0.f;
+    tqs[w][c] = rowok ? ldf(tq + qbase + i * s.qsn + c) : 0.f;
   }
   __syncthreads();
   float m = -INFINITY, l = 0.f, cs = 0.f;
@@ -96,12 +96,12 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Shape s, const T* __re
     const int c = lane + 64 * t;
     if (c < s.D) {
       const float oc = ao[t] * inv;
-      stf(o + base + i * s.sn + c, oc);
-      stf(to + base + i * s.sn + c, at[t] * inv - mubar * oc);
+      stf(o + qbase + i * s.qsn + c, oc);
+      stf(to + qbase + i * s.qsn + c, at[t] * inv - mubar * oc);
     }
   }
   if (lane == 0) {
-    const long long r = (long long)bh * s.N + i;
+    const long long r = (long long)bh * s.M + i;
     if (lse) lse[r] = m + __logf(l);
     if (stats) stats[r] = mubar;
   }
@@ -121,11 +121,11 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Shape s, const T* __restri
                                                      const T* __restrict__ gO, const T* __restrict__ gTO,
                                                      float* __restrict__ dsig, float* __restrict__ sig1) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nblk = (s.N + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int nblk = (s.M + kRowsPerBlock - 1) / kRowsPerBlock;
   const int bh = blockIdx.x / nblk, b = bh / s.H, h = bh % s.H;
   const int i = (blockIdx.x % nblk) * kRowsPerBlock + w;
-  if (i >= s.N) return;
-  const long long ro = b * s.sb + h * s.sh + (long long)i * s.sn;
+  if (i >= s.M) return;
+  const long long ro = b * s.qsb + h * s.qsh + (long long)i * s.qsn;
   float a = 0.f, c1 = 0.f;
   for (int c = lane; c < s.D; c += 64) {
     const float oc = ldf(o + ro + c), toc = ldz(to, ro + c);
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Shape s, const T* __restri
   a = wave_sum(a);
   c1 = wave_sum(c1);
   if (lane == 0) {
-    const long long r = (long long)bh * s.N + i;
+    const long long r = (long long)bh * s.M + i;
     dsig[r] = a;
     sig1[r] = c1;
   }
@@ -161,19 +161,19 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
   __shared__ float gs[kRowsPerBlock][kDMax], tgs[kRowsPerBlock][kDMax];
   __shared__ float gzs[kRowsPerBlock][kTile], gzts[kRowsPerBlock][kTile];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nblk = (s.N + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int nblk = (s.M + kRowsPerBlock - 1) / kRowsPerBlock;
   const int bh = blockIdx.x / nblk, b = bh / s.H, h = bh % s.H;
   const int i = (blockIdx.x % nblk) * kRowsPerBlock + w;
-  const long long base = b * s.sb + h * s.sh;
-  const bool rowok = i < s.N;
+  const long long base = b * s.sb + h * s.sh, qbase = b * s.qsb + h * s.qsh;  // key side, query side
+  const bool rowok = i < s.M;
   for (int c = lane; c < s.D; c += 64) {
-    const long long a = base + (long long)i * s.sn + c;
+    const long long a = qbase + (long long)i * s.qsn + c;
     qs[w][c] = rowok ? ldf(q + a) : 0.f;
     tqs[w][c] = rowok ? ldz(tq, a) : 0.f;
     gs[w][c] = rowok ? ldz(gO, a) : 0.f;
     tgs[w][c] = rowok ? ldz(gTO, a) : 0.f;
   }
-  const long long r = (long long)bh * s.N + (rowok ? i : 0);
+  const long long r = (long long)bh * s.M + (rowok ? i : 0);
   const float lse_i = lse[r], mubar_i = stats ? stats[r] : 0.f, dsig_i = dsig[r], sig1_i = sig1[r];
   __syncthreads();
   float aq[kDMax / 64] = {}, atq[kDMax / 64] = {};
@@ -223,8 +223,8 @@ __global__ __launch_bounds__(256) void bwd_row_generic_kernel(Shape s, const T* 
   for (int t = 0; t < kDMax / 64; ++t) {
     const int c = lane + 64 * t;
     if (c < s.D) {
-      stf(dq + base + (long long)i * s.sn + c, aq[t] * s.alpha);
-      if (dtq) stf(dtq + base + (long long)i * s.sn + c, atq[t] * s.alpha);
+      stf(dq + qbase + (long long)i * s.qsn + c, aq[t] * s.alpha);
+      if (dtq) stf(dtq + qbase + (long long)i * s.qsn + c, atq[t] * s.alpha);
     }
   }
 }
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
   const int nblk = (s.N + kRowsPerBlock - 1) / kRowsPerBlock;
   const int bh = blockIdx.x / nblk, b = bh / s.H, h = bh % s.H;
   const int j = (blockIdx.x % nblk) * kRowsPerBlock + w;
-  const long long base = b * s.sb + h * s.sh;
+  const long long base = b * s.sb + h * s.sh, qbase = b * s.qsb + h * s.qsh;  // key side, query side
   const bool rowok = j < s.N;
   for (int c = lane; c < s.D; c += 64) {
     const long long a = base + (long long)j * s.sn + c;
@@ -262,11 +262,11 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
   }
   __syncthreads();
   float ak[kDMax / 64] = {}, atk[kDMax / 64] = {}, av[kDMax / 64] = {}, atv[kDMax / 64] = {};
-  for (int i0 = 0; i0 < s.N; i0 += kTile) {
+  for (int i0 = 0; i0 < s.M; i0 += kTile) {
     const int i = i0 + lane;
     float p = 0.f, pd = 0.f, gz = 0.f, gzt = 0.f;
-    if (i < s.N) {
-      const long long ro = base + (long long)i * s.sn;
+    if (i < s.M) {
+      const long long ro = qbase + (long long)i * s.qsn;
       float a0 = 0.f, a1 = 0.f, df = 0.f, e = 0.f;
       for (int c = 0; c < s.D; ++c) {
         const float qc = ldf(q + ro + c), tqc = ldz(tq, ro + c);
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
         df = fmaf(tgc, tvs[w][c], df);
         e = fmaf(tgc, vs[w][c], e);
       }
-      const long long r = (long long)bh * s.N + i;
+      const long long r = (long long)bh * s.M + i;
       p = __expf(a0 * s.alpha - lse[r]);
       const float n = a1 * s.alpha - (stats ? stats[r] : 0.f);
       gzt = p * (e - sig1[r]);
@@ -290,10 +290,10 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
     gzs[w][lane] = gz;
     gzts[w][lane] = gzt;
     __syncthreads();
-    const int in = min(kTile, s.N - i0);
+    const int in = min(kTile, s.M - i0);
     for (int ii = 0; ii < in; ++ii) {
       const float p_ = pp[w][ii], pd_ = ppd[w][ii], gz_ = gzs[w][ii], gzt_ = gzts[w][ii];
-      const long long ro = base + (long long)(i0 + ii) * s.sn;
+      const long long ro = qbase + (long long)(i0 + ii) * s.qsn;
 #pragma unroll
       for (int t = 0; t < kDMax / 64; ++t) {
         const int c = lane + 64 * t;
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(256) void bwd_col_generic_kernel(Shape s, const T* 
 
 template <typename T>
 hipError_t fwd_generic_t(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  dim3 grid(((s.N + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
+  dim3 grid(((s.M + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
   hipLaunchKernelGGL(fwd_generic_kernel<T>, grid, dim3(256), 0, st, s, (const T*)a.q, (const T*)a.k, (const T*)a.v,
                      (const T*)a.tq, (const T*)a.tk, (const T*)a.tv, (T*)a.o, (T*)a.to, a.lse, a.stats);
   return hipGetLastError();
@@ -335,7 +335,7 @@ hipError_t fwd_generic_t(const Shape& s, const FwdArgs& a, hipStream_t st) {
 
 template <typename T>
 hipError_t bwd_pre_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  dim3 grid(((s.N + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
+  dim3 grid(((s.M + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
   hipLaunchKernelGGL(bwd_pre_kernel<T>, grid, dim3(256), 0, st, s, (const T*)a.o, (const T*)a.to, (const T*)a.gO,
                      (const T*)a.gTO, a.dsig, a.sig1);
   return hipGetLastError();
@@ -352,7 +352,7 @@ hipError_t bwd_col_generic_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
 
 template <typename T>
 hipError_t bwd_row_generic_t(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  dim3 grid(((s.N + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
+  dim3 grid(((s.M + kRowsPerBlock - 1) / kRowsPerBlock) * s.B * s.H);
   hipLaunchKernelGGL(bwd_row_generic_kernel<T>, grid, dim3(256), 0, st, s, (const T*)a.q, (const T*)a.k,
                      (const T*)a.v, (const T*)a.tq, (const T*)a.tk, (const T*)a.tv, a.lse, a.stats, (const T*)a.gO,
                      (const T*)a.gTO, a.dsig, a.sig1, (T*)a.dq, (T*)a.dtq);

@@ -7,11 +7,15 @@ namespace tvm {
 
 typedef __bf16 bf16;
 
-// Logical [B,H,N,D] problem with the element strides shared by every big tensor.
+// Logical problem: M queries and N keys per (batch, head), head dim D.  Key-side tensors (k, v, tk, tv and their
+// gradients) are [B,H,N,D] with element strides sb, sh, sn; query-side tensors (q, tq, o, to, gO, gTO, dq,
+// dtq) are [B,H,M,D] with qsb, qsh, qsn; lse, stats and the workspace row vectors are [B,H,M] contiguous.
 struct Shape {
   int B, H, N, D;
   float alpha;          // softmax scale actually used (already resolved from desc.scale)
-  long long sb, sh, sn; // element strides
+  long long sb, sh, sn; // element strides, key side
+  int M;                // queries (= N for self-attention)
+  long long qsb, qsh, qsn;  // element strides, query side
 };
 
 __device__ __forceinline__ float ldf(const float* p) { return *p; }

@@ -17,24 +17,36 @@ inline void mark(int i, hipStream_t st) {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Validates the descriptor and resolves strides and scale.
+// One side's strides: all zero selects `dflt_*`; otherwise row pitch >= D and 16-byte multiples.
+bool side_strides(long long esz, int D, long long& sb, long long& sh, long long& sn, long long dflt_b, long long dflt_h,
+                  long long dflt_n) {
+  if (sb == 0 && sh == 0 && sn == 0) {
+    sb = dflt_b;
+    sh = dflt_h;
+    sn = dflt_n;
+  }
+  if (sn < D || sh < 1 || sb < 1) return false;
+  return (sn * esz) % 16 == 0 && (sh * esz) % 16 == 0 && (sb * esz) % 16 == 0;
+}
+
+// Validates the descriptor and resolves sizes, strides and scale.
 int resolve(const tvmattn_desc* d, tvm::Shape* s) {
   if (!d) return TVMATTN_INVALID_ARG;
-  if (d->B < 1 || d->H < 1 || d->N < 1 || d->D < 1) return TVMATTN_INVALID_ARG;
+  if (d->B < 1 || d->H < 1 || d->N < 1 || d->D < 1 || d->M < 0 || d->reserved != 0) return TVMATTN_INVALID_ARG;
   if (d->dtype != TVMATTN_F32 && d->dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
   if (d->D > 256) return TVMATTN_UNSUPPORTED;
   if (!(d->scale >= 0.f) || isinf(d->scale)) return TVMATTN_INVALID_ARG;
   const long long esz = d->dtype == TVMATTN_F32 ? 4 : 2;
+  const int M = d->M ? d->M : d->N;
   long long sb = d->stride_b, sh = d->stride_h, sn = d->stride_n;
-  if (sb == 0 && sh == 0 && sn == 0) {
-    sn = d->D;
-    sh = (long long)d->N * d->D;
-    sb = sh * d->H;
-  }
-  if (sn < d->D || sh < 1 || sb < 1) return TVMATTN_INVALID_ARG;
-  if ((sn * esz) % 16 || (sh * esz) % 16 || (sb * esz) % 16) return TVMATTN_INVALID_ARG;
-  const long long rows = (long long)d->B * d->H * d->N;
-  if (rows >= (1ll << 31)) return TVMATTN_UNSUPPORTED;
+  if (!side_strides(esz, d->D, sb, sh, sn, (long long)d->N * d->D * d->H, (long long)d->N * d->D, d->D))
+    return TVMATTN_INVALID_ARG;
+  long long qsb = d->qstride_b, qsh = d->qstride_h, qsn = d->qstride_n;
+  const bool same = M == d->N;  // self-attention: the query side defaults to the key side's layout
+  if (!side_strides(esz, d->D, qsb, qsh, qsn, same ? sb : (long long)M * d->D * d->H, same ? sh : (long long)M * d->D,
+                    same ? sn : d->D))
+    return TVMATTN_INVALID_ARG;
+  if ((long long)d->B * d->H * d->N >= (1ll << 31) || (long long)d->B * d->H * M >= (1ll << 31)) return TVMATTN_UNSUPPORTED;
   s->B = d->B;
   s->H = d->H;
   s->N = d->N;
@@ -43,6 +55,10 @@ int resolve(const tvmattn_desc* d, tvm::Shape* s) {
   s->sb = sb;
   s->sh = sh;
   s->sn = sn;
+  s->M = M;
+  s->qsb = qsb;
+  s->qsh = qsh;
+  s->qsn = qsn;
   return TVMATTN_OK;
 }
 
@@ -71,7 +87,7 @@ inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(sk
 
 extern "C" {
 
-int tvmattn_version(void) { return 200; }  // 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 300; }  // 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -121,8 +137,9 @@ int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, cons
 size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc) {
   tvm::Shape s;
   if (resolve(desc, &s)) return 0;
-  // three float32 row vectors (delta + Sigma_2, Sigma_1, lse in log2 units), each padded to a 256-byte multiple
-  const size_t rows = (size_t)s.B * s.H * s.N;
+  // three float32 row vectors (delta + Sigma_2, Sigma_1, lse in log2 units), one entry per query row, each
+  // padded to a 256-byte multiple
+  const size_t rows = (size_t)s.B * s.H * s.M;
   const size_t one = (rows * sizeof(float) + 255) & ~(size_t)255;
   return 3 * one;
 }

@@ -35,6 +35,7 @@ class Workload:
     tangent_std: float = 1.0
     key_scale: float = 1.0
     note: str = ""
+    M: int = 0            # queries, where they differ in number from the N keys (0: self-attention, M = N)
 
     @property
     def torch_dtype(self):
@@ -44,26 +45,30 @@ class Workload:
     def heads(self):
         return self.B * self.H
 
+    @property
+    def Mq(self):
+        return self.M or self.N
+
     def fwd_flops(self):
         """Six N x N x d products (S, two for Sdot, and three PV-type)."""
-        return 12.0 * self.B * self.H * self.N * self.N * self.d
+        return 12.0 * self.B * self.H * self.Mq * self.N * self.d
 
     def bwd_flops(self):
         """Fifteen N x N x d products (six score-type incl. the recompute, nine output)."""
-        return 30.0 * self.B * self.H * self.N * self.N * self.d
+        return 30.0 * self.B * self.H * self.Mq * self.N * self.d
 
     def elem_bytes(self):
         return 4 if self.dtype == "f32" else 2
 
     def fwd_bytes(self):
         """Reads q,k,v,tq,tk,tv; writes o,to and two fp32 row vectors."""
-        n = self.B * self.H * self.N
-        return 8 * n * self.d * self.elem_bytes() + 8 * n
+        nq, nk = self.B * self.H * self.Mq, self.B * self.H * self.N
+        return (4 * nq + 4 * nk) * self.d * self.elem_bytes() + 8 * nq
 
     def bwd_bytes(self):
         """Reads ten [B,H,N,d] tensors and two row vectors; writes six tensors."""
-        n = self.B * self.H * self.N
-        return 16 * n * self.d * self.elem_bytes() + 8 * n
+        nq, nk = self.B * self.H * self.Mq, self.B * self.H * self.N
+        return (8 * nq + 8 * nk) * self.d * self.elem_bytes() + 8 * nq
 
 
 CONFIGS = {
@@ -76,6 +81,9 @@ CONFIGS = {
     # its kernel ran 1.25x slower with 16 heads of 72)
     "X3": Workload("X3", 32, 18, 256, 64, "bf16", note="DiT-XL/2 as 18 x 64, 256px latents"),
     "X4": Workload("X4", 16, 18, 1024, 64, "bf16", tangent_std=0.1, note="DiT-XL/2 as 18 x 64, 512px latents"),
+    # queries and keys differing in number (the paper's Background allows it; its models do not use it):
+    # 1024 image tokens attending to 256 conditioning tokens, DiT-XL/2 head shape
+    "XA": Workload("XA", 16, 16, 256, 72, "bf16", tangent_std=0.1, note="cross-attention, 1024 queries x 256 keys", M=1024),
 }
 
 # The shapes of the paper's own kernel benchmark (App. C "Evaluation": backward latency over heads H
@@ -95,12 +103,12 @@ def custom(B, H, N, d, dtype="bf16", tangent_std=1.0, key_scale=1.0, name=None):
 
 
 def make_inputs(w: Workload, seed: int):
-    """dict name -> CPU torch tensor [B,H,N,d] in the workload's storage dtype."""
+    """dict name -> CPU torch tensor [B,H,N,d] ([B,H,M,d] for the query side) in the workload's storage dtype."""
     rng = np.random.Generator(np.random.PCG64(seed))
-    shape = (w.B, w.H, w.N, w.d)
     out = {}
     for name in NAMES:
-        x = rng.standard_normal(shape, dtype=np.float32)
+        rows = w.Mq if name in ("q", "tq", "gO", "gTO") else w.N  # query-side tensors have M rows
+        x = rng.standard_normal((w.B, w.H, rows, w.d), dtype=np.float32)
         if name in ("tq", "tk", "tv") and w.tangent_std != 1.0:
             x *= np.float32(w.tangent_std)
         if name == "k" and w.key_scale != 1.0:

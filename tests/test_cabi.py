@@ -45,8 +45,8 @@ def test_version_and_strerror(L):
         assert isinstance(tvm.tvmattn_strerror(code), str) and tvm.tvmattn_strerror(code)
 
 
-def desc(B=1, H=1, N=8, D=8, dtype=1, scale=0.0, sb=0, sh=0, sn=0):
-    return binding.tvmattn_desc(B, H, N, D, dtype, scale, sb, sh, sn)
+def desc(B=1, H=1, N=8, D=8, dtype=1, scale=0.0, sb=0, sh=0, sn=0, M=0, reserved=0, qsb=0, qsh=0, qsn=0):
+    return binding.tvmattn_desc(B, H, N, D, dtype, scale, sb, sh, sn, M, reserved, qsb, qsh, qsn)
 
 
 def fwd_status(L, d, ptrs=None):
@@ -61,6 +61,10 @@ def fwd_status(L, d, ptrs=None):
     (dict(sn=4, sh=64, sb=64), -1),            # stride_n < D
     (dict(D=8, sn=12, sh=96, sb=96), -1),       # 24-byte row pitch is not a 16-byte multiple
     (dict(B=1 << 15, H=1 << 15, N=4), -2),      # 2^32 rows
+    (dict(M=-1), -1), (dict(reserved=1), -1),
+    (dict(M=16, qsn=4, qsh=64, qsb=64), -1),    # query-side row pitch < D
+    (dict(M=16, qsn=12, qsh=192, qsb=192), -1), # query-side pitch not a 16-byte multiple
+    (dict(B=1 << 15, H=1 << 15, N=1, M=4), -2), # 2^32 query rows
 ])
 def test_bad_descriptors_rejected_without_gpu(L, kw, status):
     assert fwd_status(L, desc(**kw)) == status
@@ -120,3 +124,11 @@ def test_one_sided_backward_argument_rules(L):
     one = [0x1000 * (i + 1) for i in range(10)]
     one[9] = None
     assert fwd_status(L, d, one) == -1
+
+
+def test_queries_and_keys_may_differ_in_number(L):
+    """M queries, N keys: the workspace (one entry per query row and vector) follows M, and M = 0 means N."""
+    w = lambda **kw: L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc(B=2, H=3, D=16, **kw)))
+    assert w(N=100) == w(N=100, M=100) == w(N=7, M=100)
+    assert w(N=100, M=40) < w(N=100) < w(N=100, M=300)
+    assert w(N=100, M=300) >= 3 * 2 * 3 * 300 * 4

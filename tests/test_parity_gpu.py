@@ -148,14 +148,14 @@ def test_backward_is_linear_in_upstream_gradients():
 
 
 # ---------------------------------------------------------------- the five configs at full size
-@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2), ("X3", 4), ("X4", 2)])
+@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2), ("X3", 4), ("X4", 2), ("XA", 3)])
 def test_full_size_configs_sampled_heads(name, nheads):
     """Full B,H,N,d in the launch configuration bench.py times; the oracle checks whole heads
     (every element of all ten outputs) for a seeded sample of (b,h), always including the first
     and the last head; all outputs must be finite everywhere."""
     w = wl.CONFIGS[name]
     announce(f"full-size {w}")
-    inp = wl.make_inputs(w, 100 + int(name[1]) + (10 if name[0] == "X" else 0))
+    inp = wl.make_inputs(w, 100 + (int(name[1]) if name[1].isdigit() else 20) + (10 if name[0] == "X" else 0))
     fwd, grads = pu.run_gpu(inp)
     for t in list(fwd) + list(grads):
         assert bool(torch.isfinite(t.float()).all())
@@ -300,3 +300,67 @@ def test_one_sided_backward_full_size():
             assert e <= pu.TOL["bf16"], (name, b, h, e)
     col_sum = dk.float().sum(dim=2).abs().max()
     assert float(col_sum) <= 4.0 * (2.0 ** -8) * float(dk.float().abs().max()) * (w.N ** 0.5)
+
+
+# ---------------------------------------------------------------- M queries, N keys
+@pytest.mark.parametrize("B,H,M,N,d,dtype", [
+    (1, 2, 100, 260, 72, "bf16"), (2, 1, 300, 64, 64, "bf16"), (1, 1, 1, 70, 16, "bf16"), (1, 2, 129, 17, 32, "bf16"),
+    (1, 1, 65, 193, 96, "bf16"), (1, 1, 200, 130, 128, "bf16"), (1, 2, 40, 70, 32, "f32"), (1, 1, 70, 33, 136, "bf16"),
+])
+def test_queries_and_keys_differ(B, H, M, N, d, dtype):
+    """Cross-attention shapes (the paper's Background allows M != N): every element of all ten outputs against
+    the oracle, for the full backward and for the ordinary-attention backward."""
+    announce(f"M != N: B{B} H{H} M{M} N{N} d{d} {dtype}")
+    qs = wl.make_inputs(wl.custom(B, H, M, d, dtype), 51)   # query side: q, tq, gO, gTO
+    ks = wl.make_inputs(wl.custom(B, H, N, d, dtype), 52)   # key side: k, v, tk, tv
+    inp = {n: (qs if n in ("q", "tq", "gO", "gTO") else ks)[n] for n in wl.NAMES}
+    dev = {n: t.cuda() for n, t in inp.items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    fwd = tvm.tvmattn_jvp_fwd(*six)
+    assert fwd[0].shape == (B, H, M, d) and fwd[2].shape == (B, H, M)
+    grads = tvm.tvmattn_jvp_bwd(*six, *fwd, dev["gO"], dev["gTO"])
+    assert grads[0].shape == (B, H, M, d) and grads[1].shape == (B, H, N, d)
+    g_only = tvm.tvmattn_jvp_bwd(six[0], six[1], six[2], None, None, None, fwd[0], None, fwd[2], None, dev["gO"], None)
+    torch.cuda.synchronize()
+    tol = pu.TOL[dtype]
+    for b in range(B):
+        for h in range(H):
+            a = [wl.to_f64(inp[n][b, h]) for n in wl.NAMES]
+            ro = pu.orc.attn_jvp_fwd_head(*a[:6])
+            rg = pu.orc.attn_jvp_bwd_head(*a)
+            r1 = pu.orc.attn_jvp_bwd_head(*a[:6], a[6], np.zeros_like(a[6]))
+            for name, got, ref in (list(zip(pu.FWD_NAMES, fwd, ro)) + list(zip(pu.BWD_NAMES, grads, rg)) +
+                                   list(zip(("dq1", "dk1", "dv1"), g_only[:3], r1[:3]))):
+                e = pu.rel_err(got[b, h].float().cpu().numpy(), ref)
+                assert e <= tol, (name, b, h, e)
+
+
+def test_single_key_cross_attention():
+    """One key, many queries: P = 1, so O = V and tO = tV for every query and the gradients of Q, K, tQ, tK
+    vanish: on the GPU they are the rounding noise of terms that cancel (delta + Sigma_2 from the stored bf16
+    o, to against DF from V, tV), bounded here against the size of those terms."""
+    B, H, M, N, d = 1, 2, 129, 1, 32
+    qs = wl.make_inputs(wl.custom(B, H, M, d, "bf16"), 53)
+    ks = wl.make_inputs(wl.custom(B, H, N, d, "bf16"), 54)
+    inp = {n: (qs if n in ("q", "tq", "gO", "gTO") else ks)[n] for n in wl.NAMES}
+    dev = {n: t.cuda() for n, t in inp.items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(*six)
+    dq, dk, dv, dtq, dtk, dtv = tvm.tvmattn_jvp_bwd(*six, o, to, lse, stats, dev["gO"], dev["gTO"])
+    torch.cuda.synchronize()
+    assert torch.equal(o, dev["v"].expand(B, H, M, d))
+    assert float((to.float() - dev["tv"].float()).abs().max()) <= 2e-2 * float(dev["tv"].float().abs().max())
+    # sizes of the cancelling terms per query row, and of one bf16 rounding step on them
+    terms = (dev["gO"].float().abs() * o.float().abs() + dev["gTO"].float().abs() * to.float().abs()).sum(dim=3).max()
+    noise = float(terms) * 2.0 ** -7
+    alpha = d ** -0.5
+    assert float(dq.float().abs().max()) <= noise * alpha * float(dev["k"].float().abs().max())
+    assert float(dtq.float().abs().max()) <= noise * alpha * float(dev["k"].float().abs().max())
+    for h in range(H):
+        a = [wl.to_f64(inp[n][0, h]) for n in wl.NAMES]
+        ref = pu.orc.attn_jvp_bwd_head(*a)
+        assert pu.rel_err(dv[0, h].float().cpu().numpy(), ref[2]) <= pu.TOL["bf16"]
+        assert pu.rel_err(dtv[0, h].float().cpu().numpy(), ref[5]) <= pu.TOL["bf16"]
+        # dK, dtK: sums of M such noise terms times q, tq rows
+        bound = noise * alpha * M ** 0.5 * 4.0 * float(dev["q"].float().abs().max())
+        assert float(dk[0, h].float().abs().max()) <= bound and float(dtk[0, h].float().abs().max()) <= bound
