@@ -99,6 +99,23 @@ def test_strided_layout_bnhd():
         pu.check_heads(w, inp, (o, to, lse, stats), grads, pu.all_heads(w))
 
 
+def test_strided_layout_with_more_queries_than_keys():
+    """Query side stored [B,M,H,D], key side contiguous [B,H,N,D], M != N: the two sides have their own strides."""
+    import dataclasses
+    for dtype, d in (("bf16", 72), ("f32", 24)):
+        w = dataclasses.replace(wl.custom(2, 3, 90, d, dtype), M=150)
+        announce(f"strided, M != N {w}")
+        inp = wl.make_inputs(w, 10)
+        dev = {n: (t.cuda().permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if n in ("q", "tq", "gO", "gTO")
+                   else t.cuda()) for n, t in inp.items()}
+        assert dev["q"].stride(2) == 3 * d and dev["k"].stride(2) == d and dev["q"].shape[2] == 150
+        o, to, lse, stats = tvm.tvmattn_jvp_fwd(*(dev[n] for n in wl.NAMES[:6]))
+        grads = tvm.tvmattn_jvp_bwd(*(dev[n] for n in wl.NAMES[:6]), o, to, lse, stats, dev["gO"], dev["gTO"])
+        torch.cuda.synchronize()
+        assert o.stride() == dev["q"].stride() and grads[1].stride() == dev["k"].stride()
+        pu.check_heads(w, inp, (o, to, lse, stats), grads, pu.all_heads(w))
+
+
 def test_bitwise_reproducible():
     w = wl.custom(2, 2, 333, 72, "bf16")
     announce(f"determinism {w}")
