@@ -40,11 +40,11 @@ KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.
 _KIB = 1024.0
 MEASURED_TRAFFIC = {
     ("C4", "fwd"): 110665.0 * _KIB * 2.0 + 75776.0 * _KIB,
-    ("C4", "bwd_row"): 185467.2 * _KIB * 2.0 + 76800.0 * _KIB,
-    ("C4", "bwd_col"): 149646.2 * _KIB * 2.0 + 147456.0 * _KIB,
-    ("C3", "fwd"): 55369.0 * _KIB * 2.0 + 37888.0 * _KIB,
-    ("C3", "bwd_row"): 92794.4 * _KIB * 2.0 + 38400.0 * _KIB,
-    ("C3", "bwd_col"): 74893.3 * _KIB * 2.0 + 73728.0 * _KIB,
+    ("C4", "bwd_row"): 185462.7 * _KIB * 2.0 + 76800.0 * _KIB,
+    ("C4", "bwd_col"): 149651.2 * _KIB * 2.0 + 147456.0 * _KIB,
+    ("C3", "fwd"): 55370.4 * _KIB * 2.0 + 37888.0 * _KIB,
+    ("C3", "bwd_row"): 92790.2 * _KIB * 2.0 + 38400.0 * _KIB,
+    ("C3", "bwd_col"): 74899.0 * _KIB * 2.0 + 73728.0 * _KIB,
 }
 
 
