@@ -381,3 +381,37 @@ def test_single_key_cross_attention():
         # dK, dtK: sums of M such noise terms times q, tq rows
         bound = noise * alpha * M ** 0.5 * 4.0 * float(dev["q"].float().abs().max())
         assert float(dk[0, h].float().abs().max()) <= bound and float(dtk[0, h].float().abs().max()) <= bound
+
+
+def test_random_shapes_against_the_oracle():
+    """Forty seeded random problems (batch, heads, queries, keys, head dim, dtype, storage order of either
+    side, explicit or default scale): every element of all ten outputs against the oracle."""
+    import dataclasses
+    rng = np.random.default_rng(2511)
+    dims = [8, 16, 24, 40, 48, 64, 72, 80, 96, 104, 128, 136]
+    for case in range(40):
+        d = int(rng.choice(dims))
+        dtype = "f32" if case % 8 == 7 else "bf16"
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        # (a handful of keys is its own case: test_single_key_cross_attention and the single-token tests)
+        N = int(rng.integers(8, 400)) if case % 3 else int(rng.choice([31, 32, 64, 65, 128, 129, 255, 256]))
+        M = 0 if case % 2 else int(rng.integers(2, 400))
+        if dtype == "f32":
+            N, M = min(N, 150), min(M, 150)
+        w = dataclasses.replace(wl.custom(B, H, N, d, dtype), M=M)
+        scale = 0.0 if case % 4 else float(rng.uniform(0.05, 0.3))
+        perm_q, perm_k = bool(rng.integers(2)), bool(rng.integers(2))
+        announce(f"random case {case}: {w} scale={scale:.3f} bnhd(q side)={perm_q} bnhd(k side)={perm_k}")
+        inp = wl.make_inputs(w, 1000 + case)
+
+        def put(n, t):
+            t = t.cuda()
+            if perm_q if n in ("q", "tq", "gO", "gTO") else perm_k:
+                t = t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+            return t
+        dev = {n: put(n, t) for n, t in inp.items()}
+        six = [dev[n] for n in wl.NAMES[:6]]
+        fwd = tvm.tvmattn_jvp_fwd(*six, scale)
+        grads = tvm.tvmattn_jvp_bwd(*six, *fwd, dev["gO"], dev["gTO"], scale)
+        torch.cuda.synchronize()
+        pu.check_heads(w, inp, fwd, grads, pu.all_heads(w), scale=scale or None)
