@@ -118,10 +118,12 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
   const unsigned long long b = (unsigned long long)(uintptr_t)base;
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
   const unsigned long long bu = ((unsigned long long)hi << 32) | lo;  // provably uniform: lives in an SGPR pair
+  // (one idle slot between the write of M0 and the load that takes its LDS address from it: the wait state
+  // the ISA asks for after a scalar write of M0, which the compiler cannot insert inside an assembly statement)
   if (BYTES == 16)
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
   else
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(m), "v"(off), "s"(bu) : "memory", "m0");
 }
 // Waits until all of this wave's outstanding global loads (including dma_to_lds) have completed.
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

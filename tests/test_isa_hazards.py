@@ -1,7 +1,7 @@
 """Static check of the hand-scheduled kernels' instruction streams (no GPU needed).
 
 The hand-scheduled translation units issue their matrix-core products from inline assembly, which
-the compiler's hazard recognizer does not look into.  Three hazards are therefore ours to keep out
+the compiler's hazard recognizer does not look into.  Four hazards are therefore ours to keep out
 (the hardware interlocks neither):
   1. a matrix-core instruction must not read a register that a VALU instruction wrote in one of
      the two issue slots before it (s_nop N fills N+1 slots);
@@ -11,6 +11,8 @@ the compiler's hazard recognizer does not look into.  Three hazards are therefor
   3. the VALU instruction right behind a transcendental one (v_exp_f32, ...) must not read its result;
      the compiler keeps this apart in its own code but does not look into inline assembly, and may put
      a register copy right behind an assembly statement that ends in one.
+  4. the asynchronous global->LDS loads take their LDS address from M0: one wait state between the scalar
+     write of M0 and the load (both sit in one assembly statement, out of the compiler's sight).
 The compiler is free to put register copies right in front of or right behind an inline-assembly
 statement (at a loop exit, say), so this is checked on the generated assembly of every
 instantiation rather than argued from the source.
@@ -124,6 +126,13 @@ def trans_violations(asm_text):
     return bad
 
 
+def m0_violations(asm_text):
+    """A load that takes its LDS address from M0 right behind the scalar write of M0 (one wait state is due)."""
+    ins = list(instructions(asm_text))
+    return [(i, ins[i + 1][0]) for i, (op, ops) in enumerate(ins[:-1])
+            if op.startswith("s_mov") and ops and ops[0] == "m0" and "load_lds" in ins[i + 1][0]]
+
+
 def test_parser_flags_a_planted_hazard():
     planted = """
     v_accvgpr_write_b32 a4, v9
@@ -156,6 +165,8 @@ def test_parser_flags_a_planted_hazard():
     assert len(trans_violations(trans)) == 1
     assert trans_violations(trans.replace("v_accvgpr", "v_fma_f32 v7, v8, v9, v10\n v_accvgpr")) == []
     assert trans_violations("v_exp_f32 v3, v4\n v_exp_f32 v5, v3") == []
+    assert len(m0_violations("s_mov_b32 m0, s3\n global_load_lds_dwordx4 v1, s[4:5]")) == 1
+    assert m0_violations("s_mov_b32 m0, s3\n s_nop 0\n global_load_lds_dwordx4 v1, s[4:5]") == []
 
 
 @pytest.mark.parametrize("name", HAND_SCHEDULED)
@@ -174,3 +185,4 @@ def test_no_valu_write_feeds_next_matrix_instruction(name):
     assert not bad, f"{len(bad)} touches of unfinished matrix-core results, first: {bad[:3]}"
     bad = trans_violations(text)
     assert not bad, f"{len(bad)} reads of a transcendental result in the next slot, first: {bad[:3]}"
+    assert text.count("load_lds") > 10 and not m0_violations(text)
