@@ -23,6 +23,8 @@ PER_FILE = {
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_col_pipe.hip": ["-mllvm", "-enable-misched=false"],
+    "bwd_row_pipe_tangent.hip": ["-mllvm", "-enable-misched=false"],
+    "bwd_col_pipe_tangent.hip": ["-mllvm", "-enable-misched=false"],
 }
 
 

@@ -26,6 +26,12 @@
 // Three LDS stages: tile t in use, tile t+1 landed (it was fetched during tile t-1), tile t+2 being
 // fetched, one wave-load every few products and only in the phases without pointwise work.
 //
+// HAS_G = false is the kernel for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of
+// App. C by themselves): the products with G vanish, so the E phase has two products per 16 head dims
+// instead of three (DF = tG tV^T), OV(0) and OV(1) two per 32 instead of three (dV += tG^T Pd,
+// dtV += tG^T P), the G tile is neither fetched nor read, and the pointwise work is dealt out over the
+// products that remain.
+//
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"
 
@@ -36,6 +42,15 @@ namespace {
 
 constexpr int kFix = 128;  // keys per workgroup (4 waves x 32)
 constexpr int kNT = 256;
+// One translation unit per variant (they compile side by side): with TVM_PIPE_TANGENT_ONLY defined this
+// file yields the kernels for calls without gO and their launcher, else those for calls with both gradients.
+#if defined(TVM_PIPE_TANGENT_ONLY)
+constexpr bool kHasG = false;
+#define TVM_PIPE_LAUNCHER launch_bwd_col_pipe_tangent
+#else
+constexpr bool kHasG = true;
+#define TVM_PIPE_LAUNCHER launch_bwd_col_pipe
+#endif
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
@@ -44,7 +59,7 @@ __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
 }
 __device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
 
-template <int DK, int DV>
+template <int DK, int DV, bool HAS_G>
 __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
@@ -56,9 +71,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   constexpr int BUF = 4 * TX::BYTES + 4 * 256;  // one stage: four tiles and four float32 row vectors (64 each)
   __shared__ __attribute__((aligned(16))) char lds[3 * BUF];  // three stages: in use, landed or landing, being filled
   constexpr int NKS = DK / 16, NDB = DV / 32;
-  constexpr int NS = 3 * NKS;                      // products of a score-type phase
-  constexpr int NH = 3 * NDB;                      // products of half an output phase
-  constexpr int FS = NS > 4 ? 4 : NS - 1;          // first pointwise slot of the E phase
+  constexpr int NS = 3 * NKS;                      // products of the S phase
+  constexpr int NH = 3 * NDB;                      // products of half the OK phase
+  constexpr int PG = HAS_G ? 3 : 2;                // products per step of the phases that G takes part in
+  constexpr int NE = PG * NKS;                     // products of the E phase
+  constexpr int NHV = PG * NDB;                    // products of half the OV phase
+  constexpr int NTG = HAS_G ? 2 : 1;               // transposed tiles read for OV (G^T and tG^T, or tG^T alone)
+  constexpr int FS = NE > 4 ? 4 : NE - 1;          // first pointwise slot of the E phase
   // The 48 pieces of P, N, Pd of a block are dealt out by cost over the products of E (from FS on) and of
   // OV(0), half 0 (the first 24) complete when OV(0) starts; the 40 pieces of gZ, gZt over those of OV(1)
   // and OK(0), half 0 complete when OK(0) starts.  The transposing reads of those phases count as load.
@@ -66,14 +85,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     static constexpr int pw1(int u) { return ((u % 12) >> 1 == 1 || (u % 12) >> 1 == 2) ? 12 : 8; }
     static constexpr int pw2(int) { return 8; }
     static constexpr int base1(int v) {
-      return v < NS ? 8 * share_count(v, 2 * NDB, NS) + (v < FS ? 4 * share_count(v, 4, FS) : 0)
-                    : 8 * share_count(v - NS, 2 * NDB, NH);
+      return v < NE ? 8 * share_count(v, NTG * NDB, NE) + (v < FS ? 4 * share_count(v, 4, FS) : 0)
+                    : 8 * share_count(v - NE, NTG * NDB, NHV);
     }
-    static constexpr int base2(int v) { return 8 * share_count(v % NH, 2 * NDB, NH); }
+    static constexpr int base2(int v) {
+      return v < NHV ? 8 * share_count(v, 2 * NDB, NHV) : 8 * share_count(v - NHV, 2 * NDB, NH);
+    }
   };
-  static constexpr Deal<NS + NH> kPw1 = deal_out<NS + NH>(48, FS, NS, 24, C::pw1, C::base1);
-  static constexpr Deal<2 * NH> kPw2 = deal_out<2 * NH>(40, 0, NH, 20, C::pw2, C::base2);
-  constexpr int NDMA = 4 * TX::IPW + 1;            // wave-loads per wave and tile (the last: a row vector)
+  static constexpr Deal<NE + NHV> kPw1 = deal_out<NE + NHV>(48, FS, NE, 24, C::pw1, C::base1);
+  static constexpr Deal<NHV + NH> kPw2 = deal_out<NHV + NH>(40, 0, NHV, 20, C::pw2, C::base2);
+  constexpr int NTILE = HAS_G ? 4 : 3;             // tiles fetched per stage (the G tile's place stays empty without gO)
+  constexpr int NDMA = NTILE * TX::IPW + 1;        // wave-loads per wave and tile (the last: a row vector)
   // the tile after next is fetched behind the products of the phases that carry no pointwise work:
   // S and OK(1) of both blocks (the last of them behind the tile's barrier)
   constexpr int NQB = NS + NH;                     // such products per block
@@ -118,8 +140,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     const unsigned off = last ? of_last.o[t] : of_full.o[t];
     if (x < TX::IPW) TX::issue_at(off, t, q + ro, buf, wave);
     else if (x < 2 * TX::IPW) TX::issue_at(off, t, tq + ro, buf + OFF_TQ, wave);
-    else if (x < 3 * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
-    else if (x < 4 * TX::IPW) TX::issue_at(off, t, gTO + ro, buf + OFF_TG, wave);
+    else if (x < 3 * TX::IPW) TX::issue_at(off, t, gTO + ro, buf + OFF_TG, wave);
+    else if (x < NTILE * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
     else dma_to_lds<4>(rowsrc + i0, last ? rv_last : rv_full, buf + OFF_ROW + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
@@ -235,10 +257,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           mfma_fix<RAG>(sT, rq[kk], tkf[kk]);
         }
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NKS, NS) {
+        TVM_SHARE(x, m, NTG * NKS, NS) {
           const int k2 = x % NKS;
-          if (x < NKS) rg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_G + ib * TX::kBlkBytes + k2 * 32);
-          else rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + ib * TX::kBlkBytes + k2 * 32);
+          if (x < NKS) rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + ib * TX::kBlkBytes + k2 * 32);
+          else rg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_G + ib * TX::kBlkBytes + k2 * 32);
         }
 #pragma unroll
         TVM_SHARE(x, m, 12, NS) {  // -sig1 and -dsig of the block first (the first products of E start from them), then lse, stats of half 0
@@ -260,23 +282,23 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           sDF[4 * g4 + t] = da[g4][t];
         }
 #pragma unroll
-      for (int m = 0; m < NS; ++m) {
-        const int kk = m / 3, w = m - 3 * kk;
+      for (int m = 0; m < NE; ++m) {
+        const int kk = m / PG, w = m - PG * kk;
         if (w == 0) {
           if (V_IN_A) mfma_fix<RAG>(sE, rtg[kk], vf[kk]);
           else mfma_vv<RAG>(sE, rtg[kk], vf[kk]);
         } else if (w == 1) {
-          if (V_IN_A) mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
-          else mfma_vv<RAG>(sDF, rg[kk], vf[kk]);
-        } else {
           if (TV_IN_A) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
           else mfma_vv<RAG>(sDF, rtg[kk], tvf[kk]);
+        } else {
+          if (V_IN_A) mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
+          else mfma_vv<RAG>(sDF, rg[kk], vf[kk]);
         }
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NS) {  // G^T, tG^T of half 0
-          const int db = x >> 1;
-          if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, OFF_G + tr_imm(0, db));
-          else txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
+        TVM_SHARE(x, m, NTG * NDB, NE) {  // tG^T, G^T of half 0
+          const int db = x / NTG;
+          if (x % NTG == 0) txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
+          else xT[db] = lds_read_tr(tl, th, OFF_G + tr_imm(0, db));
         }
         if (m < FS) {
 #pragma unroll
@@ -286,7 +308,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           }
         }
         if (m == FS) {
-          if (NS < 6) mfma_settle();
+          if (NE < 6) mfma_settle();
           landed(sS, sT);
         }
         if (m >= FS) {
@@ -297,30 +319,30 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
       PROF(1);
       // ---- OV(0), with P, N, Pd of half 1
 #pragma unroll
-      for (int m = 0; m < NH; ++m) {
-        const int db = m / 3, w = m - 3 * db;
-        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], xT[db], frag_of(pk, 0)); else mfma_acc<RAG>(aV[db], xT[db], frag_of(pk, 0)); }
-        else if (w == 1) mfma_acc<RAG>(aV[db], txT[db], frag_of(pdk, 0));
-        else mfma_acc<RAG>(aTV[db], txT[db], frag_of(pk, 0));
+      for (int m = 0; m < NHV; ++m) {
+        const int db = m / PG, w = m - PG * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], txT[db], frag_of(pdk, 0)); else mfma_acc<RAG>(aV[db], txT[db], frag_of(pdk, 0)); }
+        else if (w == 1) mfma_acc<RAG>(aTV[db], txT[db], frag_of(pk, 0));
+        else mfma_acc<RAG>(aV[db], xT[db], frag_of(pk, 0));
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NH) {  // G^T, tG^T of half 1
-          const int d2 = x >> 1;
-          if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
-          else tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
+        TVM_SHARE(x, m, NTG * NDB, NHV) {  // tG^T, G^T of half 1
+          const int d2 = x / NTG;
+          if (x % NTG == 0) tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
+          else yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
         }
 #pragma unroll
-        for (int u = kPw1.first[NS + m]; u < kPw1.first[NS + m + 1]; ++u) pw1_op(u);
+        for (int u = kPw1.first[NE + m]; u < kPw1.first[NE + m + 1]; ++u) pw1_op(u);
       }
       PROF(2);
       // ---- OV(1), with gZ, gZt of half 0
 #pragma unroll
-      for (int m = 0; m < NH; ++m) {
-        const int db = m / 3, w = m - 3 * db;
-        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], yT[db], frag_of(pk, 1)); else mfma_acc<RAG>(aV[db], yT[db], frag_of(pk, 1)); }
-        else if (w == 1) mfma_acc<RAG>(aV[db], tyT[db], frag_of(pdk, 1));
-        else mfma_acc<RAG>(aTV[db], tyT[db], frag_of(pk, 1));
+      for (int m = 0; m < NHV; ++m) {
+        const int db = m / PG, w = m - PG * db;
+        if (w == 0) { if (m == 0) mfma_acc<true>(aV[db], tyT[db], frag_of(pdk, 1)); else mfma_acc<RAG>(aV[db], tyT[db], frag_of(pdk, 1)); }
+        else if (w == 1) mfma_acc<RAG>(aTV[db], tyT[db], frag_of(pk, 1));
+        else mfma_acc<RAG>(aV[db], yT[db], frag_of(pk, 1));
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 0
+        TVM_SHARE(x, m, 2 * NDB, NHV) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
           if ((x & 1) == 0) xT[d2] = lds_read_tr(tl, th, tr_imm(0, d2));
           else txT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(0, d2));
@@ -344,7 +366,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
           else tyT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(1, d2));
         }
 #pragma unroll
-        for (int u = kPw2.first[NH + m]; u < kPw2.first[NH + m + 1]; ++u) pw2_op(u);
+        for (int u = kPw2.first[NHV + m]; u < kPw2.first[NHV + m + 1]; ++u) pw2_op(u);
       }
       PROF(4);
       if (ib == 1) {
@@ -422,7 +444,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_col_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_col_pipe_kernel<DK, DV, kHasG>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      a.lse2, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
                      (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
@@ -433,7 +455,7 @@ hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
 
 // Head dims up to 96.  Needs the row vectors the hand-scheduled query-side kernel leaves in the
 // workspace (dsig, sig1 and lse in log2 units).
-hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t TVM_PIPE_LAUNCHER(const Shape& s, const BwdArgs& a, hipStream_t st) {
   switch ((s.D + 15) / 16 * 16) {
     case 16: return launch<16, 32>(s, a, st);
     case 32: return launch<32, 32>(s, a, st);
@@ -445,7 +467,7 @@ hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st)
   }
 }
 
-#if defined(TVM_PROFILE)
+#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY)
 extern "C" int tvmattn_debug_read_prof_col_pipe(long long* out16) {
   return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
 }

@@ -1,12 +1,15 @@
-// Backward dispatch on the bf16 matrix cores: hand-scheduled kernels for head dims up to 96
-// (bwd_row_pipe.hip, bwd_col_pipe.hip), generic-order kernels above (bwd_mfma_wide.hip) and where only
-// one of the two upstream gradients exists (bwd_mfma_onesided1.hip, bwd_mfma_onesided2.hip).
+// Backward dispatch on the bf16 matrix cores: hand-scheduled kernels for head dims up to 96 with both
+// upstream gradients (bwd_row_pipe.hip, bwd_col_pipe.hip) or with gTO alone (the same two sources built
+// without the products of gO: bwd_*_pipe_tangent.hip); generic-order kernels above 96
+// (bwd_mfma_wide.hip, bwd_mfma_onesided2.hip) and with gO alone (bwd_mfma_onesided1.hip).
 #include "tvm_common.h"
 
 namespace tvm {
 
 hipError_t launch_bwd_col_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_col_pipe_tangent(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_pipe_tangent(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_onesided1(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_onesided1(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_onesided2(const Shape& s, const BwdArgs& a, hipStream_t st);
@@ -20,11 +23,13 @@ bool mfma_supported(const Shape& s, int dtype) {
 // The query-side kernel runs first in both families: it leaves the row scalars of Step 1 of
 // App. C in the workspace for the key-side kernel (the hand-scheduled pair also lse in log2 units).
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  if (a.mode == 2 && s.D <= 96) return launch_bwd_col_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_col_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);
   return launch_bwd_col_mfma_wide(s, a, st);
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
+  if (a.mode == 2 && s.D <= 96) return launch_bwd_row_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_row_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);
   return launch_bwd_row_mfma_wide(s, a, st);

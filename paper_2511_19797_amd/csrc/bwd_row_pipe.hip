@@ -28,6 +28,10 @@
 // Three LDS stages: tile t in use, tile t+1 landed (it was fetched during tile t-1), tile t+2 being
 // fetched, one wave-load every few products and only in the phases without pointwise work.
 //
+// HAS_G = false is the kernel for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of
+// App. C by themselves): DF = tG tV^T and delta = 0, so an E phase has two products per 16 head dims
+// instead of three, the fragments of gO are not loaded, and P, N are dealt out over the products left.
+//
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"
 
@@ -39,9 +43,18 @@ namespace {
 constexpr int kFix = 128;  // queries per workgroup (4 waves x 32)
 constexpr int kNT = 256;
 constexpr float kLog2e = 1.4426950408889634f;
+// One translation unit per variant (they compile side by side): with TVM_PIPE_TANGENT_ONLY defined this
+// file yields the kernels for calls without gO and their launcher, else those for calls with both gradients.
+#if defined(TVM_PIPE_TANGENT_ONLY)
+constexpr bool kHasG = false;
+#define TVM_PIPE_LAUNCHER launch_bwd_row_pipe_tangent
+#else
+constexpr bool kHasG = true;
+#define TVM_PIPE_LAUNCHER launch_bwd_row_pipe
+#endif
 
 
-template <int DK, int DV>
+template <int DK, int DV, bool HAS_G>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
@@ -55,9 +68,12 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   constexpr int BUF = 2 * TK::BYTES + 2 * TV::BYTES;  // one stage: K, tK, V, tV
   __shared__ __attribute__((aligned(16))) char lds[3 * BUF];  // three stages: in use, landed or landing, being filled
   constexpr int NKS = DK / 16, NDB = DV / 32;
-  constexpr int NS = 3 * NKS;                         // products of a score-type phase
+  constexpr int NS = 3 * NKS;                         // products of an S phase
+  constexpr int PE = HAS_G ? 3 : 2;                   // products per 16 head dims of an E phase (without gO: DF = tG tV^T alone)
+  constexpr int NE = PE * NKS;                        // products of an E phase
   constexpr int NH = 3 * NDB;                         // products of half an output phase
-  constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of a score-type phase
+  constexpr int FS = NS > 4 ? 4 : NS - 1;             // first pointwise slot of an S phase
+  constexpr int FE = NE > 4 ? 4 : NE - 1;             // ... of an E phase
   constexpr int P2S = NH > 3 ? 3 : NH;                // first product of O(0) behind which gZ, gZt of block 1 are made
   constexpr int NDMA = 2 * TK::IPW + 2 * TV::IPW;     // wave-loads per wave and tile
   // the tile after next is fetched behind the products of the phases that carry no pointwise work:
@@ -120,7 +136,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
   const float mub = iok ? stats[r] : 0.f;
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS], of[NKS], tof[NKS];
-  gld_frags<NKS>(gf, gO + qbase, s.qsn, i, s.M, s.D, hh);
+  if (HAS_G) gld_frags<NKS>(gf, gO + qbase, s.qsn, i, s.M, s.D, hh);
   gld_frags<NKS>(tgf, gTO + qbase, s.qsn, i, s.M, s.D, hh);
   gld_frags<NKS>(of, o + qbase, s.qsn, i, s.M, s.D, hh);
   gld_frags<NKS>(tof, to + qbase, s.qsn, i, s.M, s.D, hh);
@@ -136,11 +152,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   for (int kk = 0; kk < NKS; ++kk)
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
-      const bf16x2 g2 = {gf[kk][e], gf[kk][e + 1]};
       const bf16x2 tg2 = {tgf[kk][e], tgf[kk][e + 1]};
       const bf16x2 o2 = {of[kk][e], of[kk][e + 1]};
       const bf16x2 to2 = {tof[kk][e], tof[kk][e + 1]};
-      ds = __builtin_amdgcn_fdot2_f32_bf16(g2, o2, ds, false);
+      if (HAS_G) {
+        const bf16x2 g2 = {gf[kk][e], gf[kk][e + 1]};
+        ds = __builtin_amdgcn_fdot2_f32_bf16(g2, o2, ds, false);
+      }
       ds = __builtin_amdgcn_fdot2_f32_bf16(tg2, to2, ds, false);
       s1 = __builtin_amdgcn_fdot2_f32_bf16(tg2, o2, s1, false);
     }
@@ -217,15 +235,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
       }
     };
     auto e_product = [&](int m) {  // m-th product of an E phase (operands rc, rd)
-      const int kk = m / 3, w = m - 3 * kk;
+      const int kk = m / PE, w = m - PE * kk;
       if (w == 0) {
         if (kk == 0) mfma_fixc<RAG>(sE, rc[0], tgf[0], cE);
         else mfma_fix<RAG>(sE, rc[kk], tgf[kk]);
       } else if (w == 1) {
-        if (kk == 0) mfma_fixc<RAG>(sDF, rc[0], gf[0], cDF);
-        else mfma_fix<RAG>(sDF, rc[kk], gf[kk]);
+        if (kk == 0) mfma_fixc<RAG>(sDF, rd[0], tgf[0], cDF);
+        else mfma_fix<RAG>(sDF, rd[kk], tgf[kk]);
       } else {
-        mfma_fix<RAG>(sDF, rd[kk], tgf[kk]);
+        mfma_fix<RAG>(sDF, rc[kk], gf[kk]);
       }
     };
     // m-th product of half cc of an output phase (transposed fragments xT, txT of that half)
@@ -288,21 +306,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     PROF(0);
     // ---- E(0), with P, N of block 0
 #pragma unroll
-    for (int m = 0; m < NS; ++m) {
+    for (int m = 0; m < NE; ++m) {
       e_product(m);
 #pragma unroll
-      TVM_SHARE(x, m, 2 * NKS, NS) {  // S-fragments of block 1
+      TVM_SHARE(x, m, 2 * NKS, NE) {  // S-fragments of block 1
         const int kk = x % NKS;
         if (x < NKS) ra[kk] = lds_read16((kk & 1) ? ko : ke, TK::kBlkBytes + kk * 32);
         else rb[kk] = lds_read16((kk & 1) ? ko : ke, OFF_TK + TK::kBlkBytes + kk * 32);
       }
-      if (m == FS) {
-        if (NS < 6) mfma_settle();
+      if (m == FE) {
+        if (NE < 6) mfma_settle();
         landed(sS, sT);
       }
-      if (m >= FS) {
+      if (m >= FE) {
 #pragma unroll
-        TVM_SHARE(u, m - FS, 24, NS - FS) pw1_op(0, u);
+        TVM_SHARE(u, m - FE, 24, NE - FE) pw1_op(0, u);
       }
     }
     PROF(1);
@@ -328,21 +346,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     PROF(2);
     // ---- E(1), with P, N of block 1
 #pragma unroll
-    for (int m = 0; m < NS; ++m) {
+    for (int m = 0; m < NE; ++m) {
       e_product(m);
 #pragma unroll
-      TVM_SHARE(x, m, 2 * NDB, NS) {  // transposed K, tK of block 0, half 0
+      TVM_SHARE(x, m, 2 * NDB, NE) {  // transposed K, tK of block 0, half 0
         const int db = x >> 1;
         if ((x & 1) == 0) xT[db] = lds_read_tr(tl, th, tr_imm(0, 0, db));
         else txT[db] = lds_read_tr(tl, th, OFF_TK + tr_imm(0, 0, db));
       }
-      if (m == FS) {
-        if (NS < 6) mfma_settle();
+      if (m == FE) {
+        if (NE < 6) mfma_settle();
         landed(sS, sT);
       }
-      if (m >= FS) {
+      if (m >= FE) {
 #pragma unroll
-        TVM_SHARE(u, m - FS, 24, NS - FS) pw1_op(1, u);
+        TVM_SHARE(u, m - FE, 24, NE - FE) pw1_op(1, u);
       }
     }
     PROF(3);
@@ -457,7 +475,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.M + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV, kHasG>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,
                      a.dsig, a.sig1, a.lse2, (bf16*)a.dq, (bf16*)a.dtq);
@@ -467,7 +485,7 @@ hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
 }  // namespace
 
 // Head dims up to 96.
-hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t TVM_PIPE_LAUNCHER(const Shape& s, const BwdArgs& a, hipStream_t st) {
   switch ((s.D + 15) / 16 * 16) {
     case 16: return launch<16, 32>(s, a, st);
     case 32: return launch<32, 32>(s, a, st);
@@ -479,7 +497,7 @@ hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st)
   }
 }
 
-#if defined(TVM_PROFILE)
+#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY)
 extern "C" int tvmattn_debug_read_prof_row_pipe(long long* out16) {
   return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
 }

@@ -263,6 +263,7 @@ def test_longest_benchmark_shape_sampled_rows():
 @pytest.mark.parametrize("B,H,N,d,dtype", [
     (1, 2, 100, 16, "bf16"), (2, 1, 200, 64, "bf16"), (1, 2, 320, 72, "bf16"), (1, 1, 193, 96, "bf16"),
     (1, 1, 257, 128, "bf16"), (1, 2, 70, 136, "bf16"), (1, 2, 64, 32, "f32"),
+    (1, 2, 130, 32, "bf16"), (1, 1, 97, 48, "bf16"), (1, 1, 64, 80, "bf16"), (2, 1, 33, 8, "bf16"), (1, 1, 2, 40, "bf16"),
 ])
 def test_one_sided_backward(B, H, N, d, dtype):
     """gTO = None is the ordinary attention backward (the oracle with a zero gTO; tangent tensors not
@@ -296,7 +297,7 @@ def test_one_sided_backward(B, H, N, d, dtype):
 
 
 def test_one_sided_backward_full_size():
-    """C4 in the launch configuration bench.py reports for the ordinary-attention backward: sampled heads
+    """C4 in the launch configurations bench.py reports for the two one-sided backwards: sampled heads
     against the oracle, key-gradient column sums for all."""
     w = wl.CONFIGS["C4"]
     announce(f"one-sided full-size {w}")
@@ -317,6 +318,20 @@ def test_one_sided_backward_full_size():
             assert e <= pu.TOL["bf16"], (name, b, h, e)
     col_sum = dk.float().sum(dim=2).abs().max()
     assert float(col_sum) <= 4.0 * (2.0 ** -8) * float(dk.float().abs().max()) * (w.N ** 0.5)
+    # the tangent path alone (Steps 1-6 of App. C by themselves), same launch configuration
+    t_only = tvm.tvmattn_jvp_bwd(*six, o, to, lse, stats, None, dev["gTO"])
+    torch.cuda.synchronize()
+    for t in t_only:
+        assert bool(torch.isfinite(t.float()).all())
+    for (b, h) in ((0, 0), (w.B - 1, w.H - 1), (5, 11)):
+        a = [wl.to_f64(inp[n][b, h]) for n in wl.NAMES]
+        ref = pu.orc.attn_jvp_bwd_head(*a[:6], np.zeros_like(a[6]), a[7])
+        for name, got, r in zip(pu.BWD_NAMES, t_only, ref):
+            e = pu.rel_err(got[b, h].float().cpu().numpy(), r)
+            assert e <= pu.TOL["bf16"], ("gTO only", name, b, h, e)
+    for g in (t_only[1], t_only[4]):  # the rows of gZ and gZt sum to zero, so dK and dtK sum to zero over the keys
+        col_sum = g.float().sum(dim=2).abs().max()
+        assert float(col_sum) <= 4.0 * (2.0 ** -8) * float(g.float().abs().max()) * (w.N ** 0.5)
 
 
 # ---------------------------------------------------------------- M queries, N keys
@@ -326,7 +341,7 @@ def test_one_sided_backward_full_size():
 ])
 def test_queries_and_keys_differ(B, H, M, N, d, dtype):
     """Cross-attention shapes (the paper's Background allows M != N): every element of all ten outputs against
-    the oracle, for the full backward and for the ordinary-attention backward."""
+    the oracle, for the full backward and for both one-sided ones."""
     announce(f"M != N: B{B} H{H} M{M} N{N} d{d} {dtype}")
     qs = wl.make_inputs(wl.custom(B, H, M, d, dtype), 51)   # query side: q, tq, gO, gTO
     ks = wl.make_inputs(wl.custom(B, H, N, d, dtype), 52)   # key side: k, v, tk, tv
@@ -338,6 +353,7 @@ def test_queries_and_keys_differ(B, H, M, N, d, dtype):
     grads = tvm.tvmattn_jvp_bwd(*six, *fwd, dev["gO"], dev["gTO"])
     assert grads[0].shape == (B, H, M, d) and grads[1].shape == (B, H, N, d)
     g_only = tvm.tvmattn_jvp_bwd(six[0], six[1], six[2], None, None, None, fwd[0], None, fwd[2], None, dev["gO"], None)
+    t_only = tvm.tvmattn_jvp_bwd(*six, *fwd, None, dev["gTO"])
     torch.cuda.synchronize()
     tol = pu.TOL[dtype]
     for b in range(B):
@@ -346,8 +362,10 @@ def test_queries_and_keys_differ(B, H, M, N, d, dtype):
             ro = pu.orc.attn_jvp_fwd_head(*a[:6])
             rg = pu.orc.attn_jvp_bwd_head(*a)
             r1 = pu.orc.attn_jvp_bwd_head(*a[:6], a[6], np.zeros_like(a[6]))
+            r2 = pu.orc.attn_jvp_bwd_head(*a[:6], np.zeros_like(a[6]), a[7])
             for name, got, ref in (list(zip(pu.FWD_NAMES, fwd, ro)) + list(zip(pu.BWD_NAMES, grads, rg)) +
-                                   list(zip(("dq1", "dk1", "dv1"), g_only[:3], r1[:3]))):
+                                   list(zip(("dq1", "dk1", "dv1"), g_only[:3], r1[:3])) +
+                                   list(zip(("dq2", "dk2", "dv2", "dtq2", "dtk2", "dtv2"), t_only, r2))):
                 e = pu.rel_err(got[b, h].float().cpu().numpy(), ref)
                 assert e <= tol, (name, b, h, e)
 
