@@ -110,6 +110,12 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_col_mfma_kernel(
   zero_acc(aTV);
   const float c1 = s.alpha * kLog2e;
 
+  pin_frags(kf);  // loaded before the wait for tile 0, not behind it
+  pin_frags(vf);
+  if (MODE != 1) {
+    pin_frags(tkf);
+    pin_frags(tvf);
+  }
   dma_wait();
   __syncthreads();  // tile 0 has landed
   for (int i0 = 0, it = 0; i0 < s.M; i0 += kTS, ++it) {
@@ -305,6 +311,10 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
   zero_acc(aTQ);
   const float c1 = s.alpha * kLog2e;
 
+  pin_frags(qf);  // loaded before the wait for tile 0, not behind it
+  if (MODE != 1) pin_frags(tqf);
+  if (MODE != 2) pin_frags(gf);
+  if (MODE != 1) pin_frags(tgf);
   dma_wait();
   __syncthreads();  // tile 0 has landed
   for (int j0 = 0, it = 0; j0 < s.N; j0 += kTS, ++it) {

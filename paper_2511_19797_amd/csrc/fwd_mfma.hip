@@ -106,8 +106,13 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   issue(0, lds0);
 
   bf16x8 qf[NKS], tqf[NKS];
-  gld_frags<NKS>(qf, q + qbase, s.qsn, i, s.M, s.D, hh);
-  gld_frags<NKS>(tqf, tq + qbase, s.qsn, i, s.M, s.D, hh);
+  {  // all loads in flight together, behind those of tile 0 and before the wait for it
+    uint4 w0[NKS], w1[NKS];
+    gld_frags_issue<NKS>(w0, q + qbase, s.qsn, i, s.M, s.D, hh);
+    gld_frags_issue<NKS>(w1, tq + qbase, s.qsn, i, s.M, s.D, hh);
+    gld_frags_finish<NKS>(qf, w0, i, s.M, s.D, hh);
+    gld_frags_finish<NKS>(tqf, w1, i, s.M, s.D, hh);
+  }
 
   f32x16 accO[NDB], accT[NDB];
 #pragma unroll
@@ -118,6 +123,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   float m = -INFINITY, l = 0.f, cs = 0.f;
   const float c1 = s.alpha * kLog2e;  // scores are exponentiated in base 2
 
+  pin_frags(qf);
+  pin_frags(tqf);
   dma_wait();
   __syncthreads();  // tile 0 has landed
   plant(lds);

@@ -256,16 +256,21 @@ __device__ __forceinline__ void lds_zero(char* lds, int bytes, int tid) {
 // Fixed-side fragments: chunks 2kk+hh (kk < NKS) of row `row` of a [N,D] matrix, zero where the row
 // or the chunk is out of range.  The loads are unconditional (from a clamped, always valid
 // address) and the zeroing is a select on the loaded value, so all of them are in flight together.
+// In two steps, so that a kernel that needs several fragments can issue the loads of all of them before it
+// touches the first value (each select waits for its load; one fragment after the other would pay one
+// memory round trip per fragment).
 template <int NKS>
-__device__ __forceinline__ void gld_frags(bf16x8 (&f)[NKS], const bf16* __restrict__ head, long long sn, int row, int N,
-                                          int D, int hh) {
+__device__ __forceinline__ void gld_frags_issue(uint4 (&raw)[NKS], const bf16* __restrict__ head, long long sn, int row,
+                                                int N, int D, int hh) {
   const bf16* p = head + (long long)min(row, N - 1) * sn;
-  uint4 raw[NKS];
 #pragma unroll
   for (int kk = 0; kk < NKS; ++kk) {
     const int c0 = kk * 16 + hh * 8;
     raw[kk] = *reinterpret_cast<const uint4*>(p + (c0 < D ? c0 : 0));
   }
+}
+template <int NKS>
+__device__ __forceinline__ void gld_frags_finish(bf16x8 (&f)[NKS], const uint4 (&raw)[NKS], int row, int N, int D, int hh) {
 #pragma unroll
   for (int kk = 0; kk < NKS; ++kk) {
     const bool ok = row < N && kk * 16 + hh * 8 < D;
@@ -276,6 +281,21 @@ __device__ __forceinline__ void gld_frags(bf16x8 (&f)[NKS], const bf16* __restri
     v.w = ok ? v.w : 0u;
     f[kk] = __builtin_bit_cast(bf16x8, v);
   }
+}
+template <int NKS>
+__device__ __forceinline__ void gld_frags(bf16x8 (&f)[NKS], const bf16* __restrict__ head, long long sn, int row, int N,
+                                          int D, int hh) {
+  uint4 raw[NKS];
+  gld_frags_issue<NKS>(raw, head, sn, row, N, D, hh);
+  gld_frags_finish<NKS>(f, raw, row, N, D, hh);
+}
+
+// Makes the fragments exist here: placed before a wait or a barrier it keeps the compiler from sinking their
+// loads below it (it would: they read memory nobody writes), which would turn one memory round trip into two.
+template <int NKS>
+__device__ __forceinline__ void pin_frags(bf16x8 (&f)[NKS]) {
+#pragma unroll
+  for (int kk = 0; kk < NKS; ++kk) asm volatile("" : "+v"(f[kk]));
 }
 
 __device__ __forceinline__ bf16x8 zero_unless(bf16x8 f, bool keep) {

@@ -17,6 +17,9 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // Optional cycle stamps per phase (build with -DTVM_PROFILE; each translation unit has its own counters and exports its own reader).
 #if defined(TVM_PROFILE)
+#if !defined(TVM_PROF_BLOCK)
+#define TVM_PROF_BLOCK 3  // hardware id of the workgroup whose stamps are kept
+#endif
 static __device__ long long g_prof_pipe[16];
 #define PROF_ENTRY const long long pe_ = clock64(); long long pp_[16]
 #define PROF_P(i) pp_[i] = clock64() - pe_
@@ -29,10 +32,10 @@ static __device__ long long g_prof_pipe[16];
   } while (0)
 #define PROF_DUMP                                  \
   const long long px_ = clock64();                 \
-  if (blockIdx.x == 3 && threadIdx.x == 0)         \
+  if (blockIdx.x == TVM_PROF_BLOCK && threadIdx.x == 0)         \
     for (int i_ = 0; i_ < 8; ++i_) g_prof_pipe[i_] = pa_[i_]
 #define PROF_EXIT                                                      \
-  if (blockIdx.x == 3 && threadIdx.x == 0) {                           \
+  if (blockIdx.x == TVM_PROF_BLOCK && threadIdx.x == 0) {                           \
     g_prof_pipe[8] = pl_ - pe_;                                        \
     g_prof_pipe[9] = px_ - pl_;                                        \
     g_prof_pipe[10] = clock64() - px_;                                 \
