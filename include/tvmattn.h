@@ -157,6 +157,51 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc,
                     void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/*
+ * RMSNorm with a learnable gain as QK-norm, with tangent: the operation that normalises queries and keys
+ * right before attention in the paper's network (Sec. "Semi-Lipschitz control"; definition and Jacobian in
+ * App. "Lipschitzness of RMSNorm").  Per row x of q or of k (D elements), with its tangent tx:
+ *
+ *     r = 1 / sqrt( (1/D) sum_i x_i^2 + eps )        (the mean of squares: what the printed Jacobian belongs to)
+ *     y = g o x r                                    ty = g o ( tx r - x r^3 (1/D) sum_i x_i tx_i )
+ *
+ * ty is the directional derivative of y along tx; the gain g has no tangent.  One launch normalises both sides.
+ *   in : q, tq            [B,H,M,D] dtype, query-side strides of the descriptor
+ *        k, tk            [B,H,N,D] dtype, key-side strides
+ *        gain_q, gain_k   [D] float32, contiguous, shared by all batches and heads
+ *        eps              >= 0, finite
+ *   out: qn, tqn, kn, tkn like their inputs; these are what tvmattn_jvp_fwd takes as q, tq, k, tk
+ * desc->scale is not used.  Arithmetic is float32; outputs are rounded once to dtype.
+ */
+int tvmattn_qknorm_jvp_fwd(const tvmattn_desc* desc,
+                           const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps,
+                           void* qn, void* tqn, void* kn, void* tkn,
+                           void* hip_stream);
+
+/* Bytes of device scratch tvmattn_qknorm_jvp_bwd needs for this descriptor (0 on a bad descriptor). */
+size_t tvmattn_qknorm_jvp_bwd_workspace_bytes(const tvmattn_desc* desc);
+
+/*
+ * Backward of the above: the gradient of  <gqn,qn> + <gtqn,tqn> + <gkn,kn> + <gtkn,tkn>.
+ *   in : q, tq, k, tk, gain_q, gain_k, eps   as given to the forward (nothing is saved: r is recomputed)
+ *        gqn, gtqn, gkn, gtkn                upstream gradients, like qn, tqn, kn, tkn (the dq, dtq, dk, dtk that
+ *                                            tvmattn_jvp_bwd returns)
+ *   out: dq, dtq, dk, dtk                    like q, tq, k, tk
+ *        dgain_q, dgain_k                    [D] float32, summed over all rows of their side
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_qknorm_jvp_bwd_workspace_bytes(desc) bytes;
+ *        contents need not be initialised and are undefined afterwards.
+ * Two launches (rows, then the sum of per-workgroup partial gain gradients in a fixed order).  No atomics:
+ * results are bitwise reproducible.
+ */
+int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc,
+                           const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps,
+                           const void* gqn, const void* gtqn, const void* gkn, const void* gtkn,
+                           void* dq, void* dtq, void* dk, void* dtk, float* dgain_q, float* dgain_k,
+                           void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,6 +55,13 @@ def lib():
         L.tvmattn_jvp_bwd_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
         L.tvmattn_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_jvp_bwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 19 + [ctypes.c_size_t, _P]
+        L.tvmattn_qknorm_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_qknorm_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 5
+        L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_qknorm_jvp_bwd_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
+        L.tvmattn_qknorm_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_qknorm_jvp_bwd.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 11 +
+                                             [ctypes.c_size_t, _P])
         _lib = L
     return _lib
 
@@ -172,4 +179,57 @@ def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, 
                                  _ptr(tv), o.data_ptr(), _ptr(to), lse.data_ptr(), _ptr(stats), _ptr(gO), _ptr(gTO),
                                  dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _ptr(dtq), _ptr(dtk), _ptr(dtv),
                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def _gain_ok(g, ref):
+    if g.dtype != torch.float32 or g.dim() != 1 or g.shape[0] != ref.shape[3] or not g.is_contiguous() or g.device != ref.device:
+        raise ValueError("gains must be contiguous float32 [D] tensors on the inputs' device")
+
+
+def tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gain_q, gain_k, eps, out=None):
+    """Returns (qn, tqn, kn, tkn): RMSNorm with gain of the rows of q and k, and the tangents along tq, tk."""
+    _same_layout(q, tq)
+    _same_layout(k, tk)
+    _gain_ok(gain_q, q)
+    _gain_ok(gain_k, k)
+    desc = make_desc(k, 0.0, q)
+    if out is None:
+        out = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(k))
+    else:
+        _same_layout(q, out[0], out[1])
+        _same_layout(k, out[2], out[3])
+    _check(lib().tvmattn_qknorm_jvp_fwd(ctypes.byref(desc), q.data_ptr(), tq.data_ptr(), k.data_ptr(), tk.data_ptr(),
+                                        gain_q.data_ptr(), gain_k.data_ptr(), float(eps), out[0].data_ptr(),
+                                        out[1].data_ptr(), out[2].data_ptr(), out[3].data_ptr(), _stream()))
+    return out
+
+
+def tvmattn_qknorm_jvp_bwd_workspace_bytes(q, k=None):
+    desc = make_desc(q if k is None else k, 0.0, q)
+    return int(lib().tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
+
+
+def tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gain_q, gain_k, eps, gqn, gtqn, gkn, gtkn, out=None, workspace=None):
+    """Returns (dq, dtq, dk, dtk, dgain_q, dgain_k)."""
+    _same_layout(q, tq, gqn, gtqn)
+    _same_layout(k, tk, gkn, gtkn)
+    _gain_ok(gain_q, q)
+    _gain_ok(gain_k, k)
+    desc = make_desc(k, 0.0, q)
+    if out is None:
+        out = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(k),
+               torch.empty_like(gain_q), torch.empty_like(gain_k))
+    else:
+        _same_layout(q, out[0], out[1])
+        _same_layout(k, out[2], out[3])
+        _gain_ok(out[4], q)
+        _gain_ok(out[5], k)
+    need = int(lib().tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    _check(lib().tvmattn_qknorm_jvp_bwd(ctypes.byref(desc), q.data_ptr(), tq.data_ptr(), k.data_ptr(), tk.data_ptr(),
+                                        gain_q.data_ptr(), gain_k.data_ptr(), float(eps), gqn.data_ptr(), gtqn.data_ptr(),
+                                        gkn.data_ptr(), gtkn.data_ptr(), *[t.data_ptr() for t in out],
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
     return out

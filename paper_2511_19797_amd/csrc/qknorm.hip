@@ -1,0 +1,261 @@
+// RMSNorm with a learnable gain as QK-norm (Terminal Velocity Matching, Sec. "Semi-Lipschitz control";
+// definition and Jacobian in App. "Lipschitzness of RMSNorm"), with its JVP tangent and its backward, for
+// the rows of q and of k in one launch.  Per row x in R^d, with r = 1 / sqrt(mean(x^2) + eps) and
+// m = mean(x tx):
+//     y  = g o x r                          ty = g o (tx r - x r^3 m)
+// Backward of <gy, y> + <gty, ty>, with u = g o gy, w = g o gty, A = <u, x>, Bw = <w, x>, C = <w, tx>:
+//     gtx = r w - (r^3 Bw / d) x
+//     gx  = r u - r^3 m w - (r^3 Bw / d) tx + x (3 r^5 m Bw - r^3 (A + C)) / d
+//     gg  = sum over rows of  gy o x r + gty o (tx r - x r^3 m)
+// Memory-bound: every tensor is read once and written once, 16 bytes per lane, 16 lanes to a row (their
+// sums meet by lane exchange), float32 arithmetic whatever the storage type.  The gain gradient is summed
+// without atomics: each thread keeps the column sums of the rows it worked on, a workgroup adds its 16 row
+// slots in LDS and writes one partial row, and a second small kernel adds the partial rows in order, so
+// the result does not depend on timing.
+#include "tvm_common.h"
+
+namespace tvm {
+namespace {
+
+constexpr int kNT = 256;
+constexpr int kLpr = 16;  // lanes per row
+
+template <typename T>
+struct Chunk {  // 16 bytes of T
+  static constexpr int VEC = 16 / sizeof(T);
+  T v[VEC];
+};
+
+// Elements [c0, c0 + VEC) of the row at p as float32, zero beyond D.  Whole chunks are one 16-byte load
+// (rows start on 16-byte boundaries); a chunk that crosses D is read element by element.
+template <typename T>
+__device__ __forceinline__ void load_chunk(float (&out)[Chunk<T>::VEC], const T* p, int c0, int D) {
+  constexpr int VEC = Chunk<T>::VEC;
+  if (c0 + VEC <= D) {
+    const Chunk<T> c = *reinterpret_cast<const Chunk<T>*>(p + c0);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = (float)c.v[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = c0 + e < D ? (float)p[c0 + e] : 0.f;
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store_chunk(T* p, int c0, int D, const float (&in)[Chunk<T>::VEC]) {
+  constexpr int VEC = Chunk<T>::VEC;
+  if (c0 + VEC <= D) {
+    Chunk<T> c;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) c.v[e] = (T)in[e];  // round to nearest even
+    *reinterpret_cast<Chunk<T>*>(p + c0) = c;
+  } else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+      if (c0 + e < D) p[c0 + e] = (T)in[e];
+  }
+}
+// Sum over the 16 lanes of a row (lanes 16k .. 16k+15 of the wave).
+__device__ __forceinline__ float row_sum(float x) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+struct RowIter {  // the rows of one side that this thread's row slot works on
+  long long row, end, step;
+};
+__device__ __forceinline__ long long row_offset(const NormArgs& a, const NormSide& s, long long row) {
+  const long long bh = row / s.n, i = row - bh * s.n;
+  const long long b = bh / a.H, h = bh - b * a.H;
+  return b * s.sb + h * s.sh + i * s.sn;
+}
+
+// MAXC: chunks per lane (16 lanes x MAXC x VEC >= D).
+template <typename T, int MAXC>
+__global__ __launch_bounds__(kNT) void qknorm_fwd_kernel(NormArgs a) {
+  constexpr int VEC = Chunk<T>::VEC;
+  const int sd = (int)blockIdx.x >= a.side[0].nwg ? 1 : 0;
+  const NormSide s = sd ? a.side[1] : a.side[0];  // (a select per field: the arguments stay in scalar registers)
+  const int wg = blockIdx.x - (sd ? a.side[0].nwg : 0);
+  const int lr = threadIdx.x & (kLpr - 1), slot = threadIdx.x / kLpr;
+  const long long R = (long long)a.B * a.H * s.n;
+  const float invd = 1.0f / (float)a.D;
+  float g[MAXC][VEC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int col = (lr + kLpr * c) * VEC + e;
+      g[c][e] = col < a.D ? s.g[col] : 0.f;
+    }
+  for (long long row = (long long)wg * kNormRowsPerWg + slot; row < R; row += (long long)s.nwg * kNormRowsPerWg) {
+    const long long off = row_offset(a, s, row);
+    const T* xp = static_cast<const T*>(s.x) + off;
+    const T* tp = static_cast<const T*>(s.tx) + off;
+    float x[MAXC][VEC], t[MAXC][VEC];
+    float sxx = 0.f, sxt = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      const int c0 = (lr + kLpr * c) * VEC;
+      load_chunk<T>(x[c], xp, c0, a.D);
+      load_chunk<T>(t[c], tp, c0, a.D);
+    }
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        sxx = fmaf(x[c][e], x[c][e], sxx);
+        sxt = fmaf(x[c][e], t[c][e], sxt);
+      }
+    sxx = row_sum(sxx);
+    sxt = row_sum(sxt);
+    const float r = 1.0f / sqrtf(sxx * invd + a.eps);
+    const float r3m = r * r * r * (sxt * invd);
+    T* yp = static_cast<T*>(s.y) + off;
+    T* typ = static_cast<T*>(s.ty) + off;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      const int c0 = (lr + kLpr * c) * VEC;
+      if (c0 >= a.D) continue;
+      float y[VEC], ty[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        y[e] = g[c][e] * (x[c][e] * r);
+        ty[e] = g[c][e] * (t[c][e] * r - x[c][e] * r3m);
+      }
+      store_chunk<T>(yp, c0, a.D, y);
+      store_chunk<T>(typ, c0, a.D, ty);
+    }
+  }
+}
+
+template <typename T, int MAXC>
+__global__ __launch_bounds__(kNT) void qknorm_bwd_kernel(NormArgs a) {
+  constexpr int VEC = Chunk<T>::VEC;
+  __shared__ float red[kNT / kLpr][kLpr * MAXC * VEC];  // one row of column sums per row slot
+  const int sd = (int)blockIdx.x >= a.side[0].nwg ? 1 : 0;
+  const NormSide s = sd ? a.side[1] : a.side[0];  // (a select per field: the arguments stay in scalar registers)
+  const int wg = blockIdx.x - (sd ? a.side[0].nwg : 0);
+  const int lr = threadIdx.x & (kLpr - 1), slot = threadIdx.x / kLpr;
+  const long long R = (long long)a.B * a.H * s.n;
+  const float invd = 1.0f / (float)a.D;
+  float g[MAXC][VEC], acc[MAXC][VEC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int col = (lr + kLpr * c) * VEC + e;
+      g[c][e] = col < a.D ? s.g[col] : 0.f;
+      acc[c][e] = 0.f;
+    }
+  for (long long row = (long long)wg * kNormRowsPerWg + slot; row < R; row += (long long)s.nwg * kNormRowsPerWg) {
+    const long long off = row_offset(a, s, row);
+    const T* xp = static_cast<const T*>(s.x) + off;
+    const T* tp = static_cast<const T*>(s.tx) + off;
+    const T* gyp = static_cast<const T*>(s.gy) + off;
+    const T* gtp = static_cast<const T*>(s.gty) + off;
+    float x[MAXC][VEC], t[MAXC][VEC], gy[MAXC][VEC], gt[MAXC][VEC];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      const int c0 = (lr + kLpr * c) * VEC;
+      load_chunk<T>(x[c], xp, c0, a.D);
+      load_chunk<T>(t[c], tp, c0, a.D);
+      load_chunk<T>(gy[c], gyp, c0, a.D);
+      load_chunk<T>(gt[c], gtp, c0, a.D);
+    }
+    float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float u = g[c][e] * gy[c][e], w = g[c][e] * gt[c][e];
+        sxx = fmaf(x[c][e], x[c][e], sxx);
+        sxt = fmaf(x[c][e], t[c][e], sxt);
+        sA = fmaf(u, x[c][e], sA);
+        sB = fmaf(w, x[c][e], sB);
+        sC = fmaf(w, t[c][e], sC);
+      }
+    sxx = row_sum(sxx);
+    sxt = row_sum(sxt);
+    sA = row_sum(sA);
+    sB = row_sum(sB);
+    sC = row_sum(sC);
+    const float r = 1.0f / sqrtf(sxx * invd + a.eps);
+    const float r3 = r * r * r, m = sxt * invd;
+    const float r3m = r3 * m;
+    const float kB = r3 * sB * invd;                                      // r^3 Bw / d
+    const float kx = (3.0f * r3 * r * r * m * sB - r3 * (sA + sC)) * invd;  // coefficient of x in gx
+    T* gxp = static_cast<T*>(s.y) + off;
+    T* gtxp = static_cast<T*>(s.ty) + off;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+      const int c0 = (lr + kLpr * c) * VEC;
+      if (c0 >= a.D) continue;
+      float gx[VEC], gtx[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float u = g[c][e] * gy[c][e], w = g[c][e] * gt[c][e];
+        gtx[e] = r * w - kB * x[c][e];
+        gx[e] = r * u - r3m * w - kB * t[c][e] + kx * x[c][e];
+        acc[c][e] += gy[c][e] * (x[c][e] * r) + gt[c][e] * (t[c][e] * r - x[c][e] * r3m);
+      }
+      store_chunk<T>(gxp, c0, a.D, gx);
+      store_chunk<T>(gtxp, c0, a.D, gtx);
+    }
+  }
+  // column sums of this workgroup: the 16 row slots added in order
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[slot][(lr + kLpr * c) * VEC + e] = acc[c][e];
+  __syncthreads();
+  for (int col = threadIdx.x; col < a.D; col += kNT) {
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < kNT / kLpr; ++k) sum += red[k][col];
+    s.part[(long long)wg * a.D + col] = sum;
+  }
+}
+
+// gg[col] = sum over the partial rows, in order.  One workgroup per side.
+__global__ __launch_bounds__(kNT) void qknorm_gain_grad_kernel(NormArgs a) {
+  const NormSide s = blockIdx.x ? a.side[1] : a.side[0];
+  for (int col = threadIdx.x; col < a.D; col += kNT) {
+    float sum = 0.f;
+    for (int w = 0; w < s.nwg; ++w) sum += s.part[(long long)w * a.D + col];
+    s.gg[col] = sum;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid(a.side[0].nwg + a.side[1].nwg), block(kNT);
+  if (dtype == 1) {
+    if (a.D <= 128) hipLaunchKernelGGL((qknorm_fwd_kernel<bf16, 1>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((qknorm_fwd_kernel<bf16, 2>), grid, block, 0, st, a);
+  } else {
+    if (a.D <= 64) hipLaunchKernelGGL((qknorm_fwd_kernel<float, 1>), grid, block, 0, st, a);
+    else if (a.D <= 128) hipLaunchKernelGGL((qknorm_fwd_kernel<float, 2>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((qknorm_fwd_kernel<float, 4>), grid, block, 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid(a.side[0].nwg + a.side[1].nwg), block(kNT);
+  if (dtype == 1) {
+    if (a.D <= 128) hipLaunchKernelGGL((qknorm_bwd_kernel<bf16, 1>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((qknorm_bwd_kernel<bf16, 2>), grid, block, 0, st, a);
+  } else {
+    if (a.D <= 64) hipLaunchKernelGGL((qknorm_bwd_kernel<float, 1>), grid, block, 0, st, a);
+    else if (a.D <= 128) hipLaunchKernelGGL((qknorm_bwd_kernel<float, 2>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((qknorm_bwd_kernel<float, 4>), grid, block, 0, st, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2), block, 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace tvm

@@ -66,4 +66,27 @@ hipError_t launch_bwd_row_onesided(const Shape& s, const BwdArgs& a, hipStream_t
 hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96
 hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96, after the former
 
+
+// RMSNorm with gain as QK-norm, with tangent (qknorm.hip).  One side = the rows of q (and tq) or of k (and tk).
+struct NormSide {
+  const void *x, *tx;      // inputs [B,H,n,D]
+  const float* g;          // gain [D]
+  const void *gy, *gty;    // backward: upstream gradients of the normalised tensor and of its tangent
+  void *y, *ty;            // forward: outputs; backward: gradients of x and tx
+  float* part;             // backward: per-workgroup partial sums of the gain gradient [nwg][D]
+  float* gg;               // backward: gain gradient [D]
+  int n;                   // rows per (batch, head)
+  long long sb, sh, sn;    // element strides
+  int nwg;                 // workgroups that work on this side
+};
+struct NormArgs {
+  NormSide side[2];
+  int B, H, D;
+  float eps;
+};
+constexpr int kNormRowsPerWg = 16;   // rows a workgroup works on at a time (16 lanes each)
+constexpr int kNormMaxWg = 1024;     // workgroups per side at most (they stride over the rows)
+hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st);
+hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st);
+
 }  // namespace tvm

@@ -87,7 +87,7 @@ inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(sk
 
 extern "C" {
 
-int tvmattn_version(void) { return 300; }  // 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 400; }  // 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -183,6 +183,105 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   mark(2, st);
   e = mf ? tvm::launch_bwd_col_mfma(s, a, st) : tvm::launch_bwd_col_generic(s, desc->dtype, a, st);
   mark(3, st);
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
+// ---- RMSNorm with gain as QK-norm, with tangent
+namespace {
+int norm_wgs(long long rows) {
+  const long long w = (rows + tvm::kNormRowsPerWg - 1) / tvm::kNormRowsPerWg;
+  return (int)(w < tvm::kNormMaxWg ? w : tvm::kNormMaxWg);
+}
+void norm_sides(const tvm::Shape& s, tvm::NormArgs* a, float eps) {
+  a->B = s.B;
+  a->H = s.H;
+  a->D = s.D;
+  a->eps = eps;
+  a->side[0].n = s.M;
+  a->side[0].sb = s.qsb;
+  a->side[0].sh = s.qsh;
+  a->side[0].sn = s.qsn;
+  a->side[1].n = s.N;
+  a->side[1].sb = s.sb;
+  a->side[1].sh = s.sh;
+  a->side[1].sn = s.sn;
+  for (int i = 0; i < 2; ++i) a->side[i].nwg = norm_wgs((long long)s.B * s.H * a->side[i].n);
+}
+size_t norm_part_bytes(const tvm::NormArgs& a, int side) {  // padded to a 256-byte multiple
+  return ((size_t)a.side[side].nwg * a.D * sizeof(float) + 255) & ~(size_t)255;
+}
+}  // namespace
+
+int tvmattn_qknorm_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps, void* qn, void* tqn, void* kn,
+                           void* tkn, void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
+  const void* const in[] = {q, tq, k, tk, gain_q, gain_k};
+  void* const out[] = {qn, tqn, kn, tkn};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  tvm::NormArgs a{};
+  norm_sides(s, &a, eps);
+  a.side[0].x = q;
+  a.side[0].tx = tq;
+  a.side[0].g = gain_q;
+  a.side[0].y = qn;
+  a.side[0].ty = tqn;
+  a.side[1].x = k;
+  a.side[1].tx = tk;
+  a.side[1].g = gain_k;
+  a.side[1].y = kn;
+  a.side[1].ty = tkn;
+  const hipError_t e = tvm::launch_qknorm_fwd(a, desc->dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
+size_t tvmattn_qknorm_jvp_bwd_workspace_bytes(const tvmattn_desc* desc) {
+  tvm::Shape s;
+  if (resolve(desc, &s)) return 0;
+  tvm::NormArgs a{};
+  norm_sides(s, &a, 0.f);
+  return norm_part_bytes(a, 0) + norm_part_bytes(a, 1);  // one partial gain-gradient row per workgroup and side
+}
+
+int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps, const void* gqn, const void* gtqn,
+                           const void* gkn, const void* gtkn, void* dq, void* dtq, void* dk, void* dtk,
+                           float* dgain_q, float* dgain_k, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
+  const void* const in[] = {q, tq, k, tk, gain_q, gain_k, gqn, gtqn, gkn, gtkn};
+  void* const out[] = {dq, dtq, dk, dtk, dgain_q, dgain_k, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  if (workspace_bytes < tvmattn_qknorm_jvp_bwd_workspace_bytes(desc)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::NormArgs a{};
+  norm_sides(s, &a, eps);
+  a.side[0].x = q;
+  a.side[0].tx = tq;
+  a.side[0].g = gain_q;
+  a.side[0].gy = gqn;
+  a.side[0].gty = gtqn;
+  a.side[0].y = dq;
+  a.side[0].ty = dtq;
+  a.side[0].gg = dgain_q;
+  a.side[0].part = static_cast<float*>(workspace);
+  a.side[1].x = k;
+  a.side[1].tx = tk;
+  a.side[1].g = gain_k;
+  a.side[1].gy = gkn;
+  a.side[1].gty = gtkn;
+  a.side[1].y = dk;
+  a.side[1].ty = dtk;
+  a.side[1].gg = dgain_k;
+  a.side[1].part = reinterpret_cast<float*>(static_cast<char*>(workspace) + norm_part_bytes(a, 0));
+  const hipError_t e = tvm::launch_qknorm_bwd(a, desc->dtype, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
 

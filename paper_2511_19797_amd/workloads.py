@@ -117,6 +117,12 @@ def make_inputs(w: Workload, seed: int):
     return out
 
 
+def make_gains(w: Workload, seed: int):
+    """(gain_q, gain_k): float32 [d] gains of the QK-norm, around one as after some training."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return tuple(torch.from_numpy((1.0 + 0.2 * rng.standard_normal(w.d)).astype(np.float32)) for _ in range(2))
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()

@@ -132,3 +132,51 @@ def test_queries_and_keys_may_differ_in_number(L):
     assert w(N=100) == w(N=100, M=100) == w(N=7, M=100)
     assert w(N=100, M=40) < w(N=100) < w(N=100, M=300)
     assert w(N=100, M=300) >= 3 * 2 * 3 * 300 * 4
+
+
+def test_qknorm_argument_rules(L):
+    """The QK-norm entry points validate before anything is launched.  (Status -3, workspace too small,
+    shows that the pointer checks of the backward were passed; no call here is a valid one.)"""
+    L.tvmattn_qknorm_jvp_fwd.argtypes = [ctypes.POINTER(binding.tvmattn_desc)] + [ctypes.c_void_p] * 6 + \
+        [ctypes.c_float] + [ctypes.c_void_p] * 5
+    L.tvmattn_qknorm_jvp_bwd.argtypes = [ctypes.POINTER(binding.tvmattn_desc)] + [ctypes.c_void_p] * 6 + \
+        [ctypes.c_float] + [ctypes.c_void_p] * 11 + [ctypes.c_size_t, ctypes.c_void_p]
+    L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+    d = desc(B=2, H=3, N=100, D=72, M=40)
+    ins = [0x1000 * (i + 1) for i in range(6)]
+    outs = [0x1000 * (i + 7) for i in range(4)]
+    fwd = lambda i, o, eps=1e-6, dd=d: L.tvmattn_qknorm_jvp_fwd(ctypes.byref(dd), *i, eps, *o, None)
+    for bad_eps in (-1.0, float("nan"), float("inf")):
+        assert fwd(ins, outs, bad_eps) == -1
+    assert fwd(ins, outs, dd=desc(D=0)) == -1 and fwd(ins, outs, dd=desc(dtype=9)) == -2
+    for i in range(6):
+        p = list(ins)
+        p[i] = None
+        assert fwd(p, outs) == -1
+        p[i] = ins[i] + 8
+        assert fwd(p, outs) == -1
+    for o in range(4):
+        p = list(outs)
+        p[o] = None
+        assert fwd(ins, p) == -1
+        p[o] = ins[0]          # an output aliases q
+        assert fwd(ins, p) == -1
+    # backward: one partial gain-gradient row per workgroup and side, 16 rows per workgroup, at most 1024 workgroups
+    need = L.tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(d))
+    rows_q, rows_k = 2 * 3 * 40, 2 * 3 * 100
+    assert need >= ((rows_q + 15) // 16 + (rows_k + 15) // 16) * 72 * 4 and need % 256 == 0
+    big = L.tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc(B=64, H=16, N=1024, D=72)))
+    assert big <= 2 * (1024 * 72 * 4 + 256)
+    assert L.tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc(D=0))) == 0
+    b_in = [0x1000 * (i + 1) for i in range(6)]
+    b_rest = [0x1000 * (i + 7) for i in range(11)]   # 4 upstream gradients, 6 outputs, workspace
+    bwd = lambda a, b, ws=need - 1, eps=1e-6: L.tvmattn_qknorm_jvp_bwd(ctypes.byref(d), *a, eps, *b, ws, None)
+    assert bwd(b_in, b_rest) == -3
+    assert bwd(b_in, b_rest, eps=-2.0) == -1
+    for i in range(11):
+        p = list(b_rest)
+        p[i] = None
+        assert bwd(b_in, p) == -1
+    p = list(b_rest)
+    p[5] = p[4]                # dtq aliases dq
+    assert bwd(b_in, p) == -1

@@ -1,0 +1,159 @@
+"""GPU-vs-oracle parity of the QK-norm entry points (RMSNorm with gain, tangent, backward) through the
+C-ABI.  Every case prints its name before touching the GPU."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_19797_amd as tvm
+from oracle import rmsnorm_oracle as norc
+from oracle import tvmattn_oracle as aorc
+from paper_2511_19797_amd import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-6
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def sides(B, H, M, N, d, dtype, seed):
+    """Query-side and key-side inputs: q, tq and upstream gradients with M rows, k, tk with N rows."""
+    qs = wl.make_inputs(wl.custom(B, H, M, d, dtype), seed)
+    ks = wl.make_inputs(wl.custom(B, H, N, d, dtype), seed + 1)
+    gq, gk = wl.make_gains(wl.custom(B, H, N, d, dtype), seed + 2)
+    return dict(q=qs["q"], tq=qs["tq"], gqn=qs["gO"], gtqn=qs["gTO"], k=ks["k"], tk=ks["tk"], gkn=ks["v"], gtkn=ks["tv"],
+                gain_q=gq, gain_k=gk)
+
+
+def check(inp, fwd, bwd, dtype, rows=None):
+    """Every element (or the listed rows of the flattened [B*H*n, d] view) against the oracle."""
+    tol = pu.TOL[dtype]
+    f64 = {n: wl.to_f64(t) for n, t in inp.items()}
+    worst = {}
+    for sd, x, tx, g, gy, gty, o in (("q", "q", "tq", "gain_q", "gqn", "gtqn", 0), ("k", "k", "tk", "gain_k", "gkn", "gtkn", 2)):
+        d = f64[x].shape[-1]
+        flat = lambda a: a.reshape(-1, d)
+        sel = slice(None) if rows is None else rows[sd]
+        y, ty = norc.rmsnorm_jvp_fwd(flat(f64[x])[sel], flat(f64[tx])[sel], f64[g], EPS)
+        gx, gtx, gg = norc.rmsnorm_jvp_bwd(flat(f64[x]), flat(f64[tx]), f64[g], EPS, flat(f64[gy]), flat(f64[gty]))
+        got = lambda t: flat(t.float().cpu().numpy())[sel]
+        for name, a, ref in ((sd + "n", fwd[o], y), ("t" + sd + "n", fwd[o + 1], ty), ("d" + sd, bwd[o], gx[sel]),
+                             ("dt" + sd, bwd[o + 1], gtx[sel])):
+            worst[name] = pu.rel_err(got(a), ref)
+        worst["dgain_" + sd] = pu.rel_err(bwd[4 + o // 2].cpu().numpy(), gg)
+    bad = {k: v for k, v in worst.items() if not (v <= tol)}
+    assert not bad, f"rel err above {tol}: {bad} (all: {worst})"
+    # the gain gradient is a float32 sum of float32 terms whatever the storage type
+    assert worst["dgain_q"] <= 1e-4 and worst["dgain_k"] <= 1e-4, worst
+    return worst
+
+
+def run(inp):
+    dev = {n: t.cuda() for n, t in inp.items()}
+    fwd = tvm.tvmattn_qknorm_jvp_fwd(dev["q"], dev["tq"], dev["k"], dev["tk"], dev["gain_q"], dev["gain_k"], EPS)
+    bwd = tvm.tvmattn_qknorm_jvp_bwd(dev["q"], dev["tq"], dev["k"], dev["tk"], dev["gain_q"], dev["gain_k"], EPS,
+                                     dev["gqn"], dev["gtqn"], dev["gkn"], dev["gtkn"])
+    torch.cuda.synchronize()
+    return fwd, bwd
+
+
+@pytest.mark.parametrize("B,H,M,N,d,dtype", [
+    (1, 1, 1, 1, 8, "bf16"), (2, 3, 77, 77, 72, "bf16"), (1, 2, 100, 260, 64, "bf16"), (2, 1, 33, 17, 128, "bf16"),
+    (1, 2, 50, 50, 136, "bf16"), (1, 1, 19, 40, 256, "bf16"), (1, 1, 70, 70, 16, "bf16"),
+    (2, 3, 77, 31, 40, "f32"), (1, 2, 64, 64, 4, "f32"), (1, 1, 30, 45, 100, "f32"), (1, 1, 20, 20, 256, "f32"),
+    (2, 4, 2500, 2100, 72, "bf16"),   # more rows than the workgroups cover in one pass
+])
+def test_every_element_against_the_oracle(B, H, M, N, d, dtype):
+    announce(f"qknorm B{B} H{H} M{M} N{N} d{d} {dtype}")
+    inp = sides(B, H, M, N, d, dtype, 61)
+    fwd, bwd = run(inp)
+    worst = check(inp, fwd, bwd, dtype)
+    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
+@pytest.mark.parametrize("d,pitch,dtype", [(20, 24, "bf16"), (7, 8, "f32"), (72, 80, "bf16"), (130, 136, "bf16")])
+def test_padded_rows_and_head_dims_that_end_inside_a_chunk(d, pitch, dtype):
+    """Rows pitch elements apart (a 16-byte multiple) holding d of them: the last 16-byte chunk of a row is
+    read and written element by element, and the padding is left alone."""
+    B, H, M, N = 2, 2, 37, 50
+    announce(f"qknorm strided d{d} pitch{pitch} {dtype}")
+    inp = sides(B, H, M, N, d, dtype, 62)
+    dev = {}
+    for n, t in inp.items():
+        if t.dim() == 4:
+            buf = torch.full((t.shape[0], t.shape[1], t.shape[2], pitch), 7.0, dtype=t.dtype, device="cuda")
+            buf[..., :d] = t.cuda()
+            dev[n] = buf[..., :d]
+        else:
+            dev[n] = t.cuda()
+    mk = lambda like: torch.full((like.shape[0], like.shape[1], like.shape[2], pitch), 7.0, dtype=like.dtype,
+                                 device="cuda")
+    bufs = [mk(dev["q"]), mk(dev["q"]), mk(dev["k"]), mk(dev["k"])]
+    fwd = tvm.tvmattn_qknorm_jvp_fwd(dev["q"], dev["tq"], dev["k"], dev["tk"], dev["gain_q"], dev["gain_k"], EPS,
+                                     out=tuple(b[..., :d] for b in bufs))
+    gbufs = [mk(dev["q"]), mk(dev["q"]), mk(dev["k"]), mk(dev["k"])]
+    bwd = tvm.tvmattn_qknorm_jvp_bwd(dev["q"], dev["tq"], dev["k"], dev["tk"], dev["gain_q"], dev["gain_k"], EPS,
+                                     dev["gqn"], dev["gtqn"], dev["gkn"], dev["gtkn"],
+                                     out=tuple(b[..., :d] for b in gbufs) + (torch.empty_like(dev["gain_q"]),
+                                                                              torch.empty_like(dev["gain_k"])))
+    torch.cuda.synchronize()
+    check(inp, fwd, bwd, dtype)
+    for b in bufs + gbufs:
+        assert bool((b[..., d:] == 7.0).all()), "padding was written"
+
+
+def test_bitwise_reproducible():
+    inp = sides(2, 4, 900, 1100, 72, "bf16", 63)
+    announce("qknorm determinism")
+    a = run(inp)
+    b = run(inp)
+    for x, y in zip(a[0] + a[1], b[0] + b[1]):
+        assert torch.equal(x, y)
+
+
+def test_full_size():
+    """C4's shape in the launch configuration bench.py times: every element of every output."""
+    w = wl.CONFIGS["C4"]
+    announce(f"qknorm full-size {w}")
+    inp = sides(w.B, w.H, w.N, w.N, w.d, w.dtype, 64)
+    fwd, bwd = run(inp)
+    worst = check(inp, fwd, bwd, w.dtype)
+    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+
+
+def test_chain_with_attention():
+    """QK-norm -> attention with tangent -> both backwards, as the paper's block runs them, against the two
+    oracles chained in float64.  The chain rounds the normalised tensors and the gradients that flow back to
+    storage precision between the two steps, the oracle chain does not: same tolerance as each step alone."""
+    B, H, N, d, dtype = 2, 3, 200, 72, "bf16"
+    announce("qknorm + attention chain")
+    inp = wl.make_inputs(wl.custom(B, H, N, d, dtype), 65)
+    gq, gk = wl.make_gains(wl.custom(B, H, N, d, dtype), 66)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    gqd, gkd = gq.cuda(), gk.cuda()
+    qn, tqn, kn, tkn = tvm.tvmattn_qknorm_jvp_fwd(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS)
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(qn, kn, dev["v"], tqn, tkn, dev["tv"])
+    dqn, dkn, dv, dtqn, dtkn, dtv = tvm.tvmattn_jvp_bwd(qn, kn, dev["v"], tqn, tkn, dev["tv"], o, to, lse, stats,
+                                                        dev["gO"], dev["gTO"])
+    dq, dtq, dk, dtk, dgq, dgk = tvm.tvmattn_qknorm_jvp_bwd(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS,
+                                                            dqn, dtqn, dkn, dtkn)
+    torch.cuda.synchronize()
+    f = {n: wl.to_f64(t) for n, t in inp.items()}
+    g64q, g64k = wl.to_f64(gq), wl.to_f64(gk)
+    rqn, rtqn = norc.rmsnorm_jvp_fwd(f["q"], f["tq"], g64q, EPS)
+    rkn, rtkn = norc.rmsnorm_jvp_fwd(f["k"], f["tk"], g64k, EPS)
+    ro = aorc.attn_jvp_fwd(rqn, rkn, f["v"], rtqn, rtkn, f["tv"])
+    rg = aorc.attn_jvp_bwd(rqn, rkn, f["v"], rtqn, rtkn, f["tv"], f["gO"], f["gTO"])
+    rdq, rdtq, rdgq = norc.rmsnorm_jvp_bwd(f["q"], f["tq"], g64q, EPS, rg[0], rg[3])
+    rdk, rdtk, rdgk = norc.rmsnorm_jvp_bwd(f["k"], f["tk"], g64k, EPS, rg[1], rg[4])
+    tol = pu.TOL[dtype]
+    for name, got, ref in (("o", o, ro[0]), ("to", to, ro[1]), ("dq", dq, rdq), ("dtq", dtq, rdtq), ("dk", dk, rdk),
+                           ("dtk", dtk, rdtk), ("dv", dv, rg[2]), ("dtv", dtv, rg[5]), ("dgain_q", dgq, rdgq),
+                           ("dgain_k", dgk, rdgk)):
+        e = pu.rel_err(got.float().cpu().numpy(), ref)
+        assert e <= tol, (name, e)
