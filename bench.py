@@ -224,6 +224,50 @@ def one_sided(w, steps, seed=2024):
     return out
 
 
+def qknorm(w, steps, seed=2024):
+    """The QK-norm with tangent that feeds the attention (RMSNorm with gain, Sec. "Semi-Lipschitz control"),
+    forward and backward on the workload's q and k, timed outside the timed region of the headline figure
+    (wall clock over `steps` calls each, device synchronised).  Memory-bound: algorithmic bytes = every
+    tensor once (forward reads 4 and writes 4, backward reads 8 and writes 4), against 8 TB/s."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    inp = wl.make_inputs(w, seed)
+    dev = {n: inp[n].cuda() for n in ("q", "tq", "k", "tk", "gO", "gTO", "v", "tv")}
+    del inp
+    gq, gk = [g.cuda() for g in wl.make_gains(w, seed + 1)]
+    q, tq, k, tk = dev["q"], dev["tq"], dev["k"], dev["tk"]
+    fo = tuple(torch.empty_like(t) for t in (q, q, k, k))
+    bo = tuple(torch.empty_like(t) for t in (q, q, k, k)) + (torch.empty_like(gq), torch.empty_like(gk))
+    ws = torch.empty(tvm.tvmattn_qknorm_jvp_bwd_workspace_bytes(q, k=k), dtype=torch.uint8, device="cuda")
+    side_bytes = float(w.B) * w.H * w.d * (2 if w.dtype == "bf16" else 4)
+    tensors_q, tensors_k = side_bytes * w.Mq, side_bytes * w.N
+    cases = {
+        "fwd": (4.0 * (tensors_q + tensors_k),
+                lambda: tvm.tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gq, gk, 1e-6, out=fo)),
+        # upstream gradients: any tensors of the right shapes
+        "bwd": (6.0 * (tensors_q + tensors_k),
+                lambda: tvm.tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gq, gk, 1e-6, dev["gO"], dev["gTO"], dev["v"], dev["tv"],
+                                                   out=bo, workspace=ws)),
+    }
+    out = {}
+    for name, (nbytes, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
+                     "frac": gbs / 8000.0}
+    return out
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -303,6 +347,7 @@ def main():
         "kernels": res["kernels"], "roofline": roofline, "also": also,
     }
     out["one_sided"] = one_sided(w, args.steps)
+    out["qknorm"] = qknorm(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

@@ -21,17 +21,29 @@ constexpr int kNT = 256;
 constexpr int kLpr = 16;  // lanes per row
 
 template <typename T>
-struct Chunk {  // 16 bytes of T
+struct alignas(16) Chunk {  // 16 bytes of T, 16-byte aligned: one load or store instruction
   static constexpr int VEC = 16 / sizeof(T);
   T v[VEC];
 };
 
 // Elements [c0, c0 + VEC) of the row at p as float32, zero beyond D.  Whole chunks are one 16-byte load
-// (rows start on 16-byte boundaries); a chunk that crosses D is read element by element.
-template <typename T>
+// (rows start on 16-byte boundaries); a chunk that crosses D is read element by element.  FULL: D is a
+// multiple of VEC, every chunk is whole or empty, and the load is unconditional (an empty chunk reads the
+// row's first one and discards it), so that the loads of a row are all in flight before the first is used.
+template <typename T, bool FULL>
 __device__ __forceinline__ void load_chunk(float (&out)[Chunk<T>::VEC], const T* p, int c0, int D) {
   constexpr int VEC = Chunk<T>::VEC;
-  if (c0 + VEC <= D) {
+  if (FULL) {
+    const bool live = c0 < D;
+    uint4 raw = *reinterpret_cast<const uint4*>(p + (live ? c0 : 0));  // one 16-byte load
+    raw.x = live ? raw.x : 0u;
+    raw.y = live ? raw.y : 0u;
+    raw.z = live ? raw.z : 0u;
+    raw.w = live ? raw.w : 0u;
+    const Chunk<T> c = __builtin_bit_cast(Chunk<T>, raw);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = (float)c.v[e];
+  } else if (c0 + VEC <= D) {
     const Chunk<T> c = *reinterpret_cast<const Chunk<T>*>(p + c0);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) out[e] = (float)c.v[e];
@@ -40,24 +52,32 @@ __device__ __forceinline__ void load_chunk(float (&out)[Chunk<T>::VEC], const T*
     for (int e = 0; e < VEC; ++e) out[e] = c0 + e < D ? (float)p[c0 + e] : 0.f;
   }
 }
-template <typename T>
+template <typename T, bool FULL>
 __device__ __forceinline__ void store_chunk(T* p, int c0, int D, const float (&in)[Chunk<T>::VEC]) {
   constexpr int VEC = Chunk<T>::VEC;
-  if (c0 + VEC <= D) {
+  if (FULL || c0 + VEC <= D) {  // (callers skip chunks that start at or beyond D)
     Chunk<T> c;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) c.v[e] = (T)in[e];  // round to nearest even
-    *reinterpret_cast<Chunk<T>*>(p + c0) = c;
+    *reinterpret_cast<uint4*>(p + c0) = __builtin_bit_cast(uint4, c);  // one 16-byte store
   } else {
 #pragma unroll
     for (int e = 0; e < VEC; ++e)
       if (c0 + e < D) p[c0 + e] = (T)in[e];
   }
 }
-// Sum over the 16 lanes of a row (lanes 16k .. 16k+15 of the wave).
+// Sum over the 16 lanes of a row (lanes 16k .. 16k+15 of the wave), the same bits in all of them: a butterfly
+// of four data-parallel-primitive moves (neighbour, pair, mirrored half, mirrored row; after the first two a
+// quad holds one value, so the mirrors pair whole quads and halves), no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float row_sum(float x) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_move<0x141>(x);  // row_half_mirror
+  x += dpp_move<0x140>(x);  // row_mirror
   return x;
 }
 
@@ -65,13 +85,14 @@ struct RowIter {  // the rows of one side that this thread's row slot works on
   long long row, end, step;
 };
 __device__ __forceinline__ long long row_offset(const NormArgs& a, const NormSide& s, long long row) {
-  const long long bh = row / s.n, i = row - bh * s.n;
-  const long long b = bh / a.H, h = bh - b * a.H;
-  return b * s.sb + h * s.sh + i * s.sn;
+  const unsigned r = (unsigned)row;  // fewer than 2^31 rows per side: 32-bit divisions
+  const unsigned bh = r / (unsigned)s.n, i = r - bh * (unsigned)s.n;
+  const unsigned b = bh / (unsigned)a.H, h = bh - b * (unsigned)a.H;
+  return (long long)b * s.sb + (long long)h * s.sh + (long long)i * s.sn;
 }
 
 // MAXC: chunks per lane (16 lanes x MAXC x VEC >= D).
-template <typename T, int MAXC>
+template <typename T, int MAXC, bool FULL>
 __global__ __launch_bounds__(kNT) void qknorm_fwd_kernel(NormArgs a) {
   constexpr int VEC = Chunk<T>::VEC;
   const int sd = (int)blockIdx.x >= a.side[0].nwg ? 1 : 0;
@@ -97,8 +118,8 @@ __global__ __launch_bounds__(kNT) void qknorm_fwd_kernel(NormArgs a) {
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
       const int c0 = (lr + kLpr * c) * VEC;
-      load_chunk<T>(x[c], xp, c0, a.D);
-      load_chunk<T>(t[c], tp, c0, a.D);
+      load_chunk<T, FULL>(x[c], xp, c0, a.D);
+      load_chunk<T, FULL>(t[c], tp, c0, a.D);
     }
 #pragma unroll
     for (int c = 0; c < MAXC; ++c)
@@ -123,13 +144,13 @@ __global__ __launch_bounds__(kNT) void qknorm_fwd_kernel(NormArgs a) {
         y[e] = g[c][e] * (x[c][e] * r);
         ty[e] = g[c][e] * (t[c][e] * r - x[c][e] * r3m);
       }
-      store_chunk<T>(yp, c0, a.D, y);
-      store_chunk<T>(typ, c0, a.D, ty);
+      store_chunk<T, FULL>(yp, c0, a.D, y);
+      store_chunk<T, FULL>(typ, c0, a.D, ty);
     }
   }
 }
 
-template <typename T, int MAXC>
+template <typename T, int MAXC, bool FULL>
 __global__ __launch_bounds__(kNT) void qknorm_bwd_kernel(NormArgs a) {
   constexpr int VEC = Chunk<T>::VEC;
   __shared__ float red[kNT / kLpr][kLpr * MAXC * VEC];  // one row of column sums per row slot
@@ -158,10 +179,10 @@ __global__ __launch_bounds__(kNT) void qknorm_bwd_kernel(NormArgs a) {
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
       const int c0 = (lr + kLpr * c) * VEC;
-      load_chunk<T>(x[c], xp, c0, a.D);
-      load_chunk<T>(t[c], tp, c0, a.D);
-      load_chunk<T>(gy[c], gyp, c0, a.D);
-      load_chunk<T>(gt[c], gtp, c0, a.D);
+      load_chunk<T, FULL>(x[c], xp, c0, a.D);
+      load_chunk<T, FULL>(t[c], tp, c0, a.D);
+      load_chunk<T, FULL>(gy[c], gyp, c0, a.D);
+      load_chunk<T, FULL>(gt[c], gtp, c0, a.D);
     }
     float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
 #pragma unroll
@@ -199,8 +220,8 @@ __global__ __launch_bounds__(kNT) void qknorm_bwd_kernel(NormArgs a) {
         gx[e] = r * u - r3m * w - kB * t[c][e] + kx * x[c][e];
         acc[c][e] += gy[c][e] * (x[c][e] * r) + gt[c][e] * (t[c][e] * r - x[c][e] * r3m);
       }
-      store_chunk<T>(gxp, c0, a.D, gx);
-      store_chunk<T>(gtxp, c0, a.D, gtx);
+      store_chunk<T, FULL>(gxp, c0, a.D, gx);
+      store_chunk<T, FULL>(gtxp, c0, a.D, gtx);
     }
   }
   // column sums of this workgroup: the 16 row slots added in order
@@ -217,44 +238,69 @@ __global__ __launch_bounds__(kNT) void qknorm_bwd_kernel(NormArgs a) {
   }
 }
 
-// gg[col] = sum over the partial rows, in order.  One workgroup per side.
-__global__ __launch_bounds__(kNT) void qknorm_gain_grad_kernel(NormArgs a) {
+// gg[col] = sum over the partial rows, in a fixed order: a workgroup takes 64 columns of one side, its 16 row
+// slices each add every 16th partial row (eight loads in flight at a time), and the slices are added in order.
+constexpr int kRedCols = 64, kRedSlices = 16;
+__global__ __launch_bounds__(kRedCols * kRedSlices) void qknorm_gain_grad_kernel(NormArgs a) {
+  __shared__ float red[kRedSlices][kRedCols];
   const NormSide s = blockIdx.x ? a.side[1] : a.side[0];
-  for (int col = threadIdx.x; col < a.D; col += kNT) {
-    float sum = 0.f;
-    for (int w = 0; w < s.nwg; ++w) sum += s.part[(long long)w * a.D + col];
-    s.gg[col] = sum;
+  const int lc = threadIdx.x % kRedCols, sl = threadIdx.x / kRedCols;
+  const int col = blockIdx.y * kRedCols + lc;
+  float sum = 0.f;
+  if (col < a.D) {
+    int w = sl;
+    for (; w + 7 * kRedSlices < s.nwg; w += 8 * kRedSlices) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = s.part[(long long)(w + u * kRedSlices) * a.D + col];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+    for (; w < s.nwg; w += kRedSlices) sum += s.part[(long long)w * a.D + col];
+  }
+  red[sl][lc] = sum;
+  __syncthreads();
+  if (sl == 0 && col < a.D) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < kRedSlices; ++k) t += red[k][lc];
+    s.gg[col] = t;
   }
 }
 
 }  // namespace
 
+// Kernel choice: chunks per lane from D, and whether D is a whole number of 16-byte chunks.
+#define TVM_NORM_LAUNCH(KERNEL, T, MAXC)                                                         \
+  do {                                                                                           \
+    if (a.D % Chunk<T>::VEC == 0) hipLaunchKernelGGL((KERNEL<T, MAXC, true>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((KERNEL<T, MAXC, false>), grid, block, 0, st, a);                   \
+  } while (0)
+#define TVM_NORM_BY_TYPE(KERNEL)                                   \
+  do {                                                             \
+    if (dtype == 1) {                                              \
+      if (a.D <= 128) TVM_NORM_LAUNCH(KERNEL, bf16, 1);            \
+      else TVM_NORM_LAUNCH(KERNEL, bf16, 2);                       \
+    } else {                                                       \
+      if (a.D <= 64) TVM_NORM_LAUNCH(KERNEL, float, 1);            \
+      else if (a.D <= 128) TVM_NORM_LAUNCH(KERNEL, float, 2);      \
+      else TVM_NORM_LAUNCH(KERNEL, float, 4);                      \
+    }                                                              \
+  } while (0)
+
 hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(a.side[0].nwg + a.side[1].nwg), block(kNT);
-  if (dtype == 1) {
-    if (a.D <= 128) hipLaunchKernelGGL((qknorm_fwd_kernel<bf16, 1>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((qknorm_fwd_kernel<bf16, 2>), grid, block, 0, st, a);
-  } else {
-    if (a.D <= 64) hipLaunchKernelGGL((qknorm_fwd_kernel<float, 1>), grid, block, 0, st, a);
-    else if (a.D <= 128) hipLaunchKernelGGL((qknorm_fwd_kernel<float, 2>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((qknorm_fwd_kernel<float, 4>), grid, block, 0, st, a);
-  }
+  TVM_NORM_BY_TYPE(qknorm_fwd_kernel);
   return hipGetLastError();
 }
 
 hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(a.side[0].nwg + a.side[1].nwg), block(kNT);
-  if (dtype == 1) {
-    if (a.D <= 128) hipLaunchKernelGGL((qknorm_bwd_kernel<bf16, 1>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((qknorm_bwd_kernel<bf16, 2>), grid, block, 0, st, a);
-  } else {
-    if (a.D <= 64) hipLaunchKernelGGL((qknorm_bwd_kernel<float, 1>), grid, block, 0, st, a);
-    else if (a.D <= 128) hipLaunchKernelGGL((qknorm_bwd_kernel<float, 2>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((qknorm_bwd_kernel<float, 4>), grid, block, 0, st, a);
-  }
+  TVM_NORM_BY_TYPE(qknorm_bwd_kernel);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2), block, 0, st, a);
+  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2, (a.D + kRedCols - 1) / kRedCols), dim3(kRedCols * kRedSlices), 0,
+                     st, a);
   return hipGetLastError();
 }
 

@@ -85,7 +85,7 @@ struct NormArgs {
   float eps;
 };
 constexpr int kNormRowsPerWg = 16;   // rows a workgroup works on at a time (16 lanes each)
-constexpr int kNormMaxWg = 1024;     // workgroups per side at most (they stride over the rows)
+constexpr int kNormMaxWg = 1024;     // workgroups per side at most (they stride over the rows; two sides fill the chip)
 hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st);
 hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st);
 
