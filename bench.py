@@ -252,8 +252,7 @@ def qknorm(w, steps, seed=2024):
                 lambda: tvm.tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gq, gk, 1e-6, dev["gO"], dev["gTO"], dev["v"], dev["tv"],
                                                    out=bo, workspace=ws)),
     }
-    out = {}
-    for name, (nbytes, fn) in cases.items():
+    def timed(fn):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
@@ -261,10 +260,32 @@ def qknorm(w, steps, seed=2024):
         for _ in range(steps):
             fn()
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    out = {}
+    for name, (nbytes, fn) in cases.items():
+        ms = timed(fn)
         gbs = nbytes / (ms * 1e-3) / 1e9
         out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
                      "frac": gbs / 8000.0}
+    # the block as the paper runs it: attention on the normalised tensors, then both backwards, as two calls and
+    # as the one call that does the norm's backward in the attention kernels' epilogues (where that is served)
+    if tvm.tvmattn_jvp_bwd_qknorm_workspace_bytes(q, k=k) > 0:
+        qn, tqn, kn, tkn = tvm.tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gq, gk, 1e-6, out=fo)
+        v, tv, gO, gTO = dev["v"], dev["tv"], dev["gO"], dev["gTO"]
+        o, to, lse, stats = tvm.tvmattn_jvp_fwd(qn, kn, v, tqn, tkn, tv)
+        g6 = tuple(torch.empty_like(q if n in (0, 3) else k) for n in range(6))
+        aws = torch.empty(tvm.tvmattn_jvp_bwd_workspace_bytes(q, k=k), dtype=torch.uint8, device="cuda")
+        fws = torch.empty(tvm.tvmattn_jvp_bwd_qknorm_workspace_bytes(q, k=k), dtype=torch.uint8, device="cuda")
+        f8 = tuple(torch.empty_like(t) for t in g6) + (torch.empty_like(gq), torch.empty_like(gk))
+
+        def two_calls():
+            tvm.tvmattn_jvp_bwd(qn, kn, v, tqn, tkn, tv, o, to, lse, stats, gO, gTO, out=g6, workspace=aws)
+            tvm.tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gq, gk, 1e-6, g6[0], g6[3], g6[1], g6[4], out=bo, workspace=ws)
+
+        out["attention_bwd_then_norm_bwd"] = {"ms": timed(two_calls)}
+        out["attention_bwd_with_norm_bwd_fused"] = {"ms": timed(lambda: tvm.tvmattn_jvp_bwd_qknorm(
+            q, tq, k, tk, gq, gk, 1e-6, qn, tqn, kn, tkn, v, tv, o, to, lse, stats, gO, gTO, out=f8, workspace=fws))}
     return out
 
 

@@ -202,6 +202,37 @@ int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc,
                            void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
+/*
+ * tvmattn_jvp_bwd and tvmattn_qknorm_jvp_bwd in one call, for attention whose q, tq, k, tk came out of
+ * tvmattn_qknorm_jvp_fwd: the backward of the normalisation runs in the epilogues of the attention's two
+ * backward kernels (each has the rows of one side in registers when it ends), so the gradients with respect to the
+ * normalised tensors never reach device memory.
+ *   in : q, tq, k, tk, gain_q, gain_k, eps   as given to tvmattn_qknorm_jvp_fwd
+ *        qn, tqn, kn, tkn                    as it wrote them (and as given to tvmattn_jvp_fwd as q, tq, k, tk)
+ *        v, tv, o, to, lse, stats, gO, gTO   as for tvmattn_jvp_bwd; both upstream gradients are required
+ *   out: dq, dtq, dk, dtk                    gradients with respect to q, tq, k, tk (before the normalisation)
+ *        dv, dtv                             as from tvmattn_jvp_bwd
+ *        dgain_q, dgain_k                    [D] float32
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_jvp_bwd_qknorm_workspace_bytes(desc) bytes.
+ * Served by the hand-scheduled kernels only: bfloat16, D a multiple of 8, D <= 96; anything else returns
+ * TVMATTN_UNSUPPORTED (and the size query 0): call tvmattn_jvp_bwd and tvmattn_qknorm_jvp_bwd one after the other
+ * there.  Three launches (query side, key side, the ordered sum of per-workgroup gain-gradient rows); no atomics.
+ * The gradients with respect to the normalised rows are rounded to dtype between the two steps, as they are when
+ * the two calls are made separately.
+ */
+size_t tvmattn_jvp_bwd_qknorm_workspace_bytes(const tvmattn_desc* desc);
+int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc,
+                           const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps,
+                           const void* qn, const void* tqn, const void* kn, const void* tkn,
+                           const void* v, const void* tv,
+                           const void* o, const void* to, const float* lse, const float* stats,
+                           const void* gO, const void* gTO,
+                           void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
+                           float* dgain_q, float* dgain_k,
+                           void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,6 +62,11 @@ def lib():
         L.tvmattn_qknorm_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_qknorm_jvp_bwd.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 11 +
                                              [ctypes.c_size_t, _P])
+        L.tvmattn_jvp_bwd_qknorm_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_jvp_bwd_qknorm_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
+        L.tvmattn_jvp_bwd_qknorm.restype = ctypes.c_int
+        L.tvmattn_jvp_bwd_qknorm.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 21 +
+                                             [ctypes.c_size_t, _P])
         _lib = L
     return _lib
 
@@ -232,4 +237,40 @@ def tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gain_q, gain_k, eps, gqn, gtqn, gkn, gt
                                         gain_q.data_ptr(), gain_k.data_ptr(), float(eps), gqn.data_ptr(), gtqn.data_ptr(),
                                         gkn.data_ptr(), gtkn.data_ptr(), *[t.data_ptr() for t in out],
                                         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def tvmattn_jvp_bwd_qknorm_workspace_bytes(q, k=None):
+    """0 where the fused call is not supported (see tvmattn_jvp_bwd_qknorm)."""
+    desc = make_desc(q if k is None else k, 0.0, q)
+    return int(lib().tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(desc)))
+
+
+def tvmattn_jvp_bwd_qknorm(q, tq, k, tk, gain_q, gain_k, eps, qn, tqn, kn, tkn, v, tv, o, to, lse, stats, gO, gTO,
+                           scale=0.0, out=None, workspace=None):
+    """Attention backward and QK-norm backward in one call.  Returns (dq, dk, dv, dtq, dtk, dtv, dgain_q, dgain_k),
+    the first six with respect to the tensors before the normalisation.  Raises TvmattnError (status -2) for
+    shapes the fused kernels do not take."""
+    _same_layout(q, tq, qn, tqn, o, to, gO, gTO)
+    _same_layout(k, tk, kn, tkn, v, tv)
+    _gain_ok(gain_q, q)
+    _gain_ok(gain_k, k)
+    desc = make_desc(k, scale, q)
+    if out is None:
+        out = tuple(torch.empty_like(q if n in (0, 3) else k) for n in range(6)) + (torch.empty_like(gain_q),
+                                                                                 torch.empty_like(gain_k))
+    else:
+        _same_layout(q, out[0], out[3])
+        _same_layout(k, out[1], out[2], out[4], out[5])
+        _gain_ok(out[6], q)
+        _gain_ok(out[7], k)
+    need = int(lib().tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib().tvmattn_jvp_bwd_qknorm(ctypes.byref(desc), q.data_ptr(), tq.data_ptr(), k.data_ptr(), tk.data_ptr(),
+                                        gain_q.data_ptr(), gain_k.data_ptr(), float(eps), qn.data_ptr(), tqn.data_ptr(),
+                                        kn.data_ptr(), tkn.data_ptr(), v.data_ptr(), tv.data_ptr(), o.data_ptr(),
+                                        to.data_ptr(), lse.data_ptr(), stats.data_ptr(), gO.data_ptr(), gTO.data_ptr(),
+                                        *[t.data_ptr() for t in out], workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream()))
     return out

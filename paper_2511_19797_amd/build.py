@@ -25,6 +25,8 @@ PER_FILE = {
     "bwd_col_pipe.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_row_pipe_tangent.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_col_pipe_tangent.hip": ["-mllvm", "-enable-misched=false"],
+    "bwd_row_pipe_qknorm.hip": ["-mllvm", "-enable-misched=false"],
+    "bwd_col_pipe_qknorm.hip": ["-mllvm", "-enable-misched=false"],
 }
 
 

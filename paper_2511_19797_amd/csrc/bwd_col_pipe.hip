@@ -46,9 +46,15 @@ constexpr int kNT = 256;
 // file yields the kernels for calls without gO and their launcher, else those for calls with both gradients.
 #if defined(TVM_PIPE_TANGENT_ONLY)
 constexpr bool kHasG = false;
+constexpr bool kNorm = false;
 #define TVM_PIPE_LAUNCHER launch_bwd_col_pipe_tangent
+#elif defined(TVM_PIPE_QKNORM)  // ... and with the backward of the QK-norm of the keys in the epilogue
+constexpr bool kHasG = true;
+constexpr bool kNorm = true;
+#define TVM_PIPE_LAUNCHER launch_bwd_col_pipe_qknorm
 #else
 constexpr bool kHasG = true;
+constexpr bool kNorm = false;
 #define TVM_PIPE_LAUNCHER launch_bwd_col_pipe
 #endif
 
@@ -59,13 +65,15 @@ __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
 }
 __device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
 
-template <int DK, int DV, bool HAS_G>
+template <int DK, int DV, bool HAS_G, bool NORM>
 __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const float* __restrict__ lse2w, const float* __restrict__ stats, const bf16* __restrict__ gO,
     const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
-    bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv) {
+    bf16* __restrict__ dk, bf16* __restrict__ dtk, bf16* __restrict__ dv, bf16* __restrict__ dtv,
+    const bf16* __restrict__ nx, const bf16* __restrict__ ntx, const float* __restrict__ ngain, float neps,
+    float* __restrict__ npart) {
   using TX = Tile<64, DV / 8, kNT / 64>;  // Q, tQ, G, tG: read both ways
   constexpr int OFF_TQ = TX::BYTES, OFF_G = 2 * TX::BYTES, OFF_TG = 3 * TX::BYTES, OFF_ROW = 4 * TX::BYTES;
   constexpr int BUF = 4 * TX::BYTES + 4 * 256;  // one stage: four tiles and four float32 row vectors (64 each)
@@ -431,10 +439,24 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
   {
     // nobody reads the tile buffers any more and no tile load is in flight: each wave stages its
     // four output tiles through a region of its own
-    const unsigned lw = lds0 + wave * (32 * (64 * NDB + 16));
+    constexpr unsigned REG = 32 * (64 * NDB + 16);
+    const unsigned lw = lds0 + wave * (2 * REG);
     const int row0 = fb * kFix + wave * 32;
-    store_tile_coalesced<NDB>(lw, dk + base, s.sn, row0, s.N, s.D, aK, s.alpha, lane);
-    store_tile_coalesced<NDB>(lw, dtk + base, s.sn, row0, s.N, s.D, aTK, s.alpha, lane);
+    if (!NORM) {
+      store_tile_coalesced<NDB>(lw, dk + base, s.sn, row0, s.N, s.D, aK, s.alpha, lane);
+      store_tile_coalesced<NDB>(lw, dtk + base, s.sn, row0, s.N, s.D, aTK, s.alpha, lane);
+    } else {
+      // k and tk were RMS-normalised with a gain before this attention (nx, ntx: the rows before that): the
+      // accumulators hold the gradients with respect to the normalised rows; park both tiles and write the
+      // gradients with respect to nx, ntx, and this workgroup's row of the gain gradient
+      NormRows nr;
+      norm_rows_fetch(nr, nx + base, ntx + base, s.sn, row0, s.N, s.D, lane);
+      park_tile<NDB>(lw, aK, s.alpha, lane);
+      park_tile<NDB>(lw + REG, aTK, s.alpha, lane);
+      float gacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      store_tiles_through_norm<NDB>(lw, lw + REG, nr, ngain, neps, dk + base, dtk + base, s.sn, row0, s.N, s.D, lane, gacc);
+      gain_partial_row(reinterpret_cast<float*>(lds + 4 * 2 * REG), gacc, npart + (long long)blockIdx.x * s.D, s.D, tid);
+    }
     store_tile_coalesced<NDB>(lw, dv + base, s.sn, row0, s.N, s.D, aV, 1.f, lane);
     store_tile_coalesced<NDB>(lw, dtv + base, s.sn, row0, s.N, s.D, aTV, 1.f, lane);
   }
@@ -444,10 +466,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_col_pipe_kernel<DK, DV, kHasG>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_col_pipe_kernel<DK, DV, kHasG, kNorm>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      a.lse2, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk,
-                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv);
+                     (bf16*)a.dtk, (bf16*)a.dv, (bf16*)a.dtv, (const bf16*)a.nk, (const bf16*)a.ntk, a.ngk, a.neps, a.npart_k);
   return hipGetLastError();
 }
 
@@ -467,7 +489,7 @@ hipError_t TVM_PIPE_LAUNCHER(const Shape& s, const BwdArgs& a, hipStream_t st) {
   }
 }
 
-#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY)
+#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY) && !defined(TVM_PIPE_QKNORM)
 extern "C" int tvmattn_debug_read_prof_col_pipe(long long* out16) {
   return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
 }

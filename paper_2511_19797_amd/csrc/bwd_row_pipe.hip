@@ -47,21 +47,28 @@ constexpr float kLog2e = 1.4426950408889634f;
 // file yields the kernels for calls without gO and their launcher, else those for calls with both gradients.
 #if defined(TVM_PIPE_TANGENT_ONLY)
 constexpr bool kHasG = false;
+constexpr bool kNorm = false;
 #define TVM_PIPE_LAUNCHER launch_bwd_row_pipe_tangent
+#elif defined(TVM_PIPE_QKNORM)  // ... and with the backward of the QK-norm of the queries in the epilogue
+constexpr bool kHasG = true;
+constexpr bool kNorm = true;
+#define TVM_PIPE_LAUNCHER launch_bwd_row_pipe_qknorm
 #else
 constexpr bool kHasG = true;
+constexpr bool kNorm = false;
 #define TVM_PIPE_LAUNCHER launch_bwd_row_pipe
 #endif
 
 
-template <int DK, int DV, bool HAS_G>
+template <int DK, int DV, bool HAS_G, bool NORM>
 __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const bf16* __restrict__ o, const bf16* __restrict__ to, const float* __restrict__ lse,
     const float* __restrict__ stats, const bf16* __restrict__ gO, const bf16* __restrict__ gTO,
     float* __restrict__ dsig, float* __restrict__ sig1, float* __restrict__ lse2w, bf16* __restrict__ dq,
-    bf16* __restrict__ dtq) {
+    bf16* __restrict__ dtq, const bf16* __restrict__ nx, const bf16* __restrict__ ntx, const float* __restrict__ ngain,
+    float neps, float* __restrict__ npart) {
   using TK = Tile<64, DV / 8, kNT / 64>;  // K, tK: read both ways
   using TV = Tile<64, DK / 8, kNT / 64>;  // V, tV: score-type products only
   constexpr int OFF_TK = TK::BYTES, OFF_V = 2 * TK::BYTES, OFF_TV = 2 * TK::BYTES + TV::BYTES;
@@ -461,13 +468,27 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
     landed_acc(aQ[db]);
     landed_acc(aTQ[db]);
   }
-  {
+  if (!NORM) {
     // nobody reads the tile buffers any more and no tile load is in flight: each wave stages its
     // two output tiles through a region of its own
     const unsigned lw = lds0 + wave * (32 * (64 * NDB + 16));
     const int row0 = fb * kFix + wave * 32;
     store_tile_coalesced<NDB>(lw, dq + qbase, s.qsn, row0, s.M, s.D, aQ, s.alpha, lane);
     store_tile_coalesced<NDB>(lw, dtq + qbase, s.qsn, row0, s.M, s.D, aTQ, s.alpha, lane);
+  } else {
+    // q and tq were RMS-normalised with a gain before this attention (nx, ntx: the rows before that): what is
+    // in the accumulators are the gradients with respect to the normalised rows; park both tiles and write the
+    // gradients with respect to nx, ntx, and this workgroup's row of the gain gradient
+    constexpr unsigned REG = 32 * (64 * NDB + 16);
+    const unsigned lw = lds0 + wave * (2 * REG);
+    const int row0 = fb * kFix + wave * 32;
+    NormRows nr;
+    norm_rows_fetch(nr, nx + qbase, ntx + qbase, s.qsn, row0, s.M, s.D, lane);
+    park_tile<NDB>(lw, aQ, s.alpha, lane);
+    park_tile<NDB>(lw + REG, aTQ, s.alpha, lane);
+    float gacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_tiles_through_norm<NDB>(lw, lw + REG, nr, ngain, neps, dq + qbase, dtq + qbase, s.qsn, row0, s.M, s.D, lane, gacc);
+    gain_partial_row(reinterpret_cast<float*>(lds + 4 * 2 * REG), gacc, npart + (long long)blockIdx.x * s.D, s.D, tid);
   }
   PROF_EXIT;
 }
@@ -475,10 +496,11 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
 template <int DK, int DV>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.M + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV, kHasG>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_row_pipe_kernel<DK, DV, kHasG, kNorm>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv,
                      (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO, (const bf16*)a.gTO,
-                     a.dsig, a.sig1, a.lse2, (bf16*)a.dq, (bf16*)a.dtq);
+                     a.dsig, a.sig1, a.lse2, (bf16*)a.dq, (bf16*)a.dtq, (const bf16*)a.nq, (const bf16*)a.ntq, a.ngq, a.neps,
+                     a.npart_q);
   return hipGetLastError();
 }
 
@@ -497,7 +519,7 @@ hipError_t TVM_PIPE_LAUNCHER(const Shape& s, const BwdArgs& a, hipStream_t st) {
   }
 }
 
-#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY)
+#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY) && !defined(TVM_PIPE_QKNORM)
 extern "C" int tvmattn_debug_read_prof_row_pipe(long long* out16) {
   return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
 }

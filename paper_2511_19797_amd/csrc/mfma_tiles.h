@@ -378,4 +378,141 @@ __device__ __forceinline__ void store_tile_coalesced(unsigned lds_wave, bf16* __
   }
 }
 
+
+// ---- Backward through an RMSNorm with gain that normalised the rows before the attention, in the epilogue.
+// Sum over the 16 lanes of a row group (lanes 16k .. 16k+15), the same bits in all of them: a butterfly of four
+// data-parallel-primitive moves, no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move16(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float sum16(float x) {
+  x += dpp_move16<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_move16<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_move16<0x141>(x);  // row_half_mirror
+  x += dpp_move16<0x140>(x);  // row_mirror
+  return x;
+}
+// Parks one wave's [32 x D] tile (transposed accumulators, scaled) in its LDS region as bf16, row by row: the
+// first half of store_tile_coalesced.  Region: 32 * (64*NDB + 16) bytes.
+template <int NDB>
+__device__ __forceinline__ void park_tile(unsigned lds_wave, const f32x16 (&a)[NDB], float scale, int lane) {
+  constexpr int PB = 64 * NDB + 16;
+  typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+  typedef u32x2 __attribute__((address_space(3))) * wp;
+  const int ic = lane & 31, hh = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 o;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) o[t] = (bf16)(a[db][4 * g + t] * scale);
+      *(wp)(uintptr_t)(lds_wave + (unsigned)(ic * PB + (db * 32 + 8 * g + 4 * hh) * 2)) = __builtin_bit_cast(u32x2, o);
+    }
+}
+// The wave's 32 rows were y = g o x r, ty = g o (tx r - x r^3 m) with r = 1 / sqrt(mean(x^2) + eps), m = mean(x tx)
+// (RMSNorm with gain as QK-norm and its tangent; Sec. "Semi-Lipschitz control", App. "Lipschitzness of RMSNorm")
+// before they entered the attention.  With the gradients gy, gty of the attention with respect to y, ty parked at
+// lds_gy, lds_gty (park_tile), this reads x, tx, writes the gradients with respect to them,
+//     gtx = r w - (r^3 Bw / d) x,   gx = r u - r^3 m w - (r^3 Bw / d) tx + x (3 r^5 m Bw - r^3 (A + C)) / d
+//     (u = g o gy, w = g o gty, A = <u,x>, Bw = <w,x>, C = <w,tx>),
+// 16 lanes to a row and 16 bytes per lane, four rows at a time, and adds this wave's part of the gain gradient,
+// gy o x r + gty o (tx r - x r^3 m), for the lane's eight columns into gacc.  Needs D <= 128.
+// The rows of x and tx are fetched first, all of them (norm_rows_fetch: call it before the tiles are parked, so
+// that one memory round trip covers the wave's 32 rows), then worked on.
+struct NormRows {
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+  u32x4 x[8], t[8];
+};
+__device__ __forceinline__ void norm_rows_fetch(NormRows& nr, const bf16* __restrict__ x_head, const bf16* __restrict__ tx_head,
+                                                long long sn, int row0, int N, int D, int lane) {
+  const int lr = lane & 15, slot = lane >> 4;
+  const int c8 = lr * 8 < D ? lr * 8 : 0;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const long long off = (long long)min(row0 + it * 4 + slot, N - 1) * sn + c8;
+    nr.x[it] = *reinterpret_cast<const NormRows::u32x4*>(x_head + off);
+    nr.t[it] = *reinterpret_cast<const NormRows::u32x4*>(tx_head + off);
+  }
+}
+template <int NDB>
+__device__ __forceinline__ void store_tiles_through_norm(unsigned lds_gy, unsigned lds_gty, const NormRows& nr,
+                                                         const float* __restrict__ gain, float eps,
+                                                         bf16* __restrict__ gx_head, bf16* __restrict__ gtx_head,
+                                                         long long sn, int row0, int N, int D, int lane, float (&gacc)[8]) {
+  constexpr int PB = 64 * NDB + 16;
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+  typedef const u32x4 __attribute__((address_space(3))) * rp;
+  const int lr = lane & 15, slot = lane >> 4;
+  const bool live = lr * 8 < D;   // (D is a multiple of 8 on this path)
+  const int c8 = live ? lr * 8 : 0;
+  const float invd = 1.0f / (float)D;
+  float g[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) g[e] = live ? gain[c8 + e] : 0.f;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = it * 4 + slot;
+    const bool valid = row0 + r < N;
+    const long long off = (long long)min(row0 + r, N - 1) * sn + c8;
+    u32x4 rx = nr.x[it];
+    u32x4 rt = nr.t[it];
+    u32x4 ry = *(rp)(uintptr_t)(lds_gy + (unsigned)(r * PB + c8 * 2));
+    u32x4 rz = *(rp)(uintptr_t)(lds_gty + (unsigned)(r * PB + c8 * 2));
+    if (!live) rx = rt = ry = rz = u32x4{0u, 0u, 0u, 0u};
+    const bf16x8 xb = __builtin_bit_cast(bf16x8, rx), tb = __builtin_bit_cast(bf16x8, rt);
+    const bf16x8 yb = __builtin_bit_cast(bf16x8, ry), zb = __builtin_bit_cast(bf16x8, rz);
+    float x[8], t[8], u[8], w[8];
+    float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[e] = (float)xb[e];
+      t[e] = (float)tb[e];
+      u[e] = g[e] * (float)yb[e];
+      w[e] = g[e] * (float)zb[e];
+      sxx = fmaf(x[e], x[e], sxx);
+      sxt = fmaf(x[e], t[e], sxt);
+      sA = fmaf(u[e], x[e], sA);
+      sB = fmaf(w[e], x[e], sB);
+      sC = fmaf(w[e], t[e], sC);
+    }
+    sxx = sum16(sxx);
+    sxt = sum16(sxt);
+    sA = sum16(sA);
+    sB = sum16(sB);
+    sC = sum16(sC);
+    const float rr = 1.0f / sqrtf(sxx * invd + eps);
+    const float r3 = rr * rr * rr, m = sxt * invd;
+    const float r3m = r3 * m, kB = r3 * sB * invd;
+    const float kx = (3.0f * r3 * rr * rr * m * sB - r3 * (sA + sC)) * invd;
+    bf16x8 ox, ot;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      ot[e] = (bf16)(rr * w[e] - kB * x[e]);
+      ox[e] = (bf16)(rr * u[e] - r3m * w[e] - kB * t[e] + kx * x[e]);
+      const float term = (float)yb[e] * (x[e] * rr) + (float)zb[e] * (t[e] * rr - x[e] * r3m);
+      gacc[e] += valid ? term : 0.f;
+    }
+    if (live && valid) {
+      *reinterpret_cast<u32x4*>(gx_head + off) = __builtin_bit_cast(u32x4, ox);
+      *reinterpret_cast<u32x4*>(gtx_head + off) = __builtin_bit_cast(u32x4, ot);
+    }
+  }
+}
+// One row of gain-gradient column sums per workgroup: the 4 waves x 4 row slots add their gacc in a fixed order
+// through `red` (LDS, 16 x 128 floats, free to use) and the row goes to part[0 .. D).  Call with all threads.
+__device__ __forceinline__ void gain_partial_row(float* red, const float (&gacc)[8], float* __restrict__ part, int D, int tid) {
+  const int lane = tid & 63, wave = tid >> 6, lr = lane & 15, slot = lane >> 4;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[(wave * 4 + slot) * 128 + lr * 8 + e] = gacc[e];
+  __syncthreads();
+  for (int col = tid; col < D; col += 256) {
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sum += red[k * 128 + col];
+    part[col] = sum;
+  }
+}
+
 }  // namespace tvm

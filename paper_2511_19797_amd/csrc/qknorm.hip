@@ -304,4 +304,21 @@ hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st) {
   return hipGetLastError();
 }
 
+
+// The same ordered sum for partial rows that other kernels wrote (the attention backward kernels with the
+// QK-norm's backward in their epilogues: one row per workgroup).
+hipError_t launch_gain_grad_sum(const float* part_q, int rows_q, float* gg_q, const float* part_k, int rows_k, float* gg_k,
+                                int D, hipStream_t st) {
+  NormArgs a{};
+  a.D = D;
+  a.side[0].part = const_cast<float*>(part_q);
+  a.side[0].nwg = rows_q;
+  a.side[0].gg = gg_q;
+  a.side[1].part = const_cast<float*>(part_k);
+  a.side[1].nwg = rows_k;
+  a.side[1].gg = gg_k;
+  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2, (D + kRedCols - 1) / kRedCols), dim3(kRedCols * kRedSlices), 0, st, a);
+  return hipGetLastError();
+}
+
 }  // namespace tvm

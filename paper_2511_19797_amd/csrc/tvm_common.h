@@ -49,6 +49,12 @@ struct BwdArgs {
   float *sig1;  // workspace: Sigma_1 per row
   float *lse2;  // workspace: lse in log2 units per row (written and read by the hand-scheduled kernels only)
   int mode;     // upstream gradients that exist: 0 both, 1 gO only (gTO null), 2 gTO only (gO null)
+  // backward through the QK-norm in the epilogues (launch_bwd_*_pipe_qknorm only): the rows before the
+  // normalisation, the gains, eps, and one partial gain-gradient row per workgroup of the two kernels
+  const void *nq = nullptr, *ntq = nullptr, *nk = nullptr, *ntk = nullptr;
+  const float *ngq = nullptr, *ngk = nullptr;
+  float neps = 0.f;
+  float *npart_q = nullptr, *npart_k = nullptr;
 };
 
 hipError_t launch_fwd_generic(const Shape& s, int dtype, const FwdArgs& a, hipStream_t st);
@@ -65,6 +71,10 @@ hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t
 hipError_t launch_bwd_row_onesided(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96
 hipError_t launch_bwd_col_pipe(const Shape& s, const BwdArgs& a, hipStream_t st);  // head dims up to 96, after the former
+hipError_t launch_bwd_row_pipe_qknorm(const Shape& s, const BwdArgs& a, hipStream_t st);  // the same two with the QK-norm's
+hipError_t launch_bwd_col_pipe_qknorm(const Shape& s, const BwdArgs& a, hipStream_t st);  // backward in their epilogues
+hipError_t launch_gain_grad_sum(const float* part_q, int rows_q, float* gg_q, const float* part_k, int rows_k, float* gg_k,
+                                int D, hipStream_t st);  // adds partial gain-gradient rows in order (qknorm.hip)
 
 
 // RMSNorm with gain as QK-norm, with tangent (qknorm.hip).  One side = the rows of q (and tq) or of k (and tk).

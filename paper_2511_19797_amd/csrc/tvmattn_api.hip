@@ -285,4 +285,60 @@ int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* 
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
 
+// ---- attention backward with the QK-norm's backward in the kernels' epilogues
+namespace {
+size_t pad256(size_t n) { return (n + 255) & ~(size_t)255; }
+size_t fused_part_bytes(const tvm::Shape& s, bool query_side) {  // one float32 row of D per workgroup (128 rows of a head)
+  const size_t blocks = (size_t)(((query_side ? s.M : s.N) + 127) / 128) * s.B * s.H;
+  return pad256(blocks * s.D * sizeof(float));
+}
+bool fused_supported(const tvm::Shape& s, int dtype) {
+  return g_path == 0 && tvm::mfma_supported(s, dtype) && s.D <= 96;
+}
+}  // namespace
+
+size_t tvmattn_jvp_bwd_qknorm_workspace_bytes(const tvmattn_desc* desc) {
+  tvm::Shape s;
+  if (resolve(desc, &s) || !fused_supported(s, desc->dtype)) return 0;
+  return tvmattn_jvp_bwd_workspace_bytes(desc) + fused_part_bytes(s, true) + fused_part_bytes(s, false);
+}
+
+int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc, const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps, const void* qn, const void* tqn,
+                           const void* kn, const void* tkn, const void* v, const void* tv, const void* o, const void* to,
+                           const float* lse, const float* stats, const void* gO, const void* gTO, void* dq, void* dk,
+                           void* dv, void* dtq, void* dtk, void* dtv, float* dgain_q, float* dgain_k, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
+  const void* const in[] = {q, tq, k, tk, gain_q, gain_k, qn, tqn, kn, tkn, v, tv, o, to, lse, stats, gO, gTO};
+  void* const out[] = {dq, dk, dv, dtq, dtk, dtv, dgain_q, dgain_k, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  if (!fused_supported(s, desc->dtype)) return TVMATTN_UNSUPPORTED;
+  if (workspace_bytes < tvmattn_jvp_bwd_qknorm_workspace_bytes(desc)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  const size_t need0 = tvmattn_jvp_bwd_workspace_bytes(desc);
+  char* const ws = static_cast<char*>(workspace);
+  tvm::BwdArgs a{qn, kn, v, tqn, tkn, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
+                 reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + need0 / 3),
+                 reinterpret_cast<float*>(ws + 2 * (need0 / 3)), 0};
+  a.nq = q;
+  a.ntq = tq;
+  a.nk = k;
+  a.ntk = tk;
+  a.ngq = gain_q;
+  a.ngk = gain_k;
+  a.neps = eps;
+  a.npart_q = reinterpret_cast<float*>(ws + need0);
+  a.npart_k = reinterpret_cast<float*>(ws + need0 + fused_part_bytes(s, true));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (tvm::launch_bwd_row_pipe_qknorm(s, a, st) != hipSuccess) return TVMATTN_LAUNCH_FAILED;
+  if (tvm::launch_bwd_col_pipe_qknorm(s, a, st) != hipSuccess) return TVMATTN_LAUNCH_FAILED;
+  const int rows_q = ((s.M + 127) / 128) * s.B * s.H, rows_k = ((s.N + 127) / 128) * s.B * s.H;
+  const hipError_t e = tvm::launch_gain_grad_sum(a.npart_q, rows_q, dgain_q, a.npart_k, rows_k, dgain_k, s.D, st);
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
 }  // extern "C"

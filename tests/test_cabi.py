@@ -180,3 +180,31 @@ def test_qknorm_argument_rules(L):
     p = list(b_rest)
     p[5] = p[4]                # dtq aliases dq
     assert bwd(b_in, p) == -1
+
+
+def test_fused_backward_argument_rules(L):
+    """tvmattn_jvp_bwd_qknorm: checked before anything is launched; status -3 (workspace too small) shows that
+    the pointer checks were passed, -2 that the shape is one the fused kernels do not take."""
+    L.tvmattn_jvp_bwd_qknorm.argtypes = [ctypes.POINTER(binding.tvmattn_desc)] + [ctypes.c_void_p] * 6 + \
+        [ctypes.c_float] + [ctypes.c_void_p] * 21 + [ctypes.c_size_t, ctypes.c_void_p]
+    L.tvmattn_jvp_bwd_qknorm_workspace_bytes.restype = ctypes.c_size_t
+    d = desc(B=2, H=3, N=300, D=72, M=100)
+    need = L.tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(d))
+    plain = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
+    assert need >= plain + (1 + 3) * 2 * 3 * 72 * 4 and need % 256 == 0   # one gain-gradient row per 128 rows of a head
+    head = [0x1000 * (i + 1) for i in range(6)]
+    rest = [0x1000 * (i + 7) for i in range(21)]   # 12 more inputs, 8 outputs, workspace
+    call = lambda a, b, ws=need - 1, eps=1e-6, dd=d: L.tvmattn_jvp_bwd_qknorm(ctypes.byref(dd), *a, eps, *b, ws, None)
+    assert call(head, rest) == -3
+    assert call(head, rest, eps=float("nan")) == -1
+    for i in range(21):
+        p = list(rest)
+        p[i] = None
+        assert call(head, p) == -1
+    p = list(rest)
+    p[13] = p[12]              # dk aliases dq
+    assert call(head, p) == -1
+    for kw in (dict(D=128), dict(D=72, dtype=0), dict(D=20, sn=24, sh=24 * 8, sb=24 * 8)):
+        dd = desc(**kw)
+        assert L.tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(dd)) == 0
+        assert call(head, rest, ws=1 << 30, dd=dd) == -2

@@ -157,3 +157,96 @@ def test_chain_with_attention():
                            ("dgain_k", dgk, rdgk)):
         e = pu.rel_err(got.float().cpu().numpy(), ref)
         assert e <= tol, (name, e)
+
+
+# ---------------------------------------------------------------- both backwards in one call
+def fused_and_chained(B, H, M, N, d, seed):
+    """Runs norm -> attention -> (a) the two backward calls one after the other, (b) the fused call."""
+    qs = wl.make_inputs(wl.custom(B, H, M, d, "bf16"), seed)
+    ks = wl.make_inputs(wl.custom(B, H, N, d, "bf16"), seed + 1)
+    inp = {n: (qs if n in ("q", "tq", "gO", "gTO") else ks)[n] for n in wl.NAMES}
+    gq, gk = wl.make_gains(wl.custom(B, H, N, d, "bf16"), seed + 2)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    gqd, gkd = gq.cuda(), gk.cuda()
+    qn, tqn, kn, tkn = tvm.tvmattn_qknorm_jvp_fwd(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS)
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(qn, kn, dev["v"], tqn, tkn, dev["tv"])
+    dqn, dkn, dv, dtqn, dtkn, dtv = tvm.tvmattn_jvp_bwd(qn, kn, dev["v"], tqn, tkn, dev["tv"], o, to, lse, stats,
+                                                        dev["gO"], dev["gTO"])
+    dq, dtq, dk, dtk, dgq, dgk = tvm.tvmattn_qknorm_jvp_bwd(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS,
+                                                            dqn, dtqn, dkn, dtkn)
+    chained = (dq, dk, dv, dtq, dtk, dtv, dgq, dgk)
+    fused = tvm.tvmattn_jvp_bwd_qknorm(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS, qn, tqn, kn, tkn,
+                                       dev["v"], dev["tv"], o, to, lse, stats, dev["gO"], dev["gTO"])
+    torch.cuda.synchronize()
+    return inp, (gq, gk), chained, fused
+
+
+FUSED_NAMES = ("dq", "dk", "dv", "dtq", "dtk", "dtv", "dgain_q", "dgain_k")
+
+
+def oracle_chain(inp, gains, b, h):
+    f = {n: wl.to_f64(t[b, h]) for n, t in inp.items()}
+    g64q, g64k = wl.to_f64(gains[0]), wl.to_f64(gains[1])
+    rqn, rtqn = norc.rmsnorm_jvp_fwd(f["q"], f["tq"], g64q, EPS)
+    rkn, rtkn = norc.rmsnorm_jvp_fwd(f["k"], f["tk"], g64k, EPS)
+    rg = aorc.attn_jvp_bwd_head(rqn, rkn, f["v"], rtqn, rtkn, f["tv"], f["gO"], f["gTO"])
+    rdq, rdtq, rdgq = norc.rmsnorm_jvp_bwd(f["q"], f["tq"], g64q, EPS, rg[0], rg[3])
+    rdk, rdtk, rdgk = norc.rmsnorm_jvp_bwd(f["k"], f["tk"], g64k, EPS, rg[1], rg[4])
+    return (rdq, rdk, rg[2], rdtq, rdtk, rg[5]), (rdgq, rdgk)
+
+
+@pytest.mark.parametrize("B,H,M,N,d", [
+    (1, 2, 100, 100, 16), (2, 1, 130, 70, 32), (1, 1, 97, 200, 48), (1, 2, 200, 200, 64), (2, 3, 200, 260, 72),
+    (1, 1, 65, 193, 96), (1, 1, 1, 1, 8), (1, 2, 300, 40, 40),
+])
+def test_fused_backward_against_the_oracle_chain_and_the_two_calls(B, H, M, N, d):
+    announce(f"fused attention + qknorm backward B{B} H{H} M{M} N{N} d{d}")
+    inp, gains, chained, fused = fused_and_chained(B, H, M, N, d, 71)
+    # against the two calls made one after the other: the same arithmetic on the same rounded gradients, so the six
+    # tensors agree to the last bit; the gain gradients add the same terms in another order
+    for name, a, b in zip(FUSED_NAMES[:6], chained, fused):
+        assert torch.equal(a, b), name
+    for name, a, b in zip(FUSED_NAMES[6:], chained[6:], fused[6:]):
+        assert pu.rel_err(b.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= 1e-5, name
+    # against the float64 chain of the two oracles, every head
+    gsum = [np.zeros(d), np.zeros(d)]
+    for b in range(B):
+        for h in range(H):
+            ref, rg = oracle_chain(inp, gains, b, h)
+            for name, got, r in zip(FUSED_NAMES[:6], fused, ref):
+                e = pu.rel_err(got[b, h].float().cpu().numpy(), r)
+                assert e <= pu.TOL["bf16"], (name, b, h, e)
+            gsum[0] += rg[0]
+            gsum[1] += rg[1]
+    for name, got, r in zip(FUSED_NAMES[6:], fused[6:], gsum):
+        assert pu.rel_err(got.cpu().numpy(), r) <= pu.TOL["bf16"], name
+
+
+def test_fused_backward_full_size():
+    """C4 in the launch configuration bench.py times: bitwise against the two separate calls for the tensors,
+    sampled heads against the oracle chain."""
+    w = wl.CONFIGS["C4"]
+    announce(f"fused attention + qknorm backward, full size {w}")
+    inp, gains, chained, fused = fused_and_chained(w.B, w.H, w.N, w.N, w.d, 72)
+    for name, a, b in zip(FUSED_NAMES[:6], chained, fused):
+        assert torch.equal(a, b), name
+    for name, a, b in zip(FUSED_NAMES[6:], chained[6:], fused[6:]):
+        assert pu.rel_err(b.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= 1e-5, name
+    for (b, h) in ((0, 0), (w.B - 1, w.H - 1)):
+        ref, _ = oracle_chain(inp, gains, b, h)
+        for name, got, r in zip(FUSED_NAMES[:6], fused, ref):
+            e = pu.rel_err(got[b, h].float().cpu().numpy(), r)
+            assert e <= pu.TOL["bf16"], (name, b, h, e)
+
+
+def test_fused_backward_refuses_what_it_does_not_serve():
+    """float32 and head dims above 96 are answered with status -2 and a zero workspace size, nothing launched."""
+    for B, H, N, d, dtype in ((1, 1, 64, 128, "bf16"), (1, 1, 64, 32, "f32")):
+        announce(f"fused backward unsupported d{d} {dtype}")
+        x = wl.make_inputs(wl.custom(B, H, N, d, dtype), 73)["q"].cuda()
+        g = torch.ones(d, dtype=torch.float32, device="cuda")
+        assert tvm.tvmattn_jvp_bwd_qknorm_workspace_bytes(x) == 0
+        row = torch.empty((B, H, N), dtype=torch.float32, device="cuda")
+        with pytest.raises(tvm.TvmattnError) as ei:
+            tvm.tvmattn_jvp_bwd_qknorm(x, x, x, x, g, g, EPS, x, x, x, x, x, x, x, x, row, row, x, x)
+        assert ei.value.status == -2
