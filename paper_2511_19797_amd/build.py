@@ -14,12 +14,12 @@ COMMON = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-inline-asm",  # the LDS-DMA asm names m0 on purpose
 ]
-# MFMA results straight into VGPRs (the score tiles are consumed by the VALU).  Not used for the
-# d > 96 instantiations, whose register pressure sends the compiler's AGPR rewrite pass astray.
+# MFMA results straight into VGPRs (the score tiles are consumed by the VALU).  Not used for the translation
+# units that hold only d > 96 instantiations (bwd_mfma_wide.hip, bwd_mfma_onesided2.hip), whose register
+# pressure sends the compiler's AGPR rewrite pass astray (more spills, 2 % slower).
 PER_FILE = {
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "bwd_mfma_onesided1.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "bwd_mfma_onesided2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_col_pipe.hip": ["-mllvm", "-enable-misched=false"],

@@ -1,17 +1,11 @@
-// Backward launchers for one upstream gradient (gTO only: the tangent path by itself), every head dim the matrix-core
-// path takes (see bwd_mfma_kernels.h for the kernels).
+// Backward launchers for one upstream gradient (gTO only: the tangent path by itself) at head dims above 96, where
+// the hand-scheduled kernels do not go (see bwd_mfma_kernels.h for the kernels; up to 96 it is bwd_*_pipe_tangent.hip).
 #include "bwd_mfma_kernels.h"
 
 namespace tvm {
 
 #define TVM_BY_HEAD_DIM(fn)                          \
   switch ((s.D + 15) / 16 * 16) {                    \
-    case 16: return fn<16, 32, 2>(s, a, st);          \
-    case 32: return fn<32, 32, 2>(s, a, st);          \
-    case 48: return fn<48, 64, 2>(s, a, st);          \
-    case 64: return fn<64, 64, 2>(s, a, st);          \
-    case 80: return fn<80, 96, 2>(s, a, st);          \
-    case 96: return fn<96, 96, 2>(s, a, st);          \
     case 112: return fn<112, 128, 2>(s, a, st);       \
     case 128: return fn<128, 128, 2>(s, a, st);       \
     default: return hipErrorNotSupported;            \
