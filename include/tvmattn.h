@@ -233,6 +233,45 @@ int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc,
                            void* workspace, size_t workspace_bytes,
                            void* hip_stream);
 
+/*
+ * Normalised adaptive-layer-norm modulation with tangent: the operand of ATTN and of MLP in the paper's block
+ * (Sec. "Semi-Lipschitz control", the equation for AdaLN(x, t); App. "Full Description of Normalization of
+ * Modulation").  With RMSNorm^- the RMSNorm without learnable parameters (v / sqrt(mean(v^2) + eps) over the C
+ * entries of a vector v):
+ *
+ *     y  = RMSNorm^-(x) o RMSNorm^-(a) + RMSNorm^-(b)
+ *     ty = its directional derivative along (tx, ta, tb)
+ *
+ *   in : x, tx           [B,T,C] dtype, contiguous: a token's features and their tangent
+ *        a, ta, b, tb    [B,C] float32, contiguous: scale and shift of the token's batch element, and tangents
+ *        eps             >= 0, finite
+ *   out: y, ty           [B,T,C] dtype
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_adaln_jvp_fwd_workspace_bytes(...) bytes.
+ * C must be a multiple of 16 bytes' worth of elements and at most 256 such chunks (2048 for bfloat16, 1024 for
+ * float32), B at most 65535; otherwise TVMATTN_UNSUPPORTED.  Two launches.  Arithmetic is float32.
+ */
+size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype);
+int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype,
+                          const void* x, const void* tx,
+                          const float* a, const float* ta, const float* b, const float* tb, float eps,
+                          void* y, void* ty,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of the above: the gradient of <gy,y> + <gty,ty> with respect to all six inputs.
+ *   in : x, tx, a, ta, b, tb, eps as given to the forward (nothing is saved); gy, gty [B,T,C] dtype
+ *   out: gx, gtx [B,T,C] dtype; ga, gta, gb, gtb [B,C] float32 (summed over the T tokens of their batch element)
+ *   workspace: at least tvmattn_adaln_jvp_bwd_workspace_bytes(...) bytes.
+ * Three launches; the sums over tokens use no atomics and are bitwise reproducible.
+ */
+size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype);
+int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype,
+                          const void* x, const void* tx,
+                          const float* a, const float* ta, const float* b, const float* tb, float eps,
+                          const void* gy, const void* gty,
+                          void* gx, void* gtx, float* ga, float* gta, float* gb, float* gtb,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

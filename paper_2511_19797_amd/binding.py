@@ -67,6 +67,14 @@ def lib():
         L.tvmattn_jvp_bwd_qknorm.restype = ctypes.c_int
         L.tvmattn_jvp_bwd_qknorm.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 21 +
                                              [ctypes.c_size_t, _P])
+        _I = ctypes.c_int
+        for fn in (L.tvmattn_adaln_jvp_fwd_workspace_bytes, L.tvmattn_adaln_jvp_bwd_workspace_bytes):
+            fn.restype = ctypes.c_size_t
+            fn.argtypes = [_I] * 4
+        L.tvmattn_adaln_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3 + [ctypes.c_size_t, _P]
+        L.tvmattn_adaln_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_adaln_jvp_bwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 9 + [ctypes.c_size_t, _P]
         _lib = L
     return _lib
 
@@ -273,4 +281,49 @@ def tvmattn_jvp_bwd_qknorm(q, tq, k, tk, gain_q, gain_k, eps, qn, tqn, kn, tkn, 
                                         to.data_ptr(), lse.data_ptr(), stats.data_ptr(), gO.data_ptr(), gTO.data_ptr(),
                                         *[t.data_ptr() for t in out], workspace.data_ptr(),
                                         workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def _adaln_args(x, tx, mods):
+    if x.dim() != 3 or not x.is_contiguous() or not x.is_cuda:
+        raise ValueError("expected contiguous [B,T,C] device tensors")
+    if tx.shape != x.shape or tx.dtype != x.dtype or not tx.is_contiguous():
+        raise ValueError("x and its tangent must agree in shape, dtype and layout")
+    B, T, C = x.shape
+    for m in mods:
+        if m.shape != (B, C) or m.dtype != torch.float32 or not m.is_contiguous() or m.device != x.device:
+            raise ValueError("scale, shift and their tangents must be contiguous float32 [B,C] tensors")
+    dt = TVMATTN_F32 if x.dtype == torch.float32 else TVMATTN_BF16 if x.dtype == torch.bfloat16 else None
+    if dt is None:
+        raise ValueError(f"unsupported dtype {x.dtype}")
+    return B, T, C, dt
+
+
+def tvmattn_adaln_jvp_fwd(x, tx, a, ta, b, tb, eps, out=None, workspace=None):
+    """Returns (y, ty): RMSNorm^-(x) * RMSNorm^-(a) + RMSNorm^-(b) and its tangent along (tx, ta, tb)."""
+    B, T, C, dt = _adaln_args(x, tx, (a, ta, b, tb))
+    y, ty = out if out is not None else (torch.empty_like(x), torch.empty_like(x))
+    need = int(lib().tvmattn_adaln_jvp_fwd_workspace_bytes(B, T, C, dt))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().tvmattn_adaln_jvp_fwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(), b.data_ptr(),
+                                       tb.data_ptr(), float(eps), y.data_ptr(), ty.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel(), _stream()))
+    return y, ty
+
+
+def tvmattn_adaln_jvp_bwd(x, tx, a, ta, b, tb, eps, gy, gty, out=None, workspace=None):
+    """Returns (gx, gtx, ga, gta, gb, gtb)."""
+    B, T, C, dt = _adaln_args(x, tx, (a, ta, b, tb))
+    _adaln_args(gy, gty, ())
+    if gy.shape != x.shape or gy.dtype != x.dtype:
+        raise ValueError("upstream gradients must look like x")
+    if out is None:
+        out = (torch.empty_like(x), torch.empty_like(x)) + tuple(torch.empty_like(a) for _ in range(4))
+    need = int(lib().tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, dt))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().tvmattn_adaln_jvp_bwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(), b.data_ptr(),
+                                       tb.data_ptr(), float(eps), gy.data_ptr(), gty.data_ptr(),
+                                       *[t.data_ptr() for t in out], workspace.data_ptr(), workspace.numel(), _stream()))
     return out

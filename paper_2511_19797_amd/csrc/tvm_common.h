@@ -99,4 +99,20 @@ constexpr int kNormMaxWg = 1024;     // workgroups per side at most (they stride
 hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st);
 hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st);
 
+
+// Normalised adaptive-layer-norm modulation with tangent (adaln.hip).
+struct AdalnArgs {
+  const void *x, *tx, *gy, *gty;    // [B,T,C] dtype, contiguous (gy, gty: backward only)
+  const float *a, *ta, *b, *tb;     // [B,C] float32
+  void *y, *ty;                     // forward: outputs; backward: gradients of x and tx
+  float* mod;                       // workspace [B][4][C]: the normalised a, its tangent, the normalised b, its tangent
+  float* part;                      // backward workspace [B][nwg][4][C]: per-workgroup sums over tokens
+  float *ga, *gta, *gb, *gtb;       // backward: gradients of a, ta, b, tb
+  int B, T, C, nwg;                 // nwg: workgroups per batch element
+  float eps;
+};
+bool adaln_supported(int C, int dtype);
+hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st);
+
 }  // namespace tvm

@@ -341,4 +341,95 @@ int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc, const void* q, const void* 
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
 
+// ---- normalised adaptive-layer-norm modulation with tangent
+namespace {
+int adaln_check(int B, int T, int C, int dtype, float eps) {
+  if (B < 1 || T < 1 || C < 1) return TVMATTN_INVALID_ARG;
+  if (dtype != TVMATTN_F32 && dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
+  if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
+  if (!tvm::adaln_supported(C, dtype) || (long long)B * T >= (1ll << 31) || B > 65535) return TVMATTN_UNSUPPORTED;
+  return TVMATTN_OK;
+}
+int adaln_wgs(int B, int T) {  // workgroups per batch element: four token rows each per pass, about 2048 in all
+  const int want = (T + 3) / 4, cap = 2048 / B > 1 ? 2048 / B : 1;
+  return want < cap ? want : cap;
+}
+size_t adaln_mod_bytes(int B, int C) { return pad256((size_t)B * 4 * C * sizeof(float)); }
+}  // namespace
+
+size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype) {
+  return adaln_check(B, T, C, dtype, 0.f) ? 0 : adaln_mod_bytes(B, C);
+}
+
+int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
+                          const float* b, const float* tb, float eps, void* y, void* ty, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  int rc = adaln_check(B, T, C, dtype, eps);
+  if (rc) return rc;
+  const void* const in[] = {x, tx, a, ta, b, tb};
+  void* const out[] = {y, ty, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  if (workspace_bytes < adaln_mod_bytes(B, C)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::AdalnArgs g{};
+  g.x = x;
+  g.tx = tx;
+  g.a = a;
+  g.ta = ta;
+  g.b = b;
+  g.tb = tb;
+  g.y = y;
+  g.ty = ty;
+  g.mod = static_cast<float*>(workspace);
+  g.B = B;
+  g.T = T;
+  g.C = C;
+  g.nwg = adaln_wgs(B, T);
+  g.eps = eps;
+  return tvm::launch_adaln_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
+                                                                                           : TVMATTN_LAUNCH_FAILED;
+}
+
+size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
+  if (adaln_check(B, T, C, dtype, 0.f)) return 0;
+  return adaln_mod_bytes(B, C) + pad256((size_t)B * adaln_wgs(B, T) * 4 * C * sizeof(float));
+}
+
+int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
+                          const float* b, const float* tb, float eps, const void* gy, const void* gty, void* gx,
+                          void* gtx, float* ga, float* gta, float* gb, float* gtb, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  int rc = adaln_check(B, T, C, dtype, eps);
+  if (rc) return rc;
+  const void* const in[] = {x, tx, a, ta, b, tb, gy, gty};
+  void* const out[] = {gx, gtx, ga, gta, gb, gtb, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  if (workspace_bytes < tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, dtype)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::AdalnArgs g{};
+  g.x = x;
+  g.tx = tx;
+  g.gy = gy;
+  g.gty = gty;
+  g.a = a;
+  g.ta = ta;
+  g.b = b;
+  g.tb = tb;
+  g.y = gx;
+  g.ty = gtx;
+  g.ga = ga;
+  g.gta = gta;
+  g.gb = gb;
+  g.gtb = gtb;
+  g.mod = static_cast<float*>(workspace);
+  g.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + adaln_mod_bytes(B, C));
+  g.B = B;
+  g.T = T;
+  g.C = C;
+  g.nwg = adaln_wgs(B, T);
+  g.eps = eps;
+  return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
+                                                                                           : TVMATTN_LAUNCH_FAILED;
+}
+
 }  // extern "C"

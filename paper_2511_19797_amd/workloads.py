@@ -123,6 +123,19 @@ def make_gains(w: Workload, seed: int):
     return tuple(torch.from_numpy((1.0 + 0.2 * rng.standard_normal(w.d)).astype(np.float32)) for _ in range(2))
 
 
+def make_adaln_inputs(B: int, T: int, C: int, dtype: str, seed: int):
+    """Inputs of the normalised AdaLN modulation: token features x with tangent tx and upstream gradients gy, gty
+    ([B,T,C], storage dtype), scale a and shift b per batch element with tangents ta, tb ([B,C] float32)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    out = {}
+    for name in ("x", "tx", "gy", "gty"):
+        out[name] = torch.from_numpy(rng.standard_normal((B, T, C), dtype=np.float32)).to(td).contiguous()
+    for name in ("a", "ta", "b", "tb"):
+        out[name] = torch.from_numpy(rng.standard_normal((B, C), dtype=np.float32)).contiguous()
+    return out
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()
