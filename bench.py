@@ -289,6 +289,43 @@ def qknorm(w, steps, seed=2024):
     return out
 
 
+def adaln(w, steps, seed=2024):
+    """The normalised AdaLN modulation with tangent (Sec. "Semi-Lipschitz control"; the operand of ATTN and MLP in
+    the paper's block) at the workload's token count and hidden size H*d, forward and backward, timed outside the
+    timed region of the headline figure.  Memory-bound: algorithmic bytes = every [B,T,C] tensor once (forward
+    reads 2 and writes 2, backward reads 4 and writes 2), against 8 TB/s."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    B, T, C = w.B, w.Mq, w.H * w.d
+    inp = wl.make_adaln_inputs(B, T, C, w.dtype, seed)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    del inp
+    args = [dev[n] for n in ("x", "tx", "a", "ta", "b", "tb")]
+    fo = (torch.empty_like(dev["x"]), torch.empty_like(dev["x"]))
+    bo = fo + tuple(torch.empty_like(dev["a"]) for _ in range(4))
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device="cuda")
+    one = float(B) * T * C * (2 if w.dtype == "bf16" else 4)
+    cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_adaln_jvp_fwd(*args, 1e-6, out=fo, workspace=ws)),
+             "bwd": (6.0 * one, lambda: tvm.tvmattn_adaln_jvp_bwd(*args, 1e-6, dev["gy"], dev["gty"], out=bo, workspace=ws))}
+    out = {"shape": {"B": B, "T": T, "C": C}}
+    for name, (nbytes, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
+                     "frac": gbs / 8000.0}
+    return out
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -369,6 +406,8 @@ def main():
     }
     out["one_sided"] = one_sided(w, args.steps)
     out["qknorm"] = qknorm(w, args.steps)
+    if w.dtype == "bf16" and (w.H * w.d) % 8 == 0 and w.H * w.d <= 2048:
+        out["adaln"] = adaln(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

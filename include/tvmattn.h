@@ -262,7 +262,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype,
  *   in : x, tx, a, ta, b, tb, eps as given to the forward (nothing is saved); gy, gty [B,T,C] dtype
  *   out: gx, gtx [B,T,C] dtype; ga, gta, gb, gtb [B,C] float32 (summed over the T tokens of their batch element)
  *   workspace: at least tvmattn_adaln_jvp_bwd_workspace_bytes(...) bytes.
- * Three launches; the sums over tokens use no atomics and are bitwise reproducible.
+ * Four launches; the sums over tokens use no atomics and are bitwise reproducible.
  */
 size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype);
 int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype,

@@ -10,7 +10,7 @@
 // Memory-bound: a wave per token row, 16 bytes per lane and tensor; the normalised modulation vectors are worked
 // out once per batch element by a small kernel and sit in LDS while a workgroup walks its tokens.  The sums over
 // tokens use no atomics: column sums per thread, per workgroup through LDS, one partial row per workgroup, added
-// in a fixed order by the kernel that finishes the gradients of a and b.
+// in a fixed order by a small kernel, and a last one finishes the gradients of a and b.
 #include "tvm_common.h"
 
 namespace tvm {
@@ -58,6 +58,19 @@ __device__ __forceinline__ void store16(T* p, const float (&in)[Chunk16<T>::VEC]
 #pragma unroll
   for (int e = 0; e < Chunk16<T>::VEC; ++e) c.v[e] = (T)in[e];
   *reinterpret_cast<uint4*>(p) = __builtin_bit_cast(uint4, c);
+}
+
+// VEC consecutive floats from LDS at a 16-byte aligned address, as 16-byte reads.
+template <int VEC>
+__device__ __forceinline__ void lds_vec(float (&out)[VEC], const float* p) {
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q) {
+    const float4 v = reinterpret_cast<const float4*>(p)[q];
+    out[4 * q] = v.x;
+    out[4 * q + 1] = v.y;
+    out[4 * q + 2] = v.z;
+    out[4 * q + 3] = v.w;
+  }
 }
 
 // Sum over the workgroup, the same bits in every thread: waves by lane exchange, then the four waves in order.
@@ -135,13 +148,16 @@ __global__ __launch_bounds__(kNT) void adaln_fwd_kernel(AdalnArgs a) {
     for (int i = 0; i < MAXC; ++i) {
       const int c0 = (lane + 64 * i) * VEC;
       if (c0 >= a.C) continue;
-      float y[VEC], ty[VEC];
+      float y[VEC], ty[VEC], ah[VEC], tah[VEC], bh[VEC], tbh[VEC];
+      lds_vec<VEC>(ah, lds + c0);
+      lds_vec<VEC>(tah, lds + a.C + c0);
+      lds_vec<VEC>(bh, lds + 2 * a.C + c0);
+      lds_vec<VEC>(tbh, lds + 3 * a.C + c0);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         const float xh = x[i][e] * r, txh = tx[i][e] * r - x[i][e] * r3m;
-        const float ah = lds[c0 + e], tah = lds[a.C + c0 + e], bh = lds[2 * a.C + c0 + e], tbh = lds[3 * a.C + c0 + e];
-        y[e] = fmaf(xh, ah, bh);
-        ty[e] = fmaf(txh, ah, fmaf(xh, tah, tbh));
+        y[e] = fmaf(xh, ah[e], bh[e]);
+        ty[e] = fmaf(txh, ah[e], fmaf(xh, tah[e], tbh[e]));
       }
       store16<T>(yp + c0, y);
       store16<T>(typ + c0, ty);
@@ -186,15 +202,16 @@ __global__ __launch_bounds__(kNT) void adaln_bwd_kernel(AdalnArgs a) {
     for (int i = 0; i < MAXC; ++i) {
       const int c0 = (lane + 64 * i) * VEC;
       const int cl = c0 < a.C ? c0 : 0;
-      float x[VEC], tx[VEC], gy[VEC], gty[VEC];
+      float x[VEC], tx[VEC], gy[VEC], gty[VEC], ah[VEC], tah[VEC];
       widen16<T>(x, rx[i]);
       widen16<T>(tx, rtx[i]);
       widen16<T>(gy, rgy[i]);
       widen16<T>(gty, rgt[i]);
+      lds_vec<VEC>(ah, lds + cl);
+      lds_vec<VEC>(tah, lds + a.C + cl);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float ah = lds[cl + e], tah = lds[a.C + cl + e];
-        const float u = fmaf(gy[e], ah, gty[e] * tah), w = gty[e] * ah;
+        const float u = fmaf(gy[e], ah[e], gty[e] * tah[e]), w = gty[e] * ah[e];
         sxx = fmaf(x[e], x[e], sxx);
         sxt = fmaf(x[e], tx[e], sxt);
         sA = fmaf(u, x[e], sA);
@@ -217,15 +234,16 @@ __global__ __launch_bounds__(kNT) void adaln_bwd_kernel(AdalnArgs a) {
     for (int i = 0; i < MAXC; ++i) {
       const int c0 = (lane + 64 * i) * VEC;
       if (c0 >= a.C) continue;
-      float gx[VEC], gtx[VEC], x[VEC], tx[VEC], gy[VEC], gty[VEC];
+      float gx[VEC], gtx[VEC], x[VEC], tx[VEC], gy[VEC], gty[VEC], ah[VEC], tah[VEC];
       widen16<T>(x, rx[i]);
       widen16<T>(tx, rtx[i]);
       widen16<T>(gy, rgy[i]);
       widen16<T>(gty, rgt[i]);
+      lds_vec<VEC>(ah, lds + c0);
+      lds_vec<VEC>(tah, lds + a.C + c0);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float ah = lds[c0 + e], tah = lds[a.C + c0 + e];
-        const float u = fmaf(gy[e], ah, gty[e] * tah), w = gty[e] * ah;
+        const float u = fmaf(gy[e], ah[e], gty[e] * tah[e]), w = gty[e] * ah[e];
         const float xh = x[e] * r, txh = tx[e] * r - x[e] * r3m;
         gtx[e] = r * w - kB * x[e];
         gx[e] = r * u - r3m * w - kB * tx[e] + kx * x[e];
@@ -262,25 +280,35 @@ __global__ __launch_bounds__(kNT) void adaln_bwd_kernel(AdalnArgs a) {
   for (int c = tid; c < 4 * a.C; c += kNT) part[c] = sums[c];
 }
 
-// Per batch element: adds the partial rows in order, then RMSNorm^- backward for a (from g_ah, g_tah) and for b.
+// gsum[b][0..3][C] (in place of mod, which nobody reads any more) = the partial rows of batch element b added in
+// order: a thread per column, four loads in flight.
+__global__ __launch_bounds__(kNT) void adaln_sum_kernel(AdalnArgs a) {
+  const int b = blockIdx.y, c = blockIdx.x * kNT + threadIdx.x;
+  if (c >= 4 * a.C) return;
+  const float* part = a.part + (long long)b * a.nwg * 4 * a.C + c;
+  const long long stride = (long long)4 * a.C;
+  float s = 0.f;
+  int w = 0;
+  for (; w + 3 < a.nwg; w += 4) {
+    const float v0 = part[w * stride], v1 = part[(w + 1) * stride], v2 = part[(w + 2) * stride], v3 = part[(w + 3) * stride];
+    s = (((s + v0) + v1) + v2) + v3;
+  }
+  for (; w < a.nwg; ++w) s += part[w * stride];
+  a.mod[(long long)b * 4 * a.C + c] = s;
+}
+
+// Per batch element: RMSNorm^- backward for a (from the sums g_ah, g_tah) and for b (from g_bh, g_tbh).
 __global__ __launch_bounds__(kNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
-  extern __shared__ float lds[];  // g_ah, g_tah, g_bh, g_tbh: 4 x C floats
   __shared__ float red4[kWaves];
   const int b = blockIdx.x, tid = threadIdx.x;
-  const float* part = a.part + (long long)b * a.nwg * 4 * a.C;
-  for (int c = tid; c < 4 * a.C; c += kNT) {
-    float s = 0.f;
-    for (int w = 0; w < a.nwg; ++w) s += part[(long long)w * 4 * a.C + c];
-    lds[c] = s;
-  }
-  __syncthreads();
+  const float* gsum = a.mod + (long long)b * 4 * a.C;
   const long long o = (long long)b * a.C;
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
     const float* v = (which ? a.b : a.a) + o;
     const float* tv = (which ? a.tb : a.ta) + o;
-    const float* u = lds + (which ? 2 : 0) * a.C;   // gradient of the normalised vector
-    const float* w = u + a.C;                        // ... of its tangent
+    const float* u = gsum + (which ? 2 : 0) * a.C;   // gradient of the normalised vector
+    const float* w = u + a.C;                         // ... of its tangent
     float* gv = (which ? a.gb : a.ga) + o;
     float* gtv = (which ? a.gtb : a.gta) + o;
     float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
@@ -354,7 +382,10 @@ hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st) {
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(a.B), dim3(kNT), (size_t)4 * a.C * sizeof(float), st, a);
+  hipLaunchKernelGGL(adaln_sum_kernel, dim3((4 * a.C + kNT - 1) / kNT, a.B), dim3(kNT), 0, st, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(a.B), dim3(kNT), 0, st, a);
   return hipGetLastError();
 }
 

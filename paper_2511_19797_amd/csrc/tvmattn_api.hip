@@ -350,10 +350,13 @@ int adaln_check(int B, int T, int C, int dtype, float eps) {
   if (!tvm::adaln_supported(C, dtype) || (long long)B * T >= (1ll << 31) || B > 65535) return TVMATTN_UNSUPPORTED;
   return TVMATTN_OK;
 }
-int adaln_wgs(int B, int T) {  // workgroups per batch element: four token rows each per pass, about 2048 in all
-  const int want = (T + 3) / 4, cap = 2048 / B > 1 ? 2048 / B : 1;
+// Workgroups per batch element: four token rows each per pass, about `total` in all (each loads its batch element's
+// modulation into LDS once; a backward one leaves a partial row of column sums and runs one wave per SIMD).
+int adaln_wgs(int B, int T, int total) {
+  const int want = (T + 3) / 4, cap = total / B > 1 ? total / B : 1;
   return want < cap ? want : cap;
 }
+constexpr int kAdalnFwdWgs = 1024, kAdalnBwdWgs = 512;
 size_t adaln_mod_bytes(int B, int C) { return pad256((size_t)B * 4 * C * sizeof(float)); }
 }  // namespace
 
@@ -384,7 +387,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = adaln_wgs(B, T);
+  g.nwg = adaln_wgs(B, T, kAdalnFwdWgs);
   g.eps = eps;
   return tvm::launch_adaln_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
@@ -392,7 +395,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
 
 size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
   if (adaln_check(B, T, C, dtype, 0.f)) return 0;
-  return adaln_mod_bytes(B, C) + pad256((size_t)B * adaln_wgs(B, T) * 4 * C * sizeof(float));
+  return adaln_mod_bytes(B, C) + pad256((size_t)B * adaln_wgs(B, T, kAdalnBwdWgs) * 4 * C * sizeof(float));
 }
 
 int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
@@ -426,7 +429,7 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = adaln_wgs(B, T);
+  g.nwg = adaln_wgs(B, T, kAdalnBwdWgs);
   g.eps = eps;
   return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;

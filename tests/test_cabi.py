@@ -208,3 +208,40 @@ def test_fused_backward_argument_rules(L):
         dd = desc(**kw)
         assert L.tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(dd)) == 0
         assert call(head, rest, ws=1 << 30, dd=dd) == -2
+
+
+def test_adaln_argument_rules(L):
+    """The AdaLN modulation entry points validate before anything is launched; status -3 (workspace too small)
+    shows that the shape and pointer checks were passed."""
+    I, P, F, Z = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+    L.tvmattn_adaln_jvp_fwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 3 + [Z, P]
+    L.tvmattn_adaln_jvp_bwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 9 + [Z, P]
+    for fn in (L.tvmattn_adaln_jvp_fwd_workspace_bytes, L.tvmattn_adaln_jvp_bwd_workspace_bytes):
+        fn.restype, fn.argtypes = Z, [I] * 4
+    B, T, C = 4, 100, 1152
+    nf = L.tvmattn_adaln_jvp_fwd_workspace_bytes(B, T, C, 1)
+    nb = L.tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, 1)
+    assert nf >= B * 4 * C * 4 and nf % 256 == 0 and nb > nf
+    for bad in ((0, T, C, 1), (B, 0, C, 1), (B, T, 0, 1), (B, T, C, 5), (B, T, 1156, 1), (B, T, 2056, 1), (B, T, 1028, 0),
+                (70000, 1, 64, 1)):
+        assert L.tvmattn_adaln_jvp_fwd_workspace_bytes(*bad) == 0 and L.tvmattn_adaln_jvp_bwd_workspace_bytes(*bad) == 0
+    ins = [0x1000 * (i + 1) for i in range(6)]
+    fouts = [0x1000 * (i + 7) for i in range(3)]
+    fwd = lambda i, o, ws=nf - 1, eps=1e-6, shape=(B, T, C, 1): L.tvmattn_adaln_jvp_fwd(*shape, *i, eps, *o, ws, None)
+    assert fwd(ins, fouts) == -3
+    assert fwd(ins, fouts, eps=-1.0) == -1 and fwd(ins, fouts, shape=(B, T, 12, 1)) == -2
+    assert fwd(ins, fouts, shape=(B, T, C, 3)) == -2 and fwd(ins, fouts, shape=(B, -1, C, 1)) == -1
+    for k in range(6):
+        p = list(ins)
+        p[k] = None
+        assert fwd(p, fouts) == -1
+    p = list(fouts)
+    p[1] = p[0]
+    assert fwd(ins, p) == -1
+    brest = [0x1000 * (i + 7) for i in range(9)]   # gy, gty, six outputs, workspace
+    bwd = lambda i, r, ws=nb - 1: L.tvmattn_adaln_jvp_bwd(B, T, C, 1, *i, 1e-6, *r, ws, None)
+    assert bwd(ins, brest) == -3
+    for k in range(9):
+        p = list(brest)
+        p[k] = None
+        assert bwd(ins, p) == -1
