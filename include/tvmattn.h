@@ -246,9 +246,10 @@ int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc,
  *        a, ta, b, tb    [B,C] float32, contiguous: scale and shift of the token's batch element, and tangents
  *        eps             >= 0, finite
  *   out: y, ty           [B,T,C] dtype
- *   workspace: device memory, 16-byte aligned, at least tvmattn_adaln_jvp_fwd_workspace_bytes(...) bytes.
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_adaln_jvp_fwd_workspace_bytes(...) bytes (a small
+ *              constant for every supported shape, 0 for an unsupported one; the forward leaves it untouched).
  * C must be a multiple of 16 bytes' worth of elements and at most 256 such chunks (2048 for bfloat16, 1024 for
- * float32), B at most 65535; otherwise TVMATTN_UNSUPPORTED.  Two launches.  Arithmetic is float32.
+ * float32), B at most 65535; otherwise TVMATTN_UNSUPPORTED.  One launch.  Arithmetic is float32.
  */
 size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype);
 int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype,
@@ -262,7 +263,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype,
  *   in : x, tx, a, ta, b, tb, eps as given to the forward (nothing is saved); gy, gty [B,T,C] dtype
  *   out: gx, gtx [B,T,C] dtype; ga, gta, gb, gtb [B,C] float32 (summed over the T tokens of their batch element)
  *   workspace: at least tvmattn_adaln_jvp_bwd_workspace_bytes(...) bytes.
- * Four launches; the sums over tokens use no atomics and are bitwise reproducible.
+ * Two launches; the sums over tokens use no atomics and are bitwise reproducible.
  */
 size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype);
 int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype,

@@ -7,208 +7,239 @@
 // Backward of <gy, y> + <gty, ty>:  g_xh = gy ah + gty tah,  g_txh = gty ah, then RMSNorm^- backward per token (the
 // closed form of qknorm.hip with unit gain);  g_ah = sum_t gy xh + gty txh,  g_tah = sum_t gty xh,  g_bh = sum_t gy,
 // g_tbh = sum_t gty, then RMSNorm^- backward per batch element for a and b.
-// Memory-bound: a wave per token row, 16 bytes per lane and tensor; the normalised modulation vectors are worked
-// out once per batch element by a small kernel and sit in LDS while a workgroup walks its tokens.  The sums over
-// tokens use no atomics: column sums per thread, per workgroup through LDS, one partial row per workgroup, added
-// in a fixed order by a small kernel, and a last one finishes the gradients of a and b.
+// Memory-bound.  A thread owns one 16-byte chunk of columns for the whole kernel: a workgroup is as wide as a row
+// (64 to 256 threads), works out its batch element's normalised modulation for its own columns once, into
+// registers, and then walks its token rows R at a time (all their loads in flight together, one barrier per R rows
+// for the row sums).  The sums over tokens are then per-thread registers: one partial row per workgroup straight
+// from registers, no atomics, added in a fixed order by a second, small kernel that also finishes the gradients of
+// a and b.
 #include "tvm_common.h"
 
 namespace tvm {
 namespace {
 
-constexpr int kNT = 256;
-constexpr int kWaves = kNT / 64;
-
+// A thread's share of a row: 16 bytes, VEC = 4 columns of float32 or 8 of bfloat16.  (Tried: 8 bytes of bfloat16 per
+// thread, i.e. half the registers and twice the waves: slower, forward and backward; what counts is the number of
+// bytes a compute unit has in flight.)
 template <typename T>
-struct alignas(16) Chunk16 {
+struct alignas(16) Chunk {
   static constexpr int VEC = 16 / sizeof(T);
   T v[VEC];
 };
+template <typename T> using Raw = uint4;
+// Nothing is done to the bytes on the way in (arithmetic right behind a load makes the compiler wait for it there
+// and then): idle threads read a valid address like the others and drop their share of the sums instead.
 template <typename T>
-__device__ __forceinline__ void load16(float (&out)[Chunk16<T>::VEC], const T* p, bool live) {
-  uint4 raw = *reinterpret_cast<const uint4*>(p);  // callers pass a valid address also for idle lanes
-  raw.x = live ? raw.x : 0u;
-  raw.y = live ? raw.y : 0u;
-  raw.z = live ? raw.z : 0u;
-  raw.w = live ? raw.w : 0u;
-  const Chunk16<T> c = __builtin_bit_cast(Chunk16<T>, raw);
+__device__ __forceinline__ Raw<T> load_raw(const T* p) {
+  return *reinterpret_cast<const Raw<T>*>(p);
+}
+template <typename T>
+__device__ __forceinline__ void widen(float (&out)[Chunk<T>::VEC], const Raw<T>& raw) {
+  const Chunk<T> c = __builtin_bit_cast(Chunk<T>, raw);
 #pragma unroll
-  for (int e = 0; e < Chunk16<T>::VEC; ++e) out[e] = (float)c.v[e];
+  for (int e = 0; e < Chunk<T>::VEC; ++e) out[e] = (float)c.v[e];
 }
-// The same in two steps, for kernels that keep the 16 bytes as loaded and widen them where they are used (half the
-// registers for bfloat16).
+// The bytes as a value the compiler knows nothing about: what was widened from them before is not kept in
+// registers across this point but widened again (half the registers for bfloat16).
+__device__ __forceinline__ void forget(uint4& raw) { asm volatile("" : "+v"(raw.x), "+v"(raw.y), "+v"(raw.z), "+v"(raw.w)); }
 template <typename T>
-__device__ __forceinline__ uint4 load16_raw(const T* p, bool live) {
-  uint4 raw = *reinterpret_cast<const uint4*>(p);
-  raw.x = live ? raw.x : 0u;
-  raw.y = live ? raw.y : 0u;
-  raw.z = live ? raw.z : 0u;
-  raw.w = live ? raw.w : 0u;
-  return raw;
-}
-template <typename T>
-__device__ __forceinline__ void widen16(float (&out)[Chunk16<T>::VEC], const uint4& raw) {
-  const Chunk16<T> c = __builtin_bit_cast(Chunk16<T>, raw);
+__device__ __forceinline__ void store_row(T* p, const float (&in)[Chunk<T>::VEC]) {
+  Chunk<T> c;
 #pragma unroll
-  for (int e = 0; e < Chunk16<T>::VEC; ++e) out[e] = (float)c.v[e];
+  for (int e = 0; e < Chunk<T>::VEC; ++e) c.v[e] = (T)in[e];
+  *reinterpret_cast<Raw<T>*>(p) = __builtin_bit_cast(Raw<T>, c);
 }
-template <typename T>
-__device__ __forceinline__ void store16(T* p, const float (&in)[Chunk16<T>::VEC]) {
-  Chunk16<T> c;
-#pragma unroll
-  for (int e = 0; e < Chunk16<T>::VEC; ++e) c.v[e] = (T)in[e];
-  *reinterpret_cast<uint4*>(p) = __builtin_bit_cast(uint4, c);
-}
-
-// VEC consecutive floats from LDS at a 16-byte aligned address, as 16-byte reads.
+// VEC consecutive floats at a 16-byte aligned address (zeros for idle lanes), and back.
 template <int VEC>
-__device__ __forceinline__ void lds_vec(float (&out)[VEC], const float* p) {
+__device__ __forceinline__ void load_f32(float (&out)[VEC], const float* p, bool live) {
 #pragma unroll
   for (int q = 0; q < VEC / 4; ++q) {
     const float4 v = reinterpret_cast<const float4*>(p)[q];
-    out[4 * q] = v.x;
-    out[4 * q + 1] = v.y;
-    out[4 * q + 2] = v.z;
-    out[4 * q + 3] = v.w;
+    out[4 * q] = live ? v.x : 0.f;
+    out[4 * q + 1] = live ? v.y : 0.f;
+    out[4 * q + 2] = live ? v.z : 0.f;
+    out[4 * q + 3] = live ? v.w : 0.f;
   }
 }
-
-// Sum over the workgroup, the same bits in every thread: waves by lane exchange, then the four waves in order.
-__device__ __forceinline__ float block_sum(float v, float* red4, int tid) {
-  v = wave_sum(v);
-  __syncthreads();  // red4 may still be read from the previous call
-  if ((tid & 63) == 0) red4[tid >> 6] = v;
-  __syncthreads();
-  return ((red4[0] + red4[1]) + red4[2]) + red4[3];
-}
-
-// RMSNorm^- with tangent of the C entries at v, tv (float32) into out, tout (float32): one workgroup.
-__device__ __forceinline__ void norm_row_block(const float* v, const float* tv, float* out, float* tout, int C, float eps,
-                                               float* red4, int tid) {
-  float sxx = 0.f, sxt = 0.f;
-  for (int c = tid; c < C; c += kNT) {
-    sxx = fmaf(v[c], v[c], sxx);
-    sxt = fmaf(v[c], tv[c], sxt);
-  }
-  sxx = block_sum(sxx, red4, tid);
-  sxt = block_sum(sxt, red4, tid);
-  const float r = 1.0f / sqrtf(sxx / (float)C + eps), r3m = r * r * r * (sxt / (float)C);
-  for (int c = tid; c < C; c += kNT) {
-    out[c] = v[c] * r;
-    tout[c] = tv[c] * r - v[c] * r3m;
-  }
-}
-
-// mod[b][0..3][C] = ah, tah, bh, tbh of batch element b.
-__global__ __launch_bounds__(kNT) void adaln_mod_kernel(AdalnArgs a) {
-  __shared__ float red4[kWaves];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const long long o = (long long)b * a.C;
-  float* m = a.mod + (long long)b * 4 * a.C;
-  norm_row_block(a.a + o, a.ta + o, m, m + a.C, a.C, a.eps, red4, tid);
-  norm_row_block(a.b + o, a.tb + o, m + 2 * a.C, m + 3 * a.C, a.C, a.eps, red4, tid);
-}
-
-// MAXC: 16-byte chunks per lane (64 lanes x MAXC x VEC >= C; C is a multiple of VEC).
-template <typename T, int MAXC>
-__global__ __launch_bounds__(kNT) void adaln_fwd_kernel(AdalnArgs a) {
-  constexpr int VEC = Chunk16<T>::VEC;
-  extern __shared__ float lds[];  // ah, tah, bh, tbh: 4 x C floats
-  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* m = a.mod + (long long)b * 4 * a.C;
-  for (int c = tid; c < 4 * a.C; c += kNT) lds[c] = m[c];
-  __syncthreads();
-  const float invc = 1.0f / (float)a.C;
-  for (int t = blockIdx.x * kWaves + wave; t < a.T; t += gridDim.x * kWaves) {
-    const long long off = ((long long)b * a.T + t) * a.C;
-    const T* xp = static_cast<const T*>(a.x) + off;
-    const T* tp = static_cast<const T*>(a.tx) + off;
-    float x[MAXC][VEC], tx[MAXC][VEC];
-    float sxx = 0.f, sxt = 0.f;
+template <int VEC>
+__device__ __forceinline__ void store_f32(float* p, const float (&in)[VEC]) {
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c0 = (lane + 64 * i) * VEC;
-      const bool live = c0 < a.C;
-      load16<T>(x[i], xp + (live ? c0 : 0), live);
-      load16<T>(tx[i], tp + (live ? c0 : 0), live);
+  for (int q = 0; q < VEC / 4; ++q)
+    reinterpret_cast<float4*>(p)[q] = make_float4(in[4 * q], in[4 * q + 1], in[4 * q + 2], in[4 * q + 3]);
+}
+
+// Sum over the wave with data-parallel-primitive moves only (no LDS traffic): a butterfly inside each row of 16
+// lanes, then row 0 into row 1 and row 2 into row 3, rows 0-1 into rows 2-3; lane 63 holds the whole and is read
+// into a scalar, so every lane gets the same bits.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_from(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROWS, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+  x += dpp_from<0xB1, 0xf>(x);   // quad_perm [1,0,3,2]
+  x += dpp_from<0x4E, 0xf>(x);   // quad_perm [2,3,0,1]
+  x += dpp_from<0x141, 0xf>(x);  // row_half_mirror
+  x += dpp_from<0x140, 0xf>(x);  // row_mirror
+  x += dpp_from<0x142, 0xa>(x);  // lane 15 of the row before, into rows 1 and 3 (the others add 0)
+  x += dpp_from<0x143, 0xc>(x);  // lane 31, into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// K sums over the workgroup's NW waves, the same bits in every thread: waves by lane exchange, then the waves in
+// order through `red` (NW x K floats).  One barrier: consecutive calls must alternate between two such buffers.
+template <int NW, int K>
+__device__ __forceinline__ void wg_sums(float (&s)[K], float* red, int wave, int lane) {
+#pragma unroll
+  for (int k = 0; k < K; ++k) s[k] = wave_sum_dpp(s[k]);
+  if constexpr (NW > 1) {
+    if (lane == 0) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) red[wave * K + k] = s[k];
     }
+    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i)
+    for (int k = 0; k < K; ++k) {
+      float t = red[k];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += red[w * K + k];
+      s[k] = t;
+    }
+  }
+}
+
+// RMSNorm^- with tangent of the C entries at v, tv (float32), the thread's own VEC columns of it (at c0) into out, tout.
+template <int NW, int VEC>
+__device__ __forceinline__ void norm_own_chunk(const float* v, const float* tv, int c0, bool live, int C, float eps,
+                                               float (&out)[VEC], float (&tout)[VEC], float* red, int wave, int lane) {
+  float x[VEC], t[VEC];
+  load_f32<VEC>(x, v + c0, live);
+  load_f32<VEC>(t, tv + c0, live);
+  float s[2] = {0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    s[0] = fmaf(x[e], x[e], s[0]);
+    s[1] = fmaf(x[e], t[e], s[1]);
+  }
+  wg_sums<NW, 2>(s, red, wave, lane);
+  const float r = 1.0f / sqrtf(s[0] / (float)C + eps), r3m = r * r * r * (s[1] / (float)C);
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    out[e] = x[e] * r;
+    tout[e] = t[e] * r - x[e] * r3m;
+  }
+}
+
+// NW waves to a row (64 NW x VEC >= C; C is a multiple of VEC), R token rows per pass.
+template <typename T, int NW, int R>
+__global__ __launch_bounds__(64 * NW) void adaln_fwd_kernel(AdalnArgs a) {
+  constexpr int VEC = Chunk<T>::VEC, K = 2 * R;
+  __shared__ float red[2 * NW * K];
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool live = tid * VEC < a.C;
+  const int c0 = live ? tid * VEC : 0;
+  float ah[VEC], tah[VEC], bh[VEC], tbh[VEC];
+  const long long mo = (long long)b * a.C;
+  norm_own_chunk<NW, VEC>(a.a + mo, a.ta + mo, c0, live, a.C, a.eps, ah, tah, red, wave, lane);
+  norm_own_chunk<NW, VEC>(a.b + mo, a.tb + mo, c0, live, a.C, a.eps, bh, tbh, red + NW * K, wave, lane);
+  const float invc = 1.0f / (float)a.C;
+  const T* xb = static_cast<const T*>(a.x) + (long long)b * a.T * a.C + c0;
+  const T* tb_ = static_cast<const T*>(a.tx) + (long long)b * a.T * a.C + c0;
+  T* yb = static_cast<T*>(a.y) + (long long)b * a.T * a.C + c0;
+  T* tyb = static_cast<T*>(a.ty) + (long long)b * a.T * a.C + c0;
+  int par = 0;
+  for (int t0 = blockIdx.x * R; t0 < a.T; t0 += gridDim.x * R, par ^= 1) {
+    Raw<T> rx[R], rt[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {  // rows beyond the last one are read as the last one and not stored
+      const long long off = (long long)(t0 + j < a.T ? t0 + j : a.T - 1) * a.C;
+      rx[j] = load_raw<T>(xb + off);
+      rt[j] = load_raw<T>(tb_ + off);
+    }
+    float s[K];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      float x[VEC], tx[VEC];
+      widen<T>(x, rx[j]);
+      widen<T>(tx, rt[j]);
+      float sxx = 0.f, sxt = 0.f;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        sxx = fmaf(x[i][e], x[i][e], sxx);
-        sxt = fmaf(x[i][e], tx[i][e], sxt);
+        sxx = fmaf(x[e], x[e], sxx);
+        sxt = fmaf(x[e], tx[e], sxt);
       }
-    sxx = wave_sum(sxx);
-    sxt = wave_sum(sxt);
-    const float r = 1.0f / sqrtf(sxx * invc + a.eps), r3m = r * r * r * (sxt * invc);
-    T* yp = static_cast<T*>(a.y) + off;
-    T* typ = static_cast<T*>(a.ty) + off;
+      s[2 * j] = live ? sxx : 0.f;
+      s[2 * j + 1] = live ? sxt : 0.f;
+    }
+    wg_sums<NW, K>(s, red + par * NW * K, wave, lane);
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c0 = (lane + 64 * i) * VEC;
-      if (c0 >= a.C) continue;
-      float y[VEC], ty[VEC], ah[VEC], tah[VEC], bh[VEC], tbh[VEC];
-      lds_vec<VEC>(ah, lds + c0);
-      lds_vec<VEC>(tah, lds + a.C + c0);
-      lds_vec<VEC>(bh, lds + 2 * a.C + c0);
-      lds_vec<VEC>(tbh, lds + 3 * a.C + c0);
+    for (int j = 0; j < R; ++j) {
+      if (!live || t0 + j >= a.T) continue;
+      const float r = 1.0f / sqrtf(s[2 * j] * invc + a.eps), r3m = r * r * r * (s[2 * j + 1] * invc);
+      float x[VEC], tx[VEC], y[VEC], ty[VEC];
+      forget(rx[j]);
+      forget(rt[j]);
+      widen<T>(x, rx[j]);
+      widen<T>(tx, rt[j]);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        const float xh = x[i][e] * r, txh = tx[i][e] * r - x[i][e] * r3m;
+        const float xh = x[e] * r, txh = tx[e] * r - x[e] * r3m;
         y[e] = fmaf(xh, ah[e], bh[e]);
         ty[e] = fmaf(txh, ah[e], fmaf(xh, tah[e], tbh[e]));
       }
-      store16<T>(yp + c0, y);
-      store16<T>(typ + c0, ty);
+      const long long off = (long long)(t0 + j) * a.C;
+      store_row<T>(yb + off, y);
+      store_row<T>(tyb + off, ty);
     }
   }
 }
 
-template <typename T, int MAXC>
-__global__ __launch_bounds__(kNT) void adaln_bwd_kernel(AdalnArgs a) {
-  constexpr int VEC = Chunk16<T>::VEC;
-  extern __shared__ float lds[];  // ah, tah (2 x C floats), then the workgroup's column sums (4 x C floats)
+constexpr int kTotalBwd = 512;
+template <typename T, int NW, int R>
+__global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
+  constexpr int VEC = Chunk<T>::VEC, K = 5 * R;
+  __shared__ float red[2 * NW * K];
   const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* m = a.mod + (long long)b * 4 * a.C;
-  for (int c = tid; c < 2 * a.C; c += kNT) lds[c] = m[c];
-  __syncthreads();
+  const bool live = tid * VEC < a.C;
+  const int c0 = live ? tid * VEC : 0;
+  float ah[VEC], tah[VEC];
+  const long long mo = (long long)b * a.C;
+  norm_own_chunk<NW, VEC>(a.a + mo, a.ta + mo, c0, live, a.C, a.eps, ah, tah, red + NW * K, wave, lane);
   const float invc = 1.0f / (float)a.C;
-  float pa[MAXC][VEC], pta[MAXC][VEC], pb[MAXC][VEC], ptb[MAXC][VEC];  // column sums over this wave's tokens
+  const long long bo = (long long)b * a.T * a.C + c0;
+  const T* xb = static_cast<const T*>(a.x) + bo;
+  const T* tb_ = static_cast<const T*>(a.tx) + bo;
+  const T* gyb = static_cast<const T*>(a.gy) + bo;
+  const T* gtb_ = static_cast<const T*>(a.gty) + bo;
+  T* gxb = static_cast<T*>(a.y) + bo;
+  T* gtxb = static_cast<T*>(a.ty) + bo;
+  float pa[VEC], pta[VEC], pb[VEC], ptb[VEC];  // this thread's columns summed over the workgroup's tokens
 #pragma unroll
-  for (int i = 0; i < MAXC; ++i)
+  for (int e = 0; e < VEC; ++e) pa[e] = pta[e] = pb[e] = ptb[e] = 0.f;
+  struct Rows {
+    Raw<T> x[R], tx[R], gy[R], gty[R];  // as loaded; widened where used
+  };
+  // rows beyond the last one are read as the last one and take no further part
+  auto load = [&](Rows& q, int t0) {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) pa[i][e] = pta[i][e] = pb[i][e] = ptb[i][e] = 0.f;
-  for (int t = blockIdx.x * kWaves + wave; t < a.T; t += gridDim.x * kWaves) {
-    const long long off = ((long long)b * a.T + t) * a.C;
-    const T* xp = static_cast<const T*>(a.x) + off;
-    const T* tp = static_cast<const T*>(a.tx) + off;
-    const T* gyp = static_cast<const T*>(a.gy) + off;
-    const T* gtp = static_cast<const T*>(a.gty) + off;
-    uint4 rx[MAXC], rtx[MAXC], rgy[MAXC], rgt[MAXC];  // as loaded; widened where used
-#pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c0 = (lane + 64 * i) * VEC;
-      const bool live = c0 < a.C;
-      const int cl = live ? c0 : 0;
-      rx[i] = load16_raw<T>(xp + cl, live);
-      rtx[i] = load16_raw<T>(tp + cl, live);
-      rgy[i] = load16_raw<T>(gyp + cl, live);
-      rgt[i] = load16_raw<T>(gtp + cl, live);
+    for (int j = 0; j < R; ++j) {
+      const long long off = (long long)(t0 + j < a.T ? t0 + j : a.T - 1) * a.C;
+      q.x[j] = load_raw<T>(xb + off);
+      q.tx[j] = load_raw<T>(tb_ + off);
+      q.gy[j] = load_raw<T>(gyb + off);
+      q.gty[j] = load_raw<T>(gtb_ + off);
     }
+  };
+  auto pass = [&](Rows& q, int t0, int par) {
     // u = gy ah + gty tah and w = gty ah flow back into the normalised token and its tangent
-    float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
+    float s[K];
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c0 = (lane + 64 * i) * VEC;
-      const int cl = c0 < a.C ? c0 : 0;
-      float x[VEC], tx[VEC], gy[VEC], gty[VEC], ah[VEC], tah[VEC];
-      widen16<T>(x, rx[i]);
-      widen16<T>(tx, rtx[i]);
-      widen16<T>(gy, rgy[i]);
-      widen16<T>(gty, rgt[i]);
-      lds_vec<VEC>(ah, lds + cl);
-      lds_vec<VEC>(tah, lds + a.C + cl);
+    for (int j = 0; j < R; ++j) {
+      float x[VEC], tx[VEC], gy[VEC], gty[VEC];
+      widen<T>(x, q.x[j]);
+      widen<T>(tx, q.tx[j]);
+      widen<T>(gy, q.gy[j]);
+      widen<T>(gty, q.gty[j]);
+      float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         const float u = fmaf(gy[e], ah[e], gty[e] * tah[e]), w = gty[e] * ah[e];
@@ -218,174 +249,197 @@ __global__ __launch_bounds__(kNT) void adaln_bwd_kernel(AdalnArgs a) {
         sB = fmaf(w, x[e], sB);
         sC = fmaf(w, tx[e], sC);
       }
+      s[5 * j] = live ? sxx : 0.f;
+      s[5 * j + 1] = live ? sxt : 0.f;
+      s[5 * j + 2] = live ? sA : 0.f;
+      s[5 * j + 3] = live ? sB : 0.f;
+      s[5 * j + 4] = live ? sC : 0.f;
+      __builtin_amdgcn_sched_barrier(0);  // one row at a time: interleaved rows cost more registers than they gain
     }
-    sxx = wave_sum(sxx);
-    sxt = wave_sum(sxt);
-    sA = wave_sum(sA);
-    sB = wave_sum(sB);
-    sC = wave_sum(sC);
-    const float r = 1.0f / sqrtf(sxx * invc + a.eps);
-    const float r3 = r * r * r, mm = sxt * invc;
-    const float r3m = r3 * mm, kB = r3 * sB * invc;
-    const float kx = (3.0f * r3 * r * r * mm * sB - r3 * (sA + sC)) * invc;
-    T* gxp = static_cast<T*>(a.y) + off;
-    T* gtxp = static_cast<T*>(a.ty) + off;
+    wg_sums<NW, K>(s, red + par * NW * K, wave, lane);
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c0 = (lane + 64 * i) * VEC;
-      if (c0 >= a.C) continue;
-      float gx[VEC], gtx[VEC], x[VEC], tx[VEC], gy[VEC], gty[VEC], ah[VEC], tah[VEC];
-      widen16<T>(x, rx[i]);
-      widen16<T>(tx, rtx[i]);
-      widen16<T>(gy, rgy[i]);
-      widen16<T>(gty, rgt[i]);
-      lds_vec<VEC>(ah, lds + c0);
-      lds_vec<VEC>(tah, lds + a.C + c0);
+    for (int j = 0; j < R; ++j) {
+      // a row beyond the last one is a copy of the last one: it is worked on like the others, weighs nothing in
+      // the sums over tokens and is not stored (no branch around the arithmetic: it would split the sums' registers)
+      const float rowf = t0 + j < a.T ? 1.f : 0.f;
+      const float sB = s[5 * j + 3];
+      const float r = 1.0f / sqrtf(s[5 * j] * invc + a.eps);
+      const float r3 = r * r * r, mm = s[5 * j + 1] * invc;
+      const float r3m = r3 * mm, kB = r3 * sB * invc;
+      const float kx = (3.0f * r3 * r * r * mm * sB - r3 * (s[5 * j + 2] + s[5 * j + 4])) * invc;
+      const float rz = r * rowf, r3mz = r3m * rowf;
+      float gx[VEC], gtx[VEC], x[VEC], tx[VEC], gy[VEC], gty[VEC];
+      forget(q.x[j]);
+      forget(q.tx[j]);
+      forget(q.gy[j]);
+      forget(q.gty[j]);
+      widen<T>(x, q.x[j]);
+      widen<T>(tx, q.tx[j]);
+      widen<T>(gy, q.gy[j]);
+      widen<T>(gty, q.gty[j]);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         const float u = fmaf(gy[e], ah[e], gty[e] * tah[e]), w = gty[e] * ah[e];
-        const float xh = x[e] * r, txh = tx[e] * r - x[e] * r3m;
+        const float xh = x[e] * rz, txh = tx[e] * rz - x[e] * r3mz;
         gtx[e] = r * w - kB * x[e];
         gx[e] = r * u - r3m * w - kB * tx[e] + kx * x[e];
-        pa[i][e] += fmaf(gy[e], xh, gty[e] * txh);
-        pta[i][e] = fmaf(gty[e], xh, pta[i][e]);
-        pb[i][e] += gy[e];
-        ptb[i][e] += gty[e];
+        pa[e] += fmaf(gy[e], xh, gty[e] * txh);
+        pta[e] = fmaf(gty[e], xh, pta[e]);
+        pb[e] = fmaf(gy[e], rowf, pb[e]);
+        ptb[e] = fmaf(gty[e], rowf, ptb[e]);
       }
-      store16<T>(gxp + c0, gx);
-      store16<T>(gtxp + c0, gtx);
-    }
-  }
-  // column sums of this workgroup: its four waves add theirs one after the other, in order
-  float* sums = lds + 2 * a.C;
-  for (int k = 0; k < kWaves; ++k) {
-    if (wave == k) {
-#pragma unroll
-      for (int i = 0; i < MAXC; ++i) {
-        const int c0 = (lane + 64 * i) * VEC;
-        if (c0 >= a.C) continue;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          float* s = sums + c0 + e;
-          s[0] = (k ? s[0] : 0.f) + pa[i][e];
-          s[a.C] = (k ? s[a.C] : 0.f) + pta[i][e];
-          s[2 * a.C] = (k ? s[2 * a.C] : 0.f) + pb[i][e];
-          s[3 * a.C] = (k ? s[3 * a.C] : 0.f) + ptb[i][e];
-        }
+      if (live && t0 + j < a.T) {
+        const long long off = (long long)(t0 + j) * a.C;
+        store_row<T>(gxb + off, gx);
+        store_row<T>(gtxb + off, gtx);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
+  };
+  int par = 0;
+  for (int t0 = blockIdx.x * R; t0 < a.T; t0 += gridDim.x * R, par ^= 1) {
+    Rows q;
+    load(q, t0);
+    pass(q, t0, par);
   }
-  float* part = a.part + ((long long)b * gridDim.x + blockIdx.x) * 4 * a.C;
-  for (int c = tid; c < 4 * a.C; c += kNT) part[c] = sums[c];
+  if (live) {
+    float* part = a.part + ((long long)b * gridDim.x + blockIdx.x) * 4 * a.C + c0;
+    store_f32<VEC>(part, pa);
+    store_f32<VEC>(part + a.C, pta);
+    store_f32<VEC>(part + 2 * a.C, pb);
+    store_f32<VEC>(part + 3 * a.C, ptb);
+  }
 }
 
-// gsum[b][0..3][C] (in place of mod, which nobody reads any more) = the partial rows of batch element b added in
-// order: a thread per column, four loads in flight.
-__global__ __launch_bounds__(kNT) void adaln_sum_kernel(AdalnArgs a) {
-  const int b = blockIdx.y, c = blockIdx.x * kNT + threadIdx.x;
-  if (c >= 4 * a.C) return;
-  const float* part = a.part + (long long)b * a.nwg * 4 * a.C + c;
-  const long long stride = (long long)4 * a.C;
-  float s = 0.f;
-  int w = 0;
-  for (; w + 3 < a.nwg; w += 4) {
-    const float v0 = part[w * stride], v1 = part[(w + 1) * stride], v2 = part[(w + 2) * stride], v3 = part[(w + 3) * stride];
-    s = (((s + v0) + v1) + v2) + v3;
-  }
-  for (; w < a.nwg; ++w) s += part[w * stride];
-  a.mod[(long long)b * 4 * a.C + c] = s;
-}
-
-// Per batch element: RMSNorm^- backward for a (from the sums g_ah, g_tah) and for b (from g_bh, g_tbh).
-__global__ __launch_bounds__(kNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
-  __shared__ float red4[kWaves];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const float* gsum = a.mod + (long long)b * 4 * a.C;
+// Workgroup (which, b): the partial rows of batch element b added in a fixed order, which = 0: g_ah, g_tah, then
+// RMSNorm^- backward for a; which = 1: g_bh, g_tbh and the same for b.  1024 threads: first a thread sums a quarter
+// of the partial rows for up to two 16-byte chunks of columns (all its loads in flight together), the quarters meet
+// in LDS, then a thread owns one chunk of columns.
+constexpr int kModNT = 1024, kModWaves = kModNT / 64, kModQ = 4, kModCols = kModNT / kModQ, kModChunks = 2;
+__global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
+  extern __shared__ float qsum[];  // [kModQ][2][C]
+  __shared__ float red[kModWaves * 5];
+  const int which = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const long long o = (long long)b * a.C;
+  const float* v = (which ? a.b : a.a) + o;
+  const float* tv = (which ? a.tb : a.ta) + o;
+  float* gv = (which ? a.gb : a.ga) + o;
+  float* gtv = (which ? a.gtb : a.gta) + o;
+  const float* part = a.part + (long long)b * a.nwg * 4 * a.C + which * 2 * a.C;
+  const long long stride = (long long)4 * a.C;
+  {
+    const int q = tid / kModCols, ct = tid % kModCols;
+    const int g0 = (a.nwg * q) / kModQ, g1 = (a.nwg * (q + 1)) / kModQ;
 #pragma unroll
-  for (int which = 0; which < 2; ++which) {
-    const float* v = (which ? a.b : a.a) + o;
-    const float* tv = (which ? a.tb : a.ta) + o;
-    const float* u = gsum + (which ? 2 : 0) * a.C;   // gradient of the normalised vector
-    const float* w = u + a.C;                         // ... of its tangent
-    float* gv = (which ? a.gb : a.ga) + o;
-    float* gtv = (which ? a.gtb : a.gta) + o;
-    float sxx = 0.f, sxt = 0.f, sA = 0.f, sB = 0.f, sC = 0.f;
-    for (int c = tid; c < a.C; c += kNT) {
-      sxx = fmaf(v[c], v[c], sxx);
-      sxt = fmaf(v[c], tv[c], sxt);
-      sA = fmaf(u[c], v[c], sA);
-      sB = fmaf(w[c], v[c], sB);
-      sC = fmaf(w[c], tv[c], sC);
+    for (int j = 0; j < kModChunks; ++j) {
+      const int c0 = (ct + kModCols * j) * 4;
+      if (c0 >= a.C) continue;
+      float4 su = make_float4(0.f, 0.f, 0.f, 0.f), sw = su;
+#pragma unroll 8
+      for (int g = g0; g < g1; ++g) {
+        const float4 pu = *reinterpret_cast<const float4*>(part + g * stride + c0);
+        const float4 pw = *reinterpret_cast<const float4*>(part + g * stride + a.C + c0);
+        su.x += pu.x; su.y += pu.y; su.z += pu.z; su.w += pu.w;
+        sw.x += pw.x; sw.y += pw.y; sw.z += pw.z; sw.w += pw.w;
+      }
+      *reinterpret_cast<float4*>(qsum + (q * 2) * a.C + c0) = su;
+      *reinterpret_cast<float4*>(qsum + (q * 2 + 1) * a.C + c0) = sw;
     }
-    sxx = block_sum(sxx, red4, tid);
-    sxt = block_sum(sxt, red4, tid);
-    sA = block_sum(sA, red4, tid);
-    sB = block_sum(sB, red4, tid);
-    sC = block_sum(sC, red4, tid);
-    const float invc = 1.0f / (float)a.C;
-    const float r = 1.0f / sqrtf(sxx * invc + a.eps);
-    const float r3 = r * r * r, mm = sxt * invc;
-    const float r3m = r3 * mm, kB = r3 * sB * invc;
-    const float kx = (3.0f * r3 * r * r * mm * sB - r3 * (sA + sC)) * invc;
-    for (int c = tid; c < a.C; c += kNT) {
-      gtv[c] = r * w[c] - kB * v[c];
-      gv[c] = r * u[c] - r3m * w[c] - kB * tv[c] + kx * v[c];
+  }
+  __syncthreads();
+  const bool live = tid * 4 < a.C;
+  const int c0 = live ? tid * 4 : 0;
+  float u[4], w[4], x[4], t[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float su = qsum[c0 + e], sw = qsum[a.C + c0 + e];
+#pragma unroll
+    for (int q = 1; q < kModQ; ++q) {
+      su += qsum[(q * 2) * a.C + c0 + e];
+      sw += qsum[(q * 2 + 1) * a.C + c0 + e];
     }
+    u[e] = live ? su : 0.f;
+    w[e] = live ? sw : 0.f;
+  }
+  load_f32<4>(x, v + c0, live);
+  load_f32<4>(t, tv + c0, live);
+  float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    s[0] = fmaf(x[e], x[e], s[0]);
+    s[1] = fmaf(x[e], t[e], s[1]);
+    s[2] = fmaf(u[e], x[e], s[2]);
+    s[3] = fmaf(w[e], x[e], s[3]);
+    s[4] = fmaf(w[e], t[e], s[4]);
+  }
+  wg_sums<kModWaves, 5>(s, red, tid >> 6, tid & 63);
+  const float invc = 1.0f / (float)a.C;
+  const float r = 1.0f / sqrtf(s[0] * invc + a.eps);
+  const float r3 = r * r * r, mm = s[1] * invc;
+  const float r3m = r3 * mm, kB = r3 * s[3] * invc;
+  const float kx = (3.0f * r3 * r * r * mm * s[3] - r3 * (s[2] + s[4])) * invc;
+  if (live) {
+    float g[4], gt[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      gt[e] = r * w[e] - kB * x[e];
+      g[e] = r * u[e] - r3m * w[e] - kB * t[e] + kx * x[e];
+    }
+    store_f32<4>(gv + c0, g);
+    store_f32<4>(gtv + c0, gt);
   }
 }
 
 template <typename T>
-int chunks_per_lane(int C) { return (C / Chunk16<T>::VEC + 63) / 64; }
+int waves_per_row(int C) { return (C / Chunk<T>::VEC + 63) / 64; }
+
+constexpr int kRowsFwd = 4, kRowsBwd = 4;
 
 }  // namespace
 
-#define TVM_ADALN_BY_SIZE(KERNEL, T, SHMEM)                                                    \
-  switch (chunks_per_lane<T>(a.C)) {                                                           \
-    case 1: hipLaunchKernelGGL((KERNEL<T, 1>), grid, dim3(kNT), SHMEM, st, a); break;          \
-    case 2: hipLaunchKernelGGL((KERNEL<T, 2>), grid, dim3(kNT), SHMEM, st, a); break;          \
-    case 3: hipLaunchKernelGGL((KERNEL<T, 3>), grid, dim3(kNT), SHMEM, st, a); break;          \
-    case 4: hipLaunchKernelGGL((KERNEL<T, 4>), grid, dim3(kNT), SHMEM, st, a); break;          \
-    default: return hipErrorNotSupported;                                                      \
+#define TVM_ADALN_BY_SIZE(KERNEL, T, R)                                                              \
+  switch (waves_per_row<T>(a.C)) {                                                                   \
+    case 1: hipLaunchKernelGGL((KERNEL<T, 1, R>), grid, dim3(64), 0, st, a); break;                  \
+    case 2: hipLaunchKernelGGL((KERNEL<T, 2, R>), grid, dim3(128), 0, st, a); break;                 \
+    case 3: hipLaunchKernelGGL((KERNEL<T, 3, R>), grid, dim3(192), 0, st, a); break;                 \
+    case 4: hipLaunchKernelGGL((KERNEL<T, 4, R>), grid, dim3(256), 0, st, a); break;                 \
+    default: return hipErrorNotSupported;                                                            \
   }
+
+// Workgroups per batch element: R token rows per pass, at most about `total` workgroups in all, and every one the
+// same number of passes where T allows.
+int adaln_wgs(int B, int T, bool backward) {
+  const int R = backward ? kRowsBwd : kRowsFwd, total = backward ? kTotalBwd : 1024;
+  const int groups = (T + R - 1) / R, cap = total / B > 1 ? total / B : 1;
+  const int passes = (groups + cap - 1) / cap;
+  return (groups + passes - 1) / passes;
+}
 
 bool adaln_supported(int C, int dtype) {
   const int vec = dtype == 1 ? 8 : 4;
-  return C % vec == 0 && C / vec <= 256;  // at most four 16-byte chunks per lane
+  return C % vec == 0 && C / vec <= 256;  // a thread per 16-byte chunk, at most 256 threads
 }
 
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st) {
-  hipLaunchKernelGGL(adaln_mod_kernel, dim3(a.B), dim3(kNT), 0, st, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   const dim3 grid(a.nwg, a.B);
-  const size_t shmem = (size_t)4 * a.C * sizeof(float);
   if (dtype == 1) {
-    TVM_ADALN_BY_SIZE(adaln_fwd_kernel, bf16, shmem)
+    TVM_ADALN_BY_SIZE(adaln_fwd_kernel, bf16, kRowsFwd)
   } else {
-    TVM_ADALN_BY_SIZE(adaln_fwd_kernel, float, shmem)
+    TVM_ADALN_BY_SIZE(adaln_fwd_kernel, float, kRowsFwd)
   }
   return hipGetLastError();
 }
 
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st) {
-  hipLaunchKernelGGL(adaln_mod_kernel, dim3(a.B), dim3(kNT), 0, st, a);
+  const dim3 grid(a.nwg, a.B);
+  if (dtype == 1) {
+    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, bf16, kRowsBwd)
+  } else {
+    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, float, kRowsBwd)
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid(a.nwg, a.B);
-  const size_t shmem = (size_t)6 * a.C * sizeof(float);
-  if (dtype == 1) {
-    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, bf16, shmem)
-  } else {
-    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, float, shmem)
-  }
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(adaln_sum_kernel, dim3((4 * a.C + kNT - 1) / kNT, a.B), dim3(kNT), 0, st, a);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(a.B), dim3(kNT), 0, st, a);
+  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(2, a.B), dim3(kModNT), (size_t)kModQ * 2 * a.C * sizeof(float), st, a);
   return hipGetLastError();
 }
 

@@ -105,13 +105,13 @@ struct AdalnArgs {
   const void *x, *tx, *gy, *gty;    // [B,T,C] dtype, contiguous (gy, gty: backward only)
   const float *a, *ta, *b, *tb;     // [B,C] float32
   void *y, *ty;                     // forward: outputs; backward: gradients of x and tx
-  float* mod;                       // workspace [B][4][C]: the normalised a, its tangent, the normalised b, its tangent
   float* part;                      // backward workspace [B][nwg][4][C]: per-workgroup sums over tokens
   float *ga, *gta, *gb, *gtb;       // backward: gradients of a, ta, b, tb
   int B, T, C, nwg;                 // nwg: workgroups per batch element
   float eps;
 };
 bool adaln_supported(int C, int dtype);
+int adaln_wgs(int B, int T, bool backward);  // workgroups per batch element of the forward / backward token kernel
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st);
 

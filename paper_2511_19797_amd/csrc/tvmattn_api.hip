@@ -350,18 +350,15 @@ int adaln_check(int B, int T, int C, int dtype, float eps) {
   if (!tvm::adaln_supported(C, dtype) || (long long)B * T >= (1ll << 31) || B > 65535) return TVMATTN_UNSUPPORTED;
   return TVMATTN_OK;
 }
-// Workgroups per batch element: four token rows each per pass, about `total` in all (each loads its batch element's
-// modulation into LDS once; a backward one leaves a partial row of column sums and runs one wave per SIMD).
-int adaln_wgs(int B, int T, int total) {
-  const int want = (T + 3) / 4, cap = total / B > 1 ? total / B : 1;
-  return want < cap ? want : cap;
+// The forward needs no workspace any more; the query keeps a non-zero answer for valid shapes (0 = unsupported).
+constexpr size_t kAdalnFwdWorkspace = 256;
+size_t adaln_part_bytes(int B, int T, int C) {
+  return pad256((size_t)B * tvm::adaln_wgs(B, T, true) * 4 * C * sizeof(float));
 }
-constexpr int kAdalnFwdWgs = 1024, kAdalnBwdWgs = 512;
-size_t adaln_mod_bytes(int B, int C) { return pad256((size_t)B * 4 * C * sizeof(float)); }
 }  // namespace
 
 size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype) {
-  return adaln_check(B, T, C, dtype, 0.f) ? 0 : adaln_mod_bytes(B, C);
+  return adaln_check(B, T, C, dtype, 0.f) ? 0 : kAdalnFwdWorkspace;
 }
 
 int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
@@ -373,7 +370,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
   void* const out[] = {y, ty, workspace};
   rc = check_ptrs(in, out);
   if (rc) return rc;
-  if (workspace_bytes < adaln_mod_bytes(B, C)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < kAdalnFwdWorkspace) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::AdalnArgs g{};
   g.x = x;
   g.tx = tx;
@@ -383,11 +380,10 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
   g.tb = tb;
   g.y = y;
   g.ty = ty;
-  g.mod = static_cast<float*>(workspace);
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = adaln_wgs(B, T, kAdalnFwdWgs);
+  g.nwg = tvm::adaln_wgs(B, T, false);
   g.eps = eps;
   return tvm::launch_adaln_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
@@ -395,7 +391,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
 
 size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
   if (adaln_check(B, T, C, dtype, 0.f)) return 0;
-  return adaln_mod_bytes(B, C) + pad256((size_t)B * adaln_wgs(B, T, kAdalnBwdWgs) * 4 * C * sizeof(float));
+  return adaln_part_bytes(B, T, C);
 }
 
 int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
@@ -424,12 +420,11 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.gta = gta;
   g.gb = gb;
   g.gtb = gtb;
-  g.mod = static_cast<float*>(workspace);
-  g.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + adaln_mod_bytes(B, C));
+  g.part = static_cast<float*>(workspace);
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = adaln_wgs(B, T, kAdalnBwdWgs);
+  g.nwg = tvm::adaln_wgs(B, T, true);
   g.eps = eps;
   return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
