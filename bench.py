@@ -326,6 +326,44 @@ def adaln(w, steps, seed=2024):
     return out
 
 
+def gate(w, steps, seed=2024):
+    """The normalised gate of a residual branch with tangent (App. "Full Description of Normalization of Modulation":
+    how the output of ATTN and of MLP re-enters the stream) at the workload's token count and hidden size H*d,
+    forward and backward, timed outside the timed region of the headline figure.  Memory-bound: algorithmic bytes =
+    every [B,T,C] tensor once (forward reads 4 and writes 2, backward reads 4 and writes 2), against 8 TB/s."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    B, T, C = w.B, w.Mq, w.H * w.d
+    inp = wl.make_gate_inputs(B, T, C, w.dtype, seed)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    del inp
+    fo = (torch.empty_like(dev["x"]), torch.empty_like(dev["x"]))
+    bo = fo + (torch.empty_like(dev["c"]), torch.empty_like(dev["c"]))
+    ws = torch.empty(1 << 26, dtype=torch.uint8, device="cuda")
+    one = float(B) * T * C * (2 if w.dtype == "bf16" else 4)
+    cases = {"fwd": (6.0 * one, lambda: tvm.tvmattn_gate_jvp_fwd(dev["x"], dev["tx"], dev["h"], dev["th"], dev["c"],
+                                                               dev["tc"], 1e-6, out=fo)),
+             "bwd": (6.0 * one, lambda: tvm.tvmattn_gate_jvp_bwd(dev["h"], dev["th"], dev["c"], dev["tc"], 1e-6,
+                                                               dev["gz"], dev["gtz"], out=bo, workspace=ws))}
+    out = {"shape": {"B": B, "T": T, "C": C}}
+    for name, (nbytes, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
+                     "frac": gbs / 8000.0}
+    return out
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -408,6 +446,7 @@ def main():
     out["qknorm"] = qknorm(w, args.steps)
     if w.dtype == "bf16" and (w.H * w.d) % 8 == 0 and w.H * w.d <= 2048:
         out["adaln"] = adaln(w, args.steps)
+        out["gate"] = gate(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

@@ -273,6 +273,40 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype,
                           void* gx, void* gtx, float* ga, float* gta, float* gb, float* gtb,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Normalised gate of a residual branch with tangent: how the output h of ATTN or of MLP re-enters the residual
+ * stream in the paper's block (App. "Full Description of Normalization of Modulation", the two layer equations):
+ *
+ *     z  = x + RMSNorm^-(c) o h
+ *     tz = its directional derivative along (tx, th, tc)
+ *
+ *   in : x, tx, h, th    [B,T,C] dtype, contiguous: the stream, the branch output, and their tangents
+ *        c, tc           [B,C] float32, contiguous: the gate of the token's batch element and its tangent
+ *        eps             >= 0, finite
+ *   out: z, tz           [B,T,C] dtype; must not alias an input
+ * Shape limits as for tvmattn_adaln_jvp_fwd.  One launch, no workspace.  Arithmetic is float32.
+ */
+int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype,
+                         const void* x, const void* tx, const void* h, const void* th,
+                         const float* c, const float* tc, float eps,
+                         void* z, void* tz, void* hip_stream);
+
+/*
+ * Backward of the above: the gradient of <gz,z> + <gtz,tz>.  The gradients with respect to x and tx are gz and gtz
+ * themselves and are not written.
+ *   in : h, th, c, tc, eps as given to the forward (nothing is saved); gz, gtz [B,T,C] dtype
+ *   out: gh, gth [B,T,C] dtype; gc, gtc [B,C] float32 (summed over the T tokens of their batch element)
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_gate_jvp_bwd_workspace_bytes(...) bytes
+ *              (0 = unsupported shape).
+ * Two launches; the sums over tokens use no atomics and are bitwise reproducible.
+ */
+size_t tvmattn_gate_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype);
+int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype,
+                         const void* h, const void* th, const float* c, const float* tc, float eps,
+                         const void* gz, const void* gtz,
+                         void* gh, void* gth, float* gc, float* gtc,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

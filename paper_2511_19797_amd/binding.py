@@ -75,6 +75,12 @@ def lib():
         L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3 + [ctypes.c_size_t, _P]
         L.tvmattn_adaln_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_adaln_jvp_bwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 9 + [ctypes.c_size_t, _P]
+        L.tvmattn_gate_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_gate_jvp_bwd_workspace_bytes.argtypes = [_I] * 4
+        L.tvmattn_gate_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_gate_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3
+        L.tvmattn_gate_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_gate_jvp_bwd.argtypes = [_I] * 4 + [_P] * 4 + [ctypes.c_float] + [_P] * 7 + [ctypes.c_size_t, _P]
         _lib = L
     return _lib
 
@@ -326,4 +332,33 @@ def tvmattn_adaln_jvp_bwd(x, tx, a, ta, b, tb, eps, gy, gty, out=None, workspace
     _check(lib().tvmattn_adaln_jvp_bwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(), b.data_ptr(),
                                        tb.data_ptr(), float(eps), gy.data_ptr(), gty.data_ptr(),
                                        *[t.data_ptr() for t in out], workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+def tvmattn_gate_jvp_fwd(x, tx, h, th, c, tc, eps, out=None):
+    """Returns (z, tz): x + RMSNorm^-(c) * h and its tangent along (tx, th, tc)."""
+    B, T, C, dt = _adaln_args(x, tx, (c, tc))
+    _adaln_args(h, th, ())
+    if h.shape != x.shape or h.dtype != x.dtype:
+        raise ValueError("the branch output must look like x")
+    z, tz = out if out is not None else (torch.empty_like(x), torch.empty_like(x))
+    _check(lib().tvmattn_gate_jvp_fwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), h.data_ptr(), th.data_ptr(), c.data_ptr(),
+                                      tc.data_ptr(), float(eps), z.data_ptr(), tz.data_ptr(), _stream()))
+    return z, tz
+
+
+def tvmattn_gate_jvp_bwd(h, th, c, tc, eps, gz, gtz, out=None, workspace=None):
+    """Returns (gh, gth, gc, gtc); the gradients with respect to x and tx are gz and gtz themselves."""
+    B, T, C, dt = _adaln_args(h, th, (c, tc))
+    _adaln_args(gz, gtz, ())
+    if gz.shape != h.shape or gz.dtype != h.dtype:
+        raise ValueError("upstream gradients must look like h")
+    if out is None:
+        out = (torch.empty_like(h), torch.empty_like(h), torch.empty_like(c), torch.empty_like(c))
+    need = int(lib().tvmattn_gate_jvp_bwd_workspace_bytes(B, T, C, dt))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=h.device)
+    _check(lib().tvmattn_gate_jvp_bwd(B, T, C, dt, h.data_ptr(), th.data_ptr(), c.data_ptr(), tc.data_ptr(), float(eps),
+                                      gz.data_ptr(), gtz.data_ptr(), *[t.data_ptr() for t in out], workspace.data_ptr(),
+                                      workspace.numel(), _stream()))
     return out

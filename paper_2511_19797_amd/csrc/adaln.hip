@@ -311,58 +311,63 @@ __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
   }
 }
 
-// Workgroup (which, b): the partial rows of batch element b added in a fixed order, which = 0: g_ah, g_tah, then
-// RMSNorm^- backward for a; which = 1: g_bh, g_tbh and the same for b.  1024 threads: first a thread sums a quarter
-// of the partial rows for up to two 16-byte chunks of columns (all its loads in flight together), the quarters meet
-// in LDS, then a thread owns one chunk of columns.
+// The end of a backward for one normalised [C] vector v with tangent tv (a, b or the gate c of a batch element): the
+// workgroups' partial rows (u = gradient of the normalised vector, w = of its tangent, at part and part + C, `stride`
+// floats from one workgroup's to the next's) added in a fixed order, then RMSNorm^- backward.  1024 threads: first a
+// thread sums a quarter of the partial rows for up to two 16-byte chunks of columns (all its loads in flight
+// together, v and tv requested before them), the quarters meet in LDS, then a thread owns one chunk of columns.
 constexpr int kModNT = 1024, kModWaves = kModNT / 64, kModQ = 4, kModCols = kModNT / kModQ, kModChunks = 2;
-__global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
-  extern __shared__ float qsum[];  // [kModQ][2][C]
-  __shared__ float red[kModWaves * 5];
-  const int which = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const long long o = (long long)b * a.C;
-  const float* v = (which ? a.b : a.a) + o;
-  const float* tv = (which ? a.tb : a.ta) + o;
-  float* gv = (which ? a.gb : a.ga) + o;
-  float* gtv = (which ? a.gtb : a.gta) + o;
-  const float* part = a.part + (long long)b * a.nwg * 4 * a.C + which * 2 * a.C;
-  const long long stride = (long long)4 * a.C;
+__device__ __forceinline__ void mod_bwd_body(const float* part, long long stride, int nwg, int C, float eps, const float* v,
+                                             const float* tv, float* gv, float* gtv, float* qsum /* [kModQ][2][C] */,
+                                             float* red /* [kModWaves][5] */) {
+  const int tid = threadIdx.x;
+  const bool live = tid * 4 < C;
+  const int c0 = live ? tid * 4 : 0;
+  float x[4], t[4];
+  load_f32<4>(x, v + c0, live);
+  load_f32<4>(t, tv + c0, live);
   {
     const int q = tid / kModCols, ct = tid % kModCols;
-    const int g0 = (a.nwg * q) / kModQ, g1 = (a.nwg * (q + 1)) / kModQ;
+    const int g0 = (nwg * q) / kModQ, g1 = (nwg * (q + 1)) / kModQ;
+    bool on[kModChunks];
+    int cc[kModChunks];
+    float4 su[kModChunks], sw[kModChunks];
 #pragma unroll
     for (int j = 0; j < kModChunks; ++j) {
-      const int c0 = (ct + kModCols * j) * 4;
-      if (c0 >= a.C) continue;
-      float4 su = make_float4(0.f, 0.f, 0.f, 0.f), sw = su;
+      on[j] = (ct + kModCols * j) * 4 < C;
+      cc[j] = on[j] ? (ct + kModCols * j) * 4 : 0;
+      su[j] = sw[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 #pragma unroll 8
-      for (int g = g0; g < g1; ++g) {
-        const float4 pu = *reinterpret_cast<const float4*>(part + g * stride + c0);
-        const float4 pw = *reinterpret_cast<const float4*>(part + g * stride + a.C + c0);
-        su.x += pu.x; su.y += pu.y; su.z += pu.z; su.w += pu.w;
-        sw.x += pw.x; sw.y += pw.y; sw.z += pw.z; sw.w += pw.w;
+    for (int g = g0; g < g1; ++g) {
+#pragma unroll
+      for (int j = 0; j < kModChunks; ++j) {
+        const float4 pu = *reinterpret_cast<const float4*>(part + g * stride + cc[j]);
+        const float4 pw = *reinterpret_cast<const float4*>(part + g * stride + C + cc[j]);
+        su[j].x += pu.x; su[j].y += pu.y; su[j].z += pu.z; su[j].w += pu.w;
+        sw[j].x += pw.x; sw[j].y += pw.y; sw[j].z += pw.z; sw[j].w += pw.w;
       }
-      *reinterpret_cast<float4*>(qsum + (q * 2) * a.C + c0) = su;
-      *reinterpret_cast<float4*>(qsum + (q * 2 + 1) * a.C + c0) = sw;
+    }
+#pragma unroll
+    for (int j = 0; j < kModChunks; ++j) {
+      if (!on[j]) continue;
+      *reinterpret_cast<float4*>(qsum + (q * 2) * C + cc[j]) = su[j];
+      *reinterpret_cast<float4*>(qsum + (q * 2 + 1) * C + cc[j]) = sw[j];
     }
   }
   __syncthreads();
-  const bool live = tid * 4 < a.C;
-  const int c0 = live ? tid * 4 : 0;
-  float u[4], w[4], x[4], t[4];
+  float u[4], w[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    float su = qsum[c0 + e], sw = qsum[a.C + c0 + e];
+    float au = qsum[c0 + e], aw = qsum[C + c0 + e];
 #pragma unroll
     for (int q = 1; q < kModQ; ++q) {
-      su += qsum[(q * 2) * a.C + c0 + e];
-      sw += qsum[(q * 2 + 1) * a.C + c0 + e];
+      au += qsum[(q * 2) * C + c0 + e];
+      aw += qsum[(q * 2 + 1) * C + c0 + e];
     }
-    u[e] = live ? su : 0.f;
-    w[e] = live ? sw : 0.f;
+    u[e] = live ? au : 0.f;
+    w[e] = live ? aw : 0.f;
   }
-  load_f32<4>(x, v + c0, live);
-  load_f32<4>(t, tv + c0, live);
   float s[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -373,8 +378,8 @@ __global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
     s[4] = fmaf(w[e], t[e], s[4]);
   }
   wg_sums<kModWaves, 5>(s, red, tid >> 6, tid & 63);
-  const float invc = 1.0f / (float)a.C;
-  const float r = 1.0f / sqrtf(s[0] * invc + a.eps);
+  const float invc = 1.0f / (float)C;
+  const float r = 1.0f / sqrtf(s[0] * invc + eps);
   const float r3 = r * r * r, mm = s[1] * invc;
   const float r3m = r3 * mm, kB = r3 * s[3] * invc;
   const float kx = (3.0f * r3 * r * r * mm * s[3] - r3 * (s[2] + s[4])) * invc;
@@ -388,6 +393,139 @@ __global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
     store_f32<4>(gv + c0, g);
     store_f32<4>(gtv + c0, gt);
   }
+}
+
+// Workgroup (which, b): which = 0: g_ah, g_tah and the gradients of a, ta; which = 1: g_bh, g_tbh and those of b, tb.
+__global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
+  extern __shared__ float qsum[];
+  __shared__ float red[kModWaves * 5];
+  const int which = blockIdx.x, b = blockIdx.y;
+  const long long o = (long long)b * a.C;
+  mod_bwd_body(a.part + (long long)b * a.nwg * 4 * a.C + which * 2 * a.C, (long long)4 * a.C, a.nwg, a.C, a.eps,
+               (which ? a.b : a.a) + o, (which ? a.tb : a.ta) + o, (which ? a.gb : a.ga) + o,
+               (which ? a.gtb : a.gta) + o, qsum, red);
+}
+
+// ---- Normalised gate of a residual branch (App. "Full Description of Normalization of Modulation", the layer
+// equations): z = x + ch o h, tz = tx + tch o h + ch o th with ch, tch = RMSNorm^-(c) and its tangent per batch
+// element.  Backward of <gz, z> + <gtz, tz>: gh = ch gz + tch gtz, gth = ch gtz (the gradients of x and tx are gz
+// and gtz themselves and are not written), g_ch = sum_t gz h + gtz th, g_tch = sum_t gtz h, then RMSNorm^- backward
+// for c.  No row sums: pure streaming, the same thread-per-chunk layout, R rows per pass, no barrier in the loop.
+template <typename T, int NW, int R>
+__global__ __launch_bounds__(64 * NW) void gate_fwd_kernel(GateArgs a) {
+  constexpr int VEC = Chunk<T>::VEC;
+  __shared__ float red[NW * 2];
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool live = tid * VEC < a.C;
+  const int c0 = live ? tid * VEC : 0;
+  float ch[VEC], tch[VEC];
+  const long long mo = (long long)b * a.C;
+  norm_own_chunk<NW, VEC>(a.c + mo, a.tc + mo, c0, live, a.C, a.eps, ch, tch, red, wave, lane);
+  if (!live) return;  // no barrier from here on
+  const long long bo = (long long)b * a.T * a.C + c0;
+  const T* xb = static_cast<const T*>(a.x) + bo;
+  const T* txb = static_cast<const T*>(a.tx) + bo;
+  const T* hb = static_cast<const T*>(a.h) + bo;
+  const T* thb = static_cast<const T*>(a.th) + bo;
+  T* zb = static_cast<T*>(a.z) + bo;
+  T* tzb = static_cast<T*>(a.tz) + bo;
+  for (int t0 = blockIdx.x * R; t0 < a.T; t0 += gridDim.x * R) {
+    Raw<T> rx[R], rtx[R], rh[R], rth[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {  // rows beyond the last one are read as the last one and not stored
+      const long long off = (long long)(t0 + j < a.T ? t0 + j : a.T - 1) * a.C;
+      rx[j] = load_raw<T>(xb + off);
+      rtx[j] = load_raw<T>(txb + off);
+      rh[j] = load_raw<T>(hb + off);
+      rth[j] = load_raw<T>(thb + off);
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      if (t0 + j >= a.T) continue;
+      float x[VEC], tx[VEC], h[VEC], th[VEC], z[VEC], tz[VEC];
+      widen<T>(x, rx[j]);
+      widen<T>(tx, rtx[j]);
+      widen<T>(h, rh[j]);
+      widen<T>(th, rth[j]);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        z[e] = fmaf(ch[e], h[e], x[e]);
+        tz[e] = fmaf(tch[e], h[e], fmaf(ch[e], th[e], tx[e]));
+      }
+      const long long off = (long long)(t0 + j) * a.C;
+      store_row<T>(zb + off, z);
+      store_row<T>(tzb + off, tz);
+    }
+  }
+}
+
+template <typename T, int NW, int R>
+__global__ __launch_bounds__(64 * NW) void gate_bwd_kernel(GateArgs a) {
+  constexpr int VEC = Chunk<T>::VEC;
+  __shared__ float red[NW * 2];
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool live = tid * VEC < a.C;
+  const int c0 = live ? tid * VEC : 0;
+  float ch[VEC], tch[VEC];
+  const long long mo = (long long)b * a.C;
+  norm_own_chunk<NW, VEC>(a.c + mo, a.tc + mo, c0, live, a.C, a.eps, ch, tch, red, wave, lane);
+  if (!live) return;  // no barrier from here on
+  const long long bo = (long long)b * a.T * a.C + c0;
+  const T* hb = static_cast<const T*>(a.h) + bo;
+  const T* thb = static_cast<const T*>(a.th) + bo;
+  const T* gzb = static_cast<const T*>(a.gz) + bo;
+  const T* gtzb = static_cast<const T*>(a.gtz) + bo;
+  T* ghb = static_cast<T*>(a.z) + bo;
+  T* gthb = static_cast<T*>(a.tz) + bo;
+  float pc[VEC], ptc[VEC];  // this thread's columns summed over the workgroup's tokens
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) pc[e] = ptc[e] = 0.f;
+  for (int t0 = blockIdx.x * R; t0 < a.T; t0 += gridDim.x * R) {
+    Raw<T> rh[R], rth[R], rgz[R], rgtz[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const long long off = (long long)(t0 + j < a.T ? t0 + j : a.T - 1) * a.C;
+      rh[j] = load_raw<T>(hb + off);
+      rth[j] = load_raw<T>(thb + off);
+      rgz[j] = load_raw<T>(gzb + off);
+      rgtz[j] = load_raw<T>(gtzb + off);
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const float rowf = t0 + j < a.T ? 1.f : 0.f;  // a copy of the last row weighs nothing and is not stored
+      float h[VEC], th[VEC], gz[VEC], gtz[VEC], gh[VEC], gth[VEC];
+      widen<T>(h, rh[j]);
+      widen<T>(th, rth[j]);
+      widen<T>(gz, rgz[j]);
+      widen<T>(gtz, rgtz[j]);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        gh[e] = fmaf(ch[e], gz[e], tch[e] * gtz[e]);
+        gth[e] = ch[e] * gtz[e];
+        const float hv = h[e] * rowf;
+        pc[e] += fmaf(gz[e], hv, gtz[e] * th[e] * rowf);
+        ptc[e] = fmaf(gtz[e], hv, ptc[e]);
+      }
+      if (t0 + j < a.T) {
+        const long long off = (long long)(t0 + j) * a.C;
+        store_row<T>(ghb + off, gh);
+        store_row<T>(gthb + off, gth);
+      }
+    }
+  }
+  float* part = a.part + ((long long)b * gridDim.x + blockIdx.x) * 2 * a.C + c0;
+  store_f32<VEC>(part, pc);
+  store_f32<VEC>(part + a.C, ptc);
+}
+
+// Workgroup b: g_ch, g_tch and the gradients of c, tc.
+__global__ __launch_bounds__(kModNT) void gate_mod_bwd_kernel(GateArgs a) {
+  extern __shared__ float qsum[];
+  __shared__ float red[kModWaves * 5];
+  const int b = blockIdx.x;
+  const long long o = (long long)b * a.C;
+  mod_bwd_body(a.part + (long long)b * a.nwg * 2 * a.C, (long long)2 * a.C, a.nwg, a.C, a.eps, a.c + o, a.tc + o,
+               a.gc + o, a.gtc + o, qsum, red);
 }
 
 template <typename T>
@@ -418,6 +556,29 @@ int adaln_wgs(int B, int T, bool backward) {
 bool adaln_supported(int C, int dtype) {
   const int vec = dtype == 1 ? 8 : 4;
   return C % vec == 0 && C / vec <= 256;  // a thread per 16-byte chunk, at most 256 threads
+}
+
+hipError_t launch_gate_fwd(const GateArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid(a.nwg, a.B);
+  if (dtype == 1) {
+    TVM_ADALN_BY_SIZE(gate_fwd_kernel, bf16, kRowsFwd)
+  } else {
+    TVM_ADALN_BY_SIZE(gate_fwd_kernel, float, kRowsFwd)
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gate_bwd(const GateArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid(a.nwg, a.B);
+  if (dtype == 1) {
+    TVM_ADALN_BY_SIZE(gate_bwd_kernel, bf16, kRowsBwd)
+  } else {
+    TVM_ADALN_BY_SIZE(gate_bwd_kernel, float, kRowsBwd)
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gate_mod_bwd_kernel, dim3(a.B), dim3(kModNT), (size_t)kModQ * 2 * a.C * sizeof(float), st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st) {

@@ -110,6 +110,19 @@ struct AdalnArgs {
   int B, T, C, nwg;                 // nwg: workgroups per batch element
   float eps;
 };
+// Normalised gate of a residual branch: z = x + RMSNorm^-(c) o h with tangent, and its backward.
+struct GateArgs {
+  const void *x, *tx, *h, *th;      // [B,T,C] dtype, contiguous (x, tx: forward only)
+  const void *gz, *gtz;             // backward: upstream gradients, [B,T,C] dtype
+  const float *c, *tc;              // [B,C] float32
+  void *z, *tz;                     // forward: outputs; backward: gradients of h and th
+  float* part;                      // backward workspace [B][nwg][2][C]: per-workgroup sums over tokens
+  float *gc, *gtc;                  // backward: gradients of c, tc
+  int B, T, C, nwg;
+  float eps;
+};
+hipError_t launch_gate_fwd(const GateArgs& a, int dtype, hipStream_t st);
+hipError_t launch_gate_bwd(const GateArgs& a, int dtype, hipStream_t st);
 bool adaln_supported(int C, int dtype);
 int adaln_wgs(int B, int T, bool backward);  // workgroups per batch element of the forward / backward token kernel
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);

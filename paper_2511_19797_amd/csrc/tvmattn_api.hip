@@ -87,7 +87,7 @@ inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(sk
 
 extern "C" {
 
-int tvmattn_version(void) { return 400; }  // 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 500; }  // 0.5.0: AdaLN modulation and residual gate; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -428,6 +428,69 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.eps = eps;
   return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
+}
+
+// ---- normalised gate of a residual branch with tangent
+size_t tvmattn_gate_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
+  if (adaln_check(B, T, C, dtype, 0.f)) return 0;
+  return pad256((size_t)B * tvm::adaln_wgs(B, T, true) * 2 * C * sizeof(float));
+}
+
+int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype, const void* x, const void* tx, const void* h, const void* th,
+                         const float* c, const float* tc, float eps, void* z, void* tz, void* hip_stream) {
+  int rc = adaln_check(B, T, C, dtype, eps);
+  if (rc) return rc;
+  const void* const in[] = {x, tx, h, th, c, tc};
+  void* const out[] = {z, tz};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  tvm::GateArgs g{};
+  g.x = x;
+  g.tx = tx;
+  g.h = h;
+  g.th = th;
+  g.c = c;
+  g.tc = tc;
+  g.z = z;
+  g.tz = tz;
+  g.B = B;
+  g.T = T;
+  g.C = C;
+  g.nwg = tvm::adaln_wgs(B, T, false);
+  g.eps = eps;
+  return tvm::launch_gate_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
+                                                                                          : TVMATTN_LAUNCH_FAILED;
+}
+
+int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype, const void* h, const void* th, const float* c, const float* tc,
+                         float eps, const void* gz, const void* gtz, void* gh, void* gth, float* gc, float* gtc,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = adaln_check(B, T, C, dtype, eps);
+  if (rc) return rc;
+  const void* const in[] = {h, th, c, tc, gz, gtz};
+  void* const out[] = {gh, gth, gc, gtc, workspace};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  if (workspace_bytes < tvmattn_gate_jvp_bwd_workspace_bytes(B, T, C, dtype)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::GateArgs g{};
+  g.h = h;
+  g.th = th;
+  g.gz = gz;
+  g.gtz = gtz;
+  g.c = c;
+  g.tc = tc;
+  g.z = gh;
+  g.tz = gth;
+  g.gc = gc;
+  g.gtc = gtc;
+  g.part = static_cast<float*>(workspace);
+  g.B = B;
+  g.T = T;
+  g.C = C;
+  g.nwg = tvm::adaln_wgs(B, T, true);
+  g.eps = eps;
+  return tvm::launch_gate_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
+                                                                                          : TVMATTN_LAUNCH_FAILED;
 }
 
 }  // extern "C"

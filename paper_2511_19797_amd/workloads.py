@@ -136,6 +136,19 @@ def make_adaln_inputs(B: int, T: int, C: int, dtype: str, seed: int):
     return out
 
 
+def make_gate_inputs(B: int, T: int, C: int, dtype: str, seed: int):
+    """Inputs of the normalised residual gate: the stream x and the branch output h with tangents tx, th and upstream
+    gradients gz, gtz ([B,T,C], storage dtype), the gate c per batch element with tangent tc ([B,C] float32)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    out = {}
+    for name in ("x", "tx", "h", "th", "gz", "gtz"):
+        out[name] = torch.from_numpy(rng.standard_normal((B, T, C), dtype=np.float32)).to(td).contiguous()
+    for name in ("c", "tc"):
+        out[name] = torch.from_numpy(rng.standard_normal((B, C), dtype=np.float32)).contiguous()
+    return out
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()

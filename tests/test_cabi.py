@@ -245,3 +245,40 @@ def test_adaln_argument_rules(L):
         p = list(brest)
         p[k] = None
         assert bwd(ins, p) == -1
+
+
+def test_gate_argument_rules(L):
+    """The residual-gate entry points validate before anything is launched."""
+    I, P, F, Z = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+    L.tvmattn_gate_jvp_fwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 3
+    L.tvmattn_gate_jvp_bwd.argtypes = [I] * 4 + [P] * 4 + [F] + [P] * 7 + [Z, P]
+    L.tvmattn_gate_jvp_bwd_workspace_bytes.restype, L.tvmattn_gate_jvp_bwd_workspace_bytes.argtypes = Z, [I] * 4
+    B, T, C = 4, 100, 1152
+    nb = L.tvmattn_gate_jvp_bwd_workspace_bytes(B, T, C, 1)
+    assert nb >= B * 2 * C * 4 and nb % 256 == 0
+    for bad in ((0, T, C, 1), (B, 0, C, 1), (B, T, 0, 1), (B, T, C, 5), (B, T, 1156, 1), (B, T, 2056, 1), (B, T, 1028, 0)):
+        assert L.tvmattn_gate_jvp_bwd_workspace_bytes(*bad) == 0
+    ins = [0x1000 * (i + 1) for i in range(6)]
+    outs = [0x1000 * (i + 7) for i in range(2)]
+    fwd = lambda i, o, eps=1e-6, shape=(B, T, C, 1): L.tvmattn_gate_jvp_fwd(*shape, *i, eps, *o, None)
+    assert fwd(ins, outs, eps=-1.0) == -1 and fwd(ins, outs, shape=(B, T, 12, 1)) == -2
+    assert fwd(ins, outs, shape=(B, T, C, 3)) == -2 and fwd(ins, outs, shape=(B, -1, C, 1)) == -1
+    for k in range(6):
+        p = list(ins)
+        p[k] = None
+        assert fwd(p, outs) == -1
+        p[k] = ins[k] + 4     # not 16-byte aligned
+        assert fwd(p, outs) == -1
+    assert fwd(ins, [outs[0], outs[0]]) == -1 and fwd(ins, [ins[0], outs[1]]) == -1   # aliasing
+    bins = [0x1000 * (i + 1) for i in range(4)]          # h, th, c, tc
+    brest = [0x1000 * (i + 5) for i in range(7)]         # gz, gtz, gh, gth, gc, gtc, workspace
+    bwd = lambda i, r, ws=nb - 1: L.tvmattn_gate_jvp_bwd(B, T, C, 1, *i, 1e-6, *r, ws, None)
+    assert bwd(bins, brest) == -3
+    for k in range(7):
+        p = list(brest)
+        p[k] = None
+        assert bwd(bins, p) == -1
+    for k in range(4):
+        p = list(bins)
+        p[k] = None
+        assert bwd(p, brest) == -1
