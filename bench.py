@@ -364,6 +364,37 @@ def gate(w, steps, seed=2024):
     return out
 
 
+def gelu(w, steps, seed=2024):
+    """The MLP's activation with tangent (tanh-form GELU; the hidden layer is 4 x the model width) at the workload's
+    token count, forward and backward.  Memory-bound: algorithmic bytes = every tensor once (forward reads 2 and
+    writes 2, backward reads 4 and writes 2), against 8 TB/s."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    shape = (w.B, w.Mq, 4 * w.H * w.d)
+    dev = {n: t.cuda() for n, t in wl.make_gelu_inputs(shape, w.dtype, seed).items()}
+    fo = (torch.empty_like(dev["u"]), torch.empty_like(dev["u"]))
+    one = float(dev["u"].numel()) * dev["u"].element_size()
+    cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_gelu_jvp_fwd(dev["u"], dev["tu"], out=fo)),
+             "bwd": (6.0 * one, lambda: tvm.tvmattn_gelu_jvp_bwd(dev["u"], dev["tu"], dev["ga"], dev["gta"], out=fo))}
+    out = {"shape": list(shape)}
+    for name, (nbytes, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
+                     "frac": gbs / 8000.0}
+    return out
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -447,6 +478,7 @@ def main():
     if w.dtype == "bf16" and (w.H * w.d) % 8 == 0 and w.H * w.d <= 2048:
         out["adaln"] = adaln(w, args.steps)
         out["gate"] = gate(w, args.steps)
+        out["gelu"] = gelu(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

@@ -307,6 +307,27 @@ int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype,
                          void* gh, void* gth, float* gc, float* gtc,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * The activation between the MLP's two linear layers, with tangent (the MLP branch of the paper's block, App. "Full
+ * Description of Normalization of Modulation"; the JVP of Sec. 4 runs through it).  The paper does not name the
+ * activation: DiT's is taken, the GELU in its tanh form, gelu(u) = u/2 (1 + tanh(sqrt(2/pi) (u + 0.044715 u^3))):
+ *
+ *     a = gelu(u),   ta = gelu'(u) tu          (pointwise; the linear layers around it are plain matrix products)
+ *
+ *   in : u, tu   n elements of dtype each, contiguous, 16-byte aligned; n a whole number of 16-byte chunks
+ *   out: a, ta   likewise; must not alias an input
+ * One launch, no workspace.  Arithmetic is float32.
+ */
+int tvmattn_gelu_jvp_fwd(long long n, int dtype, const void* u, const void* tu, void* a, void* ta, void* hip_stream);
+
+/*
+ * Backward of the above: the gradient of <ga,a> + <gta,ta>:  gu = ga gelu'(u) + gta tu gelu''(u),  gtu = gta gelu'(u).
+ *   in : u, tu as given to the forward (nothing is saved); ga, gta n elements of dtype
+ *   out: gu, gtu
+ */
+int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
+                         void* gu, void* gtu, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

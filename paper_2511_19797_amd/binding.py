@@ -75,6 +75,10 @@ def lib():
         L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3 + [ctypes.c_size_t, _P]
         L.tvmattn_adaln_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_adaln_jvp_bwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 9 + [ctypes.c_size_t, _P]
+        L.tvmattn_gelu_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_gelu_jvp_fwd.argtypes = [ctypes.c_longlong, _I] + [_P] * 5
+        L.tvmattn_gelu_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_gelu_jvp_bwd.argtypes = [ctypes.c_longlong, _I] + [_P] * 7
         L.tvmattn_gate_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.tvmattn_gate_jvp_bwd_workspace_bytes.argtypes = [_I] * 4
         L.tvmattn_gate_jvp_fwd.restype = ctypes.c_int
@@ -362,3 +366,32 @@ def tvmattn_gate_jvp_bwd(h, th, c, tc, eps, gz, gtz, out=None, workspace=None):
                                       gz.data_ptr(), gtz.data_ptr(), *[t.data_ptr() for t in out], workspace.data_ptr(),
                                       workspace.numel(), _stream()))
     return out
+
+
+def _pointwise_args(first, *rest):
+    if not first.is_cuda or not first.is_contiguous():
+        raise ValueError("expected contiguous device tensors")
+    for t in rest:
+        if t.shape != first.shape or t.dtype != first.dtype or t.device != first.device or not t.is_contiguous():
+            raise ValueError("all tensors must agree in shape, dtype, device and be contiguous")
+    dt = TVMATTN_F32 if first.dtype == torch.float32 else TVMATTN_BF16 if first.dtype == torch.bfloat16 else None
+    if dt is None:
+        raise ValueError(f"unsupported dtype {first.dtype}")
+    return first.numel(), dt
+
+
+def tvmattn_gelu_jvp_fwd(u, tu, out=None):
+    """Returns (a, ta): the tanh-form GELU of u and its tangent gelu'(u) * tu."""
+    a, ta = out if out is not None else (torch.empty_like(u), torch.empty_like(u))
+    n, dt = _pointwise_args(u, tu, a, ta)
+    _check(lib().tvmattn_gelu_jvp_fwd(n, dt, u.data_ptr(), tu.data_ptr(), a.data_ptr(), ta.data_ptr(), _stream()))
+    return a, ta
+
+
+def tvmattn_gelu_jvp_bwd(u, tu, ga, gta, out=None):
+    """Returns (gu, gtu), the gradient of <ga, a> + <gta, ta>."""
+    gu, gtu = out if out is not None else (torch.empty_like(u), torch.empty_like(u))
+    n, dt = _pointwise_args(u, tu, ga, gta, gu, gtu)
+    _check(lib().tvmattn_gelu_jvp_bwd(n, dt, u.data_ptr(), tu.data_ptr(), ga.data_ptr(), gta.data_ptr(), gu.data_ptr(),
+                                      gtu.data_ptr(), _stream()))
+    return gu, gtu

@@ -124,6 +124,10 @@ struct GateArgs {
 hipError_t launch_gate_fwd(const GateArgs& a, int dtype, hipStream_t st);
 hipError_t launch_gate_bwd(const GateArgs& a, int dtype, hipStream_t st);
 bool adaln_supported(int C, int dtype);
+// The MLP's activation with tangent (n elements per tensor, a whole number of 16-byte chunks).
+hipError_t launch_gelu_fwd(long long n, int dtype, const void* u, const void* tu, void* a, void* ta, hipStream_t st);
+hipError_t launch_gelu_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
+                           void* gu, void* gtu, hipStream_t st);
 int adaln_wgs(int B, int T, bool backward);  // workgroups per batch element of the forward / backward token kernel
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st);

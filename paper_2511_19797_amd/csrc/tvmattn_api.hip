@@ -87,7 +87,7 @@ inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(sk
 
 extern "C" {
 
-int tvmattn_version(void) { return 500; }  // 0.5.0: AdaLN modulation and residual gate; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 500; }  // 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -491,6 +491,41 @@ int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype, const void* h, const vo
   g.eps = eps;
   return tvm::launch_gate_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                           : TVMATTN_LAUNCH_FAILED;
+}
+
+// ---- the MLP's activation with tangent
+namespace {
+int gelu_check(long long n, int dtype) {
+  if (n < 1) return TVMATTN_INVALID_ARG;
+  if (dtype != TVMATTN_F32 && dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
+  if (n % (dtype == TVMATTN_BF16 ? 8 : 4) != 0 || n > (1ll << 40)) return TVMATTN_UNSUPPORTED;
+  return TVMATTN_OK;
+}
+}  // namespace
+
+int tvmattn_gelu_jvp_fwd(long long n, int dtype, const void* u, const void* tu, void* a, void* ta, void* hip_stream) {
+  int rc = gelu_check(n, dtype);
+  if (rc) return rc;
+  const void* const in[] = {u, tu};
+  void* const out[] = {a, ta};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  return tvm::launch_gelu_fwd(n, dtype, u, tu, a, ta, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? TVMATTN_OK
+             : TVMATTN_LAUNCH_FAILED;
+}
+
+int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
+                         void* gu, void* gtu, void* hip_stream) {
+  int rc = gelu_check(n, dtype);
+  if (rc) return rc;
+  const void* const in[] = {u, tu, ga, gta};
+  void* const out[] = {gu, gtu};
+  rc = check_ptrs(in, out);
+  if (rc) return rc;
+  return tvm::launch_gelu_bwd(n, dtype, u, tu, ga, gta, gu, gtu, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? TVMATTN_OK
+             : TVMATTN_LAUNCH_FAILED;
 }
 
 }  // extern "C"

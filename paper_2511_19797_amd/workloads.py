@@ -149,6 +149,15 @@ def make_gate_inputs(B: int, T: int, C: int, dtype: str, seed: int):
     return out
 
 
+def make_gelu_inputs(shape, dtype: str, seed: int):
+    """Inputs of the MLP's activation: pre-activations u (standard normal, what a normalised, modulated token times a
+    freshly initialised weight gives), their tangent tu and the upstream gradients ga, gta, all of `shape`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    return {name: torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)).to(td).contiguous()
+            for name in ("u", "tu", "ga", "gta")}
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()

@@ -282,3 +282,26 @@ def test_gate_argument_rules(L):
         p = list(bins)
         p[k] = None
         assert bwd(p, brest) == -1
+
+
+def test_gelu_argument_rules(L):
+    I, P, LL = ctypes.c_int, ctypes.c_void_p, ctypes.c_longlong
+    L.tvmattn_gelu_jvp_fwd.argtypes = [LL, I] + [P] * 5
+    L.tvmattn_gelu_jvp_bwd.argtypes = [LL, I] + [P] * 7
+    ptr = [0x1000 * (i + 1) for i in range(6)]
+    fwd = lambda n, dt, p: L.tvmattn_gelu_jvp_fwd(n, dt, *p, None)
+    bwd = lambda n, dt, p: L.tvmattn_gelu_jvp_bwd(n, dt, *p, None)
+    assert fwd(0, 1, ptr[:4]) == -1 and fwd(-8, 1, ptr[:4]) == -1 and bwd(0, 1, ptr) == -1
+    assert fwd(12, 1, ptr[:4]) == -2 and fwd(6, 0, ptr[:4]) == -2 and fwd(8, 7, ptr[:4]) == -2 and bwd(12, 1, ptr) == -2
+    for k in range(4):
+        p = list(ptr[:4])
+        p[k] = None
+        assert fwd(64, 1, p) == -1
+        p[k] = ptr[k] + 8
+        assert fwd(64, 1, p) == -1
+    assert fwd(64, 1, [ptr[0], ptr[1], ptr[0], ptr[3]]) == -1 and fwd(64, 1, [ptr[0], ptr[1], ptr[2], ptr[2]]) == -1
+    for k in range(6):
+        p = list(ptr)
+        p[k] = None
+        assert bwd(64, 1, p) == -1
+    assert bwd(64, 1, ptr[:4] + [ptr[4], ptr[4]]) == -1 and bwd(64, 1, ptr[:4] + [ptr[1], ptr[5]]) == -1
