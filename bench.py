@@ -224,6 +224,31 @@ def one_sided(w, steps, seed=2024):
     return out
 
 
+def _timed_ms(fn, steps):
+    """Wall clock per call over `steps` calls after 3 warm-up calls, device synchronised on both sides."""
+    import torch
+
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def _hbm_cases(cases, steps):
+    """cases: name -> (algorithmic bytes per call, callable).  Times each and prices it against 8 TB/s."""
+    out = {}
+    for name, (nbytes, fn) in cases.items():
+        ms = _timed_ms(fn, steps)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
+                     "frac": gbs / 8000.0}
+    return out
+
+
 def qknorm(w, steps, seed=2024):
     """The QK-norm with tangent that feeds the attention (RMSNorm with gain, Sec. "Semi-Lipschitz control"),
     forward and backward on the workload's q and k, timed outside the timed region of the headline figure
@@ -252,22 +277,8 @@ def qknorm(w, steps, seed=2024):
                 lambda: tvm.tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gq, gk, 1e-6, dev["gO"], dev["gTO"], dev["v"], dev["tv"],
                                                    out=bo, workspace=ws)),
     }
-    def timed(fn):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
-    out = {}
-    for name, (nbytes, fn) in cases.items():
-        ms = timed(fn)
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
-                     "frac": gbs / 8000.0}
+    timed = lambda fn: _timed_ms(fn, steps)
+    out = _hbm_cases(cases, steps)
     # the block as the paper runs it: attention on the normalised tensors, then both backwards, as two calls and
     # as the one call that does the norm's backward in the attention kernels' epilogues (where that is served)
     if tvm.tvmattn_jvp_bwd_qknorm_workspace_bytes(q, k=k) > 0:
@@ -311,18 +322,7 @@ def adaln(w, steps, seed=2024):
     cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_adaln_jvp_fwd(*args, 1e-6, out=fo, workspace=ws)),
              "bwd": (6.0 * one, lambda: tvm.tvmattn_adaln_jvp_bwd(*args, 1e-6, dev["gy"], dev["gty"], out=bo, workspace=ws))}
     out = {"shape": {"B": B, "T": T, "C": C}}
-    for name, (nbytes, fn) in cases.items():
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
-                     "frac": gbs / 8000.0}
+    out.update(_hbm_cases(cases, steps))
     return out
 
 
@@ -349,18 +349,7 @@ def gate(w, steps, seed=2024):
              "bwd": (6.0 * one, lambda: tvm.tvmattn_gate_jvp_bwd(dev["h"], dev["th"], dev["c"], dev["tc"], 1e-6,
                                                                dev["gz"], dev["gtz"], out=bo, workspace=ws))}
     out = {"shape": {"B": B, "T": T, "C": C}}
-    for name, (nbytes, fn) in cases.items():
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
-                     "frac": gbs / 8000.0}
+    out.update(_hbm_cases(cases, steps))
     return out
 
 
@@ -380,18 +369,7 @@ def gelu(w, steps, seed=2024):
     cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_gelu_jvp_fwd(dev["u"], dev["tu"], out=fo)),
              "bwd": (6.0 * one, lambda: tvm.tvmattn_gelu_jvp_bwd(dev["u"], dev["tu"], dev["ga"], dev["gta"], out=fo))}
     out = {"shape": list(shape)}
-    for name, (nbytes, fn) in cases.items():
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        out[name] = {"ms": ms, "algorithmic_bytes": nbytes, "GBps": gbs, "bound": "hbm", "peak": 8000.0,
-                     "frac": gbs / 8000.0}
+    out.update(_hbm_cases(cases, steps))
     return out
 
 

@@ -6,14 +6,18 @@
 //     gelu'  = (1 + t)/2 + u/2 (1 - t^2) w'                      w'  = k (1 + 3 c u^2)
 //     gelu'' = (1 - t^2) w' + u/2 (1 - t^2) (w'' - 2 t w'^2)      w'' = 6 k c u
 // Backward of <ga, a> + <gta, ta>:  gu = ga gelu' + gta tu gelu'',  gtu = gta gelu'.
-// Memory-bound, pointwise: 16 bytes per thread and tensor, four chunks per thread in flight, float32 arithmetic,
-// tanh(w) = 1 - 2 / (exp(2w) + 1) (exact limits for large |w|: exp overflows to inf or underflows to 0).
+// Pointwise: 16 bytes per thread and tensor, float32 arithmetic, tanh(w) = 1 - 2 / (exp(2w) + 1) (exact limits for
+// large |w|: exp overflows to inf or underflows to 0).  About as much unpacked float32 arithmetic as memory time.
 #include "tvm_common.h"
 
 namespace tvm {
 namespace {
 
-constexpr int kNT = 256, kUnroll = 4;
+#ifndef GELU_UNROLL
+#define GELU_UNROLL 1     // chunks per thread in flight (1 with a thread per chunk measured best: 108 / 168 us
+#define GELU_MAXGRID 65535  // forward / backward at 16 x 1024 x 4608 against 114 / 177 us with 4 and 8192 workgroups)
+#endif
+constexpr int kNT = 256, kUnroll = GELU_UNROLL;
 constexpr float kK = 0.7978845608028654f, kC = 0.044715f, kTwoLog2e = 2.8853900817779268f;
 
 template <typename T>
@@ -38,18 +42,21 @@ __device__ __forceinline__ uint4 narrow(const float (&in)[Chunk<T>::VEC]) {
 struct Gelu {
   float half_1pt, g1, g2;  // (1 + t)/2, gelu', gelu''
 };
+// With e = exp(2w) and r = 1/(e + 1):  t = 1 - 2r,  (1 + t)/2 = 1 - r =: h,  1 - t^2 = 4 r h.  For large |w| the
+// exponential overflows to inf (r = 0, h = 1) or underflows to 0 (r = 1, h = 0): the limits come out exact.
 template <bool SECOND>
 __device__ __forceinline__ Gelu gelu_parts(float u) {
   const float u2 = u * u;
-  const float w = kK * u * fmaf(kC, u2, 1.0f);
-  const float e = __builtin_amdgcn_exp2f(kTwoLog2e * w);
-  const float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
-  const float s = 1.0f - t * t, wp = kK * fmaf(3.0f * kC, u2, 1.0f);
+  const float e = __builtin_amdgcn_exp2f(u * fmaf(kTwoLog2e * kK * kC, u2, kTwoLog2e * kK));  // exp(2w)
+  const float r = __builtin_amdgcn_rcpf(e + 1.0f);
+  const float h = 1.0f - r;
+  const float q = u * r * h;                               // u (1 - t^2) / 4
+  const float wp = fmaf(3.0f * kK * kC, u2, kK);           // w'
   Gelu g;
-  g.half_1pt = 0.5f + 0.5f * t;
-  const float hus = 0.5f * u * s;
-  g.g1 = fmaf(hus, wp, g.half_1pt);
-  g.g2 = SECOND ? fmaf(hus, 6.0f * kK * kC * u - 2.0f * t * wp * wp, s * wp) : 0.f;
+  g.half_1pt = h;
+  g.g1 = fmaf(2.0f * q, wp, h);
+  // gelu'' = (1 - t^2) w' + u/2 (1 - t^2) (w'' - 2 t w'^2),  t = 1 - 2r
+  g.g2 = SECOND ? fmaf(2.0f * q, fmaf(wp * wp, fmaf(4.0f, r, -2.0f), 6.0f * kK * kC * u), 4.0f * r * h * wp) : 0.f;
   return g;
 }
 
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(kNT) void gelu_bwd_kernel(const uint4* __restrict__
 
 int grid_for(long long chunks) {
   const long long want = (chunks + (long long)kNT * kUnroll - 1) / ((long long)kNT * kUnroll);
-  return (int)(want < 1 ? 1 : want > 8192 ? 8192 : want);
+  return (int)(want < 1 ? 1 : want > GELU_MAXGRID ? GELU_MAXGRID : want);
 }
 
 }  // namespace
