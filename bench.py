@@ -224,6 +224,42 @@ def one_sided(w, steps, seed=2024):
     return out
 
 
+def graph_step(w, steps, ramp_ms=100.0, seed=2024):
+    """One forward + backward step captured in a HIP graph (the library allocates nothing, issues no memset and never
+    synchronises, so it can be captured as it is) and replayed `steps` times: what a training loop that captures
+    its step pays per step, without the caller's per-call overhead.  Wall clock per replay."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    dev = {n: t.cuda() for n, t in wl.make_inputs(w, seed).items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    fo = tvm.tvmattn_jvp_fwd(*six)
+    go = tvm.tvmattn_jvp_bwd(*six, *fo, dev["gO"], dev["gTO"])
+    ws = torch.empty(max(tvm.tvmattn_jvp_bwd_workspace_bytes(six[0], k=six[1]), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        tvm.tvmattn_jvp_fwd(*six, out=fo)
+        tvm.tvmattn_jvp_bwd(*six, *fo, dev["gO"], dev["gTO"], out=go, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    t0 = time.perf_counter()  # the same 100 ms under load as the eager measurement gets (the clock ramps up)
+    while time.perf_counter() - t0 < ramp_ms * 1e-3:
+        graph.replay()
+        torch.cuda.synchronize()
+    ms = _timed_ms(graph.replay, steps)
+    return {"ms_per_step": ms, "tflops": 42.0 * w.B * w.H * w.Mq * w.N * w.d / (ms * 1e-3) / 1e12}
+
+
 def _timed_ms(fn, steps):
     """Wall clock per call over `steps` calls after 3 warm-up calls, device synchronised on both sides."""
     import torch
@@ -452,6 +488,8 @@ def main():
         "kernels": res["kernels"], "roofline": roofline, "also": also,
     }
     out["one_sided"] = one_sided(w, args.steps)
+    out["graph_replay"] = {name: graph_step(wl.CONFIGS[name], args.steps, args.ramp_ms) for name in dict.fromkeys([w.name] + list(also))
+                           if name in wl.CONFIGS}
     out["qknorm"] = qknorm(w, args.steps)
     if w.dtype == "bf16" and (w.H * w.d) % 8 == 0 and w.H * w.d <= 2048:
         out["adaln"] = adaln(w, args.steps)
