@@ -193,7 +193,6 @@ __global__ __launch_bounds__(64 * NW) void adaln_fwd_kernel(AdalnArgs a) {
   }
 }
 
-constexpr int kTotalBwd = 512;
 template <typename T, int NW, int R>
 __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
   constexpr int VEC = Chunk<T>::VEC, K = 5 * R;
@@ -531,7 +530,20 @@ __global__ __launch_bounds__(kModNT) void gate_mod_bwd_kernel(GateArgs a) {
 template <typename T>
 int waves_per_row(int C) { return (C / Chunk<T>::VEC + 63) / 64; }
 
-constexpr int kRowsFwd = 4, kRowsBwd = 4;
+// Rows per pass and the number of workgroups aimed at, measured at 16 x 1024 tokens x 1152 (us per call with the
+// tail kernel): AdaLN backward 2 rows on 1024 workgroups 57-58 (4 on 512: 63, 2 on 512: 63, 1 on 1024: 58, 2 on
+// 2048: 73, 8 on 512: 88); gate backward 2 on 256: 41 (4 on 512: 45, 4 on 256: 44, 2 on 384: 42.5, 1 on 256: 46, 4 on
+// 128: 54): fewer workgroups leave fewer partial rows to the tail kernel, shorter passes stall less at the
+// barrier.  Forward 4 on 1024 (2 or 8 rows, 768 or 2048 workgroups: the same or worse).
+#ifndef ADALN_RF
+#define ADALN_RF 4
+#define ADALN_TF 1024
+#define ADALN_RB 2
+#define ADALN_TB 1024
+#define GATE_RB 2
+#define GATE_TB 256
+#endif
+constexpr int kRowsFwd = ADALN_RF, kRowsBwd = ADALN_RB, kRowsGateBwd = GATE_RB;
 
 }  // namespace
 
@@ -546,8 +558,9 @@ constexpr int kRowsFwd = 4, kRowsBwd = 4;
 
 // Workgroups per batch element: R token rows per pass, at most about `total` workgroups in all, and every one the
 // same number of passes where T allows.
-int adaln_wgs(int B, int T, bool backward) {
-  const int R = backward ? kRowsBwd : kRowsFwd, total = backward ? kTotalBwd : 1024;
+int adaln_wgs(int B, int T, bool backward, bool gate) {
+  const int R = !backward ? kRowsFwd : gate ? kRowsGateBwd : kRowsBwd;
+  const int total = !backward ? ADALN_TF : gate ? GATE_TB : ADALN_TB;
   const int groups = (T + R - 1) / R, cap = total / B > 1 ? total / B : 1;
   const int passes = (groups + cap - 1) / cap;
   return (groups + passes - 1) / passes;
@@ -571,9 +584,9 @@ hipError_t launch_gate_fwd(const GateArgs& a, int dtype, hipStream_t st) {
 hipError_t launch_gate_bwd(const GateArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(a.nwg, a.B);
   if (dtype == 1) {
-    TVM_ADALN_BY_SIZE(gate_bwd_kernel, bf16, kRowsBwd)
+    TVM_ADALN_BY_SIZE(gate_bwd_kernel, bf16, kRowsGateBwd)
   } else {
-    TVM_ADALN_BY_SIZE(gate_bwd_kernel, float, kRowsBwd)
+    TVM_ADALN_BY_SIZE(gate_bwd_kernel, float, kRowsGateBwd)
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -128,7 +128,7 @@ bool adaln_supported(int C, int dtype);
 hipError_t launch_gelu_fwd(long long n, int dtype, const void* u, const void* tu, void* a, void* ta, hipStream_t st);
 hipError_t launch_gelu_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
                            void* gu, void* gtu, hipStream_t st);
-int adaln_wgs(int B, int T, bool backward);  // workgroups per batch element of the forward / backward token kernel
+int adaln_wgs(int B, int T, bool backward, bool gate);  // workgroups per batch element of a token kernel
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st);
 

@@ -353,7 +353,7 @@ int adaln_check(int B, int T, int C, int dtype, float eps) {
 // The forward needs no workspace any more; the query keeps a non-zero answer for valid shapes (0 = unsupported).
 constexpr size_t kAdalnFwdWorkspace = 256;
 size_t adaln_part_bytes(int B, int T, int C) {
-  return pad256((size_t)B * tvm::adaln_wgs(B, T, true) * 4 * C * sizeof(float));
+  return pad256((size_t)B * tvm::adaln_wgs(B, T, true, false) * 4 * C * sizeof(float));
 }
 }  // namespace
 
@@ -383,7 +383,7 @@ int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const v
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = tvm::adaln_wgs(B, T, false);
+  g.nwg = tvm::adaln_wgs(B, T, false, false);
   g.eps = eps;
   return tvm::launch_adaln_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
@@ -424,7 +424,7 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = tvm::adaln_wgs(B, T, true);
+  g.nwg = tvm::adaln_wgs(B, T, true, false);
   g.eps = eps;
   return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
@@ -433,7 +433,7 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
 // ---- normalised gate of a residual branch with tangent
 size_t tvmattn_gate_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
   if (adaln_check(B, T, C, dtype, 0.f)) return 0;
-  return pad256((size_t)B * tvm::adaln_wgs(B, T, true) * 2 * C * sizeof(float));
+  return pad256((size_t)B * tvm::adaln_wgs(B, T, true, true) * 2 * C * sizeof(float));
 }
 
 int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype, const void* x, const void* tx, const void* h, const void* th,
@@ -456,7 +456,7 @@ int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype, const void* x, const vo
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = tvm::adaln_wgs(B, T, false);
+  g.nwg = tvm::adaln_wgs(B, T, false, true);
   g.eps = eps;
   return tvm::launch_gate_fwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                           : TVMATTN_LAUNCH_FAILED;
@@ -487,7 +487,7 @@ int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype, const void* h, const vo
   g.B = B;
   g.T = T;
   g.C = C;
-  g.nwg = tvm::adaln_wgs(B, T, true);
+  g.nwg = tvm::adaln_wgs(B, T, true, true);
   g.eps = eps;
   return tvm::launch_gate_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                           : TVMATTN_LAUNCH_FAILED;
