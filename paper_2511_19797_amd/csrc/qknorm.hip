@@ -268,6 +268,48 @@ __global__ __launch_bounds__(kRedCols * kRedSlices) void qknorm_gain_grad_kernel
   }
 }
 
+// The same for D a multiple of 4 (16-byte aligned partial rows): a thread takes one 16-byte chunk of columns and one
+// slice of the rows, as many slices as 1024 threads give (56 at D = 72: 18 rows each of 1024, all loads of a slice in
+// flight within two or three round trips instead of eight); the slices meet in LDS and are added in order.
+constexpr int kRed4NT = 1024;
+__global__ __launch_bounds__(kRed4NT) void qknorm_gain_grad4_kernel(NormArgs a) {
+  __shared__ float red[kRed4NT * 4];  // [slices][D], slices * D <= 4096
+  const NormSide s = blockIdx.x ? a.side[1] : a.side[0];
+  const int nch = a.D >> 2, slices = kRed4NT / nch;
+  const int ch = threadIdx.x % nch, sl = threadIdx.x / nch;
+  if (sl < slices) {
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4* p = reinterpret_cast<const float4*>(s.part) + ch;
+    int w = sl;
+    for (; w + 7 * slices < s.nwg; w += 8 * slices) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(long long)(w + u * slices) * nch];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        sum.x += v[u].x;
+        sum.y += v[u].y;
+        sum.z += v[u].z;
+        sum.w += v[u].w;
+      }
+    }
+    for (; w < s.nwg; w += slices) {
+      const float4 v = p[(long long)w * nch];
+      sum.x += v.x;
+      sum.y += v.y;
+      sum.z += v.z;
+      sum.w += v.w;
+    }
+    *reinterpret_cast<float4*>(red + sl * a.D + 4 * ch) = sum;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < a.D) {
+    float t = 0.f;
+    for (int k = 0; k < slices; ++k) t += red[k * a.D + threadIdx.x];
+    s.gg[threadIdx.x] = t;
+  }
+}
+
 }  // namespace
 
 // Kernel choice: chunks per lane from D, and whether D is a whole number of 16-byte chunks.
@@ -294,13 +336,22 @@ hipError_t launch_qknorm_fwd(const NormArgs& a, int dtype, hipStream_t st) {
   return hipGetLastError();
 }
 
+namespace {
+void launch_gain_grad(const NormArgs& a, hipStream_t st) {
+  if (a.D % 4 == 0 && a.D <= 1024)  // (the norm kernels take D <= 256)
+    hipLaunchKernelGGL(qknorm_gain_grad4_kernel, dim3(2), dim3(kRed4NT), 0, st, a);
+  else
+    hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2, (a.D + kRedCols - 1) / kRedCols), dim3(kRedCols * kRedSlices), 0,
+                       st, a);
+}
+}  // namespace
+
 hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(a.side[0].nwg + a.side[1].nwg), block(kNT);
   TVM_NORM_BY_TYPE(qknorm_bwd_kernel);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2, (a.D + kRedCols - 1) / kRedCols), dim3(kRedCols * kRedSlices), 0,
-                     st, a);
+  launch_gain_grad(a, st);
   return hipGetLastError();
 }
 
@@ -317,7 +368,7 @@ hipError_t launch_gain_grad_sum(const float* part_q, int rows_q, float* gg_q, co
   a.side[1].part = const_cast<float*>(part_k);
   a.side[1].nwg = rows_k;
   a.side[1].gg = gg_k;
-  hipLaunchKernelGGL(qknorm_gain_grad_kernel, dim3(2, (D + kRedCols - 1) / kRedCols), dim3(kRedCols * kRedSlices), 0, st, a);
+  launch_gain_grad(a, st);
   return hipGetLastError();
 }
 
