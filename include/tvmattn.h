@@ -274,6 +274,19 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same with the gradients that reach x and tx by another way added on the way out: in the block, x feeds the
+ * modulation and also runs on along the residual connection, so its gradient is the stream's (gres, gtres) plus the
+ * modulation's.  gres, gtres: [B,T,C] dtype, both given or both NULL (NULL: the call above); gx may not alias them.
+ * Saves the pass over six tensors that a separate addition would take.
+ */
+int tvmattn_adaln_jvp_bwd_residual(int B, int T, int C, int dtype,
+                                   const void* x, const void* tx,
+                                   const float* a, const float* ta, const float* b, const float* tb, float eps,
+                                   const void* gy, const void* gty, const void* gres, const void* gtres,
+                                   void* gx, void* gtx, float* ga, float* gta, float* gb, float* gtb,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Normalised gate of a residual branch with tangent: how the output h of ATTN or of MLP re-enters the residual
  * stream in the paper's block (App. "Full Description of Normalization of Modulation", the two layer equations):
  *

@@ -75,6 +75,8 @@ def lib():
         L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3 + [ctypes.c_size_t, _P]
         L.tvmattn_adaln_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_adaln_jvp_bwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 9 + [ctypes.c_size_t, _P]
+        L.tvmattn_adaln_jvp_bwd_residual.restype = ctypes.c_int
+        L.tvmattn_adaln_jvp_bwd_residual.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 11 + [ctypes.c_size_t, _P]
         L.tvmattn_gelu_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_gelu_jvp_fwd.argtypes = [ctypes.c_longlong, _I] + [_P] * 5
         L.tvmattn_gelu_jvp_bwd.restype = ctypes.c_int
@@ -322,20 +324,30 @@ def tvmattn_adaln_jvp_fwd(x, tx, a, ta, b, tb, eps, out=None, workspace=None):
     return y, ty
 
 
-def tvmattn_adaln_jvp_bwd(x, tx, a, ta, b, tb, eps, gy, gty, out=None, workspace=None):
-    """Returns (gx, gtx, ga, gta, gb, gtb)."""
+def tvmattn_adaln_jvp_bwd(x, tx, a, ta, b, tb, eps, gy, gty, out=None, workspace=None, gres=None, gtres=None):
+    """Returns (gx, gtx, ga, gta, gb, gtb).  gres, gtres (both or neither): gradients that reach x and tx along the
+    residual connection, added to gx and gtx (tvmattn_adaln_jvp_bwd_residual)."""
     B, T, C, dt = _adaln_args(x, tx, (a, ta, b, tb))
     _adaln_args(gy, gty, ())
     if gy.shape != x.shape or gy.dtype != x.dtype:
         raise ValueError("upstream gradients must look like x")
+    if (gres is None) != (gtres is None):
+        raise ValueError("gres and gtres come together")
+    if gres is not None:
+        _adaln_args(gres, gtres, ())
+        if gres.shape != x.shape or gres.dtype != x.dtype:
+            raise ValueError("residual gradients must look like x")
     if out is None:
         out = (torch.empty_like(x), torch.empty_like(x)) + tuple(torch.empty_like(a) for _ in range(4))
     need = int(lib().tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, dt))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _check(lib().tvmattn_adaln_jvp_bwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(), b.data_ptr(),
-                                       tb.data_ptr(), float(eps), gy.data_ptr(), gty.data_ptr(),
-                                       *[t.data_ptr() for t in out], workspace.data_ptr(), workspace.numel(), _stream()))
+    _check(lib().tvmattn_adaln_jvp_bwd_residual(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(),
+                                                b.data_ptr(), tb.data_ptr(), float(eps), gy.data_ptr(), gty.data_ptr(),
+                                                gres.data_ptr() if gres is not None else None,
+                                                gtres.data_ptr() if gtres is not None else None,
+                                                *[t.data_ptr() for t in out], workspace.data_ptr(), workspace.numel(),
+                                                _stream()))
     return out
 
 

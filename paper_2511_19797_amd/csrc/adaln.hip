@@ -193,7 +193,9 @@ __global__ __launch_bounds__(64 * NW) void adaln_fwd_kernel(AdalnArgs a) {
   }
 }
 
-template <typename T, int NW, int R>
+// RES: the gradients that reach x and tx by another way (a residual connection around the modulated branch) are
+// added to gx and gtx on the way out.
+template <typename T, int NW, int R, bool RES>
 __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
   constexpr int VEC = Chunk<T>::VEC, K = 5 * R;
   __shared__ float red[2 * NW * K];
@@ -211,11 +213,14 @@ __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
   const T* gtb_ = static_cast<const T*>(a.gty) + bo;
   T* gxb = static_cast<T*>(a.y) + bo;
   T* gtxb = static_cast<T*>(a.ty) + bo;
+  const T* grb = RES ? static_cast<const T*>(a.gres) + bo : nullptr;
+  const T* gtrb = RES ? static_cast<const T*>(a.gtres) + bo : nullptr;
   float pa[VEC], pta[VEC], pb[VEC], ptb[VEC];  // this thread's columns summed over the workgroup's tokens
 #pragma unroll
   for (int e = 0; e < VEC; ++e) pa[e] = pta[e] = pb[e] = ptb[e] = 0.f;
   struct Rows {
     Raw<T> x[R], tx[R], gy[R], gty[R];  // as loaded; widened where used
+    Raw<T> gr[RES ? R : 1], gtr[RES ? R : 1];
   };
   // rows beyond the last one are read as the last one and take no further part
   auto load = [&](Rows& q, int t0) {
@@ -226,6 +231,10 @@ __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
       q.tx[j] = load_raw<T>(tb_ + off);
       q.gy[j] = load_raw<T>(gyb + off);
       q.gty[j] = load_raw<T>(gtb_ + off);
+      if constexpr (RES) {
+        q.gr[j] = load_raw<T>(grb + off);
+        q.gtr[j] = load_raw<T>(gtrb + off);
+      }
     }
   };
   auto pass = [&](Rows& q, int t0, int par) {
@@ -286,6 +295,16 @@ __global__ __launch_bounds__(64 * NW) void adaln_bwd_kernel(AdalnArgs a) {
         pta[e] = fmaf(gty[e], xh, pta[e]);
         pb[e] = fmaf(gy[e], rowf, pb[e]);
         ptb[e] = fmaf(gty[e], rowf, ptb[e]);
+      }
+      if constexpr (RES) {
+        float r0[VEC], r1[VEC];
+        widen<T>(r0, q.gr[j]);
+        widen<T>(r1, q.gtr[j]);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          gx[e] += r0[e];
+          gtx[e] += r1[e];
+        }
       }
       if (live && t0 + j < a.T) {
         const long long off = (long long)(t0 + j) * a.C;
@@ -547,12 +566,12 @@ constexpr int kRowsFwd = ADALN_RF, kRowsBwd = ADALN_RB, kRowsGateBwd = GATE_RB;
 
 }  // namespace
 
-#define TVM_ADALN_BY_SIZE(KERNEL, T, R)                                                              \
+#define TVM_ADALN_BY_SIZE(KERNEL, T, ...)                                                            \
   switch (waves_per_row<T>(a.C)) {                                                                   \
-    case 1: hipLaunchKernelGGL((KERNEL<T, 1, R>), grid, dim3(64), 0, st, a); break;                  \
-    case 2: hipLaunchKernelGGL((KERNEL<T, 2, R>), grid, dim3(128), 0, st, a); break;                 \
-    case 3: hipLaunchKernelGGL((KERNEL<T, 3, R>), grid, dim3(192), 0, st, a); break;                 \
-    case 4: hipLaunchKernelGGL((KERNEL<T, 4, R>), grid, dim3(256), 0, st, a); break;                 \
+    case 1: hipLaunchKernelGGL((KERNEL<T, 1, __VA_ARGS__>), grid, dim3(64), 0, st, a); break;        \
+    case 2: hipLaunchKernelGGL((KERNEL<T, 2, __VA_ARGS__>), grid, dim3(128), 0, st, a); break;       \
+    case 3: hipLaunchKernelGGL((KERNEL<T, 3, __VA_ARGS__>), grid, dim3(192), 0, st, a); break;       \
+    case 4: hipLaunchKernelGGL((KERNEL<T, 4, __VA_ARGS__>), grid, dim3(256), 0, st, a); break;       \
     default: return hipErrorNotSupported;                                                            \
   }
 
@@ -607,9 +626,17 @@ hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st) {
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st) {
   const dim3 grid(a.nwg, a.B);
   if (dtype == 1) {
-    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, bf16, kRowsBwd)
+    if (a.gres) {
+      TVM_ADALN_BY_SIZE(adaln_bwd_kernel, bf16, kRowsBwd, true)
+    } else {
+      TVM_ADALN_BY_SIZE(adaln_bwd_kernel, bf16, kRowsBwd, false)
+    }
   } else {
-    TVM_ADALN_BY_SIZE(adaln_bwd_kernel, float, kRowsBwd)
+    if (a.gres) {
+      TVM_ADALN_BY_SIZE(adaln_bwd_kernel, float, kRowsBwd, true)
+    } else {
+      TVM_ADALN_BY_SIZE(adaln_bwd_kernel, float, kRowsBwd, false)
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -103,6 +103,7 @@ hipError_t launch_qknorm_bwd(const NormArgs& a, int dtype, hipStream_t st);
 // Normalised adaptive-layer-norm modulation with tangent (adaln.hip).
 struct AdalnArgs {
   const void *x, *tx, *gy, *gty;    // [B,T,C] dtype, contiguous (gy, gty: backward only)
+  const void *gres = nullptr, *gtres = nullptr;  // backward, optional (both or neither): added to the gradients of x, tx
   const float *a, *ta, *b, *tb;     // [B,C] float32
   void *y, *ty;                     // forward: outputs; backward: gradients of x and tx
   float* part;                      // backward workspace [B][nwg][4][C]: per-workgroup sums over tokens

@@ -394,13 +394,14 @@ size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype) {
   return adaln_part_bytes(B, T, C);
 }
 
-int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
-                          const float* b, const float* tb, float eps, const void* gy, const void* gty, void* gx,
+int tvmattn_adaln_jvp_bwd_residual(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
+                          const float* b, const float* tb, float eps, const void* gy, const void* gty, const void* gres, const void* gtres, void* gx,
                           void* gtx, float* ga, float* gta, float* gb, float* gtb, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
   int rc = adaln_check(B, T, C, dtype, eps);
   if (rc) return rc;
-  const void* const in[] = {x, tx, a, ta, b, tb, gy, gty};
+  if ((gres == nullptr) != (gtres == nullptr)) return TVMATTN_INVALID_ARG;
+  const void* const in[] = {x, tx, a, ta, b, tb, gy, gty, unless(!gres, gres), unless(!gtres, gtres)};
   void* const out[] = {gx, gtx, ga, gta, gb, gtb, workspace};
   rc = check_ptrs(in, out);
   if (rc) return rc;
@@ -410,6 +411,8 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.tx = tx;
   g.gy = gy;
   g.gty = gty;
+  g.gres = gres;
+  g.gtres = gtres;
   g.a = a;
   g.ta = ta;
   g.b = b;
@@ -428,6 +431,14 @@ int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const v
   g.eps = eps;
   return tvm::launch_adaln_bwd(g, dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TVMATTN_OK
                                                                                            : TVMATTN_LAUNCH_FAILED;
+}
+
+int tvmattn_adaln_jvp_bwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
+                          const float* b, const float* tb, float eps, const void* gy, const void* gty, void* gx,
+                          void* gtx, float* ga, float* gta, float* gb, float* gtb, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  return tvmattn_adaln_jvp_bwd_residual(B, T, C, dtype, x, tx, a, ta, b, tb, eps, gy, gty, nullptr, nullptr, gx, gtx, ga,
+                                        gta, gb, gtb, workspace, workspace_bytes, hip_stream);
 }
 
 // ---- normalised gate of a residual branch with tangent

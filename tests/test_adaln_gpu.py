@@ -79,3 +79,28 @@ def test_unsupported_sizes_are_refused():
     with pytest.raises(tvm.TvmattnError) as ei:
         tvm.tvmattn_adaln_jvp_fwd(dev["x"], dev["tx"], dev["a"], dev["ta"], dev["b"], dev["tb"], EPS)
     assert ei.value.status == -2
+
+
+def test_backward_with_the_residual_gradients_added():
+    """gres, gtres are added to gx, gtx: the gradient of <gy,y> + <gty,ty> + <gres,x> + <gtres,tx>.  The other four
+    gradients are those of the plain call, bit for bit."""
+    for B, T, C, dtype in ((2, 37, 1152, "bf16"), (1, 9, 260, "f32")):
+        announce(f"adaln backward with residual gradients B{B} T{T} C{C} {dtype}")
+        inp = wl.make_adaln_inputs(B, T, C, dtype, 85)
+        res = wl.make_gate_inputs(B, T, C, dtype, 86)      # any two [B,T,C] tensors: its gz, gtz
+        dev = {n: t.cuda() for n, t in inp.items()}
+        gres, gtres = res["gz"].cuda(), res["gtz"].cuda()
+        six = [dev[n] for n in ("x", "tx", "a", "ta", "b", "tb")]
+        plain = tvm.tvmattn_adaln_jvp_bwd(*six, EPS, dev["gy"], dev["gty"])
+        fused = tvm.tvmattn_adaln_jvp_bwd(*six, EPS, dev["gy"], dev["gty"], gres=gres, gtres=gtres)
+        torch.cuda.synchronize()
+        for k in range(2, 6):
+            assert torch.equal(plain[k], fused[k])
+        f = {n: wl.to_f64(t) for n, t in inp.items()}
+        ref = orc.adaln_jvp_bwd(f["x"], f["tx"], f["a"], f["ta"], f["b"], f["tb"], EPS, f["gy"], f["gty"])
+        want = (ref[0] + wl.to_f64(res["gz"]), ref[1] + wl.to_f64(res["gtz"]))
+        for k in range(2):
+            e = pu.rel_err(fused[k].float().cpu().numpy(), want[k])
+            assert e <= pu.TOL[dtype], (k, e)
+        with pytest.raises(ValueError):
+            tvm.tvmattn_adaln_jvp_bwd(*six, EPS, dev["gy"], dev["gty"], gres=gres)

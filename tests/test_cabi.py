@@ -245,6 +245,13 @@ def test_adaln_argument_rules(L):
         p = list(brest)
         p[k] = None
         assert bwd(ins, p) == -1
+    # the variant that adds the residual connection's gradients: both or neither, aligned, not aliased by an output
+    L.tvmattn_adaln_jvp_bwd_residual.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 11 + [Z, P]
+    res = lambda g, gt, r=brest, ws=nb - 1: L.tvmattn_adaln_jvp_bwd_residual(B, T, C, 1, *ins, 1e-6, r[0], r[1], g, gt, *r[2:],
+                                                                          ws, None)
+    assert res(None, None) == -3 and res(0x20000, 0x21000) == -3
+    assert res(0x20000, None) == -1 and res(None, 0x21000) == -1 and res(0x20004, 0x21000) == -1
+    assert res(brest[2], 0x21000) == -1     # gx aliases gres
 
 
 def test_gate_argument_rules(L):
