@@ -252,12 +252,14 @@ def graph_step(w, steps, ramp_ms=100.0, seed=2024):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
         step()
-    t0 = time.perf_counter()  # the same 100 ms under load as the eager measurement gets (the clock ramps up)
+    t0, ramp = time.perf_counter(), 0  # the same 100 ms under load as the eager measurement gets (the clock ramps up)
     while time.perf_counter() - t0 < ramp_ms * 1e-3:
         graph.replay()
         torch.cuda.synchronize()
+        ramp += 1
     ms = _timed_ms(graph.replay, steps)
-    return {"ms_per_step": ms, "tflops": 42.0 * w.B * w.H * w.Mq * w.N * w.d / (ms * 1e-3) / 1e12}
+    # launches: every step this function ran, eager or replayed (2 eager, the ramp, 3 warm-up replays, the timed ones)
+    return {"ms_per_step": ms, "launches": 2 + ramp + 3 + steps, "tflops": 42.0 * w.B * w.H * w.Mq * w.N * w.d / (ms * 1e-3) / 1e12}
 
 
 def _timed_ms(fn, steps):
