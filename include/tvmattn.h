@@ -296,7 +296,8 @@ int tvmattn_adaln_jvp_bwd_residual(int B, int T, int C, int dtype,
  *   in : x, tx, h, th    [B,T,C] dtype, contiguous: the stream, the branch output, and their tangents
  *        c, tc           [B,C] float32, contiguous: the gate of the token's batch element and its tangent
  *        eps             >= 0, finite
- *   out: z, tz           [B,T,C] dtype; must not alias an input
+ *   out: z, tz           [B,T,C] dtype; z may be x itself and tz may be tx itself (the stream updated in place);
+ *                        no other aliasing of an input
  * Shape limits as for tvmattn_adaln_jvp_fwd.  One launch, no workspace.  Arithmetic is float32.
  */
 int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype,

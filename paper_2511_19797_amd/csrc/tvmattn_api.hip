@@ -451,8 +451,11 @@ int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype, const void* x, const vo
                          const float* c, const float* tc, float eps, void* z, void* tz, void* hip_stream) {
   int rc = adaln_check(B, T, C, dtype, eps);
   if (rc) return rc;
-  const void* const in[] = {x, tx, h, th, c, tc};
+  // the stream may be updated in place (z = x and tz = tx, each exactly): a thread reads its 16 bytes of x and tx
+  // before it writes the same 16 bytes of z and tz, and nobody else touches them
+  const void* const in[] = {z == x ? skip : x, tz == tx ? skip : tx, h, th, c, tc};
   void* const out[] = {z, tz};
+  if (!x || !tx || !aligned16(x) || !aligned16(tx)) return TVMATTN_INVALID_ARG;
   rc = check_ptrs(in, out);
   if (rc) return rc;
   tvm::GateArgs g{};

@@ -276,7 +276,8 @@ def test_gate_argument_rules(L):
         assert fwd(p, outs) == -1
         p[k] = ins[k] + 4     # not 16-byte aligned
         assert fwd(p, outs) == -1
-    assert fwd(ins, [outs[0], outs[0]]) == -1 and fwd(ins, [ins[0], outs[1]]) == -1   # aliasing
+    assert fwd(ins, [outs[0], outs[0]]) == -1 and fwd(ins, [ins[1], outs[1]]) == -1 and fwd(ins, [outs[0], ins[2]]) == -1
+    # (z = x and tz = tx exactly are allowed: the stream updated in place; they pass the checks and would launch)
     bins = [0x1000 * (i + 1) for i in range(4)]          # h, th, c, tc
     brest = [0x1000 * (i + 5) for i in range(7)]         # gz, gtz, gh, gth, gc, gtc, workspace
     bwd = lambda i, r, ws=nb - 1: L.tvmattn_gate_jvp_bwd(B, T, C, 1, *i, 1e-6, *r, ws, None)

@@ -88,3 +88,17 @@ def test_unsupported_sizes_raise():
         tvm.tvmattn_gate_jvp_fwd(dev["x"], dev["tx"], dev["h"], dev["th"], dev["c"], dev["tc"], EPS)
     with pytest.raises(tvm.TvmattnError):
         tvm.tvmattn_gate_jvp_bwd(dev["h"], dev["th"], dev["c"], dev["tc"], EPS, dev["gz"], dev["gtz"])
+
+
+def test_stream_updated_in_place():
+    """z = x and tz = tx as the same buffers: the same bits as the out-of-place call."""
+    announce("gate in place B2 T130 C1152 bf16")
+    inp = wl.make_gate_inputs(2, 130, 1152, "bf16", 95)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    z, tz = tvm.tvmattn_gate_jvp_fwd(dev["x"], dev["tx"], dev["h"], dev["th"], dev["c"], dev["tc"], EPS)
+    x, tx = dev["x"].clone(), dev["tx"].clone()
+    tvm.tvmattn_gate_jvp_fwd(x, tx, dev["h"], dev["th"], dev["c"], dev["tc"], EPS, out=(x, tx))
+    torch.cuda.synchronize()
+    assert torch.equal(x, z) and torch.equal(tx, tz)
+    with pytest.raises(tvm.TvmattnError):   # any other aliasing is refused
+        tvm.tvmattn_gate_jvp_fwd(dev["x"], dev["tx"], dev["h"], dev["th"], dev["c"], dev["tc"], EPS, out=(dev["tx"], tz))
