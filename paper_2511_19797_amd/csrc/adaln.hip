@@ -29,6 +29,7 @@ struct alignas(16) Chunk {
 template <typename T> using Raw = uint4;
 // Nothing is done to the bytes on the way in (arithmetic right behind a load makes the compiler wait for it there
 // and then): idle threads read a valid address like the others and drop their share of the sums instead.
+// (Non-temporal loads, which gain 5 % in the activation kernels, lose here: forward +10 %, gate backward +40 %.)
 template <typename T>
 __device__ __forceinline__ Raw<T> load_raw(const T* p) {
   return *reinterpret_cast<const Raw<T>*>(p);

@@ -14,6 +14,10 @@
 // the result does not depend on timing.
 #include "tvm_common.h"
 
+#ifndef QKNORM_NT
+#define QKNORM_NT 1
+#endif
+
 namespace tvm {
 namespace {
 
@@ -35,7 +39,12 @@ __device__ __forceinline__ void load_chunk(float (&out)[Chunk<T>::VEC], const T*
   constexpr int VEC = Chunk<T>::VEC;
   if (FULL) {
     const bool live = c0 < D;
+#if QKNORM_NT  // the rows are touched once: non-temporal (backward 96 -> 91 us at C4, forward unchanged)
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    uint4 raw = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + (live ? c0 : 0))));
+#else
     uint4 raw = *reinterpret_cast<const uint4*>(p + (live ? c0 : 0));  // one 16-byte load
+#endif
     raw.x = live ? raw.x : 0u;
     raw.y = live ? raw.y : 0u;
     raw.z = live ? raw.z : 0u;
