@@ -184,7 +184,8 @@ def run_workload(w, steps, warmup, hip, seed=2024, ramp_ms=RAMP_MS):
 
 def one_sided(w, steps, seed=2024):
     """Backward with one upstream gradient only, and the forward that saves nothing, timed outside
-    the timed region of the headline figure (wall clock over `steps` calls each, device synchronised)."""
+    the timed region of the headline figure (wall clock over `steps` calls each after a short ramp, device
+    synchronised)."""
     import torch
 
     import paper_2511_19797_amd as tvm
@@ -212,14 +213,7 @@ def one_sided(w, steps, seed=2024):
     }
     out = {}
     for name, (units, fn) in cases.items():
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
+        ms = _timed_ms(fn, steps)
         out[name] = {"ms": ms, "tflops": units * unit / (ms * 1e-3) / 1e12}
     return out
 
@@ -262,12 +256,32 @@ def graph_step(w, steps, ramp_ms=100.0, seed=2024):
     return {"ms_per_step": ms, "launches": 2 + ramp + 3 + steps, "tflops": 42.0 * w.B * w.H * w.Mq * w.N * w.d / (ms * 1e-3) / 1e12}
 
 
-def _timed_ms(fn, steps):
-    """Wall clock per call over `steps` calls after 3 warm-up calls, device synchronised on both sides."""
+def _marker():
+    """One tiny float32 forward (the plain-ALU kernel, which nothing else in a default run launches) right behind the
+    headline's timed region: in a kernel trace, the launches of the step's kernels just before it are that region."""
     import torch
 
-    for _ in range(3):
+    import paper_2511_19797_amd as tvm
+
+    t = [torch.zeros(1, 1, 8, 8, device="cuda") for _ in range(6)]
+    tvm.tvmattn_jvp_fwd(*t)
+    torch.cuda.synchronize()
+
+
+SIDE_RAMP_MS = 50.0  # load before a side measurement: the sections start from an idle device, i.e. a low clock
+
+
+def _timed_ms(fn, steps):
+    """Wall clock per call over `steps` calls, after SIDE_RAMP_MS of the same call (at least 3 of them), device
+    synchronised on both sides."""
+    import torch
+
+    t0, n = time.perf_counter(), 0
+    while n < 3 or (time.perf_counter() - t0) * 1e3 < SIDE_RAMP_MS:
         fn()
+        n += 1
+        if n % 8 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -465,6 +479,7 @@ def main():
     hip = Hip()
     w = wl.CONFIGS[args.workload]
     res, kern_ms, unit = run_workload(w, args.steps, args.warmup, hip, ramp_ms=args.ramp_ms)
+    _marker()
 
     dom = res["dominant"]["kernel"]
     dom_ms = res["dominant"]["ms_in_timed_region"]  # HIP events around every launch of it in the timed region
