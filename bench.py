@@ -268,7 +268,7 @@ def _marker():
     torch.cuda.synchronize()
 
 
-SIDE_RAMP_MS = 50.0  # load before a side measurement: the sections start from an idle device, i.e. a low clock
+SIDE_RAMP_MS = 50.0  # load before a side measurement (half of --ramp-ms): the sections start from an idle device, i.e. a low clock
 
 
 def _timed_ms(fn, steps):
@@ -478,6 +478,8 @@ def main():
     torch.cuda.set_device(0)
     hip = Hip()
     w = wl.CONFIGS[args.workload]
+    global SIDE_RAMP_MS
+    SIDE_RAMP_MS = 0.5 * args.ramp_ms  # (--ramp-ms 0: counter runs, a handful of launches per kernel)
     res, kern_ms, unit = run_workload(w, args.steps, args.warmup, hip, ramp_ms=args.ramp_ms)
     _marker()
 
