@@ -12,7 +12,10 @@ untimed pass of K steps with every launch bracketed (bracketing all of them insi
 region would cost ~20 us per step, 10 % of a step at N = 256).  Before either pass the card is
 kept under load for --ramp-ms (default 100 ms) so that both see the clock it sustains.
 cpu_baseline = the float64 oracle timed on this machine's host cores on a bounded sample of heads of
-the same workload.
+the same workload.  Side sections, all outside the timed region and each timed after half of
+--ramp-ms of the same call: one_sided (one upstream gradient alone; the forward that saves nothing),
+graph_replay (the step captured in a HIP graph), qknorm, adaln, gate, gelu (the block's memory-bound
+pieces, priced against 8 TB/s).
 """
 import argparse
 import ctypes
