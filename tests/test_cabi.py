@@ -313,3 +313,17 @@ def test_gelu_argument_rules(L):
         p[k] = None
         assert bwd(64, 1, p) == -1
     assert bwd(64, 1, ptr[:4] + [ptr[4], ptr[4]]) == -1 and bwd(64, 1, ptr[:4] + [ptr[1], ptr[5]]) == -1
+
+
+def test_missing_library_raises_and_nothing_falls_back(monkeypatch, tmp_path):
+    """Without the built library every entry point of the binding raises: there is no CPU or eager path behind it."""
+    import paper_2511_19797_amd.binding as b
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libtvmattn_missing.so"))
+    monkeypatch.setattr(b, "_lib", None)
+    with pytest.raises(ImportError):
+        b.tvmattn_version()
+    with pytest.raises(ImportError):
+        b.lib()
+    import inspect
+    src = inspect.getsource(b)
+    assert "oracle" not in src, "the binding must not know the oracle"
