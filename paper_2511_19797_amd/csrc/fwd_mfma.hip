@@ -26,6 +26,9 @@
 // zero in LDS, so row D of accO is l and row D of accT is c, accumulated (and rescaled) by the
 // matrix cores along with everything else, from the same bf16-rounded weights as the outputs.
 #include "mfma_tiles.h"
+#ifndef FWD_WIDE_FROM
+#define FWD_WIDE_FROM 512  // keys from which a workgroup is eight waves instead of four (see launch)
+#endif
 #ifndef FWD_NW
 #define FWD_NW 4   // waves per workgroup (two workgroups share a CU)
 #define FWD_BN 32  // keys per LDS tile (one 32-key block)
@@ -270,9 +273,9 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
   }
 }
 
-template <int DK, int DV>
-hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
-  constexpr int NW = FWD_NW, BN = FWD_BN;  // waves per workgroup, keys per LDS tile
+template <int DK, int DV, int NW>
+hipError_t launch_nw(const Shape& s, const FwdArgs& a, hipStream_t st) {
+  constexpr int BN = FWD_BN;  // keys per LDS tile
   const int nmb = (s.M + 32 * NW - 1) / (32 * NW);
   const dim3 grid(nmb * s.B * s.H), block(64 * NW);
   const bf16 *q = (const bf16*)a.q, *k = (const bf16*)a.k, *v = (const bf16*)a.v, *tq = (const bf16*)a.tq,
@@ -286,6 +289,18 @@ hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
   else
     return hipErrorNotSupported;  // D <= DK < DV: not reached
   return hipGetLastError();
+}
+
+// Waves per workgroup: four (two workgroups share a CU) for short key sequences, where a workgroup's start-up and
+// epilogue overlap the other's loop; eight (one workgroup per CU, the same two waves per SIMD, every tile fetched
+// once per CU instead of twice) from 512 keys on: 2 % faster at N = 1024 (250 against 256 us at C4, 236 against 241 us
+// at d = 64), 3 % slower at N = 256.
+template <int DK, int DV>
+hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
+  if constexpr (DV <= 96) {  // (above that a wave needs more than the 256 registers that two waves per SIMD leave it)
+    if (s.N >= FWD_WIDE_FROM && s.M > 32 * FWD_NW) return launch_nw<DK, DV, 2 * FWD_NW>(s, a, st);
+  }
+  return launch_nw<DK, DV, FWD_NW>(s, a, st);
 }
 
 }  // namespace
