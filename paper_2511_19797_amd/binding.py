@@ -149,6 +149,13 @@ def _same_layout(ref, *ts):
             raise ValueError("device tensors required")
 
 
+def _like(ref):
+    """A new tensor with exactly `ref`'s shape AND strides.  The descriptor carries one set of strides per side, taken
+    from the inputs, and every kernel store uses them; torch.empty_like keeps strides only for dense tensors (a q
+    sliced out of a fused [B,N,3,H,D] projection would get a compact output that the kernels then overrun)."""
+    return torch.empty_strided(ref.shape, ref.stride(), dtype=ref.dtype, device=ref.device)
+
+
 def _stream():
     return _P(torch.cuda.current_stream().cuda_stream)
 
@@ -165,7 +172,7 @@ def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True):
     desc = make_desc(k, scale, q)
     B, H, N, _ = q.shape  # row vectors go with the queries
     if out is None:
-        o, to = torch.empty_like(q), torch.empty_like(q)
+        o, to = _like(q), _like(q)
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if save else None
         stats = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if save else None
     else:
@@ -192,7 +199,7 @@ def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, 
     _same_layout(*[t for t in (k, v, tk, tv) if t is not None])
     desc = make_desc(k, scale, q)
     if out is None:  # dq, dk, dv, dtq, dtk, dtv
-        out = tuple(torch.empty_like(q if n in (0, 3) else k) if (gTO is not None or n < 3) else None for n in range(6))
+        out = tuple(_like(q if n in (0, 3) else k) if (gTO is not None or n < 3) else None for n in range(6))
     else:
         _same_layout(q, *[t for n, t in enumerate(out) if t is not None and n in (0, 3)])
         _same_layout(k, *[t for n, t in enumerate(out) if t is not None and n not in (0, 3)])
@@ -220,7 +227,7 @@ def tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gain_q, gain_k, eps, out=None):
     _gain_ok(gain_k, k)
     desc = make_desc(k, 0.0, q)
     if out is None:
-        out = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(k))
+        out = (_like(q), _like(q), _like(k), _like(k))
     else:
         _same_layout(q, out[0], out[1])
         _same_layout(k, out[2], out[3])
@@ -243,8 +250,7 @@ def tvmattn_qknorm_jvp_bwd(q, tq, k, tk, gain_q, gain_k, eps, gqn, gtqn, gkn, gt
     _gain_ok(gain_k, k)
     desc = make_desc(k, 0.0, q)
     if out is None:
-        out = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(k),
-               torch.empty_like(gain_q), torch.empty_like(gain_k))
+        out = (_like(q), _like(q), _like(k), _like(k), torch.empty_like(gain_q), torch.empty_like(gain_k))
     else:
         _same_layout(q, out[0], out[1])
         _same_layout(k, out[2], out[3])
@@ -277,8 +283,7 @@ def tvmattn_jvp_bwd_qknorm(q, tq, k, tk, gain_q, gain_k, eps, qn, tqn, kn, tkn, 
     _gain_ok(gain_k, k)
     desc = make_desc(k, scale, q)
     if out is None:
-        out = tuple(torch.empty_like(q if n in (0, 3) else k) for n in range(6)) + (torch.empty_like(gain_q),
-                                                                                 torch.empty_like(gain_k))
+        out = tuple(_like(q if n in (0, 3) else k) for n in range(6)) + (torch.empty_like(gain_q), torch.empty_like(gain_k))
     else:
         _same_layout(q, out[0], out[3])
         _same_layout(k, out[1], out[2], out[4], out[5])

@@ -327,3 +327,23 @@ def test_missing_library_raises_and_nothing_falls_back(monkeypatch, tmp_path):
     import inspect
     src = inspect.getsource(b)
     assert "oracle" not in src, "the binding must not know the oracle"
+
+
+def test_outputs_are_allocated_with_the_inputs_strides():
+    """q, k, v sliced out of one fused [B,N,3,H,D] projection are not dense: the descriptor carries their strides
+    and the kernels store through them, so the binding must allocate outputs with those very strides (a compact
+    torch.empty_like would be overrun)."""
+    import torch
+    B, N, H, D = 2, 5, 4, 8
+    qkv = torch.zeros(B, N, 3, H, D, dtype=torch.bfloat16)
+    q = qkv[:, :, 0].permute(0, 2, 1, 3)   # [B,H,N,D] view
+    assert not q.is_contiguous() and q.stride() == (N * 3 * H * D, D, 3 * H * D, 1)
+    assert torch.empty_like(q).stride() != q.stride()      # what went wrong before
+    o = binding._like(q)
+    assert o.shape == q.shape and o.stride() == q.stride() and o.dtype == q.dtype
+    d = binding.make_desc(q)
+    assert (d.stride_b, d.stride_h, d.stride_n) == o.stride()[:3]
+    assert (d.qstride_b, d.qstride_h, d.qstride_n) == o.stride()[:3]
+    # the largest element offset the kernels can reach lies inside the allocation
+    reach = sum((n - 1) * s for n, s in zip(o.shape, o.stride()))
+    assert reach < o.untyped_storage().nbytes() // o.element_size()

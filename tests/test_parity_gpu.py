@@ -27,8 +27,7 @@ def run_case(w, seed, heads=None, scale=0.0, force_generic=False):
     finally:
         tvm.tvmattn_set_path(0)
     heads = pu.all_heads(w) if heads is None else heads
-    worst = pu.check_heads(w, inp, fwd, grads, heads, scale=(scale or None))
-    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    pu.check_heads(w, inp, fwd, grads, heads, scale=(scale or None))
     return inp, fwd, grads
 
 
@@ -75,6 +74,43 @@ def test_bf16_hand_scheduled_tile_boundaries(d):
     and three tiles (the three LDS stages wrap), one row more or fewer, a workgroup boundary."""
     for N in (17, 63, 64, 65, 127, 128, 129, 191, 192, 193, 320):
         run_case(wl.custom(1, 1, N, d, "bf16"), seed=20 + N % 7)
+
+
+@pytest.mark.parametrize("d", [8, 24, 40, 64, 72, 96])
+def test_bf16_wide_forward_workgroups(d):
+    """From 512 keys on (head dims up to 96, more than 128 queries) the forward runs eight-wave workgroups of 256
+    query rows.  Every instantiation of it (one per padded head dim), with a whole and a ragged last key block,
+    with workgroups whose upper waves hold no query row (M = 257, 300), and with M != N either way round: every
+    element of all ten outputs against the oracle."""
+    import dataclasses
+    for N in (512, 513, 543, 1000):
+        run_case(wl.custom(1, 2 if N == 512 else 1, N, d, "bf16"), seed=60 + N % 11)
+    for M, N in ((257, 512), (300, 543), (700, 600), (600, 700)):
+        w = dataclasses.replace(wl.custom(1, 1, N, d, "bf16"), M=M)
+        run_case(w, seed=70 + M % 13)
+
+
+def test_inputs_sliced_from_a_fused_projection():
+    """q, k, v (and the tangents, and the upstream gradients) sliced out of fused [B,N,3,H,D] buffers: not dense, so
+    the outputs must be allocated with the inputs' strides.  Forward and backward against the oracle, matrix-core
+    and plain-ALU paths."""
+    for dtype, d, N in (("bf16", 72, 200), ("bf16", 64, 520), ("f32", 24, 70)):
+        w = wl.custom(2, 3, N, d, dtype)
+        announce(f"fused-QKV slices {w}")
+        inp = wl.make_inputs(w, 15)
+        def fused(a, b, c):  # [B,H,N,D] x 3 -> one [B,N,3,H,D] buffer and its three [B,H,N,D] views
+            buf = torch.stack([a, b, c], dim=0).permute(1, 3, 0, 2, 4).contiguous().cuda()
+            return [buf[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+        q, k, v = fused(inp["q"], inp["k"], inp["v"])
+        tq, tk, tv = fused(inp["tq"], inp["tk"], inp["tv"])
+        gO, gTO, _ = fused(inp["gO"], inp["gTO"], inp["gO"])
+        assert not q.is_contiguous() and q.stride() == (N * 3 * 3 * d, d, 3 * 3 * d, 1)
+        o, to, lse, stats = tvm.tvmattn_jvp_fwd(q, k, v, tq, tk, tv)
+        assert o.stride() == q.stride()
+        grads = tvm.tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO)
+        torch.cuda.synchronize()
+        assert grads[0].stride() == q.stride() and grads[1].stride() == k.stride()
+        pu.check_heads(w, inp, (o, to, lse, stats), grads, pu.all_heads(w))
 
 
 def test_bf16_mfma_scaled_inputs():
@@ -164,35 +200,6 @@ def test_backward_is_linear_in_upstream_gradients():
         assert torch.equal((a.float() * 4.0).to(torch.bfloat16), b)
 
 
-# ---------------------------------------------------------------- the five configs at full size
-@pytest.mark.parametrize("name,nheads", [("C2", 6), ("C3", 6), ("C4", 3), ("C5", 2), ("X3", 4), ("X4", 2), ("XA", 3)])
-def test_full_size_configs_sampled_heads(name, nheads):
-    """Full B,H,N,d in the launch configuration bench.py times; the oracle checks whole heads
-    (every element of all ten outputs) for a seeded sample of (b,h), always including the first
-    and the last head; all outputs must be finite everywhere."""
-    w = wl.CONFIGS[name]
-    announce(f"full-size {w}")
-    inp = wl.make_inputs(w, 100 + (int(name[1]) if name[1].isdigit() else 20) + (10 if name[0] == "X" else 0))
-    fwd, grads = pu.run_gpu(inp)
-    for t in list(fwd) + list(grads):
-        assert bool(torch.isfinite(t.float()).all())
-    rng = np.random.default_rng(12)
-    heads = {(0, 0), (w.B - 1, w.H - 1)}
-    while len(heads) < nheads:
-        heads.add((int(rng.integers(w.B)), int(rng.integers(w.H))))
-    worst = pu.check_heads(w, inp, fwd, grads, sorted(heads))
-    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
-    # properties that hold for every head at any size: adding one vector to all keys of a head changes
-    # neither O nor tO, so the key gradients and the key-tangent gradients sum to zero over the keys
-    # (up to the bf16 rounding of each of the N summands)
-    dq, dk, dv, dtq, dtk, dtv = grads
-    for g in (dk, dtk):
-        col_sum = g.float().sum(dim=2).abs().max()
-        bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
-        assert float(col_sum) <= float(bound), (float(col_sum), float(bound))
-
-
-# ---------------------------------------------------------------- long sequences (the paper's kernel-benchmark shapes)
 def _chunked_oracle_bwd(a, rows_per_chunk=512):
     """The oracle's backward of one head, one block of query rows at a time: softmax rows are
     independent, so the query gradients of a block are exact and the key-side gradients are the sums
@@ -212,6 +219,62 @@ def _chunked_oracle_bwd(a, rows_per_chunk=512):
     return dq, dk, dv, dtq, dtk, dtv
 
 
+# ---------------------------------------------------------------- the five configs at full size
+def _column_sums_vanish(w, grads):
+    """Holds for every head at any size: adding one vector to all keys of a head changes neither O nor tO, so the
+    key gradients and the key-tangent gradients sum to zero over the keys (up to the bf16 rounding of each of
+    the N summands)."""
+    dq, dk, dv, dtq, dtk, dtv = grads
+    for g in (dk, dtk):
+        col_sum = g.float().sum(dim=2).abs().max()
+        bound = 4.0 * (2.0 ** -8) * g.float().abs().max() * (w.N ** 0.5)
+        assert float(col_sum) <= float(bound), (float(col_sum), float(bound))
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "X3", "X4", "XA"])
+def test_full_size_configs_all_heads(name):
+    """Full B,H,N,d in the launch configuration bench.py times: every element of all ten outputs of EVERY
+    (batch, head) against the oracle."""
+    w = wl.CONFIGS[name]
+    announce(f"full-size, all {w.heads} heads: {w}")
+    inp = wl.make_inputs(w, 100 + (int(name[1]) if name[1].isdigit() else 20) + (10 if name[0] == "X" else 0))
+    fwd, grads = pu.run_gpu(inp)
+    for t in list(fwd) + list(grads):
+        assert bool(torch.isfinite(t.float()).all())
+    pu.check_heads(w, inp, fwd, grads, pu.all_heads(w))
+    _column_sums_vanish(w, grads)
+
+
+def test_full_size_c5_all_heads():
+    """C5 (N = 4096, d = 128, keys x 2) at full size, all 48 heads: the oracle works through a head in blocks of
+    query rows (softmax rows are independent), which keeps its N x N matrices at 512 x 4096."""
+    w = wl.CONFIGS["C5"]
+    announce(f"full-size, all {w.heads} heads: {w}")
+    inp = wl.make_inputs(w, 105)
+    fwd, grads = pu.run_gpu(inp)
+    for t in list(fwd) + list(grads):
+        assert bool(torch.isfinite(t.float()).all())
+    got_host = [t.float().cpu().numpy() for t in list(fwd) + list(grads)]
+    worst, worst_elem = {}, {}
+    for n_done, (b, h) in enumerate(pu.all_heads(w)):
+        a = [wl.to_f64(inp[n][b, h]) for n in wl.NAMES]
+        ref_f = [np.concatenate(x) for x in zip(*[
+            pu.orc.attn_jvp_fwd_head(a[0][r0:r0 + 1024], a[1], a[2], a[3][r0:r0 + 1024], a[4], a[5])
+            for r0 in range(0, w.N, 1024)])]
+        ref_g = _chunked_oracle_bwd(a)
+        for nm, got, ref in zip(pu.FWD_NAMES + pu.BWD_NAMES, got_host, list(ref_f) + list(ref_g)):
+            worst[nm] = max(worst.get(nm, 0.0), pu.rel_err(got[b, h], ref))
+            worst_elem[nm] = max(worst_elem.get(nm, 0.0), pu.elem_err(got[b, h], ref))
+        if n_done % 8 == 7:
+            print(f"   {n_done + 1} heads compared", flush=True)
+    print("   max|err|/max|ref|      :", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    print("   max |err|/(|ref|+rms)  :", {k: f"{v:.2e}" for k, v in worst_elem.items()}, flush=True)
+    bad = {k: v for k, v in worst.items() if not (v <= pu.TOL["bf16"])}
+    assert not bad, bad
+    _column_sums_vanish(w, grads)
+
+
+# ---------------------------------------------------------------- long sequences (the paper's kernel-benchmark shapes)
 def test_long_sequence_whole_head():
     """N = 8192 (128 tiles; every LDS stage reused 40 times), one head of 64: every element of all ten
     outputs against the oracle, which works through the head in blocks of query rows."""
@@ -224,10 +287,12 @@ def test_long_sequence_whole_head():
         pu.orc.attn_jvp_fwd_head(a[0][r0:r0 + 1024], a[1], a[2], a[3][r0:r0 + 1024], a[4], a[5])
         for r0 in range(0, w.N, 1024)])]
     ref_g = _chunked_oracle_bwd(a)
-    worst = {}
+    worst, worst_elem = {}, {}
     for name, got, ref in list(zip(pu.FWD_NAMES, fwd, ref_f)) + list(zip(pu.BWD_NAMES, grads, ref_g)):
         worst[name] = pu.rel_err(got[0, 0].float().cpu().numpy(), ref)
-    print("   worst rel err:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+        worst_elem[name] = pu.elem_err(got[0, 0].float().cpu().numpy(), ref)
+    print("   max|err|/max|ref|      :", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    print("   max |err|/(|ref|+rms)  :", {k: f"{v:.2e}" for k, v in worst_elem.items()}, flush=True)
     bad = {k: v for k, v in worst.items() if not (v <= pu.TOL["bf16"])}
     assert not bad, bad
 
@@ -432,4 +497,23 @@ def test_random_shapes_against_the_oracle():
         fwd = tvm.tvmattn_jvp_fwd(*six, scale)
         grads = tvm.tvmattn_jvp_bwd(*six, *fwd, dev["gO"], dev["gTO"], scale)
         torch.cuda.synchronize()
+        pu.check_heads(w, inp, fwd, grads, pu.all_heads(w), scale=scale or None)
+
+
+def test_random_long_shapes_against_the_oracle():
+    """Sixteen more seeded random problems with 400 to 1100 keys (the eight-wave forward, many tiles in every
+    kernel, ragged last tiles), M = N or M drawn separately: every element of all ten outputs against the oracle."""
+    import dataclasses
+    rng = np.random.default_rng(19797)
+    dims = [8, 24, 40, 48, 64, 72, 80, 96, 128]
+    for case in range(16):
+        d = int(rng.choice(dims))
+        B, H = 1, int(rng.integers(1, 3))
+        N = int(rng.integers(400, 1100))
+        M = 0 if case % 2 else int(rng.integers(130, 1100))
+        w = dataclasses.replace(wl.custom(B, H, N, d, "bf16"), M=M)
+        scale = 0.0 if case % 4 else float(rng.uniform(0.05, 0.3))
+        announce(f"random long case {case}: {w} scale={scale:.3f}")
+        inp = wl.make_inputs(w, 3000 + case)
+        fwd, grads = pu.run_gpu(inp, scale)
         pu.check_heads(w, inp, fwd, grads, pu.all_heads(w), scale=scale or None)
