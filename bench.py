@@ -15,7 +15,9 @@ cpu_baseline = the float64 oracle timed on this machine's host cores on a bounded sa
 the same workload.  Side sections, all outside the timed region and each timed after half of
 --ramp-ms of the same call: one_sided (one upstream gradient alone; the forward that saves nothing),
 graph_replay (the step captured in a HIP graph), qknorm, adaln, gate, gelu (the block's memory-bound
-pieces, priced against 8 TB/s).
+pieces, priced against 8 TB/s), peaks (the card's own matrix-core and HBM rates from plain microbenchmarks).
+roofline.traffic comes from the committed counter summary under profiles/ and is null once the kernel's sources
+differ from the ones that were profiled.
 """
 import argparse
 import ctypes
@@ -37,18 +39,44 @@ PEAK_HBM_GBS = 8000.0
 # them is overhead, not algorithmic work.  12 + 24 + 6 = 42.
 KERNEL_FLOP_UNITS = {"fwd": 12.0, "bwd_pre": 0.0, "bwd_col": 24.0, "bwd_row": 6.0}
 
-# HBM traffic per launch (bytes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch),
-# each scaled by what the same counter reads for a 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0);
-# figures and commands in profiles/tvmattn_kernels_C4_counters.md.  None where not measured.
-_KIB = 1024.0
-MEASURED_TRAFFIC = {
-    ("C4", "fwd"): 110666.8 * _KIB * 2.0 + 75776.0 * _KIB,
-    ("C4", "bwd_row"): 185456.8 * _KIB * 2.0 + 76800.0 * _KIB,
-    ("C4", "bwd_col"): 149655.1 * _KIB * 2.0 + 147456.0 * _KIB,
-    ("C3", "fwd"): 55370.2 * _KIB * 2.0 + 37888.0 * _KIB,
-    ("C3", "bwd_row"): 92783.7 * _KIB * 2.0 + 38400.0 * _KIB,
-    ("C3", "bwd_col"): 74902.2 * _KIB * 2.0 + 73728.0 * _KIB,
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch), each scaled by what the
+# same counter reads for a 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  The figures are not kept here: they are
+# read from the table rows "| traffic | <workload> | <kernel> | <FETCH KiB> | <WRITE KiB> | <source hash> |" of
+# profiles/tvmattn_kernels_C4_counters.md, and a row counts only while the hash recorded with it equals the hash of
+# the kernel's sources as they are now (a kernel that changed since it was profiled reports traffic = null).
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "tvmattn_kernels_C4_counters.md")
+FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
+_CSRC = os.path.join(ROOT, "paper_2511_19797_amd", "csrc")
+KERNEL_SOURCES = {
+    "fwd": ("fwd_mfma.hip", "mfma_tiles.h", "tvm_common.h"),
+    "bwd_row": ("bwd_row_pipe.hip", "pipe_ops.h", "mfma_tiles.h", "tvm_common.h"),
+    "bwd_col": ("bwd_col_pipe.hip", "pipe_ops.h", "mfma_tiles.h", "tvm_common.h"),
 }
+
+
+def source_sha16(kernel):
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES[kernel]:
+        with open(os.path.join(_CSRC, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """Bytes per launch from the committed counter summary, or None (no row, or the kernel's sources changed)."""
+    import re
+    if kernel not in KERNEL_SOURCES or not os.path.exists(TRAFFIC_PROFILE):
+        return None
+    pat = re.compile(r"^\|\s*traffic\s*\|\s*(\w+)\s*\|\s*(\w+)\s*\|\s*([\d.]+)\s*\|\s*([\d.]+)\s*\|\s*([0-9a-f]{16})\s*\|")
+    with open(TRAFFIC_PROFILE) as fh:
+        for line in fh:
+            m = pat.match(line)
+            if m and m.group(1) == workload and m.group(2) == kernel:
+                if m.group(5) != source_sha16(kernel):
+                    return None
+                return float(m.group(3)) * 1024.0 * FETCH_FACTOR + float(m.group(4)) * 1024.0 * WRITE_FACTOR
+    return None
 
 
 # Backward latency of the paper's own kernels on one H100 (App. C "Evaluation"; batch size and head
@@ -121,8 +149,8 @@ def run_workload(w, steps, warmup, hip, seed=2024, ramp_ms=RAMP_MS):
         if ev is not None:
             if ev[1]:
                 hip.record(ev[1], stream)
-            tvm.tvmattn_set_bwd_events(ev[2:6])
-        tvm.tvmattn_jvp_bwd(*six, *fwd_out, dev["gO"], dev["gTO"], out=bwd_out, workspace=ws)
+        tvm.tvmattn_jvp_bwd(*six, *fwd_out, dev["gO"], dev["gTO"], out=bwd_out, workspace=ws,
+                            events=None if ev is None else ev[2:6])
 
     names = ("fwd", "bwd_pre", "bwd_col", "bwd_row")
     pairs = ((0, 1), (2, 3), (4, 5), (3, 4))  # bwd events: start, after pre, after row, after col
@@ -156,7 +184,6 @@ def run_workload(w, steps, warmup, hip, seed=2024, ramp_ms=RAMP_MS):
         step(timed[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    tvm.tvmattn_set_bwd_events(None)
     dom_ms = sum(hip.elapsed_ms(ev[a], ev[b]) for ev in events) / steps
     for ev in events:
         for e in ev:
@@ -374,7 +401,7 @@ def adaln(w, steps, seed=2024):
     bo = fo + tuple(torch.empty_like(dev["a"]) for _ in range(4))
     ws = torch.empty(1 << 26, dtype=torch.uint8, device="cuda")
     one = float(B) * T * C * (2 if w.dtype == "bf16" else 4)
-    cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_adaln_jvp_fwd(*args, 1e-6, out=fo, workspace=ws)),
+    cases = {"fwd": (4.0 * one, lambda: tvm.tvmattn_adaln_jvp_fwd(*args, 1e-6, out=fo)),
              "bwd": (6.0 * one, lambda: tvm.tvmattn_adaln_jvp_bwd(*args, 1e-6, dev["gy"], dev["gty"], out=bo, workspace=ws))}
     out = {"shape": {"B": B, "T": T, "C": C}}
     out.update(_hbm_cases(cases, steps))
@@ -428,6 +455,46 @@ def gelu(w, steps, seed=2024):
     return out
 
 
+def peaks(steps):
+    """The card's own ceilings, measured beside the kernels: the rate of the matrix-core instruction the attention
+    kernels use (two waves per SIMD issuing it back to back) and the HBM rate of a plain copy and a plain read of
+    1 GiB, each after SIDE_RAMP_MS of the same load.  The roofline's `peak` stays the published figure; these say
+    how much of it this card sustains."""
+    import torch
+
+    from paper_2511_19797_amd import build as b
+    if not os.path.exists(b.PEAKS_LIB):
+        raise ImportError(f"{b.PEAKS_LIB} not found: run __graft_entry__.build() first")
+    L = ctypes.CDLL(b.PEAKS_LIB)
+    L.tvmpeaks_mfma_bf16.restype = ctypes.c_double
+    L.tvmpeaks_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    L.tvmpeaks_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    L.tvmpeaks_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    stream = torch.cuda.current_stream().cuda_stream
+    blocks = 2 * torch.cuda.get_device_properties(0).multi_processor_count   # two waves per SIMD
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    iters = 4000   # 64,000 products per wave, about 1 ms
+    flops = []
+
+    def mfma():
+        flops.append(L.tvmpeaks_mfma_bf16(blocks, iters, out.data_ptr(), stream))
+    ms = _timed_ms(mfma, steps)
+    assert flops[-1] > 0, "matrix-core rate kernel failed to launch"
+    res = {"mfma_bf16_tflops": flops[-1] / (ms * 1e-3) / 1e12, "mfma_ms": ms,
+           "mfma_note": "v_mfma_f32_32x32x16_bf16, 4 independent accumulators per wave, 2 waves per SIMD"}
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    flag = torch.zeros(4, dtype=torch.int32, device="cuda")
+    wg = 16 * torch.cuda.get_device_properties(0).multi_processor_count
+    ms = _timed_ms(lambda: L.tvmpeaks_copy(dst.data_ptr(), src.data_ptr(), n, wg, stream), steps)
+    res["copy_gbs"] = 2.0 * n / (ms * 1e-3) / 1e9   # bytes read + bytes written
+    ms = _timed_ms(lambda: L.tvmpeaks_read(src.data_ptr(), n, flag.data_ptr(), wg, stream), steps)
+    res["read_gbs"] = n / (ms * 1e-3) / 1e9
+    assert torch.equal(src[:1 << 20], dst[:1 << 20]) and torch.equal(src[-(1 << 20):], dst[-(1 << 20):])
+    return res
+
+
 def cpu_baseline(w, budget_s=20.0, seed=2024):
     """Times the oracle (forward + backward, whole heads) until about `budget_s` seconds are spent."""
     from oracle import tvmattn_oracle as orc
@@ -464,11 +531,16 @@ def main():
     ap.add_argument("--ramp-ms", type=float, default=RAMP_MS,
                     help="untimed stepping after the warm-up steps until the clock has ramped (0: none)")
     ap.add_argument("--workload", default="C4")
-    ap.add_argument("--also", default="C3", help="comma-separated extra workloads reported under 'also'")
+    ap.add_argument("--also", default="C2,C3,C5", help="comma-separated extra workloads reported under 'also'")
+    ap.add_argument("--source-hashes", action="store_true",
+                    help="print the hashes of the kernels' sources (what a traffic row of the counter summary records) and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the shapes of the paper's kernel benchmark (H in 1, 24; S = 128 ... 32768) under 'sweep'")
     args = ap.parse_args()
+    if args.source_hashes:
+        print(json.dumps({k: source_sha16(k) for k in KERNEL_SOURCES}))
+        return
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
               "Heads shard over GPUs with no exchange; no multi-GPU figure is produced.", file=sys.stderr)
@@ -491,7 +563,7 @@ def main():
     achieved = KERNEL_FLOP_UNITS[dom] * unit / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_ms": dom_ms,
-                "traffic": MEASURED_TRAFFIC.get((w.name, dom))}
+                "traffic": measured_traffic(w.name, dom)}
 
     also = {}
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
@@ -527,6 +599,8 @@ def main():
                 "H": sw.H, "S": sw.N, "B": sw.B, "d": sw.d, "steps": k, "ms_per_step": r["ms_per_step"],
                 "fwd_ms": km["fwd"], "bwd_ms": km["bwd_pre"] + km["bwd_row"] + km["bwd_col"], "tflops": r["tflops"],
                 "paper_h100_bwd_ms": PAPER_H100_BWD_MS.get((sw.H, sw.N))})
+    out["peaks"] = peaks(args.steps)
+    out["roofline"]["frac_of_measured_mfma_rate"] = achieved / out["peaks"]["mfma_bf16_tflops"]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -40,8 +40,10 @@
  *     validated before the first launch: on INVALID_ARG, UNSUPPORTED or
  *     WORKSPACE_TOO_SMALL nothing has been enqueued.  No C++ exception crosses
  *     this boundary.
- *   - Outputs must not alias inputs.  Calls on the same stream are ordered;
- *     calls on different streams may overlap if their buffers are disjoint.
+ *   - No output may overlap an input, another output or the workspace: checked element-exactly for tensors of
+ *     one layout (slices of one fused buffer that interleave without sharing an element are fine), by address
+ *     range otherwise.  Calls on the same stream are ordered; calls on different streams may overlap if their
+ *     buffers are disjoint.  The library keeps no state between calls.
  */
 #ifndef TVMATTN_H
 #define TVMATTN_H
@@ -66,6 +68,13 @@ typedef enum {
   TVMATTN_LAUNCH_FAILED = -4        /* hipGetLastError() after a launch was not hipSuccess */
 } tvmattn_status;
 
+/* Per-call switches, OR-ed into tvmattn_desc.flags.  Unknown bits are TVMATTN_INVALID_ARG. */
+enum {
+  /* Diagnostic: serve this call with the plain-ALU kernels even where the matrix-core kernels would take it
+   * (bf16 with D a multiple of 8 and D <= 128).  Both families compute the operation stated above. */
+  TVMATTN_FLAG_PLAIN_ALU = 1
+};
+
 typedef struct {
   int32_t B;        /* batch                       >= 1 */
   int32_t H;        /* heads                       >= 1 */
@@ -77,7 +86,7 @@ typedef struct {
   int64_t stride_h;
   int64_t stride_n;
   int32_t M;        /* queries; 0 = N (self-attention) */
-  int32_t reserved; /* 0 */
+  int32_t flags;    /* 0, or TVMATTN_FLAG_* bits */
   int64_t qstride_b; /* element strides of the query-side [B,H,M,D] tensors; all zero = contiguous, */
   int64_t qstride_h; /* or the key side's strides where M is 0 or N */
   int64_t qstride_n;
@@ -90,29 +99,11 @@ int tvmattn_version(void);
 const char* tvmattn_strerror(int status);
 
 /*
- * Diagnostic switch, process-wide, not thread-safe: 0 (default) picks the kernel family per
- * shape (matrix-core kernels for bf16 with D a multiple of 8 and D <= 128, plain-ALU kernels
- * otherwise); 1 forces the plain-ALU kernels for every call.  Returns TVMATTN_OK or
- * TVMATTN_INVALID_ARG.  Both families compute the operation stated above.
- */
-int tvmattn_set_path(int path);
-
-/*
- * Diagnostic timing hook, process-wide, not thread-safe.  `events` is NULL (off, the default)
- * or points to four hipEvent_t handles created by the caller with timing enabled; while set,
- * every tvmattn_jvp_bwd call records, on its stream, events[0] before its first launch,
- * events[1] after the row-scalar kernel (a separate launch only on the plain-ALU path),
- * events[2] after the query-side kernel and events[3] after the key-side kernel.  A NULL
- * handle among the four skips that record.  The four handles are copied; the array need not
- * outlive the call.
- */
-int tvmattn_set_bwd_events(void* const* events);
-
-/*
  * Forward with tangent (one online-softmax pass over the keys).
- *   in : q,k,v,tq,tk,tv   [B,H,N,D] dtype
- *   out: o, to            [B,H,N,D] dtype
- *        lse, stats       [B,H,N]   float32 (natural log of the row sum of exp(z); mu/l)
+ *   in : q, tq            [B,H,M,D] dtype (query side)
+ *        k, v, tk, tv     [B,H,N,D] dtype (key side)
+ *   out: o, to            [B,H,M,D] dtype
+ *        lse, stats       [B,H,M]   float32 (natural log of the row sum of exp(z); mu/l)
  * lse and stats may both be NULL: a forward whose backward will not be taken saves nothing
  * (the "detached" use of the tangent; one of the two alone is TVMATTN_INVALID_ARG).
  */
@@ -129,8 +120,8 @@ size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc);
  * Backward through both outputs.
  *   in : q,k,v,tq,tk,tv   as given to the forward
  *        o,to,lse,stats   as written by the forward
- *        gO, gTO          [B,H,N,D] dtype, upstream gradients of o and to
- *   out: dq,dk,dv,dtq,dtk,dtv  [B,H,N,D] dtype, each element written exactly once
+ *        gO, gTO          [B,H,M,D] dtype, upstream gradients of o and to
+ *   out: dq, dtq          [B,H,M,D] dtype;  dk, dv, dtk, dtv  [B,H,N,D] dtype; each element written exactly once
  *   workspace: device memory, 16-byte aligned, at least
  *        tvmattn_jvp_bwd_workspace_bytes(desc) bytes; contents need not be initialised
  *        and are undefined afterwards.
@@ -156,6 +147,22 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc,
                     void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
                     void* workspace, size_t workspace_bytes,
                     void* hip_stream);
+
+/*
+ * tvmattn_jvp_bwd with a timing hook, for benchmarks: `events` points to four hipEvent_t handles created by the
+ * caller with timing enabled; the call records, on its stream, events[0] before its first launch, events[1] after
+ * the row-scalar kernel (a separate launch only on the plain-ALU path), events[2] after the query-side kernel and
+ * events[3] after the key-side kernel.  A NULL handle among the four skips that record; events == NULL is
+ * tvmattn_jvp_bwd itself.  Nothing is kept between calls.
+ */
+int tvmattn_jvp_bwd_timed(const tvmattn_desc* desc,
+                          const void* q, const void* k, const void* v,
+                          const void* tq, const void* tk, const void* tv,
+                          const void* o, const void* to, const float* lse, const float* stats,
+                          const void* gO, const void* gTO,
+                          void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
+                          void* workspace, size_t workspace_bytes,
+                          void* const* events, void* hip_stream);
 
 /*
  * RMSNorm with a learnable gain as QK-norm, with tangent: the operation that normalises queries and keys
@@ -246,23 +253,20 @@ int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc,
  *        a, ta, b, tb    [B,C] float32, contiguous: scale and shift of the token's batch element, and tangents
  *        eps             >= 0, finite
  *   out: y, ty           [B,T,C] dtype
- *   workspace: device memory, 16-byte aligned, at least tvmattn_adaln_jvp_fwd_workspace_bytes(...) bytes (a small
- *              constant for every supported shape, 0 for an unsupported one; the forward leaves it untouched).
  * C must be a multiple of 16 bytes' worth of elements and at most 256 such chunks (2048 for bfloat16, 1024 for
- * float32), B at most 65535; otherwise TVMATTN_UNSUPPORTED.  One launch.  Arithmetic is float32.
+ * float32), B at most 65535; otherwise TVMATTN_UNSUPPORTED.  One launch, no workspace.  Arithmetic is float32.
  */
-size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype);
 int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype,
                           const void* x, const void* tx,
                           const float* a, const float* ta, const float* b, const float* tb, float eps,
-                          void* y, void* ty,
-                          void* workspace, size_t workspace_bytes, void* hip_stream);
+                          void* y, void* ty, void* hip_stream);
 
 /*
  * Backward of the above: the gradient of <gy,y> + <gty,ty> with respect to all six inputs.
  *   in : x, tx, a, ta, b, tb, eps as given to the forward (nothing is saved); gy, gty [B,T,C] dtype
  *   out: gx, gtx [B,T,C] dtype; ga, gta, gb, gtb [B,C] float32 (summed over the T tokens of their batch element)
- *   workspace: at least tvmattn_adaln_jvp_bwd_workspace_bytes(...) bytes.
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_adaln_jvp_bwd_workspace_bytes(...) bytes
+ *              (0 = unsupported shape).
  * Two launches; the sums over tokens use no atomics and are bitwise reproducible.
  */
 size_t tvmattn_adaln_jvp_bwd_workspace_bytes(int B, int T, int C, int dtype);

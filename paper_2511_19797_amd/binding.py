@@ -14,13 +14,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtvmattn.so")
 
 TVMATTN_F32, TVMATTN_BF16 = 0, 1
+TVMATTN_FLAG_PLAIN_ALU = 1
 
 
 class tvmattn_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("M", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("M", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("qstride_b", ctypes.c_int64), ("qstride_h", ctypes.c_int64), ("qstride_n", ctypes.c_int64)]
 
 
@@ -45,16 +46,15 @@ def lib():
         L.tvmattn_version.restype = ctypes.c_int
         L.tvmattn_strerror.restype = ctypes.c_char_p
         L.tvmattn_strerror.argtypes = [ctypes.c_int]
-        L.tvmattn_set_path.restype = ctypes.c_int
-        L.tvmattn_set_path.argtypes = [ctypes.c_int]
-        L.tvmattn_set_bwd_events.restype = ctypes.c_int
-        L.tvmattn_set_bwd_events.argtypes = [ctypes.POINTER(_P)]
         L.tvmattn_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 11
         L.tvmattn_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.tvmattn_jvp_bwd_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
         L.tvmattn_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_jvp_bwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 19 + [ctypes.c_size_t, _P]
+        L.tvmattn_jvp_bwd_timed.restype = ctypes.c_int
+        L.tvmattn_jvp_bwd_timed.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 19 +
+                                            [ctypes.c_size_t, ctypes.POINTER(_P), _P])
         L.tvmattn_qknorm_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_qknorm_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 5
         L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -68,11 +68,10 @@ def lib():
         L.tvmattn_jvp_bwd_qknorm.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 21 +
                                              [ctypes.c_size_t, _P])
         _I = ctypes.c_int
-        for fn in (L.tvmattn_adaln_jvp_fwd_workspace_bytes, L.tvmattn_adaln_jvp_bwd_workspace_bytes):
-            fn.restype = ctypes.c_size_t
-            fn.argtypes = [_I] * 4
+        L.tvmattn_adaln_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_adaln_jvp_bwd_workspace_bytes.argtypes = [_I] * 4
         L.tvmattn_adaln_jvp_fwd.restype = ctypes.c_int
-        L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3 + [ctypes.c_size_t, _P]
+        L.tvmattn_adaln_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3
         L.tvmattn_adaln_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_adaln_jvp_bwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 9 + [ctypes.c_size_t, _P]
         L.tvmattn_adaln_jvp_bwd_residual.restype = ctypes.c_int
@@ -99,28 +98,14 @@ def tvmattn_strerror(status):
     return lib().tvmattn_strerror(int(status)).decode()
 
 
-def tvmattn_set_path(path):
-    _check(lib().tvmattn_set_path(int(path)))
-
-
-def tvmattn_set_bwd_events(events):
-    """`events`: None, or four raw hipEvent_t handles (ints, created with timing enabled; None or 0
-    skips that record)."""
-    if events is None:
-        _check(lib().tvmattn_set_bwd_events(None))
-    else:
-        arr = (_P * 4)(*[_P(int(e)) if e else _P(None) for e in events])
-        _check(lib().tvmattn_set_bwd_events(arr))
-
-
 def _check(status):
     if status != 0:
         raise TvmattnError(status, tvmattn_strerror(status))
 
 
-def make_desc(x: torch.Tensor, scale=0.0, q: torch.Tensor = None) -> tvmattn_desc:
+def make_desc(x: torch.Tensor, scale=0.0, q: torch.Tensor = None, flags=0) -> tvmattn_desc:
     """Descriptor for key-side tensors shaped and strided like `x` [B,H,N,D] and query-side tensors like `q`
-    [B,H,M,D] (default: like `x`); any strides with unit innermost stride."""
+    [B,H,M,D] (default: like `x`); any strides with unit innermost stride.  `flags`: TVMATTN_FLAG_* bits."""
     q = x if q is None else q
     for t in (x, q):
         if t.dim() != 4:
@@ -137,7 +122,7 @@ def make_desc(x: torch.Tensor, scale=0.0, q: torch.Tensor = None) -> tvmattn_des
     if q.dtype != x.dtype or (q.shape[0], q.shape[1], q.shape[3]) != (B, H, D):
         raise ValueError("query-side and key-side tensors must agree in B, H, D and dtype")
     return tvmattn_desc(B, H, N, D, dt, float(scale), x.stride(0), x.stride(1), x.stride(2),
-                        q.shape[2], 0, q.stride(0), q.stride(1), q.stride(2))
+                        q.shape[2], int(flags), q.stride(0), q.stride(1), q.stride(2))
 
 
 def _same_layout(ref, *ts):
@@ -164,12 +149,12 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
-def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True):
+def tvmattn_jvp_fwd(q, k, v, tq, tk, tv, scale=0.0, out=None, save=True, flags=0):
     """Returns (o, to, lse, stats).  `out`, if given, is that same tuple of preallocated tensors.
     save=False: nothing is kept for a backward (lse and stats are None)."""
     _same_layout(q, tq)
     _same_layout(k, v, tk, tv)
-    desc = make_desc(k, scale, q)
+    desc = make_desc(k, scale, q, flags)
     B, H, N, _ = q.shape  # row vectors go with the queries
     if out is None:
         o, to = _like(q), _like(q)
@@ -190,27 +175,40 @@ def tvmattn_jvp_bwd_workspace_bytes(q, scale=0.0, k=None):
     return int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
 
 
-def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, out=None, workspace=None):
-    """Returns (dq, dk, dv, dtq, dtk, dtv).
-
-    gTO=None: the ordinary attention backward (gradient of <gO, O> alone); tq, tk, tv, to, stats may be
-    None and dtq, dtk, dtv come back as None.  gO=None: the gradient of <gTO, tO> alone."""
+def _bwd_args(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale, out, flags):
     _same_layout(*[t for t in (q, tq, o, to, gO, gTO) if t is not None])
     _same_layout(*[t for t in (k, v, tk, tv) if t is not None])
-    desc = make_desc(k, scale, q)
+    desc = make_desc(k, scale, q, flags)
     if out is None:  # dq, dk, dv, dtq, dtk, dtv
         out = tuple(_like(q if n in (0, 3) else k) if (gTO is not None or n < 3) else None for n in range(6))
     else:
         _same_layout(q, *[t for n, t in enumerate(out) if t is not None and n in (0, 3)])
         _same_layout(k, *[t for n, t in enumerate(out) if t is not None and n not in (0, 3)])
+    dq, dk, dv, dtq, dtk, dtv = out
+    ptrs = [q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk), _ptr(tv), o.data_ptr(), _ptr(to),
+            lse.data_ptr(), _ptr(stats), _ptr(gO), _ptr(gTO), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _ptr(dtq),
+            _ptr(dtk), _ptr(dtv)]
+    return desc, out, ptrs
+
+
+def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, out=None, workspace=None, flags=0,
+                    events=None):
+    """Returns (dq, dk, dv, dtq, dtk, dtv).
+
+    gTO=None: the ordinary attention backward (gradient of <gO, O> alone); tq, tk, tv, to, stats may be
+    None and dtq, dtk, dtv come back as None.  gO=None: the gradient of <gTO, tO> alone.
+    events: None, or four raw hipEvent_t handles (ints, created with timing enabled; None or 0 skips that
+    record): the call goes through tvmattn_jvp_bwd_timed."""
+    desc, out, ptrs = _bwd_args(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale, out, flags)
     need = int(lib().tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(desc)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    dq, dk, dv, dtq, dtk, dtv = out
-    _check(lib().tvmattn_jvp_bwd(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk),
-                                 _ptr(tv), o.data_ptr(), _ptr(to), lse.data_ptr(), _ptr(stats), _ptr(gO), _ptr(gTO),
-                                 dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _ptr(dtq), _ptr(dtk), _ptr(dtv),
-                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    wsb = workspace.numel() * workspace.element_size()
+    if events is None:
+        _check(lib().tvmattn_jvp_bwd(ctypes.byref(desc), *ptrs, workspace.data_ptr(), wsb, _stream()))
+    else:
+        arr = (_P * 4)(*[_P(int(e)) if e else _P(None) for e in events])
+        _check(lib().tvmattn_jvp_bwd_timed(ctypes.byref(desc), *ptrs, workspace.data_ptr(), wsb, arr, _stream()))
     return out
 
 
@@ -316,16 +314,12 @@ def _adaln_args(x, tx, mods):
     return B, T, C, dt
 
 
-def tvmattn_adaln_jvp_fwd(x, tx, a, ta, b, tb, eps, out=None, workspace=None):
+def tvmattn_adaln_jvp_fwd(x, tx, a, ta, b, tb, eps, out=None):
     """Returns (y, ty): RMSNorm^-(x) * RMSNorm^-(a) + RMSNorm^-(b) and its tangent along (tx, ta, tb)."""
     B, T, C, dt = _adaln_args(x, tx, (a, ta, b, tb))
     y, ty = out if out is not None else (torch.empty_like(x), torch.empty_like(x))
-    need = int(lib().tvmattn_adaln_jvp_fwd_workspace_bytes(B, T, C, dt))
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     _check(lib().tvmattn_adaln_jvp_fwd(B, T, C, dt, x.data_ptr(), tx.data_ptr(), a.data_ptr(), ta.data_ptr(), b.data_ptr(),
-                                       tb.data_ptr(), float(eps), y.data_ptr(), ty.data_ptr(), workspace.data_ptr(),
-                                       workspace.numel(), _stream()))
+                                       tb.data_ptr(), float(eps), y.data_ptr(), ty.data_ptr(), _stream()))
     return y, ty
 
 

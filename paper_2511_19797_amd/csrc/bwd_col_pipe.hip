@@ -33,6 +33,9 @@
 // products that remain.
 //
 // The translation unit is built with the machine scheduler off: source order is issue order.
+#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY) && !defined(TVM_PIPE_QKNORM)
+#define TVM_PROF_READER tvmattn_debug_read_prof_col_pipe
+#endif
 #include "pipe_ops.h"
 
 #include <type_traits>
@@ -489,9 +492,4 @@ hipError_t TVM_PIPE_LAUNCHER(const Shape& s, const BwdArgs& a, hipStream_t st) {
   }
 }
 
-#if defined(TVM_PROFILE) && !defined(TVM_PIPE_TANGENT_ONLY) && !defined(TVM_PIPE_QKNORM)
-extern "C" int tvmattn_debug_read_prof_col_pipe(long long* out16) {
-  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(tvm::g_prof_pipe), sizeof(long long) * 16);
-}
-#endif
 }  // namespace tvm

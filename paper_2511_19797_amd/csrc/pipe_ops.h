@@ -15,40 +15,7 @@ namespace tvm {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-// Optional cycle stamps per phase (build with -DTVM_PROFILE; each translation unit has its own counters and exports its own reader).
-#if defined(TVM_PROFILE)
-#if !defined(TVM_PROF_BLOCK)
-#define TVM_PROF_BLOCK 3  // hardware id of the workgroup whose stamps are kept
-#endif
-static __device__ long long g_prof_pipe[16];
-#define PROF_ENTRY const long long pe_ = clock64(); long long pp_[16]
-#define PROF_P(i) pp_[i] = clock64() - pe_
-#define PROF_DECL long long pt_ = clock64(), pa_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; const long long pl_ = pt_
-#define PROF(i)                        \
-  do {                                 \
-    const long long n_ = clock64();    \
-    pa_[i] += n_ - pt_;                \
-    pt_ = n_;                          \
-  } while (0)
-#define PROF_DUMP                                  \
-  const long long px_ = clock64();                 \
-  if (blockIdx.x == TVM_PROF_BLOCK && threadIdx.x == 0)         \
-    for (int i_ = 0; i_ < 8; ++i_) g_prof_pipe[i_] = pa_[i_]
-#define PROF_EXIT                                                      \
-  if (blockIdx.x == TVM_PROF_BLOCK && threadIdx.x == 0) {                           \
-    g_prof_pipe[8] = pl_ - pe_;                                        \
-    g_prof_pipe[9] = px_ - pl_;                                        \
-    g_prof_pipe[10] = clock64() - px_;                                 \
-    for (int i_ = 11; i_ < 16; ++i_) g_prof_pipe[i_] = pp_[i_];        \
-  }
-#else
-#define PROF_ENTRY
-#define PROF_P(i)
-#define PROF_DECL
-#define PROF(i)
-#define PROF_DUMP
-#define PROF_EXIT
-#endif
+#include "pipe_prof.h"  // PROF_* cycle stamps: empty unless this is a diagnostic build (-DTVM_PROFILE)
 
 __device__ __forceinline__ bf16x8 lds_read16(unsigned addr, int imm) {
   typedef const bf16x8 __attribute__((address_space(3))) * lp;

@@ -7,46 +7,52 @@
 
 namespace {
 
-int g_path = 0;  // 0 = choose per shape, 1 = plain-ALU kernels only (diagnostic)
-hipEvent_t g_ev[4];
-bool g_ev_on = false;
-
-inline void mark(int i, hipStream_t st) {
-  if (g_ev_on && g_ev[i]) (void)hipEventRecord(g_ev[i], st);
+inline void mark(void* const* events, int i, hipStream_t st) {
+  if (events && events[i]) (void)hipEventRecord(static_cast<hipEvent_t>(events[i]), st);
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// One side's strides: all zero selects `dflt_*`; otherwise row pitch >= D and 16-byte multiples.
-bool side_strides(long long esz, int D, long long& sb, long long& sh, long long& sn, long long dflt_b, long long dflt_h,
-                  long long dflt_n) {
+// One side's strides: all zero selects `dflt_*`; otherwise row pitch >= D and 16-byte multiples.  The whole tensor
+// must fit the 2^47-byte address space (which also keeps every later product of sizes and strides inside 64 bits).
+bool side_strides(long long esz, int B, int H, int rows, int D, long long& sb, long long& sh, long long& sn,
+                  long long dflt_b, long long dflt_h, long long dflt_n) {
   if (sb == 0 && sh == 0 && sn == 0) {
     sb = dflt_b;
     sh = dflt_h;
     sn = dflt_n;
   }
-  if (sn < D || sh < 1 || sb < 1) return false;
+  constexpr long long kMax = 1ll << 46;  // elements
+  if (sn < D || sh < 1 || sb < 1 || sn > kMax || sh > kMax || sb > kMax) return false;
+  long long eb, eh, en, ext;
+  if (__builtin_mul_overflow((long long)(B - 1), sb, &eb) || __builtin_mul_overflow((long long)(H - 1), sh, &eh) ||
+      __builtin_mul_overflow((long long)(rows - 1), sn, &en) || __builtin_add_overflow(eb, eh, &ext) ||
+      __builtin_add_overflow(ext, en, &ext) || __builtin_add_overflow(ext, (long long)D, &ext) || ext > kMax)
+    return false;
   return (sn * esz) % 16 == 0 && (sh * esz) % 16 == 0 && (sb * esz) % 16 == 0;
 }
 
 // Validates the descriptor and resolves sizes, strides and scale.
 int resolve(const tvmattn_desc* d, tvm::Shape* s) {
   if (!d) return TVMATTN_INVALID_ARG;
-  if (d->B < 1 || d->H < 1 || d->N < 1 || d->D < 1 || d->M < 0 || d->reserved != 0) return TVMATTN_INVALID_ARG;
+  if (d->B < 1 || d->H < 1 || d->N < 1 || d->D < 1 || d->M < 0 || (d->flags & ~TVMATTN_FLAG_PLAIN_ALU) != 0)
+    return TVMATTN_INVALID_ARG;
   if (d->dtype != TVMATTN_F32 && d->dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
   if (d->D > 256) return TVMATTN_UNSUPPORTED;
   if (!(d->scale >= 0.f) || isinf(d->scale)) return TVMATTN_INVALID_ARG;
   const long long esz = d->dtype == TVMATTN_F32 ? 4 : 2;
   const int M = d->M ? d->M : d->N;
+  if ((long long)d->B * d->H >= (1ll << 31) || (long long)d->B * d->H * d->N >= (1ll << 31) ||
+      (long long)d->B * d->H * M >= (1ll << 31))
+    return TVMATTN_UNSUPPORTED;
   long long sb = d->stride_b, sh = d->stride_h, sn = d->stride_n;
-  if (!side_strides(esz, d->D, sb, sh, sn, (long long)d->N * d->D * d->H, (long long)d->N * d->D, d->D))
+  if (!side_strides(esz, d->B, d->H, d->N, d->D, sb, sh, sn, (long long)d->N * d->D * d->H, (long long)d->N * d->D, d->D))
     return TVMATTN_INVALID_ARG;
   long long qsb = d->qstride_b, qsh = d->qstride_h, qsn = d->qstride_n;
   const bool same = M == d->N;  // self-attention: the query side defaults to the key side's layout
-  if (!side_strides(esz, d->D, qsb, qsh, qsn, same ? sb : (long long)M * d->D * d->H, same ? sh : (long long)M * d->D,
-                    same ? sn : d->D))
+  if (!side_strides(esz, d->B, d->H, M, d->D, qsb, qsh, qsn, same ? sb : (long long)M * d->D * d->H,
+                    same ? sh : (long long)M * d->D, same ? sn : d->D))
     return TVMATTN_INVALID_ARG;
-  if ((long long)d->B * d->H * d->N >= (1ll << 31) || (long long)d->B * d->H * M >= (1ll << 31)) return TVMATTN_UNSUPPORTED;
   s->B = d->B;
   s->H = d->H;
   s->N = d->N;
@@ -62,32 +68,105 @@ int resolve(const tvmattn_desc* d, tvm::Shape* s) {
   return TVMATTN_OK;
 }
 
-// Every listed pointer must be non-null and 16-byte aligned, no output may be an input or another
-// output.  Entries that the call's mode does not use are passed as `skip` (a null there is fine,
-// and the pointer takes no part in the aliasing check).
-const void* const skip = reinterpret_cast<const void*>(uintptr_t(1));
+// A buffer as the overlap check sees it: `dims` levels of (count, byte stride) around an innermost run of
+// `inner` bytes.  dims = 0 is a plain range.
+struct Buf {
+  const void* p;
+  int dims;
+  long long n[3], s[3];
+  long long inner;
+  long long extent() const {
+    long long e = inner;
+    for (int i = 0; i < dims; ++i) e += (n[i] - 1) * s[i];
+    return e;
+  }
+  bool same_layout(const Buf& o) const {
+    if (dims != o.dims || inner != o.inner) return false;
+    for (int i = 0; i < dims; ++i)
+      if (n[i] != o.n[i] || s[i] != o.s[i]) return false;
+    return true;
+  }
+};
+const void* const skip = reinterpret_cast<const void*>(uintptr_t(1));  // an entry the call's mode does not use
+inline Buf plain(const void* p, long long bytes) { return Buf{p, 0, {0, 0, 0}, {0, 0, 0}, bytes}; }
+// One side's [B,H,rows,D] tensor with that side's strides, levels sorted by descending stride.
+Buf side_buf(const void* p, const tvm::Shape& s, bool query_side, long long esz) {
+  Buf b{p, 3, {s.B, s.H, query_side ? s.M : s.N},
+        {(query_side ? s.qsb : s.sb) * esz, (query_side ? s.qsh : s.sh) * esz, (query_side ? s.qsn : s.sn) * esz},
+        (long long)s.D * esz};
+  for (int i = 0; i < 3; ++i)
+    for (int j = i + 1; j < 3; ++j)
+      if (b.s[j] > b.s[i]) {
+        const long long tn = b.n[i], ts = b.s[i];
+        b.n[i] = b.n[j];
+        b.s[i] = b.s[j];
+        b.n[j] = tn;
+        b.s[j] = ts;
+      }
+  return b;
+}
+// Do two buffers of ONE layout, `delta` bytes apart, share a byte?  They do iff delta = sum_k d_k s_k + e with
+// |d_k| < n_k and |e| < inner.  Where every stride is at least the extent of the levels inside it (any dense or
+// sliced tensor), what the inner levels can contribute is smaller than the stride, so only the two multiples of
+// s_k around delta can start a solution: a walk of depth `dims` with two branches per level.
+bool lattice_hit(const Buf& b, int level, long long delta) {
+  if (level == b.dims) return delta > -b.inner && delta < b.inner;
+  const long long st = b.s[level];
+  long long d0 = delta / st;
+  if (delta < 0 && d0 * st != delta) --d0;  // floor
+  for (long long d = d0; d <= d0 + 1; ++d)
+    if (d > -b.n[level] && d < b.n[level] && lattice_hit(b, level + 1, delta - d * st)) return true;
+  return false;
+}
+bool nested(const Buf& b) {
+  long long inside = b.inner;
+  for (int i = b.dims - 1; i >= 0; --i) {
+    if (b.s[i] < inside) return false;
+    inside = (b.n[i] - 1) * b.s[i] + inside;
+  }
+  return true;
+}
+bool overlap(const Buf& a, const Buf& b) {
+  const long long pa = (long long)reinterpret_cast<uintptr_t>(a.p), pb = (long long)reinterpret_cast<uintptr_t>(b.p);
+  if (pa + a.extent() <= pb || pb + b.extent() <= pa) return false;  // disjoint address ranges
+  if (a.same_layout(b) && nested(a)) return lattice_hit(a, 0, pb - pa);
+  return true;
+}
+// Every listed pointer must be non-null and 16-byte aligned, and no output may overlap an input or another
+// output.  Entries that the call's mode does not use are passed with p == skip (a null there is fine, and the
+// buffer takes no part in the overlap check).  `inout`: pairs (output index, input index) that may be the very
+// same buffer (an update in place).
 template <size_t NI, size_t NO>
-int check_ptrs(const void* const (&in)[NI], void* const (&out)[NO]) {
+int check_bufs(const Buf (&in)[NI], const Buf (&out)[NO], int same_o = -1, int same_i = -1, int same_o2 = -1,
+               int same_i2 = -1) {
   for (size_t i = 0; i < NI; ++i)
-    if (in[i] != skip && (!in[i] || !aligned16(in[i]))) return TVMATTN_INVALID_ARG;
+    if (in[i].p != skip && (!in[i].p || !aligned16(in[i].p))) return TVMATTN_INVALID_ARG;
   for (size_t o = 0; o < NO; ++o) {
-    if (out[o] == skip) continue;
-    if (!out[o] || !aligned16(out[o])) return TVMATTN_INVALID_ARG;
-    for (size_t i = 0; i < NI; ++i)
-      if (out[o] == in[i]) return TVMATTN_INVALID_ARG;
+    if (out[o].p == skip) continue;
+    if (!out[o].p || !aligned16(out[o].p)) return TVMATTN_INVALID_ARG;
+    for (size_t i = 0; i < NI; ++i) {
+      if (in[i].p == skip) continue;
+      const bool allowed = ((int)o == same_o && (int)i == same_i) || ((int)o == same_o2 && (int)i == same_i2);
+      if (allowed && out[o].p == in[i].p) continue;
+      if (overlap(out[o], in[i])) return TVMATTN_INVALID_ARG;
+    }
     for (size_t p = 0; p < o; ++p)
-      if (out[o] == out[p]) return TVMATTN_INVALID_ARG;
+      if (out[p].p != skip && overlap(out[o], out[p])) return TVMATTN_INVALID_ARG;
   }
   return TVMATTN_OK;
 }
-inline const void* unless(bool unused, const void* p) { return unused ? skip : p; }
-inline void* unless(bool unused, void* p) { return unused ? const_cast<void*>(skip) : p; }
+inline Buf unless(bool unused, Buf b) {
+  if (unused) b.p = skip;
+  return b;
+}
+inline long long esz_of(int dtype) { return dtype == TVMATTN_F32 ? 4 : 2; }
+inline bool plain_alu(const tvmattn_desc* d) { return (d->flags & TVMATTN_FLAG_PLAIN_ALU) != 0; }
 
 }  // namespace
 
 extern "C" {
 
-int tvmattn_version(void) { return 500; }  // 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 600; }  // 0.6.0: per-call flags instead of process-wide switches, tvmattn_jvp_bwd_timed; 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -100,19 +179,6 @@ const char* tvmattn_strerror(int status) {
   }
 }
 
-int tvmattn_set_path(int path) {
-  if (path != 0 && path != 1) return TVMATTN_INVALID_ARG;
-  g_path = path;
-  return TVMATTN_OK;
-}
-
-int tvmattn_set_bwd_events(void* const* events) {
-  g_ev_on = events != nullptr;
-  if (events)
-    for (int i = 0; i < 4; ++i) g_ev[i] = static_cast<hipEvent_t>(events[i]);  // NULL: that record is skipped
-  return TVMATTN_OK;
-}
-
 int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
                     const void* tk, const void* tv, void* o, void* to, float* lse, float* stats, void* hip_stream) {
   tvm::Shape s;
@@ -120,14 +186,17 @@ int tvmattn_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* k, cons
   if (rc) return rc;
   if ((lse == nullptr) != (stats == nullptr)) return TVMATTN_INVALID_ARG;  // saved together or not at all
   const bool nosave = lse == nullptr;
-  const void* const in[] = {q, k, v, tq, tk, tv};
-  void* const out[] = {o, to, unless(nosave, (void*)lse), unless(nosave, (void*)stats)};
-  rc = check_ptrs(in, out);
+  const long long esz = esz_of(desc->dtype), rvb = (long long)s.B * s.H * s.M * 4;
+  const Buf in[] = {side_buf(q, s, true, esz),  side_buf(k, s, false, esz),  side_buf(v, s, false, esz),
+                    side_buf(tq, s, true, esz), side_buf(tk, s, false, esz), side_buf(tv, s, false, esz)};
+  const Buf out[] = {side_buf(o, s, true, esz), side_buf(to, s, true, esz), unless(nosave, plain(lse, rvb)),
+                     unless(nosave, plain(stats, rvb))};
+  rc = check_bufs(in, out);
   if (rc) return rc;
   tvm::FwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats};
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (g_path == 0 && tvm::mfma_supported(s, desc->dtype))
+  if (!plain_alu(desc) && tvm::mfma_supported(s, desc->dtype))
     e = tvm::launch_fwd_mfma(s, a, st);
   else
     e = tvm::launch_fwd_generic(s, desc->dtype, a, st);
@@ -144,46 +213,74 @@ size_t tvmattn_jvp_bwd_workspace_bytes(const tvmattn_desc* desc) {
   return 3 * one;
 }
 
-int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
-                    const void* tk, const void* tv, const void* o, const void* to, const float* lse,
-                    const float* stats, const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq,
-                    void* dtk, void* dtv, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  tvm::Shape s;
-  int rc = resolve(desc, &s);
-  if (rc) return rc;
+namespace {
+// The backward proper, with the three row vectors (one float per query row each) wherever the caller's entry
+// point keeps them.  Pointer checks of everything but the row vectors included.
+int bwd_impl(const tvmattn_desc* desc, const tvm::Shape& s, const void* q, const void* k, const void* v, const void* tq,
+             const void* tk, const void* tv, const void* o, const void* to, const float* lse, const float* stats,
+             const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv, float* row0,
+             float* row1, float* row2, bool rows_fit, void* const* events, void* hip_stream) {
   if (!gO && !gTO) return TVMATTN_INVALID_ARG;
   // one upstream gradient only: 1 = gO (the tangent inputs and outputs take no part), 2 = gTO
   const int mode = !gTO ? 1 : !gO ? 2 : 0;
   const bool m1 = mode == 1;
-  const void* const in[] = {q, k, v, unless(m1, tq), unless(m1, tk), unless(m1, tv), o, unless(m1, to), lse,
-                            unless(m1, (const void*)stats), unless(mode == 2, gO), unless(m1, gTO)};
-  void* const out[] = {dq, dk, dv, unless(m1, dtq), unless(m1, dtk), unless(m1, dtv), workspace};
-  rc = check_ptrs(in, out);
+  const long long esz = esz_of(desc->dtype), rvb = (long long)s.B * s.H * s.M * 4;
+  auto qs = [&](const void* p) { return side_buf(p, s, true, esz); };
+  auto ks = [&](const void* p) { return side_buf(p, s, false, esz); };
+  const Buf in[] = {qs(q), ks(k), ks(v), unless(m1, qs(tq)), unless(m1, ks(tk)), unless(m1, ks(tv)), qs(o),
+                    unless(m1, qs(to)), plain(lse, rvb), unless(m1, plain(stats, rvb)), unless(mode == 2, qs(gO)),
+                    unless(m1, qs(gTO))};
+  const Buf out[] = {qs(dq), ks(dk), ks(dv), unless(m1, qs(dtq)), unless(m1, ks(dtk)), unless(m1, ks(dtv)),
+                     plain(row0, rvb), plain(row1, rvb), plain(row2, rvb)};
+  const int rc = check_bufs(in, out);
   if (rc) return rc;
-  const size_t need = tvmattn_jvp_bwd_workspace_bytes(desc);
-  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
-  tvm::BwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
-                 static_cast<float*>(workspace),
-                 reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 3),
-                 reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * (need / 3)), mode};
+  if (!rows_fit) return TVMATTN_WORKSPACE_TOO_SMALL;
+  tvm::BwdArgs a{q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv, row0, row1, row2, mode};
   if (m1) {  // not read, not written: whatever was passed
     a.tq = a.tk = a.tv = a.to = nullptr;
     a.stats = nullptr;
     a.dtq = a.dtk = a.dtv = nullptr;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const bool mf = g_path == 0 && tvm::mfma_supported(s, desc->dtype);
+  const bool mf = !plain_alu(desc) && tvm::mfma_supported(s, desc->dtype);
   hipError_t e = hipSuccess;
-  mark(0, st);
+  mark(events, 0, st);
   if (!mf) e = tvm::launch_bwd_pre(s, desc->dtype, a, st);  // the matrix-core query-side kernel does Step 1 itself
   if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
-  mark(1, st);
+  mark(events, 1, st);
   e = mf ? tvm::launch_bwd_row_mfma(s, a, st) : tvm::launch_bwd_row_generic(s, desc->dtype, a, st);
   if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
-  mark(2, st);
+  mark(events, 2, st);
   e = mf ? tvm::launch_bwd_col_mfma(s, a, st) : tvm::launch_bwd_col_generic(s, desc->dtype, a, st);
-  mark(3, st);
+  mark(events, 3, st);
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+inline size_t row_vector_bytes(const tvm::Shape& s) {  // one float32 per query row, padded to a 256-byte multiple
+  return ((size_t)s.B * s.H * s.M * sizeof(float) + 255) & ~(size_t)255;
+}
+}  // namespace
+
+int tvmattn_jvp_bwd_timed(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
+                          const void* tk, const void* tv, const void* o, const void* to, const float* lse,
+                          const float* stats, const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq,
+                          void* dtk, void* dtv, void* workspace, size_t workspace_bytes, void* const* events,
+                          void* hip_stream) {
+  tvm::Shape s;
+  const int rc = resolve(desc, &s);
+  if (rc) return rc;
+  const size_t one = row_vector_bytes(s);
+  char* const ws = static_cast<char*>(workspace);  // (a null workspace fails the pointer checks in bwd_impl)
+  return bwd_impl(desc, s, q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
+                  reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws ? ws + one : nullptr),
+                  reinterpret_cast<float*>(ws ? ws + 2 * one : nullptr), workspace_bytes >= 3 * one, events, hip_stream);
+}
+
+int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
+                    const void* tk, const void* tv, const void* o, const void* to, const float* lse,
+                    const float* stats, const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq,
+                    void* dtk, void* dtv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return tvmattn_jvp_bwd_timed(desc, q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
+                               workspace, workspace_bytes, nullptr, hip_stream);
 }
 
 // ---- RMSNorm with gain as QK-norm, with tangent
@@ -219,9 +316,12 @@ int tvmattn_qknorm_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* 
   int rc = resolve(desc, &s);
   if (rc) return rc;
   if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
-  const void* const in[] = {q, tq, k, tk, gain_q, gain_k};
-  void* const out[] = {qn, tqn, kn, tkn};
-  rc = check_ptrs(in, out);
+  const long long esz = esz_of(desc->dtype), gb = (long long)s.D * 4;
+  auto qs = [&](const void* p) { return side_buf(p, s, true, esz); };
+  auto ks = [&](const void* p) { return side_buf(p, s, false, esz); };
+  const Buf in[] = {qs(q), qs(tq), ks(k), ks(tk), plain(gain_q, gb), plain(gain_k, gb)};
+  const Buf out[] = {qs(qn), qs(tqn), ks(kn), ks(tkn)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
   tvm::NormArgs a{};
   norm_sides(s, &a, eps);
@@ -256,11 +356,15 @@ int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* 
   int rc = resolve(desc, &s);
   if (rc) return rc;
   if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
-  const void* const in[] = {q, tq, k, tk, gain_q, gain_k, gqn, gtqn, gkn, gtkn};
-  void* const out[] = {dq, dtq, dk, dtk, dgain_q, dgain_k, workspace};
-  rc = check_ptrs(in, out);
+  const long long esz = esz_of(desc->dtype), gb = (long long)s.D * 4;
+  const size_t need = tvmattn_qknorm_jvp_bwd_workspace_bytes(desc);
+  auto qs = [&](const void* p) { return side_buf(p, s, true, esz); };
+  auto ks = [&](const void* p) { return side_buf(p, s, false, esz); };
+  const Buf in[] = {qs(q), qs(tq), ks(k), ks(tk), plain(gain_q, gb), plain(gain_k, gb), qs(gqn), qs(gtqn), ks(gkn), ks(gtkn)};
+  const Buf out[] = {qs(dq), qs(dtq), ks(dk), ks(dtk), plain(dgain_q, gb), plain(dgain_k, gb), plain(workspace, (long long)need)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
-  if (workspace_bytes < tvmattn_qknorm_jvp_bwd_workspace_bytes(desc)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::NormArgs a{};
   norm_sides(s, &a, eps);
   a.side[0].x = q;
@@ -292,14 +396,14 @@ size_t fused_part_bytes(const tvm::Shape& s, bool query_side) {  // one float32 
   const size_t blocks = (size_t)(((query_side ? s.M : s.N) + 127) / 128) * s.B * s.H;
   return pad256(blocks * s.D * sizeof(float));
 }
-bool fused_supported(const tvm::Shape& s, int dtype) {
-  return g_path == 0 && tvm::mfma_supported(s, dtype) && s.D <= 96;
+bool fused_supported(const tvmattn_desc* d, const tvm::Shape& s) {
+  return !plain_alu(d) && tvm::mfma_supported(s, d->dtype) && s.D <= 96;
 }
 }  // namespace
 
 size_t tvmattn_jvp_bwd_qknorm_workspace_bytes(const tvmattn_desc* desc) {
   tvm::Shape s;
-  if (resolve(desc, &s) || !fused_supported(s, desc->dtype)) return 0;
+  if (resolve(desc, &s) || !fused_supported(desc, s)) return 0;
   return tvmattn_jvp_bwd_workspace_bytes(desc) + fused_part_bytes(s, true) + fused_part_bytes(s, false);
 }
 
@@ -313,12 +417,18 @@ int tvmattn_jvp_bwd_qknorm(const tvmattn_desc* desc, const void* q, const void* 
   int rc = resolve(desc, &s);
   if (rc) return rc;
   if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
-  const void* const in[] = {q, tq, k, tk, gain_q, gain_k, qn, tqn, kn, tkn, v, tv, o, to, lse, stats, gO, gTO};
-  void* const out[] = {dq, dk, dv, dtq, dtk, dtv, dgain_q, dgain_k, workspace};
-  rc = check_ptrs(in, out);
+  if (!fused_supported(desc, s)) return TVMATTN_UNSUPPORTED;
+  const long long esz = esz_of(desc->dtype), gb = (long long)s.D * 4, rvb = (long long)s.B * s.H * s.M * 4;
+  const size_t need = tvmattn_jvp_bwd_qknorm_workspace_bytes(desc);
+  auto qs = [&](const void* p) { return side_buf(p, s, true, esz); };
+  auto ks = [&](const void* p) { return side_buf(p, s, false, esz); };
+  const Buf in[] = {qs(q),  qs(tq), ks(k), ks(tk), plain(gain_q, gb), plain(gain_k, gb), qs(qn),  qs(tqn),          ks(kn),
+                    ks(tkn), ks(v),  ks(tv), qs(o), qs(to),            plain(lse, rvb),   plain(stats, rvb), qs(gO), qs(gTO)};
+  const Buf out[] = {qs(dq), ks(dk), ks(dv), qs(dtq), ks(dtk), ks(dtv), plain(dgain_q, gb), plain(dgain_k, gb),
+                     plain(workspace, (long long)need)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
-  if (!fused_supported(s, desc->dtype)) return TVMATTN_UNSUPPORTED;
-  if (workspace_bytes < tvmattn_jvp_bwd_qknorm_workspace_bytes(desc)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
   const size_t need0 = tvmattn_jvp_bwd_workspace_bytes(desc);
   char* const ws = static_cast<char*>(workspace);
   tvm::BwdArgs a{qn, kn, v, tqn, tkn, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
@@ -350,27 +460,22 @@ int adaln_check(int B, int T, int C, int dtype, float eps) {
   if (!tvm::adaln_supported(C, dtype) || (long long)B * T >= (1ll << 31) || B > 65535) return TVMATTN_UNSUPPORTED;
   return TVMATTN_OK;
 }
-// The forward needs no workspace any more; the query keeps a non-zero answer for valid shapes (0 = unsupported).
-constexpr size_t kAdalnFwdWorkspace = 256;
+inline long long tok_bytes(int B, int T, int C, int dtype) { return (long long)B * T * C * esz_of(dtype); }
+inline long long mod_bytes(int B, int C) { return (long long)B * C * 4; }
 size_t adaln_part_bytes(int B, int T, int C) {
   return pad256((size_t)B * tvm::adaln_wgs(B, T, true, false) * 4 * C * sizeof(float));
 }
 }  // namespace
 
-size_t tvmattn_adaln_jvp_fwd_workspace_bytes(int B, int T, int C, int dtype) {
-  return adaln_check(B, T, C, dtype, 0.f) ? 0 : kAdalnFwdWorkspace;
-}
-
 int tvmattn_adaln_jvp_fwd(int B, int T, int C, int dtype, const void* x, const void* tx, const float* a, const float* ta,
-                          const float* b, const float* tb, float eps, void* y, void* ty, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+                          const float* b, const float* tb, float eps, void* y, void* ty, void* hip_stream) {
   int rc = adaln_check(B, T, C, dtype, eps);
   if (rc) return rc;
-  const void* const in[] = {x, tx, a, ta, b, tb};
-  void* const out[] = {y, ty, workspace};
-  rc = check_ptrs(in, out);
+  const long long tb_ = tok_bytes(B, T, C, dtype), mb = mod_bytes(B, C);
+  const Buf in[] = {plain(x, tb_), plain(tx, tb_), plain(a, mb), plain(ta, mb), plain(b, mb), plain(tb, mb)};
+  const Buf out[] = {plain(y, tb_), plain(ty, tb_)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
-  if (workspace_bytes < kAdalnFwdWorkspace) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::AdalnArgs g{};
   g.x = x;
   g.tx = tx;
@@ -401,11 +506,16 @@ int tvmattn_adaln_jvp_bwd_residual(int B, int T, int C, int dtype, const void* x
   int rc = adaln_check(B, T, C, dtype, eps);
   if (rc) return rc;
   if ((gres == nullptr) != (gtres == nullptr)) return TVMATTN_INVALID_ARG;
-  const void* const in[] = {x, tx, a, ta, b, tb, gy, gty, unless(!gres, gres), unless(!gtres, gtres)};
-  void* const out[] = {gx, gtx, ga, gta, gb, gtb, workspace};
-  rc = check_ptrs(in, out);
+  const long long tb_ = tok_bytes(B, T, C, dtype), mb = mod_bytes(B, C);
+  const size_t need = tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, dtype);
+  const Buf in[] = {plain(x, tb_),  plain(tx, tb_), plain(a, mb),   plain(ta, mb),
+                    plain(b, mb),   plain(tb, mb),  plain(gy, tb_), plain(gty, tb_),
+                    unless(!gres, plain(gres, tb_)), unless(!gtres, plain(gtres, tb_))};
+  const Buf out[] = {plain(gx, tb_), plain(gtx, tb_), plain(ga, mb), plain(gta, mb), plain(gb, mb), plain(gtb, mb),
+                     plain(workspace, (long long)need)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
-  if (workspace_bytes < tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, dtype)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::AdalnArgs g{};
   g.x = x;
   g.tx = tx;
@@ -453,10 +563,10 @@ int tvmattn_gate_jvp_fwd(int B, int T, int C, int dtype, const void* x, const vo
   if (rc) return rc;
   // the stream may be updated in place (z = x and tz = tx, each exactly): a thread reads its 16 bytes of x and tx
   // before it writes the same 16 bytes of z and tz, and nobody else touches them
-  const void* const in[] = {z == x ? skip : x, tz == tx ? skip : tx, h, th, c, tc};
-  void* const out[] = {z, tz};
-  if (!x || !tx || !aligned16(x) || !aligned16(tx)) return TVMATTN_INVALID_ARG;
-  rc = check_ptrs(in, out);
+  const long long tb_ = tok_bytes(B, T, C, dtype), mb = mod_bytes(B, C);
+  const Buf in[] = {plain(x, tb_), plain(tx, tb_), plain(h, tb_), plain(th, tb_), plain(c, mb), plain(tc, mb)};
+  const Buf out[] = {plain(z, tb_), plain(tz, tb_)};
+  rc = check_bufs(in, out, 0, 0, 1, 1);  // z may be x itself, tz may be tx itself
   if (rc) return rc;
   tvm::GateArgs g{};
   g.x = x;
@@ -481,11 +591,13 @@ int tvmattn_gate_jvp_bwd(int B, int T, int C, int dtype, const void* h, const vo
                          void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = adaln_check(B, T, C, dtype, eps);
   if (rc) return rc;
-  const void* const in[] = {h, th, c, tc, gz, gtz};
-  void* const out[] = {gh, gth, gc, gtc, workspace};
-  rc = check_ptrs(in, out);
+  const long long tb_ = tok_bytes(B, T, C, dtype), mb = mod_bytes(B, C);
+  const size_t need = tvmattn_gate_jvp_bwd_workspace_bytes(B, T, C, dtype);
+  const Buf in[] = {plain(h, tb_), plain(th, tb_), plain(c, mb), plain(tc, mb), plain(gz, tb_), plain(gtz, tb_)};
+  const Buf out[] = {plain(gh, tb_), plain(gth, tb_), plain(gc, mb), plain(gtc, mb), plain(workspace, (long long)need)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
-  if (workspace_bytes < tvmattn_gate_jvp_bwd_workspace_bytes(B, T, C, dtype)) return TVMATTN_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
   tvm::GateArgs g{};
   g.h = h;
   g.th = th;
@@ -520,9 +632,10 @@ int gelu_check(long long n, int dtype) {
 int tvmattn_gelu_jvp_fwd(long long n, int dtype, const void* u, const void* tu, void* a, void* ta, void* hip_stream) {
   int rc = gelu_check(n, dtype);
   if (rc) return rc;
-  const void* const in[] = {u, tu};
-  void* const out[] = {a, ta};
-  rc = check_ptrs(in, out);
+  const long long nb = n * esz_of(dtype);
+  const Buf in[] = {plain(u, nb), plain(tu, nb)};
+  const Buf out[] = {plain(a, nb), plain(ta, nb)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
   return tvm::launch_gelu_fwd(n, dtype, u, tu, a, ta, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? TVMATTN_OK
@@ -533,9 +646,10 @@ int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, 
                          void* gu, void* gtu, void* hip_stream) {
   int rc = gelu_check(n, dtype);
   if (rc) return rc;
-  const void* const in[] = {u, tu, ga, gta};
-  void* const out[] = {gu, gtu};
-  rc = check_ptrs(in, out);
+  const long long nb = n * esz_of(dtype);
+  const Buf in[] = {plain(u, nb), plain(tu, nb), plain(ga, nb), plain(gta, nb)};
+  const Buf out[] = {plain(gu, nb), plain(gtu, nb)};
+  rc = check_bufs(in, out);
   if (rc) return rc;
   return tvm::launch_gelu_bwd(n, dtype, u, tu, ga, gta, gu, gtu, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? TVMATTN_OK

@@ -1,0 +1,105 @@
+// Microbenchmarks of the two ceilings the attention kernels are priced against, measured on the card itself:
+// the rate of the one matrix-core instruction they use (v_mfma_f32_32x32x16_bf16) and the HBM rate of a plain
+// copy and of a plain read.  Built into a library of its own (libtvmpeaks.so, used by bench.py only): nothing
+// of it is part of the product library.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int kAcc = 4;     // independent accumulators per wave
+constexpr int kUnroll = 4;  // products per accumulator and loop iteration
+
+// Every wave issues iters * kAcc * kUnroll products back to back; operands never change, results are summed into
+// one float per thread so that nothing is optimised away.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out, int iters, float seed) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(seed + (float)(threadIdx.x & 7) * 0.001f);
+    b[e] = (__bf16)(seed * 0.5f);
+  }
+  f32x16 acc[kAcc];
+#pragma unroll
+  for (int n = 0; n < kAcc; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int n = 0; n < kAcc; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int n = 0; n < kAcc; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[n][r];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// 16 bytes per thread and step, consecutive threads on consecutive chunks, four steps in flight.
+__global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+    dst[i] = v0;
+    dst[i + stride] = v1;
+    dst[i + 2 * stride] = v2;
+    dst[i + 3 * stride] = v3;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ out) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned x = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+    x ^= v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+  }
+  for (; i < n16; i += stride) {
+    const u32x4 v = src[i];
+    x ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (x == 0x9E3779B9u) out[0] = x;  // (practically never: the read must not be optimised away)
+}
+
+}  // namespace
+
+extern "C" {
+
+// Launches the matrix-core rate kernel on `blocks` workgroups of four waves.  `out`: device memory for
+// blocks * 256 floats.  Returns the number of floating-point operations the launch performs (0 on a bad argument
+// or a failed launch): blocks * 4 waves * iters * 16 products * 32 * 32 * 16 * 2.
+double tvmpeaks_mfma_bf16(int blocks, int iters, void* out, void* hip_stream) {
+  if (blocks < 1 || iters < 1 || !out) return 0.0;
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(out), iters, 1.0f);
+  if (hipGetLastError() != hipSuccess) return 0.0;
+  return (double)blocks * 4.0 * iters * (kAcc * kUnroll) * (32.0 * 32.0 * 16.0 * 2.0);
+}
+
+// Copies `bytes` (a multiple of 16; both pointers 16-byte aligned, device memory).  Returns 0 on success.
+int tvmpeaks_copy(void* dst, const void* src, size_t bytes, int blocks, void* hip_stream) {
+  if (!dst || !src || bytes % 16 != 0 || blocks < 1 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0) return -1;
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+// Reads `bytes` once.  `out`: device memory for one unsigned.  Returns 0 on success.
+int tvmpeaks_read(const void* src, size_t bytes, void* out, int blocks, void* hip_stream) {
+  if (!src || !out || bytes % 16 != 0 || blocks < 1 || (uintptr_t)src % 16 != 0) return -1;
+  hipLaunchKernelGGL(read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const u32x4*>(src), bytes / 16, static_cast<unsigned*>(out));
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+}  // extern "C"

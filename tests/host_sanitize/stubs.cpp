@@ -1,0 +1,35 @@
+// Stand-ins for the kernel launchers, so that the C-ABI's host code (argument validation, workspace layout,
+// dispatch) can run under AddressSanitizer and UndefinedBehaviorSanitizer on a machine without a GPU: every
+// launcher records that it was reached and returns success without touching the device.
+#include "../../paper_2511_19797_amd/csrc/tvm_common.h"
+
+int g_stub_launches = 0;
+
+namespace tvm {
+#define STUB(sig) hipError_t sig { ++g_stub_launches; return hipSuccess; }
+STUB(launch_fwd_generic(const Shape&, int, const FwdArgs&, hipStream_t))
+STUB(launch_bwd_pre(const Shape&, int, const BwdArgs&, hipStream_t))
+STUB(launch_bwd_col_generic(const Shape&, int, const BwdArgs&, hipStream_t))
+STUB(launch_bwd_row_generic(const Shape&, int, const BwdArgs&, hipStream_t))
+STUB(launch_fwd_mfma(const Shape&, const FwdArgs&, hipStream_t))
+STUB(launch_bwd_col_mfma(const Shape&, const BwdArgs&, hipStream_t))
+STUB(launch_bwd_row_mfma(const Shape&, const BwdArgs&, hipStream_t))
+STUB(launch_bwd_row_pipe_qknorm(const Shape&, const BwdArgs&, hipStream_t))
+STUB(launch_bwd_col_pipe_qknorm(const Shape&, const BwdArgs&, hipStream_t))
+STUB(launch_gain_grad_sum(const float*, int, float*, const float*, int, float*, int, hipStream_t))
+STUB(launch_qknorm_fwd(const NormArgs&, int, hipStream_t))
+STUB(launch_qknorm_bwd(const NormArgs&, int, hipStream_t))
+STUB(launch_gate_fwd(const GateArgs&, int, hipStream_t))
+STUB(launch_gate_bwd(const GateArgs&, int, hipStream_t))
+STUB(launch_gelu_fwd(long long, int, const void*, const void*, void*, void*, hipStream_t))
+STUB(launch_gelu_bwd(long long, int, const void*, const void*, const void*, const void*, void*, void*, hipStream_t))
+STUB(launch_adaln_fwd(const AdalnArgs&, int, hipStream_t))
+STUB(launch_adaln_bwd(const AdalnArgs&, int, hipStream_t))
+#undef STUB
+bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 == 0 && s.D <= 128; }
+bool adaln_supported(int C, int dtype) {
+  const int per = dtype == 1 ? 8 : 4;
+  return C % per == 0 && C / per <= 256;
+}
+int adaln_wgs(int, int T, bool, bool) { return T < 64 ? 1 : 16; }
+}  // namespace tvm

@@ -37,12 +37,13 @@ def elem_err(got, ref):
     return float((np.abs(got - ref) / (np.abs(ref) + rms)).max())
 
 
-def run_gpu(inp, scale=0.0):
+def run_gpu(inp, scale=0.0, flags=0):
     """inp: dict of CPU tensors (workloads.make_inputs).  Returns (fwd tuple, bwd tuple) on the GPU."""
     dev = {n: t.cuda() for n, t in inp.items()}
-    o, to, lse, stats = tvm.tvmattn_jvp_fwd(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale)
+    o, to, lse, stats = tvm.tvmattn_jvp_fwd(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                            flags=flags)
     grads = tvm.tvmattn_jvp_bwd(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], o, to, lse, stats,
-                                dev["gO"], dev["gTO"], scale)
+                                dev["gO"], dev["gTO"], scale, flags=flags)
     torch.cuda.synchronize()
     return (o, to, lse, stats), grads
 

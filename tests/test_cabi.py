@@ -34,7 +34,7 @@ def declared_functions():
 def test_header_symbols_exported(L):
     names = declared_functions()
     assert {"tvmattn_jvp_fwd", "tvmattn_jvp_bwd", "tvmattn_jvp_bwd_workspace_bytes", "tvmattn_strerror",
-            "tvmattn_version", "tvmattn_set_path"} <= set(names)
+            "tvmattn_version", "tvmattn_jvp_bwd_timed"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"{n} declared in include/ but not exported"
 
@@ -45,12 +45,12 @@ def test_version_and_strerror(L):
         assert isinstance(tvm.tvmattn_strerror(code), str) and tvm.tvmattn_strerror(code)
 
 
-def desc(B=1, H=1, N=8, D=8, dtype=1, scale=0.0, sb=0, sh=0, sn=0, M=0, reserved=0, qsb=0, qsh=0, qsn=0):
-    return binding.tvmattn_desc(B, H, N, D, dtype, scale, sb, sh, sn, M, reserved, qsb, qsh, qsn)
+def desc(B=1, H=1, N=8, D=8, dtype=1, scale=0.0, sb=0, sh=0, sn=0, M=0, flags=0, qsb=0, qsh=0, qsn=0):
+    return binding.tvmattn_desc(B, H, N, D, dtype, scale, sb, sh, sn, M, flags, qsb, qsh, qsn)
 
 
 def fwd_status(L, d, ptrs=None):
-    p = ptrs or [0x1000 * (i + 1) for i in range(10)]
+    p = ptrs or [0x1000000 * (i + 1) for i in range(10)]
     return L.tvmattn_jvp_fwd(ctypes.byref(d), *p, None)
 
 
@@ -61,7 +61,7 @@ def fwd_status(L, d, ptrs=None):
     (dict(sn=4, sh=64, sb=64), -1),            # stride_n < D
     (dict(D=8, sn=12, sh=96, sb=96), -1),       # 24-byte row pitch is not a 16-byte multiple
     (dict(B=1 << 15, H=1 << 15, N=4), -2),      # 2^32 rows
-    (dict(M=-1), -1), (dict(reserved=1), -1),
+    (dict(M=-1), -1), (dict(flags=2), -1), (dict(flags=-1), -1),
     (dict(M=16, qsn=4, qsh=64, qsb=64), -1),    # query-side row pitch < D
     (dict(M=16, qsn=12, qsh=192, qsb=192), -1), # query-side pitch not a 16-byte multiple
     (dict(B=1 << 15, H=1 << 15, N=1, M=4), -2), # 2^32 query rows
@@ -73,7 +73,7 @@ def test_bad_descriptors_rejected_without_gpu(L, kw, status):
 
 def test_null_misaligned_and_aliased_pointers(L):
     d = desc()
-    good = [0x1000 * (i + 1) for i in range(10)]
+    good = [0x1000000 * (i + 1) for i in range(10)]
     assert L.tvmattn_jvp_fwd(None, *good, None) == -1
     for i in range(10):
         p = list(good)
@@ -93,12 +93,19 @@ def test_bwd_workspace_contract(L):
     d = desc(B=2, H=3, N=100, D=72)
     need = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
     assert need >= 2 * 2 * 3 * 100 * 4 and need % 256 == 0
-    ptrs = [0x1000 * (i + 1) for i in range(19)]
+    ptrs = [0x1000000 * (i + 1) for i in range(19)]
     assert L.tvmattn_jvp_bwd(ctypes.byref(d), *ptrs, need - 1, None) == -3
     bad = list(ptrs)
     bad[18] = None
     assert L.tvmattn_jvp_bwd(ctypes.byref(d), *bad, need, None) == -1
-    assert L.tvmattn_set_path(5) == -1 and L.tvmattn_set_path(0) == 0
+    # the diagnostic flag is a per-call field of the descriptor; nothing process-wide is left
+    assert not hasattr(L, "tvmattn_set_path") and not hasattr(L, "tvmattn_set_bwd_events")
+    df = desc(B=2, H=3, N=100, D=72, flags=binding.TVMATTN_FLAG_PLAIN_ALU)
+    assert L.tvmattn_jvp_bwd(ctypes.byref(df), *ptrs, need - 1, None) == -3
+    # the timed variant: same checks, the events argument in front of the stream
+    ev = (ctypes.c_void_p * 4)(None, None, None, None)
+    assert L.tvmattn_jvp_bwd_timed(ctypes.byref(d), *ptrs, need - 1, ev, None) == -3
+    assert L.tvmattn_jvp_bwd_timed(ctypes.byref(d), *bad, need, None, None) == -1
 
 
 def test_one_sided_backward_argument_rules(L):
@@ -107,7 +114,7 @@ def test_one_sided_backward_argument_rules(L):
     pointer checks were passed; nothing is launched.)"""
     d = desc(B=2, H=3, N=100, D=72)
     need = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
-    ptrs = [0x1000 * (i + 1) for i in range(19)]
+    ptrs = [0x1000000 * (i + 1) for i in range(19)]
     Q, K, V, TQ, TK, TV, O, TO, LSE, STATS, GO, GTO, DQ, DK, DV, DTQ, DTK, DTV, WS = range(19)
 
     def call(nulls, ws=need - 1):
@@ -121,7 +128,7 @@ def test_one_sided_backward_argument_rules(L):
     assert call({GO}) == -3
     assert call({GO, TQ}) == -1 and call({GO, DTK}) == -1 and call({GO, STATS}) == -1
     # forward: lse and stats are saved together or not at all (both NULL is accepted: GPU tests)
-    one = [0x1000 * (i + 1) for i in range(10)]
+    one = [0x1000000 * (i + 1) for i in range(10)]
     one[9] = None
     assert fwd_status(L, d, one) == -1
 
@@ -143,8 +150,8 @@ def test_qknorm_argument_rules(L):
         [ctypes.c_float] + [ctypes.c_void_p] * 11 + [ctypes.c_size_t, ctypes.c_void_p]
     L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
     d = desc(B=2, H=3, N=100, D=72, M=40)
-    ins = [0x1000 * (i + 1) for i in range(6)]
-    outs = [0x1000 * (i + 7) for i in range(4)]
+    ins = [0x1000000 * (i + 1) for i in range(6)]
+    outs = [0x1000000 * (i + 7) for i in range(4)]
     fwd = lambda i, o, eps=1e-6, dd=d: L.tvmattn_qknorm_jvp_fwd(ctypes.byref(dd), *i, eps, *o, None)
     for bad_eps in (-1.0, float("nan"), float("inf")):
         assert fwd(ins, outs, bad_eps) == -1
@@ -168,8 +175,8 @@ def test_qknorm_argument_rules(L):
     big = L.tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc(B=64, H=16, N=1024, D=72)))
     assert big <= 2 * (1024 * 72 * 4 + 256)
     assert L.tvmattn_qknorm_jvp_bwd_workspace_bytes(ctypes.byref(desc(D=0))) == 0
-    b_in = [0x1000 * (i + 1) for i in range(6)]
-    b_rest = [0x1000 * (i + 7) for i in range(11)]   # 4 upstream gradients, 6 outputs, workspace
+    b_in = [0x1000000 * (i + 1) for i in range(6)]
+    b_rest = [0x1000000 * (i + 7) for i in range(11)]   # 4 upstream gradients, 6 outputs, workspace
     bwd = lambda a, b, ws=need - 1, eps=1e-6: L.tvmattn_qknorm_jvp_bwd(ctypes.byref(d), *a, eps, *b, ws, None)
     assert bwd(b_in, b_rest) == -3
     assert bwd(b_in, b_rest, eps=-2.0) == -1
@@ -192,8 +199,8 @@ def test_fused_backward_argument_rules(L):
     need = L.tvmattn_jvp_bwd_qknorm_workspace_bytes(ctypes.byref(d))
     plain = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
     assert need >= plain + (1 + 3) * 2 * 3 * 72 * 4 and need % 256 == 0   # one gain-gradient row per 128 rows of a head
-    head = [0x1000 * (i + 1) for i in range(6)]
-    rest = [0x1000 * (i + 7) for i in range(21)]   # 12 more inputs, 8 outputs, workspace
+    head = [0x1000000 * (i + 1) for i in range(6)]
+    rest = [0x1000000 * (i + 7) for i in range(21)]   # 12 more inputs, 8 outputs, workspace
     call = lambda a, b, ws=need - 1, eps=1e-6, dd=d: L.tvmattn_jvp_bwd_qknorm(ctypes.byref(dd), *a, eps, *b, ws, None)
     assert call(head, rest) == -3
     assert call(head, rest, eps=float("nan")) == -1
@@ -212,23 +219,22 @@ def test_fused_backward_argument_rules(L):
 
 def test_adaln_argument_rules(L):
     """The AdaLN modulation entry points validate before anything is launched; status -3 (workspace too small)
-    shows that the shape and pointer checks were passed."""
+    shows that the backward's shape and pointer checks were passed.  The forward takes no workspace: no call of it
+    here is a valid one."""
     I, P, F, Z = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
-    L.tvmattn_adaln_jvp_fwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 3 + [Z, P]
+    L.tvmattn_adaln_jvp_fwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 3
     L.tvmattn_adaln_jvp_bwd.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 9 + [Z, P]
-    for fn in (L.tvmattn_adaln_jvp_fwd_workspace_bytes, L.tvmattn_adaln_jvp_bwd_workspace_bytes):
-        fn.restype, fn.argtypes = Z, [I] * 4
+    L.tvmattn_adaln_jvp_bwd_workspace_bytes.restype, L.tvmattn_adaln_jvp_bwd_workspace_bytes.argtypes = Z, [I] * 4
+    assert not hasattr(L, "tvmattn_adaln_jvp_fwd_workspace_bytes")
     B, T, C = 4, 100, 1152
-    nf = L.tvmattn_adaln_jvp_fwd_workspace_bytes(B, T, C, 1)
     nb = L.tvmattn_adaln_jvp_bwd_workspace_bytes(B, T, C, 1)
-    assert nf > 0 and nf % 256 == 0 and nb >= B * 4 * C * 4 and nb % 256 == 0
+    assert nb >= B * 4 * C * 4 and nb % 256 == 0
     for bad in ((0, T, C, 1), (B, 0, C, 1), (B, T, 0, 1), (B, T, C, 5), (B, T, 1156, 1), (B, T, 2056, 1), (B, T, 1028, 0),
                 (70000, 1, 64, 1)):
-        assert L.tvmattn_adaln_jvp_fwd_workspace_bytes(*bad) == 0 and L.tvmattn_adaln_jvp_bwd_workspace_bytes(*bad) == 0
-    ins = [0x1000 * (i + 1) for i in range(6)]
-    fouts = [0x1000 * (i + 7) for i in range(3)]
-    fwd = lambda i, o, ws=nf - 1, eps=1e-6, shape=(B, T, C, 1): L.tvmattn_adaln_jvp_fwd(*shape, *i, eps, *o, ws, None)
-    assert fwd(ins, fouts) == -3
+        assert L.tvmattn_adaln_jvp_bwd_workspace_bytes(*bad) == 0
+    ins = [0x1000000 * (i + 1) for i in range(6)]
+    fouts = [0x1000000 * (i + 7) for i in range(2)]
+    fwd = lambda i, o, eps=1e-6, shape=(B, T, C, 1): L.tvmattn_adaln_jvp_fwd(*shape, *i, eps, *o, None)
     assert fwd(ins, fouts, eps=-1.0) == -1 and fwd(ins, fouts, shape=(B, T, 12, 1)) == -2
     assert fwd(ins, fouts, shape=(B, T, C, 3)) == -2 and fwd(ins, fouts, shape=(B, -1, C, 1)) == -1
     for k in range(6):
@@ -238,7 +244,8 @@ def test_adaln_argument_rules(L):
     p = list(fouts)
     p[1] = p[0]
     assert fwd(ins, p) == -1
-    brest = [0x1000 * (i + 7) for i in range(9)]   # gy, gty, six outputs, workspace
+    assert fwd(ins, [fouts[0], ins[0] + 4096]) == -1     # ty starts inside x
+    brest = [0x1000000 * (i + 7) for i in range(9)]   # gy, gty, six outputs, workspace
     bwd = lambda i, r, ws=nb - 1: L.tvmattn_adaln_jvp_bwd(B, T, C, 1, *i, 1e-6, *r, ws, None)
     assert bwd(ins, brest) == -3
     for k in range(9):
@@ -249,9 +256,9 @@ def test_adaln_argument_rules(L):
     L.tvmattn_adaln_jvp_bwd_residual.argtypes = [I] * 4 + [P] * 6 + [F] + [P] * 11 + [Z, P]
     res = lambda g, gt, r=brest, ws=nb - 1: L.tvmattn_adaln_jvp_bwd_residual(B, T, C, 1, *ins, 1e-6, r[0], r[1], g, gt, *r[2:],
                                                                           ws, None)
-    assert res(None, None) == -3 and res(0x20000, 0x21000) == -3
-    assert res(0x20000, None) == -1 and res(None, 0x21000) == -1 and res(0x20004, 0x21000) == -1
-    assert res(brest[2], 0x21000) == -1     # gx aliases gres
+    assert res(None, None) == -3 and res(0x30000000, 0x31000000) == -3
+    assert res(0x30000000, None) == -1 and res(None, 0x31000000) == -1 and res(0x30000004, 0x31000000) == -1
+    assert res(brest[2], 0x31000000) == -1     # gx aliases gres
 
 
 def test_gate_argument_rules(L):
@@ -265,8 +272,8 @@ def test_gate_argument_rules(L):
     assert nb >= B * 2 * C * 4 and nb % 256 == 0
     for bad in ((0, T, C, 1), (B, 0, C, 1), (B, T, 0, 1), (B, T, C, 5), (B, T, 1156, 1), (B, T, 2056, 1), (B, T, 1028, 0)):
         assert L.tvmattn_gate_jvp_bwd_workspace_bytes(*bad) == 0
-    ins = [0x1000 * (i + 1) for i in range(6)]
-    outs = [0x1000 * (i + 7) for i in range(2)]
+    ins = [0x1000000 * (i + 1) for i in range(6)]
+    outs = [0x1000000 * (i + 7) for i in range(2)]
     fwd = lambda i, o, eps=1e-6, shape=(B, T, C, 1): L.tvmattn_gate_jvp_fwd(*shape, *i, eps, *o, None)
     assert fwd(ins, outs, eps=-1.0) == -1 and fwd(ins, outs, shape=(B, T, 12, 1)) == -2
     assert fwd(ins, outs, shape=(B, T, C, 3)) == -2 and fwd(ins, outs, shape=(B, -1, C, 1)) == -1
@@ -278,8 +285,8 @@ def test_gate_argument_rules(L):
         assert fwd(p, outs) == -1
     assert fwd(ins, [outs[0], outs[0]]) == -1 and fwd(ins, [ins[1], outs[1]]) == -1 and fwd(ins, [outs[0], ins[2]]) == -1
     # (z = x and tz = tx exactly are allowed: the stream updated in place; they pass the checks and would launch)
-    bins = [0x1000 * (i + 1) for i in range(4)]          # h, th, c, tc
-    brest = [0x1000 * (i + 5) for i in range(7)]         # gz, gtz, gh, gth, gc, gtc, workspace
+    bins = [0x1000000 * (i + 1) for i in range(4)]          # h, th, c, tc
+    brest = [0x1000000 * (i + 5) for i in range(7)]         # gz, gtz, gh, gth, gc, gtc, workspace
     bwd = lambda i, r, ws=nb - 1: L.tvmattn_gate_jvp_bwd(B, T, C, 1, *i, 1e-6, *r, ws, None)
     assert bwd(bins, brest) == -3
     for k in range(7):
@@ -296,7 +303,7 @@ def test_gelu_argument_rules(L):
     I, P, LL = ctypes.c_int, ctypes.c_void_p, ctypes.c_longlong
     L.tvmattn_gelu_jvp_fwd.argtypes = [LL, I] + [P] * 5
     L.tvmattn_gelu_jvp_bwd.argtypes = [LL, I] + [P] * 7
-    ptr = [0x1000 * (i + 1) for i in range(6)]
+    ptr = [0x1000000 * (i + 1) for i in range(6)]
     fwd = lambda n, dt, p: L.tvmattn_gelu_jvp_fwd(n, dt, *p, None)
     bwd = lambda n, dt, p: L.tvmattn_gelu_jvp_bwd(n, dt, *p, None)
     assert fwd(0, 1, ptr[:4]) == -1 and fwd(-8, 1, ptr[:4]) == -1 and bwd(0, 1, ptr) == -1
@@ -347,3 +354,41 @@ def test_outputs_are_allocated_with_the_inputs_strides():
     # the largest element offset the kernels can reach lies inside the allocation
     reach = sum((n - 1) * s for n, s in zip(o.shape, o.stride()))
     assert reach < o.untyped_storage().nbytes() // o.element_size()
+
+
+def test_outputs_may_not_overlap_but_interleaved_slices_may(L):
+    """The overlap check is exact for tensors of one layout: dq, dk, dv written as the three slices of one fused
+    [B,N,3,H,D] gradient buffer interleave without sharing an element and are accepted; an output that starts inside
+    an input, or a slice shifted by less than a row, is rejected.  (-3, workspace too small, = checks passed.)"""
+    B, H, N, D = 2, 3, 100, 72
+    sn, sh, sb = 3 * H * D, D, N * 3 * H * D          # element strides of a [B,H,N,D] view of [B,N,3,H,D]
+    d = desc(B=B, H=H, N=N, D=D, sb=sb, sh=sh, sn=sn)
+    need = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(d))
+    big = 0x10000000
+    bufs = [big * (i + 1) for i in range(8)]          # fused buffers: [q|k|v], [tq|tk|tv], [o|..], [to|..], [gO|..], [gTO|..], grads, tangent grads
+    sl = lambda base, i: base + i * H * D * 2          # slice i of a fused buffer (bf16)
+    q, k, v = (sl(bufs[0], i) for i in range(3))
+    tq, tk, tv = (sl(bufs[1], i) for i in range(3))
+    o, to, gO, gTO = bufs[2], bufs[3], bufs[4], bufs[5]
+    lse, stats, ws = big * 9, big * 10, big * 11
+    dq, dk, dv = (sl(bufs[6], i) for i in range(3))
+    dtq, dtk, dtv = (sl(bufs[7], i) for i in range(3))
+    call = lambda *outs: L.tvmattn_jvp_bwd(ctypes.byref(d), q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, *outs, ws,
+                                           need - 1, None)
+    assert call(dq, dk, dv, dtq, dtk, dtv) == -3                       # interleaved slices: fine
+    assert call(dq, dq + 16, dv, dtq, dtk, dtv) == -1                  # dk shifted by 8 elements: shares elements with dq
+    assert call(dq, dk, dv, dtq, dtk, sl(bufs[0], 2) + sn * 2) == -1   # dtv = v one row down: same elements as v
+    assert call(dq, dk, dv, dtq, dtk, sl(bufs[0], 1) + 32) == -1       # starts inside a row of k
+    assert call(dq, dk, dv, dtq, dtk, bufs[2] + 4096) == -1            # starts inside o
+    assert call(dq, dk, dv, dtq, dtk, ws) == -1                        # the workspace is an output too
+    # contiguous tensors: an output that begins inside another tensor's range
+    dc = desc(B=B, H=H, N=N, D=D)
+    nb = B * H * N * D * 2
+    ptrs = [big * (i + 1) for i in range(19)]
+    needc = L.tvmattn_jvp_bwd_workspace_bytes(ctypes.byref(dc))
+    assert L.tvmattn_jvp_bwd(ctypes.byref(dc), *ptrs, needc - 1, None) == -3
+    p = list(ptrs)
+    p[13] = p[12] + nb - 16                                             # dk starts in the last row of dq
+    assert L.tvmattn_jvp_bwd(ctypes.byref(dc), *p, needc - 1, None) == -1
+    p[13] = p[12] + nb                                                  # right behind it: fine
+    assert L.tvmattn_jvp_bwd(ctypes.byref(dc), *p, needc - 1, None) == -3

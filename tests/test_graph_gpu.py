@@ -74,7 +74,7 @@ def test_captured_block_pieces_replay_bit_for_bit():
         k = iter(out) if out is not None else None
         nxt = lambda: next(k) if k is not None else None
         res = []
-        res.append(tvm.tvmattn_adaln_jvp_fwd(a["x"], a["tx"], a["a"], a["ta"], a["b"], a["tb"], eps, out=nxt(), workspace=ws))
+        res.append(tvm.tvmattn_adaln_jvp_fwd(a["x"], a["tx"], a["a"], a["ta"], a["b"], a["tb"], eps, out=nxt()))
         res.append(tvm.tvmattn_adaln_jvp_bwd(a["x"], a["tx"], a["a"], a["ta"], a["b"], a["tb"], eps, a["gy"], a["gty"],
                                              out=nxt(), workspace=ws))
         res.append(tvm.tvmattn_gate_jvp_fwd(g["x"], g["tx"], g["h"], g["th"], g["c"], g["tc"], eps, out=nxt()))

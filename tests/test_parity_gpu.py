@@ -21,11 +21,7 @@ def announce(msg):
 def run_case(w, seed, heads=None, scale=0.0, force_generic=False):
     announce(f"{w} seed={seed} scale={scale} generic={force_generic}")
     inp = wl.make_inputs(w, seed)
-    tvm.tvmattn_set_path(1 if force_generic else 0)
-    try:
-        fwd, grads = pu.run_gpu(inp, scale)
-    finally:
-        tvm.tvmattn_set_path(0)
+    fwd, grads = pu.run_gpu(inp, scale, flags=tvm.TVMATTN_FLAG_PLAIN_ALU if force_generic else 0)
     heads = pu.all_heads(w) if heads is None else heads
     pu.check_heads(w, inp, fwd, grads, heads, scale=(scale or None))
     return inp, fwd, grads
