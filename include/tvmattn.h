@@ -43,7 +43,7 @@
  *   - No output may overlap an input, another output or the workspace: checked element-exactly for tensors of
  *     one layout (slices of one fused buffer that interleave without sharing an element are fine), by address
  *     range otherwise.  Calls on the same stream are ordered; calls on different streams may overlap if their
- *     buffers are disjoint.  The library keeps no state between calls.
+ *     buffers are disjoint.  The library keeps no state between calls (tvmattn_jvp_bwd_static's scratch aside).
  */
 #ifndef TVMATTN_H
 #define TVMATTN_H
@@ -65,7 +65,8 @@ typedef enum {
   TVMATTN_INVALID_ARG = -1,         /* null pointer, bad shape, misaligned pointer or stride */
   TVMATTN_UNSUPPORTED = -2,         /* dtype unknown, D > 256, sizes beyond 2^31 rows */
   TVMATTN_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < tvmattn_jvp_bwd_workspace_bytes() */
-  TVMATTN_LAUNCH_FAILED = -4        /* hipGetLastError() after a launch was not hipSuccess */
+  TVMATTN_LAUNCH_FAILED = -4,       /* hipGetLastError() after a launch was not hipSuccess */
+  TVMATTN_SCRATCH_TOO_SMALL = -5    /* tvmattn_jvp_bwd_static: more than TVMATTN_STATIC_MAX_ROWS query rows */
 } tvmattn_status;
 
 /* Per-call switches, OR-ed into tvmattn_desc.flags.  Unknown bits are TVMATTN_INVALID_ARG. */
@@ -163,6 +164,28 @@ int tvmattn_jvp_bwd_timed(const tvmattn_desc* desc,
                           void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
                           void* workspace, size_t workspace_bytes,
                           void* const* events, void* hip_stream);
+
+/*
+ * tvmattn_jvp_bwd for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same
+ * kernels, same results bit for bit.  The three float32 row vectors that the workspace otherwise holds live in a
+ * static device array of 3 * TVMATTN_STATIC_MAX_ROWS floats (12 MiB on every GPU the library runs on, held until
+ * the process ends).  The call allocates nothing and frees nothing.
+ *   - B*H*M (query rows) above TVMATTN_STATIC_MAX_ROWS: TVMATTN_SCRATCH_TOO_SMALL, nothing enqueued.
+ *   - The device that is current at the call must be the one hip_stream belongs to; each GPU has its own array.
+ *   - Every call on a GPU shares that GPU's array: calls that may overlap in time on one GPU (different streams,
+ *     or different host threads without an order between their streams) race on it.  Calls on one stream are safe.
+ *   - Nothing in the array has to start at zero and nothing of a previous call is read: every entry a call reads
+ *     it has written before.
+ */
+#define TVMATTN_STATIC_MAX_ROWS (1 << 20)
+int tvmattn_jvp_bwd_static(const tvmattn_desc* desc,
+                           const void* q, const void* k, const void* v,
+                           const void* tq, const void* tk, const void* tv,
+                           const void* o, const void* to, const float* lse, const float* stats,
+                           const void* gO, const void* gTO,
+                           void* dq, void* dk, void* dv, void* dtq, void* dtk, void* dtv,
+                           void* hip_stream);
 
 /*
  * RMSNorm with a learnable gain as QK-norm, with tangent: the operation that normalises queries and keys

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtvmattn.so")
 
 TVMATTN_F32, TVMATTN_BF16 = 0, 1
 TVMATTN_FLAG_PLAIN_ALU = 1
+TVMATTN_STATIC_MAX_ROWS = 1 << 20
 
 
 class tvmattn_desc(ctypes.Structure):
@@ -55,6 +56,8 @@ def lib():
         L.tvmattn_jvp_bwd_timed.restype = ctypes.c_int
         L.tvmattn_jvp_bwd_timed.argtypes = ([ctypes.POINTER(tvmattn_desc)] + [_P] * 19 +
                                             [ctypes.c_size_t, ctypes.POINTER(_P), _P])
+        L.tvmattn_jvp_bwd_static.restype = ctypes.c_int
+        L.tvmattn_jvp_bwd_static.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 19
         L.tvmattn_qknorm_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_qknorm_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 5
         L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -209,6 +212,15 @@ def tvmattn_jvp_bwd(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, 
     else:
         arr = (_P * 4)(*[_P(int(e)) if e else _P(None) for e in events])
         _check(lib().tvmattn_jvp_bwd_timed(ctypes.byref(desc), *ptrs, workspace.data_ptr(), wsb, arr, _stream()))
+    return out
+
+
+def tvmattn_jvp_bwd_static(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale=0.0, out=None, flags=0):
+    """tvmattn_jvp_bwd without a workspace: the library's static device scratch holds the row vectors (at most
+    TVMATTN_STATIC_MAX_ROWS query rows B*H*M).  The entry point itself allocates nothing; pass `out` to keep this
+    wrapper from allocating the six gradients."""
+    desc, out, ptrs = _bwd_args(q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, scale, out, flags)
+    _check(lib().tvmattn_jvp_bwd_static(ctypes.byref(desc), *ptrs, _stream()))
     return out
 
 

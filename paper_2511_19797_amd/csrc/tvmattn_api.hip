@@ -3,6 +3,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "tvm_common.h"
 
 namespace {
@@ -166,7 +168,7 @@ inline bool plain_alu(const tvmattn_desc* d) { return (d->flags & TVMATTN_FLAG_P
 
 extern "C" {
 
-int tvmattn_version(void) { return 600; }  // 0.6.0: per-call flags instead of process-wide switches, tvmattn_jvp_bwd_timed; 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 600; }  // 0.6.0: per-call flags instead of process-wide switches, tvmattn_jvp_bwd_timed, tvmattn_jvp_bwd_static, linear layers; 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -175,6 +177,8 @@ const char* tvmattn_strerror(int status) {
     case TVMATTN_UNSUPPORTED: return "unsupported (dtype, head dimension > 256, or too many rows)";
     case TVMATTN_WORKSPACE_TOO_SMALL: return "workspace too small";
     case TVMATTN_LAUNCH_FAILED: return "kernel launch failed";
+    case TVMATTN_SCRATCH_TOO_SMALL:
+      return "too many query rows (B*H*M) for the static scratch of tvmattn_jvp_bwd_static; use tvmattn_jvp_bwd with a workspace";
     default: return "unknown status";
   }
 }
@@ -281,6 +285,41 @@ int tvmattn_jvp_bwd(const tvmattn_desc* desc, const void* q, const void* k, cons
                     void* dtk, void* dtv, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return tvmattn_jvp_bwd_timed(desc, q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv,
                                workspace, workspace_bytes, nullptr, hip_stream);
+}
+
+// ---- the same backward for callers that cannot allocate: the row vectors live in a static device array
+namespace {
+constexpr long long kStaticMaxRows = TVMATTN_STATIC_MAX_ROWS;  // query rows B*H*M served by the static scratch
+// Three row vectors of kStaticMaxRows floats each (12 MiB per GPU the library runs on, held until the process ends).
+static __device__ __align__(256) float scratch[3 * kStaticMaxRows];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];         // device address of `scratch` on each GPU (its name is no device address)
+std::once_flag g_scratch_once[kMaxDevices];
+hipError_t g_scratch_err[kMaxDevices];
+}  // namespace
+
+int tvmattn_jvp_bwd_static(const tvmattn_desc* desc, const void* q, const void* k, const void* v, const void* tq,
+                           const void* tk, const void* tv, const void* o, const void* to, const float* lse,
+                           const float* stats, const void* gO, const void* gTO, void* dq, void* dk, void* dv, void* dtq,
+                           void* dtk, void* dtv, void* hip_stream) {
+  tvm::Shape s;
+  const int rc = resolve(desc, &s);
+  if (rc) return rc;
+  if ((long long)s.B * s.H * s.M > kStaticMaxRows) return TVMATTN_SCRATCH_TOO_SMALL;  // before any HIP call
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TVMATTN_LAUNCH_FAILED;
+  // once per device, with that device current: each GPU holds its own copy of the array at its own address
+  std::call_once(g_scratch_once[dev], [dev] {
+    void* p = nullptr;
+    g_scratch_err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    g_scratch_ptr[dev] = g_scratch_err[dev] == hipSuccess ? static_cast<float*>(p) : nullptr;
+  });
+  float* const base = g_scratch_ptr[dev];
+  if (!base) return TVMATTN_LAUNCH_FAILED;
+  // nothing has to start at zero: the query-side kernel writes every row's three entries before the key-side
+  // kernel, behind it on the same stream, reads them
+  return bwd_impl(desc, s, q, k, v, tq, tk, tv, o, to, lse, stats, gO, gTO, dq, dk, dv, dtq, dtk, dtv, base,
+                  base + kStaticMaxRows, base + 2 * kStaticMaxRows, true, nullptr, hip_stream);
 }
 
 // ---- RMSNorm with gain as QK-norm, with tangent

@@ -79,6 +79,15 @@ int main() {
   d.flags = 4;
   EXPECT(bwd(P(11 * G), P(12 * G), P(19 * G), need, P(14 * G)) == TVMATTN_INVALID_ARG);
   d.flags = 0;
+  // ---- static-scratch backward: size limit first; without a GPU the device query fails cleanly
+  tvmattn_desc big = mk(16, 16, 4097, 64);
+  EXPECT(tvmattn_jvp_bwd_static(&big, P(G), P(2 * G), P(3 * G), P(4 * G), P(5 * G), P(6 * G), P(7 * G), P(8 * G),
+                                (float*)P(9 * G), (float*)P(10 * G), P(11 * G), P(12 * G), P(13 * G), P(14 * G), P(15 * G),
+                                P(16 * G), P(17 * G), P(18 * G), nullptr) == TVMATTN_SCRATCH_TOO_SMALL);
+  const int rs = tvmattn_jvp_bwd_static(&d, P(G), P(2 * G), P(3 * G), P(4 * G), P(5 * G), P(6 * G), P(7 * G), P(8 * G),
+                                        (float*)P(9 * G), (float*)P(10 * G), P(11 * G), P(12 * G), P(13 * G), P(14 * G),
+                                        P(15 * G), P(16 * G), P(17 * G), P(18 * G), nullptr);
+  EXPECT(rs == TVMATTN_OK || rs == TVMATTN_LAUNCH_FAILED);
   // ---- the overlap check on random strided layouts: two tensors of one layout share an element exactly when a
   // brute-force walk over their elements says so
   std::mt19937 rng(2511);

@@ -34,7 +34,7 @@ def declared_functions():
 def test_header_symbols_exported(L):
     names = declared_functions()
     assert {"tvmattn_jvp_fwd", "tvmattn_jvp_bwd", "tvmattn_jvp_bwd_workspace_bytes", "tvmattn_strerror",
-            "tvmattn_version", "tvmattn_jvp_bwd_timed"} <= set(names)
+            "tvmattn_version", "tvmattn_jvp_bwd_static", "tvmattn_jvp_bwd_timed"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"{n} declared in include/ but not exported"
 
@@ -392,3 +392,18 @@ def test_outputs_may_not_overlap_but_interleaved_slices_may(L):
     assert L.tvmattn_jvp_bwd(ctypes.byref(dc), *p, needc - 1, None) == -1
     p[13] = p[12] + nb                                                  # right behind it: fine
     assert L.tvmattn_jvp_bwd(ctypes.byref(dc), *p, needc - 1, None) == -3
+
+
+def test_static_scratch_backward_rejects_what_does_not_fit(L):
+    """tvmattn_jvp_bwd_static keeps its row vectors in a static device array of TVMATTN_STATIC_MAX_ROWS entries each:
+    more query rows than that is a clear error, returned before anything touches the GPU."""
+    L.tvmattn_jvp_bwd_static.argtypes = [ctypes.POINTER(binding.tvmattn_desc)] + [ctypes.c_void_p] * 19
+    ptrs = [0x100000000 * (i + 1) for i in range(18)]
+    too_big = desc(B=16, H=16, N=4097, D=64)          # 1,048,832 rows
+    assert 16 * 16 * 4097 > binding.TVMATTN_STATIC_MAX_ROWS
+    assert L.tvmattn_jvp_bwd_static(ctypes.byref(too_big), *ptrs, None) == -5
+    assert "static scratch" in tvm.tvmattn_strerror(-5)
+    assert L.tvmattn_jvp_bwd_static(ctypes.byref(desc(D=0)), *ptrs, None) == -1
+    assert L.tvmattn_jvp_bwd_static(None, *ptrs, None) == -1
+    header = open(os.path.join(ROOT, "include", "tvmattn.h")).read()
+    assert re.search(r"#define\s+TVMATTN_STATIC_MAX_ROWS\s+\(1 << 20\)", header)
