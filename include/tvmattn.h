@@ -369,6 +369,41 @@ int tvmattn_gelu_jvp_fwd(long long n, int dtype, const void* u, const void* tu, 
 int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
                          void* gu, void* gtu, void* hip_stream);
 
+/*
+ * A linear layer applied to a token and to its tangent: the query/key/value and output projections around the
+ * attention and the two layers of the MLP in the paper's block (App. "Full Description of Normalization of
+ * Modulation", the two layer equations; the JVP of Sec. 4 runs through them along the network's inputs, so the
+ * weights carry no tangent):
+ *
+ *     y = x W^T + b,   ty = tx W^T
+ *
+ *   in : x, tx   [R,K] dtype, contiguous rows (R tokens of K features)
+ *        w       [F,K] dtype, contiguous (row f holds the weights of output feature f)
+ *        bias    [F] dtype, or NULL
+ *   out: y, ty   [R,F] dtype, contiguous
+ * Served for bfloat16 with K and F multiples of 32 (products on the matrix cores, float32 accumulation, outputs
+ * rounded once); anything else returns TVMATTN_UNSUPPORTED.  One launch over the stacked rows [x; tx], no workspace.
+ */
+int tvmattn_linear_jvp_fwd(int R, int K, int F, int dtype,
+                           const void* x, const void* tx, const void* w, const void* bias,
+                           void* y, void* ty, void* hip_stream);
+
+/*
+ * Backward of the above: the gradient of <gy,y> + <gty,ty>:
+ *     gx = gy W,   gtx = gty W,   gw = gy^T x + gty^T tx,   gbias = sum over the R tokens of gy.
+ *   in : x, tx, w as given to the forward; gy, gty [R,F] dtype
+ *   out: gx, gtx [R,K] dtype; gw [F,K] dtype; gbias [F] dtype or NULL (not wanted)
+ *   workspace: device memory, 16-byte aligned, at least tvmattn_linear_jvp_bwd_workspace_bytes(...) bytes (0 =
+ *              unsupported shape): float32 partial sums of gw over ranges of tokens, and of gbias.
+ * Launches: gx and gtx in one; gw as partial sums over token ranges and their sum in a fixed order (no atomics,
+ * bitwise reproducible); gbias likewise.
+ */
+size_t tvmattn_linear_jvp_bwd_workspace_bytes(int R, int K, int F, int dtype);
+int tvmattn_linear_jvp_bwd(int R, int K, int F, int dtype,
+                           const void* x, const void* tx, const void* w, const void* gy, const void* gty,
+                           void* gx, void* gtx, void* gw, void* gbias,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

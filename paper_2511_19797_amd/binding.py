@@ -89,6 +89,12 @@ def lib():
         L.tvmattn_gate_jvp_fwd.argtypes = [_I] * 4 + [_P] * 6 + [ctypes.c_float] + [_P] * 3
         L.tvmattn_gate_jvp_bwd.restype = ctypes.c_int
         L.tvmattn_gate_jvp_bwd.argtypes = [_I] * 4 + [_P] * 4 + [ctypes.c_float] + [_P] * 7 + [ctypes.c_size_t, _P]
+        L.tvmattn_linear_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.tvmattn_linear_jvp_bwd_workspace_bytes.argtypes = [_I] * 4
+        L.tvmattn_linear_jvp_fwd.restype = ctypes.c_int
+        L.tvmattn_linear_jvp_fwd.argtypes = [_I] * 4 + [_P] * 7
+        L.tvmattn_linear_jvp_bwd.restype = ctypes.c_int
+        L.tvmattn_linear_jvp_bwd.argtypes = [_I] * 4 + [_P] * 10 + [ctypes.c_size_t, _P]
         _lib = L
     return _lib
 
@@ -418,3 +424,59 @@ def tvmattn_gelu_jvp_bwd(u, tu, ga, gta, out=None):
     _check(lib().tvmattn_gelu_jvp_bwd(n, dt, u.data_ptr(), tu.data_ptr(), ga.data_ptr(), gta.data_ptr(), gu.data_ptr(),
                                       gtu.data_ptr(), _stream()))
     return gu, gtu
+
+
+def _linear_args(x, tx, w, bias):
+    if x.dim() < 2 or not x.is_cuda or not x.is_contiguous():
+        raise ValueError("expected contiguous [..., K] device tensors")
+    if tx.shape != x.shape or tx.dtype != x.dtype or not tx.is_contiguous() or tx.device != x.device:
+        raise ValueError("x and its tangent must agree in shape, dtype and layout")
+    if w.dim() != 2 or w.shape[1] != x.shape[-1] or w.dtype != x.dtype or not w.is_contiguous() or w.device != x.device:
+        raise ValueError("the weight must be a contiguous [F, K] tensor of x's dtype on its device")
+    if bias is not None and (bias.shape != (w.shape[0],) or bias.dtype != x.dtype or not bias.is_contiguous()
+                             or bias.device != x.device):
+        raise ValueError("the bias must be a contiguous [F] tensor of x's dtype on its device")
+    dt = TVMATTN_F32 if x.dtype == torch.float32 else TVMATTN_BF16 if x.dtype == torch.bfloat16 else None
+    if dt is None:
+        raise ValueError(f"unsupported dtype {x.dtype}")
+    K, F = x.shape[-1], w.shape[0]
+    return x.numel() // K, K, F, dt
+
+
+def tvmattn_linear_jvp_fwd(x, tx, w, bias=None, out=None):
+    """Returns (y, ty): x W^T + b and tx W^T, for x, tx [..., K] and w [F, K]."""
+    R, K, F, dt = _linear_args(x, tx, w, bias)
+    shape = x.shape[:-1] + (F,)
+    y, ty = out if out is not None else (torch.empty(shape, dtype=x.dtype, device=x.device),
+                                         torch.empty(shape, dtype=x.dtype, device=x.device))
+    for t in (y, ty):
+        if t.shape != shape or t.dtype != x.dtype or not t.is_contiguous() or t.device != x.device:
+            raise ValueError("outputs must be contiguous [..., F] tensors of x's dtype on its device")
+    _check(lib().tvmattn_linear_jvp_fwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), w.data_ptr(), _ptr(bias), y.data_ptr(),
+                                        ty.data_ptr(), _stream()))
+    return y, ty
+
+
+def tvmattn_linear_jvp_bwd_workspace_bytes(x, w):
+    K, F = x.shape[-1], w.shape[0]
+    dt = TVMATTN_F32 if x.dtype == torch.float32 else TVMATTN_BF16
+    return int(lib().tvmattn_linear_jvp_bwd_workspace_bytes(x.numel() // K, K, F, dt))
+
+
+def tvmattn_linear_jvp_bwd(x, tx, w, gy, gty, bias_grad=True, out=None, workspace=None):
+    """Returns (gx, gtx, gw, gbias), the gradient of <gy, y> + <gty, ty> (gbias None unless bias_grad)."""
+    R, K, F, dt = _linear_args(x, tx, w, None)
+    for t in (gy, gty):
+        if t.shape != x.shape[:-1] + (F,) or t.dtype != x.dtype or not t.is_contiguous() or t.device != x.device:
+            raise ValueError("upstream gradients must be contiguous [..., F] tensors of x's dtype on its device")
+    if out is None:
+        out = (torch.empty_like(x), torch.empty_like(x), torch.empty_like(w),
+               torch.empty(F, dtype=x.dtype, device=x.device) if bias_grad else None)
+    gx, gtx, gw, gb = out
+    need = int(lib().tvmattn_linear_jvp_bwd_workspace_bytes(R, K, F, dt))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().tvmattn_linear_jvp_bwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), w.data_ptr(), gy.data_ptr(),
+                                        gty.data_ptr(), gx.data_ptr(), gtx.data_ptr(), gw.data_ptr(), _ptr(gb),
+                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return out

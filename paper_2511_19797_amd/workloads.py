@@ -158,6 +158,19 @@ def make_gelu_inputs(shape, dtype: str, seed: int):
             for name in ("u", "tu", "ga", "gta")}
 
 
+def make_linear_inputs(R: int, K: int, F: int, dtype: str, seed: int):
+    """Inputs of a linear layer with tangent: tokens x [R,K] with tangent tx, upstream gradients gy, gty [R,F] (standard
+    normal), a weight w [F,K] of standard deviation 1/sqrt(K) (a freshly initialised layer: outputs of unit size) and
+    a bias b [F] of standard deviation 0.1, all in the storage dtype."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    out = {}
+    for name, shape, scale in (("x", (R, K), 1.0), ("tx", (R, K), 1.0), ("w", (F, K), K ** -0.5), ("b", (F,), 0.1),
+                               ("gy", (R, F), 1.0), ("gty", (R, F), 1.0)):
+        out[name] = torch.from_numpy(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale)).to(td).contiguous()
+    return out
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()

@@ -407,3 +407,47 @@ def test_static_scratch_backward_rejects_what_does_not_fit(L):
     assert L.tvmattn_jvp_bwd_static(None, *ptrs, None) == -1
     header = open(os.path.join(ROOT, "include", "tvmattn.h")).read()
     assert re.search(r"#define\s+TVMATTN_STATIC_MAX_ROWS\s+\(1 << 20\)", header)
+
+
+def test_linear_argument_rules(L):
+    """The linear-layer entry points validate before anything is launched; -3 (workspace too small) shows that the
+    backward's checks were passed.  No forward call here is a valid one."""
+    I, P, Z = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    L.tvmattn_linear_jvp_fwd.argtypes = [I] * 4 + [P] * 7
+    L.tvmattn_linear_jvp_bwd.argtypes = [I] * 4 + [P] * 10 + [Z, P]
+    L.tvmattn_linear_jvp_bwd_workspace_bytes.restype, L.tvmattn_linear_jvp_bwd_workspace_bytes.argtypes = Z, [I] * 4
+    R, K, F = 1000, 1152, 3456
+    need = L.tvmattn_linear_jvp_bwd_workspace_bytes(R, K, F, 1)
+    assert need >= F * K * 4 + F * 4 and need % 256 == 0
+    for bad in ((0, K, F, 1), (R, 0, F, 1), (R, K, -1, 1)):
+        assert L.tvmattn_linear_jvp_bwd_workspace_bytes(*bad) == 0
+    for unsup in ((R, K, F, 0), (R, K, F, 9), (R, 40, F, 1), (R, K, 100, 1), (R, 16, F, 1)):
+        assert L.tvmattn_linear_jvp_bwd_workspace_bytes(*unsup) == 0
+    G = 0x100000000
+    ins = [G * (i + 1) for i in range(4)]       # x, tx, w, bias
+    outs = [G * (i + 5) for i in range(2)]
+    fwd = lambda i, o, shape=(R, K, F, 1): L.tvmattn_linear_jvp_fwd(*shape, *i, *o, None)
+    assert fwd(ins, outs, (0, K, F, 1)) == -1 and fwd(ins, outs, (R, K, F, 0)) == -2 and fwd(ins, outs, (R, 40, F, 1)) == -2
+    for k in range(3):
+        p = list(ins)
+        p[k] = None
+        assert fwd(p, outs) == -1
+    assert fwd(ins, [outs[0], outs[0] + 1024]) == -1 and fwd(ins, [ins[2] + 64, outs[1]]) == -1
+    b_in = [G * (i + 1) for i in range(5)]      # x, tx, w, gy, gty
+    b_out = [G * (i + 6) for i in range(5)]     # gx, gtx, gw, gbias, workspace
+    bwd = lambda i, o, ws=need - 1: L.tvmattn_linear_jvp_bwd(R, K, F, 1, *i, *o, ws, None)
+    assert bwd(b_in, b_out) == -3
+    nob = list(b_out)
+    nob[3] = None                               # no bias gradient wanted: fine
+    assert bwd(b_in, nob) == -3
+    for k in (0, 1, 2, 4):
+        p = list(b_out)
+        p[k] = None
+        assert bwd(b_in, p) == -1
+    for k in range(5):
+        p = list(b_in)
+        p[k] = None
+        assert bwd(p, b_out) == -1
+    p = list(b_out)
+    p[2] = b_in[2] + 4096                       # gw inside w
+    assert bwd(b_in, p) == -1

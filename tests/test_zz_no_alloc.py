@@ -37,7 +37,7 @@ def _both_ways(w, seed, flags=0):
                                               ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     assert rc == 0, tvm.tvmattn_strerror(rc)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before   # (the garbage collector may free earlier cases' tensors meanwhile)
     for name, a, b in zip(pu.BWD_NAMES, out, ref):
         assert torch.equal(a, b), f"{name} differs from tvmattn_jvp_bwd's"
     return inp, fwd, out
