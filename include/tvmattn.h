@@ -377,22 +377,24 @@ int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, 
  *
  *     y = x W^T + b,   ty = tx W^T
  *
- *   in : x, tx   [R,K] dtype, contiguous rows (R tokens of K features)
+ *   in : x, tx   [R,K] dtype: R tokens of K features, rows ldx elements apart (0 = K: dense)
  *        w       [F,K] dtype, contiguous (row f holds the weights of output feature f)
  *        bias    [F] dtype, or NULL
- *   out: y, ty   [R,F] dtype, contiguous
+ *   out: y, ty   [R,F] dtype, rows ldy elements apart (0 = F: dense)
+ * Row pitches let a layer read from or write into a slice of a wider buffer (the q, k, v slices of a fused projection,
+ * an attention output laid out like its queries) without a copy; they must be multiples of 8 elements.
  * Served for bfloat16 with K and F multiples of 32 (products on the matrix cores, float32 accumulation, outputs
  * rounded once); anything else returns TVMATTN_UNSUPPORTED.  One launch over the stacked rows [x; tx], no workspace.
  */
 int tvmattn_linear_jvp_fwd(int R, int K, int F, int dtype,
-                           const void* x, const void* tx, const void* w, const void* bias,
-                           void* y, void* ty, void* hip_stream);
+                           const void* x, const void* tx, long long ldx, const void* w, const void* bias,
+                           void* y, void* ty, long long ldy, void* hip_stream);
 
 /*
  * Backward of the above: the gradient of <gy,y> + <gty,ty>:
  *     gx = gy W,   gtx = gty W,   gw = gy^T x + gty^T tx,   gbias = sum over the R tokens of gy.
- *   in : x, tx, w as given to the forward; gy, gty [R,F] dtype
- *   out: gx, gtx [R,K] dtype; gw [F,K] dtype; gbias [F] dtype or NULL (not wanted)
+ *   in : x, tx (pitch ldx), w as given to the forward; gy, gty [R,F] dtype (pitch ldy)
+ *   out: gx, gtx [R,K] dtype (pitch ldx); gw [F,K] dtype, contiguous; gbias [F] dtype or NULL (not wanted)
  *   workspace: device memory, 16-byte aligned, at least tvmattn_linear_jvp_bwd_workspace_bytes(...) bytes (0 =
  *              unsupported shape): float32 partial sums of gw over ranges of tokens, and of gbias.
  * Launches: gx and gtx in one; gw as partial sums over token ranges and their sum in a fixed order (no atomics,
@@ -400,7 +402,8 @@ int tvmattn_linear_jvp_fwd(int R, int K, int F, int dtype,
  */
 size_t tvmattn_linear_jvp_bwd_workspace_bytes(int R, int K, int F, int dtype);
 int tvmattn_linear_jvp_bwd(int R, int K, int F, int dtype,
-                           const void* x, const void* tx, const void* w, const void* gy, const void* gty,
+                           const void* x, const void* tx, long long ldx, const void* w,
+                           const void* gy, const void* gty, long long ldy,
                            void* gx, void* gtx, void* gw, void* gbias,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 

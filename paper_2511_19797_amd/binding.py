@@ -92,9 +92,10 @@ def lib():
         L.tvmattn_linear_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.tvmattn_linear_jvp_bwd_workspace_bytes.argtypes = [_I] * 4
         L.tvmattn_linear_jvp_fwd.restype = ctypes.c_int
-        L.tvmattn_linear_jvp_fwd.argtypes = [_I] * 4 + [_P] * 7
+        _LL = ctypes.c_longlong
+        L.tvmattn_linear_jvp_fwd.argtypes = [_I] * 4 + [_P, _P, _LL, _P, _P, _P, _P, _LL, _P]
         L.tvmattn_linear_jvp_bwd.restype = ctypes.c_int
-        L.tvmattn_linear_jvp_bwd.argtypes = [_I] * 4 + [_P] * 10 + [ctypes.c_size_t, _P]
+        L.tvmattn_linear_jvp_bwd.argtypes = [_I] * 4 + [_P, _P, _LL, _P, _P, _P, _LL] + [_P] * 5 + [ctypes.c_size_t, _P]
         _lib = L
     return _lib
 
@@ -426,57 +427,75 @@ def tvmattn_gelu_jvp_bwd(u, tu, ga, gta, out=None):
     return gu, gtu
 
 
+def _rows(t, cols, what):
+    """(R, pitch) of a tensor used as R rows of `cols` elements: a contiguous [..., cols] tensor, or a 2-D [R, cols]
+    view with unit inner stride and any row pitch (a slice of a wider buffer)."""
+    if not t.is_cuda or t.shape[-1] != cols or t.stride(-1) != 1:
+        raise ValueError(f"{what}: expected device tensors [..., {cols}] with unit inner stride")
+    if t.is_contiguous():
+        return t.numel() // cols, cols
+    if t.dim() == 2:
+        return t.shape[0], t.stride(0)
+    raise ValueError(f"{what}: a non-contiguous tensor must be given as a 2-D [R, {cols}] view")
+
+
 def _linear_args(x, tx, w, bias):
-    if x.dim() < 2 or not x.is_cuda or not x.is_contiguous():
-        raise ValueError("expected contiguous [..., K] device tensors")
-    if tx.shape != x.shape or tx.dtype != x.dtype or not tx.is_contiguous() or tx.device != x.device:
-        raise ValueError("x and its tangent must agree in shape, dtype and layout")
-    if w.dim() != 2 or w.shape[1] != x.shape[-1] or w.dtype != x.dtype or not w.is_contiguous() or w.device != x.device:
+    if w.dim() != 2 or w.dtype != x.dtype or not w.is_contiguous() or w.device != x.device:
         raise ValueError("the weight must be a contiguous [F, K] tensor of x's dtype on its device")
-    if bias is not None and (bias.shape != (w.shape[0],) or bias.dtype != x.dtype or not bias.is_contiguous()
+    F, K = w.shape
+    R, ldx = _rows(x, K, "x")
+    if tx.shape != x.shape or tx.dtype != x.dtype or tx.stride() != x.stride() or tx.device != x.device:
+        raise ValueError("x and its tangent must agree in shape, dtype and layout")
+    if bias is not None and (bias.shape != (F,) or bias.dtype != x.dtype or not bias.is_contiguous()
                              or bias.device != x.device):
         raise ValueError("the bias must be a contiguous [F] tensor of x's dtype on its device")
     dt = TVMATTN_F32 if x.dtype == torch.float32 else TVMATTN_BF16 if x.dtype == torch.bfloat16 else None
     if dt is None:
         raise ValueError(f"unsupported dtype {x.dtype}")
-    K, F = x.shape[-1], w.shape[0]
-    return x.numel() // K, K, F, dt
+    return R, K, F, dt, ldx
 
 
 def tvmattn_linear_jvp_fwd(x, tx, w, bias=None, out=None):
-    """Returns (y, ty): x W^T + b and tx W^T, for x, tx [..., K] and w [F, K]."""
-    R, K, F, dt = _linear_args(x, tx, w, bias)
-    shape = x.shape[:-1] + (F,)
-    y, ty = out if out is not None else (torch.empty(shape, dtype=x.dtype, device=x.device),
-                                         torch.empty(shape, dtype=x.dtype, device=x.device))
-    for t in (y, ty):
-        if t.shape != shape or t.dtype != x.dtype or not t.is_contiguous() or t.device != x.device:
-            raise ValueError("outputs must be contiguous [..., F] tensors of x's dtype on its device")
-    _check(lib().tvmattn_linear_jvp_fwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), w.data_ptr(), _ptr(bias), y.data_ptr(),
-                                        ty.data_ptr(), _stream()))
+    """Returns (y, ty): x W^T + b and tx W^T, for x, tx [..., K] (or 2-D [R, K] views with a row pitch) and w [F, K].
+    `out`: preallocated (y, ty), contiguous [..., F] or 2-D [R, F] views with a row pitch."""
+    R, K, F, dt, ldx = _linear_args(x, tx, w, bias)
+    if out is None:
+        shape = x.shape[:-1] + (F,)
+        out = (torch.empty(shape, dtype=x.dtype, device=x.device), torch.empty(shape, dtype=x.dtype, device=x.device))
+    y, ty = out
+    Ry, ldy = _rows(y, F, "y")
+    if Ry != R or ty.shape != y.shape or ty.stride() != y.stride() or y.dtype != x.dtype or ty.dtype != x.dtype:
+        raise ValueError("outputs must be two [R, F] tensors of x's dtype and one layout")
+    _check(lib().tvmattn_linear_jvp_fwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), ldx, w.data_ptr(), _ptr(bias),
+                                        y.data_ptr(), ty.data_ptr(), ldy, _stream()))
     return y, ty
 
 
 def tvmattn_linear_jvp_bwd_workspace_bytes(x, w):
-    K, F = x.shape[-1], w.shape[0]
+    F, K = w.shape
     dt = TVMATTN_F32 if x.dtype == torch.float32 else TVMATTN_BF16
-    return int(lib().tvmattn_linear_jvp_bwd_workspace_bytes(x.numel() // K, K, F, dt))
+    return int(lib().tvmattn_linear_jvp_bwd_workspace_bytes(_rows(x, K, "x")[0], K, F, dt))
 
 
 def tvmattn_linear_jvp_bwd(x, tx, w, gy, gty, bias_grad=True, out=None, workspace=None):
-    """Returns (gx, gtx, gw, gbias), the gradient of <gy, y> + <gty, ty> (gbias None unless bias_grad)."""
-    R, K, F, dt = _linear_args(x, tx, w, None)
-    for t in (gy, gty):
-        if t.shape != x.shape[:-1] + (F,) or t.dtype != x.dtype or not t.is_contiguous() or t.device != x.device:
-            raise ValueError("upstream gradients must be contiguous [..., F] tensors of x's dtype on its device")
+    """Returns (gx, gtx, gw, gbias), the gradient of <gy, y> + <gty, ty> (gbias None unless bias_grad).  `out`:
+    preallocated (gx, gtx, gw, gbias or None); gx, gtx must be laid out like x."""
+    R, K, F, dt, ldx = _linear_args(x, tx, w, None)
+    Ry, ldy = _rows(gy, F, "gy")
+    if Ry != R or gty.shape != gy.shape or gty.stride() != gy.stride() or gy.dtype != x.dtype or gty.dtype != x.dtype:
+        raise ValueError("upstream gradients must be two [R, F] tensors of x's dtype and one layout")
     if out is None:
-        out = (torch.empty_like(x), torch.empty_like(x), torch.empty_like(w),
-               torch.empty(F, dtype=x.dtype, device=x.device) if bias_grad else None)
+        out = (_like(x), _like(x), torch.empty_like(w), torch.empty(F, dtype=x.dtype, device=x.device) if bias_grad else None)
     gx, gtx, gw, gb = out
+    for t in (gx, gtx):
+        if t.shape != x.shape or t.stride() != x.stride() or t.dtype != x.dtype:
+            raise ValueError("gx and gtx must be laid out like x")
+    if gw.shape != w.shape or not gw.is_contiguous() or gw.dtype != w.dtype:
+        raise ValueError("gw must be contiguous like w")
     need = int(lib().tvmattn_linear_jvp_bwd_workspace_bytes(R, K, F, dt))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    _check(lib().tvmattn_linear_jvp_bwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), w.data_ptr(), gy.data_ptr(),
-                                        gty.data_ptr(), gx.data_ptr(), gtx.data_ptr(), gw.data_ptr(), _ptr(gb),
+    _check(lib().tvmattn_linear_jvp_bwd(R, K, F, dt, x.data_ptr(), tx.data_ptr(), ldx, w.data_ptr(), gy.data_ptr(),
+                                        gty.data_ptr(), ldy, gx.data_ptr(), gtx.data_ptr(), gw.data_ptr(), _ptr(gb),
                                         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
     return out

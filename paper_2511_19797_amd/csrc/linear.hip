@@ -245,13 +245,13 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
 }
 
 // Column sums of gy [R][F] over `chunks` row ranges: part[chunk][f] (float32).  A thread per column.
-__global__ __launch_bounds__(256) void colsum_kernel(const bf16* __restrict__ gy, int R, int F, int chunks,
+__global__ __launch_bounds__(256) void colsum_kernel(const bf16* __restrict__ gy, int R, int F, long long ld, int chunks,
                                                      float* __restrict__ part) {
   const int f = blockIdx.x * 256 + threadIdx.x, ch = blockIdx.y;
   if (f >= F) return;
   const int r0 = (int)((long long)ch * R / chunks), r1 = (int)((long long)(ch + 1) * R / chunks);
   float s = 0.f;
-  for (int r = r0; r < r1; ++r) s += (float)gy[(long long)r * F + f];
+  for (int r = r0; r < r1; ++r) s += (float)gy[(long long)r * ld + f];
   part[(long long)ch * F + f] = s;
 }
 
@@ -270,9 +270,10 @@ int bias_chunks(int R) {
 
 }  // namespace
 
-bool linear_supported(int R, int K, int F, int dtype) {
-  return dtype == 1 && R >= 1 && K >= 32 && F >= 32 && K % 32 == 0 && F % 32 == 0 && (long long)R * K < (1ll << 40) &&
-         (long long)R * F < (1ll << 40) && (long long)K * 2 < (1ll << 31) && (long long)F * 2 < (1ll << 31);
+// Row pitches (elements) up to 2^20: a tile's per-lane byte offsets (row within the tile x pitch) stay inside 32 bits.
+bool linear_supported(int R, int K, int F, long long ldx, long long ldy, int dtype) {
+  return dtype == 1 && R >= 1 && K >= 32 && F >= 32 && K % 32 == 0 && F % 32 == 0 && ldx >= K && ldy >= F &&
+         ldx % 8 == 0 && ldy % 8 == 0 && ldx <= (1ll << 20) && ldy <= (1ll << 20) && K <= (1 << 20) && F <= (1 << 20);
 }
 
 size_t linear_bwd_workspace_bytes(int R, int K, int F) {
@@ -281,13 +282,13 @@ size_t linear_bwd_workspace_bytes(int R, int K, int F) {
   return ((dw + 255) & ~(size_t)255) + ((db + 255) & ~(size_t)255);
 }
 
-hipError_t launch_linear_fwd(int R, int K, int F, const void* x, const void* tx, const void* w, const void* bias, void* y,
-                             void* ty, hipStream_t st) {
+hipError_t launch_linear_fwd(int R, int K, int F, long long ldx, long long ldy, const void* x, const void* tx,
+                             const void* w, const void* bias, void* y, void* ty, hipStream_t st) {
   GemmArgs g{};
   g.P[0] = (const bf16*)x;
   g.P[1] = (const bf16*)tx;
   g.Q[0] = g.Q[1] = (const bf16*)w;
-  g.ldP = K;
+  g.ldP = ldx;
   g.ldQ = K;
   g.I = R;
   g.J = F;
@@ -295,21 +296,22 @@ hipError_t launch_linear_fwd(int R, int K, int F, const void* x, const void* tx,
   g.csets = 1;
   g.out[0] = (bf16*)y;
   g.out[1] = (bf16*)ty;
-  g.ldo = F;
+  g.ldo = ldy;
   g.bias = (const bf16*)bias;
   const int grid = 2 * ((R + kTI - 1) / kTI) * ((F + kTJ - 1) / kTJ);
   hipLaunchKernelGGL((gemm_kernel<false, false, false>), dim3(grid), dim3(kNT), 0, st, g);
   return hipGetLastError();
 }
 
-hipError_t launch_linear_bwd(int R, int K, int F, const void* x, const void* tx, const void* w, const void* gy,
-                             const void* gty, void* gx, void* gtx, void* gw, void* gbias, void* workspace, hipStream_t st) {
+hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, const void* x, const void* tx,
+                             const void* w, const void* gy, const void* gty, void* gx, void* gtx, void* gw, void* gbias,
+                             void* workspace, hipStream_t st) {
   {  // gx = gy W, gtx = gty W: rows = tokens, contraction over f, W read transposed
     GemmArgs g{};
     g.P[0] = (const bf16*)gy;
     g.P[1] = (const bf16*)gty;
     g.Q[0] = g.Q[1] = (const bf16*)w;
-    g.ldP = F;
+    g.ldP = ldy;
     g.ldQ = K;
     g.I = R;
     g.J = K;
@@ -317,7 +319,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, const void* x, const void* tx,
     g.csets = 1;
     g.out[0] = (bf16*)gx;
     g.out[1] = (bf16*)gtx;
-    g.ldo = K;
+    g.ldo = ldx;
     const int grid = 2 * ((R + kTI - 1) / kTI) * ((K + kTJ - 1) / kTJ);
     hipLaunchKernelGGL((gemm_kernel<false, true, false>), dim3(grid), dim3(kNT), 0, st, g);
     const hipError_t e = hipGetLastError();
@@ -331,8 +333,8 @@ hipError_t launch_linear_bwd(int R, int K, int F, const void* x, const void* tx,
     g.P[1] = (const bf16*)gty;
     g.Q[0] = (const bf16*)x;
     g.Q[1] = (const bf16*)tx;
-    g.ldP = F;
-    g.ldQ = K;
+    g.ldP = ldy;
+    g.ldQ = ldx;
     g.I = F;
     g.J = K;
     g.C = R;
@@ -353,7 +355,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, const void* x, const void* tx,
     const size_t dw = ((size_t)splits * F * K * sizeof(float) + 255) & ~(size_t)255;
     float* bp = reinterpret_cast<float*>(static_cast<char*>(workspace) + dw);
     const int chunks = bias_chunks(R);
-    hipLaunchKernelGGL(colsum_kernel, dim3((F + 255) / 256, chunks), dim3(256), 0, st, (const bf16*)gy, R, F, chunks, bp);
+    hipLaunchKernelGGL(colsum_kernel, dim3((F + 255) / 256, chunks), dim3(256), 0, st, (const bf16*)gy, R, F, ldy, chunks, bp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((F / 8 + 255) / 256)), dim3(256), 0, st, bp, chunks, (long long)F,

@@ -130,12 +130,14 @@ hipError_t launch_gelu_fwd(long long n, int dtype, const void* u, const void* tu
 hipError_t launch_gelu_bwd(long long n, int dtype, const void* u, const void* tu, const void* ga, const void* gta,
                            void* gu, void* gtu, hipStream_t st);
 // Linear layer on a token and its tangent (linear.hip): bf16 only, K and F multiples of 32.
-bool linear_supported(int R, int K, int F, int dtype);
+// ldx, ldy: row pitch in elements of the [R,K] tensors (x, tx, gx, gtx) and of the [R,F] tensors (y, ty, gy, gty).
+bool linear_supported(int R, int K, int F, long long ldx, long long ldy, int dtype);
 size_t linear_bwd_workspace_bytes(int R, int K, int F);
-hipError_t launch_linear_fwd(int R, int K, int F, const void* x, const void* tx, const void* w, const void* bias, void* y,
-                             void* ty, hipStream_t st);
-hipError_t launch_linear_bwd(int R, int K, int F, const void* x, const void* tx, const void* w, const void* gy,
-                             const void* gty, void* gx, void* gtx, void* gw, void* gbias, void* workspace, hipStream_t st);
+hipError_t launch_linear_fwd(int R, int K, int F, long long ldx, long long ldy, const void* x, const void* tx,
+                             const void* w, const void* bias, void* y, void* ty, hipStream_t st);
+hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, const void* x, const void* tx,
+                             const void* w, const void* gy, const void* gty, void* gx, void* gtx, void* gw, void* gbias,
+                             void* workspace, hipStream_t st);
 int adaln_wgs(int B, int T, bool backward, bool gate);  // workgroups per batch element of a token kernel
 hipError_t launch_adaln_fwd(const AdalnArgs& a, int dtype, hipStream_t st);
 hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st);

@@ -697,45 +697,54 @@ int tvmattn_gelu_jvp_bwd(long long n, int dtype, const void* u, const void* tu, 
 
 // ---- linear layer on a token and its tangent
 namespace {
-int linear_check(int R, int K, int F, int dtype) {
-  if (R < 1 || K < 1 || F < 1) return TVMATTN_INVALID_ARG;
+int linear_check(int R, int K, int F, int dtype, long long& ldx, long long& ldy) {
+  if (R < 1 || K < 1 || F < 1 || ldx < 0 || ldy < 0) return TVMATTN_INVALID_ARG;
   if (dtype != TVMATTN_F32 && dtype != TVMATTN_BF16) return TVMATTN_UNSUPPORTED;
-  return tvm::linear_supported(R, K, F, dtype) ? TVMATTN_OK : TVMATTN_UNSUPPORTED;
+  if (ldx == 0) ldx = K;
+  if (ldy == 0) ldy = F;
+  if (ldx < K || ldy < F) return TVMATTN_INVALID_ARG;
+  return tvm::linear_supported(R, K, F, ldx, ldy, dtype) ? TVMATTN_OK : TVMATTN_UNSUPPORTED;
+}
+// R rows of `cols` elements at a pitch of `ld` elements
+Buf rows_buf(const void* p, int R, int cols, long long ld, long long esz) {
+  return Buf{p, 1, {R, 0, 0}, {ld * esz, 0, 0}, cols * esz};
 }
 }  // namespace
 
 size_t tvmattn_linear_jvp_bwd_workspace_bytes(int R, int K, int F, int dtype) {
-  return linear_check(R, K, F, dtype) ? 0 : tvm::linear_bwd_workspace_bytes(R, K, F);
+  long long ldx = 0, ldy = 0;
+  return linear_check(R, K, F, dtype, ldx, ldy) ? 0 : tvm::linear_bwd_workspace_bytes(R, K, F);
 }
 
-int tvmattn_linear_jvp_fwd(int R, int K, int F, int dtype, const void* x, const void* tx, const void* w, const void* bias,
-                           void* y, void* ty, void* hip_stream) {
-  int rc = linear_check(R, K, F, dtype);
+int tvmattn_linear_jvp_fwd(int R, int K, int F, int dtype, const void* x, const void* tx, long long ldx, const void* w,
+                           const void* bias, void* y, void* ty, long long ldy, void* hip_stream) {
+  int rc = linear_check(R, K, F, dtype, ldx, ldy);
   if (rc) return rc;
-  const long long e = esz_of(dtype), xb = (long long)R * K * e, yb = (long long)R * F * e, wb = (long long)F * K * e;
-  const Buf in[] = {plain(x, xb), plain(tx, xb), plain(w, wb), unless(!bias, plain(bias, F * e))};
-  const Buf out[] = {plain(y, yb), plain(ty, yb)};
+  const long long e = esz_of(dtype), wb = (long long)F * K * e;
+  const Buf in[] = {rows_buf(x, R, K, ldx, e), rows_buf(tx, R, K, ldx, e), plain(w, wb), unless(!bias, plain(bias, F * e))};
+  const Buf out[] = {rows_buf(y, R, F, ldy, e), rows_buf(ty, R, F, ldy, e)};
   rc = check_bufs(in, out);
   if (rc) return rc;
-  return tvm::launch_linear_fwd(R, K, F, x, tx, w, bias, y, ty, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+  return tvm::launch_linear_fwd(R, K, F, ldx, ldy, x, tx, w, bias, y, ty, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? TVMATTN_OK
              : TVMATTN_LAUNCH_FAILED;
 }
 
-int tvmattn_linear_jvp_bwd(int R, int K, int F, int dtype, const void* x, const void* tx, const void* w, const void* gy,
-                           const void* gty, void* gx, void* gtx, void* gw, void* gbias, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
-  int rc = linear_check(R, K, F, dtype);
+int tvmattn_linear_jvp_bwd(int R, int K, int F, int dtype, const void* x, const void* tx, long long ldx, const void* w,
+                           const void* gy, const void* gty, long long ldy, void* gx, void* gtx, void* gw, void* gbias,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = linear_check(R, K, F, dtype, ldx, ldy);
   if (rc) return rc;
-  const long long e = esz_of(dtype), xb = (long long)R * K * e, yb = (long long)R * F * e, wb = (long long)F * K * e;
+  const long long e = esz_of(dtype), wb = (long long)F * K * e;
   const size_t need = tvm::linear_bwd_workspace_bytes(R, K, F);
-  const Buf in[] = {plain(x, xb), plain(tx, xb), plain(w, wb), plain(gy, yb), plain(gty, yb)};
-  const Buf out[] = {plain(gx, xb), plain(gtx, xb), plain(gw, wb), unless(!gbias, plain(gbias, F * e)),
+  const Buf in[] = {rows_buf(x, R, K, ldx, e), rows_buf(tx, R, K, ldx, e), plain(w, wb), rows_buf(gy, R, F, ldy, e),
+                    rows_buf(gty, R, F, ldy, e)};
+  const Buf out[] = {rows_buf(gx, R, K, ldx, e), rows_buf(gtx, R, K, ldx, e), plain(gw, wb), unless(!gbias, plain(gbias, F * e)),
                      plain(workspace, (long long)need)};
   rc = check_bufs(in, out);
   if (rc) return rc;
   if (workspace_bytes < need) return TVMATTN_WORKSPACE_TOO_SMALL;
-  return tvm::launch_linear_bwd(R, K, F, x, tx, w, gy, gty, gx, gtx, gw, gbias, workspace,
+  return tvm::launch_linear_bwd(R, K, F, ldx, ldy, x, tx, w, gy, gty, gx, gtx, gw, gbias, workspace,
                                 static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? TVMATTN_OK
              : TVMATTN_LAUNCH_FAILED;

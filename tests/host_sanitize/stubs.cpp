@@ -25,9 +25,10 @@ STUB(launch_gelu_fwd(long long, int, const void*, const void*, void*, void*, hip
 STUB(launch_gelu_bwd(long long, int, const void*, const void*, const void*, const void*, void*, void*, hipStream_t))
 STUB(launch_adaln_fwd(const AdalnArgs&, int, hipStream_t))
 STUB(launch_adaln_bwd(const AdalnArgs&, int, hipStream_t))
-STUB(launch_linear_fwd(int, int, int, const void*, const void*, const void*, const void*, void*, void*, hipStream_t))
-STUB(launch_linear_bwd(int, int, int, const void*, const void*, const void*, const void*, const void*, void*, void*, void*,
-                       void*, void*, hipStream_t))
+STUB(launch_linear_fwd(int, int, int, long long, long long, const void*, const void*, const void*, const void*, void*, void*,
+                       hipStream_t))
+STUB(launch_linear_bwd(int, int, int, long long, long long, const void*, const void*, const void*, const void*, const void*,
+                       void*, void*, void*, void*, void*, hipStream_t))
 #undef STUB
 bool mfma_supported(const Shape& s, int dtype) { return dtype == 1 && s.D % 8 == 0 && s.D <= 128; }
 bool adaln_supported(int C, int dtype) {
@@ -35,6 +36,8 @@ bool adaln_supported(int C, int dtype) {
   return C % per == 0 && C / per <= 256;
 }
 int adaln_wgs(int, int T, bool, bool) { return T < 64 ? 1 : 16; }
-bool linear_supported(int R, int K, int F, int dtype) { return dtype == 1 && R >= 1 && K % 32 == 0 && F % 32 == 0; }
+bool linear_supported(int R, int K, int F, long long ldx, long long ldy, int dtype) {
+  return dtype == 1 && R >= 1 && K % 32 == 0 && F % 32 == 0 && ldx % 8 == 0 && ldy % 8 == 0;
+}
 size_t linear_bwd_workspace_bytes(int, int K, int F) { return (size_t)4 * F * K * 4 + (size_t)64 * F * 4; }
 }  // namespace tvm

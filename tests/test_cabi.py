@@ -412,9 +412,9 @@ def test_static_scratch_backward_rejects_what_does_not_fit(L):
 def test_linear_argument_rules(L):
     """The linear-layer entry points validate before anything is launched; -3 (workspace too small) shows that the
     backward's checks were passed.  No forward call here is a valid one."""
-    I, P, Z = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
-    L.tvmattn_linear_jvp_fwd.argtypes = [I] * 4 + [P] * 7
-    L.tvmattn_linear_jvp_bwd.argtypes = [I] * 4 + [P] * 10 + [Z, P]
+    I, P, Z, LL = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_longlong
+    L.tvmattn_linear_jvp_fwd.argtypes = [I] * 4 + [P, P, LL, P, P, P, P, LL, P]
+    L.tvmattn_linear_jvp_bwd.argtypes = [I] * 4 + [P, P, LL, P, P, P, LL] + [P] * 5 + [Z, P]
     L.tvmattn_linear_jvp_bwd_workspace_bytes.restype, L.tvmattn_linear_jvp_bwd_workspace_bytes.argtypes = Z, [I] * 4
     R, K, F = 1000, 1152, 3456
     need = L.tvmattn_linear_jvp_bwd_workspace_bytes(R, K, F, 1)
@@ -424,30 +424,22 @@ def test_linear_argument_rules(L):
     for unsup in ((R, K, F, 0), (R, K, F, 9), (R, 40, F, 1), (R, K, 100, 1), (R, 16, F, 1)):
         assert L.tvmattn_linear_jvp_bwd_workspace_bytes(*unsup) == 0
     G = 0x100000000
-    ins = [G * (i + 1) for i in range(4)]       # x, tx, w, bias
-    outs = [G * (i + 5) for i in range(2)]
-    fwd = lambda i, o, shape=(R, K, F, 1): L.tvmattn_linear_jvp_fwd(*shape, *i, *o, None)
-    assert fwd(ins, outs, (0, K, F, 1)) == -1 and fwd(ins, outs, (R, K, F, 0)) == -2 and fwd(ins, outs, (R, 40, F, 1)) == -2
-    for k in range(3):
-        p = list(ins)
-        p[k] = None
-        assert fwd(p, outs) == -1
-    assert fwd(ins, [outs[0], outs[0] + 1024]) == -1 and fwd(ins, [ins[2] + 64, outs[1]]) == -1
-    b_in = [G * (i + 1) for i in range(5)]      # x, tx, w, gy, gty
-    b_out = [G * (i + 6) for i in range(5)]     # gx, gtx, gw, gbias, workspace
-    bwd = lambda i, o, ws=need - 1: L.tvmattn_linear_jvp_bwd(R, K, F, 1, *i, *o, ws, None)
-    assert bwd(b_in, b_out) == -3
-    nob = list(b_out)
-    nob[3] = None                               # no bias gradient wanted: fine
-    assert bwd(b_in, nob) == -3
-    for k in (0, 1, 2, 4):
-        p = list(b_out)
-        p[k] = None
-        assert bwd(b_in, p) == -1
-    for k in range(5):
-        p = list(b_in)
-        p[k] = None
-        assert bwd(p, b_out) == -1
-    p = list(b_out)
-    p[2] = b_in[2] + 4096                       # gw inside w
-    assert bwd(b_in, p) == -1
+    x, tx, w, b, y, ty = (G * (i + 1) for i in range(6))
+    fwd = lambda shape=(R, K, F, 1), x=x, tx=tx, w=w, b=b, y=y, ty=ty, ldx=0, ldy=0: \
+        L.tvmattn_linear_jvp_fwd(*shape, x, tx, ldx, w, b, y, ty, ldy, None)
+    assert fwd((0, K, F, 1)) == -1 and fwd((R, K, F, 0)) == -2 and fwd((R, 40, F, 1)) == -2
+    assert fwd(x=None) == -1 and fwd(tx=None) == -1 and fwd(w=None) == -1 and fwd(y=None) == -1
+    assert fwd(ty=y + 1024) == -1 and fwd(y=w + 64) == -1
+    assert fwd(ldx=K - 8) == -1 and fwd(ldy=-1) == -1 and fwd(ldx=K + 4) == -2    # below K; negative; not 16-byte rows
+    # x and tx as two slices of one [R, 3K] buffer (pitch 3K): they interleave without sharing an element
+    assert fwd(tx=x + 2 * K, ldx=3 * K, y=x + 8) == -1                            # ... but y inside x's rows does
+    gy, gty, gx, gtx, gw, gb, ws = (G * (i + 7) for i in range(7))
+    bwd = lambda x=x, tx=tx, w=w, gy=gy, gty=gty, gx=gx, gtx=gtx, gw=gw, gb=gb, ws=ws, wsb=need - 1, ldx=0, ldy=0: \
+        L.tvmattn_linear_jvp_bwd(R, K, F, 1, x, tx, ldx, w, gy, gty, ldy, gx, gtx, gw, gb, ws, wsb, None)
+    assert bwd() == -3 and bwd(gb=None) == -3                                      # no bias gradient wanted: fine
+    assert bwd(tx=x + 2 * K, gtx=gx + 2 * K, ldx=3 * K) == -3                      # slices of fused buffers
+    assert bwd(tx=x + 2 * K, gtx=gx + 2 * K + 16, ldx=3 * K - 8) == -3               # (addresses are bytes: K elements in)
+    assert bwd(gtx=gx + 2 * K, ldx=K) == -1                                        # dense rows: that overlaps gx
+    for nul in ("x", "tx", "w", "gy", "gty", "gx", "gtx", "gw", "ws"):
+        assert bwd(**{nul: None}) == -1
+    assert bwd(gw=w + 4096) == -1                                                  # gw inside w

@@ -77,6 +77,35 @@ def test_linear_batched_shapes_and_the_tangent_is_the_forward_of_the_tangent():
     assert y.shape == (2, 77, 160) and torch.equal(ty, y2)
 
 
+def test_linear_on_slices_of_wider_buffers():
+    """x and tx as slices of one [R, 3K] buffer (how an attention output laid out like its fused-projection queries
+    reaches the output projection), y and ty written into slices of a [R, 2F + 64] buffer, and the same layouts for the
+    backward's gradients: against the oracle, and bit for bit against the call on dense copies."""
+    R, K, F = 300, 96, 160
+    inp = wl.make_linear_inputs(R, K, F, "bf16", 21)
+    d = {n: t.cuda() for n, t in inp.items()}
+    xb = torch.zeros(R, 3 * K, dtype=torch.bfloat16, device="cuda")
+    xb[:, :K], xb[:, 2 * K:] = d["x"], d["tx"]
+    xs, txs = xb[:, :K], xb[:, 2 * K:]
+    yb = torch.full((R, 2 * F + 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ys, tys = yb[:, :F], yb[:, F + 64:]
+    tvm.tvmattn_linear_jvp_fwd(xs, txs, d["w"], d["b"], out=(ys, tys))
+    y, ty = tvm.tvmattn_linear_jvp_fwd(d["x"], d["tx"], d["w"], d["b"])
+    gb_ = torch.zeros(R, 2 * F + 64, dtype=torch.bfloat16, device="cuda")
+    gb_[:, :F], gb_[:, F + 64:] = d["gy"], d["gty"]
+    gxb = torch.full((R, 3 * K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    out = (gxb[:, :K], gxb[:, 2 * K:], torch.empty_like(d["w"]), torch.empty(F, dtype=torch.bfloat16, device="cuda"))
+    tvm.tvmattn_linear_jvp_bwd(xs, txs, d["w"], gb_[:, :F], gb_[:, F + 64:], out=out)
+    ref = tvm.tvmattn_linear_jvp_bwd(d["x"], d["tx"], d["w"], d["gy"], d["gty"])
+    torch.cuda.synchronize()
+    assert torch.equal(ys, y) and torch.equal(tys, ty)
+    for a, b in zip(out, ref):
+        assert torch.equal(a, b)
+    assert bool(torch.isnan(yb[:, F:F + 64].float()).all()) and bool(torch.isnan(gxb[:, K:2 * K].float()).all())  # gaps untouched
+    f = {n: wl.to_f64(t) for n, t in inp.items()}
+    assert pu.rel_err(ys.float().cpu().numpy(), orc.linear_jvp_fwd(f["x"], f["tx"], f["w"], f["b"])[0]) <= TOL
+
+
 @pytest.mark.parametrize("K,F", [(1152, 1152), (1152, 4608), (4608, 1152), (1152, 3456)])
 def test_linear_at_the_block_sizes(K, F):
     """The layers of a DiT-XL/2 block at 512 px (16 x 1024 tokens; hidden 1152, MLP width 4608, fused QKV 3456), at the
