@@ -171,6 +171,25 @@ def make_linear_inputs(R: int, K: int, F: int, dtype: str, seed: int):
     return out
 
 
+def make_block_inputs(B: int, T: int, H: int, d: int, hidden: int, seed: int):
+    """Inputs of one normalised DiT block with tangent: the stream x [B,T,C] (C = H d) with tangent tx and upstream
+    gradients gz, gtz (standard normal, bf16); the six modulation vectors a1 ... c2 [B,C] and their tangents (standard
+    normal, float32); weights of standard deviation 1/sqrt(fan-in) and biases of 0.1 (bf16); QK-norm gains 1 + 0.2 x
+    standard normal (float32).  Returns (x, tx, mods, tmods, params, gz, gtz)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    C = H * d
+    bf = lambda *s, scale=1.0: torch.from_numpy(rng.standard_normal(s, dtype=np.float32) * np.float32(scale)).to(torch.bfloat16)
+    f32 = lambda *s, scale=1.0, shift=0.0: torch.from_numpy((shift + scale * rng.standard_normal(s)).astype(np.float32))
+    x, tx = bf(B, T, C), bf(B, T, C)
+    mods = {k: f32(B, C) for k in ("a1", "b1", "c1", "a2", "b2", "c2")}
+    tmods = {k: f32(B, C) for k in ("a1", "b1", "c1", "a2", "b2", "c2")}
+    params = {"wqkv": bf(3 * C, C, scale=C ** -0.5), "bqkv": bf(3 * C, scale=0.1), "gq": f32(d, scale=0.2, shift=1.0),
+              "gk": f32(d, scale=0.2, shift=1.0), "wo": bf(C, C, scale=C ** -0.5), "bo": bf(C, scale=0.1),
+              "w1": bf(hidden, C, scale=C ** -0.5), "b1": bf(hidden, scale=0.1), "w2": bf(C, hidden, scale=hidden ** -0.5),
+              "b2": bf(C, scale=0.1)}
+    return x, tx, mods, tmods, params, bf(B, T, C), bf(B, T, C)
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor to float64 (what the oracle consumes)."""
     return t.detach().cpu().to(torch.float64).numpy()
