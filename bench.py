@@ -15,7 +15,8 @@ cpu_baseline = the float64 oracle timed on this machine's host cores on a bounded sa
 the same workload.  Side sections, all outside the timed region and each timed after half of
 --ramp-ms of the same call: one_sided (one upstream gradient alone; the forward that saves nothing),
 graph_replay (the step captured in a HIP graph), qknorm, adaln, gate, gelu (the block's memory-bound
-pieces, priced against 8 TB/s), peaks (the card's own matrix-core and HBM rates from plain microbenchmarks).
+pieces, priced against 8 TB/s), linear (the block's four linear layers with tangents, against the matrix-core peak),
+block (one whole block, forward and backward, as a chain of library calls), peaks (the card's own matrix-core and HBM rates from plain microbenchmarks).
 roofline.traffic comes from the committed counter summary under profiles/ and is null once the kernel's sources
 differ from the ones that were profiled.
 """
@@ -455,6 +456,59 @@ def gelu(w, steps, seed=2024):
     return out
 
 
+def linear(w, steps, seed=2024):
+    """The four linear layers of the block (fused q, k, v projection, output projection, the MLP's two; App. "Full
+    Description of Normalization of Modulation") on the workload's B x M tokens at hidden size H*d, each with tangent:
+    forward (one product over the stacked rows [x; tx]: 4 R K F flops) and backward (grad x over the stacked rows and
+    grad W over both row sets: 8 R K F flops), priced against the bf16 matrix-core peak."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    R, C = w.B * w.Mq, w.H * w.d
+    out = {"tokens": R}
+    for name, K, F in (("qkv", C, 3 * C), ("proj", C, C), ("mlp_up", C, 4 * C), ("mlp_down", 4 * C, C)):
+        d = {n: t.cuda() for n, t in wl.make_linear_inputs(R, K, F, w.dtype, seed).items()}
+        fo = (torch.empty(R, F, dtype=d["x"].dtype, device="cuda"), torch.empty(R, F, dtype=d["x"].dtype, device="cuda"))
+        bo = (torch.empty_like(d["x"]), torch.empty_like(d["x"]), torch.empty_like(d["w"]), torch.empty_like(d["b"]))
+        ws = torch.empty(tvm.tvmattn_linear_jvp_bwd_workspace_bytes(d["x"], d["w"]), dtype=torch.uint8, device="cuda")
+        fms = _timed_ms(lambda: tvm.tvmattn_linear_jvp_fwd(d["x"], d["tx"], d["w"], d["b"], out=fo), steps)
+        bms = _timed_ms(lambda: tvm.tvmattn_linear_jvp_bwd(d["x"], d["tx"], d["w"], d["gy"], d["gty"], out=bo, workspace=ws), steps)
+        fl = 4.0 * R * K * F
+        out[name] = {"K": K, "F": F, "fwd_ms": fms, "fwd_tflops": fl / (fms * 1e-3) / 1e12, "bwd_ms": bms,
+                     "bwd_tflops": 2.0 * fl / (bms * 1e-3) / 1e12, "bound": "mfma", "peak": PEAK_BF16_TFLOPS,
+                     "fwd_frac": fl / (fms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "bwd_frac": 2.0 * fl / (bms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del d, fo, bo, ws
+    return out
+
+
+def block_step(w, steps, seed=2024):
+    """One whole normalised DiT block with tangent (modulation, fused projection, QK-norm, attention, projection, gate,
+    modulation, MLP, gate), forward and backward, as the chain of library calls in paper_2511_19797_amd/block.py at the
+    workload's batch, tokens and heads.  Wall clock per forward + backward (the chain allocates its intermediates through
+    torch's caching allocator: what a training step pays)."""
+    import torch
+
+    from paper_2511_19797_amd import block, workloads as wl
+
+    x, tx, mods, tmods, params, gz, gtz = wl.make_block_inputs(w.B, w.Mq, w.H, w.d, 4 * w.H * w.d, seed)
+    dev = lambda t: t.cuda()
+    x, tx, gz, gtz = dev(x), dev(tx), dev(gz), dev(gtz)
+    dm, dtm, dp = ({k: dev(v) for k, v in m.items()} for m in (mods, tmods, params))
+
+    def step():
+        z, tz, saved = block.block_jvp_fwd(x, tx, dm, dtm, dp, w.H, 1e-6, 1e-6)
+        block.block_jvp_bwd(x, tx, dm, dtm, dp, w.H, 1e-6, 1e-6, saved, gz, gtz)
+    ms = _timed_ms(step, max(3, steps // 2))
+    R, C = w.B * w.Mq, w.H * w.d
+    gemm = 12.0 * R * C * (3 * C + C + 4 * C + 4 * C)          # the four layers, forward 4 R K F + backward 8 R K F
+    attn = 42.0 * w.B * w.H * w.Mq * w.N * w.d
+    return {"ms_fwd_bwd": ms, "algorithmic_tflops": (gemm + attn) / (ms * 1e-3) / 1e12,
+            "flops": {"linear_layers": gemm, "attention": attn}}
+
+
 def peaks(steps):
     """The card's own ceilings, measured beside the kernels: the rate of the matrix-core instruction the attention
     kernels use (two waves per SIMD issuing it back to back) and the HBM rate of a plain copy and a plain read of
@@ -492,6 +546,20 @@ def peaks(steps):
     ms = _timed_ms(lambda: L.tvmpeaks_read(src.data_ptr(), n, flag.data_ptr(), wg, stream), steps)
     res["read_gbs"] = n / (ms * 1e-3) / 1e9
     assert torch.equal(src[:1 << 20], dst[:1 << 20]) and torch.equal(src[-(1 << 20):], dst[-(1 << 20):])
+    del src, dst
+    # float32 atomic adds into L2-resident per-head tiles, in the pattern and volume a backward that formed dQ, dtQ in
+    # its key-side pass would need at C4 (256 heads x 8 workgroups x 4 waves, each adding 2 x 1024 x 72 floats per pass
+    # over the queries: 4.8 GB per backward; reduced across the four waves of a workgroup first it would be 1.2 GB)
+    L.tvmpeaks_atomic_add.restype = ctypes.c_double
+    L.tvmpeaks_atomic_add.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p]
+    heads, per_head, rows, cols = 256, 8, 1024, 72
+    acc = torch.zeros(heads * 2 * rows * cols, dtype=torch.float32, device="cuda")
+    nbytes = []
+    ms4 = _timed_ms(lambda: nbytes.append(L.tvmpeaks_atomic_add(acc.data_ptr(), heads, per_head, rows, cols, 1, 4, stream)), steps)
+    assert nbytes[-1] > 0
+    res["atomic_add_f32_gbs"] = nbytes[-1] / (ms4 * 1e-3) / 1e9
+    ms1 = _timed_ms(lambda: nbytes.append(L.tvmpeaks_atomic_add(acc.data_ptr(), heads, per_head, rows, cols, 1, 1, stream)), steps)
+    res["atomic_add_ms_for_a_C4_backward"] = {"every_wave_adds": ms4, "one_wave_per_workgroup_adds": ms1}
     return res
 
 
@@ -589,6 +657,9 @@ def main():
         out["adaln"] = adaln(w, args.steps)
         out["gate"] = gate(w, args.steps)
         out["gelu"] = gelu(w, args.steps)
+        if (w.H * w.d) % 32 == 0:
+            out["linear"] = linear(w, args.steps)
+            out["block"] = block_step(w, args.steps)
     if args.sweep:
         out["sweep"] = []
         for sw in wl.sweep_configs():

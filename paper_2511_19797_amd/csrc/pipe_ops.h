@@ -10,12 +10,11 @@
 //     next two issue slots (the PAD form of the product puts two idle slots in front).
 #pragma once
 #include "mfma_tiles.h"
+#include "pipe_prof.h"  // PROF_* cycle stamps: empty unless this is a diagnostic build (-DTVM_PROFILE)
 
 namespace tvm {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-
-#include "pipe_prof.h"  // PROF_* cycle stamps: empty unless this is a diagnostic build (-DTVM_PROFILE)
 
 __device__ __forceinline__ bf16x8 lds_read16(unsigned addr, int imm) {
   typedef const bf16x8 __attribute__((address_space(3))) * lp;

@@ -71,6 +71,26 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src
   if (x == 0x9E3779B9u) out[0] = x;  // (practically never: the read must not be optimised away)
 }
 
+// What a backward kernel that forms dQ, dtQ in its key-side pass would have to do: every wave adds float32 partial
+// tiles into the query-side gradients of its head, which other workgroups of the head add to as well.  Each
+// workgroup (four waves) owns 1/wgs_per_head of a head's keys and walks the head's `rows` queries in blocks of
+// 32; per block every wave adds 2 x 32 x cols floats, 256 contiguous bytes per wave instruction (the friendliest
+// pattern a kernel could stage through LDS), to the head's [2][rows][cols] region, which the XCD's L2 holds.
+__global__ __launch_bounds__(256) void atomic_tile_kernel(float* __restrict__ base, int wgs_per_head, int rows, int cols,
+                                                          int reps, int waves) {
+  if ((int)(threadIdx.x >> 6) >= waves) return;  // (waves < 4: as if the workgroup had summed its waves' tiles first)
+  const int head = blockIdx.x / wgs_per_head;
+  const int lane = threadIdx.x & 63;
+  float* region = base + (size_t)head * 2 * rows * cols;
+  const float v = 1.0f + (float)(threadIdx.x & 3);
+  for (int rep = 0; rep < reps; ++rep)
+    for (int qb = 0; qb < rows / 32; ++qb) {
+      float* tile = region + (size_t)qb * 32 * cols;
+      for (int t = 0; t < 2; ++t)
+        for (int e = lane; e < 32 * cols; e += 64) atomicAdd(tile + (size_t)t * rows * cols + e, v);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -100,6 +120,20 @@ int tvmpeaks_read(const void* src, size_t bytes, void* out, int blocks, void* hi
   hipLaunchKernelGGL(read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                      static_cast<const u32x4*>(src), bytes / 16, static_cast<unsigned*>(out));
   return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+// Launches the atomic-add pattern above on heads * wgs_per_head workgroups.  `base`: device memory for
+// heads * 2 * rows * cols floats (rows a multiple of 32).  Returns the number of bytes added atomically (0 on a bad
+// argument or a failed launch): heads * wgs_per_head * waves * reps * rows * cols * 2 tensors * 4 (waves: 1..4 of a
+// workgroup's waves take part).
+double tvmpeaks_atomic_add(void* base, int heads, int wgs_per_head, int rows, int cols, int reps, int waves,
+                           void* hip_stream) {
+  if (!base || heads < 1 || wgs_per_head < 1 || rows < 32 || rows % 32 != 0 || cols < 1 || reps < 1 || waves < 1 || waves > 4)
+    return 0.0;
+  hipLaunchKernelGGL(atomic_tile_kernel, dim3(heads * wgs_per_head), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(base), wgs_per_head, rows, cols, reps, waves);
+  if (hipGetLastError() != hipSuccess) return 0.0;
+  return (double)heads * wgs_per_head * waves * reps * rows * cols * 2.0 * 4.0;
 }
 
 }  // extern "C"
