@@ -28,11 +28,16 @@
 namespace tvm {
 namespace {
 
-constexpr int kNW = 4, kNT = 256;
-constexpr int kWI = 2, kWJ = 4;              // 32 x 32 blocks per wave along i (lane dimension) and j
-constexpr int kTI = 2 * kWI * 32;            // output rows per workgroup (128)
-constexpr int kTJ = 2 * kWJ * 32;            // output columns per workgroup (256)
-constexpr int kBK = 32;                      // contraction per LDS tile
+// Shape of a workgroup: NWI x NWJ waves, each with WI x WJ blocks of 32 x 32; NST LDS stages; OCC workgroups per CU.
+template <int NWI_, int NWJ_, int WI_, int WJ_, int NST_, int OCC_>
+struct Cfg {
+  static constexpr int NWI = NWI_, NWJ = NWJ_, WI = WI_, WJ = WJ_, NST = NST_, OCC = OCC_;
+  static constexpr int NW = NWI_ * NWJ_, NT = 64 * NW;
+  static constexpr int TI = NWI_ * WI_ * 32;  // output rows per workgroup
+  static constexpr int TJ = NWJ_ * WJ_ * 32;  // output columns per workgroup
+};
+constexpr int kBK = 64;                      // contraction per LDS tile
+constexpr int kGI = 8;                       // tile rows per group in the order the tiles are handed out
 
 // Transposed fragment with the contraction index in natural order: lane (ic, hh) gets, of column 32*db + ic of the
 // tile, rows 16*cc + 8*hh + 0..7 (the first transposing read takes rows 8hh..8hh+3, the second 8hh+4..8hh+7;
@@ -67,27 +72,42 @@ struct GemmArgs {
   const bf16* bias;   // added to out[0] only (the tangent has no bias), may be null
   float* part;        // grad W: float32 partial tiles [splits][I][J]
   int splits;
+  int nz;             // row sets (forward, grad x: 2) or splits (grad W)
 };
 
-template <bool PTR, bool QTR, bool PARTIAL>
-__global__ __launch_bounds__(kNT, 2) void gemm_kernel(GemmArgs g) {
-  // tiles: "row" access [rows of the operand][kBK], "transposed" access [kBK][columns of the stored matrix]
-  using TP = typename std::conditional<PTR, Tile<kBK, kTI / 8, kNW>, Tile<kTI, kBK / 8, kNW>>::type;
-  using TQ = typename std::conditional<QTR, Tile<kBK, kTJ / 8, kNW>, Tile<kTJ, kBK / 8, kNW>>::type;
-  constexpr int BUF = TP::BYTES + TQ::BYTES;
-  constexpr int STAGE_BYTES = 2 * BUF;
+template <bool PTR, bool QTR, bool PARTIAL, class C>
+__global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
+  constexpr int kNW = C::NW, kWI = C::WI, kWJ = C::WJ, kTI = C::TI, kTJ = C::TJ, NST = C::NST;
+  // tiles: "transposed" access [kBK][columns of the stored matrix]; "row" access [rows of the operand][32], two of
+  // them back to back for the kBK = 64 entries of a contraction tile (rows of 64 bytes are dense in LDS and free of
+  // bank conflicts; rows of 128 bytes would need padding)
+  static_assert(kBK == 64, "a row-access operand is staged as two tiles of 32");
+  using TP = typename std::conditional<PTR, Tile<kBK, kTI / 8, kNW>, Tile<kTI, 4, kNW>>::type;
+  using TQ = typename std::conditional<QTR, Tile<kBK, kTJ / 8, kNW>, Tile<kTJ, 4, kNW>>::type;
+  constexpr int P_BYTES = PTR ? TP::BYTES : 2 * TP::BYTES, Q_BYTES = QTR ? TQ::BYTES : 2 * TQ::BYTES;
+  constexpr int BUF = P_BYTES + Q_BYTES;
+  constexpr int STAGE_BYTES = NST * BUF;  // NST stages: tile t in use, tiles t+1 .. t+NST-2 landed or landing, one being refilled
+  constexpr int LOADS = (PTR ? 1 : 2) * TP::IPW + (QTR ? 1 : 2) * TQ::IPW;  // wave-loads per wave and tile
   constexpr int OUT_REGION = 32 * (64 * kWJ + 16);  // per wave, for store_tile_coalesced
   constexpr int LDS_BYTES = STAGE_BYTES > kNW * OUT_REGION ? STAGE_BYTES : kNW * OUT_REGION;
   __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wi = wave & 1, wj = wave >> 1;
+  const int wi = wave % C::NWI, wj = wave / C::NWI;
   const int nI = (g.I + kTI - 1) / kTI, nJ = (g.J + kTJ - 1) / kTJ;
-  int wg = blockIdx.x;
-  const int jt = wg % nJ;
-  wg /= nJ;
-  const int it = wg % nI;
-  const int zz = wg / nI;  // row set (forward, grad x) or split (grad W)
+  // Which tile: hardware workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own, and a CU runs
+  // them in increasing order.  XCD x works through the x-th eighth of the logical ids (the launcher pads the grid to
+  // a multiple of 8), and logical ids walk the tiles of a row set (or split) in groups of kGI tile rows, down the
+  // group first: the ~64 workgroups an XCD runs at one time then cover about 8 x 8 tiles and march through the
+  // contraction together, so that each operand panel comes from HBM once for the 8 tiles that share it.
+  const int per_xcd = (int)(gridDim.x >> 3);
+  const int wg = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (wg >= g.nz * nI * nJ) return;  // (padding)
+  const int zz = wg / (nI * nJ);  // row set (forward, grad x) or split (grad W)
+  const int id = wg - zz * (nI * nJ);
+  const int grp = id / (kGI * nJ), it_first = grp * kGI, gs = min(nI - it_first, kGI);
+  const int rem = id - grp * (kGI * nJ);
+  const int jt = rem / gs, it = it_first + (rem - jt * gs);
   const int i0 = it * kTI, j0 = jt * kTJ;
   const int nct = (g.C + kBK - 1) / kBK;  // contraction tiles per set
   const int ntot = g.csets * nct;
@@ -107,28 +127,37 @@ __global__ __launch_bounds__(kNT, 2) void gemm_kernel(GemmArgs g) {
       op_full = TP::offsets(l, pitchP, kBK);
       op_last = TP::offsets(l, pitchP, clast);
     } else {
-      const typename TP::Lane l = TP::lane_setup(kBK, wave, lane);
-      op_full = op_last = TP::offsets(l, pitchP, g.I - i0);
+      op_full = op_last = TP::offsets(TP::lane_setup(32, wave, lane), pitchP, g.I - i0);
     }
     if (QTR) {
       const typename TQ::Lane l = TQ::lane_setup(min(g.J - j0, kTJ), wave, lane);
       oq_full = TQ::offsets(l, pitchQ, kBK);
       oq_last = TQ::offsets(l, pitchQ, clast);
     } else {
-      const typename TQ::Lane l = TQ::lane_setup(kBK, wave, lane);
-      oq_full = oq_last = TQ::offsets(l, pitchQ, g.J - j0);
+      oq_full = oq_last = TQ::offsets(TQ::lane_setup(32, wave, lane), pitchQ, g.J - j0);
     }
   }
-  auto issue = [&](int t, unsigned buf) {
+  // wave-load number x (compile-time, 0 .. LOADS-1) of contraction tile t into the stage at `buf`
+  auto issue = [&](int t, unsigned buf, int x) {
     const int set = t / nct, ct = t - set * nct;
     const long long c0 = (long long)ct * kBK;
     const bool last = ct == nct - 1;
     const bf16* pb = g.P[PARTIAL ? set : pset] + (PTR ? c0 * g.ldP + i0 : (long long)i0 * g.ldP + c0);
     const bf16* qb = g.Q[PARTIAL ? set : 0] + (QTR ? c0 * g.ldQ + j0 : (long long)j0 * g.ldQ + c0);
-#pragma unroll
-    for (int x = 0; x < TP::IPW; ++x) TP::issue_at(last ? op_last.o[x] : op_full.o[x], x, pb, buf, wave);
-#pragma unroll
-    for (int x = 0; x < TQ::IPW; ++x) TQ::issue_at(last ? oq_last.o[x] : oq_full.o[x], x, qb, buf + TP::BYTES, wave);
+    // (row access: the contraction length is a multiple of 32, so the second half of a set's last tile is either
+    // whole or absent; an absent half fetches the first half again, and its fragments are zeroed on the P side)
+    const int half2 = (last && g.C - (int)c0 <= 32) ? 0 : 32;
+    constexpr int NP = (PTR ? 1 : 2) * TP::IPW;
+    if (x < NP) {
+      if (PTR) TP::issue_at(last ? op_last.o[x] : op_full.o[x], x, pb, buf, wave);
+      else if (x < TP::IPW) TP::issue_at(op_full.o[x], x, pb, buf, wave);
+      else TP::issue_at(op_full.o[x - TP::IPW], x - TP::IPW, pb + half2, buf + TP::BYTES, wave);
+    } else {
+      const int y = x - NP;
+      if (QTR) TQ::issue_at(last ? oq_last.o[y] : oq_full.o[y], y, qb, buf + P_BYTES, wave);
+      else if (y < TQ::IPW) TQ::issue_at(oq_full.o[y], y, qb, buf + P_BYTES, wave);
+      else TQ::issue_at(oq_full.o[y - TQ::IPW], y - TQ::IPW, qb + half2, buf + P_BYTES + TQ::BYTES, wave);
+    }
   };
   const typename TP::RAddr rp = TP::raddr(ic, hh);
   const typename TQ::RAddr rq = TQ::raddr(ic, hh);
@@ -141,43 +170,70 @@ __global__ __launch_bounds__(kNT, 2) void gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int b = 0; b < kWJ; ++b) acc[a][b] = zero16();
 
-  if (t_begin < t_end) issue(t_begin, lds0);
-  dma_wait();
-  __syncthreads();
-  for (int t = t_begin, n = 0; t < t_end; ++t, ++n) {
-    const char* sp = lds + (n & 1) * BUF;
-    const char* sq = sp + TP::BYTES;
-    if (t + 1 < t_end) issue(t + 1, lds0 + ((n + 1) & 1) * BUF);  // uniform: lands during this tile
-    // a ragged last contraction tile (transposed access only: a row set's token count is arbitrary): entries beyond
-    // the set's end were fetched as copies of its last row; the P fragment gets zeros there
+  // A ragged last contraction tile of a set: entries beyond the set's end were fetched as copies of valid ones (the
+  // set's last row, or the first half of the tile); on the P side each wave overwrites with zeros what it fetched of
+  // them (call this once its own loads have landed), so that those entries contribute nothing.
+  auto fix_ragged = [&](int t, int n) {
     const int ct = t % nct;
-    const int cvalid = (PTR && ct == nct - 1) ? g.C - ct * kBK : kBK;
+    const int cvalid = ct == nct - 1 ? g.C - ct * kBK : kBK;
+    if (cvalid < kBK) {
+      char* pt = lds + n * BUF;
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      bf16x8 pf[kWI], qf[kWJ];
-#pragma unroll
-      for (int a = 0; a < kWI; ++a) {
-        pf[a] = PTR ? tp.frag(sp, kk, wi * kWI + a) : TP::frag_row(sp, rp, wi * kWI + a, kk);
-        if (PTR && cvalid < kBK) {
-          uint4 v = __builtin_bit_cast(uint4, pf[a]);
-          const int k0 = kk * 16 + hh * 8;  // contraction index of the fragment's first element
-          v.x = k0 + 0 < cvalid ? (k0 + 1 < cvalid ? v.x : v.x & 0xFFFFu) : 0u;
-          v.y = k0 + 2 < cvalid ? (k0 + 3 < cvalid ? v.y : v.y & 0xFFFFu) : 0u;
-          v.z = k0 + 4 < cvalid ? (k0 + 5 < cvalid ? v.z : v.z & 0xFFFFu) : 0u;
-          v.w = k0 + 6 < cvalid ? (k0 + 7 < cvalid ? v.w : v.w & 0xFFFFu) : 0u;
-          pf[a] = __builtin_bit_cast(bf16x8, v);
+      for (int x = 0; x < TP::IPW; ++x) {
+        const int pos = (wave + x * kNW) * 64 + lane;  // chunk of the tile this lane fetched with wave-load x
+        if (PTR) {
+          if (pos / TP::PCH >= cvalid) *reinterpret_cast<uint4*>(pt + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
+        } else if (cvalid <= 32) {
+          *reinterpret_cast<uint4*>(pt + TP::BYTES + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
         }
       }
+    }
+  };
+  bf16x8 pf[2][kWI], qf[2][kWJ];
+  static_assert(NST == 2, "two stages");
+  if (t_begin < t_end) {
 #pragma unroll
-      for (int b = 0; b < kWJ; ++b) qf[b] = QTR ? tq.frag(sq, kk, wj * kWJ + b) : TQ::frag_row(sq, rq, wj * kWJ + b, kk);
+    for (int x = 0; x < LOADS; ++x) issue(t_begin, lds0, x);
+    dma_wait();
+    fix_ragged(t_begin, 0);
+  }
+  __syncthreads();
+  for (int t = t_begin, n = 0; t < t_end; ++t, n ^= 1) {
+    // tile t is there for everyone and everyone is done with tile t-1, whose stage is refilled now
+    const bool more = t + 1 < t_end;  // uniform
+    if (more) {
+#pragma unroll
+      for (int x = 0; x < LOADS; ++x) issue(t + 1, lds0 + (n ^ 1) * BUF, x);
+    }
+    const char* sp = lds + n * BUF;
+    const char* sq = sp + P_BYTES;
+    // fragments of contraction step kk into register set `set`
+    auto fetch = [&](int set, int kk) {
+#pragma unroll
+      for (int a = 0; a < kWI; ++a) {
+        pf[set][a] = PTR ? tp.frag(sp, kk, wi * kWI + a) : TP::frag_row(sp + (kk >> 1) * TP::BYTES, rp, wi * kWI + a, kk & 1);
+      }
+#pragma unroll
+      for (int b = 0; b < kWJ; ++b) qf[set][b] = QTR ? tq.frag(sq, kk, wj * kWJ + b) : TQ::frag_row(sq + (kk >> 1) * TQ::BYTES, rq, wj * kWJ + b, kk & 1);
+    };
+    // two register sets take turns: the LDS reads of step kk+1 are issued ahead of the products of step kk (the
+    // scheduling barriers keep the compiler from sinking them back to their first use)
+    fetch(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < kBK / 16; ++kk) {
+      if (kk + 1 < kBK / 16) fetch((kk + 1) & 1, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int a = 0; a < kWI; ++a)
 #pragma unroll
-        for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[b], pf[a], acc[a][b]);
+        for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[kk & 1][b], pf[kk & 1][a], acc[a][b]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    dma_wait();
-    __syncthreads();  // the next tile has landed; everyone is done with this one
+    dma_wait();  // the next tile has landed
+    if (more) fix_ragged(t + 1, n ^ 1);
+    __syncthreads();
   }
+  // everyone is done with the last tile (no load is in flight): the stages become output staging
 
   const int jw = j0 + wj * (kWJ * 32);  // first output column of this wave
   if (PARTIAL) {
@@ -244,28 +300,69 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
   *reinterpret_cast<bf16x8*>(out + e) = o;
 }
 
-// Column sums of gy [R][F] over `chunks` row ranges: part[chunk][f] (float32).  A thread per column.
+// Column sums of gy [R][F] over `chunks` row ranges: part[chunk][f] (float32).  A lane takes 8 columns (16-byte
+// loads, a wave 512 columns of a row), the four waves of a workgroup every fourth row of the chunk each; their sums
+// meet in LDS, in a fixed order.
 __global__ __launch_bounds__(256) void colsum_kernel(const bf16* __restrict__ gy, int R, int F, long long ld, int chunks,
                                                      float* __restrict__ part) {
-  const int f = blockIdx.x * 256 + threadIdx.x, ch = blockIdx.y;
-  if (f >= F) return;
+  __shared__ float red[4][64][8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ch = blockIdx.y;
+  const int f = (blockIdx.x * 64 + lane) * 8;  // (F is a multiple of 8: eight columns are in range together)
   const int r0 = (int)((long long)ch * R / chunks), r1 = (int)((long long)(ch + 1) * R / chunks);
-  float s = 0.f;
-  for (int r = r0; r < r1; ++r) s += (float)gy[(long long)r * ld + f];
-  part[(long long)ch * F + f] = s;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (f < F) {
+    const bf16* col = gy + f;
+    int r = r0 + wave;
+    for (; r + 12 < r1; r += 16) {  // four rows in flight
+      bf16x8 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const bf16x8*>(col + (long long)(r + 4 * u) * ld);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (float)v[u][e];
+    }
+    for (; r < r1; r += 4) {
+      const bf16x8 v = *reinterpret_cast<const bf16x8*>(col + (long long)r * ld);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += (float)v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[wave][lane][e] = acc[e];
+  __syncthreads();
+  if (wave == 0 && f < F) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[(long long)ch * F + f + e] = (red[0][lane][e] + red[1][lane][e]) + (red[2][lane][e] + red[3][lane][e]);
+  }
 }
 
+// The shapes in use: forward and grad x, grad W
+using CfgF = Cfg<2, 4, 4, 2, 2, 1>;
+using CfgX = Cfg<2, 4, 4, 2, 2, 1>;
+using CfgW = Cfg<2, 4, 4, 2, 2, 1>;
+
 int dw_splits(int F, int K, int R) {
-  const int tiles = ((F + kTI - 1) / kTI) * ((K + kTJ - 1) / kTJ);
+  const int tiles = ((F + CfgW::TI - 1) / CfgW::TI) * ((K + CfgW::TJ - 1) / CfgW::TJ);
   const int ntot = 2 * ((R + kBK - 1) / kBK);
-  int s = (384 + tiles - 1) / tiles;
-  s = s > 16 ? 16 : s;
-  s = s > ntot ? ntot : s;
-  return s < 1 ? 1 : s;
+  // The fewest rounds of workgroups over the chip's 256 CUs (one workgroup each), each round costing its share of
+  // the contraction plus a fixed part (start-up, the float32 partial tile); ties go to fewer splits.
+  int best = 1;
+  long long best_cost = -1;
+  for (int s = 1; s <= 32 && s <= ntot; ++s) {
+    const long long rounds = ((long long)s * tiles + 255) / 256;
+    const long long cost = rounds * ((ntot + s - 1) / s + 64);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = s;
+    }
+  }
+  return best;
 }
+int pad8(int n) { return (n + 7) & ~7; }
 int bias_chunks(int R) {
-  const int c = (R + 127) / 128;
-  return c > 64 ? 64 : c;
+  const int c = (R + 63) / 64;
+  return c > 256 ? 256 : c;
 }
 
 }  // namespace
@@ -298,8 +395,9 @@ hipError_t launch_linear_fwd(int R, int K, int F, long long ldx, long long ldy, 
   g.out[1] = (bf16*)ty;
   g.ldo = ldy;
   g.bias = (const bf16*)bias;
-  const int grid = 2 * ((R + kTI - 1) / kTI) * ((F + kTJ - 1) / kTJ);
-  hipLaunchKernelGGL((gemm_kernel<false, false, false>), dim3(grid), dim3(kNT), 0, st, g);
+  g.nz = 2;
+  const int grid = pad8(2 * ((R + CfgF::TI - 1) / CfgF::TI) * ((F + CfgF::TJ - 1) / CfgF::TJ));
+  hipLaunchKernelGGL((gemm_kernel<false, false, false, CfgF>), dim3(grid), dim3(CfgF::NT), 0, st, g);
   return hipGetLastError();
 }
 
@@ -320,8 +418,9 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     g.out[0] = (bf16*)gx;
     g.out[1] = (bf16*)gtx;
     g.ldo = ldx;
-    const int grid = 2 * ((R + kTI - 1) / kTI) * ((K + kTJ - 1) / kTJ);
-    hipLaunchKernelGGL((gemm_kernel<false, true, false>), dim3(grid), dim3(kNT), 0, st, g);
+    g.nz = 2;
+    const int grid = pad8(2 * ((R + CfgX::TI - 1) / CfgX::TI) * ((K + CfgX::TJ - 1) / CfgX::TJ));
+    hipLaunchKernelGGL((gemm_kernel<false, true, false, CfgX>), dim3(grid), dim3(CfgX::NT), 0, st, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -341,8 +440,9 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     g.csets = 2;
     g.part = part;
     g.splits = splits;
-    const int grid = splits * ((F + kTI - 1) / kTI) * ((K + kTJ - 1) / kTJ);
-    hipLaunchKernelGGL((gemm_kernel<true, true, true>), dim3(grid), dim3(kNT), 0, st, g);
+    g.nz = splits;
+    const int grid = pad8(splits * ((F + CfgW::TI - 1) / CfgW::TI) * ((K + CfgW::TJ - 1) / CfgW::TJ));
+    hipLaunchKernelGGL((gemm_kernel<true, true, true, CfgW>), dim3(grid), dim3(CfgW::NT), 0, st, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const long long n = (long long)F * K;
@@ -355,7 +455,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     const size_t dw = ((size_t)splits * F * K * sizeof(float) + 255) & ~(size_t)255;
     float* bp = reinterpret_cast<float*>(static_cast<char*>(workspace) + dw);
     const int chunks = bias_chunks(R);
-    hipLaunchKernelGGL(colsum_kernel, dim3((F + 255) / 256, chunks), dim3(256), 0, st, (const bf16*)gy, R, F, ldy, chunks, bp);
+    hipLaunchKernelGGL(colsum_kernel, dim3((F + 511) / 512, chunks), dim3(256), 0, st, (const bf16*)gy, R, F, ldy, chunks, bp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((F / 8 + 255) / 256)), dim3(256), 0, st, bp, chunks, (long long)F,

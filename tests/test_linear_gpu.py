@@ -50,6 +50,8 @@ def run(R, K, F, seed, bias=True):
     (257, 160, 544),      # three row tiles, ragged in every dimension of the tiling
     (300, 1152, 384), (300, 384, 1152),
     (1000, 288, 864),     # the shape of a QKV projection (F = 3 K) with many contraction splits
+    (513, 64, 256),       # one row beyond two row tiles of 256; contraction of exactly one tile
+    (600, 352, 608),      # contraction lengths that end in half a tile (352 = 5.5 x 64, 608 = 9.5 x 64)
 ])
 def test_linear_against_the_oracle(R, K, F):
     run(R, K, F, seed=7 + R % 5)
