@@ -95,186 +95,204 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wi = wave % C::NWI, wj = wave / C::NWI;
   const int nI = (g.I + kTI - 1) / kTI, nJ = (g.J + kTJ - 1) / kTJ;
-  // Which tile: hardware workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own, and a CU runs
-  // them in increasing order.  XCD x works through the x-th eighth of the logical ids (the launcher pads the grid to
-  // a multiple of 8), and logical ids walk the tiles of a row set (or split) in groups of kGI tile rows, down the
-  // group first: the ~64 workgroups an XCD runs at one time then cover about 8 x 8 tiles and march through the
-  // contraction together, so that each operand panel comes from HBM once for the 8 tiles that share it.
-  const int per_xcd = (int)(gridDim.x >> 3);
-  const int wg = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if (wg >= g.nz * nI * nJ) return;  // (padding)
-  const int zz = wg / (nI * nJ);  // row set (forward, grad x) or split (grad W)
-  const int id = wg - zz * (nI * nJ);
-  const int grp = id / (kGI * nJ), it_first = grp * kGI, gs = min(nI - it_first, kGI);
-  const int rem = id - grp * (kGI * nJ);
-  const int jt = rem / gs, it = it_first + (rem - jt * gs);
-  const int i0 = it * kTI, j0 = jt * kTJ;
   const int nct = (g.C + kBK - 1) / kBK;  // contraction tiles per set
   const int ntot = g.csets * nct;
-  const int t_begin = PARTIAL ? (int)((long long)zz * ntot / g.splits) : 0;
-  const int t_end = PARTIAL ? (int)((long long)(zz + 1) * ntot / g.splits) : ntot;
-  const int pset = PARTIAL ? 0 : zz;
-
   const unsigned lds0 = lds_addr_of(lds);
-  // per-lane byte offsets of this wave's loads within a tile, worked out once
-  typename TP::Offs op_full, op_last;
-  typename TQ::Offs oq_full, oq_last;
-  {
-    const unsigned pitchP = (unsigned)(g.ldP * 2), pitchQ = (unsigned)(g.ldQ * 2);
-    const int clast = g.C - (nct - 1) * kBK;  // contraction entries in a set's last tile
-    if (PTR) {
-      const typename TP::Lane l = TP::lane_setup(min(g.I - i0, kTI), wave, lane);  // columns of the stored matrix = output rows
-      op_full = TP::offsets(l, pitchP, kBK);
-      op_last = TP::offsets(l, pitchP, clast);
-    } else {
-      op_full = op_last = TP::offsets(TP::lane_setup(32, wave, lane), pitchP, g.I - i0);
-    }
-    if (QTR) {
-      const typename TQ::Lane l = TQ::lane_setup(min(g.J - j0, kTJ), wave, lane);
-      oq_full = TQ::offsets(l, pitchQ, kBK);
-      oq_last = TQ::offsets(l, pitchQ, clast);
-    } else {
-      oq_full = oq_last = TQ::offsets(TQ::lane_setup(32, wave, lane), pitchQ, g.J - j0);
-    }
-  }
-  // wave-load number x (compile-time, 0 .. LOADS-1) of contraction tile t into the stage at `buf`
-  auto issue = [&](int t, unsigned buf, int x) {
-    const int set = t / nct, ct = t - set * nct;
-    const long long c0 = (long long)ct * kBK;
-    const bool last = ct == nct - 1;
-    const bf16* pb = g.P[PARTIAL ? set : pset] + (PTR ? c0 * g.ldP + i0 : (long long)i0 * g.ldP + c0);
-    const bf16* qb = g.Q[PARTIAL ? set : 0] + (QTR ? c0 * g.ldQ + j0 : (long long)j0 * g.ldQ + c0);
-    // (row access: the contraction length is a multiple of 32, so the second half of a set's last tile is either
-    // whole or absent; an absent half fetches the first half again, and its fragments are zeroed on the P side)
-    const int half2 = (last && g.C - (int)c0 <= 32) ? 0 : 32;
-    constexpr int NP = (PTR ? 1 : 2) * TP::IPW;
-    if (x < NP) {
-      if (PTR) TP::issue_at(last ? op_last.o[x] : op_full.o[x], x, pb, buf, wave);
-      else if (x < TP::IPW) TP::issue_at(op_full.o[x], x, pb, buf, wave);
-      else TP::issue_at(op_full.o[x - TP::IPW], x - TP::IPW, pb + half2, buf + TP::BYTES, wave);
-    } else {
-      const int y = x - NP;
-      if (QTR) TQ::issue_at(last ? oq_last.o[y] : oq_full.o[y], y, qb, buf + P_BYTES, wave);
-      else if (y < TQ::IPW) TQ::issue_at(oq_full.o[y], y, qb, buf + P_BYTES, wave);
-      else TQ::issue_at(oq_full.o[y - TQ::IPW], y - TQ::IPW, qb + half2, buf + P_BYTES + TQ::BYTES, wave);
-    }
-  };
   const typename TP::RAddr rp = TP::raddr(ic, hh);
   const typename TQ::RAddr rq = TQ::raddr(ic, hh);
   const TrNat<TP> tp = TrNat<TP>::make(ic, hh);
   const TrNat<TQ> tq = TrNat<TQ>::make(ic, hh);
-
   f32x16 acc[kWI][kWJ];
-#pragma unroll
-  for (int a = 0; a < kWI; ++a)
-#pragma unroll
-    for (int b = 0; b < kWJ; ++b) acc[a][b] = zero16();
+  bf16x8 pf[2][kWI], qf[2][kWJ];
+  static_assert(NST == 2, "two stages");
+  static_assert(kNW * OUT_REGION <= BUF, "the output staging fits in one stage");
 
-  // A ragged last contraction tile of a set: entries beyond the set's end were fetched as copies of valid ones (the
-  // set's last row, or the first half of the tile); on the P side each wave overwrites with zeros what it fetched of
-  // them (call this once its own loads have landed), so that those entries contribute nothing.
-  auto fix_ragged = [&](int t, int n) {
-    const int ct = t % nct;
-    const int cvalid = ct == nct - 1 ? g.C - ct * kBK : kBK;
-    if (cvalid < kBK) {
-      char* pt = lds + n * BUF;
+  // Writes out the accumulators of output tile (i0, j0) of row set / split zz.  Runs while the first loads of the
+  // workgroup's next tile are on their way into the first stage: bf16 results are staged through the second one.
+  auto write_out = [&](int i0, int j0, int zz) {
+    const int jw = j0 + wj * (kWJ * 32);  // first output column of this wave
+    if (PARTIAL) {
+      // float32 partial tile: lane = output row, four consecutive columns per register group
+      float* dst = g.part + (long long)zz * g.I * g.J;
 #pragma unroll
-      for (int x = 0; x < TP::IPW; ++x) {
-        const int pos = (wave + x * kNW) * 64 + lane;  // chunk of the tile this lane fetched with wave-load x
-        if (PTR) {
-          if (pos / TP::PCH >= cvalid) *reinterpret_cast<uint4*>(pt + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
-        } else if (cvalid <= 32) {
-          *reinterpret_cast<uint4*>(pt + TP::BYTES + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
+      for (int a = 0; a < kWI; ++a) {
+        const int i = i0 + (wi * kWI + a) * 32 + ic;
+        if (i >= g.I) continue;
+#pragma unroll
+        for (int b = 0; b < kWJ; ++b)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int j = jw + b * 32 + 8 * q4 + 4 * hh;
+            if (j < g.J) {  // (J is a multiple of 8: four columns are in range together)
+              typedef __attribute__((ext_vector_type(4))) float f32x4;
+              const f32x4 v = {acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3]};
+              *reinterpret_cast<f32x4*>(dst + (long long)i * g.J + j) = v;
+            }
+          }
+      }
+    } else {
+      const unsigned lw = lds0 + BUF + (unsigned)wave * OUT_REGION;  // each wave stages its rows through a region of its own
+      if (jw < g.J) {
+#pragma unroll
+        for (int a = 0; a < kWI; ++a) {
+          const int row0 = i0 + (wi * kWI + a) * 32;
+          store_tile_coalesced<kWJ>(lw, g.out[zz] + jw, g.ldo, row0, g.I, g.J - jw, acc[a], 1.f, lane);
         }
       }
     }
   };
-  bf16x8 pf[2][kWI], qf[2][kWJ];
-  static_assert(NST == 2, "two stages");
-  if (t_begin < t_end) {
-#pragma unroll
-    for (int x = 0; x < LOADS; ++x) issue(t_begin, lds0, x);
-    dma_wait();
-    fix_ragged(t_begin, 0);
-  }
-  __syncthreads();
-  for (int t = t_begin, n = 0; t < t_end; ++t, n ^= 1) {
-    // tile t is there for everyone and everyone is done with tile t-1, whose stage is refilled now
-    const bool more = t + 1 < t_end;  // uniform
-    if (more) {
-#pragma unroll
-      for (int x = 0; x < LOADS; ++x) issue(t + 1, lds0 + (n ^ 1) * BUF, x);
-    }
-    const char* sp = lds + n * BUF;
-    const char* sq = sp + P_BYTES;
-    // fragments of contraction step kk into register set `set`
-    auto fetch = [&](int set, int kk) {
-#pragma unroll
-      for (int a = 0; a < kWI; ++a) {
-        pf[set][a] = PTR ? tp.frag(sp, kk, wi * kWI + a) : TP::frag_row(sp + (kk >> 1) * TP::BYTES, rp, wi * kWI + a, kk & 1);
-      }
-#pragma unroll
-      for (int b = 0; b < kWJ; ++b) qf[set][b] = QTR ? tq.frag(sq, kk, wj * kWJ + b) : TQ::frag_row(sq + (kk >> 1) * TQ::BYTES, rq, wj * kWJ + b, kk & 1);
-    };
-    // two register sets take turns: the LDS reads of step kk+1 are issued ahead of the products of step kk (the
-    // scheduling barriers keep the compiler from sinking them back to their first use)
-    fetch(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      if (kk + 1 < kBK / 16) fetch((kk + 1) & 1, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int a = 0; a < kWI; ++a)
-#pragma unroll
-        for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[kk & 1][b], pf[kk & 1][a], acc[a][b]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    dma_wait();  // the next tile has landed
-    if (more) fix_ragged(t + 1, n ^ 1);
-    __syncthreads();
-  }
-  // everyone is done with the last tile (no load is in flight): the stages become output staging
 
-  const int jw = j0 + wj * (kWJ * 32);  // first output column of this wave
-  if (PARTIAL) {
-    // float32 partial tile: lane = output row, four consecutive columns per register group
-    float* dst = g.part + (long long)zz * g.I * g.J;
+  // Persistent workgroups, one per CU, each working through a list of output tiles, so that a tile's results are
+  // written while the next tile's first operands are fetched (and drain to HBM while it is computed).  Hardware
+  // workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own: XCD x owns the x-th eighth of the
+  // logical tile ids, which its workgroups take in turn; logical ids walk the tiles of a row set (or split) in groups
+  // of kGI tile rows, down the group first.  The ~32 workgroups of an XCD are then on a patch of about 8 x 4 tiles at
+  // any one time and march through the contraction together: an operand panel comes from HBM once for the tiles of
+  // the patch that share it.
+  const int total = g.nz * nI * nJ;
+  const int per_xcd = (total + 7) >> 3, wg_per_xcd = (int)(gridDim.x >> 3);
+  const int id_end = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
+  int prev_i0 = 0, prev_j0 = 0, prev_zz = -1;  // the tile whose results are still in the accumulators (zz < 0: none)
+  for (int wg = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);; wg += wg_per_xcd) {
+    if (wg >= id_end) {
+      if (prev_zz >= 0) write_out(prev_i0, prev_j0, prev_zz);
+      break;
+    }
+    const int zz = wg / (nI * nJ);  // row set (forward, grad x) or split (grad W)
+    const int id = wg - zz * (nI * nJ);
+    const int grp = id / (kGI * nJ), it_first = grp * kGI, gs = min(nI - it_first, kGI);
+    const int rem = id - grp * (kGI * nJ);
+    const int jt = rem / gs, it = it_first + (rem - jt * gs);
+    const int i0 = it * kTI, j0 = jt * kTJ;
+    const int t_begin = PARTIAL ? (int)((long long)zz * ntot / g.splits) : 0;
+    const int t_end = PARTIAL ? (int)((long long)(zz + 1) * ntot / g.splits) : ntot;
+    const int pset = PARTIAL ? 0 : zz;
+
+    // per-lane byte offsets of this wave's loads within a tile, worked out once per output tile
+    typename TP::Offs op_full, op_last;
+    typename TQ::Offs oq_full, oq_last;
+    {
+      const unsigned pitchP = (unsigned)(g.ldP * 2), pitchQ = (unsigned)(g.ldQ * 2);
+      const int clast = g.C - (nct - 1) * kBK;  // contraction entries in a set's last tile
+      if (PTR) {
+        const typename TP::Lane l = TP::lane_setup(min(g.I - i0, kTI), wave, lane);  // columns of the stored matrix = output rows
+        op_full = TP::offsets(l, pitchP, kBK);
+        op_last = TP::offsets(l, pitchP, clast);
+      } else {
+        op_full = op_last = TP::offsets(TP::lane_setup(32, wave, lane), pitchP, g.I - i0);
+      }
+      if (QTR) {
+        const typename TQ::Lane l = TQ::lane_setup(min(g.J - j0, kTJ), wave, lane);
+        oq_full = TQ::offsets(l, pitchQ, kBK);
+        oq_last = TQ::offsets(l, pitchQ, clast);
+      } else {
+        oq_full = oq_last = TQ::offsets(TQ::lane_setup(32, wave, lane), pitchQ, g.J - j0);
+      }
+    }
+    // wave-load number x (compile-time, 0 .. LOADS-1) of contraction tile t into the stage at `buf`
+    auto issue = [&](int t, unsigned buf, int x) {
+      const int set = t / nct, ct = t - set * nct;
+      const long long c0 = (long long)ct * kBK;
+      const bool last = ct == nct - 1;
+      const bf16* pb = g.P[PARTIAL ? set : pset] + (PTR ? c0 * g.ldP + i0 : (long long)i0 * g.ldP + c0);
+      const bf16* qb = g.Q[PARTIAL ? set : 0] + (QTR ? c0 * g.ldQ + j0 : (long long)j0 * g.ldQ + c0);
+      // (row access: the contraction length is a multiple of 32, so the second half of a set's last tile is either
+      // whole or absent; an absent half fetches the first half again, and its fragments are zeroed on the P side)
+      const int half2 = (last && g.C - (int)c0 <= 32) ? 0 : 32;
+      constexpr int NP = (PTR ? 1 : 2) * TP::IPW;
+      if (x < NP) {
+        if (PTR) TP::issue_at(last ? op_last.o[x] : op_full.o[x], x, pb, buf, wave);
+        else if (x < TP::IPW) TP::issue_at(op_full.o[x], x, pb, buf, wave);
+        else TP::issue_at(op_full.o[x - TP::IPW], x - TP::IPW, pb + half2, buf + TP::BYTES, wave);
+      } else {
+        const int y = x - NP;
+        if (QTR) TQ::issue_at(last ? oq_last.o[y] : oq_full.o[y], y, qb, buf + P_BYTES, wave);
+        else if (y < TQ::IPW) TQ::issue_at(oq_full.o[y], y, qb, buf + P_BYTES, wave);
+        else TQ::issue_at(oq_full.o[y - TQ::IPW], y - TQ::IPW, qb + half2, buf + P_BYTES + TQ::BYTES, wave);
+      }
+    };
+    // A ragged last contraction tile of a set: entries beyond the set's end were fetched as copies of valid ones (the
+    // set's last row, or the first half of the tile); on the P side each wave overwrites with zeros what it fetched of
+    // them (call this once its own loads have landed), so that those entries contribute nothing.
+    auto fix_ragged = [&](int t, int n) {
+      const int ct = t % nct;
+      const int cvalid = ct == nct - 1 ? g.C - ct * kBK : kBK;
+      if (cvalid < kBK) {
+        char* pt = lds + n * BUF;
 #pragma unroll
-    for (int a = 0; a < kWI; ++a) {
-      const int i = i0 + (wi * kWI + a) * 32 + ic;
-      if (i >= g.I) continue;
-#pragma unroll
-      for (int b = 0; b < kWJ; ++b)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int j = jw + b * 32 + 8 * q4 + 4 * hh;
-          if (j < g.J) {  // (J is a multiple of 8: four columns are in range together)
-            typedef __attribute__((ext_vector_type(4))) float f32x4;
-            const f32x4 v = {acc[a][b][4 * q4], acc[a][b][4 * q4 + 1], acc[a][b][4 * q4 + 2], acc[a][b][4 * q4 + 3]};
-            *reinterpret_cast<f32x4*>(dst + (long long)i * g.J + j) = v;
+        for (int x = 0; x < TP::IPW; ++x) {
+          const int pos = (wave + x * kNW) * 64 + lane;  // chunk of the tile this lane fetched with wave-load x
+          if (PTR) {
+            if (pos / TP::PCH >= cvalid) *reinterpret_cast<uint4*>(pt + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
+          } else if (cvalid <= 32) {
+            *reinterpret_cast<uint4*>(pt + TP::BYTES + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
           }
         }
-    }
-  } else {
-    if (g.bias != nullptr && pset == 0) {
+      }
+    };
+
+    // The tile before ended with a barrier: both stages are free.  This tile's first loads go out, then the results of
+    // the tile before leave (through the second stage), then the accumulators start from the bias (row set 0; the
+    // tangent has none) or from zero.
+#pragma unroll
+    for (int x = 0; x < LOADS; ++x) issue(t_begin, lds0, x);
+    if (prev_zz >= 0) write_out(prev_i0, prev_j0, prev_zz);
+    prev_i0 = i0;
+    prev_j0 = j0;
+    prev_zz = zz;
+    {
+      const bool with_bias = !PARTIAL && g.bias != nullptr && pset == 0;
+      const int jw = j0 + wj * (kWJ * 32);
 #pragma unroll
       for (int b = 0; b < kWJ; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = jw + b * 32 + drow(r, hh);
-          const float bv = j < g.J ? (float)g.bias[j] : 0.f;
+          const float bv = with_bias && j < g.J ? (float)g.bias[j] : 0.f;
 #pragma unroll
-          for (int a = 0; a < kWI; ++a) acc[a][b][r] += bv;
+          for (int a = 0; a < kWI; ++a) acc[a][b][r] = bv;
         }
     }
-    // the loop ended with a barrier and no tile load is in flight: each wave stages its rows through a region of its own
-    const unsigned lw = lds0 + (unsigned)wave * OUT_REGION;
-    if (jw < g.J) {
+    dma_wait();
+    fix_ragged(t_begin, 0);
+    __syncthreads();  // the first contraction tile is there for everyone; everyone's staging reads are over
+    for (int t = t_begin, n = 0; t < t_end; ++t, n ^= 1) {
+      // tile t is there for everyone and everyone is done with tile t-1, whose stage is refilled now
+      const bool more = t + 1 < t_end;  // uniform
+      const char* sp = lds + n * BUF;
+      const char* sq = sp + P_BYTES;
+      // fragments of contraction step kk into register set `set`
+      auto fetch = [&](int set, int kk) {
 #pragma unroll
-      for (int a = 0; a < kWI; ++a) {
-        const int row0 = i0 + (wi * kWI + a) * 32;
-        store_tile_coalesced<kWJ>(lw, g.out[pset] + jw, g.ldo, row0, g.I, g.J - jw, acc[a], 1.f, lane);
+        for (int a = 0; a < kWI; ++a)
+          pf[set][a] = PTR ? tp.frag(sp, kk, wi * kWI + a) : TP::frag_row(sp + (kk >> 1) * TP::BYTES, rp, wi * kWI + a, kk & 1);
+#pragma unroll
+        for (int b = 0; b < kWJ; ++b)
+          qf[set][b] = QTR ? tq.frag(sq, kk, wj * kWJ + b) : TQ::frag_row(sq + (kk >> 1) * TQ::BYTES, rq, wj * kWJ + b, kk & 1);
+      };
+      // two register sets take turns: the LDS reads of step kk+1 are issued ahead of the products of step kk (the
+      // scheduling barriers keep the compiler from sinking them back to their first use)
+      // (the next tile's loads are issued while the first fragments are on their way from LDS)
+      fetch(0, 0);
+      fetch(1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) {
+#pragma unroll
+        for (int x = 0; x < LOADS; ++x) issue(t + 1, lds0 + (n ^ 1) * BUF, x);
       }
+#pragma unroll
+      for (int kk = 0; kk < kBK / 16; ++kk) {
+        if (kk > 0 && kk + 1 < kBK / 16) fetch((kk + 1) & 1, kk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < kWI; ++a)
+#pragma unroll
+          for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[kk & 1][b], pf[kk & 1][a], acc[a][b]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      dma_wait();  // the next tile has landed
+      if (more) fix_ragged(t + 1, n ^ 1);
+      __syncthreads();
     }
   }
 }
@@ -359,7 +377,11 @@ int dw_splits(int F, int K, int R) {
   }
   return best;
 }
-int pad8(int n) { return (n + 7) & ~7; }
+// Persistent workgroups: 8 XCDs x at most 32 CUs, fewer where an XCD's share of the tiles is smaller.
+int persistent_grid(int tiles) {
+  const int per = (tiles + 7) / 8;
+  return 8 * (per < 32 ? per : 32);
+}
 int bias_chunks(int R) {
   const int c = (R + 63) / 64;
   return c > 256 ? 256 : c;
@@ -396,7 +418,7 @@ hipError_t launch_linear_fwd(int R, int K, int F, long long ldx, long long ldy, 
   g.ldo = ldy;
   g.bias = (const bf16*)bias;
   g.nz = 2;
-  const int grid = pad8(2 * ((R + CfgF::TI - 1) / CfgF::TI) * ((F + CfgF::TJ - 1) / CfgF::TJ));
+  const int grid = persistent_grid(2 * ((R + CfgF::TI - 1) / CfgF::TI) * ((F + CfgF::TJ - 1) / CfgF::TJ));
   hipLaunchKernelGGL((gemm_kernel<false, false, false, CfgF>), dim3(grid), dim3(CfgF::NT), 0, st, g);
   return hipGetLastError();
 }
@@ -419,7 +441,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     g.out[1] = (bf16*)gtx;
     g.ldo = ldx;
     g.nz = 2;
-    const int grid = pad8(2 * ((R + CfgX::TI - 1) / CfgX::TI) * ((K + CfgX::TJ - 1) / CfgX::TJ));
+    const int grid = persistent_grid(2 * ((R + CfgX::TI - 1) / CfgX::TI) * ((K + CfgX::TJ - 1) / CfgX::TJ));
     hipLaunchKernelGGL((gemm_kernel<false, true, false, CfgX>), dim3(grid), dim3(CfgX::NT), 0, st, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -441,7 +463,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     g.part = part;
     g.splits = splits;
     g.nz = splits;
-    const int grid = pad8(splits * ((F + CfgW::TI - 1) / CfgW::TI) * ((K + CfgW::TJ - 1) / CfgW::TJ));
+    const int grid = persistent_grid(splits * ((F + CfgW::TI - 1) / CfgW::TI) * ((K + CfgW::TJ - 1) / CfgW::TJ));
     hipLaunchKernelGGL((gemm_kernel<true, true, true, CfgW>), dim3(grid), dim3(CfgW::NT), 0, st, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
