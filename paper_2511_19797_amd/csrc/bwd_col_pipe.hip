@@ -162,18 +162,10 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pipe_kernel(
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
   bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
-  {
-    // all loads first, then the values: one memory round trip for the four tensors, not one each
-    uint4 w0[NKS], w1[NKS], w2[NKS], w3[NKS];
-    gld_frags_issue<NKS>(w0, k + base, s.sn, j, s.N, s.D, hh);
-    gld_frags_issue<NKS>(w1, tk + base, s.sn, j, s.N, s.D, hh);
-    gld_frags_issue<NKS>(w2, v + base, s.sn, j, s.N, s.D, hh);
-    gld_frags_issue<NKS>(w3, tv + base, s.sn, j, s.N, s.D, hh);
-    gld_frags_finish<NKS>(kf, w0, j, s.N, s.D, hh);
-    gld_frags_finish<NKS>(tkf, w1, j, s.N, s.D, hh);
-    gld_frags_finish<NKS>(vf, w2, j, s.N, s.D, hh);
-    gld_frags_finish<NKS>(tvf, w3, j, s.N, s.D, hh);
-  }
+  gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
+  gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
   PROF_P(11);
   f32x16 aK[NDB], aTK[NDB], aV[NDB], aTV[NDB];
 #pragma unroll

@@ -143,26 +143,15 @@ __global__ __launch_bounds__(kNT, 1) void bwd_row_pipe_kernel(
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
   // rows beyond N: zeros keep everything finite; nothing of theirs is stored
   const long long r = (long long)bh * s.M + (iok ? i : 0);
-  const float lse_r = lse[r], stats_r = stats[r];  // (used below, behind the fragment loads: no wait in between)
+  const float lse2 = iok ? lse[r] * kLog2e : 0.f;
+  const float mub = iok ? stats[r] : 0.f;
   bf16x8 qf[NKS], tqf[NKS], gf[NKS], tgf[NKS], of[NKS], tof[NKS];
-  {
-    // all loads first, then the values: one memory round trip for the six tensors, not one each
-    uint4 w0[NKS], w1[NKS], w2[NKS], w3[NKS], w4[NKS], w5[NKS];
-    if (HAS_G) gld_frags_issue<NKS>(w0, gO + qbase, s.qsn, i, s.M, s.D, hh);
-    gld_frags_issue<NKS>(w1, gTO + qbase, s.qsn, i, s.M, s.D, hh);
-    gld_frags_issue<NKS>(w2, o + qbase, s.qsn, i, s.M, s.D, hh);
-    gld_frags_issue<NKS>(w3, to + qbase, s.qsn, i, s.M, s.D, hh);
-    gld_frags_issue<NKS>(w4, q + qbase, s.qsn, i, s.M, s.D, hh);
-    gld_frags_issue<NKS>(w5, tq + qbase, s.qsn, i, s.M, s.D, hh);
-    if (HAS_G) gld_frags_finish<NKS>(gf, w0, i, s.M, s.D, hh);
-    gld_frags_finish<NKS>(tgf, w1, i, s.M, s.D, hh);
-    gld_frags_finish<NKS>(of, w2, i, s.M, s.D, hh);
-    gld_frags_finish<NKS>(tof, w3, i, s.M, s.D, hh);
-    gld_frags_finish<NKS>(qf, w4, i, s.M, s.D, hh);
-    gld_frags_finish<NKS>(tqf, w5, i, s.M, s.D, hh);
-  }
-  const float lse2 = iok ? lse_r * kLog2e : 0.f;
-  const float mub = iok ? stats_r : 0.f;
+  if (HAS_G) gld_frags<NKS>(gf, gO + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tgf, gTO + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(of, o + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tof, to + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(qf, q + qbase, s.qsn, i, s.M, s.D, hh);
+  gld_frags<NKS>(tqf, tq + qbase, s.qsn, i, s.M, s.D, hh);
   PROF_P(11);
   // Step 1 of App. C, fused: the row scalars delta + Sigma_2 = gO.O + gTO.tO and Sigma_1 = gTO.O of
   // this lane's query, from the same fragment layout (each half-wave holds half of the row), two
