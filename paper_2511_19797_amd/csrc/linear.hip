@@ -149,6 +149,7 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
   // of kGI tile rows, down the group first.  The ~32 workgroups of an XCD are then on a patch of about 8 x 4 tiles at
   // any one time and march through the contraction together: an operand panel comes from HBM once for the tiles of
   // the patch that share it.
+  const bool late = !PARTIAL && wave >= kNW / 2;  // (uniform; waves w and w + 4 share a SIMD; grad W has no registers to spare for it)
   const int total = g.nz * nI * nJ;
   const int per_xcd = (total + 7) >> 3, wg_per_xcd = (int)(gridDim.x >> 3);
   const int id_end = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
@@ -270,9 +271,24 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
         for (int b = 0; b < kWJ; ++b)
           qf[set][b] = QTR ? tq.frag(sq, kk, wj * kWJ + b) : TQ::frag_row(sq + (kk >> 1) * TQ::BYTES, rq, wj * kWJ + b, kk & 1);
       };
-      // two register sets take turns: the LDS reads of step kk+1 are issued ahead of the products of step kk (the
-      // scheduling barriers keep the compiler from sinking them back to their first use)
-      // (the next tile's loads are issued while the first fragments are on their way from LDS)
+      auto products = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < kWI; ++a)
+#pragma unroll
+          for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[set][b], pf[set][a], acc[a][b]);
+      };
+      // Two register sets take turns: the LDS reads of step kk+1 are issued ahead of the products of step kk (the
+      // scheduling barriers keep the compiler from sinking them back to their first use), and the next tile's loads
+      // are issued while the first fragments are on their way from LDS.  The two waves that share a SIMD meet the
+      // per-tile barrier one contraction step apart: the second one (`late`) arrives before its last step, whose
+      // fragments it already holds, so that right behind the barrier the matrix pipe has that step's products to
+      // run while both waves wait for their first fragments of the new tile.
+      static_assert(kBK / 16 == 4, "four contraction steps per tile");
+      auto sync = [&]() {
+        dma_wait();  // the next tile has landed
+        if (more) fix_ragged(t + 1, n ^ 1);
+        __syncthreads();  // it is there for everyone, and nobody reads this tile from LDS any more
+      };
       fetch(0, 0);
       fetch(1, 1);
       __builtin_amdgcn_sched_barrier(0);
@@ -280,19 +296,22 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int x = 0; x < LOADS; ++x) issue(t + 1, lds0 + (n ^ 1) * BUF, x);
       }
-#pragma unroll
-      for (int kk = 0; kk < kBK / 16; ++kk) {
-        if (kk > 0 && kk + 1 < kBK / 16) fetch((kk + 1) & 1, kk + 1);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int a = 0; a < kWI; ++a)
-#pragma unroll
-          for (int b = 0; b < kWJ; ++b) acc[a][b] = mfma(qf[kk & 1][b], pf[kk & 1][a], acc[a][b]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      dma_wait();  // the next tile has landed
-      if (more) fix_ragged(t + 1, n ^ 1);
-      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      products(0);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(0, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      products(1);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(1, 3);
+      __builtin_amdgcn_sched_barrier(0);
+      products(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (late) sync();
+      __builtin_amdgcn_sched_barrier(0);
+      products(1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!late) sync();
     }
   }
 }
