@@ -108,8 +108,8 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
   static_assert(kNW * OUT_REGION <= BUF, "the output staging fits in one stage");
 
   // Writes out the accumulators of output tile (i0, j0) of row set / split zz.  Runs while the first loads of the
-  // workgroup's next tile are on their way into the first stage: bf16 results are staged through the second one.
-  auto write_out = [&](int i0, int j0, int zz) {
+  // workgroup's next tile are on their way into one stage: bf16 results are staged through the other one, `stage`.
+  auto write_out = [&](int i0, int j0, int zz, int stage) {
     const int jw = j0 + wj * (kWJ * 32);  // first output column of this wave
     if (PARTIAL) {
       // float32 partial tile: lane = output row, four consecutive columns per register group
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
           }
       }
     } else {
-      const unsigned lw = lds0 + BUF + (unsigned)wave * OUT_REGION;  // each wave stages its rows through a region of its own
+      const unsigned lw = lds0 + (unsigned)stage * BUF + (unsigned)wave * OUT_REGION;  // each wave stages its rows through a region of its own
       if (jw < g.J) {
 #pragma unroll
         for (int a = 0; a < kWI; ++a) {
@@ -142,8 +142,9 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
     }
   };
 
-  // Persistent workgroups, one per CU, each working through a list of output tiles, so that a tile's results are
-  // written while the next tile's first operands are fetched (and drain to HBM while it is computed).  Hardware
+  // Persistent workgroups, one per CU, each working through a list of output tiles: the next tile's first operands
+  // are requested during the last contraction tile of the current one, and a tile's results are written while they
+  // land (and drain to HBM while the next tile is computed).  Hardware
   // workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own: XCD x owns the x-th eighth of the
   // logical tile ids, which its workgroups take in turn; logical ids walk the tiles of a row set (or split) in groups
   // of kGI tile rows, down the group first.  The ~32 workgroups of an XCD are then on a patch of about 8 x 4 tiles at
@@ -153,111 +154,128 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
   const int total = g.nz * nI * nJ;
   const int per_xcd = (total + 7) >> 3, wg_per_xcd = (int)(gridDim.x >> 3);
   const int id_end = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
-  int prev_i0 = 0, prev_j0 = 0, prev_zz = -1;  // the tile whose results are still in the accumulators (zz < 0: none)
-  for (int wg = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);; wg += wg_per_xcd) {
-    if (wg >= id_end) {
-      if (prev_zz >= 0) write_out(prev_i0, prev_j0, prev_zz);
-      break;
-    }
-    const int zz = wg / (nI * nJ);  // row set (forward, grad x) or split (grad W)
-    const int id = wg - zz * (nI * nJ);
+
+  // An output tile: where it is, its range of contraction tiles, and the per-lane byte offsets of this wave's loads
+  // within an operand tile (whole tiles / a set's last tile)
+  struct Ctx {
+    int i0, j0, zz, t_begin, t_end, pset;
+    typename TP::Offs op_full, op_last;
+    typename TQ::Offs oq_full, oq_last;
+  };
+  auto locate = [&](int wg) {
+    Ctx c;
+    c.zz = wg / (nI * nJ);  // row set (forward, grad x) or split (grad W)
+    const int id = wg - c.zz * (nI * nJ);
     const int grp = id / (kGI * nJ), it_first = grp * kGI, gs = min(nI - it_first, kGI);
     const int rem = id - grp * (kGI * nJ);
     const int jt = rem / gs, it = it_first + (rem - jt * gs);
-    const int i0 = it * kTI, j0 = jt * kTJ;
-    const int t_begin = PARTIAL ? (int)((long long)zz * ntot / g.splits) : 0;
-    const int t_end = PARTIAL ? (int)((long long)(zz + 1) * ntot / g.splits) : ntot;
-    const int pset = PARTIAL ? 0 : zz;
-
-    // per-lane byte offsets of this wave's loads within a tile, worked out once per output tile
-    typename TP::Offs op_full, op_last;
-    typename TQ::Offs oq_full, oq_last;
-    {
-      const unsigned pitchP = (unsigned)(g.ldP * 2), pitchQ = (unsigned)(g.ldQ * 2);
-      const int clast = g.C - (nct - 1) * kBK;  // contraction entries in a set's last tile
-      if (PTR) {
-        const typename TP::Lane l = TP::lane_setup(min(g.I - i0, kTI), wave, lane);  // columns of the stored matrix = output rows
-        op_full = TP::offsets(l, pitchP, kBK);
-        op_last = TP::offsets(l, pitchP, clast);
-      } else {
-        op_full = op_last = TP::offsets(TP::lane_setup(32, wave, lane), pitchP, g.I - i0);
-      }
-      if (QTR) {
-        const typename TQ::Lane l = TQ::lane_setup(min(g.J - j0, kTJ), wave, lane);
-        oq_full = TQ::offsets(l, pitchQ, kBK);
-        oq_last = TQ::offsets(l, pitchQ, clast);
-      } else {
-        oq_full = oq_last = TQ::offsets(TQ::lane_setup(32, wave, lane), pitchQ, g.J - j0);
-      }
+    c.i0 = it * kTI;
+    c.j0 = jt * kTJ;
+    c.t_begin = PARTIAL ? (int)((long long)c.zz * ntot / g.splits) : 0;
+    c.t_end = PARTIAL ? (int)((long long)(c.zz + 1) * ntot / g.splits) : ntot;
+    c.pset = PARTIAL ? 0 : c.zz;
+    const unsigned pitchP = (unsigned)(g.ldP * 2), pitchQ = (unsigned)(g.ldQ * 2);
+    const int clast = g.C - (nct - 1) * kBK;  // contraction entries in a set's last tile
+    if (PTR) {
+      const typename TP::Lane l = TP::lane_setup(min(g.I - c.i0, kTI), wave, lane);  // columns of the stored matrix = output rows
+      c.op_full = TP::offsets(l, pitchP, kBK);
+      c.op_last = TP::offsets(l, pitchP, clast);
+    } else {
+      c.op_full = c.op_last = TP::offsets(TP::lane_setup(32, wave, lane), pitchP, g.I - c.i0);
     }
-    // wave-load number x (compile-time, 0 .. LOADS-1) of contraction tile t into the stage at `buf`
-    auto issue = [&](int t, unsigned buf, int x) {
-      const int set = t / nct, ct = t - set * nct;
-      const long long c0 = (long long)ct * kBK;
-      const bool last = ct == nct - 1;
-      const bf16* pb = g.P[PARTIAL ? set : pset] + (PTR ? c0 * g.ldP + i0 : (long long)i0 * g.ldP + c0);
-      const bf16* qb = g.Q[PARTIAL ? set : 0] + (QTR ? c0 * g.ldQ + j0 : (long long)j0 * g.ldQ + c0);
-      // (row access: the contraction length is a multiple of 32, so the second half of a set's last tile is either
-      // whole or absent; an absent half fetches the first half again, and its fragments are zeroed on the P side)
-      const int half2 = (last && g.C - (int)c0 <= 32) ? 0 : 32;
-      constexpr int NP = (PTR ? 1 : 2) * TP::IPW;
-      if (x < NP) {
-        if (PTR) TP::issue_at(last ? op_last.o[x] : op_full.o[x], x, pb, buf, wave);
-        else if (x < TP::IPW) TP::issue_at(op_full.o[x], x, pb, buf, wave);
-        else TP::issue_at(op_full.o[x - TP::IPW], x - TP::IPW, pb + half2, buf + TP::BYTES, wave);
-      } else {
-        const int y = x - NP;
-        if (QTR) TQ::issue_at(last ? oq_last.o[y] : oq_full.o[y], y, qb, buf + P_BYTES, wave);
-        else if (y < TQ::IPW) TQ::issue_at(oq_full.o[y], y, qb, buf + P_BYTES, wave);
-        else TQ::issue_at(oq_full.o[y - TQ::IPW], y - TQ::IPW, qb + half2, buf + P_BYTES + TQ::BYTES, wave);
-      }
-    };
-    // A ragged last contraction tile of a set: entries beyond the set's end were fetched as copies of valid ones (the
-    // set's last row, or the first half of the tile); on the P side each wave overwrites with zeros what it fetched of
-    // them (call this once its own loads have landed), so that those entries contribute nothing.
-    auto fix_ragged = [&](int t, int n) {
-      const int ct = t % nct;
-      const int cvalid = ct == nct - 1 ? g.C - ct * kBK : kBK;
-      if (cvalid < kBK) {
-        char* pt = lds + n * BUF;
+    if (QTR) {
+      const typename TQ::Lane l = TQ::lane_setup(min(g.J - c.j0, kTJ), wave, lane);
+      c.oq_full = TQ::offsets(l, pitchQ, kBK);
+      c.oq_last = TQ::offsets(l, pitchQ, clast);
+    } else {
+      c.oq_full = c.oq_last = TQ::offsets(TQ::lane_setup(32, wave, lane), pitchQ, g.J - c.j0);
+    }
+    return c;
+  };
+  // wave-load number x (compile-time, 0 .. LOADS-1) of contraction tile t of output tile c into the stage at `buf`
+  auto issue = [&](const Ctx& c, int t, unsigned buf, int x) {
+    const int set = t / nct, ct = t - set * nct;
+    const long long c0 = (long long)ct * kBK;
+    const bool last = ct == nct - 1;
+    const bf16* pb = g.P[PARTIAL ? set : c.pset] + (PTR ? c0 * g.ldP + c.i0 : (long long)c.i0 * g.ldP + c0);
+    const bf16* qb = g.Q[PARTIAL ? set : 0] + (QTR ? c0 * g.ldQ + c.j0 : (long long)c.j0 * g.ldQ + c0);
+    // (row access: the contraction length is a multiple of 32, so the second half of a set's last tile is either
+    // whole or absent; an absent half fetches the first half again, and its fragments are zeroed on the P side)
+    const int half2 = (last && g.C - (int)c0 <= 32) ? 0 : 32;
+    constexpr int NP = (PTR ? 1 : 2) * TP::IPW;
+    if (x < NP) {
+      if (PTR) TP::issue_at(last ? c.op_last.o[x] : c.op_full.o[x], x, pb, buf, wave);
+      else if (x < TP::IPW) TP::issue_at(c.op_full.o[x], x, pb, buf, wave);
+      else TP::issue_at(c.op_full.o[x - TP::IPW], x - TP::IPW, pb + half2, buf + TP::BYTES, wave);
+    } else {
+      const int y = x - NP;
+      if (QTR) TQ::issue_at(last ? c.oq_last.o[y] : c.oq_full.o[y], y, qb, buf + P_BYTES, wave);
+      else if (y < TQ::IPW) TQ::issue_at(c.oq_full.o[y], y, qb, buf + P_BYTES, wave);
+      else TQ::issue_at(c.oq_full.o[y - TQ::IPW], y - TQ::IPW, qb + half2, buf + P_BYTES + TQ::BYTES, wave);
+    }
+  };
+  // A ragged last contraction tile of a set: entries beyond the set's end were fetched as copies of valid ones (the
+  // set's last row, or the first half of the tile); on the P side each wave overwrites with zeros what it fetched of
+  // them (call this once its own loads have landed), so that those entries contribute nothing.
+  auto fix_ragged = [&](int t, int n) {
+    const int ct = t % nct;
+    const int cvalid = ct == nct - 1 ? g.C - ct * kBK : kBK;
+    if (cvalid < kBK) {
+      char* pt = lds + n * BUF;
 #pragma unroll
-        for (int x = 0; x < TP::IPW; ++x) {
-          const int pos = (wave + x * kNW) * 64 + lane;  // chunk of the tile this lane fetched with wave-load x
-          if (PTR) {
-            if (pos / TP::PCH >= cvalid) *reinterpret_cast<uint4*>(pt + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
-          } else if (cvalid <= 32) {
-            *reinterpret_cast<uint4*>(pt + TP::BYTES + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
-          }
+      for (int x = 0; x < TP::IPW; ++x) {
+        const int pos = (wave + x * kNW) * 64 + lane;  // chunk of the tile this lane fetched with wave-load x
+        if (PTR) {
+          if (pos / TP::PCH >= cvalid) *reinterpret_cast<uint4*>(pt + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
+        } else if (cvalid <= 32) {
+          *reinterpret_cast<uint4*>(pt + TP::BYTES + pos * 16) = make_uint4(0u, 0u, 0u, 0u);
         }
       }
-    };
+    }
+  };
 
-    // The tile before ended with a barrier: both stages are free.  This tile's first loads go out, then the results of
-    // the tile before leave (through the second stage), then the accumulators start from the bias (row set 0; the
-    // tangent has none) or from zero.
+  int wg = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (wg >= id_end) return;  // (the grid is never larger than the tiles need, but an XCD's share may be short)
+  Ctx cur = locate(wg);
+  int n0 = 0;  // the stage that holds (or is receiving) the first contraction tile of `cur`
 #pragma unroll
-    for (int x = 0; x < LOADS; ++x) issue(t_begin, lds0, x);
-    if (prev_zz >= 0) write_out(prev_i0, prev_j0, prev_zz);
-    prev_i0 = i0;
-    prev_j0 = j0;
-    prev_zz = zz;
+  for (int x = 0; x < LOADS; ++x) issue(cur, cur.t_begin, lds0, x);
+  int prev_i0 = 0, prev_j0 = 0, prev_zz = -1;  // the tile whose results are still in the accumulators (zz < 0: none)
+  for (;;) {
+    // The first contraction tile of `cur` is on its way into stage n0 (requested during the last contraction tile of
+    // the output tile before, or just now for the workgroup's first one); the other stage is free.  In this order: the
+    // bias values are requested; the wait for the loads in flight; the results of the tile before leave through the
+    // free stage (their stores are not waited for here: the next wait comes a contraction tile later); the
+    // accumulators start from the bias (row set 0; the tangent has none) or from zero.
+    float bv[kWJ][16];
     {
-      const bool with_bias = !PARTIAL && g.bias != nullptr && pset == 0;
-      const int jw = j0 + wj * (kWJ * 32);
+      const bool with_bias = !PARTIAL && g.bias != nullptr && cur.pset == 0;
+      const int jw = cur.j0 + wj * (kWJ * 32);
 #pragma unroll
       for (int b = 0; b < kWJ; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = jw + b * 32 + drow(r, hh);
-          const float bv = with_bias && j < g.J ? (float)g.bias[j] : 0.f;
-#pragma unroll
-          for (int a = 0; a < kWI; ++a) acc[a][b][r] = bv;
+          bv[b][r] = with_bias && j < g.J ? (float)g.bias[j] : 0.f;
         }
     }
     dma_wait();
-    fix_ragged(t_begin, 0);
+    fix_ragged(cur.t_begin, n0);
+    if (prev_zz >= 0) write_out(prev_i0, prev_j0, prev_zz, n0 ^ 1);
+    prev_i0 = cur.i0;
+    prev_j0 = cur.j0;
+    prev_zz = cur.zz;
+#pragma unroll
+    for (int b = 0; b < kWJ; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+#pragma unroll
+        for (int a = 0; a < kWI; ++a) acc[a][b][r] = bv[b][r];
     __syncthreads();  // the first contraction tile is there for everyone; everyone's staging reads are over
-    for (int t = t_begin, n = 0; t < t_end; ++t, n ^= 1) {
+    const bool has_next = wg + wg_per_xcd < id_end;  // uniform
+    const int t_begin = cur.t_begin, t_end = cur.t_end;
+    int n = n0;
+    for (int t = t_begin; t < t_end; ++t, n ^= 1) {
       // tile t is there for everyone and everyone is done with tile t-1, whose stage is refilled now
       const bool more = t + 1 < t_end;  // uniform
       const char* sp = lds + n * BUF;
@@ -285,8 +303,10 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
       // run while both waves wait for their first fragments of the new tile.
       static_assert(kBK / 16 == 4, "four contraction steps per tile");
       auto sync = [&]() {
-        dma_wait();  // the next tile has landed
-        if (more) fix_ragged(t + 1, n ^ 1);
+        if (more) {
+          dma_wait();  // the next tile has landed
+          fix_ragged(t + 1, n ^ 1);
+        }  // (behind an output tile's last contraction tile the loads in flight are the next output tile's: not waited for here)
         __syncthreads();  // it is there for everyone, and nobody reads this tile from LDS any more
       };
       fetch(0, 0);
@@ -294,7 +314,13 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
       __builtin_amdgcn_sched_barrier(0);
       if (more) {
 #pragma unroll
-        for (int x = 0; x < LOADS; ++x) issue(t + 1, lds0 + (n ^ 1) * BUF, x);
+        for (int x = 0; x < LOADS; ++x) issue(cur, t + 1, lds0 + (n ^ 1) * BUF, x);
+      } else if (has_next) {
+        // the workgroup's next output tile: its first operands are requested now, a contraction tile ahead of the
+        // results of this one, into the stage that this tile no longer uses
+        const Ctx nx = locate(wg + wg_per_xcd);
+#pragma unroll
+        for (int x = 0; x < LOADS; ++x) issue(nx, nx.t_begin, lds0 + (n ^ 1) * BUF, x);
       }
       __builtin_amdgcn_sched_barrier(0);
       products(0);
@@ -313,6 +339,14 @@ __global__ __launch_bounds__(C::NT, C::OCC) void gemm_kernel(GemmArgs g) {
       __builtin_amdgcn_sched_barrier(0);
       if (!late) sync();
     }
+    // n: the stage behind the one computed from last, i.e. where the next output tile's first operands are landing
+    if (!has_next) {
+      write_out(prev_i0, prev_j0, prev_zz, n ^ 1);
+      break;
+    }
+    wg += wg_per_xcd;
+    cur = locate(wg);  // (worked out again rather than kept in registers through the loop)
+    n0 = n;
   }
 }
 
