@@ -57,8 +57,8 @@ def test_captured_step_replays_bit_for_bit(B, H, N, d, dtype):
 
 
 def test_captured_block_pieces_replay_bit_for_bit():
-    """The pointwise entry points of the block (AdaLN modulation, QK-norm, the fused attention + QK-norm backward,
-    gate, activation) in one captured graph, forward pieces and backward pieces."""
+    """The entry points of the block (AdaLN modulation, QK-norm, the fused attention + QK-norm backward, gate,
+    activation, a linear layer) in one captured graph, forward pieces and backward pieces."""
     announce("graph capture of the pointwise entry points")
     B, T, C, H, d, eps = 2, 130, 576, 8, 72, 1e-6
     a = {n: t.cuda() for n, t in wl.make_adaln_inputs(B, T, C, "bf16", 11).items()}
@@ -67,7 +67,8 @@ def test_captured_block_pieces_replay_bit_for_bit():
     w = wl.custom(B, H, T, d, "bf16")
     q = {n: t.cuda() for n, t in wl.make_inputs(w, 14).items()}
     gq, gk = [t.cuda() for t in wl.make_gains(w, 15)]
-    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    lin = {n: t.cuda() for n, t in wl.make_linear_inputs(B * T, C, 3 * C, "bf16", 16).items()}
+    ws = torch.empty(max(1 << 24, tvm.tvmattn_linear_jvp_bwd_workspace_bytes(lin["x"], lin["w"])), dtype=torch.uint8, device="cuda")
 
     def calls(out):
         """out: None (eager, the binding allocates) or the list of output tuples to write into."""
@@ -87,6 +88,8 @@ def test_captured_block_pieces_replay_bit_for_bit():
         res.append(f4)
         res.append(tvm.tvmattn_jvp_bwd_qknorm(q["q"], q["tq"], q["k"], q["tk"], gq, gk, eps, *n4, q["v"], q["tv"], *f4,
                                               q["gO"], q["gTO"], out=nxt(), workspace=ws))
+        res.append(tvm.tvmattn_linear_jvp_fwd(lin["x"], lin["tx"], lin["w"], lin["b"], out=nxt()))
+        res.append(tvm.tvmattn_linear_jvp_bwd(lin["x"], lin["tx"], lin["w"], lin["gy"], lin["gty"], out=nxt(), workspace=ws))
         return res
 
     ref = calls(None)
