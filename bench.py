@@ -380,6 +380,21 @@ def qknorm(w, steps, seed=2024):
         out["attention_bwd_then_norm_bwd"] = {"ms": timed(two_calls)}
         out["attention_bwd_with_norm_bwd_fused"] = {"ms": timed(lambda: tvm.tvmattn_jvp_bwd_qknorm(
             q, tq, k, tk, gq, gk, 1e-6, qn, tqn, kn, tkn, v, tv, o, to, lse, stats, gO, gTO, out=f8, workspace=fws))}
+    # the forward likewise: norm then attention as two calls, and as the one call that normalises the query side
+    # where the attention kernel loads its query rows (where the matrix-core forward is served)
+    if w.dtype == "bf16" and w.d % 8 == 0 and w.d <= 128:
+        v, tv = dev["v"], dev["tv"]
+        rows = lambda: torch.empty((w.B, w.H, w.Mq), dtype=torch.float32, device="cuda")
+        f4 = (torch.empty_like(q), torch.empty_like(q), rows(), rows())
+        f8b = tuple(torch.empty_like(t) for t in (q, q, k, k, q, q)) + (rows(), rows())
+
+        def two_fwd_calls():
+            n4 = tvm.tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gq, gk, 1e-6, out=fo)
+            tvm.tvmattn_jvp_fwd(n4[0], n4[2], v, n4[1], n4[3], tv, out=f4)
+
+        out["norm_fwd_then_attention_fwd"] = {"ms": timed(two_fwd_calls)}
+        out["attention_fwd_with_query_norm_fused"] = {"ms": timed(lambda: tvm.tvmattn_jvp_fwd_qknorm(
+            q, tq, k, tk, gq, gk, 1e-6, v, tv, out=f8b))}
     return out
 
 

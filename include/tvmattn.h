@@ -233,6 +233,31 @@ int tvmattn_qknorm_jvp_bwd(const tvmattn_desc* desc,
                            void* hip_stream);
 
 /*
+ * tvmattn_qknorm_jvp_fwd and tvmattn_jvp_fwd in one call (Sec. "Semi-Lipschitz control": RMSNorm with a learnable
+ * gain on q and k right before the attention; App. C for the attention and its tangent).  The key side goes through
+ * the normalisation kernel; the query side is normalised inside the attention forward, where each wave loads its
+ * query rows as fragments, so the forward reads the rows as they were before the norm and the normalised query rows
+ * are only written, not read back.
+ *   in : q, tq, k, tk, gain_q, gain_k, eps   as for tvmattn_qknorm_jvp_fwd
+ *        v, tv                               as for tvmattn_jvp_fwd
+ *   out: qn, tqn, kn, tkn                    the normalised rows and their tangents (the backward needs them:
+ *                                            give them to tvmattn_jvp_bwd_qknorm or tvmattn_jvp_bwd)
+ *        o, to, lse, stats                   as from tvmattn_jvp_fwd on (qn, kn, v, tqn, tkn, tv); lse and stats both
+ *                                            NULL: nothing is saved
+ * The normalised rows are rounded to dtype before the products use them, as when the two calls are made one after
+ * the other; the results agree with those to rounding (the order of the float32 operations differs).
+ * Served by the matrix-core forward only: bfloat16, D a multiple of 8, D <= 128; anything else returns
+ * TVMATTN_UNSUPPORTED: make the two calls there.  Two launches, no workspace.
+ */
+int tvmattn_jvp_fwd_qknorm(const tvmattn_desc* desc,
+                           const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps,
+                           const void* v, const void* tv,
+                           void* qn, void* tqn, void* kn, void* tkn,
+                           void* o, void* to, float* lse, float* stats,
+                           void* hip_stream);
+
+/*
  * tvmattn_jvp_bwd and tvmattn_qknorm_jvp_bwd in one call, for attention whose q, tq, k, tk came out of
  * tvmattn_qknorm_jvp_fwd: the backward of the normalisation runs in the epilogues of the attention's two
  * backward kernels (each has the rows of one side in registers when it ends), so the gradients with respect to the

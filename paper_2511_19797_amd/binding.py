@@ -60,6 +60,8 @@ def lib():
         L.tvmattn_jvp_bwd_static.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 19
         L.tvmattn_qknorm_jvp_fwd.restype = ctypes.c_int
         L.tvmattn_qknorm_jvp_fwd.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 5
+        L.tvmattn_jvp_fwd_qknorm.restype = ctypes.c_int
+        L.tvmattn_jvp_fwd_qknorm.argtypes = [ctypes.POINTER(tvmattn_desc)] + [_P] * 6 + [ctypes.c_float] + [_P] * 11
         L.tvmattn_qknorm_jvp_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.tvmattn_qknorm_jvp_bwd_workspace_bytes.argtypes = [ctypes.POINTER(tvmattn_desc)]
         L.tvmattn_qknorm_jvp_bwd.restype = ctypes.c_int
@@ -251,6 +253,29 @@ def tvmattn_qknorm_jvp_fwd(q, tq, k, tk, gain_q, gain_k, eps, out=None):
     _check(lib().tvmattn_qknorm_jvp_fwd(ctypes.byref(desc), q.data_ptr(), tq.data_ptr(), k.data_ptr(), tk.data_ptr(),
                                         gain_q.data_ptr(), gain_k.data_ptr(), float(eps), out[0].data_ptr(),
                                         out[1].data_ptr(), out[2].data_ptr(), out[3].data_ptr(), _stream()))
+    return out
+
+
+def tvmattn_jvp_fwd_qknorm(q, tq, k, tk, gain_q, gain_k, eps, v, tv, scale=0.0, out=None, save=True):
+    """The QK-norm and the attention forward in one call (the query side is normalised inside the attention kernel).
+    Returns (qn, tqn, kn, tkn, o, to, lse, stats); `out`, if given, is that tuple of preallocated tensors.
+    Raises TvmattnError (unsupported) for what the matrix-core forward does not take: make the two calls there."""
+    _same_layout(q, tq)
+    _same_layout(k, tk, v, tv)
+    _gain_ok(gain_q, q)
+    _gain_ok(gain_k, k)
+    desc = make_desc(k, scale, q)
+    B, H, M, _ = q.shape
+    if out is None:
+        rows = lambda: torch.empty((B, H, M), dtype=torch.float32, device=q.device) if save else None
+        out = (_like(q), _like(q), _like(k), _like(k), _like(q), _like(q), rows(), rows())
+    else:
+        _same_layout(q, out[0], out[1], out[4], out[5])
+        _same_layout(k, out[2], out[3])
+    _check(lib().tvmattn_jvp_fwd_qknorm(ctypes.byref(desc), q.data_ptr(), tq.data_ptr(), k.data_ptr(), tk.data_ptr(),
+                                        gain_q.data_ptr(), gain_k.data_ptr(), float(eps), v.data_ptr(), tv.data_ptr(),
+                                        out[0].data_ptr(), out[1].data_ptr(), out[2].data_ptr(), out[3].data_ptr(),
+                                        out[4].data_ptr(), out[5].data_ptr(), _ptr(out[6]), _ptr(out[7]), _stream()))
     return out
 
 

@@ -20,6 +20,7 @@ COMMON = [
 # pressure sends the compiler's AGPR rewrite pass astray (more spills, 2 % slower).
 PER_FILE = {
     "fwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "fwd_mfma_qnorm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "bwd_mfma_onesided1.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     # hand-ordered instruction stream: source order must survive to the ISA
     "bwd_row_pipe.hip": ["-mllvm", "-enable-misched=false"],

@@ -33,6 +33,14 @@
 #define FWD_NW 4   // waves per workgroup (two workgroups share a CU)
 #define FWD_BN 32  // keys per LDS tile (one 32-key block)
 #endif
+// A second translation unit builds the same kernels with the query side's RMSNorm folded in (fwd_mfma_qnorm.hip):
+// q, tq are then the rows before the normalisation, and each wave normalises its 32 rows where it loads them as
+// fragments (RMSNorm with gain and its tangent: Sec. "Semi-Lipschitz control"; App. "Lipschitzness of RMSNorm"),
+// writes the normalised rows out for the backward, and goes on as usual.
+#ifndef TVM_FWD_QNORM
+#define TVM_FWD_QNORM 0
+#define TVM_FWD_LAUNCHER launch_fwd_mfma
+#endif
 
 namespace tvm {
 namespace {
@@ -46,7 +54,9 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
                                                           const bf16* __restrict__ tq, const bf16* __restrict__ tk,
                                                           const bf16* __restrict__ tv, bf16* __restrict__ o,
                                                           bf16* __restrict__ to, float* __restrict__ lse,
-                                                          float* __restrict__ stats) {
+                                                          float* __restrict__ stats, const float* __restrict__ ngain,
+                                                          float neps, bf16* __restrict__ qn, bf16* __restrict__ tqn) {
+  constexpr bool QNORM = TVM_FWD_QNORM != 0;
   constexpr int NT = 64 * NW, BM = 32 * NW;
   using TK = Tile<kBN, DK / 8, NW>;
   using TV = Tile<kBN, DV / 8, NW>;
@@ -115,6 +125,49 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void fwd_mfma_kernel(Shap
     gld_frags_issue<NKS>(w1, tq + qbase, s.qsn, i, s.M, s.D, hh);
     gld_frags_finish<NKS>(qf, w0, i, s.M, s.D, hh);
     gld_frags_finish<NKS>(tqf, w1, i, s.M, s.D, hh);
+  }
+  if (QNORM) {
+    // This lane holds half of row i (chunks 2kk + hh; zeros beyond D and beyond M), the lane 32 away the other half.
+    // With r = 1/sqrt(mean(x^2) + eps) and mu = mean(x tx):  y = g x r,  ty = g (tx r - x r^3 mu), rounded to bf16
+    // like the rows a separate normalisation would have stored; the rounded values are what the products use and
+    // what is written out.
+    float ss = 0.f, st = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NKS; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = (float)qf[kk][e], t = (float)tqf[kk][e];
+        ss = fmaf(x, x, ss);
+        st = fmaf(x, t, st);
+      }
+    ss += xhalf(ss);
+    st += xhalf(st);
+    const float invd = 1.f / (float)s.D;
+    const float r = 1.f / sqrtf(fmaf(ss, invd, neps));
+    const float r3mu = r * r * r * (st * invd);
+    const long long rowoff = qbase + (long long)(iok ? i : 0) * s.qsn;
+#pragma unroll
+    for (int kk = 0; kk < NKS; ++kk) {
+      const int c0 = kk * 16 + hh * 8;
+      if (c0 < s.D) {  // (D is a multiple of 8: a chunk is in range as a whole)
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        const f32x4 g0 = *reinterpret_cast<const f32x4*>(ngain + c0), g1 = *reinterpret_cast<const f32x4*>(ngain + c0 + 4);
+        bf16x8 y, ty;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float g = e < 4 ? g0[e] : g1[e - 4];
+          const float x = (float)qf[kk][e], t = (float)tqf[kk][e];
+          y[e] = (bf16)(g * x * r);
+          ty[e] = (bf16)(g * fmaf(t, r, -x * r3mu));
+        }
+        qf[kk] = y;
+        tqf[kk] = ty;
+        if (iok) {
+          *reinterpret_cast<bf16x8*>(qn + rowoff + c0) = y;
+          *reinterpret_cast<bf16x8*>(tqn + rowoff + c0) = ty;
+        }
+      }
+    }
   }
 
   f32x16 accO[NDB], accT[NDB];
@@ -282,10 +335,10 @@ hipError_t launch_nw(const Shape& s, const FwdArgs& a, hipStream_t st) {
              *tk = (const bf16*)a.tk, *tv = (const bf16*)a.tv;
   if (s.D < DV)  // a spare column in the output tiles carries the row sums
     hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN, true>), grid, block, 0, st, s, q, k, v, tq, tk, tv, (bf16*)a.o,
-                       (bf16*)a.to, a.lse, a.stats);
+                       (bf16*)a.to, a.lse, a.stats, a.ngq, a.neps, (bf16*)a.qn, (bf16*)a.tqn);
   else if constexpr (DK == DV)
     hipLaunchKernelGGL((fwd_mfma_kernel<DK, DV, NW, BN, false>), grid, block, 0, st, s, q, k, v, tq, tk, tv, (bf16*)a.o,
-                       (bf16*)a.to, a.lse, a.stats);
+                       (bf16*)a.to, a.lse, a.stats, a.ngq, a.neps, (bf16*)a.qn, (bf16*)a.tqn);
   else
     return hipErrorNotSupported;  // D <= DK < DV: not reached
   return hipGetLastError();
@@ -305,7 +358,7 @@ hipError_t launch(const Shape& s, const FwdArgs& a, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st) {
+hipError_t TVM_FWD_LAUNCHER(const Shape& s, const FwdArgs& a, hipStream_t st) {
   switch ((s.D + 15) / 16 * 16) {
     case 16: return launch<16, 32>(s, a, st);
     case 32: return launch<32, 32>(s, a, st);

@@ -39,6 +39,11 @@ struct FwdArgs {
   const void *q, *k, *v, *tq, *tk, *tv;
   void *o, *to;
   float *lse, *stats;
+  // forward with the query side's normalisation folded in (launch_fwd_mfma_qnorm only): q, tq are the rows before the
+  // norm; the gain, eps, and where the normalised rows go
+  const float* ngq = nullptr;
+  float neps = 0.f;
+  void *qn = nullptr, *tqn = nullptr;
 };
 struct BwdArgs {
   const void *q, *k, *v, *tq, *tk, *tv, *o, *to;
@@ -65,6 +70,7 @@ hipError_t launch_bwd_row_generic(const Shape& s, int dtype, const BwdArgs& a, h
 // bf16 matrix-core paths; `supported` says whether the shape is one they take.
 bool mfma_supported(const Shape& s, int dtype);
 hipError_t launch_fwd_mfma(const Shape& s, const FwdArgs& a, hipStream_t st);
+hipError_t launch_fwd_mfma_qnorm(const Shape& s, const FwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t st);  // a.mode 1 or 2, any head dim

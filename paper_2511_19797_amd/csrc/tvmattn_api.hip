@@ -168,7 +168,7 @@ inline bool plain_alu(const tvmattn_desc* d) { return (d->flags & TVMATTN_FLAG_P
 
 extern "C" {
 
-int tvmattn_version(void) { return 600; }  // 0.6.0: per-call flags instead of process-wide switches, tvmattn_jvp_bwd_timed, tvmattn_jvp_bwd_static, linear layers; 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
+int tvmattn_version(void) { return 610; }  // 0.6.1: tvmattn_jvp_fwd_qknorm; 0.6.0: per-call flags instead of process-wide switches, tvmattn_jvp_bwd_timed, tvmattn_jvp_bwd_static, linear layers; 0.5.0: AdaLN modulation, residual gate, MLP activation; 0.4.0: QK-norm entry points; 0.3.0: M != N (the descriptor grew); 0.2.0: one-sided backward, forward that saves nothing
 
 const char* tvmattn_strerror(int status) {
   switch (status) {
@@ -375,6 +375,47 @@ int tvmattn_qknorm_jvp_fwd(const tvmattn_desc* desc, const void* q, const void* 
   a.side[1].y = kn;
   a.side[1].ty = tkn;
   const hipError_t e = tvm::launch_qknorm_fwd(a, desc->dtype, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
+}
+
+int tvmattn_jvp_fwd_qknorm(const tvmattn_desc* desc, const void* q, const void* tq, const void* k, const void* tk,
+                           const float* gain_q, const float* gain_k, float eps, const void* v, const void* tv, void* qn,
+                           void* tqn, void* kn, void* tkn, void* o, void* to, float* lse, float* stats,
+                           void* hip_stream) {
+  tvm::Shape s;
+  int rc = resolve(desc, &s);
+  if (rc) return rc;
+  if (!(eps >= 0.f) || isinf(eps)) return TVMATTN_INVALID_ARG;
+  if ((lse == nullptr) != (stats == nullptr)) return TVMATTN_INVALID_ARG;  // saved together or not at all
+  if (plain_alu(desc) || !tvm::mfma_supported(s, desc->dtype)) return TVMATTN_UNSUPPORTED;
+  const bool nosave = lse == nullptr;
+  const long long esz = esz_of(desc->dtype), gb = (long long)s.D * 4, rvb = (long long)s.B * s.H * s.M * 4;
+  auto qs = [&](const void* p) { return side_buf(p, s, true, esz); };
+  auto ks = [&](const void* p) { return side_buf(p, s, false, esz); };
+  const Buf in[] = {qs(q), qs(tq), ks(k), ks(tk), plain(gain_q, gb), plain(gain_k, gb), ks(v), ks(tv)};
+  const Buf out[] = {qs(qn), qs(tqn), ks(kn), ks(tkn), qs(o), qs(to), unless(nosave, plain(lse, rvb)),
+                     unless(nosave, plain(stats, rvb))};
+  rc = check_bufs(in, out);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the key side through the normalisation kernel (no workgroups for the query side) ...
+  tvm::NormArgs n{};
+  norm_sides(s, &n, eps);
+  n.side[0].nwg = 0;
+  n.side[1].x = k;
+  n.side[1].tx = tk;
+  n.side[1].g = gain_k;
+  n.side[1].y = kn;
+  n.side[1].ty = tkn;
+  hipError_t e = tvm::launch_qknorm_fwd(n, desc->dtype, st);
+  if (e != hipSuccess) return TVMATTN_LAUNCH_FAILED;
+  // ... the query side inside the attention forward, which leaves the normalised rows behind for the backward
+  tvm::FwdArgs a{q, kn, v, tq, tkn, tv, o, to, lse, stats};
+  a.ngq = gain_q;
+  a.neps = eps;
+  a.qn = qn;
+  a.tqn = tqn;
+  e = tvm::launch_fwd_mfma_qnorm(s, a, st);
   return e == hipSuccess ? TVMATTN_OK : TVMATTN_LAUNCH_FAILED;
 }
 

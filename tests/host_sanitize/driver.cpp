@@ -50,6 +50,28 @@ int main() {
           (void)tvmattn_jvp_fwd(&e, P(G), P(2 * G), P(3 * G), P(4 * G), P(5 * G), P(6 * G), P(7 * G), P(8 * G), (float*)P(9 * G),
                                 (float*)P(10 * G), nullptr);
         }
+  // ---- norm + forward in one call: a valid call is two launches; the same extreme descriptors
+  {
+    const int before = g_stub_launches;
+    EXPECT(tvmattn_jvp_fwd_qknorm(&d, P(G), P(2 * G), P(3 * G), P(4 * G), (const float*)P(5 * G), (const float*)P(6 * G), 1e-6f,
+                                  P(7 * G), P(8 * G), P(9 * G), P(10 * G), P(11 * G), P(12 * G), P(13 * G), P(14 * G),
+                                  (float*)P(15 * G), (float*)P(16 * G), nullptr) == TVMATTN_OK);
+    EXPECT(g_stub_launches == before + 2);
+    EXPECT(tvmattn_jvp_fwd_qknorm(&d, P(G), P(2 * G), P(3 * G), P(4 * G), (const float*)P(5 * G), (const float*)P(6 * G), 1e-6f,
+                                  P(7 * G), P(8 * G), P(9 * G), P(10 * G), P(11 * G), P(3 * G + 32), P(13 * G), P(14 * G),
+                                  (float*)P(15 * G), (float*)P(16 * G), nullptr) == TVMATTN_INVALID_ARG);  // tkn inside k
+    for (int B : {1, 65535, INT32_MAX})
+      for (int N : {1, 4096, INT32_MAX})
+        for (int D : {8, 128, 136, INT32_MAX})
+          for (int64_t st : {(int64_t)0, (int64_t)8, (int64_t)1 << 40, INT64_MAX / 4}) {
+            tvmattn_desc e = mk(B, 16, N, D);
+            e.stride_b = st; e.stride_h = st; e.stride_n = st;
+            e.M = N / 2;
+            (void)tvmattn_jvp_fwd_qknorm(&e, P(G), P(2 * G), P(3 * G), P(4 * G), (const float*)P(5 * G), (const float*)P(6 * G),
+                                         1e-6f, P(7 * G), P(8 * G), P(9 * G), P(10 * G), P(11 * G), P(12 * G), P(13 * G),
+                                         P(14 * G), (float*)P(15 * G), (float*)P(16 * G), nullptr);
+          }
+  }
   // ---- backward: workspace contract, one-sided calls, the timed variant
   const size_t need = tvmattn_jvp_bwd_workspace_bytes(&d);
   EXPECT(need >= 3u * 2 * 3 * 100 * 4 && need % 256 == 0);

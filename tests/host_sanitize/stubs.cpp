@@ -12,6 +12,7 @@ STUB(launch_bwd_pre(const Shape&, int, const BwdArgs&, hipStream_t))
 STUB(launch_bwd_col_generic(const Shape&, int, const BwdArgs&, hipStream_t))
 STUB(launch_bwd_row_generic(const Shape&, int, const BwdArgs&, hipStream_t))
 STUB(launch_fwd_mfma(const Shape&, const FwdArgs&, hipStream_t))
+STUB(launch_fwd_mfma_qnorm(const Shape&, const FwdArgs&, hipStream_t))
 STUB(launch_bwd_col_mfma(const Shape&, const BwdArgs&, hipStream_t))
 STUB(launch_bwd_row_mfma(const Shape&, const BwdArgs&, hipStream_t))
 STUB(launch_bwd_row_pipe_qknorm(const Shape&, const BwdArgs&, hipStream_t))

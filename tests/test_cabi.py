@@ -189,6 +189,38 @@ def test_qknorm_argument_rules(L):
     assert bwd(b_in, p) == -1
 
 
+def test_fused_forward_argument_rules(L):
+    """tvmattn_jvp_fwd_qknorm validates before anything is launched: no call here is a valid one (every pointer is
+    fake), and each returns from the checks."""
+    L.tvmattn_jvp_fwd_qknorm.argtypes = [ctypes.POINTER(binding.tvmattn_desc)] + [ctypes.c_void_p] * 6 + \
+        [ctypes.c_float] + [ctypes.c_void_p] * 11
+    d = desc(B=2, H=3, N=100, D=72, M=40)
+    ins = [0x1000000 * (i + 1) for i in range(6)]          # q, tq, k, tk, gain_q, gain_k
+    vs = [0x1000000 * (i + 7) for i in range(2)]           # v, tv
+    outs = [0x1000000 * (i + 9) for i in range(8)]         # qn, tqn, kn, tkn, o, to, lse, stats
+    call = lambda i, v, o, eps=1e-6, dd=d: L.tvmattn_jvp_fwd_qknorm(ctypes.byref(dd), *i, eps, *v, *o, None)
+    for bad_eps in (-1.0, float("nan"), float("inf")):
+        assert call(ins, vs, outs, bad_eps) == -1
+    assert call(ins, vs, outs, dd=desc(D=0)) == -1
+    # what the matrix-core forward does not take is refused, not sent elsewhere
+    assert call(ins, vs, outs, dd=desc(dtype=0, D=32)) == -2 and call(ins, vs, outs, dd=desc(D=136)) == -2
+    assert call(ins, vs, outs, dd=desc(D=72, flags=binding.TVMATTN_FLAG_PLAIN_ALU)) == -2
+    for i in range(6):
+        p = list(ins)
+        p[i] = None
+        assert call(p, vs, outs) == -1
+        p[i] = ins[i] + 8
+        assert call(p, vs, outs) == -1
+    for o in range(6):
+        p = list(outs)
+        p[o] = None
+        assert call(ins, vs, p) == -1
+        p[o] = ins[0]          # an output aliases q
+        assert call(ins, vs, p) == -1
+    assert call(ins, vs, outs[:6] + [None, outs[7]]) == -1   # lse and stats are saved together or not at all
+    assert call(ins, [None, vs[1]], outs) == -1
+
+
 def test_fused_backward_argument_rules(L):
     """tvmattn_jvp_bwd_qknorm: checked before anything is launched; status -3 (workspace too small) shows that
     the pointer checks were passed, -2 that the shape is one the fused kernels do not take."""

@@ -250,3 +250,96 @@ def test_fused_backward_refuses_what_it_does_not_serve():
         with pytest.raises(tvm.TvmattnError) as ei:
             tvm.tvmattn_jvp_bwd_qknorm(x, x, x, x, g, g, EPS, x, x, x, x, x, x, x, x, row, row, x, x)
         assert ei.value.status == -2
+
+
+# ---------------------------------------------------------------- norm and attention forward in one call
+FWD_NAMES = ("qn", "tqn", "kn", "tkn", "o", "to", "lse", "stats")
+
+
+def fused_forward_and_two_calls(B, H, M, N, d, seed, scale=0.0):
+    qs = wl.make_inputs(wl.custom(B, H, M, d, "bf16"), seed)
+    ks = wl.make_inputs(wl.custom(B, H, N, d, "bf16"), seed + 1)
+    inp = {n: (qs if n in ("q", "tq", "gO", "gTO") else ks)[n] for n in wl.NAMES}
+    gq, gk = wl.make_gains(wl.custom(B, H, N, d, "bf16"), seed + 2)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    gqd, gkd = gq.cuda(), gk.cuda()
+    n4 = tvm.tvmattn_qknorm_jvp_fwd(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS)
+    f4 = tvm.tvmattn_jvp_fwd(n4[0], n4[2], dev["v"], n4[1], n4[3], dev["tv"], scale=scale)
+    fused = tvm.tvmattn_jvp_fwd_qknorm(dev["q"], dev["tq"], dev["k"], dev["tk"], gqd, gkd, EPS, dev["v"], dev["tv"], scale=scale)
+    torch.cuda.synchronize()
+    return inp, (gq, gk), tuple(n4) + tuple(f4), fused
+
+
+def check_fused_forward(inp, gains, two, fused, heads, scale=None):
+    # the key side runs through the same kernel either way
+    assert torch.equal(two[2], fused[2]) and torch.equal(two[3], fused[3])
+    # against the two calls: the same formulas in float32 in another order, then one bf16 rounding of qn, tqn
+    for name, a, b in zip(FWD_NAMES, two, fused):
+        e = pu.rel_err(b.float().cpu().numpy(), a.float().cpu().numpy().astype(np.float64))
+        assert e <= 1e-2, (name, e)
+    g64q, g64k = wl.to_f64(gains[0]), wl.to_f64(gains[1])
+    for (b, h) in heads:
+        f = {n: wl.to_f64(t[b, h]) for n, t in inp.items()}
+        rqn, rtqn = norc.rmsnorm_jvp_fwd(f["q"], f["tq"], g64q, EPS)
+        rkn, rtkn = norc.rmsnorm_jvp_fwd(f["k"], f["tk"], g64k, EPS)
+        ro, rto, rlse, rstats = aorc.attn_jvp_fwd_head(rqn, rkn, f["v"], rtqn, rtkn, f["tv"], scale)
+        for name, got, r in zip(FWD_NAMES, fused, (rqn, rtqn, rkn, rtkn, ro, rto, rlse, rstats)):
+            g = got[b, h].float().cpu().numpy()
+            # (lse and stats are sums of O(1) scores: with a single key they are one score, whose error is that of a
+            # dot product of bf16-rounded rows, absolute, however small the score)
+            e = float(np.abs(g - r).max()) / max(1.0, float(np.abs(r).max())) if name in ("lse", "stats") else pu.rel_err(g, r)
+            assert e <= pu.TOL["bf16"], (name, b, h, e)
+
+
+@pytest.mark.parametrize("B,H,M,N,d", [
+    (1, 2, 100, 100, 16), (2, 1, 130, 70, 32), (1, 1, 97, 200, 48), (1, 2, 200, 200, 64), (2, 3, 200, 260, 72),
+    (1, 1, 65, 193, 96), (1, 1, 1, 1, 8), (1, 2, 300, 40, 40), (1, 1, 70, 150, 128), (1, 1, 33, 90, 104),
+    (1, 2, 300, 600, 72),   # eight-wave workgroups (512 keys or more, more than 128 queries), ragged in both
+    (1, 1, 257, 513, 64), (1, 1, 512, 1000, 96), (1, 1, 129, 512, 24),
+])
+def test_fused_forward_against_the_oracle_chain_and_the_two_calls(B, H, M, N, d):
+    announce(f"qknorm + attention forward in one call B{B} H{H} M{M} N{N} d{d}")
+    inp, gains, two, fused = fused_forward_and_two_calls(B, H, M, N, d, 81)
+    check_fused_forward(inp, gains, two, fused, [(b, h) for b in range(B) for h in range(H)])
+
+
+def test_fused_forward_explicit_scale_and_nothing_saved():
+    announce("qknorm + attention forward in one call: explicit scale, save=False")
+    B, H, M, N, d = 1, 2, 150, 220, 72
+    inp, gains, two, fused = fused_forward_and_two_calls(B, H, M, N, d, 82, scale=0.2)
+    check_fused_forward(inp, gains, two, fused, [(0, 0), (0, 1)], scale=0.2)
+    dev = {n: t.cuda() for n, t in inp.items()}
+    out = tvm.tvmattn_jvp_fwd_qknorm(dev["q"], dev["tq"], dev["k"], dev["tk"], gains[0].cuda(), gains[1].cuda(), EPS,
+                                     dev["v"], dev["tv"], scale=0.2, save=False)
+    torch.cuda.synchronize()
+    assert out[6] is None and out[7] is None
+    for name, a, b in zip(FWD_NAMES[:6], fused, out):
+        assert torch.equal(a, b), name
+
+
+def test_fused_forward_full_size_and_the_backward_takes_its_outputs():
+    """C4 in the launch configuration bench.py times; sampled heads against the oracle chain; the rows it leaves
+    behind feed the fused backward, whose gradients are compared with those from the two forward calls' rows."""
+    w = wl.CONFIGS["C4"]
+    announce(f"qknorm + attention forward in one call, full size {w}")
+    inp, gains, two, fused = fused_forward_and_two_calls(w.B, w.H, w.N, w.N, w.d, 83)
+    check_fused_forward(inp, gains, two, fused, [(0, 0), (w.B - 1, w.H - 1)])
+    dev = {n: t.cuda() for n, t in inp.items()}
+    gq, gk = gains[0].cuda(), gains[1].cuda()
+    bwd = lambda f: tvm.tvmattn_jvp_bwd_qknorm(dev["q"], dev["tq"], dev["k"], dev["tk"], gq, gk, EPS, f[0], f[1], f[2], f[3],
+                                               dev["v"], dev["tv"], f[4], f[5], f[6], f[7], dev["gO"], dev["gTO"])
+    ga, gb = bwd(two), bwd(fused)
+    torch.cuda.synchronize()
+    for name, a, b in zip(FUSED_NAMES, ga, gb):
+        e = pu.rel_err(b.float().cpu().numpy(), a.float().cpu().numpy().astype(np.float64))
+        assert e <= 1e-2, (name, e)
+
+
+def test_fused_forward_refuses_what_it_does_not_serve():
+    for B, H, N, d, dtype in ((1, 1, 64, 32, "f32"), (1, 1, 64, 136, "bf16")):
+        announce(f"fused forward unsupported d{d} {dtype}")
+        x = wl.make_inputs(wl.custom(B, H, N, d, dtype), 84)["q"].cuda()
+        g = torch.ones(d, dtype=torch.float32, device="cuda")
+        with pytest.raises(tvm.TvmattnError) as ei:
+            tvm.tvmattn_jvp_fwd_qknorm(x, x, x, x, g, g, EPS, x, x)
+        assert ei.value.status == -2
