@@ -12,11 +12,15 @@
 // both sets.  Everything is computed transposed, D = Q-fragment x P-fragment, so that a lane owns one output ROW
 // (32 per 32x32 block) and 16 of its columns: results leave through LDS as whole rows (store_tile_coalesced).
 //
-// Workgroup: four waves as 2 x 2, each with 2 x 4 blocks of 32 x 32 (128 accumulator registers): a 128 x 256 output
-// tile, contraction in steps of 32 through two LDS stages filled by asynchronous global->LDS loads (mfma_tiles.h:
-// the same swizzled row-major tiles as the attention kernels; "row" fragments are 16-byte reads, "transposed"
-// ones the transposing LDS read, here with the contraction index in natural order so that both kinds pair up).
-// Per contraction step of 16 a wave reads 2 + 4 fragments for 8 products.  Two workgroups share a CU.
+// Workgroup: eight waves as 2 x 4 (two per SIMD), each with 4 x 2 blocks of 32 x 32 (128 accumulator registers): a
+// 256 x 256 output tile (128 flop per byte staged: smaller tiles are bound by L2->LDS traffic), contraction in
+// tiles of 64 through two LDS stages filled by asynchronous global->LDS loads (mfma_tiles.h: the same swizzled
+// row-major tiles as the attention kernels; "row" fragments are 16-byte reads, "transposed" ones the transposing LDS
+// read, here with the contraction index in natural order so that both kinds pair up).  Per contraction step of 16
+// a wave reads 4 + 2 fragments for 8 products, a step ahead of the products that use them.  Workgroups are
+// persistent, one per CU: each walks a list of output tiles in an order that keeps an XCD's workgroups on one patch
+// of tiles, requests the next tile's first operands during the last contraction tile of the current one, and writes
+// a tile's results while those land.
 //
 // grad W contracts over all tokens of both sets (32K rows at DiT-XL/2 512 px) for few output tiles, so the token
 // range is split over several workgroups per tile; each leaves a float32 partial tile in the workspace and a second
