@@ -52,6 +52,7 @@ def run(R, K, F, seed, bias=True):
     (1000, 288, 864),     # the shape of a QKV projection (F = 3 K) with many contraction splits
     (513, 64, 256),       # one row beyond two row tiles of 256; contraction of exactly one tile
     (600, 352, 608),      # contraction lengths that end in half a tile (352 = 5.5 x 64, 608 = 9.5 x 64)
+    (4000, 1152, 3392),   # two rounds of persistent workgroups, ragged in rows and columns
 ])
 def test_linear_against_the_oracle(R, K, F):
     run(R, K, F, seed=7 + R % 5)
