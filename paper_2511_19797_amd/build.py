@@ -29,6 +29,9 @@ PER_FILE = {
     "bwd_col_pipe_tangent.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_row_pipe_qknorm.hip": ["-mllvm", "-enable-misched=false"],
     "bwd_col_pipe_qknorm.hip": ["-mllvm", "-enable-misched=false"],
+    # (its unrolled phases exceed the default size limit of "#pragma unroll": a loop left rolled would index
+    # register arrays at run time)
+    "bwd_col_pass.hip": ["-mllvm", "-enable-misched=false", "-mllvm", "-pragma-unroll-threshold=262144"],
 }
 
 

@@ -1,13 +1,15 @@
 // Backward dispatch on the bf16 matrix cores: hand-scheduled kernels for head dims up to 96 with both
 // upstream gradients (bwd_row_pipe.hip, bwd_col_pipe.hip) or with gTO alone (the same two sources built
-// without the products of gO: bwd_*_pipe_tangent.hip); generic-order kernels above 96
-// (bwd_mfma_wide.hip, bwd_mfma_onesided2.hip) and with gO alone (bwd_mfma_onesided1.hip).
+// without the products of gO: bwd_*_pipe_tangent.hip); above 96 the generic-order query-side kernel
+// (bwd_mfma_wide.hip) followed by the hand-scheduled key-side passes (bwd_col_pass.hip); generic-order kernels
+// with one upstream gradient above 96 (bwd_mfma_onesided2.hip) and with gO alone (bwd_mfma_onesided1.hip).
 #include "tvm_common.h"
 
 namespace tvm {
 
 hipError_t launch_bwd_col_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
-hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_mfma_wide(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws);
+hipError_t launch_bwd_col_pass(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_pipe_tangent(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_pipe_tangent(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_onesided1(const Shape& s, const BwdArgs& a, hipStream_t st);
@@ -26,13 +28,21 @@ hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st)
   if (a.mode == 2 && s.D <= 96) return launch_bwd_col_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_col_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);
+#if defined(TVM_ONE_PASS_WIDE)
   return launch_bwd_col_mfma_wide(s, a, st);
+#else
+  return launch_bwd_col_pass(s, a, st);
+#endif
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 2 && s.D <= 96) return launch_bwd_row_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_row_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);
-  return launch_bwd_row_mfma_wide(s, a, st);
+#if defined(TVM_ONE_PASS_WIDE)
+  return launch_bwd_row_mfma_wide(s, a, st, false);
+#else
+  return launch_bwd_row_mfma_wide(s, a, st, true);  // (the row vectors as the key-side passes read them)
+#endif
 }
 // One upstream gradient only (generic-order kernels that leave out what vanishes with the other).
 hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t st) {

@@ -233,7 +233,8 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
     const bf16* __restrict__ o, const bf16* __restrict__ to, const float* __restrict__ lse,
     const float* __restrict__ stats, const bf16* __restrict__ gO, const bf16* __restrict__ gTO,
-    float* __restrict__ dsig, float* __restrict__ sig1, bf16* __restrict__ dq, bf16* __restrict__ dtq) {
+    float* __restrict__ dsig, float* __restrict__ sig1, bf16* __restrict__ dq, bf16* __restrict__ dtq,
+    float* __restrict__ lse2w) {
   using TK = Tile<kTS, DV / 8, kNT / 64>;  // K, tK: read both ways
   using TV = Tile<kTS, DK / 8, kNT / 64>;  // V, tV: score products only
   // one stage: K, tK, V, tV; without gTO only K and V (half the LDS: two workgroups per CU)
@@ -303,8 +304,15 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
   const float lse2 = iok ? lse[r] * kLog2e : 0.f;
   const float mub = (MODE != 1 && iok) ? stats[r] : 0.f;
   if (iok && hh == 0) {
-    dsig[r] = ds;
-    if (MODE != 1) sig1[r] = s1;
+    if (lse2w != nullptr) {
+      // for the hand-scheduled key-side passes (bwd_col_pass.hip): lse in log2 units, the two sums negated
+      lse2w[r] = lse2;
+      dsig[r] = -ds;
+      sig1[r] = -s1;
+    } else {
+      dsig[r] = ds;
+      if (MODE != 1) sig1[r] = s1;
+    }
   }
   f32x16 aQ[NDB], aTQ[NDB];
   zero_acc(aQ);
@@ -425,13 +433,14 @@ hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// pipe_ws: leave the row vectors in the workspace in the convention of the hand-scheduled key-side kernels
 template <int DK, int DV, int MODE>
-hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws = false) {
   const int nfb = (s.M + kFix - 1) / kFix;
   hipLaunchKernelGGL((bwd_row_mfma_kernel<DK, DV, (DV > 96 ? 32 : 64), MODE>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s,
                      (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk,
                      (const bf16*)a.tv, (const bf16*)a.o, (const bf16*)a.to, a.lse, a.stats, (const bf16*)a.gO,
-                     (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq);
+                     (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dq, (bf16*)a.dtq, pipe_ws ? a.lse2 : nullptr);
   return hipGetLastError();
 }
 
