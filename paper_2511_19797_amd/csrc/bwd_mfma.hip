@@ -22,27 +22,24 @@ bool mfma_supported(const Shape& s, int dtype) {
   return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22) && s.qsn < (1ll << 22);
 }
 
+// Head dims above 96 with both gradients: the key side runs as the two hand-scheduled passes unless there are so few
+// queries (two tiles of 32 at most) that a second launch costs more than the passes save (measured: 64 queries 56
+// against 51 us, from 128 queries on the passes are ahead, 2.40 against 3.18 ms at 4096).
+static bool key_side_in_two_passes(const Shape& s) { return s.D > 96 && s.M > 64; }
+
 // The query-side kernel runs first in both families: it leaves the row scalars of Step 1 of
 // App. C in the workspace for the key-side kernel (the hand-scheduled pair also lse in log2 units).
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 2 && s.D <= 96) return launch_bwd_col_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_col_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);
-#if defined(TVM_ONE_PASS_WIDE)
-  return launch_bwd_col_mfma_wide(s, a, st);
-#else
-  return launch_bwd_col_pass(s, a, st);
-#endif
+  return key_side_in_two_passes(s) ? launch_bwd_col_pass(s, a, st) : launch_bwd_col_mfma_wide(s, a, st);
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 2 && s.D <= 96) return launch_bwd_row_pipe_tangent(s, a, st);
   if (a.mode != 0) return launch_bwd_row_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);
-#if defined(TVM_ONE_PASS_WIDE)
-  return launch_bwd_row_mfma_wide(s, a, st, false);
-#else
-  return launch_bwd_row_mfma_wide(s, a, st, true);  // (the row vectors as the key-side passes read them)
-#endif
+  return launch_bwd_row_mfma_wide(s, a, st, key_side_in_two_passes(s));  // (the row vectors as the passes read them)
 }
 // One upstream gradient only (generic-order kernels that leave out what vanishes with the other).
 hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t st) {

@@ -72,6 +72,21 @@ def test_bf16_hand_scheduled_tile_boundaries(d):
         run_case(wl.custom(1, 1, N, d, "bf16"), seed=20 + N % 7)
 
 
+@pytest.mark.parametrize("d", [104, 112, 120, 128])
+def test_bf16_two_pass_key_side_tile_boundaries(d):
+    """Head dims above 96: from 65 queries on the key side of the backward runs as two hand-scheduled passes over
+    tiles of 32 queries (both instantiations: contraction padded to 112 and to 128).  Sequence lengths where that
+    pipeline changes shape: the last one-pass length and the first two-pass one, three and four tiles (the three
+    LDS stages wrap), one row more or fewer, a workgroup boundary of 128 keys, several workgroups per head; then
+    M != N either way round, with a ragged last tile on both sides.  Every element of all ten outputs."""
+    import dataclasses
+    for N in (64, 65, 95, 96, 97, 127, 128, 129, 161, 320):
+        run_case(wl.custom(1, 1, N, d, "bf16"), seed=30 + N % 7)
+    for M, N in ((65, 300), (300, 65), (130, 129)):
+        w = dataclasses.replace(wl.custom(1, 2, N, d, "bf16"), M=M)
+        run_case(w, seed=40 + M % 13)
+
+
 @pytest.mark.parametrize("d", [8, 24, 40, 64, 72, 96])
 def test_bf16_wide_forward_workgroups(d):
     """From 512 keys on (head dims up to 96, more than 128 queries) the forward runs eight-wave workgroups of 256
