@@ -19,6 +19,10 @@
 //
 // The tile after next is fetched behind the products of S and of the last phase, which carry no pointwise work.
 //
+// HAS_G = false is the pair of passes for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of App. C by
+// themselves): the products with G vanish (E phase: two per 16 head dims, DF = tG tV^T; OV: two per 32, dV += tG^T Pd,
+// dtV += tG^T P), and the G tile is neither fetched nor read.
+//
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"
 
@@ -38,7 +42,7 @@ __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
 __device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
 
 // PASS 1: dV, dtV into out0, out1;  PASS 2: dK, dtK into out0, out1.
-template <int DK, int DV, int PASS>
+template <int DK, int DV, int PASS, bool HAS_G>
 __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
     const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
@@ -53,22 +57,26 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
   static_assert(3 * BUF <= 160 * 1024, "three stages fit the LDS");
   __shared__ __attribute__((aligned(16))) char lds[3 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
-  constexpr int NS = 3 * NKS;  // products of the S phase, and of the E phase
-  constexpr int NH = 3 * NDB;  // products of half an output phase (three per 32 output columns in either pass)
-  constexpr int FS = 4;        // first pointwise slot of the E phase
+  constexpr int PG = HAS_G ? 3 : 2;          // products per step of the phases that G takes part in
+  constexpr int NTG = HAS_G ? 2 : 1;         // tiles of upstream gradients (tG and G, or tG alone)
+  constexpr int NS = 3 * NKS;                // products of the S phase
+  constexpr int NE = PG * NKS;               // products of the E phase
+  constexpr int NH = (PV ? PG : 3) * NDB;    // products of half the output phase of this pass
+  constexpr int FS = 4;                      // first pointwise slot of the E phase
   // pass V: pieces 24..47 of P, N, Pd (half 1) go behind the products of OV(0);  pass K: the 24 pieces of P, N behind
   // those of E from FS on, pieces 20..39 of gZ, gZt (half 1) behind those of OK(0)
   struct C {
     static constexpr int pwv(int u) { return (((u + 24) % 12) >> 1 == 1 || ((u + 24) % 12) >> 1 == 2) ? 12 : 8; }
     static constexpr int pwk(int u) { return (u % 6) >> 1 == 0 ? 8 : 12; }
     static constexpr int pw2(int) { return 8; }
-    static constexpr int base_h(int v) { return 8 * share_count(v, 2 * NDB, NH); }
-    static constexpr int base_e(int v) { return 8 * share_count(v, 2 * NDB, NS) + (v < FS ? 4 * share_count(v, 4, FS) : 0); }
+    static constexpr int base_h(int v) { return 8 * share_count(v, (PV ? NTG : 2) * NDB, NH); }
+    static constexpr int base_e(int v) { return 8 * share_count(v, 2 * NDB, NE) + (v < FS ? 4 * share_count(v, 4, FS) : 0); }
   };
   static constexpr Deal<NH> kPwV = deal_out<NH>(24, 0, NH, 24, C::pwv, C::base_h);
-  static constexpr Deal<NS> kPwK = deal_out<NS>(24, FS, NS, 24, C::pwk, C::base_e);
+  static constexpr Deal<NE> kPwK = deal_out<NE>(24, FS, NE, 24, C::pwk, C::base_e);
   static constexpr Deal<NH> kPw2 = deal_out<NH>(20, 0, NH, 20, C::pw2, C::base_h);
-  constexpr int NDMA = 4 * TX::IPW + 1;       // wave-loads per wave and tile (the last: a row vector)
+  constexpr int NTILE = HAS_G ? 4 : 3;        // tiles fetched per stage (the G tile's place stays empty without gO)
+  constexpr int NDMA = NTILE * TX::IPW + 1;   // wave-loads per wave and tile (the last: a row vector)
   constexpr int NQB = NS + NH;                // products that carry tile loads: S and the last phase
   constexpr int NDMA_PRE = NS * NDMA / NQB;   // wave-loads issued before the barrier (behind the products of S)
   const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
@@ -108,7 +116,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     if (x < TX::IPW) TX::issue_at(off, t, q + ro, buf, wave);
     else if (x < 2 * TX::IPW) TX::issue_at(off, t, tq + ro, buf + OFF_TQ, wave);
     else if (x < 3 * TX::IPW) TX::issue_at(off, t, gTO + ro, buf + OFF_TG, wave);
-    else if (x < 4 * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
+    else if (x < NTILE * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
     else dma_to_lds<4>(rowsrc + i0, last ? rv_last : rv_full, buf + OFF_ROW + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
@@ -220,9 +228,9 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
       }
       if (PV) {
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NS) {  // tG^T, G^T of half 0
-          const int db = x >> 1;
-          if ((x & 1) == 0) txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
+        TVM_SHARE(x, m, NTG * NDB, NS) {  // tG^T, G^T of half 0
+          const int db = x / NTG;
+          if (x % NTG == 0) txT[db] = lds_read_tr(tl, th, OFF_TG + tr_imm(0, db));
           else xT[db] = lds_read_tr(tl, th, OFF_G + tr_imm(0, db));
         }
 #pragma unroll
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
         }
       } else {
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NKS, NS) {  // tG, G rows
+        TVM_SHARE(x, m, NTG * NKS, NS) {  // tG, G rows
           const int k2 = x % NKS;
           if (x < NKS) rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + k2 * 32);
           else rg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_G + k2 * 32);
@@ -257,14 +265,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
       // ---- OV(0), with P, N, Pd of half 1
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
-        const int db = m / 3, w = m - 3 * db;
+        const int db = m / PG, w = m - PG * db;
         if (w == 0) { if (m == 0) mfma_acc<true>(a0[db], txT[db], frag_of(pdk, 0)); else mfma_acc<RAG>(a0[db], txT[db], frag_of(pdk, 0)); }
         else if (w == 1) mfma_acc<RAG>(a1[db], txT[db], frag_of(pk, 0));
         else mfma_acc<RAG>(a0[db], xT[db], frag_of(pk, 0));
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NH) {  // tG^T, G^T of half 1
-          const int d2 = x >> 1;
-          if ((x & 1) == 0) tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
+        TVM_SHARE(x, m, NTG * NDB, NH) {  // tG^T, G^T of half 1
+          const int d2 = x / NTG;
+          if (x % NTG == 0) tyT[d2] = lds_read_tr(tl, th, OFF_TG + tr_imm(1, d2));
           else yT[d2] = lds_read_tr(tl, th, OFF_G + tr_imm(1, d2));
         }
 #pragma unroll
@@ -280,13 +288,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
           sDF[4 * g4 + t] = da[g4][t];
         }
 #pragma unroll
-      for (int m = 0; m < NS; ++m) {
-        const int kk = m / 3, w = m - 3 * kk;
+      for (int m = 0; m < NE; ++m) {
+        const int kk = m / PG, w = m - PG * kk;
         if (w == 0) mfma_fix<RAG>(sE, rtg[kk], vf[kk]);
         else if (w == 1) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
         else mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
 #pragma unroll
-        TVM_SHARE(x, m, 2 * NDB, NS) {  // Q^T, tQ^T of half 0
+        TVM_SHARE(x, m, 2 * NDB, NE) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
           if ((x & 1) == 0) xT[d2] = lds_read_tr(tl, th, tr_imm(0, d2));
           else txT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(0, d2));
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     // ---- second half of the output products; Q, tQ rows of the next block; tile loads
 #pragma unroll
     for (int m = 0; m < NH; ++m) {
-      const int db = m / 3, w = m - 3 * db;
+      const int db = m / (PV ? PG : 3), w = m - (PV ? PG : 3) * db;
       if (PV) {
         if (w == 0) { if (m == 0) mfma_acc<true>(a0[db], tyT[db], frag_of(pdk, 1)); else mfma_acc<RAG>(a0[db], tyT[db], frag_of(pdk, 1)); }
         else if (w == 1) mfma_acc<RAG>(a1[db], tyT[db], frag_of(pk, 1));
@@ -392,17 +400,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
   }
 }
 
-template <int DK, int DV>
+template <int DK, int DV, bool HAS_G>
 hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
   const dim3 grid(nfb * s.B * s.H), block(kNT);
   // pass K first: it is the longer one
-  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 2>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
+  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 2, HAS_G>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
                      (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse2, a.stats,
                      (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk, (bf16*)a.dtk);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 1>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
+  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 1, HAS_G>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
                      (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse2, a.stats,
                      (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dv, (bf16*)a.dtv);
   return hipGetLastError();
@@ -410,12 +418,12 @@ hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
 
 }  // namespace
 
-// Head dims 97..128, both upstream gradients given.  Needs the row vectors in the workspace in the convention of
-// the hand-scheduled kernels (dsig, sig1 negated and lse in log2 units).
+// Head dims 97..128, with both upstream gradients (a.mode 0) or with gTO alone (a.mode 2).  Needs the row vectors in
+// the workspace in the convention of the hand-scheduled kernels (dsig, sig1 negated and lse in log2 units).
 hipError_t launch_bwd_col_pass(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  if (s.D > 96 && s.D <= 112) return launch<112, 128>(s, a, st);
-  if (s.D > 112 && s.D <= 128) return launch<128, 128>(s, a, st);
-  return hipErrorNotSupported;
+  if (a.mode == 1 || s.D <= 96 || s.D > 128) return hipErrorNotSupported;
+  if (s.D <= 112) return a.mode == 0 ? launch<112, 128, true>(s, a, st) : launch<112, 128, false>(s, a, st);
+  return a.mode == 0 ? launch<128, 128, true>(s, a, st) : launch<128, 128, false>(s, a, st);
 }
 
 }  // namespace tvm

@@ -15,14 +15,14 @@ hipError_t launch_bwd_row_pipe_tangent(const Shape& s, const BwdArgs& a, hipStre
 hipError_t launch_bwd_col_onesided1(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_row_onesided1(const Shape& s, const BwdArgs& a, hipStream_t st);
 hipError_t launch_bwd_col_onesided2(const Shape& s, const BwdArgs& a, hipStream_t st);
-hipError_t launch_bwd_row_onesided2(const Shape& s, const BwdArgs& a, hipStream_t st);
+hipError_t launch_bwd_row_onesided2(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws);
 
 bool mfma_supported(const Shape& s, int dtype) {
   // bf16, 16-byte chunks, and row pitches whose tile offsets fit the 32-bit lane offsets of the LDS loads
   return dtype == 1 && s.D % 8 == 0 && s.D <= 128 && s.sn < (1ll << 22) && s.qsn < (1ll << 22);
 }
 
-// Head dims above 96 with both gradients: the key side runs as the two hand-scheduled passes unless there are so few
+// Head dims above 96 with both gradients or with gTO alone: the key side runs as the two hand-scheduled passes unless there are so few
 // queries (two tiles of 32 at most) that a second launch costs more than the passes save (measured: 64 queries 56
 // against 51 us, from 128 queries on the passes are ahead, 2.40 against 3.18 ms at 4096).
 static bool key_side_in_two_passes(const Shape& s) { return s.D > 96 && s.M > 64; }
@@ -31,6 +31,7 @@ static bool key_side_in_two_passes(const Shape& s) { return s.D > 96 && s.M > 64
 // App. C in the workspace for the key-side kernel (the hand-scheduled pair also lse in log2 units).
 hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 2 && s.D <= 96) return launch_bwd_col_pipe_tangent(s, a, st);
+  if (a.mode == 2 && key_side_in_two_passes(s)) return launch_bwd_col_pass(s, a, st);
   if (a.mode != 0) return launch_bwd_col_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_col_pipe(s, a, st);
   return key_side_in_two_passes(s) ? launch_bwd_col_pass(s, a, st) : launch_bwd_col_mfma_wide(s, a, st);
@@ -46,7 +47,7 @@ hipError_t launch_bwd_col_onesided(const Shape& s, const BwdArgs& a, hipStream_t
   return a.mode == 1 ? launch_bwd_col_onesided1(s, a, st) : launch_bwd_col_onesided2(s, a, st);
 }
 hipError_t launch_bwd_row_onesided(const Shape& s, const BwdArgs& a, hipStream_t st) {
-  return a.mode == 1 ? launch_bwd_row_onesided1(s, a, st) : launch_bwd_row_onesided2(s, a, st);
+  return a.mode == 1 ? launch_bwd_row_onesided1(s, a, st) : launch_bwd_row_onesided2(s, a, st, key_side_in_two_passes(s));
 }
 
 }  // namespace tvm

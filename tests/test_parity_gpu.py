@@ -340,6 +340,8 @@ def test_longest_benchmark_shape_sampled_rows():
     (1, 2, 100, 16, "bf16"), (2, 1, 200, 64, "bf16"), (1, 2, 320, 72, "bf16"), (1, 1, 193, 96, "bf16"),
     (1, 1, 257, 128, "bf16"), (1, 2, 70, 136, "bf16"), (1, 2, 64, 32, "f32"),
     (1, 2, 130, 32, "bf16"), (1, 1, 97, 48, "bf16"), (1, 1, 64, 80, "bf16"), (2, 1, 33, 8, "bf16"), (1, 1, 2, 40, "bf16"),
+    # head dims above 96: the tangent path's key side as two passes (more than 64 queries) and in one (64)
+    (1, 2, 97, 112, "bf16"), (1, 1, 65, 104, "bf16"), (1, 1, 64, 120, "bf16"), (2, 1, 160, 128, "bf16"),
 ])
 def test_one_sided_backward(B, H, N, d, dtype):
     """gTO = None is the ordinary attention backward (the oracle with a zero gTO; tangent tensors not
