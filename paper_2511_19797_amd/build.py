@@ -31,7 +31,7 @@ PER_FILE = {
     "bwd_col_pipe_qknorm.hip": ["-mllvm", "-enable-misched=false"],
     # (its unrolled phases exceed the default size limit of "#pragma unroll": a loop left rolled would index
     # register arrays at run time)
-    "bwd_col_pass.hip": ["-mllvm", "-enable-misched=false", "-mllvm", "-pragma-unroll-threshold=262144"],
+    "bwd_pass.hip": ["-mllvm", "-enable-misched=false", "-mllvm", "-pragma-unroll-threshold=262144"],
 }
 
 

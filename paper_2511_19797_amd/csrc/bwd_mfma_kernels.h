@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kNT, MODE == 1 ? 2 : 1) void bwd_row_mfma_kernel(
   const float mub = (MODE != 1 && iok) ? stats[r] : 0.f;
   if (iok && hh == 0) {
     if (lse2w != nullptr) {
-      // for the hand-scheduled key-side passes (bwd_col_pass.hip): lse in log2 units, the two sums negated
+      // for the hand-scheduled key-side passes (bwd_pass.hip): lse in log2 units, the two sums negated
       lse2w[r] = lse2;
       dsig[r] = -ds;
       sig1[r] = -s1;

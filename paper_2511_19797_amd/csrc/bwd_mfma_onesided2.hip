@@ -1,6 +1,6 @@
 // Backward launchers for one upstream gradient (gTO only: the tangent path by itself) at head dims above 96 on the
 // generic-order kernels (bwd_mfma_kernels.h): the query side always, the key side for few queries (otherwise it runs
-// as the hand-scheduled passes of bwd_col_pass.hip; up to 96 it is bwd_*_pipe_tangent.hip).
+// as the hand-scheduled passes of bwd_pass.hip; up to 96 it is bwd_*_pipe_tangent.hip).
 #include "bwd_mfma_kernels.h"
 
 namespace tvm {

@@ -1,5 +1,6 @@
-// Key-side backward (dK, dtK, dV, dtV; Steps 2, 4, 6 of App. C plus the ordinary-attention terms of gO) for
-// head dims in (96, 128], with the instruction stream laid out by hand, as TWO passes over the queries.
+// Backward for head dims in (96, 128] with the instruction stream laid out by hand: the key side (dK, dtK, dV, dtV;
+// Steps 2, 4, 6 of App. C plus the ordinary-attention terms of gO) as TWO passes over the queries, and the query
+// side (dQ, dtQ; Steps 1, 3, 5) as one pass over the keys with the code of pass K.
 //
 // At 128 columns the four accumulators of the one-pass kernel (bwd_col_pipe.hip) fill the AGPRs and the four
 // fixed-side fragments the VGPRs.  Here each pass keeps two accumulators (128 AGPRs) and every fixed-side
@@ -18,6 +19,13 @@
 //   pass K   S | E with P, N | gZ, gZt of half 0 (nothing to hide behind) | OK(0) with gZ, gZt of half 1 | barrier | OK(1)
 //
 // The tile after next is fetched behind the products of S and of the last phase, which carry no pointwise work.
+//
+// Pass Q is pass K with the two sides exchanged: a wave owns 32 queries (fragments of q, tq, gTO, gO fixed, dQ and dtQ
+// accumulated) and streams K, tK, V, tV through the same LDS slots; E = V gTO^T and DF = V gO^T + tV gTO^T pair the
+// same slots with the same fixed fragments as E = tG V^T, DF = tG tV^T + G V^T do in pass K, and dQ += gZ K + gZt tK,
+// dtQ += gZt K are pass K's output products.  What differs: the row scalars belong to the lane (lse, stats from the
+// forward, and Step 1's sums, formed here from the fragments and left in the workspace for the key side, which
+// runs afterwards), and the masked entries of a ragged last tile are keys.
 //
 // HAS_G = false is the pair of passes for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of App. C by
 // themselves): the products with G vanish (E phase: two per 16 head dims, DF = tG tV^T; OV: two per 32, dV += tG^T Pd,
@@ -41,16 +49,24 @@ __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
 }
 __device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
 
-// PASS 1: dV, dtV into out0, out1;  PASS 2: dK, dtK into out0, out1.
+// PASS 1: dV, dtV into out0, out1;  PASS 2: dK, dtK;  PASS 3: dQ, dtQ.
+//   f0..f3: the fixed side's tensors (passes V, K: k, tk, v, tv;  pass Q: q, tq, gTO, gO)
+//   t0..t3: the streamed side's, in LDS slot order (passes V, K: q, tq, gTO, gO;  pass Q: k, tk, v, tv)
+//   lse_in: passes V, K: lse in log2 units from the workspace;  pass Q: lse as the forward saved it
+//   dsig, sig1: passes V, K: read (negated sums);  pass Q: written, with lse in log2 units to lse2w, for the key side:
+//   negated and in log2 units if pipe_ws, else plain (the generic-order key-side kernel follows) and lse2w untouched
+//   o, to: pass Q only (Step 1)
 template <int DK, int DV, int PASS, bool HAS_G>
-__global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
-    Shape s, const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-    const bf16* __restrict__ tq, const bf16* __restrict__ tk, const bf16* __restrict__ tv,
-    const float* __restrict__ lse2w, const float* __restrict__ stats, const bf16* __restrict__ gO,
-    const bf16* __restrict__ gTO, const float* __restrict__ dsig, const float* __restrict__ sig1,
-    bf16* __restrict__ out0, bf16* __restrict__ out1) {
-  static_assert(PASS == 1 || PASS == 2, "pass V or pass K");
-  constexpr bool PV = PASS == 1;
+__global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
+    Shape s, const bf16* __restrict__ f0, const bf16* __restrict__ f1, const bf16* __restrict__ f2,
+    const bf16* __restrict__ f3, const bf16* __restrict__ t0, const bf16* __restrict__ t1,
+    const bf16* __restrict__ t2, const bf16* __restrict__ t3, const float* __restrict__ lse_in,
+    const float* __restrict__ stats, float* __restrict__ dsig, float* __restrict__ sig1, float* __restrict__ lse2w,
+    int pipe_ws, const bf16* __restrict__ o, const bf16* __restrict__ to, bf16* __restrict__ out0,
+    bf16* __restrict__ out1) {
+  static_assert(PASS >= 1 && PASS <= 3, "pass V, K or Q");
+  static_assert(PASS != 3 || HAS_G, "pass Q takes both upstream gradients");
+  constexpr bool PV = PASS == 1, PQ = PASS == 3;
   using TX = Tile<32, DV / 8, kNT / 64>;  // Q, tQ, G, tG: read both ways
   constexpr int OFF_TQ = TX::BYTES, OFF_G = 2 * TX::BYTES, OFF_TG = 3 * TX::BYTES, OFF_ROW = 4 * TX::BYTES;
   constexpr int BUF = 4 * TX::BYTES + 4 * 256;  // one stage: four tiles and four float32 row vectors (64 floats each, 32 used)
@@ -70,29 +86,32 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     static constexpr int pwk(int u) { return (u % 6) >> 1 == 0 ? 8 : 12; }
     static constexpr int pw2(int) { return 8; }
     static constexpr int base_h(int v) { return 8 * share_count(v, (PV ? NTG : 2) * NDB, NH); }
-    static constexpr int base_e(int v) { return 8 * share_count(v, 2 * NDB, NE) + (v < FS ? 4 * share_count(v, 4, FS) : 0); }
+    static constexpr int base_e(int v) { return 8 * share_count(v, 2 * NDB, NE) + (v < FS && !PQ ? 4 * share_count(v, 4, FS) : 0); }
   };
   static constexpr Deal<NH> kPwV = deal_out<NH>(24, 0, NH, 24, C::pwv, C::base_h);
   static constexpr Deal<NE> kPwK = deal_out<NE>(24, FS, NE, 24, C::pwk, C::base_e);
   static constexpr Deal<NH> kPw2 = deal_out<NH>(20, 0, NH, 20, C::pw2, C::base_h);
   constexpr int NTILE = HAS_G ? 4 : 3;        // tiles fetched per stage (the G tile's place stays empty without gO)
-  constexpr int NDMA = NTILE * TX::IPW + 1;   // wave-loads per wave and tile (the last: a row vector)
+  constexpr int NDMA = NTILE * TX::IPW + (PQ ? 0 : 1);  // wave-loads per wave and tile (passes V, K: the last is a row vector)
   constexpr int NQB = NS + NH;                // products that carry tile loads: S and the last phase
   constexpr int NDMA_PRE = NS * NDMA / NQB;   // wave-loads issued before the barrier (behind the products of S)
   const int tid = threadIdx.x, lane = tid & 63, ic = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: what depends on it alone stays out of the VALU
-  const int nfb = (s.N + kFix - 1) / kFix;
+  const int nfix = PQ ? s.M : s.N, nstr = PQ ? s.N : s.M;  // rows of the fixed side, of the streamed side
+  const int nfb = (nfix + kFix - 1) / kFix;
   const int wg = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = wg / nfb, fb = wg - bh * nfb;
   const int b = bh / s.H, h = bh - b * s.H;
-  const long long base = b * s.sb + h * s.sh;     // key side (fixed)
-  const long long qbase = b * s.qsb + h * s.qsh;  // query side (streamed)
+  const long long kbase = b * s.sb + h * s.sh, qbase = b * s.qsb + h * s.qsh;  // key side, query side
+  const long long base = PQ ? qbase : kbase;    // fixed side
+  const long long tbase = PQ ? kbase : qbase;   // streamed side
+  const long long fsn = PQ ? s.qsn : s.sn, tsn = PQ ? s.sn : s.qsn;
   const long long rbase = (long long)bh * s.M;
-  const int j = fb * kFix + wave * 32 + ic;  // this lane's key
+  const int j = fb * kFix + wave * 32 + ic;  // this lane's row of the fixed side (a key; pass Q: a query)
 
-  const unsigned pitch = (unsigned)(s.qsn * 2);  // row pitch of the streamed (query-side) tensors in bytes
+  const unsigned pitch = (unsigned)(tsn * 2);  // row pitch of the streamed tensors in bytes
   const unsigned lds0 = lds_addr_of(lds);
-  const int nt = (s.M + 31) >> 5;   // tiles
+  const int nt = (nstr + 31) >> 5;  // tiles
   const int ilast = (nt - 1) * 32;  // first query of the last tile; loads "beyond" it fetch it again, unused
   // Per-lane byte offsets of this wave's loads within a tile, worked out once: for whole tiles, and for the last
   // tile, where rows past the end fetch its last row again (masked rows, unused).  Wave w also fetches row vector w
@@ -102,21 +121,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
   {
     const typename TX::Lane lx = TX::lane_setup(s.D, wave, lane);
     of_full = TX::offsets(lx, pitch, 32);
-    of_last = TX::offsets(lx, pitch, s.M - ilast);
+    of_last = TX::offsets(lx, pitch, nstr - ilast);
     rv_full = (unsigned)min(lane, 31) * 4u;
-    rv_last = (unsigned)min(lane, s.M - ilast - 1) * 4u;
+    rv_last = (unsigned)min(lane, nstr - ilast - 1) * 4u;
   }
-  const float* const rowsrc = (wave == 0 ? lse2w : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;
-  // wave-load number x (compile-time) of the tile whose first query is i0 (< M), into the stage at `buf`;
+  const float* const rowsrc = (wave == 0 ? lse_in : wave == 1 ? stats : wave == 2 ? dsig : sig1) + rbase;  // (passes V, K)
+  // wave-load number x (compile-time) of the tile whose first row is i0 (< nstr), into the stage at `buf`;
   // `last`: that tile is the last one
   auto dma = [&](int x, int i0, unsigned buf, bool last) {
-    const long long ro = qbase + (long long)i0 * s.qsn;
+    const long long ro = tbase + (long long)i0 * tsn;
     const int t = x % TX::IPW;
     const unsigned off = last ? of_last.o[t] : of_full.o[t];
-    if (x < TX::IPW) TX::issue_at(off, t, q + ro, buf, wave);
-    else if (x < 2 * TX::IPW) TX::issue_at(off, t, tq + ro, buf + OFF_TQ, wave);
-    else if (x < 3 * TX::IPW) TX::issue_at(off, t, gTO + ro, buf + OFF_TG, wave);
-    else if (x < NTILE * TX::IPW) TX::issue_at(off, t, gO + ro, buf + OFF_G, wave);
+    if (x < TX::IPW) TX::issue_at(off, t, t0 + ro, buf, wave);
+    else if (x < 2 * TX::IPW) TX::issue_at(off, t, t1 + ro, buf + OFF_TQ, wave);
+    else if (x < 3 * TX::IPW) TX::issue_at(off, t, t2 + ro, buf + OFF_TG, wave);
+    else if (x < NTILE * TX::IPW) TX::issue_at(off, t, t3 + ro, buf + OFF_G, wave);
     else dma_to_lds<4>(rowsrc + i0, last ? rv_last : rv_full, buf + OFF_ROW + wave * 256);
   };
   const typename TX::RAddr ra = TX::raddr(ic, hh);
@@ -124,14 +143,54 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
   // Start-up: tile 0 first, then the fixed-side fragments (scattered loads), then, once those have arrived, tile 1.
 #pragma unroll
   for (int x = 0; x < NDMA; ++x) dma(x, 0, lds0, nt == 1);
-  bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];
-  gld_frags<NKS>(kf, k + base, s.sn, j, s.N, s.D, hh);
-  gld_frags<NKS>(tkf, tk + base, s.sn, j, s.N, s.D, hh);
+  bf16x8 kf[NKS], tkf[NKS], vf[NKS], tvf[NKS];  // passes V, K: of k, tk, v, tv;  pass Q: of q, tq, gTO, gO
+  gld_frags<NKS>(kf, f0 + base, fsn, j, nfix, s.D, hh);
+  gld_frags<NKS>(tkf, f1 + base, fsn, j, nfix, s.D, hh);
   if (!PV) {
-    gld_frags<NKS>(vf, v + base, s.sn, j, s.N, s.D, hh);
-    gld_frags<NKS>(tvf, tv + base, s.sn, j, s.N, s.D, hh);
+    gld_frags<NKS>(vf, f2 + base, fsn, j, nfix, s.D, hh);
+    gld_frags<NKS>(tvf, f3 + base, fsn, j, nfix, s.D, hh);
   }
-  f32x16 a0[NDB], a1[NDB];  // pass V: dV, dtV;  pass K: dK, dtK
+  // pass Q: the row scalars of this lane's query.  Step 1 of App. C, fused: delta + Sigma_2 = gO.O + gTO.tO and
+  // Sigma_1 = gTO.O from the same fragment layout (each half-wave holds half of the row); they are also written out
+  // for the key side, which runs after this kernel.
+  float lse2 = 0.f, mub = 0.f, nds = 0.f, ns1 = 0.f;
+  if (PQ) {
+    const bool iok = j < s.M;
+    float ds = 0.f, s1 = 0.f;
+    {
+      bf16x8 of[NKS], tof[NKS];
+      gld_frags<NKS>(of, o + base, fsn, j, nfix, s.D, hh);
+      gld_frags<NKS>(tof, to + base, fsn, j, nfix, s.D, hh);
+#pragma unroll
+      for (int kk = 0; kk < NKS; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float oe = (float)of[kk][e], gte = (float)vf[kk][e];
+          ds = fmaf((float)tvf[kk][e], oe, ds);
+          ds = fmaf(gte, (float)tof[kk][e], ds);
+          s1 = fmaf(gte, oe, s1);
+        }
+      ds += xhalf(ds);
+      s1 += xhalf(s1);
+    }
+    // rows beyond M: zeros keep everything finite; nothing of theirs is stored
+    const long long r = rbase + (iok ? j : 0);
+    lse2 = iok ? lse_in[r] * 1.4426950408889634f : 0.f;
+    mub = iok ? stats[r] : 0.f;
+    nds = -ds;
+    ns1 = -s1;
+    if (iok && hh == 0) {
+      if (pipe_ws) {
+        lse2w[r] = lse2;
+        dsig[r] = nds;
+        sig1[r] = ns1;
+      } else {
+        dsig[r] = ds;
+        sig1[r] = s1;
+      }
+    }
+  }
+  f32x16 a0[NDB], a1[NDB];  // pass V: dV, dtV;  pass K: dK, dtK;  pass Q: dQ, dtQ
 #pragma unroll
   for (int db = 0; db < NDB; ++db) {
     a0[db] = zero16();
@@ -174,33 +233,35 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     bf16x8 xT[NDB], txT[NDB], yT[NDB], tyT[NDB];  // transposed fragments of half 0 / of half 1
     float ta_[8], tb_[8], wa[8], wb[8];  // temporaries of element pair e, alive between its pieces
 
-    // first step of a pair: its two scores in log2 units less lse (queries beyond M: probability 0)
+    // lse (log2 units) and stats of the query of element 2e + k2: by element in passes V, K, the lane's own in pass Q
+    auto lse_of = [&](int e, int k2) { return PQ ? lse2 : f4(la[e >> 1], ((2 * e) & 3) + k2); };
+    auto mu_of = [&](int e, int k2) { return PQ ? mub : f4(ma[e >> 1], ((2 * e) & 3) + k2); };
+    // first step of a pair: its two scores in log2 units less lse (streamed rows beyond the end: probability 0)
     auto pw_scores = [&](int e) {
-      const int g4 = e >> 1, t = (2 * e) & 3;
       float s0 = sS[2 * e], s1 = sS[2 * e + 1];
       if (RAG) {
-        if (i0 + drow(2 * e, hh) >= s.M) s0 = -INFINITY;
-        if (i0 + drow(2 * e + 1, hh) >= s.M) s1 = -INFINITY;
+        if (i0 + drow(2 * e, hh) >= nstr) s0 = -INFINITY;
+        if (i0 + drow(2 * e + 1, hh) >= nstr) s1 = -INFINITY;
       }
-      pw_fma2(ta_[e], tb_[e], s0, s1, c1u, f4(la[g4], t), f4(la[g4], t + 1));
+      pw_fma2(ta_[e], tb_[e], s0, s1, c1u, lse_of(e, 0), lse_of(e, 1));
     };
     // pass V: P, N, Pd of the block as a stream of 8 x 6 pieces (pair e: elements 2e, 2e+1); two pairs take
     // turns, so that no piece reads what the piece right before it wrote
     auto pw1v_op = [&](int u) {
-      const int e = 2 * (u / 12) + (u & 1), st = (u % 12) >> 1, g4 = e >> 1, t = (2 * e) & 3;
+      const int e = 2 * (u / 12) + (u & 1), st = (u % 12) >> 1;
       if (st == 0) pw_scores(e);
-      else if (st == 1) pw_exp_fma(pp[2 * e], ta_[e], nn[2 * e], sT[2 * e], alphau, f4(ma[g4], t));
-      else if (st == 2) pw_exp_fma(pp[2 * e + 1], tb_[e], nn[2 * e + 1], sT[2 * e + 1], alphau, f4(ma[g4], t + 1));
+      else if (st == 1) pw_exp_fma(pp[2 * e], ta_[e], nn[2 * e], sT[2 * e], alphau, mu_of(e, 0));
+      else if (st == 2) pw_exp_fma(pp[2 * e + 1], tb_[e], nn[2 * e + 1], sT[2 * e + 1], alphau, mu_of(e, 1));
       else if (st == 3) pw_mul2(ta_[e], tb_[e], pp[2 * e], nn[2 * e], pp[2 * e + 1], nn[2 * e + 1]);
       else if (st == 4) pw_cvt(pk[e], pp[2 * e], pp[2 * e + 1]);
       else pw_cvt(pdk[e], ta_[e], tb_[e]);
     };
     // pass K: P, N alone (float32, for gZ and gZt) as 8 x 3 pieces
     auto pw1k_op = [&](int u) {
-      const int e = 2 * (u / 6) + (u & 1), st = (u % 6) >> 1, g4 = e >> 1, t = (2 * e) & 3;
+      const int e = 2 * (u / 6) + (u & 1), st = (u % 6) >> 1;
       if (st == 0) pw_scores(e);
-      else if (st == 1) pw_exp_fma(pp[2 * e], ta_[e], nn[2 * e], sT[2 * e], alphau, f4(ma[g4], t));
-      else pw_exp_fma(pp[2 * e + 1], tb_[e], nn[2 * e + 1], sT[2 * e + 1], alphau, f4(ma[g4], t + 1));
+      else if (st == 1) pw_exp_fma(pp[2 * e], ta_[e], nn[2 * e], sT[2 * e], alphau, mu_of(e, 0));
+      else pw_exp_fma(pp[2 * e + 1], tb_[e], nn[2 * e + 1], sT[2 * e + 1], alphau, mu_of(e, 1));
     };
     // gZ, gZt of the block as a stream of 8 x 5 pieces (E, DF come with sig1, dsig already subtracted)
     auto pw2_op = [&](int u) {
@@ -245,12 +306,14 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
           if (x < NKS) rtg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_TG + k2 * 32);
           else rg[k2] = lds_read16((k2 & 1) ? ro : re, OFF_G + k2 * 32);
         }
+        if (!PQ) {
 #pragma unroll
-        TVM_SHARE(x, m, 12, NS) {  // -sig1 and -dsig of the block first (the first products of E start from them), then lse, stats of half 0
-          if (x < 4) sa[x] = lds_read_f4(rv, 768 + x * 32);
-          else if (x < 8) da[x - 4] = lds_read_f4(rv, 512 + (x - 4) * 32);
-          else if (x < 10) la[x - 8] = lds_read_f4(rv, (x - 8) * 32);
-          else ma[x - 10] = lds_read_f4(rv, 256 + (x - 10) * 32);
+          TVM_SHARE(x, m, 12, NS) {  // -sig1 and -dsig of the block first (the first products of E start from them), then lse, stats of half 0
+            if (x < 4) sa[x] = lds_read_f4(rv, 768 + x * 32);
+            else if (x < 8) da[x - 4] = lds_read_f4(rv, 512 + (x - 4) * 32);
+            else if (x < 10) la[x - 8] = lds_read_f4(rv, (x - 8) * 32);
+            else ma[x - 10] = lds_read_f4(rv, 256 + (x - 10) * 32);
+          }
         }
       }
 #pragma unroll
@@ -279,13 +342,13 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
         for (int u = kPwV.first[m]; u < kPwV.first[m + 1]; ++u) pw1v_op(24 + u);
       }
     } else {
-      // ---- E, with P, N.  E and DF start from -sig1 and -dsig of their rows (queries).
+      // ---- E, with P, N.  E and DF start from -sig1 and -dsig of their queries.
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          sE[4 * g4 + t] = sa[g4][t];
-          sDF[4 * g4 + t] = da[g4][t];
+          sE[4 * g4 + t] = PQ ? ns1 : sa[g4][t];
+          sDF[4 * g4 + t] = PQ ? nds : da[g4][t];
         }
 #pragma unroll
       for (int m = 0; m < NE; ++m) {
@@ -299,7 +362,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
           if ((x & 1) == 0) xT[d2] = lds_read_tr(tl, th, tr_imm(0, d2));
           else txT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(0, d2));
         }
-        if (m < FS) {
+        if (m < FS && !PQ) {
 #pragma unroll
           TVM_SHARE(x, m, 4, FS) {  // lse, stats of half 1
             if (x < 2) la[2 + x] = lds_read_f4(rv, (2 + x) * 32);
@@ -369,7 +432,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
 
   // One copy of the whole-tile code serves every whole tile; tiles that do not exist are "fetched" as the last
   // tile again.
-  const int nfull = s.M >> 5;  // tiles without queries beyond M
+  const int nfull = nstr >> 5;  // tiles without rows beyond the end
   unsigned st0 = lds0, st1 = lds0 + BUF, st2 = lds0 + 2 * BUF;  // stage of this tile, of the next one, the free one
   for (int t = 0; t < nfull; ++t) {
     tile(std::false_type{}, st0, st1, st2, t * 32, min((t + 2) * 32, ilast), t + 3 >= nt, t + 1 == nt);
@@ -395,35 +458,53 @@ __global__ __launch_bounds__(kNT, 1) void bwd_col_pass_kernel(
     const unsigned lw = lds0 + wave * REG;
     const int row0 = fb * kFix + wave * 32;
     const float scale = PV ? 1.f : s.alpha;
-    store_tile_coalesced<NDB>(lw, out0 + base, s.sn, row0, s.N, s.D, a0, scale, lane);
-    store_tile_coalesced<NDB>(lw, out1 + base, s.sn, row0, s.N, s.D, a1, scale, lane);
+    store_tile_coalesced<NDB>(lw, out0 + base, fsn, row0, nfix, s.D, a0, scale, lane);
+    store_tile_coalesced<NDB>(lw, out1 + base, fsn, row0, nfix, s.D, a1, scale, lane);
   }
 }
 
 template <int DK, int DV, bool HAS_G>
-hipError_t launch(const Shape& s, const BwdArgs& a, hipStream_t st) {
+hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   const int nfb = (s.N + kFix - 1) / kFix;
   const dim3 grid(nfb * s.B * s.H), block(kNT);
   // pass K first: it is the longer one
-  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 2, HAS_G>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
-                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse2, a.stats,
-                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dk, (bf16*)a.dtk);
+  hipLaunchKernelGGL((bwd_pass_kernel<DK, DV, 2, HAS_G>), grid, block, 0, st, s, (const bf16*)a.k, (const bf16*)a.tk,
+                     (const bf16*)a.v, (const bf16*)a.tv, (const bf16*)a.q, (const bf16*)a.tq, (const bf16*)a.gTO,
+                     (const bf16*)a.gO, a.lse2, a.stats, a.dsig, a.sig1, nullptr, 1, nullptr, nullptr, (bf16*)a.dk,
+                     (bf16*)a.dtk);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((bwd_col_pass_kernel<DK, DV, 1, HAS_G>), grid, block, 0, st, s, (const bf16*)a.q, (const bf16*)a.k,
-                     (const bf16*)a.v, (const bf16*)a.tq, (const bf16*)a.tk, (const bf16*)a.tv, a.lse2, a.stats,
-                     (const bf16*)a.gO, (const bf16*)a.gTO, a.dsig, a.sig1, (bf16*)a.dv, (bf16*)a.dtv);
+  hipLaunchKernelGGL((bwd_pass_kernel<DK, DV, 1, HAS_G>), grid, block, 0, st, s, (const bf16*)a.k, (const bf16*)a.tk,
+                     (const bf16*)a.v, (const bf16*)a.tv, (const bf16*)a.q, (const bf16*)a.tq, (const bf16*)a.gTO,
+                     (const bf16*)a.gO, a.lse2, a.stats, a.dsig, a.sig1, nullptr, 1, nullptr, nullptr, (bf16*)a.dv,
+                     (bf16*)a.dtv);
+  return hipGetLastError();
+}
+
+template <int DK, int DV>
+hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws) {
+  const int nfb = (s.M + kFix - 1) / kFix;
+  hipLaunchKernelGGL((bwd_pass_kernel<DK, DV, 3, true>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+                     (const bf16*)a.tq, (const bf16*)a.gTO, (const bf16*)a.gO, (const bf16*)a.k, (const bf16*)a.tk,
+                     (const bf16*)a.v, (const bf16*)a.tv, a.lse, a.stats, a.dsig, a.sig1, a.lse2, pipe_ws ? 1 : 0,
+                     (const bf16*)a.o, (const bf16*)a.to, (bf16*)a.dq, (bf16*)a.dtq);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Head dims 97..128, with both upstream gradients (a.mode 0) or with gTO alone (a.mode 2).  Needs the row vectors in
-// the workspace in the convention of the hand-scheduled kernels (dsig, sig1 negated and lse in log2 units).
+// Key side, head dims 97..128, with both upstream gradients (a.mode 0) or with gTO alone (a.mode 2).  Needs the row
+// vectors in the workspace in the convention of the hand-scheduled kernels (dsig, sig1 negated, lse in log2 units).
 hipError_t launch_bwd_col_pass(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 1 || s.D <= 96 || s.D > 128) return hipErrorNotSupported;
-  if (s.D <= 112) return a.mode == 0 ? launch<112, 128, true>(s, a, st) : launch<112, 128, false>(s, a, st);
-  return a.mode == 0 ? launch<128, 128, true>(s, a, st) : launch<128, 128, false>(s, a, st);
+  if (s.D <= 112) return a.mode == 0 ? launch_col<112, 128, true>(s, a, st) : launch_col<112, 128, false>(s, a, st);
+  return a.mode == 0 ? launch_col<128, 128, true>(s, a, st) : launch_col<128, 128, false>(s, a, st);
+}
+// Query side, head dims 97..128, both upstream gradients.  pipe_ws: the row vectors go to the workspace in that
+// convention (the passes above follow), else plain (the generic-order key-side kernel follows).
+hipError_t launch_bwd_row_pass(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws) {
+  if (a.mode != 0 || s.D <= 96 || s.D > 128) return hipErrorNotSupported;
+  return s.D <= 112 ? launch_row<112, 128>(s, a, st, pipe_ws) : launch_row<128, 128>(s, a, st, pipe_ws);
 }
 
 }  // namespace tvm

@@ -28,7 +28,7 @@ from paper_2511_19797_amd import build
 
 CSRC = os.path.join(os.path.dirname(build.__file__), "csrc")
 HAND_SCHEDULED = ["bwd_row_pipe.hip", "bwd_col_pipe.hip", "bwd_row_pipe_tangent.hip", "bwd_col_pipe_tangent.hip",
-                  "bwd_row_pipe_qknorm.hip", "bwd_col_pipe_qknorm.hip", "bwd_col_pass.hip"]
+                  "bwd_row_pipe_qknorm.hip", "bwd_col_pipe_qknorm.hip", "bwd_pass.hip"]
 
 REG = re.compile(r"\b([va])(?:(\d+)|\[(\d+):(\d+)\])")
 

@@ -73,16 +73,18 @@ def test_bf16_hand_scheduled_tile_boundaries(d):
 
 
 @pytest.mark.parametrize("d", [104, 112, 120, 128])
-def test_bf16_two_pass_key_side_tile_boundaries(d):
-    """Head dims above 96: from 65 queries on the key side of the backward runs as two hand-scheduled passes over
-    tiles of 32 queries (both instantiations: contraction padded to 112 and to 128).  Sequence lengths where that
-    pipeline changes shape: the last one-pass length and the first two-pass one, three and four tiles (the three
-    LDS stages wrap), one row more or fewer, a workgroup boundary of 128 keys, several workgroups per head; then
-    M != N either way round, with a ragged last tile on both sides.  Every element of all ten outputs."""
+def test_bf16_hand_scheduled_passes_tile_boundaries(d):
+    """Head dims above 96: with more than 64 keys the query side of the backward runs as one hand-scheduled pass over
+    tiles of 32 keys, with more than 64 queries the key side as two such passes over tiles of 32 queries (both
+    instantiations: contraction padded to 112 and to 128).  Sequence lengths where that pipeline changes shape: the
+    last length on the generic-order kernels and the first one on the passes, three and four tiles (the three LDS
+    stages wrap), one row more or fewer, a workgroup boundary of 128 rows, several workgroups per head; then M != N
+    either way round, with a ragged last tile on both sides, and with one side short enough for its generic-order
+    kernel next to the other side's passes (the row vectors change convention).  Every element of all ten outputs."""
     import dataclasses
     for N in (64, 65, 95, 96, 97, 127, 128, 129, 161, 320):
         run_case(wl.custom(1, 1, N, d, "bf16"), seed=30 + N % 7)
-    for M, N in ((65, 300), (300, 65), (130, 129)):
+    for M, N in ((65, 300), (300, 65), (130, 129), (40, 200), (200, 40)):
         w = dataclasses.replace(wl.custom(1, 2, N, d, "bf16"), M=M)
         run_case(w, seed=40 + M % 13)
 
