@@ -26,9 +26,9 @@ bool mfma_supported(const Shape& s, int dtype) {
 
 // Head dims above 96 with both gradients or with gTO alone: the key side runs as the two hand-scheduled passes unless
 // there are so few queries (two tiles of 32 at most) that a second launch costs more than the passes save (measured:
-// 64 queries 56 against 51 us, from 128 queries on the passes are ahead, 2.40 against 3.18 ms at 4096).  With both
-// gradients the query side runs as the hand-scheduled pass over the keys on the same terms (64 keys: 40 against 35 us,
-// 128: the same, 256: 105 against 115 us, 4096: 1.43 against 1.80 ms).
+// 64 queries 56 against 51 us, from 128 queries on the passes are ahead, 2.40 against 3.18 ms at 4096).  The query
+// side runs as the hand-scheduled pass over the keys on the same terms (64 keys: 40 against 35 us,
+// 128: the same, 256: 105 against 115 us, 4096: 1.43 against 1.80 ms); so does the query side of a call with gTO alone.
 static bool key_side_in_two_passes(const Shape& s) { return s.D > 96 && s.M > 64; }
 static bool query_side_as_pass(const Shape& s) { return s.D > 96 && s.N > 64; }
 
@@ -43,6 +43,7 @@ hipError_t launch_bwd_col_mfma(const Shape& s, const BwdArgs& a, hipStream_t st)
 }
 hipError_t launch_bwd_row_mfma(const Shape& s, const BwdArgs& a, hipStream_t st) {
   if (a.mode == 2 && s.D <= 96) return launch_bwd_row_pipe_tangent(s, a, st);
+  if (a.mode == 2 && query_side_as_pass(s)) return launch_bwd_row_pass(s, a, st, key_side_in_two_passes(s));
   if (a.mode != 0) return launch_bwd_row_onesided(s, a, st);
   if (s.D <= 96) return launch_bwd_row_pipe(s, a, st);
   // (either kernel leaves the row vectors in the workspace as the key side that follows reads them)

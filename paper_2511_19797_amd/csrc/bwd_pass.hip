@@ -27,9 +27,9 @@
 // forward, and Step 1's sums, formed here from the fragments and left in the workspace for the key side, which
 // runs afterwards), and the masked entries of a ragged last tile are keys.
 //
-// HAS_G = false is the pair of passes for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of App. C by
-// themselves): the products with G vanish (E phase: two per 16 head dims, DF = tG tV^T; OV: two per 32, dV += tG^T Pd,
-// dtV += tG^T P), and the G tile is neither fetched nor read.
+// HAS_G = false are the passes for a call without gO (the gradient of <gTO, tO> alone, Steps 1-6 of App. C by
+// themselves): the products with G vanish (E phase: two per 16 head dims, DF = tG tV^T, in pass Q DF = tV gTO^T; OV:
+// two per 32, dV += tG^T Pd, dtV += tG^T P), and the G tile is neither fetched nor read (pass Q: no fragments of gO).
 //
 // The translation unit is built with the machine scheduler off: source order is issue order.
 #include "pipe_ops.h"
@@ -65,7 +65,6 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
     int pipe_ws, const bf16* __restrict__ o, const bf16* __restrict__ to, bf16* __restrict__ out0,
     bf16* __restrict__ out1) {
   static_assert(PASS >= 1 && PASS <= 3, "pass V, K or Q");
-  static_assert(PASS != 3 || HAS_G, "pass Q takes both upstream gradients");
   constexpr bool PV = PASS == 1, PQ = PASS == 3;
   using TX = Tile<32, DV / 8, kNT / 64>;  // Q, tQ, G, tG: read both ways
   constexpr int OFF_TQ = TX::BYTES, OFF_G = 2 * TX::BYTES, OFF_TG = 3 * TX::BYTES, OFF_ROW = 4 * TX::BYTES;
@@ -74,7 +73,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
   __shared__ __attribute__((aligned(16))) char lds[3 * BUF];
   constexpr int NKS = DK / 16, NDB = DV / 32;
   constexpr int PG = HAS_G ? 3 : 2;          // products per step of the phases that G takes part in
-  constexpr int NTG = HAS_G ? 2 : 1;         // tiles of upstream gradients (tG and G, or tG alone)
+  constexpr int NTG = HAS_G || PQ ? 2 : 1;   // streamed tiles in the gradient slots (tG and G, or tG alone; pass Q: V and tV)
   constexpr int NS = 3 * NKS;                // products of the S phase
   constexpr int NE = PG * NKS;               // products of the E phase
   constexpr int NH = (PV ? PG : 3) * NDB;    // products of half the output phase of this pass
@@ -91,7 +90,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
   static constexpr Deal<NH> kPwV = deal_out<NH>(24, 0, NH, 24, C::pwv, C::base_h);
   static constexpr Deal<NE> kPwK = deal_out<NE>(24, FS, NE, 24, C::pwk, C::base_e);
   static constexpr Deal<NH> kPw2 = deal_out<NH>(20, 0, NH, 20, C::pw2, C::base_h);
-  constexpr int NTILE = HAS_G ? 4 : 3;        // tiles fetched per stage (the G tile's place stays empty without gO)
+  constexpr int NTILE = 2 + NTG;              // tiles fetched per stage (passes V, K: the G tile's place stays empty without gO)
   constexpr int NDMA = NTILE * TX::IPW + (PQ ? 0 : 1);  // wave-loads per wave and tile (passes V, K: the last is a row vector)
   constexpr int NQB = NS + NH;                // products that carry tile loads: S and the last phase
   constexpr int NDMA_PRE = NS * NDMA / NQB;   // wave-loads issued before the barrier (behind the products of S)
@@ -148,7 +147,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
   gld_frags<NKS>(tkf, f1 + base, fsn, j, nfix, s.D, hh);
   if (!PV) {
     gld_frags<NKS>(vf, f2 + base, fsn, j, nfix, s.D, hh);
-    gld_frags<NKS>(tvf, f3 + base, fsn, j, nfix, s.D, hh);
+    if (HAS_G || !PQ) gld_frags<NKS>(tvf, f3 + base, fsn, j, nfix, s.D, hh);
   }
   // pass Q: the row scalars of this lane's query.  Step 1 of App. C, fused: delta + Sigma_2 = gO.O + gTO.tO and
   // Sigma_1 = gTO.O from the same fragment layout (each half-wave holds half of the row); they are also written out
@@ -166,7 +165,7 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float oe = (float)of[kk][e], gte = (float)vf[kk][e];
-          ds = fmaf((float)tvf[kk][e], oe, ds);
+          if (HAS_G) ds = fmaf((float)tvf[kk][e], oe, ds);
           ds = fmaf(gte, (float)tof[kk][e], ds);
           s1 = fmaf(gte, oe, s1);
         }
@@ -354,8 +353,8 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
       for (int m = 0; m < NE; ++m) {
         const int kk = m / PG, w = m - PG * kk;
         if (w == 0) mfma_fix<RAG>(sE, rtg[kk], vf[kk]);
-        else if (w == 1) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
-        else mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
+        else if (w == 1 && (HAS_G || !PQ)) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
+        else mfma_fix<RAG>(sDF, rg[kk], vf[kk]);  // (pass Q without gO: DF = tV gTO^T is this product alone)
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NE) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
@@ -481,10 +480,10 @@ hipError_t launch_col(const Shape& s, const BwdArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int DK, int DV>
+template <int DK, int DV, bool HAS_G>
 hipError_t launch_row(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws) {
   const int nfb = (s.M + kFix - 1) / kFix;
-  hipLaunchKernelGGL((bwd_pass_kernel<DK, DV, 3, true>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
+  hipLaunchKernelGGL((bwd_pass_kernel<DK, DV, 3, HAS_G>), dim3(nfb * s.B * s.H), dim3(kNT), 0, st, s, (const bf16*)a.q,
                      (const bf16*)a.tq, (const bf16*)a.gTO, (const bf16*)a.gO, (const bf16*)a.k, (const bf16*)a.tk,
                      (const bf16*)a.v, (const bf16*)a.tv, a.lse, a.stats, a.dsig, a.sig1, a.lse2, pipe_ws ? 1 : 0,
                      (const bf16*)a.o, (const bf16*)a.to, (bf16*)a.dq, (bf16*)a.dtq);
@@ -500,11 +499,12 @@ hipError_t launch_bwd_col_pass(const Shape& s, const BwdArgs& a, hipStream_t st)
   if (s.D <= 112) return a.mode == 0 ? launch_col<112, 128, true>(s, a, st) : launch_col<112, 128, false>(s, a, st);
   return a.mode == 0 ? launch_col<128, 128, true>(s, a, st) : launch_col<128, 128, false>(s, a, st);
 }
-// Query side, head dims 97..128, both upstream gradients.  pipe_ws: the row vectors go to the workspace in that
-// convention (the passes above follow), else plain (the generic-order key-side kernel follows).
+// Query side, head dims 97..128, with both upstream gradients or with gTO alone.  pipe_ws: the row vectors go to the
+// workspace in that convention (the passes above follow), else plain (the generic-order key-side kernel follows).
 hipError_t launch_bwd_row_pass(const Shape& s, const BwdArgs& a, hipStream_t st, bool pipe_ws) {
-  if (a.mode != 0 || s.D <= 96 || s.D > 128) return hipErrorNotSupported;
-  return s.D <= 112 ? launch_row<112, 128>(s, a, st, pipe_ws) : launch_row<128, 128>(s, a, st, pipe_ws);
+  if (a.mode == 1 || s.D <= 96 || s.D > 128) return hipErrorNotSupported;
+  if (s.D <= 112) return a.mode == 0 ? launch_row<112, 128, true>(s, a, st, pipe_ws) : launch_row<112, 128, false>(s, a, st, pipe_ws);
+  return a.mode == 0 ? launch_row<128, 128, true>(s, a, st, pipe_ws) : launch_row<128, 128, false>(s, a, st, pipe_ws);
 }
 
 }  // namespace tvm

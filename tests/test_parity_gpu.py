@@ -418,6 +418,8 @@ def test_one_sided_backward_full_size():
 @pytest.mark.parametrize("B,H,M,N,d,dtype", [
     (1, 2, 100, 260, 72, "bf16"), (2, 1, 300, 64, 64, "bf16"), (1, 1, 1, 70, 16, "bf16"), (1, 2, 129, 17, 32, "bf16"),
     (1, 1, 65, 193, 96, "bf16"), (1, 1, 200, 130, 128, "bf16"), (1, 2, 40, 70, 32, "f32"), (1, 1, 70, 33, 136, "bf16"),
+    # head dims above 96 with one side on its generic-order kernel and the other on the hand-scheduled passes
+    (1, 2, 40, 200, 104, "bf16"), (1, 1, 200, 40, 128, "bf16"),
 ])
 def test_queries_and_keys_differ(B, H, M, N, d, dtype):
     """Cross-attention shapes (the paper's Background allows M != N): every element of all ten outputs against
