@@ -24,7 +24,8 @@
 //
 // grad W contracts over all tokens of both sets (32K rows at DiT-XL/2 512 px) for few output tiles, so the token
 // range is split over several workgroups per tile; each leaves a float32 partial tile in the workspace and a second
-// small kernel adds them in a fixed order (no atomics) and rounds once.  gb is a column sum of gy, done the same way.
+// small kernel adds them in a fixed order (no atomics) and rounds once.  gb is a column sum of gy: partial sums over
+// row ranges, then one kernel that adds those.
 #include <type_traits>
 
 #include "mfma_tiles.h"
@@ -412,6 +413,38 @@ __global__ __launch_bounds__(256) void colsum_kernel(const bf16* __restrict__ gy
   }
 }
 
+// Adds the `chunks` partial rows of the column sums, part[chunk][f], and rounds once to bf16.  A workgroup of 16
+// waves takes 64 columns: wave w adds rows w, w + 16, ... (16 loads in flight), and the 16 sums meet in LDS, in a
+// fixed order.  (Few output elements and many rows: with a thread per column walking all rows in turn, one or two
+// workgroups spent 70 us on 256 rows of dependent latencies.)
+__global__ __launch_bounds__(1024) void bias_sum_kernel(const float* __restrict__ part, int chunks, int F,
+                                                        bf16* __restrict__ out) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int f = blockIdx.x * 64 + lane;
+  float acc = 0.f;
+  if (f < F) {
+    for (int c0 = wave; c0 < chunks; c0 += 256) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + 16 * u;
+        v[u] = c < chunks ? part[(long long)c * F + f] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) acc += v[u];
+    }
+  }
+  red[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && f < F) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) t += red[w][lane];
+    out[f] = (bf16)t;
+  }
+}
+
 // The shapes in use: forward and grad x, grad W
 using CfgF = Cfg<2, 4, 4, 2, 2, 1>;
 using CfgX = Cfg<2, 4, 4, 2, 2, 1>;
@@ -537,8 +570,7 @@ hipError_t launch_linear_bwd(int R, int K, int F, long long ldx, long long ldy, 
     hipLaunchKernelGGL(colsum_kernel, dim3((F + 511) / 512, chunks), dim3(256), 0, st, (const bf16*)gy, R, F, ldy, chunks, bp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((F / 8 + 255) / 256)), dim3(256), 0, st, bp, chunks, (long long)F,
-                       (bf16*)gbias);
+    hipLaunchKernelGGL(bias_sum_kernel, dim3((unsigned)((F + 63) / 64)), dim3(1024), 0, st, bp, chunks, F, (bf16*)gbias);
     return hipGetLastError();
   }
   return hipSuccess;
