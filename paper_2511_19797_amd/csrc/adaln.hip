@@ -414,6 +414,35 @@ __device__ __forceinline__ void mod_bwd_body(const float* part, long long stride
   }
 }
 
+// With many partial rows per batch element the two (or one) workgroups per element of the kernels below would spend
+// their time fetching them (64 rows: 15 us, a CU's worth of bandwidth each): this kernel adds the nwg rows of W floats
+// of batch element blockIdx.y first, 64 chunks of 16 bytes per workgroup (wave q takes quarter q of the rows, the
+// quarters meet in LDS in a fixed order), and leaves one row per element for them.
+__global__ __launch_bounds__(256) void part_rows_sum_kernel(const float* __restrict__ part, int nwg, int W,
+                                                            float* __restrict__ out) {
+  __shared__ float4 red[4][64];
+  const int q = threadIdx.x >> 6, ct = threadIdx.x & 63, b = blockIdx.y;
+  const int c = (blockIdx.x * 64 + ct) * 4;
+  const bool on = c < W;
+  const float* p = part + (long long)b * nwg * W + (on ? c : 0);
+  const int g0 = (nwg * q) / 4, g1 = (nwg * (q + 1)) / 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 16
+  for (int g = g0; g < g1; ++g) {
+    const float4 v = *reinterpret_cast<const float4*>(p + (long long)g * W);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  red[q][ct] = s;
+  __syncthreads();
+  if (q == 0 && on) {
+    const float4 r0 = red[0][ct], r1 = red[1][ct], r2 = red[2][ct], r3 = red[3][ct];
+    const float4 t = make_float4((r0.x + r1.x) + (r2.x + r3.x), (r0.y + r1.y) + (r2.y + r3.y),
+                                 (r0.z + r1.z) + (r2.z + r3.z), (r0.w + r1.w) + (r2.w + r3.w));
+    *reinterpret_cast<float4*>(out + (long long)b * W + c) = t;
+  }
+}
+constexpr int kPartRowsDirect = 16;  // up to this many partial rows the end kernels fetch them themselves
+
 // Workgroup (which, b): which = 0: g_ah, g_tah and the gradients of a, ta; which = 1: g_bh, g_tbh and those of b, tb.
 __global__ __launch_bounds__(kModNT) void adaln_mod_bwd_kernel(AdalnArgs a) {
   extern __shared__ float qsum[];
@@ -641,7 +670,17 @@ hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(2, a.B), dim3(kModNT), (size_t)kModQ * 2 * a.C * sizeof(float), st, a);
+  AdalnArgs m = a;
+  if (a.nwg > kPartRowsDirect) {  // the partial rows of an element are added first, into the row behind all of them
+    const int W = 4 * a.C;
+    float* sum = a.part + (long long)a.B * a.nwg * W;
+    hipLaunchKernelGGL(part_rows_sum_kernel, dim3((W / 4 + 63) / 64, a.B), dim3(256), 0, st, a.part, a.nwg, W, sum);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    m.part = sum;
+    m.nwg = 1;
+  }
+  hipLaunchKernelGGL(adaln_mod_bwd_kernel, dim3(2, a.B), dim3(kModNT), (size_t)kModQ * 2 * a.C * sizeof(float), st, m);
   return hipGetLastError();
 }
 

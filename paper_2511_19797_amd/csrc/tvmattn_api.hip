@@ -542,8 +542,8 @@ int adaln_check(int B, int T, int C, int dtype, float eps) {
 }
 inline long long tok_bytes(int B, int T, int C, int dtype) { return (long long)B * T * C * esz_of(dtype); }
 inline long long mod_bytes(int B, int C) { return (long long)B * C * 4; }
-size_t adaln_part_bytes(int B, int T, int C) {
-  return pad256((size_t)B * tvm::adaln_wgs(B, T, true, false) * 4 * C * sizeof(float));
+size_t adaln_part_bytes(int B, int T, int C) {  // per-workgroup sums over tokens, and one row per element for their sums
+  return pad256((size_t)B * (tvm::adaln_wgs(B, T, true, false) + 1) * 4 * C * sizeof(float));
 }
 }  // namespace
 
