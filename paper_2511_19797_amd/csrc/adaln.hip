@@ -671,7 +671,7 @@ hipError_t launch_adaln_bwd(const AdalnArgs& a, int dtype, hipStream_t st) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   AdalnArgs m = a;
-  if (a.nwg > kPartRowsDirect) {  // the partial rows of an element are added first, into the row behind all of them
+  if (a.nwg > kPartRowsDirect) {  // the partial rows of an element are added first, into [B][4][C] behind all of them
     const int W = 4 * a.C;
     float* sum = a.part + (long long)a.B * a.nwg * W;
     hipLaunchKernelGGL(part_rows_sum_kernel, dim3((W / 4 + 63) / 64, a.B), dim3(256), 0, st, a.part, a.nwg, W, sum);

@@ -112,7 +112,7 @@ struct AdalnArgs {
   const void *gres = nullptr, *gtres = nullptr;  // backward, optional (both or neither): added to the gradients of x, tx
   const float *a, *ta, *b, *tb;     // [B,C] float32
   void *y, *ty;                     // forward: outputs; backward: gradients of x and tx
-  float* part;                      // backward workspace [B][nwg][4][C]: per-workgroup sums over tokens, then [B][4][C]: their sums
+  float* part;                      // backward workspace [B][nwg][4][C]: per-workgroup sums over tokens
   float *ga, *gta, *gb, *gtb;       // backward: gradients of a, ta, b, tb
   int B, T, C, nwg;                 // nwg: workgroups per batch element
   float eps;
