@@ -517,11 +517,22 @@ def block_step(w, steps, seed=2024):
         z, tz, saved = block.block_jvp_fwd(x, tx, dm, dtm, dp, w.H, 1e-6, 1e-6)
         block.block_jvp_bwd(x, tx, dm, dtm, dp, w.H, 1e-6, 1e-6, saved, gz, gtz)
     ms = _timed_ms(step, max(3, steps // 2))
+    # the same chain captured in a HIP graph and replayed (about 50 launches per step: what the gaps between them cost)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    ms_graph = _timed_ms(graph.replay, max(3, steps // 2))
     R, C = w.B * w.Mq, w.H * w.d
     gemm = 12.0 * R * C * (3 * C + C + 4 * C + 4 * C)          # the four layers, forward 4 R K F + backward 8 R K F
     attn = 42.0 * w.B * w.H * w.Mq * w.N * w.d
     return {"ms_fwd_bwd": ms, "algorithmic_tflops": (gemm + attn) / (ms * 1e-3) / 1e12,
-            "flops": {"linear_layers": gemm, "attention": attn}}
+            "ms_fwd_bwd_graph_replay": ms_graph, "flops": {"linear_layers": gemm, "attention": attn}}
 
 
 def peaks(steps):

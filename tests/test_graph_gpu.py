@@ -115,3 +115,40 @@ def test_captured_block_pieces_replay_bit_for_bit():
         for i, (got, want) in enumerate(zip(bufs, ref)):
             for j, (x, y) in enumerate(zip(got, want)):
                 assert torch.equal(x, y), f"replay {replay}: output {j} of call {i} differs from the eager call"
+
+
+@pytest.mark.parametrize("B,T,H,d,hidden", [(2, 200, 4, 72, 1152), (1, 160, 2, 128, 512)])
+def test_captured_block_chain_replays_bit_for_bit(B, T, H, d, hidden):
+    """The whole block chain (paper_2511_19797_amd/block.py: about fifty launches, forward and backward, its
+    intermediates allocated inside the capture from the graph's memory pool) captured once and replayed: the block's
+    outputs and every gradient equal the eager chain's bit for bit on every replay, with eager work in between."""
+    from paper_2511_19797_amd import block
+    announce(f"graph capture of the block chain B{B} T{T} H{H} d{d} hidden{hidden}")
+    x, tx, mods, tmods, params, gz, gtz = wl.make_block_inputs(B, T, H, d, hidden, seed=5)
+    x, tx, gz, gtz = x.cuda(), tx.cuda(), gz.cuda(), gtz.cuda()
+    dm, dtm, dp = ({k: v.cuda() for k, v in m.items()} for m in (mods, tmods, params))
+
+    def step():
+        z, tz, saved = block.block_jvp_fwd(x, tx, dm, dtm, dp, H, 1e-6, 1e-6)
+        g = block.block_jvp_bwd(x, tx, dm, dtm, dp, H, 1e-6, 1e-6, saved, gz, gtz)
+        return [("z", z), ("tz", tz)] + sorted(g.items())
+
+    ref = [(n, t.clone()) for n, t in step()]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        outs = step()
+    for replay in range(3):
+        for _, t in outs:  # eager work between the replays: the outputs are wiped with a fill kernel
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (name, got), (rname, want) in zip(outs, ref):
+            assert name == rname and torch.equal(got, want), f"replay {replay}: {name} differs from the eager chain"
