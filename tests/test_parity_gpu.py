@@ -107,7 +107,7 @@ def test_inputs_sliced_from_a_fused_projection():
     """q, k, v (and the tangents, and the upstream gradients) sliced out of fused [B,N,3,H,D] buffers: not dense, so
     the outputs must be allocated with the inputs' strides.  Forward and backward against the oracle, matrix-core
     and plain-ALU paths."""
-    for dtype, d, N in (("bf16", 72, 200), ("bf16", 64, 520), ("f32", 24, 70)):
+    for dtype, d, N in (("bf16", 72, 200), ("bf16", 64, 520), ("bf16", 128, 200), ("f32", 24, 70)):
         w = wl.custom(2, 3, N, d, dtype)
         announce(f"fused-QKV slices {w}")
         inp = wl.make_inputs(w, 15)
@@ -135,7 +135,7 @@ def test_bf16_mfma_scaled_inputs():
 
 def test_strided_layout_bnhd():
     """Tensors stored [B,N,H,D] and viewed as [B,H,N,D] (what a fused QKV projection hands over)."""
-    for dtype, d in (("bf16", 72), ("f32", 24)):
+    for dtype, d in (("bf16", 72), ("bf16", 112), ("f32", 24)):
         w = wl.custom(2, 3, 150, d, dtype)
         announce(f"strided {w}")
         inp = wl.make_inputs(w, 9)
@@ -151,7 +151,7 @@ def test_strided_layout_bnhd():
 def test_strided_layout_with_more_queries_than_keys():
     """Query side stored [B,M,H,D], key side contiguous [B,H,N,D], M != N: the two sides have their own strides."""
     import dataclasses
-    for dtype, d in (("bf16", 72), ("f32", 24)):
+    for dtype, d in (("bf16", 72), ("bf16", 128), ("f32", 24)):
         w = dataclasses.replace(wl.custom(2, 3, 90, d, dtype), M=150)
         announce(f"strided, M != N {w}")
         inp = wl.make_inputs(w, 10)
@@ -165,8 +165,9 @@ def test_strided_layout_with_more_queries_than_keys():
         pu.check_heads(w, inp, (o, to, lse, stats), grads, pu.all_heads(w))
 
 
-def test_bitwise_reproducible():
-    w = wl.custom(2, 2, 333, 72, "bf16")
+@pytest.mark.parametrize("d", [72, 128])
+def test_bitwise_reproducible(d):
+    w = wl.custom(2, 2, 333, d, "bf16")
     announce(f"determinism {w}")
     inp = wl.make_inputs(w, 10)
     f1, g1 = pu.run_gpu(inp)
@@ -175,8 +176,9 @@ def test_bitwise_reproducible():
         assert torch.equal(a, b)
 
 
-def test_zero_tangents_and_zero_grads_on_gpu():
-    w = wl.custom(1, 2, 100, 72, "bf16")
+@pytest.mark.parametrize("d", [72, 120])
+def test_zero_tangents_and_zero_grads_on_gpu(d):
+    w = wl.custom(1, 2, 100, d, "bf16")
     announce(f"zero tangents {w}")
     inp = wl.make_inputs(w, 11)
     for n in ("tq", "tk", "tv"):
@@ -201,7 +203,15 @@ def test_growing_scores_force_rescales():
 def test_backward_is_linear_in_upstream_gradients():
     """bwd(a gO1 + gO2, a gTO1 + gTO2) = a bwd(gO1, gTO1) + bwd(gO2, gTO2) up to bf16 rounding of the
     outputs; with power-of-two a and the second pair zero it is exact scaling."""
-    w = wl.custom(1, 2, 200, 72, "bf16")
+    _backward_scales_exactly(72)
+
+
+def test_backward_is_linear_in_upstream_gradients_wide_heads():
+    _backward_scales_exactly(128)
+
+
+def _backward_scales_exactly(d):
+    w = wl.custom(1, 2, 200, d, "bf16")
     announce(f"linearity {w}")
     inp = wl.make_inputs(w, 14)
     fwd, g1 = pu.run_gpu(inp)
