@@ -16,7 +16,7 @@
 // every block ends with the workgroup barrier that frees its stage:
 //
 //   pass V   S | P, N, Pd of half 0 (nothing to hide behind) | OV(0) with P, N, Pd of half 1 | barrier | OV(1)
-//   pass K   S | E with P, N | gZ, gZt of half 0 (nothing to hide behind) | OK(0) with gZ, gZt of half 1 | barrier | OK(1)
+//   pass K   S | E (its products first, then those of DF) with P, N, then gZt | OK(0) (the products with gZt first) with gZ | barrier | OK(1)
 //
 // The tile after next is fetched behind the products of S and of the last phase, which carry no pointwise work.
 //
@@ -48,6 +48,8 @@ __device__ __forceinline__ f32x4 lds_read_f4(unsigned addr, int imm) {
   return *(lp)(uintptr_t)(addr + (unsigned)imm);
 }
 __device__ __forceinline__ float f4(const f32x4& v, int t) { return v[t]; }
+// landed() of pipe_ops.h for one tile
+__device__ __forceinline__ void landed1(f32x16& a) { asm volatile("" : "+v"(a)); }
 
 // PASS 1: dV, dtV into out0, out1;  PASS 2: dK, dtK;  PASS 3: dQ, dtQ.
 //   f0..f3: the fixed side's tensors (passes V, K: k, tk, v, tv;  pass Q: q, tq, gTO, gO)
@@ -88,8 +90,25 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
     static constexpr int base_e(int v) { return 8 * share_count(v, 2 * NDB, NE) + (v < FS && !PQ ? 4 * share_count(v, 4, FS) : 0); }
   };
   static constexpr Deal<NH> kPwV = deal_out<NH>(24, 0, NH, 24, C::pwv, C::base_h);
-  static constexpr Deal<NE> kPwK = deal_out<NE>(24, FS, NE, 24, C::pwk, C::base_e);
-  static constexpr Deal<NH> kPw2 = deal_out<NH>(20, 0, NH, 20, C::pw2, C::base_h);
+  // Passes K, Q.  E phase: the NKS products of E come first, so that E has landed (four products on) while those of
+  // DF still run: behind the products from FS to ES the 24 pieces of P, N, from ES on the 16 pieces of gZt = P o E
+  // (both halves).  OK(0) starts with the 2 NDB products that take gZt alone; from its fifth product on (DF has
+  // landed) the 12 pieces of gZ of half 0, done when its products with gZ begin, then the 12 of half 1.
+  static constexpr int ES = NKS + 4 > FS + 2 * (NE - FS) / 3 ? NKS + 4 : FS + 2 * (NE - FS) / 3;
+  static_assert(ES < NE, "room behind the products of DF for the pieces of gZt");
+  struct CE {
+    static constexpr int cost(int u) { return u < 24 ? C::pwk(u) : 8; }
+    static constexpr Deal<NE> deal() {
+      Deal<NE> d{};
+      for (int i = 0; i <= NE; ++i) d.first[i] = i < FS ? 0 : 40;
+      deal_range(d, 0, 24, FS, ES, cost, C::base_e);
+      deal_range(d, 24, 40, ES, NE, cost, C::base_e);
+      d.first[NE] = 40;
+      return d;
+    }
+  };
+  static constexpr Deal<NE> kPwE = CE::deal();
+  static constexpr Deal<NH> kPwD = deal_out<NH>(24, 4, 2 * NDB, 12, C::pw2, C::base_h);
   constexpr int NTILE = 2 + NTG;              // tiles fetched per stage (passes V, K: the G tile's place stays empty without gO)
   constexpr int NDMA = NTILE * TX::IPW + (PQ ? 0 : 1);  // wave-loads per wave and tile (passes V, K: the last is a row vector)
   constexpr int NQB = NS + NH;                // products that carry tile loads: S and the last phase
@@ -262,13 +281,17 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
       else if (st == 1) pw_exp_fma(pp[2 * e], ta_[e], nn[2 * e], sT[2 * e], alphau, mu_of(e, 0));
       else pw_exp_fma(pp[2 * e + 1], tb_[e], nn[2 * e + 1], sT[2 * e + 1], alphau, mu_of(e, 1));
     };
-    // gZ, gZt of the block as a stream of 8 x 5 pieces (E, DF come with sig1, dsig already subtracted)
-    auto pw2_op = [&](int u) {
-      const int e = 2 * (u / 10) + (u & 1), st = (u % 10) >> 1;  // two pairs take turns here too
+    // gZt = P o E of the block as a stream of 8 x 2 pieces, gZ = P o DF + gZt o N as one of 8 x 3 (E, DF come with
+    // sig1, dsig already subtracted); two pairs take turns here too
+    auto pw2e_op = [&](int u) {
+      const int e = 2 * (u / 4) + (u & 1), st = (u % 4) >> 1;
       if (st == 0) pw_mul2(ta_[e], tb_[e], pp[2 * e], sE[2 * e], pp[2 * e + 1], sE[2 * e + 1]);
-      else if (st == 1) pw_mul2(wa[e], wb[e], pp[2 * e], sDF[2 * e], pp[2 * e + 1], sDF[2 * e + 1]);
-      else if (st == 2) pw_fmac2(wa[e], wb[e], ta_[e], nn[2 * e], tb_[e], nn[2 * e + 1]);
-      else if (st == 3) pw_cvt(gzt[e], ta_[e], tb_[e]);
+      else pw_cvt(gzt[e], ta_[e], tb_[e]);
+    };
+    auto pw2d_op = [&](int u) {
+      const int e = 2 * (u / 6) + (u & 1), st = (u % 6) >> 1;
+      if (st == 0) pw_mul2(wa[e], wb[e], pp[2 * e], sDF[2 * e], pp[2 * e + 1], sDF[2 * e + 1]);
+      else if (st == 1) pw_fmac2(wa[e], wb[e], ta_[e], nn[2 * e], tb_[e], nn[2 * e + 1]);
       else pw_cvt(gz[e], wa[e], wb[e]);
     };
     auto tr_imm = [&](int cc, int db) { return cc * 16 * TX::PCH * 16 + db * 64; };
@@ -351,10 +374,21 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
         }
 #pragma unroll
       for (int m = 0; m < NE; ++m) {
-        const int kk = m / PG, w = m - PG * kk;
-        if (w == 0) mfma_fix<RAG>(sE, rtg[kk], vf[kk]);
-        else if (w == 1 && (HAS_G || !PQ)) mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
-        else mfma_fix<RAG>(sDF, rg[kk], vf[kk]);  // (pass Q without gO: DF = tV gTO^T is this product alone)
+        // (the first product of either tile in the padded form: the copies of its start values may sit right in front)
+        if (m == 0) {
+          mfma_fix<true>(sE, rtg[0], vf[0]);
+        } else if (m < NKS) {
+          mfma_fix<RAG>(sE, rtg[m], vf[m]);
+        } else {
+          const int kk = (m - NKS) / (PG - 1), w = (m - NKS) - (PG - 1) * kk;
+          if (w == 0 && (HAS_G || !PQ)) {
+            if (m == NKS) mfma_fix<true>(sDF, rtg[kk], tvf[kk]);
+            else mfma_fix<RAG>(sDF, rtg[kk], tvf[kk]);
+          } else {  // (pass Q without gO: DF = tV gTO^T is this product alone)
+            if (m == NKS) mfma_fix<true>(sDF, rg[kk], vf[kk]);
+            else mfma_fix<RAG>(sDF, rg[kk], vf[kk]);
+          }
+        }
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NE) {  // Q^T, tQ^T of half 0
           const int d2 = x >> 1;
@@ -369,31 +403,34 @@ __global__ __launch_bounds__(kNT, 1) void bwd_pass_kernel(
           }
         }
         if (m == FS) landed(sS, sT);
-        if (m >= FS) {
+        if (m == ES) landed1(sE);  // (at least four products after the last one of E)
 #pragma unroll
-          for (int u = kPwK.first[m]; u < kPwK.first[m + 1]; ++u) pw1k_op(u);
+        for (int u = kPwE.first[m]; u < kPwE.first[m + 1]; ++u) {
+          if (u < 24) pw1k_op(u);
+          else pw2e_op(u - 24);
         }
       }
-      // ---- gZ, gZt of half 0: nothing to hide behind
-      mfma_settle();
-      landed(sE, sDF);
-#pragma unroll
-      for (int u = 0; u < 20; ++u) pw2_op(u);
-      // ---- OK(0), with gZ, gZt of half 1
+      // ---- OK(0): the products with gZt first; gZ of half 0 behind them, gZ of half 1 behind those with gZ of half 0
 #pragma unroll
       for (int m = 0; m < NH; ++m) {
-        const int db = m / 3, w = m - 3 * db;
-        if (w == 0) { if (m == 0) mfma_acc<true>(a0[db], xT[db], frag_of(gz, 0)); else mfma_acc<RAG>(a0[db], xT[db], frag_of(gz, 0)); }
-        else if (w == 1) mfma_acc<RAG>(a0[db], txT[db], frag_of(gzt, 0));
-        else mfma_acc<RAG>(a1[db], xT[db], frag_of(gzt, 0));
+        if (m < 2 * NDB) {
+          const int db = m >> 1;
+          if ((m & 1) == 0) { if (m == 0) mfma_acc<true>(a0[db], txT[db], frag_of(gzt, 0)); else mfma_acc<RAG>(a0[db], txT[db], frag_of(gzt, 0)); }
+          else mfma_acc<RAG>(a1[db], xT[db], frag_of(gzt, 0));
+        } else {
+          const int db = m - 2 * NDB;
+          if (db == 0) mfma_acc<true>(a0[db], xT[db], frag_of(gz, 0));
+          else mfma_acc<RAG>(a0[db], xT[db], frag_of(gz, 0));
+        }
 #pragma unroll
         TVM_SHARE(x, m, 2 * NDB, NH) {  // Q^T, tQ^T of half 1
           const int d2 = x >> 1;
           if ((x & 1) == 0) yT[d2] = lds_read_tr(tl, th, tr_imm(1, d2));
           else tyT[d2] = lds_read_tr(tl, th, OFF_TQ + tr_imm(1, d2));
         }
+        if (m == 4) landed1(sDF);  // (four products after the last one of DF)
 #pragma unroll
-        for (int u = kPw2.first[m]; u < kPw2.first[m + 1]; ++u) pw2_op(20 + u);
+        for (int u = kPwD.first[m]; u < kPwD.first[m + 1]; ++u) pw2d_op(u);
       }
     }
     // every read of this stage has been issued; the next tile (fetched during the previous one) must have landed
