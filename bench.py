@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 
 METRIC = "fwd+JVP and bwd attention TFLOP/s & %MFMA peak at DiT-XL/2 N=256/1024"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+NOMINAL_MHZ = 2400.0        # the shader clock that figure is quoted at (256 CUs x 4 SIMDs x 1024 flop per cycle)
 PEAK_HBM_GBS = 8000.0
 
 # Algorithmic flops per launch, in units of B*H*N^2*d.  The six score-type products of the
@@ -321,6 +322,61 @@ def _timed_ms(fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def _sclk_under(fn, secs=1.6):
+    """Shader clock in MHz as rocm-smi reports it about a second into a load: `fn` (one asynchronous call) is kept
+    running for `secs` seconds while a thread asks rocm-smi once.  None where rocm-smi is missing or says nothing
+    that parses.  (The card holds its nominal 2400 MHz under a copy and under bare matrix-core instructions, and
+    settles lower under kernels that also keep LDS, VALU and HBM busy: what they could reach at most scales with it.)"""
+    import re
+    import subprocess
+    import threading
+
+    import torch
+
+    got = []
+
+    def ask():
+        time.sleep(0.7)
+        try:
+            r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10)
+            m = re.search(r"sclk clock level:\s*\d+:\s*\((\d+)Mhz\)", r.stdout)
+            if m:
+                got.append(int(m.group(1)))
+        except Exception:
+            pass
+
+    th = threading.Thread(target=ask)
+    th.start()
+    t0, n = time.perf_counter(), 0
+    while time.perf_counter() - t0 < secs or th.is_alive():
+        fn()
+        n += 1
+        if n % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    th.join()
+    return got[0] if got else None
+
+
+def sustained_clock(w, seed=2024):
+    """The shader clock under the workload's own step (forward + backward back to back)."""
+    import torch
+
+    import paper_2511_19797_amd as tvm
+    from paper_2511_19797_amd import workloads as wl
+
+    dev = {n: t.cuda() for n, t in wl.make_inputs(w, seed).items()}
+    six = [dev[n] for n in wl.NAMES[:6]]
+    fo = tvm.tvmattn_jvp_fwd(*six)
+    go = tvm.tvmattn_jvp_bwd(*six, *fo, dev["gO"], dev["gTO"])
+    ws = torch.empty(max(tvm.tvmattn_jvp_bwd_workspace_bytes(six[0], k=six[1]), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        tvm.tvmattn_jvp_fwd(*six, out=fo)
+        tvm.tvmattn_jvp_bwd(*six, *fo, dev["gO"], dev["gTO"], out=go, workspace=ws)
+    return _sclk_under(step)
+
+
 def _hbm_cases(cases, steps):
     """cases: name -> (algorithmic bytes per call, callable).  Times each and prices it against 8 TB/s."""
     out = {}
@@ -562,6 +618,8 @@ def peaks(steps):
     assert flops[-1] > 0, "matrix-core rate kernel failed to launch"
     res = {"mfma_bf16_tflops": flops[-1] / (ms * 1e-3) / 1e12, "mfma_ms": ms,
            "mfma_note": "v_mfma_f32_32x32x16_bf16, 4 independent accumulators per wave, 2 waves per SIMD"}
+    if SIDE_RAMP_MS > 0:
+        res["mfma_sclk_mhz"] = _sclk_under(mfma)
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
     dst = torch.empty_like(src)
@@ -698,6 +756,12 @@ def main():
                 "paper_h100_bwd_ms": PAPER_H100_BWD_MS.get((sw.H, sw.N))})
     out["peaks"] = peaks(args.steps)
     out["roofline"]["frac_of_measured_mfma_rate"] = achieved / out["peaks"]["mfma_bf16_tflops"]
+    if args.ramp_ms > 0:  # (not in counter runs, which keep to a handful of launches per kernel)
+        mhz = sustained_clock(w)
+        out["clock"] = {"nominal_mhz": NOMINAL_MHZ, "sclk_mhz_under_the_step": mhz,
+                        "sclk_mhz_under_the_mfma_microbenchmark": out["peaks"].get("mfma_sclk_mhz")}
+        if mhz:  # the published peak is quoted at the nominal clock: what the same units give at the clock this load runs at
+            out["roofline"]["frac_at_the_clock_under_load"] = achieved / (PEAK_BF16_TFLOPS * mhz / NOMINAL_MHZ)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
