@@ -620,6 +620,18 @@ def peaks(steps):
            "mfma_note": "v_mfma_f32_32x32x16_bf16, 4 independent accumulators per wave, 2 waves per SIMD"}
     if SIDE_RAMP_MS > 0:
         res["mfma_sclk_mhz"] = _sclk_under(mfma)
+    # the same stream of products on operands that differ from product to product and from lane to lane (pseudo-random
+    # in [-1, 1)): same products per cycle, but the matrix cores draw more power and the card lowers its clock
+    L.tvmpeaks_mfma_bf16_random.restype = ctypes.c_double
+    L.tvmpeaks_mfma_bf16_random.argtypes = L.tvmpeaks_mfma_bf16.argtypes
+
+    def mfma_random():
+        flops.append(L.tvmpeaks_mfma_bf16_random(blocks, iters, out.data_ptr(), stream))
+    ms = _timed_ms(mfma_random, steps)
+    assert flops[-1] > 0, "matrix-core rate kernel (random operands) failed to launch"
+    res["mfma_bf16_tflops_random_operands"] = flops[-1] / (ms * 1e-3) / 1e12
+    if SIDE_RAMP_MS > 0:
+        res["mfma_random_operands_sclk_mhz"] = _sclk_under(mfma_random)
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
     dst = torch.empty_like(src)
@@ -756,10 +768,12 @@ def main():
                 "paper_h100_bwd_ms": PAPER_H100_BWD_MS.get((sw.H, sw.N))})
     out["peaks"] = peaks(args.steps)
     out["roofline"]["frac_of_measured_mfma_rate"] = achieved / out["peaks"]["mfma_bf16_tflops"]
+    out["roofline"]["frac_of_measured_mfma_rate_random_operands"] = achieved / out["peaks"]["mfma_bf16_tflops_random_operands"]
     if args.ramp_ms > 0:  # (not in counter runs, which keep to a handful of launches per kernel)
         mhz = sustained_clock(w)
         out["clock"] = {"nominal_mhz": NOMINAL_MHZ, "sclk_mhz_under_the_step": mhz,
-                        "sclk_mhz_under_the_mfma_microbenchmark": out["peaks"].get("mfma_sclk_mhz")}
+                        "sclk_mhz_under_the_mfma_microbenchmark": out["peaks"].get("mfma_sclk_mhz"),
+                        "sclk_mhz_under_the_mfma_microbenchmark_random_operands": out["peaks"].get("mfma_random_operands_sclk_mhz")}
         if mhz:  # the published peak is quoted at the nominal clock: what the same units give at the clock this load runs at
             out["roofline"]["frac_at_the_clock_under_load"] = achieved / (PEAK_BF16_TFLOPS * mhz / NOMINAL_MHZ)
     if not args.no_cpu:

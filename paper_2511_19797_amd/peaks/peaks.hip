@@ -42,6 +42,43 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out,
   out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same stream of products on operands that look like data: every accumulator has fragments of its own, filled
+// with pseudo-random values in [-1, 1) that differ from lane to lane, and the two operands change places from one
+// product of an accumulator to the next.  The rate in products per cycle is the same; what differs is the power the
+// matrix cores draw with operand bits that toggle, and with it the clock the card holds.
+__global__ __launch_bounds__(256) void mfma_rate_random_kernel(float* __restrict__ out, int iters, unsigned seed) {
+  bf16x8 a[kAcc], b[kAcc];
+  unsigned h = seed ^ (blockIdx.x * 2654435761u) ^ (threadIdx.x * 40503u);
+#pragma unroll
+  for (int n = 0; n < kAcc; ++n)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      h = h * 1664525u + 1013904223u;
+      a[n][e] = (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f);
+      h = h * 1664525u + 1013904223u;
+      b[n][e] = (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f);
+    }
+  f32x16 acc[kAcc];
+#pragma unroll
+  for (int n = 0; n < kAcc; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+      for (int n = 0; n < kAcc; ++n)
+        acc[n] = (u & 1) ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[n], a[(n + 1) % kAcc], acc[n], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], b[n], acc[n], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int n = 0; n < kAcc; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[n][r];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // 16 bytes per thread and step, consecutive threads on consecutive chunks, four steps in flight.
 __global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -102,6 +139,15 @@ double tvmpeaks_mfma_bf16(int blocks, int iters, void* out, void* hip_stream) {
   if (blocks < 1 || iters < 1 || !out) return 0.0;
   hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                      static_cast<float*>(out), iters, 1.0f);
+  if (hipGetLastError() != hipSuccess) return 0.0;
+  return (double)blocks * 4.0 * iters * (kAcc * kUnroll) * (32.0 * 32.0 * 16.0 * 2.0);
+}
+
+// The same launch with operands that differ from product to product (see mfma_rate_random_kernel).
+double tvmpeaks_mfma_bf16_random(int blocks, int iters, void* out, void* hip_stream) {
+  if (blocks < 1 || iters < 1 || !out) return 0.0;
+  hipLaunchKernelGGL(mfma_rate_random_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(out), iters, 12345u);
   if (hipGetLastError() != hipSuccess) return 0.0;
   return (double)blocks * 4.0 * iters * (kAcc * kUnroll) * (32.0 * 32.0 * 16.0 * 2.0);
 }
