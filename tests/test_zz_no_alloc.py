@@ -56,6 +56,16 @@ def test_static_scratch_backward_twice_second_call_smaller():
     pu.check_heads(wl.custom(1, 2, 64, 32, "f32"), inp, fwd, out, [(0, 0), (0, 1)])
 
 
+def test_static_scratch_backward_wide_heads_change_of_row_vector_convention():
+    """Head dims above 96: the hand-scheduled passes leave the row vectors in the static array negated and in log2
+    units, the generic-order kernels (64 rows or fewer on the streamed side) plain; calls of either kind in a row on
+    the same array, each smaller than the one before."""
+    _both_ways(wl.custom(2, 2, 200, 128, "bf16"), 87)       # passes on both sides
+    _both_ways(wl.custom(1, 2, 64, 120, "bf16"), 88)        # generic-order kernels on both sides
+    inp, fwd, out = _both_ways(wl.custom(1, 1, 70, 104, "bf16"), 89)   # passes again
+    pu.check_heads(wl.custom(1, 1, 70, 104, "bf16"), inp, fwd, out, [(0, 0)])
+
+
 def test_static_scratch_backward_m_differs_and_one_sided():
     import dataclasses
     w = dataclasses.replace(wl.custom(1, 2, 200, 64, "bf16"), M=130)
