@@ -632,6 +632,15 @@ def peaks(steps):
     res["mfma_bf16_tflops_random_operands"] = flops[-1] / (ms * 1e-3) / 1e12
     if SIDE_RAMP_MS > 0:
         res["mfma_random_operands_sclk_mhz"] = _sclk_under(mfma_random)
+    # ... and with 8 of the 32 rows of one operand live, the rest zero (the last output block of a head dim of 72)
+    L.tvmpeaks_mfma_bf16_random_padded.restype = ctypes.c_double
+    L.tvmpeaks_mfma_bf16_random_padded.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+
+    def mfma_padded():
+        flops.append(L.tvmpeaks_mfma_bf16_random_padded(blocks, iters, 8, out.data_ptr(), stream))
+    ms = _timed_ms(mfma_padded, steps)
+    assert flops[-1] > 0, "matrix-core rate kernel (padded operands) failed to launch"
+    res["mfma_bf16_tflops_issued_with_8_of_32_rows_live"] = flops[-1] / (ms * 1e-3) / 1e12
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
     dst = torch.empty_like(src)

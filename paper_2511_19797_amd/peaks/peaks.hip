@@ -46,15 +46,20 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out,
 // with pseudo-random values in [-1, 1) that differ from lane to lane, and the two operands change places from one
 // product of an accumulator to the next.  The rate in products per cycle is the same; what differs is the power the
 // matrix cores draw with operand bits that toggle, and with it the clock the card holds.
-__global__ __launch_bounds__(256) void mfma_rate_random_kernel(float* __restrict__ out, int iters, unsigned seed) {
+// live_rows < 32: the first operand's rows from live_rows on are zero in every second product of an accumulator (the
+// products where it is the A operand), as the rows of a padded head dim are in the output products of the attention
+// kernels (8 of 32 live in the last block of d = 72).
+__global__ __launch_bounds__(256) void mfma_rate_random_kernel(float* __restrict__ out, int iters, unsigned seed,
+                                                               int live_rows) {
   bf16x8 a[kAcc], b[kAcc];
   unsigned h = seed ^ (blockIdx.x * 2654435761u) ^ (threadIdx.x * 40503u);
+  const bool live = (int)(threadIdx.x & 31) < live_rows;  // (a lane holds row lane % 32 of the A operand)
 #pragma unroll
   for (int n = 0; n < kAcc; ++n)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       h = h * 1664525u + 1013904223u;
-      a[n][e] = (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f);
+      a[n][e] = live ? (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f) : (__bf16)0.f;
       h = h * 1664525u + 1013904223u;
       b[n][e] = (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f);
     }
@@ -147,7 +152,16 @@ double tvmpeaks_mfma_bf16(int blocks, int iters, void* out, void* hip_stream) {
 double tvmpeaks_mfma_bf16_random(int blocks, int iters, void* out, void* hip_stream) {
   if (blocks < 1 || iters < 1 || !out) return 0.0;
   hipLaunchKernelGGL(mfma_rate_random_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<float*>(out), iters, 12345u);
+                     static_cast<float*>(out), iters, 12345u, 32);
+  if (hipGetLastError() != hipSuccess) return 0.0;
+  return (double)blocks * 4.0 * iters * (kAcc * kUnroll) * (32.0 * 32.0 * 16.0 * 2.0);
+}
+// ... and with only `live_rows` (1..32) of the 32 rows of one operand non-zero: what padded products cost.  Returns the
+// operations issued (zeros included), as above.
+double tvmpeaks_mfma_bf16_random_padded(int blocks, int iters, int live_rows, void* out, void* hip_stream) {
+  if (blocks < 1 || iters < 1 || live_rows < 1 || live_rows > 32 || !out) return 0.0;
+  hipLaunchKernelGGL(mfma_rate_random_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(out), iters, 12345u, live_rows);
   if (hipGetLastError() != hipSuccess) return 0.0;
   return (double)blocks * 4.0 * iters * (kAcc * kUnroll) * (32.0 * 32.0 * 16.0 * 2.0);
 }
